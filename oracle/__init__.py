@@ -1,0 +1,15 @@
+"""CPU oracle for the ConvBN block with frozen BatchNorm (test infrastructure only).
+
+fp64, logical NCHW numpy arrays, direct loops in C (oracle/convbn_oracle.c).
+Eval mode (Sec. 3.1, App. C, Table 2 "Eval") is the definition the GPU library is
+compared with; Tune mode (Sec. 3.3, Table 2 "Tune") is carried as a second,
+independent route so that Tune == Eval (Sec. 3.4.1) can be asserted on the CPU.
+
+Only tests, the smoke check and the CPU-baseline leg of the benchmark may import
+this package.  It imports nothing from the GPU package.
+"""
+from .oracle import (Dims, conv_fwd, conv_dgrad, conv_wgrad, eval_fwd, eval_bwd, fold,
+                     tune_fwd, tune_bwd, num_threads, out_hw)
+
+__all__ = ["Dims", "conv_fwd", "conv_dgrad", "conv_wgrad", "eval_fwd", "eval_bwd", "fold",
+           "tune_fwd", "tune_bwd", "num_threads", "out_hw"]

@@ -1,0 +1,269 @@
+/*
+ * CPU oracle for the ConvBN block (frozen BatchNorm), forward and backward.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, fp64 definition the
+ * GPU library is checked against.  It shares no code with the HIP path and must
+ * never be called from it; only the tests, the smoke check and the CPU-baseline
+ * leg of the benchmark may load it.
+ *
+ * Everything is double precision, logical NCHW indexing on dense row-major
+ * arrays:  X[N][Cin][Hin][Win], W[Cout][Cin][kH][kW], Y/Z/G[N][Cout][Hout][Wout],
+ * and per-channel vectors of length Cout.  "conv" is cross-correlation with zero
+ * padding, dilation 1, groups 1 (the deep-learning convention; Sec. 3.1 writes
+ * Y = w (*) X + b and Sec. 3.2.1 takes the rotated kernel for the input
+ * gradient, which is the adjoint of cross-correlation).
+ *
+ * Two independent routes are provided:
+ *   Eval mode  (Sec. 3.1; App. C "Eval Mode"; Table 2 row "Eval"):
+ *       Y = w (*) X + b;  Z = gamma (Y - mu)/sqrt(var+eps) + beta,
+ *       backward derived from those two lines with the broadcast sums of
+ *       App. B written out.  This is the DEFINITION the GPU is compared with.
+ *   Tune mode  (Sec. 3.3 definitions of w', b'; Table 2 row "Tune"):
+ *       fold, one convolution, six backward equations.  Present only so the
+ *       test-suite can assert Tune == Eval (Sec. 3.4.1) inside the oracle.
+ *
+ * Parity pins (tests marked "not gpu"): library conv2d+batch_norm with autograd
+ * on the CPU as an independent special-case check, 1x1 == matrix product,
+ * delta kernel, single-pixel impulse response, central finite differences for
+ * every gradient, the adjoint identities, and Tune == Eval.
+ *
+ * OpenMP is used only over independent output indices; there is no blocking,
+ * no reordering and no vector intrinsics.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct {
+  int N, Cin, Hin, Win;
+  int Cout, kH, kW;
+  int sh, sw, ph, pw;
+} cb_dims;
+
+/* floor((in + 2p - k)/s) + 1 : the usual output-size rule (paper is silent). */
+static int out_size(int in, int k, int s, int p) { return (in + 2 * p - k) / s + 1; }
+
+int cbo_hout(const cb_dims *d) { return out_size(d->Hin, d->kH, d->sh, d->ph); }
+int cbo_wout(const cb_dims *d) { return out_size(d->Win, d->kW, d->sw, d->pw); }
+
+int cbo_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+#define XI(n, c, h, w) ((((size_t)(n) * d->Cin + (c)) * d->Hin + (h)) * d->Win + (w))
+#define WI(o, c, i, j) ((((size_t)(o) * d->Cin + (c)) * d->kH + (i)) * d->kW + (j))
+#define YI(n, o, h, w) ((((size_t)(n) * d->Cout + (o)) * Ho + (h)) * Wo + (w))
+
+/* Y = w (*) X + b      (Sec. 3.1; Sec. 3.2.1).  b may be NULL (= 0). */
+void cbo_conv_fwd(const cb_dims *d, const double *X, const double *W, const double *b, double *Y) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int o = 0; o < d->Cout; ++o)
+      for (int ho = 0; ho < Ho; ++ho)
+        for (int wo = 0; wo < Wo; ++wo) {
+          double acc = b ? b[o] : 0.0;
+          for (int c = 0; c < d->Cin; ++c)
+            for (int i = 0; i < d->kH; ++i) {
+              const int h = ho * d->sh + i - d->ph;
+              if (h < 0 || h >= d->Hin) continue;
+              for (int j = 0; j < d->kW; ++j) {
+                const int w = wo * d->sw + j - d->pw;
+                if (w < 0 || w >= d->Win) continue;
+                acc += W[WI(o, c, i, j)] * X[XI(n, c, h, w)];
+              }
+            }
+          Y[YI(n, o, ho, wo)] = acc;
+        }
+}
+
+/* dJ/dX = w_rot (*) dJ/dY  (Sec. 3.2.1), written as the transpose of the forward
+ * loop: every forward read of X[n,c,h,w] with weight W[o,c,i,j] into Y[n,o,ho,wo]
+ * becomes an accumulation of W * dY into dX at the same indices. */
+void cbo_conv_dgrad(const cb_dims *d, const double *W, const double *dY, double *dX) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+  memset(dX, 0, sizeof(double) * (size_t)d->N * d->Cin * d->Hin * d->Win);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int c = 0; c < d->Cin; ++c)
+      for (int o = 0; o < d->Cout; ++o)
+        for (int ho = 0; ho < Ho; ++ho)
+          for (int wo = 0; wo < Wo; ++wo) {
+            const double g = dY[YI(n, o, ho, wo)];
+            for (int i = 0; i < d->kH; ++i) {
+              const int h = ho * d->sh + i - d->ph;
+              if (h < 0 || h >= d->Hin) continue;
+              for (int j = 0; j < d->kW; ++j) {
+                const int w = wo * d->sw + j - d->pw;
+                if (w < 0 || w >= d->Win) continue;
+                dX[XI(n, c, h, w)] += W[WI(o, c, i, j)] * g;
+              }
+            }
+          }
+}
+
+/* dJ/dw = dJ/dY (.) X  (cross-correlation of the output gradient with the
+ * padded input, Sec. 3.2.1), summed over the batch. */
+void cbo_conv_wgrad(const cb_dims *d, const double *X, const double *dY, double *dW) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int o = 0; o < d->Cout; ++o)
+    for (int c = 0; c < d->Cin; ++c)
+      for (int i = 0; i < d->kH; ++i)
+        for (int j = 0; j < d->kW; ++j) {
+          double acc = 0.0;
+          for (int n = 0; n < d->N; ++n)
+            for (int ho = 0; ho < Ho; ++ho) {
+              const int h = ho * d->sh + i - d->ph;
+              if (h < 0 || h >= d->Hin) continue;
+              for (int wo = 0; wo < Wo; ++wo) {
+                const int w = wo * d->sw + j - d->pw;
+                if (w < 0 || w >= d->Win) continue;
+                acc += dY[YI(n, o, ho, wo)] * X[XI(n, c, h, w)];
+              }
+            }
+          dW[WI(o, c, i, j)] = acc;
+        }
+}
+
+/* Per-channel sum over N, Hout, Wout: the backward of a [Cout] -> [N,Cout,H,W]
+ * broadcast (App. B).  If T is non-NULL the summand is A*T elementwise. */
+static void channel_sum(const cb_dims *d, const double *A, const double *T, double *out) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+#pragma omp parallel for schedule(static)
+  for (int o = 0; o < d->Cout; ++o) {
+    double acc = 0.0;
+    for (int n = 0; n < d->N; ++n)
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          acc += T ? A[idx] * T[idx] : A[idx];
+        }
+    out[o] = acc;
+  }
+}
+
+/* ------------------------------------------------------------------ Eval --- */
+
+/* Eval forward (Sec. 3.1; App. C "Eval Mode"):
+ *   Y = w (*) X + b ;  Ybar = (Y - mu)/sqrt(var + eps) ;  Z = gamma*Ybar + beta.
+ * Y (the tensor Eval mode keeps for backward) and Z are both returned. */
+void cbo_eval_fwd(const cb_dims *d, const double *X, const double *W, const double *b,
+                  const double *gamma, const double *beta, const double *mu, const double *var,
+                  double eps, double *Y, double *Z) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+  cbo_conv_fwd(d, X, W, b, Y);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int o = 0; o < d->Cout; ++o) {
+      const double sd = sqrt(var[o] + eps);
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          const double ybar = (Y[idx] - mu[o]) / sd;
+          Z[idx] = gamma[o] * ybar + beta[o];
+        }
+    }
+}
+
+/* Eval backward (Table 2, row "Eval", with App. B's sums restored).  G = dJ/dZ.
+ *   dY     = gamma/sqrt(var+eps) * G
+ *   dX     = w_rot (*) dY
+ *   dW     = dY (.) X
+ *   db     = sum dY                       (only if db != NULL)
+ *   dgamma = sum G * (Y - mu)/sqrt(var+eps)
+ *   dbeta  = sum G
+ * scratch_dY must hold N*Cout*Hout*Wout doubles. */
+void cbo_eval_bwd(const cb_dims *d, const double *X, const double *W, const double *gamma,
+                  const double *mu, const double *var, double eps, const double *Y,
+                  const double *G, double *scratch_dY, double *dX, double *dW, double *db,
+                  double *dgamma, double *dbeta) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+  double *dY = scratch_dY;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int o = 0; o < d->Cout; ++o) {
+      const double sd = sqrt(var[o] + eps);
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          dY[idx] = gamma[o] / sd * G[idx];
+        }
+    }
+  if (dX) cbo_conv_dgrad(d, W, dY, dX);
+  cbo_conv_wgrad(d, X, dY, dW);
+  if (db) channel_sum(d, dY, NULL, db);
+  /* dgamma: sum over the broadcast dims of G * Ybar */
+#pragma omp parallel for schedule(static)
+  for (int o = 0; o < d->Cout; ++o) {
+    const double sd = sqrt(var[o] + eps);
+    double acc = 0.0;
+    for (int n = 0; n < d->N; ++n)
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          acc += G[idx] * ((Y[idx] - mu[o]) / sd);
+        }
+    dgamma[o] = acc;
+  }
+  channel_sum(d, G, NULL, dbeta);
+}
+
+/* ------------------------------------------------------------------ Tune --- */
+
+/* Fold (Sec. 3.3):  w' = gamma/sqrt(var+eps) * w  (per output channel),
+ *                   b' = (b - mu) * gamma/sqrt(var+eps) + beta.   b may be NULL. */
+void cbo_fold(const cb_dims *d, const double *W, const double *b, const double *gamma,
+              const double *beta, const double *mu, const double *var, double eps, double *Wf,
+              double *bf) {
+  const size_t row = (size_t)d->Cin * d->kH * d->kW;
+  for (int o = 0; o < d->Cout; ++o) {
+    const double s = gamma[o] / sqrt(var[o] + eps);
+    for (size_t t = 0; t < row; ++t) Wf[o * row + t] = s * W[o * row + t];
+    bf[o] = ((b ? b[o] : 0.0) - mu[o]) * s + beta[o];
+  }
+}
+
+/* Tune forward (Sec. 3.4: fold on every call, then one convolution). */
+void cbo_tune_fwd(const cb_dims *d, const double *X, const double *W, const double *b,
+                  const double *gamma, const double *beta, const double *mu, const double *var,
+                  double eps, double *Wf, double *bf, double *Z) {
+  cbo_fold(d, W, b, gamma, beta, mu, var, eps, Wf, bf);
+  cbo_conv_fwd(d, X, Wf, bf, Z);
+}
+
+/* Tune backward (Table 2, row "Tune").  Needs X and w' only (no Y).
+ *   dX     = w'_rot (*) G
+ *   dW'    = G (.) X                        (returned in dWf)
+ *   dW     = gamma/sqrt(var+eps) * dW'
+ *   db     = gamma/sqrt(var+eps) * sum G
+ *   dgamma = <dW', w>/sqrt(var+eps) + (sum G)(b - mu)/sqrt(var+eps)
+ *   dbeta  = sum G */
+void cbo_tune_bwd(const cb_dims *d, const double *X, const double *W, const double *b,
+                  const double *gamma, const double *mu, const double *var, double eps,
+                  const double *Wf, const double *G, double *dX, double *dWf, double *dW,
+                  double *db, double *dgamma, double *dbeta) {
+  const size_t row = (size_t)d->Cin * d->kH * d->kW;
+  if (dX) cbo_conv_dgrad(d, Wf, G, dX);
+  cbo_conv_wgrad(d, X, G, dWf);
+  channel_sum(d, G, NULL, dbeta);
+  for (int o = 0; o < d->Cout; ++o) {
+    const double sd = sqrt(var[o] + eps);
+    const double s = gamma[o] / sd;
+    double dot = 0.0;
+    for (size_t t = 0; t < row; ++t) {
+      dW[o * row + t] = s * dWf[o * row + t];
+      dot += dWf[o * row + t] * W[o * row + t];
+    }
+    const double r = dbeta[o];
+    if (db) db[o] = s * r;
+    dgamma[o] = dot / sd + r * ((b ? b[o] : 0.0) - mu[o]) / sd;
+  }
+}
