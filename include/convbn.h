@@ -1,0 +1,149 @@
+/*
+ * convbn.h -- C ABI of the MI355X (gfx950) ConvBN-block library.
+ *
+ * One block = a 2-D convolution followed by a BatchNorm layer whose statistics are
+ * frozen (Sec. 3.1 of "Efficient ConvBN Blocks for Transfer Learning and Beyond"):
+ *
+ *     Y = w (*) X + b                       X: [N,Cin,Hin,Win]   w: [Cout,Cin,kH,kW]
+ *     Z = gamma (Y - mu)/sqrt(var+eps) + beta          Y,Z: [N,Cout,Hout,Wout]
+ *
+ * Two ways of running it, with identical results (Sec. 3.4.1):
+ *   Tune mode (the paper's proposal, Sec. 3.3-3.4, Table 2 row "Tune"): on every call
+ *     fold the BatchNorm into the weights, w' = s w, b' = (b - mu) s + beta with
+ *     s = gamma/sqrt(var+eps), run ONE convolution, and in backward route dJ/dw'
+ *     back to w, gamma, beta through s.  Only X and w' are kept for backward.
+ *   Eval mode (Sec. 3.1, App. C, Table 2 row "Eval"): convolution, stored Y, separate
+ *     per-channel affine; backward needs X and Y.  Built as the comparison path.
+ *
+ * GENERAL CONVENTIONS
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates nothing, frees nothing and keeps no state between calls.
+ *   - All work is enqueued asynchronously on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream).  No call synchronises with the host.
+ *   - Arguments are validated on the host before anything is launched: a call that
+ *     returns an error code has had no effect on device memory.
+ *   - Outputs are overwritten, never accumulated into.
+ *   - mu and var are frozen buffers: read-only, no gradient.
+ *   - Device-side value preconditions (var + eps > 0) are documented, not checked.
+ *
+ * MEMORY LAYOUT (the descriptor's dimensions are always the logical ones above)
+ *   The one supported layout is channels-last, CONVBN_LAYOUT_NHWC:
+ *     x, dx          [N][Hin][Win][Cin]
+ *     z, y, dz       [N][Hout][Wout][Cout]
+ *     W, dW          [Cout][kH][kW][Cin]
+ *     w_folded       [Cin][kH][kW][Cout]   (the folded weight w', stored transposed:
+ *                                           the order the input-gradient pass reads)
+ *   dense, no padding between rows.  Element type of these tensors is desc->dtype;
+ *   every [Cout] vector (b, gamma, beta, mean, var, db, dgamma, dbeta) is fp32.
+ *   With dtype BF16 all accumulation is fp32; w' = bf16(float(W) * s) and
+ *   dW = bf16(s * dJ/dw'_fp32) are each rounded once.
+ *
+ * Hout = floor((Hin + 2 pad_h - kH)/stride_h) + 1, likewise Wout.
+ */
+#ifndef CONVBN_H_
+#define CONVBN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CONVBN_OK = 0,
+  CONVBN_ERR_NULL = 1,        /* a required pointer is NULL                          */
+  CONVBN_ERR_SHAPE = 2,       /* non-positive dim, negative pad, empty output, ...   */
+  CONVBN_ERR_UNSUPPORTED = 3, /* unknown dtype / layout, tensor too large for int32  */
+  CONVBN_ERR_WORKSPACE = 4,   /* ws is NULL or ws_bytes < convbn_workspace_bytes()   */
+  CONVBN_ERR_LAUNCH = 5       /* the HIP runtime refused a launch                    */
+} convbn_status;
+
+typedef enum { CONVBN_F32 = 0, CONVBN_BF16 = 1 } convbn_dtype;
+typedef enum { CONVBN_LAYOUT_NHWC = 0 } convbn_layout;
+typedef enum { CONVBN_MODE_TUNE = 0, CONVBN_MODE_EVAL = 1 } convbn_mode;
+typedef enum { CONVBN_PASS_FWD = 0, CONVBN_PASS_BWD = 1 } convbn_pass;
+
+/* Problem descriptor: plain data, passed by pointer, caller-owned, read-only.
+ * Dilation is 1 and groups is 1 (the paper's blocks use a single k, Sec. 3.1). */
+typedef struct {
+  int32_t N, Cin, Hin, Win;   /* logical dims of X (Sec. 3.1)                       */
+  int32_t Cout, kH, kW;       /* W is logically [Cout,Cin,kH,kW] (App. C)           */
+  int32_t stride_h, stride_w;
+  int32_t pad_h, pad_w;       /* zero padding                                       */
+  float eps;                  /* BatchNorm epsilon, inside the square root          */
+  int32_t dtype;              /* convbn_dtype of x, W, z, y, dz, dx, dW, w_folded   */
+  int32_t layout;             /* convbn_layout                                      */
+} convbn_desc;
+
+/* Output spatial size for a descriptor (0 on a NULL / invalid descriptor). */
+int32_t convbn_hout(const convbn_desc *desc);
+int32_t convbn_wout(const convbn_desc *desc);
+
+/* Bytes of device workspace the given call needs (mode: convbn_mode, pass:
+ * convbn_pass).  Depends on the descriptor only.  The backward figure covers the
+ * case w_folded == NULL (re-fold).  Returns 0 for an invalid descriptor.  The
+ * workspace carries nothing from one call to the next. */
+size_t convbn_workspace_bytes(const convbn_desc *desc, int mode, int pass);
+
+/* Tune-mode forward (Sec. 3.3: definitions of w', b'; Sec. 3.4: "calculate the
+ * transformed parameters on-the-fly", then a single convolution).
+ *   in : x, W, b (nullable = no conv bias), gamma, beta, mean, var
+ *   out: z            block output
+ *        w_folded     nullable.  If given, receives w' ([Cin][kH][kW][Cout]) -- the
+ *                     tensor Tune mode keeps for backward instead of Y.  If NULL
+ *                     nothing but x needs to be kept and backward folds again.
+ */
+convbn_status convbn_tune_fwd(const convbn_desc *desc, const void *x, const void *W,
+                              const float *b, const float *gamma, const float *beta,
+                              const float *mean, const float *var, void *z, void *w_folded,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* Tune-mode backward (Table 2, row "Tune"; broadcast sums of App. B restored):
+ *   dX = w'_rot (*) dZ            dw' = dZ (.) X            r_c = sum_{n,h,w} dZ
+ *   dW = s dw'      db = s r      dgamma = (<dw'_c, w_c> + r_c (b_c - mu_c))/sqrt(var_c+eps)
+ *   dbeta = r
+ *   in : x, W, b (nullable), gamma, mean, var, dz,
+ *        w_folded (nullable: the buffer convbn_tune_fwd filled; NULL = fold again
+ *        into the workspace)
+ *   out: dx (nullable = skip the input-gradient pass), dW, db (must be NULL exactly
+ *        when b is NULL), dgamma, dbeta
+ */
+convbn_status convbn_tune_bwd(const convbn_desc *desc, const void *x, const void *W,
+                              const float *b, const float *gamma, const float *mean,
+                              const float *var, const void *w_folded, const void *dz, void *dx,
+                              void *dW, float *db, float *dgamma, float *dbeta, void *ws,
+                              size_t ws_bytes, void *stream);
+
+/* Eval-mode forward (Sec. 3.1; App. C "Eval Mode"): convolution, then the
+ * per-channel normalisation + affine as a separate pass over the stored Y.
+ *   out: z, y_saved (required: the conv output Eval mode keeps for backward). */
+convbn_status convbn_eval_fwd(const convbn_desc *desc, const void *x, const void *W,
+                              const float *b, const float *gamma, const float *beta,
+                              const float *mean, const float *var, void *z, void *y_saved,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* Eval-mode backward (Table 2, row "Eval"):
+ *   dY = s dZ;  dgamma = sum dZ (Y - mu)/sqrt(var+eps);  dbeta = sum dZ;
+ *   dX = w_rot (*) dY;  dW = dY (.) X;  db = sum dY.
+ *   in : x, W, b (nullable; only its NULL-ness matters), gamma, mean, var, y_saved, dz
+ *   out: dx (nullable), dW, db (NULL exactly when b is NULL), dgamma, dbeta */
+convbn_status convbn_eval_bwd(const convbn_desc *desc, const void *x, const void *W,
+                              const float *b, const float *gamma, const float *mean,
+                              const float *var, const void *y_saved, const void *dz, void *dx,
+                              void *dW, float *db, float *dgamma, float *dbeta, void *ws,
+                              size_t ws_bytes, void *stream);
+
+/* Bytes a block must keep alive between its forward and its backward call in
+ * addition to X (App. K.1): Eval keeps Y (N Cout Hout Wout elements); Tune keeps
+ * w' (kH kW Cin Cout elements), or nothing when `refold` is non-zero. */
+size_t convbn_saved_bytes(const convbn_desc *desc, int mode, int refold);
+
+/* Human-readable description of the last error on the calling thread
+ * (thread-local static storage; valid until the next failing call). */
+const char *convbn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONVBN_H_ */

@@ -1,0 +1,216 @@
+"""ctypes binding of libconvbn.so: same entry-point names as include/convbn.h.
+
+Argument marshalling only -- every step of the block runs in the library's HIP kernels.
+PyTorch supplies device memory and the stream.  There is no fallback: if the compiled
+library is missing this module raises on first use.
+"""
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libconvbn.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = range(6)
+F32, BF16 = 0, 1
+LAYOUT_NHWC = 0
+MODE_TUNE, MODE_EVAL = 0, 1
+PASS_FWD, PASS_BWD = 0, 1
+
+EXPORTS = ["convbn_hout", "convbn_wout", "convbn_workspace_bytes", "convbn_saved_bytes",
+           "convbn_tune_fwd", "convbn_tune_bwd", "convbn_eval_fwd", "convbn_eval_bwd",
+           "convbn_last_error"]
+
+
+class Desc(C.Structure):
+    """Mirror of convbn_desc."""
+    _fields_ = [("N", C.c_int32), ("Cin", C.c_int32), ("Hin", C.c_int32), ("Win", C.c_int32),
+                ("Cout", C.c_int32), ("kH", C.c_int32), ("kW", C.c_int32),
+                ("stride_h", C.c_int32), ("stride_w", C.c_int32),
+                ("pad_h", C.c_int32), ("pad_w", C.c_int32),
+                ("eps", C.c_float), ("dtype", C.c_int32), ("layout", C.c_int32)]
+
+
+class ConvBNError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"convbn status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  Raises if it has not been built (no silent fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2305_11624_amd.build` "
+                "(hipcc, gfx950).  This package has no CPU or PyTorch fallback.")
+        L = C.CDLL(LIB_PATH)
+        vp, fp = C.c_void_p, C.c_void_p
+        dp = C.POINTER(Desc)
+        L.convbn_hout.restype = C.c_int32
+        L.convbn_hout.argtypes = [dp]
+        L.convbn_wout.restype = C.c_int32
+        L.convbn_wout.argtypes = [dp]
+        L.convbn_workspace_bytes.restype = C.c_size_t
+        L.convbn_workspace_bytes.argtypes = [dp, C.c_int, C.c_int]
+        L.convbn_saved_bytes.restype = C.c_size_t
+        L.convbn_saved_bytes.argtypes = [dp, C.c_int, C.c_int]
+        L.convbn_last_error.restype = C.c_char_p
+        L.convbn_last_error.argtypes = []
+        L.convbn_tune_fwd.restype = C.c_int
+        L.convbn_tune_fwd.argtypes = [dp, vp, vp, fp, fp, fp, fp, fp, vp, vp, vp, C.c_size_t, vp]
+        L.convbn_tune_bwd.restype = C.c_int
+        L.convbn_tune_bwd.argtypes = [dp, vp, vp, fp, fp, fp, fp, vp, vp, vp, vp, fp, fp, fp, vp,
+                                      C.c_size_t, vp]
+        L.convbn_eval_fwd.restype = C.c_int
+        L.convbn_eval_fwd.argtypes = [dp, vp, vp, fp, fp, fp, fp, fp, vp, vp, vp, C.c_size_t, vp]
+        L.convbn_eval_bwd.restype = C.c_int
+        L.convbn_eval_bwd.argtypes = [dp, vp, vp, fp, fp, fp, fp, vp, vp, vp, vp, fp, fp, fp, vp,
+                                      C.c_size_t, vp]
+        _lib = L
+    return _lib
+
+
+def make_desc(N, Cin, Hin, Win, Cout, kH, kW, stride=1, pad=0, eps=1e-5, dtype=BF16,
+              layout=LAYOUT_NHWC, stride_w=None, pad_w=None) -> Desc:
+    return Desc(N, Cin, Hin, Win, Cout, kH, kW, stride, stride if stride_w is None else stride_w,
+                pad, pad if pad_w is None else pad_w, eps, dtype, layout)
+
+
+def desc_from_shape(s, eps=1e-5) -> Desc:
+    """Descriptor for a synth.BlockShape."""
+    return make_desc(s.N, s.Cin, s.Hin, s.Win, s.Cout, s.k, s.k, s.stride, s.pad, eps,
+                     BF16 if s.dtype == "bf16" else F32)
+
+
+def torch_dtype(desc: Desc):
+    return torch.bfloat16 if desc.dtype == BF16 else torch.float32
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return C.c_void_p(t)
+    assert t.is_cuda and t.is_contiguous(), "device, dense tensors only"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        return C.c_void_p(stream.cuda_stream)
+    return C.c_void_p(int(stream))
+
+
+def _check(status: int):
+    if status != OK:
+        raise ConvBNError(status, lib().convbn_last_error().decode())
+
+
+def convbn_last_error() -> str:
+    return lib().convbn_last_error().decode()
+
+
+def convbn_hout(desc: Desc) -> int:
+    return lib().convbn_hout(C.byref(desc))
+
+
+def convbn_wout(desc: Desc) -> int:
+    return lib().convbn_wout(C.byref(desc))
+
+
+def convbn_workspace_bytes(desc: Desc, mode: int, pass_: int) -> int:
+    return lib().convbn_workspace_bytes(C.byref(desc), mode, pass_)
+
+
+def convbn_saved_bytes(desc: Desc, mode: int, refold: bool = False) -> int:
+    return lib().convbn_saved_bytes(C.byref(desc), mode, int(refold))
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    return _ptr(ws), ws.numel() * ws.element_size()
+
+
+def convbn_tune_fwd(desc, x, W, b, gamma, beta, mean, var, z, w_folded, ws, stream=None,
+                    check=True):
+    p, n = _ws(ws)
+    st = lib().convbn_tune_fwd(C.byref(desc), _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(beta),
+                               _ptr(mean), _ptr(var), _ptr(z), _ptr(w_folded), p, n,
+                               _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_tune_bwd(desc, x, W, b, gamma, mean, var, w_folded, dz, dx, dW, db, dgamma, dbeta, ws,
+                    stream=None, check=True):
+    p, n = _ws(ws)
+    st = lib().convbn_tune_bwd(C.byref(desc), _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(mean),
+                               _ptr(var), _ptr(w_folded), _ptr(dz), _ptr(dx), _ptr(dW), _ptr(db),
+                               _ptr(dgamma), _ptr(dbeta), p, n, _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_eval_fwd(desc, x, W, b, gamma, beta, mean, var, z, y_saved, ws, stream=None,
+                    check=True):
+    p, n = _ws(ws)
+    st = lib().convbn_eval_fwd(C.byref(desc), _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(beta),
+                               _ptr(mean), _ptr(var), _ptr(z), _ptr(y_saved), p, n,
+                               _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_eval_bwd(desc, x, W, b, gamma, mean, var, y_saved, dz, dx, dW, db, dgamma, dbeta, ws,
+                    stream=None, check=True):
+    p, n = _ws(ws)
+    st = lib().convbn_eval_bwd(C.byref(desc), _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(mean),
+                               _ptr(var), _ptr(y_saved), _ptr(dz), _ptr(dx), _ptr(dW), _ptr(db),
+                               _ptr(dgamma), _ptr(dbeta), p, n, _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+# ---- layout marshalling between logical NCHW host tensors and the library's
+# ---- channels-last device buffers (pure permutes and casts) -------------------
+
+def act_to_device(t_nchw: torch.Tensor, dtype, device="cuda") -> torch.Tensor:
+    """[N,C,H,W] host tensor -> dense [N,H,W,C] device buffer."""
+    return t_nchw.permute(0, 2, 3, 1).contiguous().to(device=device, dtype=dtype)
+
+
+def act_from_device(t_nhwc: torch.Tensor) -> torch.Tensor:
+    """[N,H,W,C] device buffer -> logical [N,C,H,W] fp64 host tensor."""
+    return t_nhwc.detach().to("cpu", torch.float64).permute(0, 3, 1, 2).contiguous()
+
+
+def weight_to_device(w_oihw: torch.Tensor, dtype, device="cuda") -> torch.Tensor:
+    """[Cout,Cin,kH,kW] -> [Cout,kH,kW,Cin] device buffer."""
+    return w_oihw.permute(0, 2, 3, 1).contiguous().to(device=device, dtype=dtype)
+
+
+def weight_from_device(w_ohwi: torch.Tensor) -> torch.Tensor:
+    return w_ohwi.detach().to("cpu", torch.float64).permute(0, 3, 1, 2).contiguous()
+
+
+def folded_from_device(w_ihwo: torch.Tensor) -> torch.Tensor:
+    """w_folded buffer [Cin,kH,kW,Cout] -> logical [Cout,Cin,kH,kW] fp64 host tensor."""
+    return w_ihwo.detach().to("cpu", torch.float64).permute(3, 0, 1, 2).contiguous()
+
+
+def vec_to_device(v: Optional[torch.Tensor], device="cuda"):
+    return None if v is None else v.to(device=device, dtype=torch.float32).contiguous()

@@ -1,0 +1,294 @@
+// C ABI of libconvbn: argument validation, workspace carving and the launch sequences
+// of the Tune-mode block (Sec. 3.3-3.4, Table 2 "Tune") and of the Eval-mode comparison
+// block (Sec. 3.1, Table 2 "Eval").  Host code only enqueues; nothing here synchronises.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "common.h"
+
+using namespace convbn;
+
+namespace {
+
+thread_local char g_err[256] = "no error";
+
+convbn_status fail(convbn_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int out_size(int in, int k, int s, int p) { return (in + 2 * p - k) / s + 1; }
+
+// Fills `g`; returns CONVBN_OK or the reason the descriptor is not usable.
+convbn_status make_geom(const convbn_desc* d, Geom* g) {
+  if (!d) return fail(CONVBN_ERR_NULL, "descriptor is NULL");
+  if (d->N < 1 || d->Cin < 1 || d->Hin < 1 || d->Win < 1 || d->Cout < 1 || d->kH < 1 || d->kW < 1)
+    return fail(CONVBN_ERR_SHAPE, "non-positive dimension in descriptor");
+  if (d->stride_h < 1 || d->stride_w < 1) return fail(CONVBN_ERR_SHAPE, "stride must be >= 1");
+  if (d->pad_h < 0 || d->pad_w < 0) return fail(CONVBN_ERR_SHAPE, "padding must be >= 0");
+  if (d->Hin + 2 * d->pad_h < d->kH || d->Win + 2 * d->pad_w < d->kW)
+    return fail(CONVBN_ERR_SHAPE, "kernel larger than the padded input (empty output)");
+  if (d->dtype != CONVBN_F32 && d->dtype != CONVBN_BF16)
+    return fail(CONVBN_ERR_UNSUPPORTED, "dtype %d is not CONVBN_F32 or CONVBN_BF16", d->dtype);
+  if (d->layout != CONVBN_LAYOUT_NHWC)
+    return fail(CONVBN_ERR_UNSUPPORTED, "layout %d: only CONVBN_LAYOUT_NHWC is supported", d->layout);
+  if (!(d->eps >= 0.f)) return fail(CONVBN_ERR_SHAPE, "eps must be >= 0");
+  g->N = d->N; g->Cin = d->Cin; g->Hin = d->Hin; g->Win = d->Win;
+  g->Cout = d->Cout; g->kH = d->kH; g->kW = d->kW;
+  g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
+  g->Hout = out_size(d->Hin, d->kH, d->stride_h, d->pad_h);
+  g->Wout = out_size(d->Win, d->kW, d->stride_w, d->pad_w);
+  g->eps = d->eps;
+  const long long lim = 0x7fffffffLL;
+  const long long ax = (long long)d->N * d->Hin * d->Win * d->Cin;
+  const long long az = (long long)d->N * g->Hout * g->Wout * d->Cout;
+  const long long pp = (long long)d->Cout * d->kH * d->kW * d->Cin;
+  if (ax > lim || az > lim || pp > lim)
+    return fail(CONVBN_ERR_UNSUPPORTED, "a tensor has more than 2^31-1 elements");
+  g->M = d->N * g->Hout * g->Wout;
+  g->Min = d->N * d->Hin * d->Win;
+  g->K = d->kH * d->kW * d->Cin;
+  return CONVBN_OK;
+}
+
+size_t esize(int dtype) { return dtype == CONVBN_BF16 ? 2 : 4; }
+
+int nsplit_for(const Geom& g, int dtype) {
+  return igemm_supported(g, dtype) ? wgrad_splits(g) : wgrad_direct_splits(g);
+}
+
+// Workspace carving.  Every section starts on a 256-byte boundary.
+struct Carve {
+  char* base;
+  size_t off = 0;
+  explicit Carve(void* p) : base(static_cast<char*>(p)) {}
+  void* take(size_t bytes) {
+    void* r = base ? base + off : nullptr;
+    off += align_up(bytes, 256);
+    return r;
+  }
+};
+
+struct TuneFwdWs { void* w_krsc; float* bfold; size_t bytes; };
+TuneFwdWs carve_tune_fwd(const Geom& g, int dtype, void* ws) {
+  Carve c(ws);
+  TuneFwdWs r;
+  r.w_krsc = c.take((size_t)g.Cout * g.K * esize(dtype));
+  r.bfold = (float*)c.take((size_t)g.Cout * 4);
+  r.bytes = c.off;
+  return r;
+}
+
+struct TuneBwdWs { void* w_crsk; float* dwf_part; float* r_part; int nsplit; int nrpart; size_t bytes; };
+TuneBwdWs carve_tune_bwd(const Geom& g, int dtype, void* ws) {
+  Carve c(ws);
+  TuneBwdWs r;
+  r.nsplit = nsplit_for(g, dtype);
+  r.nrpart = colsum_parts(g);
+  r.w_crsk = c.take((size_t)g.Cout * g.K * esize(dtype));
+  r.dwf_part = (float*)c.take((size_t)r.nsplit * g.Cout * g.K * 4);
+  r.r_part = (float*)c.take((size_t)r.nrpart * g.Cout * 4);
+  r.bytes = c.off;
+  return r;
+}
+
+struct EvalBwdWs { void* dy; void* w_crsk; float* dwf_part; float* bn_part; int nsplit; int nparts; size_t bytes; };
+EvalBwdWs carve_eval_bwd(const Geom& g, int dtype, void* ws) {
+  Carve c(ws);
+  EvalBwdWs r;
+  r.nsplit = nsplit_for(g, dtype);
+  r.nparts = bn_bwd_parts(g);
+  r.dy = c.take((size_t)g.M * g.Cout * esize(dtype));
+  r.w_crsk = c.take((size_t)g.Cout * g.K * esize(dtype));
+  r.dwf_part = (float*)c.take((size_t)r.nsplit * g.Cout * g.K * 4);
+  r.bn_part = (float*)c.take((size_t)r.nparts * 2 * g.Cout * 4);
+  r.bytes = c.off;
+  return r;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+#define REQUIRE_PTR(p)                                                            \
+  do {                                                                            \
+    if (!(p)) return fail(CONVBN_ERR_NULL, "required pointer '%s' is NULL", #p);   \
+    if (misaligned(p))                                                            \
+      return fail(CONVBN_ERR_UNSUPPORTED, "pointer '%s' is not 16-byte aligned", #p); \
+  } while (0)
+#define OPTIONAL_PTR(p)                                                           \
+  do {                                                                            \
+    if ((p) && misaligned(p))                                                     \
+      return fail(CONVBN_ERR_UNSUPPORTED, "pointer '%s' is not 16-byte aligned", #p); \
+  } while (0)
+#define LAUNCH(expr)                                                              \
+  do {                                                                            \
+    hipError_t e_ = (expr);                                                       \
+    if (e_ != hipSuccess)                                                         \
+      return fail(CONVBN_ERR_LAUNCH, "%s: %s", #expr, hipGetErrorString(e_));      \
+  } while (0)
+
+convbn_status check_ws(size_t need, void* ws, size_t ws_bytes) {
+  if (need == 0) return CONVBN_OK;
+  if (!ws) return fail(CONVBN_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", need);
+  if (misaligned(ws)) return fail(CONVBN_ERR_UNSUPPORTED, "workspace is not 16-byte aligned");
+  if (ws_bytes < need)
+    return fail(CONVBN_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, need);
+  return CONVBN_OK;
+}
+
+hipError_t run_fprop(const Geom& g, int dtype, const void* x, const void* w_krsc, const float* bias,
+                     void* z, hipStream_t st) {
+  return igemm_supported(g, dtype) ? launch_fprop_igemm(g, x, w_krsc, bias, z, st)
+                                   : launch_fprop_direct(g, dtype, x, w_krsc, bias, z, st);
+}
+hipError_t run_dgrad(const Geom& g, int dtype, const void* dz, const void* w_crsk, void* dx,
+                     hipStream_t st) {
+  return igemm_supported(g, dtype) ? launch_dgrad_igemm(g, dz, w_crsk, dx, st)
+                                   : launch_dgrad_direct(g, dtype, dz, w_crsk, dx, st);
+}
+hipError_t run_wgrad(const Geom& g, int dtype, const void* x, const void* dz, float* part, int nsplit,
+                     hipStream_t st) {
+  return igemm_supported(g, dtype) ? launch_wgrad_igemm(g, x, dz, part, nsplit, st)
+                                   : launch_wgrad_direct(g, dtype, x, dz, part, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t convbn_hout(const convbn_desc* desc) {
+  Geom g;
+  return make_geom(desc, &g) == CONVBN_OK ? g.Hout : 0;
+}
+
+int32_t convbn_wout(const convbn_desc* desc) {
+  Geom g;
+  return make_geom(desc, &g) == CONVBN_OK ? g.Wout : 0;
+}
+
+size_t convbn_workspace_bytes(const convbn_desc* desc, int mode, int pass) {
+  Geom g;
+  if (make_geom(desc, &g) != CONVBN_OK) return 0;
+  if (mode == CONVBN_MODE_TUNE)
+    return pass == CONVBN_PASS_FWD ? carve_tune_fwd(g, desc->dtype, nullptr).bytes
+                                   : carve_tune_bwd(g, desc->dtype, nullptr).bytes;
+  if (mode == CONVBN_MODE_EVAL)
+    return pass == CONVBN_PASS_FWD ? 0 : carve_eval_bwd(g, desc->dtype, nullptr).bytes;
+  return 0;
+}
+
+size_t convbn_saved_bytes(const convbn_desc* desc, int mode, int refold) {
+  Geom g;
+  if (make_geom(desc, &g) != CONVBN_OK) return 0;
+  if (mode == CONVBN_MODE_EVAL) return (size_t)g.M * g.Cout * esize(desc->dtype);
+  return refold ? 0 : (size_t)g.Cout * g.K * esize(desc->dtype);
+}
+
+const char* convbn_last_error(void) { return g_err; }
+
+convbn_status convbn_tune_fwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                              const float* gamma, const float* beta, const float* mean,
+                              const float* var, void* z, void* w_folded, void* ws, size_t ws_bytes,
+                              void* stream) {
+  Geom g;
+  convbn_status s = make_geom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(beta); REQUIRE_PTR(mean);
+  REQUIRE_PTR(var); REQUIRE_PTR(z);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(w_folded);
+  const int dt = desc->dtype;
+  s = check_ws(carve_tune_fwd(g, dt, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const TuneFwdWs w = carve_tune_fwd(g, dt, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // w' = s w (both orders), b' = (b - mu) s + beta; then Z = w' (*) X + b'
+  LAUNCH(launch_fold(g, dt, W, b, gamma, beta, mean, var, 0, w.w_krsc, w_folded, w.bfold, st));
+  LAUNCH(run_fprop(g, dt, x, w.w_krsc, w.bfold, z, st));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                              const float* gamma, const float* mean, const float* var,
+                              const void* w_folded, const void* dz, void* dx, void* dW, float* db,
+                              float* dgamma, float* dbeta, void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  convbn_status s = make_geom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
+  REQUIRE_PTR(dz); REQUIRE_PTR(dW); REQUIRE_PTR(dgamma); REQUIRE_PTR(dbeta);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(w_folded); OPTIONAL_PTR(dx); OPTIONAL_PTR(db);
+  if ((b == nullptr) != (db == nullptr))
+    return fail(CONVBN_ERR_NULL, "db must be given exactly when b is given");
+  const int dt = desc->dtype;
+  s = check_ws(carve_tune_bwd(g, dt, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const TuneBwdWs w = carve_tune_bwd(g, dt, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (dx) {
+    const void* wt = w_folded;
+    if (!wt) {  // nothing was kept: fold again, transposed order only
+      LAUNCH(launch_fold(g, dt, W, b, gamma, nullptr, mean, var, 0, nullptr, w.w_crsk, nullptr, st));
+      wt = w.w_crsk;
+    }
+    LAUNCH(run_dgrad(g, dt, dz, wt, dx, st));           // dX = w'_rot (*) dZ
+  }
+  LAUNCH(run_wgrad(g, dt, x, dz, w.dwf_part, w.nsplit, st));   // dw' = dZ (.) X  (fp32 partials)
+  LAUNCH(launch_colsum(g, dt, dz, w.r_part, st));              // r = sum dZ       (partials)
+  LAUNCH(launch_fold_back(g, dt, w.dwf_part, w.nsplit, w.r_part, w.nrpart, W, b, gamma, mean, var, 0,
+                          dW, db, dgamma, dbeta, st));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_eval_fwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                              const float* gamma, const float* beta, const float* mean,
+                              const float* var, void* z, void* y_saved, void* ws, size_t ws_bytes,
+                              void* stream) {
+  (void)ws; (void)ws_bytes;
+  Geom g;
+  convbn_status s = make_geom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(beta); REQUIRE_PTR(mean);
+  REQUIRE_PTR(var); REQUIRE_PTR(z); REQUIRE_PTR(y_saved);
+  OPTIONAL_PTR(b);
+  const int dt = desc->dtype;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  LAUNCH(run_fprop(g, dt, x, W, b, y_saved, st));                         // Y = w (*) X + b
+  LAUNCH(launch_bn_affine_fwd(g, dt, y_saved, gamma, beta, mean, var, z, st));  // Z from Y
+  return CONVBN_OK;
+}
+
+convbn_status convbn_eval_bwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                              const float* gamma, const float* mean, const float* var,
+                              const void* y_saved, const void* dz, void* dx, void* dW, float* db,
+                              float* dgamma, float* dbeta, void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  convbn_status s = make_geom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
+  REQUIRE_PTR(y_saved); REQUIRE_PTR(dz); REQUIRE_PTR(dW); REQUIRE_PTR(dgamma); REQUIRE_PTR(dbeta);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(dx); OPTIONAL_PTR(db);
+  if ((b == nullptr) != (db == nullptr))
+    return fail(CONVBN_ERR_NULL, "db must be given exactly when b is given");
+  const int dt = desc->dtype;
+  s = check_ws(carve_eval_bwd(g, dt, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const EvalBwdWs w = carve_eval_bwd(g, dt, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // dY = s dZ, partial per-channel sums of dZ and dZ (Y-mu)/sqrt(var+eps)
+  LAUNCH(launch_bn_bwd(g, dt, dz, y_saved, gamma, mean, var, w.dy, w.bn_part, st));
+  LAUNCH(launch_bn_bwd_finalize(g, w.bn_part, w.nparts, gamma, var, dgamma, dbeta, db, st));
+  if (dx) {
+    // the input-gradient pass reads the weight as [Cin][kH][kW][Cout]
+    LAUNCH(launch_fold(g, dt, W, nullptr, nullptr, nullptr, nullptr, nullptr, 1, nullptr, w.w_crsk,
+                       nullptr, st));
+    LAUNCH(run_dgrad(g, dt, w.dy, w.w_crsk, dx, st));   // dX = w_rot (*) dY
+  }
+  LAUNCH(run_wgrad(g, dt, x, w.dy, w.dwf_part, w.nsplit, st));   // dW = dY (.) X
+  LAUNCH(launch_fold_back(g, dt, w.dwf_part, w.nsplit, nullptr, 0, W, nullptr, nullptr, nullptr,
+                          nullptr, 1, dW, nullptr, nullptr, nullptr, st));
+  return CONVBN_OK;
+}
+
+}  // extern "C"

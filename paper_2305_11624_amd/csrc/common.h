@@ -1,0 +1,98 @@
+// Shared device helpers and the internal launch interface of libconvbn (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/convbn.h"
+
+namespace convbn {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // RNE
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// Round-to-nearest-even fp32 -> bf16 bit pattern (finite inputs; NaN stays NaN).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  bf16_t h = (bf16_t)f;
+  return (uint32_t)__builtin_bit_cast(unsigned short, h);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// Geometry of one block, with the derived sizes the kernels index with.
+struct Geom {
+  int N, Cin, Hin, Win, Cout, kH, kW, sh, sw, ph, pw, Hout, Wout;
+  int M;      // N*Hout*Wout   (output pixels)
+  int Min;    // N*Hin*Win     (input pixels)
+  int K;      // kH*kW*Cin     (reduction length of the forward conv)
+  float eps;
+};
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- launchers (each enqueues on `st`, returns the hipError of the launch) ----
+
+// fold.hip
+// w_krsc / w_crsk / bfold may each be NULL (skipped).  identity != 0: s = 1, b' = b.
+hipError_t launch_fold(const Geom& g, int dtype, const void* W, const float* b, const float* gamma,
+                       const float* beta, const float* mean, const float* var, int identity,
+                       void* w_krsc, void* w_crsk, float* bfold, hipStream_t st);
+// Sums `nsplit` fp32 partial copies of dJ/dw' ([nsplit][Cout][K]) and `nrpart` partial
+// row-sum vectors ([nrpart][Cout]); writes dW, db, dgamma, dbeta (Table 2 "Tune").
+// identity != 0 (Eval path): dW = sum of partials only, other outputs untouched.
+hipError_t launch_fold_back(const Geom& g, int dtype, const float* dwf_part, int nsplit,
+                            const float* r_part, int nrpart, const void* W, const float* b,
+                            const float* gamma, const float* mean, const float* var, int identity,
+                            void* dW, float* db, float* dgamma, float* dbeta, hipStream_t st);
+int colsum_parts(const Geom& g);
+hipError_t launch_colsum(const Geom& g, int dtype, const void* dz, float* r_part, hipStream_t st);
+hipError_t launch_bn_affine_fwd(const Geom& g, int dtype, const void* y, const float* gamma,
+                                const float* beta, const float* mean, const float* var, void* z,
+                                hipStream_t st);
+int bn_bwd_parts(const Geom& g);
+hipError_t launch_bn_bwd(const Geom& g, int dtype, const void* dz, const void* y, const float* gamma,
+                         const float* mean, const float* var, void* dy, float* part /*[parts][2][Cout]*/,
+                         hipStream_t st);
+hipError_t launch_bn_bwd_finalize(const Geom& g, const float* part, int parts, const float* gamma,
+                                  const float* var, float* dgamma, float* dbeta, float* db,
+                                  hipStream_t st);
+
+// conv_direct.hip : one thread per output element, fp32 accumulation (any shape, both dtypes)
+hipError_t launch_fprop_direct(const Geom& g, int dtype, const void* x, const void* w_krsc,
+                               const float* bias, void* z, hipStream_t st);
+hipError_t launch_dgrad_direct(const Geom& g, int dtype, const void* dz, const void* w_crsk,
+                               void* dx, hipStream_t st);
+int wgrad_direct_splits(const Geom& g);
+hipError_t launch_wgrad_direct(const Geom& g, int dtype, const void* x, const void* dz,
+                               float* dwf_part /*[splits][Cout][K]*/, hipStream_t st);
+
+// conv_igemm.hip : bf16 MFMA implicit GEMM
+bool igemm_supported(const Geom& g, int dtype);
+int wgrad_splits(const Geom& g);
+hipError_t launch_fprop_igemm(const Geom& g, const void* x, const void* w_krsc, const float* bias,
+                              void* z, hipStream_t st);
+hipError_t launch_dgrad_igemm(const Geom& g, const void* dz, const void* w_crsk, void* dx,
+                              hipStream_t st);
+hipError_t launch_wgrad_igemm(const Geom& g, const void* x, const void* dz, float* dwf_part,
+                              int nsplit, hipStream_t st);
+
+}  // namespace convbn

@@ -1,0 +1,349 @@
+// Memory-bound kernels around the convolution:
+//   fold        w' = s w, b' = (b - mu) s + beta            (Sec. 3.3, definitions of w', b')
+//   fold-back   dW = s dw', dgamma, dbeta, db               (Table 2, row "Tune")
+//   colsum      r_c = sum_{n,h,w} dZ                        (App. B: backward of a broadcast)
+//   bn_affine   Z = gamma (Y - mu)/sqrt(var+eps) + beta     (Sec. 3.1; Eval comparison path)
+//   bn_bwd      dY = s dZ and the per-channel sums of Table 2, row "Eval"
+#include "common.h"
+
+namespace convbn {
+
+namespace {
+
+constexpr int FOLD_TCO = 32;  // output channels per tile
+constexpr int FOLD_TK = 64;   // reduction-index (tap, ci) entries per tile
+
+// One tile = FOLD_TCO rows of W x FOLD_TK columns.  Rows of W ([Cout][K], K = taps*Cin)
+// are read coalesced along K, scaled, written back in the same order (w_krsc) and,
+// through an LDS transpose, as [Cin][taps][Cout] (w_crsk) with Cout contiguous.
+template <typename T>
+__global__ __launch_bounds__(256) void fold_kernel(const T* __restrict__ W, const float* __restrict__ b,
+                                                   const float* __restrict__ gamma,
+                                                   const float* __restrict__ beta,
+                                                   const float* __restrict__ mean,
+                                                   const float* __restrict__ var, float eps,
+                                                   int identity, int Cout, int K, int Cin, int taps,
+                                                   T* __restrict__ w_krsc, T* __restrict__ w_crsk,
+                                                   float* __restrict__ bfold) {
+  __shared__ float s_scale[FOLD_TCO];
+  __shared__ T tile[FOLD_TK][FOLD_TCO + 2];
+  const int tid = threadIdx.x;
+  const int co0 = blockIdx.y * FOLD_TCO;
+  const int k0 = blockIdx.x * FOLD_TK;
+  if (tid < FOLD_TCO) {
+    const int co = co0 + tid;
+    float s = 1.f;
+    if (co < Cout) {
+      if (!identity) s = gamma[co] / sqrtf(var[co] + eps);
+      if (blockIdx.x == 0 && bfold) {
+        const float bc = b ? b[co] : 0.f;
+        bfold[co] = identity ? bc : (bc - mean[co]) * s + beta[co];
+      }
+    }
+    s_scale[tid] = s;
+  }
+  __syncthreads();
+  // read + scale: a wave reads 64 consecutive columns of one row; rows tid/64 + 4e
+  {
+    const int kc = tid & 63;
+    const int k = k0 + kc;
+#pragma unroll
+    for (int e = 0; e < FOLD_TCO / 4; ++e) {
+      const int r = (tid >> 6) + 4 * e;
+      const int co = co0 + r;
+      T v = from_f32<T>(0.f);
+      if (co < Cout && k < K) {
+        v = from_f32<T>(to_f32(W[(size_t)co * K + k]) * s_scale[r]);
+        if (w_krsc) w_krsc[(size_t)co * K + k] = v;
+      }
+      tile[kc][r] = v;
+    }
+  }
+  if (!w_crsk) return;
+  __syncthreads();
+  // transposed write: thread -> (k row = tid/4, co cols (tid%4)*8 .. +8)
+  {
+    const int kr = tid >> 2;
+    const int cc = (tid & 3) * 8;
+    const int k = k0 + kr;
+    if (k < K) {
+      const int tap = k / Cin, ci = k - tap * Cin;
+      T* dst = w_crsk + ((size_t)ci * taps + tap) * Cout + co0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (co0 + cc + e < Cout) dst[cc + e] = tile[kr][cc + e];
+    }
+  }
+}
+
+// One block per output channel.
+template <typename T>
+__global__ __launch_bounds__(256) void fold_back_kernel(
+    const float* __restrict__ part, int nsplit, const float* __restrict__ r_part, int nrpart,
+    const T* __restrict__ W, const float* __restrict__ b, const float* __restrict__ gamma,
+    const float* __restrict__ mean, const float* __restrict__ var, float eps, int identity, int Cout,
+    int K, T* __restrict__ dW, float* __restrict__ db, float* __restrict__ dgamma,
+    float* __restrict__ dbeta) {
+  __shared__ float red[4];
+  const int co = blockIdx.x;
+  const int tid = threadIdx.x;
+  const size_t P = (size_t)Cout * K;
+  float s = 1.f, sd = 1.f;
+  if (!identity) {
+    sd = sqrtf(var[co] + eps);
+    s = gamma[co] / sd;
+  }
+  float dot = 0.f;
+  for (int k = tid; k < K; k += 256) {
+    const size_t idx = (size_t)co * K + k;
+    float v = 0.f;
+    for (int sp = 0; sp < nsplit; ++sp) v += part[sp * P + idx];
+    dW[idx] = from_f32<T>(s * v);
+    dot += v * to_f32(W[idx]);
+  }
+  if (identity) return;
+  dot = wave_sum(dot);
+  if ((tid & 63) == 0) red[tid >> 6] = dot;
+  __syncthreads();
+  if (tid == 0) {
+    dot = red[0] + red[1] + red[2] + red[3];
+    float r = 0.f;
+    for (int p = 0; p < nrpart; ++p) r += r_part[(size_t)p * Cout + co];
+    const float bc = b ? b[co] : 0.f;
+    dbeta[co] = r;
+    dgamma[co] = (dot + r * (bc - mean[co])) / sd;
+    if (db) db[co] = s * r;
+  }
+}
+
+// Column reductions over a [M][Cout] channels-last tensor.  `cw` threads walk the
+// channel dimension (coalesced), 256/cw row lanes stride over this block's rows.
+__device__ __forceinline__ int pow2_cw(int Cout) {
+  int cw = 1;
+  while (cw < Cout && cw < 256) cw <<= 1;
+  return cw;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ dz, int M, int Cout,
+                                                     int rows_per_block, float* __restrict__ part) {
+  __shared__ float red[256];
+  const int cw = pow2_cw(Cout);
+  const int lanes = 256 / cw;
+  const int tc = threadIdx.x % cw, tr = threadIdx.x / cw;
+  const int m0 = blockIdx.x * rows_per_block;
+  const int m1 = min(M, m0 + rows_per_block);
+  for (int c0 = 0; c0 < Cout; c0 += cw) {
+    const int co = c0 + tc;
+    float acc = 0.f;
+    if (co < Cout)
+      for (int m = m0 + tr; m < m1; m += lanes) acc += to_f32(dz[(size_t)m * Cout + co]);
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (tr == 0 && co < Cout) {
+      for (int l = 1; l < lanes; ++l) acc += red[l * cw + tc];
+      part[(size_t)blockIdx.x * Cout + co] = acc;
+    }
+    __syncthreads();
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bn_affine_fwd_kernel(const T* __restrict__ y,
+                                                            const float* __restrict__ gamma,
+                                                            const float* __restrict__ beta,
+                                                            const float* __restrict__ mean,
+                                                            const float* __restrict__ var, float eps,
+                                                            size_t total, int Cout, T* __restrict__ z) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += stride) {
+    const int co = (int)(i % Cout);
+    const float ybar = (to_f32(y[i]) - mean[co]) / sqrtf(var[co] + eps);
+    z[i] = from_f32<T>(gamma[co] * ybar + beta[co]);
+  }
+}
+
+// 8 bf16 per thread, Cout % 8 == 0; per-channel scale/shift staged in LDS (2*Cout floats).
+__global__ __launch_bounds__(256) void bn_affine_fwd_bf16x8_kernel(
+    const uint4* __restrict__ y, const float* __restrict__ gamma, const float* __restrict__ beta,
+    const float* __restrict__ mean, const float* __restrict__ var, float eps, size_t nvec, int Cout,
+    uint4* __restrict__ z) {
+  extern __shared__ float sm[];
+  float* s_s = sm;
+  float* s_t = sm + Cout;
+  for (int c = threadIdx.x; c < Cout; c += 256) {
+    const float s = gamma[c] / sqrtf(var[c] + eps);
+    s_s[c] = s;
+    s_t[c] = beta[c] - mean[c] * s;
+  }
+  __syncthreads();
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
+    const int co = (int)((i * 8) % Cout);
+    const uint4 v = y[i];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int c = co + 2 * e;
+      o[e] = pack_bf16x2(bf16_lo(w[e]) * s_s[c] + s_t[c], bf16_hi(w[e]) * s_s[c + 1] + s_t[c + 1]);
+    }
+    z[i] = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bn_bwd_kernel(const T* __restrict__ dz, const T* __restrict__ y,
+                                                     const float* __restrict__ gamma,
+                                                     const float* __restrict__ mean,
+                                                     const float* __restrict__ var, float eps, int M,
+                                                     int Cout, int rows_per_block, T* __restrict__ dy,
+                                                     float* __restrict__ part) {
+  __shared__ float red0[256];
+  __shared__ float red1[256];
+  const int cw = pow2_cw(Cout);
+  const int lanes = 256 / cw;
+  const int tc = threadIdx.x % cw, tr = threadIdx.x / cw;
+  const int m0 = blockIdx.x * rows_per_block;
+  const int m1 = min(M, m0 + rows_per_block);
+  for (int c0 = 0; c0 < Cout; c0 += cw) {
+    const int co = c0 + tc;
+    float a0 = 0.f, a1 = 0.f;
+    if (co < Cout) {
+      const float sd = sqrtf(var[co] + eps);
+      const float s = gamma[co] / sd, mu = mean[co];
+      for (int m = m0 + tr; m < m1; m += lanes) {
+        const size_t idx = (size_t)m * Cout + co;
+        const float g = to_f32(dz[idx]);
+        dy[idx] = from_f32<T>(s * g);
+        a0 += g;
+        a1 += g * ((to_f32(y[idx]) - mu) / sd);
+      }
+    }
+    red0[threadIdx.x] = a0;
+    red1[threadIdx.x] = a1;
+    __syncthreads();
+    if (tr == 0 && co < Cout) {
+      for (int l = 1; l < lanes; ++l) {
+        a0 += red0[l * cw + tc];
+        a1 += red1[l * cw + tc];
+      }
+      part[((size_t)blockIdx.x * 2 + 0) * Cout + co] = a0;
+      part[((size_t)blockIdx.x * 2 + 1) * Cout + co] = a1;
+    }
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __restrict__ part, int parts,
+                                                              const float* __restrict__ gamma,
+                                                              const float* __restrict__ var, float eps,
+                                                              int Cout, float* __restrict__ dgamma,
+                                                              float* __restrict__ dbeta,
+                                                              float* __restrict__ db) {
+  const int co = blockIdx.x * 256 + threadIdx.x;
+  if (co >= Cout) return;
+  float a0 = 0.f, a1 = 0.f;
+  for (int p = 0; p < parts; ++p) {
+    a0 += part[((size_t)p * 2 + 0) * Cout + co];
+    a1 += part[((size_t)p * 2 + 1) * Cout + co];
+  }
+  dbeta[co] = a0;
+  dgamma[co] = a1;
+  if (db) db[co] = gamma[co] / sqrtf(var[co] + eps) * a0;
+}
+
+int rows_per_block_for(int M, int parts) { return ceil_div(M, parts); }
+
+}  // namespace
+
+hipError_t launch_fold(const Geom& g, int dtype, const void* W, const float* b, const float* gamma,
+                       const float* beta, const float* mean, const float* var, int identity,
+                       void* w_krsc, void* w_crsk, float* bfold, hipStream_t st) {
+  dim3 grid(ceil_div(g.K, FOLD_TK), ceil_div(g.Cout, FOLD_TCO));
+  const int taps = g.kH * g.kW;
+  if (dtype == CONVBN_BF16)
+    hipLaunchKernelGGL(fold_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)W, b, gamma, beta,
+                       mean, var, g.eps, identity, g.Cout, g.K, g.Cin, taps, (bf16_t*)w_krsc,
+                       (bf16_t*)w_crsk, bfold);
+  else
+    hipLaunchKernelGGL(fold_kernel<float>, grid, dim3(256), 0, st, (const float*)W, b, gamma, beta,
+                       mean, var, g.eps, identity, g.Cout, g.K, g.Cin, taps, (float*)w_krsc,
+                       (float*)w_crsk, bfold);
+  return hipGetLastError();
+}
+
+hipError_t launch_fold_back(const Geom& g, int dtype, const float* dwf_part, int nsplit,
+                            const float* r_part, int nrpart, const void* W, const float* b,
+                            const float* gamma, const float* mean, const float* var, int identity,
+                            void* dW, float* db, float* dgamma, float* dbeta, hipStream_t st) {
+  if (dtype == CONVBN_BF16)
+    hipLaunchKernelGGL(fold_back_kernel<bf16_t>, dim3(g.Cout), dim3(256), 0, st, dwf_part, nsplit,
+                       r_part, nrpart, (const bf16_t*)W, b, gamma, mean, var, g.eps, identity, g.Cout,
+                       g.K, (bf16_t*)dW, db, dgamma, dbeta);
+  else
+    hipLaunchKernelGGL(fold_back_kernel<float>, dim3(g.Cout), dim3(256), 0, st, dwf_part, nsplit,
+                       r_part, nrpart, (const float*)W, b, gamma, mean, var, g.eps, identity, g.Cout,
+                       g.K, (float*)dW, db, dgamma, dbeta);
+  return hipGetLastError();
+}
+
+int colsum_parts(const Geom& g) { return g.M < 256 * 64 ? ceil_div(g.M, 64) : 256; }
+
+hipError_t launch_colsum(const Geom& g, int dtype, const void* dz, float* r_part, hipStream_t st) {
+  const int parts = colsum_parts(g);
+  const int rpb = rows_per_block_for(g.M, parts);
+  if (dtype == CONVBN_BF16)
+    hipLaunchKernelGGL(colsum_kernel<bf16_t>, dim3(parts), dim3(256), 0, st, (const bf16_t*)dz, g.M,
+                       g.Cout, rpb, r_part);
+  else
+    hipLaunchKernelGGL(colsum_kernel<float>, dim3(parts), dim3(256), 0, st, (const float*)dz, g.M,
+                       g.Cout, rpb, r_part);
+  return hipGetLastError();
+}
+
+hipError_t launch_bn_affine_fwd(const Geom& g, int dtype, const void* y, const float* gamma,
+                                const float* beta, const float* mean, const float* var, void* z,
+                                hipStream_t st) {
+  const size_t total = (size_t)g.M * g.Cout;
+  if (dtype == CONVBN_BF16 && g.Cout % 8 == 0 && g.Cout <= 4096) {
+    const size_t nvec = total / 8;
+    const int blocks = (int)min((size_t)2048, (nvec + 255) / 256);
+    hipLaunchKernelGGL(bn_affine_fwd_bf16x8_kernel, dim3(blocks), dim3(256), 2 * g.Cout * sizeof(float), st, (const uint4*)y,
+                       gamma, beta, mean, var, g.eps, nvec, g.Cout, (uint4*)z);
+  } else {
+    const int blocks = (int)min((size_t)4096, (total + 255) / 256);
+    if (dtype == CONVBN_BF16)
+      hipLaunchKernelGGL(bn_affine_fwd_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st,
+                         (const bf16_t*)y, gamma, beta, mean, var, g.eps, total, g.Cout, (bf16_t*)z);
+    else
+      hipLaunchKernelGGL(bn_affine_fwd_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)y,
+                         gamma, beta, mean, var, g.eps, total, g.Cout, (float*)z);
+  }
+  return hipGetLastError();
+}
+
+int bn_bwd_parts(const Geom& g) { return colsum_parts(g); }
+
+hipError_t launch_bn_bwd(const Geom& g, int dtype, const void* dz, const void* y, const float* gamma,
+                         const float* mean, const float* var, void* dy, float* part, hipStream_t st) {
+  const int parts = bn_bwd_parts(g);
+  const int rpb = rows_per_block_for(g.M, parts);
+  if (dtype == CONVBN_BF16)
+    hipLaunchKernelGGL(bn_bwd_kernel<bf16_t>, dim3(parts), dim3(256), 0, st, (const bf16_t*)dz,
+                       (const bf16_t*)y, gamma, mean, var, g.eps, g.M, g.Cout, rpb, (bf16_t*)dy, part);
+  else
+    hipLaunchKernelGGL(bn_bwd_kernel<float>, dim3(parts), dim3(256), 0, st, (const float*)dz,
+                       (const float*)y, gamma, mean, var, g.eps, g.M, g.Cout, rpb, (float*)dy, part);
+  return hipGetLastError();
+}
+
+hipError_t launch_bn_bwd_finalize(const Geom& g, const float* part, int parts, const float* gamma,
+                                  const float* var, float* dgamma, float* dbeta, float* db,
+                                  hipStream_t st) {
+  hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(g.Cout, 256)), dim3(256), 0, st, part, parts,
+                     gamma, var, g.eps, g.Cout, dgamma, dbeta, db);
+  return hipGetLastError();
+}
+
+}  // namespace convbn

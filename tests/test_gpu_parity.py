@@ -1,0 +1,113 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle, element
+by element on identical seeded inputs.  Sizes span several tiles and ragged tails while
+the oracle still finishes in seconds."""
+import dataclasses
+
+import pytest
+import torch
+
+from paper_2305_11624_amd import synth
+from paper_2305_11624_amd.synth import BlockShape
+
+from helpers import compare, oracle_block
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(inp, mode, keep_folded=True, need_dx=True):
+    from paper_2305_11624_amd.runner import BlockRun
+    r = BlockRun(inp, mode=mode, keep_folded=keep_folded, need_dx=need_dx, poison=True)
+    r.step()
+    return r.results()
+
+
+def test_config0_fp32_tune_and_eval():
+    """Benchmark configuration 0 exactly as stated (fp32, seed 0), both modes."""
+    inp = synth.make_inputs(synth.CONFIGS["c0"])
+    ref = oracle_block(inp)
+    for mode in ("tune", "eval"):
+        res = _run(inp, mode)
+        compare(res, ref, "f32", tag=f"c0/{mode}")
+        if mode == "tune":
+            compare(res, ref, "f32", keys=("Wf",), tag="c0/fold")
+        else:
+            compare(res, ref, "f32", keys=("Y",), tag="c0/Y")
+
+
+F32_SHAPES = [
+    BlockShape("f32_bias_s2", 2, 5, 9, 8, 7, 3, 2, 1, "f32", 21),
+    BlockShape("f32_1x1", 3, 6, 5, 7, 10, 1, 1, 0, "f32", 22),
+    BlockShape("f32_7x7", 1, 3, 20, 20, 8, 7, 2, 3, "f32", 23),
+    BlockShape("f32_nopad", 2, 4, 8, 8, 4, 3, 1, 0, "f32", 24),
+]
+
+
+@pytest.mark.parametrize("shape", F32_SHAPES, ids=lambda s: s.name)
+@pytest.mark.parametrize("mode", ["tune", "eval"])
+def test_fp32_odd_shapes(shape, mode):
+    inp = synth.make_inputs(shape, bias=True)
+    ref = oracle_block(inp)
+    compare(_run(inp, mode), ref, "f32", tag=f"{shape.name}/{mode}")
+
+
+BF16_SHAPES = [
+    # MFMA path: several tiles + ragged tails in every GEMM dimension
+    BlockShape("b_3x3_64", 3, 64, 14, 14, 64, 3, 1, 1, "bf16", 31),
+    BlockShape("b_3x3_ragged", 2, 72, 13, 11, 136, 3, 1, 1, "bf16", 32),
+    BlockShape("b_1x1", 2, 256, 12, 12, 64, 1, 1, 0, "bf16", 33),
+    BlockShape("b_1x1_s2", 2, 64, 14, 14, 128, 1, 2, 0, "bf16", 34),
+    BlockShape("b_3x3_s2", 2, 32, 15, 15, 40, 3, 2, 1, "bf16", 35),
+    BlockShape("b_7x7_cin8", 1, 8, 30, 30, 16, 7, 2, 3, "bf16", 36),
+    BlockShape("b_small7", 4, 128, 7, 7, 160, 3, 1, 1, "bf16", 37),
+    # direct path (channels not multiples of 8), incl. a stem-like 7x7/2 with Cin=3
+    BlockShape("b_stem", 2, 3, 32, 32, 64, 7, 2, 3, "bf16", 38),
+    BlockShape("b_odd_ch", 2, 12, 9, 9, 20, 3, 1, 1, "bf16", 39),
+]
+
+
+@pytest.mark.parametrize("shape", BF16_SHAPES, ids=lambda s: s.name)
+@pytest.mark.parametrize("mode", ["tune", "eval"])
+def test_bf16_shapes(shape, mode):
+    inp = synth.make_inputs(shape)
+    ref = oracle_block(inp)
+    res = _run(inp, mode)
+    compare(res, ref, "bf16", tag=f"{shape.name}/{mode}")
+    if mode == "tune":
+        compare(res, ref, "bf16", keys=("Wf",), tag=f"{shape.name}/fold")
+
+
+def test_bf16_bias_refold_and_no_dx():
+    shape = BlockShape("b_bias", 2, 64, 10, 10, 72, 3, 1, 1, "bf16", 41)
+    inp = synth.make_inputs(shape, bias=True)
+    ref = oracle_block(inp)
+    a = _run(inp, "tune", keep_folded=True)
+    b = _run(inp, "tune", keep_folded=False)
+    c = _run(inp, "tune", need_dx=False)
+    compare(a, ref, "bf16", tag="bias/keep")
+    compare(b, ref, "bf16", tag="bias/refold")
+    for k in ("Z", "dX", "dW", "db", "dgamma", "dbeta"):
+        assert torch.equal(a[k], b[k]), k          # re-folding reproduces the kept w' bit for bit
+    assert c["dX"] is None
+    for k in ("dW", "dgamma", "dbeta"):
+        assert torch.equal(a[k], c[k]), k
+    compare(_run(inp, "eval"), ref, "bf16", tag="bias/eval")
+
+
+def test_bf16_wide_scale_with_zero_channels():
+    """BN scales spread over [0, 30] with exact zeros (the range of pretrained
+    backbones, Fig. 2a): Tune mode never divides by gamma."""
+    shape = BlockShape("b_wide", 2, 32, 12, 12, 32, 3, 1, 1, "bf16", 42)
+    inp = synth.make_inputs(shape, wide_scale=True)
+    ref = oracle_block(inp)
+    compare(_run(inp, "tune"), ref, "bf16", tag="wide/tune")
+    compare(_run(inp, "eval"), ref, "bf16", tag="wide/eval")
+
+
+def test_tune_matches_eval_on_gpu():
+    """Same library, two routes (Sec. 3.4.1): outputs agree to bf16 rounding."""
+    shape = BlockShape("b_te", 2, 64, 14, 14, 64, 3, 1, 1, "bf16", 43)
+    inp = synth.make_inputs(shape)
+    t, e = _run(inp, "tune"), _run(inp, "eval")
+    for k in ("Z", "dX", "dW", "dgamma", "dbeta"):
+        ref = e[k].numpy()
+        compare({k: t[k]}, {k: ref}, "bf16", keys=(k,), tag=f"tune-vs-eval/{k}")
