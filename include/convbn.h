@@ -86,8 +86,8 @@ int32_t convbn_wout(const convbn_desc *desc);
  * workspace carries nothing from one call to the next. */
 size_t convbn_workspace_bytes(const convbn_desc *desc, int mode, int pass);
 
-/* Tune-mode forward (Sec. 3.3: definitions of w', b'; Sec. 3.4: "calculate the
- * transformed parameters on-the-fly", then a single convolution).
+/* Tune-mode forward (Sec. 3.3: definitions of w', b'; Sec. 3.4: the folded
+ * parameters are recomputed on every call, then a single convolution runs).
  *   in : x, W, b (nullable = no conv bias), gamma, beta, mean, var
  *   out: z            block output
  *        w_folded     nullable.  If given, receives w' ([Cin][kH][kW][Cout]) -- the
@@ -133,6 +133,47 @@ convbn_status convbn_eval_bwd(const convbn_desc *desc, const void *x, const void
                               const float *var, const void *y_saved, const void *dz, void *dx,
                               void *dW, float *db, float *dgamma, float *dbeta, void *ws,
                               size_t ws_bytes, void *stream);
+
+/* ---- The individual steps of the Tune-mode block (each is one kernel) -------------
+ * convbn_tune_fwd is convbn_fold followed by convbn_conv_fprop; convbn_tune_bwd is
+ * convbn_conv_dgrad, convbn_conv_wgrad and convbn_fold_back.  They are exported so that
+ * each step can be checked and timed on its own.  Same conventions as above. */
+
+/* Fold (Sec. 3.3):  w' = s w,  b' = (b - mu) s + beta,  s = gamma/sqrt(var+eps).
+ *   out (each nullable = not wanted): w_fprop  w' as [Cout][kH][kW][Cin],
+ *                                     w_folded w' as [Cin][kH][kW][Cout],
+ *                                     b_folded [Cout] fp32. */
+convbn_status convbn_fold(const convbn_desc *desc, const void *W, const float *b,
+                          const float *gamma, const float *beta, const float *mean,
+                          const float *var, void *w_fprop, void *w_folded, float *b_folded,
+                          void *stream);
+
+/* Forward convolution  z = w (*) x + bias  (Sec. 3.1; cross-correlation, zero padding).
+ *   w is [Cout][kH][kW][Cin]; bias [Cout] fp32, nullable. */
+convbn_status convbn_conv_fprop(const convbn_desc *desc, const void *x, const void *w,
+                                const float *bias, void *z, void *stream);
+
+/* Input gradient  dx = w_rot (*) dz  (Sec. 3.2.1).  w_t is [Cin][kH][kW][Cout]. */
+convbn_status convbn_conv_dgrad(const convbn_desc *desc, const void *dz, const void *w_t,
+                                void *dx, void *stream);
+
+/* Weight gradient  dw = dz (.) x  and  r_c = sum_{n,h,w} dz  (Sec. 3.2.1; App. B), left as
+ * fp32 partial sums over slices of the output pixels:
+ *   dw_part [convbn_wgrad_parts][Cout][kH][kW][Cin],  r_part [convbn_rsum_parts][Cout].
+ * The true values are the sums over the leading index; convbn_fold_back adds them up. */
+int32_t convbn_wgrad_parts(const convbn_desc *desc);
+int32_t convbn_rsum_parts(const convbn_desc *desc);
+/* r_part is nullable (then only the weight-gradient kernel runs). */
+convbn_status convbn_conv_wgrad(const convbn_desc *desc, const void *x, const void *dz,
+                                float *dw_part, float *r_part, void *stream);
+
+/* Fold-back (Table 2, row "Tune", last four lines): from the partial sums of dw' and r,
+ *   dW = s dw',  db = s r (nullable with b),  dgamma = (<dw'_c, w_c> + r_c (b_c - mu_c))/sqrt(var_c+eps),
+ *   dbeta = r. */
+convbn_status convbn_fold_back(const convbn_desc *desc, const float *dw_part, const float *r_part,
+                               const void *W, const float *b, const float *gamma,
+                               const float *mean, const float *var, void *dW, float *db,
+                               float *dgamma, float *dbeta, void *stream);
 
 /* Bytes a block must keep alive between its forward and its backward call in
  * addition to X (App. K.1): Eval keeps Y (N Cout Hout Wout elements); Tune keeps

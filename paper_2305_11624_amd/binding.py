@@ -21,7 +21,8 @@ PASS_FWD, PASS_BWD = 0, 1
 
 EXPORTS = ["convbn_hout", "convbn_wout", "convbn_workspace_bytes", "convbn_saved_bytes",
            "convbn_tune_fwd", "convbn_tune_bwd", "convbn_eval_fwd", "convbn_eval_bwd",
-           "convbn_last_error"]
+           "convbn_last_error", "convbn_fold", "convbn_conv_fprop", "convbn_conv_dgrad",
+           "convbn_wgrad_parts", "convbn_rsum_parts", "convbn_conv_wgrad", "convbn_fold_back"]
 
 
 class Desc(C.Structure):
@@ -73,6 +74,20 @@ def lib():
         L.convbn_eval_bwd.restype = C.c_int
         L.convbn_eval_bwd.argtypes = [dp, vp, vp, fp, fp, fp, fp, vp, vp, vp, vp, fp, fp, fp, vp,
                                       C.c_size_t, vp]
+        L.convbn_fold.restype = C.c_int
+        L.convbn_fold.argtypes = [dp, vp, fp, fp, fp, fp, fp, vp, vp, fp, vp]
+        L.convbn_conv_fprop.restype = C.c_int
+        L.convbn_conv_fprop.argtypes = [dp, vp, vp, fp, vp, vp]
+        L.convbn_conv_dgrad.restype = C.c_int
+        L.convbn_conv_dgrad.argtypes = [dp, vp, vp, vp, vp]
+        L.convbn_wgrad_parts.restype = C.c_int32
+        L.convbn_wgrad_parts.argtypes = [dp]
+        L.convbn_rsum_parts.restype = C.c_int32
+        L.convbn_rsum_parts.argtypes = [dp]
+        L.convbn_conv_wgrad.restype = C.c_int
+        L.convbn_conv_wgrad.argtypes = [dp, vp, vp, fp, fp, vp]
+        L.convbn_fold_back.restype = C.c_int
+        L.convbn_fold_back.argtypes = [dp, fp, fp, vp, fp, fp, fp, fp, vp, fp, fp, fp, vp]
         _lib = L
     return _lib
 
@@ -180,6 +195,57 @@ def convbn_eval_bwd(desc, x, W, b, gamma, mean, var, y_saved, dz, dx, dW, db, dg
     st = lib().convbn_eval_bwd(C.byref(desc), _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(mean),
                                _ptr(var), _ptr(y_saved), _ptr(dz), _ptr(dx), _ptr(dW), _ptr(db),
                                _ptr(dgamma), _ptr(dbeta), p, n, _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_fold(desc, W, b, gamma, beta, mean, var, w_fprop, w_folded, b_folded, stream=None,
+                check=True):
+    st = lib().convbn_fold(C.byref(desc), _ptr(W), _ptr(b), _ptr(gamma), _ptr(beta), _ptr(mean),
+                           _ptr(var), _ptr(w_fprop), _ptr(w_folded), _ptr(b_folded),
+                           _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_conv_fprop(desc, x, w, bias, z, stream=None, check=True):
+    st = lib().convbn_conv_fprop(C.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(z),
+                                 _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_conv_dgrad(desc, dz, w_t, dx, stream=None, check=True):
+    st = lib().convbn_conv_dgrad(C.byref(desc), _ptr(dz), _ptr(w_t), _ptr(dx), _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_wgrad_parts(desc) -> int:
+    return lib().convbn_wgrad_parts(C.byref(desc))
+
+
+def convbn_rsum_parts(desc) -> int:
+    return lib().convbn_rsum_parts(C.byref(desc))
+
+
+def convbn_conv_wgrad(desc, x, dz, dw_part, r_part, stream=None, check=True):
+    st = lib().convbn_conv_wgrad(C.byref(desc), _ptr(x), _ptr(dz), _ptr(dw_part), _ptr(r_part),
+                                 _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_fold_back(desc, dw_part, r_part, W, b, gamma, mean, var, dW, db, dgamma, dbeta,
+                     stream=None, check=True):
+    st = lib().convbn_fold_back(C.byref(desc), _ptr(dw_part), _ptr(r_part), _ptr(W), _ptr(b),
+                                _ptr(gamma), _ptr(mean), _ptr(var), _ptr(dW), _ptr(db),
+                                _ptr(dgamma), _ptr(dbeta), _stream(stream))
     if check:
         _check(st)
     return st

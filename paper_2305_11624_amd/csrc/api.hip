@@ -291,4 +291,79 @@ convbn_status convbn_eval_bwd(const convbn_desc* desc, const void* x, const void
   return CONVBN_OK;
 }
 
+convbn_status convbn_fold(const convbn_desc* desc, const void* W, const float* b, const float* gamma,
+                          const float* beta, const float* mean, const float* var, void* w_fprop,
+                          void* w_folded, float* b_folded, void* stream) {
+  Geom g;
+  convbn_status s = make_geom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(beta); OPTIONAL_PTR(w_fprop); OPTIONAL_PTR(w_folded);
+  OPTIONAL_PTR(b_folded);
+  if (b_folded && !beta) return fail(CONVBN_ERR_NULL, "beta is required when b_folded is wanted");
+  LAUNCH(launch_fold(g, desc->dtype, W, b, gamma, beta, mean, var, 0, w_fprop, w_folded, b_folded,
+                     static_cast<hipStream_t>(stream)));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_conv_fprop(const convbn_desc* desc, const void* x, const void* w,
+                                const float* bias, void* z, void* stream) {
+  Geom g;
+  convbn_status s = make_geom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(w); REQUIRE_PTR(z); OPTIONAL_PTR(bias);
+  LAUNCH(run_fprop(g, desc->dtype, x, w, bias, z, static_cast<hipStream_t>(stream)));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_conv_dgrad(const convbn_desc* desc, const void* dz, const void* w_t, void* dx,
+                                void* stream) {
+  Geom g;
+  convbn_status s = make_geom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(dz); REQUIRE_PTR(w_t); REQUIRE_PTR(dx);
+  LAUNCH(run_dgrad(g, desc->dtype, dz, w_t, dx, static_cast<hipStream_t>(stream)));
+  return CONVBN_OK;
+}
+
+int32_t convbn_wgrad_parts(const convbn_desc* desc) {
+  Geom g;
+  return make_geom(desc, &g) == CONVBN_OK ? nsplit_for(g, desc->dtype) : 0;
+}
+
+int32_t convbn_rsum_parts(const convbn_desc* desc) {
+  Geom g;
+  return make_geom(desc, &g) == CONVBN_OK ? colsum_parts(g) : 0;
+}
+
+convbn_status convbn_conv_wgrad(const convbn_desc* desc, const void* x, const void* dz,
+                                float* dw_part, float* r_part, void* stream) {
+  Geom g;
+  convbn_status s = make_geom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(dz); REQUIRE_PTR(dw_part); OPTIONAL_PTR(r_part);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  LAUNCH(run_wgrad(g, desc->dtype, x, dz, dw_part, nsplit_for(g, desc->dtype), st));
+  if (r_part) LAUNCH(launch_colsum(g, desc->dtype, dz, r_part, st));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_fold_back(const convbn_desc* desc, const float* dw_part, const float* r_part,
+                               const void* W, const float* b, const float* gamma, const float* mean,
+                               const float* var, void* dW, float* db, float* dgamma, float* dbeta,
+                               void* stream) {
+  Geom g;
+  convbn_status s = make_geom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(dw_part); REQUIRE_PTR(r_part); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean);
+  REQUIRE_PTR(var); REQUIRE_PTR(dW); REQUIRE_PTR(dgamma); REQUIRE_PTR(dbeta);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(db);
+  if ((b == nullptr) != (db == nullptr))
+    return fail(CONVBN_ERR_NULL, "db must be given exactly when b is given");
+  LAUNCH(launch_fold_back(g, desc->dtype, dw_part, nsplit_for(g, desc->dtype), r_part, colsum_parts(g),
+                          W, b, gamma, mean, var, 0, dW, db, dgamma, dbeta,
+                          static_cast<hipStream_t>(stream)));
+  return CONVBN_OK;
+}
+
 }  // extern "C"
