@@ -106,13 +106,15 @@ def kernel_times(pool, reps):
             w_fprop=torch.empty(P, dtype=r.dt, device=dev),
             w_t=torch.empty(P, dtype=r.dt, device=dev),
             bfold=torch.empty(s.Cout, dtype=torch.float32, device=dev),
+            ws_f=torch.empty(max(16, B.convbn_conv_workspace_bytes(d, B.PASS_FWD)), dtype=torch.uint8, device=dev),
+            ws_d=torch.empty(max(16, B.convbn_conv_workspace_bytes(d, B.PASS_BWD)), dtype=torch.uint8, device=dev),
             dw_part=torch.empty(B.convbn_wgrad_parts(d) * P, dtype=torch.float32, device=dev),
             r_part=torch.empty(B.convbn_rsum_parts(d) * s.Cout, dtype=torch.float32, device=dev)))
     calls = {
         "fold": lambda r, w: B.convbn_fold(d, r.W, r.b, r.gamma, r.beta, r.mean, r.var,
                                             w["w_fprop"], w["w_t"], w["bfold"]),
-        "fprop": lambda r, w: B.convbn_conv_fprop(d, r.x, w["w_fprop"], w["bfold"], r.z),
-        "dgrad": lambda r, w: B.convbn_conv_dgrad(d, r.dz, w["w_t"], r.dx),
+        "fprop": lambda r, w: B.convbn_conv_fprop(d, r.x, w["w_fprop"], w["bfold"], r.z, w["ws_f"]),
+        "dgrad": lambda r, w: B.convbn_conv_dgrad(d, r.dz, w["w_t"], r.dx, w["ws_d"]),
         "wgrad": lambda r, w: B.convbn_conv_wgrad(d, r.x, r.dz, w["dw_part"], None),
         "wgrad+rsum": lambda r, w: B.convbn_conv_wgrad(d, r.x, r.dz, w["dw_part"], w["r_part"]),
         "fold_back": lambda r, w: B.convbn_fold_back(d, w["dw_part"], w["r_part"], r.W, r.b,

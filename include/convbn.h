@@ -148,14 +148,19 @@ convbn_status convbn_fold(const convbn_desc *desc, const void *W, const float *b
                           const float *var, void *w_fprop, void *w_folded, float *b_folded,
                           void *stream);
 
+/* Workspace bytes convbn_conv_fprop (pass = CONVBN_PASS_FWD) or convbn_conv_dgrad
+ * (CONVBN_PASS_BWD) need; 0 for most shapes (then ws may be NULL). */
+size_t convbn_conv_workspace_bytes(const convbn_desc *desc, int pass);
+
 /* Forward convolution  z = w (*) x + bias  (Sec. 3.1; cross-correlation, zero padding).
  *   w is [Cout][kH][kW][Cin]; bias [Cout] fp32, nullable. */
 convbn_status convbn_conv_fprop(const convbn_desc *desc, const void *x, const void *w,
-                                const float *bias, void *z, void *stream);
+                                const float *bias, void *z, void *ws, size_t ws_bytes,
+                                void *stream);
 
 /* Input gradient  dx = w_rot (*) dz  (Sec. 3.2.1).  w_t is [Cin][kH][kW][Cout]. */
 convbn_status convbn_conv_dgrad(const convbn_desc *desc, const void *dz, const void *w_t,
-                                void *dx, void *stream);
+                                void *dx, void *ws, size_t ws_bytes, void *stream);
 
 /* Weight gradient  dw = dz (.) x  and  r_c = sum_{n,h,w} dz  (Sec. 3.2.1; App. B), left as
  * fp32 partial sums over slices of the output pixels:

@@ -22,7 +22,8 @@ PASS_FWD, PASS_BWD = 0, 1
 EXPORTS = ["convbn_hout", "convbn_wout", "convbn_workspace_bytes", "convbn_saved_bytes",
            "convbn_tune_fwd", "convbn_tune_bwd", "convbn_eval_fwd", "convbn_eval_bwd",
            "convbn_last_error", "convbn_fold", "convbn_conv_fprop", "convbn_conv_dgrad",
-           "convbn_wgrad_parts", "convbn_rsum_parts", "convbn_conv_wgrad", "convbn_fold_back"]
+           "convbn_wgrad_parts", "convbn_rsum_parts", "convbn_conv_wgrad", "convbn_fold_back",
+           "convbn_conv_workspace_bytes"]
 
 
 class Desc(C.Structure):
@@ -77,9 +78,11 @@ def lib():
         L.convbn_fold.restype = C.c_int
         L.convbn_fold.argtypes = [dp, vp, fp, fp, fp, fp, fp, vp, vp, fp, vp]
         L.convbn_conv_fprop.restype = C.c_int
-        L.convbn_conv_fprop.argtypes = [dp, vp, vp, fp, vp, vp]
+        L.convbn_conv_fprop.argtypes = [dp, vp, vp, fp, vp, vp, C.c_size_t, vp]
         L.convbn_conv_dgrad.restype = C.c_int
-        L.convbn_conv_dgrad.argtypes = [dp, vp, vp, vp, vp]
+        L.convbn_conv_dgrad.argtypes = [dp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.convbn_conv_workspace_bytes.restype = C.c_size_t
+        L.convbn_conv_workspace_bytes.argtypes = [dp, C.c_int]
         L.convbn_wgrad_parts.restype = C.c_int32
         L.convbn_wgrad_parts.argtypes = [dp]
         L.convbn_rsum_parts.restype = C.c_int32
@@ -210,16 +213,23 @@ def convbn_fold(desc, W, b, gamma, beta, mean, var, w_fprop, w_folded, b_folded,
     return st
 
 
-def convbn_conv_fprop(desc, x, w, bias, z, stream=None, check=True):
-    st = lib().convbn_conv_fprop(C.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(z),
+def convbn_conv_workspace_bytes(desc, pass_: int) -> int:
+    return lib().convbn_conv_workspace_bytes(C.byref(desc), pass_)
+
+
+def convbn_conv_fprop(desc, x, w, bias, z, ws=None, stream=None, check=True):
+    p, n = _ws(ws)
+    st = lib().convbn_conv_fprop(C.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(z), p, n,
                                  _stream(stream))
     if check:
         _check(st)
     return st
 
 
-def convbn_conv_dgrad(desc, dz, w_t, dx, stream=None, check=True):
-    st = lib().convbn_conv_dgrad(C.byref(desc), _ptr(dz), _ptr(w_t), _ptr(dx), _stream(stream))
+def convbn_conv_dgrad(desc, dz, w_t, dx, ws=None, stream=None, check=True):
+    p, n = _ws(ws)
+    st = lib().convbn_conv_dgrad(C.byref(desc), _ptr(dz), _ptr(w_t), _ptr(dx), p, n,
+                                 _stream(stream))
     if check:
         _check(st)
     return st

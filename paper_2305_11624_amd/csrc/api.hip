@@ -56,9 +56,20 @@ convbn_status make_geom(const convbn_desc* d, Geom* g) {
 
 size_t esize(int dtype) { return dtype == CONVBN_BF16 ? 2 : 4; }
 
-int nsplit_for(const Geom& g, int dtype) {
-  return igemm_supported(g, dtype) ? wgrad_splits(g) : wgrad_direct_splits(g);
+// How the weight-gradient step of a problem runs: number of fp32 partial copies of dw', number of
+// partial r vectors, and whether the weight-gradient kernel produces r itself.
+struct WgradWay { int nsplit; int nrpart; bool fused_r; };
+WgradWay wgrad_way(const Geom& g, int dtype) {
+  if (wgrad_tile_supported(g, dtype)) {
+    const int s = wgrad_tile_splits(g);
+    return {s, s, true};
+  }
+  return {igemm_supported(g, dtype) ? wgrad_splits(g) : wgrad_direct_splits(g), colsum_parts(g), false};
 }
+int nsplit_for(const Geom& g, int dtype) { return wgrad_way(g, dtype).nsplit; }
+
+size_t fprop_scratch_bytes(const Geom& g, int dtype);
+size_t dgrad_scratch_bytes(const Geom& g, int dtype);
 
 // Workspace carving.  Every section starts on a 256-byte boundary.
 struct Carve {
@@ -72,30 +83,43 @@ struct Carve {
   }
 };
 
-struct TuneFwdWs { void* w_krsc; float* bfold; size_t bytes; };
+struct TuneFwdWs { void* w_krsc; float* bfold; float* conv_scratch; size_t bytes; };
 TuneFwdWs carve_tune_fwd(const Geom& g, int dtype, void* ws) {
   Carve c(ws);
   TuneFwdWs r;
   r.w_krsc = c.take((size_t)g.Cout * g.K * esize(dtype));
   r.bfold = (float*)c.take((size_t)g.Cout * 4);
+  r.conv_scratch = (float*)c.take(fprop_scratch_bytes(g, dtype));
   r.bytes = c.off;
   return r;
 }
 
-struct TuneBwdWs { void* w_crsk; float* dwf_part; float* r_part; int nsplit; int nrpart; size_t bytes; };
+// Eval forward needs only the convolution's own scratch.
+struct EvalFwdWs { float* conv_scratch; size_t bytes; };
+EvalFwdWs carve_eval_fwd(const Geom& g, int dtype, void* ws) {
+  Carve c(ws);
+  EvalFwdWs r;
+  r.conv_scratch = (float*)c.take(fprop_scratch_bytes(g, dtype));
+  r.bytes = c.off;
+  return r;
+}
+
+struct TuneBwdWs { void* w_crsk; float* dwf_part; float* r_part; float* conv_scratch; int nsplit; int nrpart; size_t bytes; };
 TuneBwdWs carve_tune_bwd(const Geom& g, int dtype, void* ws) {
   Carve c(ws);
   TuneBwdWs r;
-  r.nsplit = nsplit_for(g, dtype);
-  r.nrpart = colsum_parts(g);
+  const WgradWay way = wgrad_way(g, dtype);
+  r.nsplit = way.nsplit;
+  r.nrpart = way.nrpart;
   r.w_crsk = c.take((size_t)g.Cout * g.K * esize(dtype));
   r.dwf_part = (float*)c.take((size_t)r.nsplit * g.Cout * g.K * 4);
   r.r_part = (float*)c.take((size_t)r.nrpart * g.Cout * 4);
+  r.conv_scratch = (float*)c.take(dgrad_scratch_bytes(g, dtype));
   r.bytes = c.off;
   return r;
 }
 
-struct EvalBwdWs { void* dy; void* w_crsk; float* dwf_part; float* bn_part; int nsplit; int nparts; size_t bytes; };
+struct EvalBwdWs { void* dy; void* w_crsk; float* dwf_part; float* bn_part; float* conv_scratch; int nsplit; int nparts; size_t bytes; };
 EvalBwdWs carve_eval_bwd(const Geom& g, int dtype, void* ws) {
   Carve c(ws);
   EvalBwdWs r;
@@ -105,6 +129,7 @@ EvalBwdWs carve_eval_bwd(const Geom& g, int dtype, void* ws) {
   r.w_crsk = c.take((size_t)g.Cout * g.K * esize(dtype));
   r.dwf_part = (float*)c.take((size_t)r.nsplit * g.Cout * g.K * 4);
   r.bn_part = (float*)c.take((size_t)r.nparts * 2 * g.Cout * 4);
+  r.conv_scratch = (float*)c.take(dgrad_scratch_bytes(g, dtype));
   r.bytes = c.off;
   return r;
 }
@@ -138,20 +163,35 @@ convbn_status check_ws(size_t need, void* ws, size_t ws_bytes) {
   return CONVBN_OK;
 }
 
+// Extra fp32 scratch the forward / input-gradient convolution of a problem needs (0 for most).
+size_t fprop_scratch_bytes(const Geom& g, int dtype) {
+  return tile_fprop_supported(g, dtype) ? tile_fprop_partial_bytes(g) : 0;
+}
+size_t dgrad_scratch_bytes(const Geom& g, int dtype) {
+  return tile_dgrad_supported(g, dtype) ? tile_dgrad_partial_bytes(g) : 0;
+}
+
 hipError_t run_fprop(const Geom& g, int dtype, const void* x, const void* w_krsc, const float* bias,
-                     void* z, hipStream_t st) {
+                     void* z, float* scratch, hipStream_t st) {
+  if (tile_fprop_supported(g, dtype)) return launch_fprop_tile(g, x, w_krsc, bias, z, scratch, st);
   return igemm_supported(g, dtype) ? launch_fprop_igemm(g, x, w_krsc, bias, z, st)
                                    : launch_fprop_direct(g, dtype, x, w_krsc, bias, z, st);
 }
 hipError_t run_dgrad(const Geom& g, int dtype, const void* dz, const void* w_crsk, void* dx,
-                     hipStream_t st) {
+                     float* scratch, hipStream_t st) {
+  if (tile_dgrad_supported(g, dtype)) return launch_dgrad_tile(g, dz, w_crsk, dx, scratch, st);
   return igemm_supported(g, dtype) ? launch_dgrad_igemm(g, dz, w_crsk, dx, st)
                                    : launch_dgrad_direct(g, dtype, dz, w_crsk, dx, st);
 }
-hipError_t run_wgrad(const Geom& g, int dtype, const void* x, const void* dz, float* part, int nsplit,
+// dw' partials and, when r_part != nullptr, the partial per-channel sums of dz.
+hipError_t run_wgrad(const Geom& g, int dtype, const void* x, const void* dz, float* part, float* r_part,
                      hipStream_t st) {
-  return igemm_supported(g, dtype) ? launch_wgrad_igemm(g, x, dz, part, nsplit, st)
-                                   : launch_wgrad_direct(g, dtype, x, dz, part, st);
+  const WgradWay way = wgrad_way(g, dtype);
+  if (way.fused_r) return launch_wgrad_tile(g, x, dz, part, r_part, st);
+  hipError_t e = igemm_supported(g, dtype) ? launch_wgrad_igemm(g, x, dz, part, way.nsplit, st)
+                                           : launch_wgrad_direct(g, dtype, x, dz, part, st);
+  if (e != hipSuccess || !r_part) return e;
+  return launch_colsum(g, dtype, dz, r_part, st);
 }
 
 }  // namespace
@@ -175,7 +215,8 @@ size_t convbn_workspace_bytes(const convbn_desc* desc, int mode, int pass) {
     return pass == CONVBN_PASS_FWD ? carve_tune_fwd(g, desc->dtype, nullptr).bytes
                                    : carve_tune_bwd(g, desc->dtype, nullptr).bytes;
   if (mode == CONVBN_MODE_EVAL)
-    return pass == CONVBN_PASS_FWD ? 0 : carve_eval_bwd(g, desc->dtype, nullptr).bytes;
+    return pass == CONVBN_PASS_FWD ? carve_eval_fwd(g, desc->dtype, nullptr).bytes
+                                   : carve_eval_bwd(g, desc->dtype, nullptr).bytes;
   return 0;
 }
 
@@ -205,7 +246,7 @@ convbn_status convbn_tune_fwd(const convbn_desc* desc, const void* x, const void
   hipStream_t st = static_cast<hipStream_t>(stream);
   // w' = s w (both orders), b' = (b - mu) s + beta; then Z = w' (*) X + b'
   LAUNCH(launch_fold(g, dt, W, b, gamma, beta, mean, var, 0, w.w_krsc, w_folded, w.bfold, st));
-  LAUNCH(run_fprop(g, dt, x, w.w_krsc, w.bfold, z, st));
+  LAUNCH(run_fprop(g, dt, x, w.w_krsc, w.bfold, z, w.conv_scratch, st));
   return CONVBN_OK;
 }
 
@@ -232,10 +273,9 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
       LAUNCH(launch_fold(g, dt, W, b, gamma, nullptr, mean, var, 0, nullptr, w.w_crsk, nullptr, st));
       wt = w.w_crsk;
     }
-    LAUNCH(run_dgrad(g, dt, dz, wt, dx, st));           // dX = w'_rot (*) dZ
+    LAUNCH(run_dgrad(g, dt, dz, wt, dx, w.conv_scratch, st));   // dX = w'_rot (*) dZ
   }
-  LAUNCH(run_wgrad(g, dt, x, dz, w.dwf_part, w.nsplit, st));   // dw' = dZ (.) X  (fp32 partials)
-  LAUNCH(launch_colsum(g, dt, dz, w.r_part, st));              // r = sum dZ       (partials)
+  LAUNCH(run_wgrad(g, dt, x, dz, w.dwf_part, w.r_part, st));   // dw' = dZ (.) X and r = sum dZ (fp32 partials)
   LAUNCH(launch_fold_back(g, dt, w.dwf_part, w.nsplit, w.r_part, w.nrpart, W, b, gamma, mean, var, 0,
                           dW, db, dgamma, dbeta, st));
   return CONVBN_OK;
@@ -245,7 +285,6 @@ convbn_status convbn_eval_fwd(const convbn_desc* desc, const void* x, const void
                               const float* gamma, const float* beta, const float* mean,
                               const float* var, void* z, void* y_saved, void* ws, size_t ws_bytes,
                               void* stream) {
-  (void)ws; (void)ws_bytes;
   Geom g;
   convbn_status s = make_geom(desc, &g);
   if (s != CONVBN_OK) return s;
@@ -253,8 +292,11 @@ convbn_status convbn_eval_fwd(const convbn_desc* desc, const void* x, const void
   REQUIRE_PTR(var); REQUIRE_PTR(z); REQUIRE_PTR(y_saved);
   OPTIONAL_PTR(b);
   const int dt = desc->dtype;
+  s = check_ws(carve_eval_fwd(g, dt, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const EvalFwdWs w = carve_eval_fwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  LAUNCH(run_fprop(g, dt, x, W, b, y_saved, st));                         // Y = w (*) X + b
+  LAUNCH(run_fprop(g, dt, x, W, b, y_saved, w.conv_scratch, st));         // Y = w (*) X + b
   LAUNCH(launch_bn_affine_fwd(g, dt, y_saved, gamma, beta, mean, var, z, st));  // Z from Y
   return CONVBN_OK;
 }
@@ -283,9 +325,9 @@ convbn_status convbn_eval_bwd(const convbn_desc* desc, const void* x, const void
     // the input-gradient pass reads the weight as [Cin][kH][kW][Cout]
     LAUNCH(launch_fold(g, dt, W, nullptr, nullptr, nullptr, nullptr, nullptr, 1, nullptr, w.w_crsk,
                        nullptr, st));
-    LAUNCH(run_dgrad(g, dt, w.dy, w.w_crsk, dx, st));   // dX = w_rot (*) dY
+    LAUNCH(run_dgrad(g, dt, w.dy, w.w_crsk, dx, w.conv_scratch, st));   // dX = w_rot (*) dY
   }
-  LAUNCH(run_wgrad(g, dt, x, w.dy, w.dwf_part, w.nsplit, st));   // dW = dY (.) X
+  LAUNCH(run_wgrad(g, dt, x, w.dy, w.dwf_part, nullptr, st));   // dW = dY (.) X
   LAUNCH(launch_fold_back(g, dt, w.dwf_part, w.nsplit, nullptr, 0, W, nullptr, nullptr, nullptr,
                           nullptr, 1, dW, nullptr, nullptr, nullptr, st));
   return CONVBN_OK;
@@ -306,23 +348,34 @@ convbn_status convbn_fold(const convbn_desc* desc, const void* W, const float* b
   return CONVBN_OK;
 }
 
+size_t convbn_conv_workspace_bytes(const convbn_desc* desc, int pass) {
+  Geom g;
+  if (make_geom(desc, &g) != CONVBN_OK) return 0;
+  return align_up(pass == CONVBN_PASS_FWD ? fprop_scratch_bytes(g, desc->dtype)
+                                          : dgrad_scratch_bytes(g, desc->dtype), 256);
+}
+
 convbn_status convbn_conv_fprop(const convbn_desc* desc, const void* x, const void* w,
-                                const float* bias, void* z, void* stream) {
+                                const float* bias, void* z, void* ws, size_t ws_bytes, void* stream) {
   Geom g;
   convbn_status s = make_geom(desc, &g);
   if (s != CONVBN_OK) return s;
   REQUIRE_PTR(x); REQUIRE_PTR(w); REQUIRE_PTR(z); OPTIONAL_PTR(bias);
-  LAUNCH(run_fprop(g, desc->dtype, x, w, bias, z, static_cast<hipStream_t>(stream)));
+  s = check_ws(fprop_scratch_bytes(g, desc->dtype), ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  LAUNCH(run_fprop(g, desc->dtype, x, w, bias, z, (float*)ws, static_cast<hipStream_t>(stream)));
   return CONVBN_OK;
 }
 
 convbn_status convbn_conv_dgrad(const convbn_desc* desc, const void* dz, const void* w_t, void* dx,
-                                void* stream) {
+                                void* ws, size_t ws_bytes, void* stream) {
   Geom g;
   convbn_status s = make_geom(desc, &g);
   if (s != CONVBN_OK) return s;
   REQUIRE_PTR(dz); REQUIRE_PTR(w_t); REQUIRE_PTR(dx);
-  LAUNCH(run_dgrad(g, desc->dtype, dz, w_t, dx, static_cast<hipStream_t>(stream)));
+  s = check_ws(dgrad_scratch_bytes(g, desc->dtype), ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  LAUNCH(run_dgrad(g, desc->dtype, dz, w_t, dx, (float*)ws, static_cast<hipStream_t>(stream)));
   return CONVBN_OK;
 }
 
@@ -333,7 +386,7 @@ int32_t convbn_wgrad_parts(const convbn_desc* desc) {
 
 int32_t convbn_rsum_parts(const convbn_desc* desc) {
   Geom g;
-  return make_geom(desc, &g) == CONVBN_OK ? colsum_parts(g) : 0;
+  return make_geom(desc, &g) == CONVBN_OK ? wgrad_way(g, desc->dtype).nrpart : 0;
 }
 
 convbn_status convbn_conv_wgrad(const convbn_desc* desc, const void* x, const void* dz,
@@ -343,8 +396,7 @@ convbn_status convbn_conv_wgrad(const convbn_desc* desc, const void* x, const vo
   if (s != CONVBN_OK) return s;
   REQUIRE_PTR(x); REQUIRE_PTR(dz); REQUIRE_PTR(dw_part); OPTIONAL_PTR(r_part);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  LAUNCH(run_wgrad(g, desc->dtype, x, dz, dw_part, nsplit_for(g, desc->dtype), st));
-  if (r_part) LAUNCH(launch_colsum(g, desc->dtype, dz, r_part, st));
+  LAUNCH(run_wgrad(g, desc->dtype, x, dz, dw_part, r_part, st));
   return CONVBN_OK;
 }
 
@@ -360,7 +412,8 @@ convbn_status convbn_fold_back(const convbn_desc* desc, const float* dw_part, co
   OPTIONAL_PTR(b); OPTIONAL_PTR(db);
   if ((b == nullptr) != (db == nullptr))
     return fail(CONVBN_ERR_NULL, "db must be given exactly when b is given");
-  LAUNCH(launch_fold_back(g, desc->dtype, dw_part, nsplit_for(g, desc->dtype), r_part, colsum_parts(g),
+  const WgradWay way = wgrad_way(g, desc->dtype);
+  LAUNCH(launch_fold_back(g, desc->dtype, dw_part, way.nsplit, r_part, way.nrpart,
                           W, b, gamma, mean, var, 0, dW, db, dgamma, dbeta,
                           static_cast<hipStream_t>(stream)));
   return CONVBN_OK;

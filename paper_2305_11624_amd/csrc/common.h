@@ -95,4 +95,24 @@ hipError_t launch_dgrad_igemm(const Geom& g, const void* dz, const void* w_crsk,
 hipError_t launch_wgrad_igemm(const Geom& g, const void* x, const void* dz, float* dwf_part,
                               int nsplit, hipStream_t st);
 
+// conv_tile.hip : bf16 MFMA convolution with the input window tile resident in LDS
+// (every input element is fetched once per block and reused by all taps).
+bool tile_fprop_supported(const Geom& g, int dtype);
+bool tile_dgrad_supported(const Geom& g, int dtype);
+// Some problems split the reduced channels over several workgroups and need fp32 partial-output
+// storage of this many bytes (0 otherwise), passed as `partials`.
+size_t tile_fprop_partial_bytes(const Geom& g);
+size_t tile_dgrad_partial_bytes(const Geom& g);
+hipError_t launch_fprop_tile(const Geom& g, const void* x, const void* w_krsc, const float* bias,
+                             void* z, float* partials, hipStream_t st);
+hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, void* dx,
+                             float* partials, hipStream_t st);
+
+// wgrad_tile.hip : bf16 MFMA weight gradient with LDS-resident pixel tiles; also produces the
+// per-channel sums r (one partial per split) when r_part != nullptr.
+bool wgrad_tile_supported(const Geom& g, int dtype);
+int wgrad_tile_splits(const Geom& g);
+hipError_t launch_wgrad_tile(const Geom& g, const void* x, const void* dz, float* dwf_part, float* r_part,
+                             hipStream_t st);
+
 }  // namespace convbn

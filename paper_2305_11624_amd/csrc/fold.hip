@@ -76,14 +76,33 @@ __global__ __launch_bounds__(256) void fold_kernel(const T* __restrict__ W, cons
   }
 }
 
-// One block per output channel.
-template <typename T>
+__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ void load4(const float* p, float (&w)[4]) {
+  const float4 v = ld4(p);
+  w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+}
+__device__ __forceinline__ void load4(const bf16_t* p, float (&w)[4]) {
+  const uint2 v = *reinterpret_cast<const uint2*>(p);
+  w[0] = bf16_lo(v.x); w[1] = bf16_hi(v.x); w[2] = bf16_lo(v.y); w[3] = bf16_hi(v.y);
+}
+__device__ __forceinline__ void store4(float* p, const float (&w)[4]) {
+  *reinterpret_cast<float4*>(p) = make_float4(w[0], w[1], w[2], w[3]);
+}
+__device__ __forceinline__ void store4(bf16_t* p, const float (&w)[4]) {
+  *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3]));
+}
+
+// One block per output channel.  VEC (K % 4 == 0): 64 lanes walk the row four elements at a
+// time while the block's four waves each add up a quarter of the `nsplit` partial copies;
+// the partial sums meet in LDS.  Otherwise one element per thread, all partials in sequence.
+template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void fold_back_kernel(
     const float* __restrict__ part, int nsplit, const float* __restrict__ r_part, int nrpart,
     const T* __restrict__ W, const float* __restrict__ b, const float* __restrict__ gamma,
     const float* __restrict__ mean, const float* __restrict__ var, float eps, int identity, int Cout,
     int K, T* __restrict__ dW, float* __restrict__ db, float* __restrict__ dgamma,
     float* __restrict__ dbeta) {
+  __shared__ float4 red4[3][64];
   __shared__ float red[4];
   const int co = blockIdx.x;
   const int tid = threadIdx.x;
@@ -94,21 +113,100 @@ __global__ __launch_bounds__(256) void fold_back_kernel(
     s = gamma[co] / sd;
   }
   float dot = 0.f;
-  for (int k = tid; k < K; k += 256) {
-    const size_t idx = (size_t)co * K + k;
-    float v = 0.f;
-    for (int sp = 0; sp < nsplit; ++sp) v += part[sp * P + idx];
-    dW[idx] = from_f32<T>(s * v);
-    dot += v * to_f32(W[idx]);
+  if (VEC && (K >> 2) >= 256) {
+    // long rows: one float4 column per thread, all partial copies summed in registers, no barriers
+    const int K4 = K >> 2;
+    const float* row = part + (size_t)co * K;
+    for (int k4 = tid; k4 < K4; k4 += 256) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      int sp = 0;
+      for (; sp + 3 < nsplit; sp += 4) {
+        const float4 a0 = ld4(row + (size_t)sp * P + 4 * k4);
+        const float4 a1 = ld4(row + (size_t)(sp + 1) * P + 4 * k4);
+        const float4 a2 = ld4(row + (size_t)(sp + 2) * P + 4 * k4);
+        const float4 a3 = ld4(row + (size_t)(sp + 3) * P + 4 * k4);
+        v.x += (a0.x + a1.x) + (a2.x + a3.x);
+        v.y += (a0.y + a1.y) + (a2.y + a3.y);
+        v.z += (a0.z + a1.z) + (a2.z + a3.z);
+        v.w += (a0.w + a1.w) + (a2.w + a3.w);
+      }
+      for (; sp < nsplit; ++sp) {
+        const float4 a0 = ld4(row + (size_t)sp * P + 4 * k4);
+        v.x += a0.x; v.y += a0.y; v.z += a0.z; v.w += a0.w;
+      }
+      const float g4[4] = {v.x, v.y, v.z, v.w};
+      float w4[4], o4[4];
+      load4(W + (size_t)co * K + 4 * k4, w4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        o4[e] = s * g4[e];
+        dot += g4[e] * w4[e];
+      }
+      store4(dW + (size_t)co * K + 4 * k4, o4);
+    }
+  } else if (VEC) {
+    const int kq = tid & 63, sg = tid >> 6;
+    const int K4 = K >> 2;
+    const float* row = part + (size_t)co * K;
+    for (int base = 0; base < K4; base += 64) {
+      const int k4 = base + kq;
+      const bool live = k4 < K4;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (live) {
+        int sp = sg;
+        for (; sp + 12 < nsplit; sp += 16) {
+          const float4 a0 = ld4(row + (size_t)sp * P + 4 * k4);
+          const float4 a1 = ld4(row + (size_t)(sp + 4) * P + 4 * k4);
+          const float4 a2 = ld4(row + (size_t)(sp + 8) * P + 4 * k4);
+          const float4 a3 = ld4(row + (size_t)(sp + 12) * P + 4 * k4);
+          v.x += (a0.x + a1.x) + (a2.x + a3.x);
+          v.y += (a0.y + a1.y) + (a2.y + a3.y);
+          v.z += (a0.z + a1.z) + (a2.z + a3.z);
+          v.w += (a0.w + a1.w) + (a2.w + a3.w);
+        }
+        for (; sp < nsplit; sp += 4) {
+          const float4 a0 = ld4(row + (size_t)sp * P + 4 * k4);
+          v.x += a0.x; v.y += a0.y; v.z += a0.z; v.w += a0.w;
+        }
+      }
+      if (sg > 0) red4[sg - 1][kq] = v;
+      __syncthreads();
+      if (sg == 0 && live) {
+        const float4 b0 = red4[0][kq], b1 = red4[1][kq], b2 = red4[2][kq];
+        float g4[4] = {v.x + b0.x + b1.x + b2.x, v.y + b0.y + b1.y + b2.y,
+                       v.z + b0.z + b1.z + b2.z, v.w + b0.w + b1.w + b2.w};
+        float w4[4];
+        load4(W + (size_t)co * K + 4 * k4, w4);
+        float o4[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          o4[e] = s * g4[e];
+          dot += g4[e] * w4[e];
+        }
+        store4(dW + (size_t)co * K + 4 * k4, o4);
+      }
+      __syncthreads();
+    }
+  } else {
+    for (int k = tid; k < K; k += 256) {
+      const size_t idx = (size_t)co * K + k;
+      float v = 0.f;
+      for (int sp = 0; sp < nsplit; ++sp) v += part[sp * P + idx];
+      dW[idx] = from_f32<T>(s * v);
+      dot += v * to_f32(W[idx]);
+    }
   }
   if (identity) return;
+  float r = 0.f;
+  for (int q = tid; q < nrpart; q += 256) r += r_part[(size_t)q * Cout + co];
   dot = wave_sum(dot);
-  if ((tid & 63) == 0) red[tid >> 6] = dot;
+  r = wave_sum(r);
+  __shared__ float redr[4];
+  if ((tid & 63) == 0) { red[tid >> 6] = dot; redr[tid >> 6] = r; }
   __syncthreads();
   if (tid == 0) {
     dot = red[0] + red[1] + red[2] + red[3];
-    float r = 0.f;
-    for (int p = 0; p < nrpart; ++p) r += r_part[(size_t)p * Cout + co];
+    r = redr[0] + redr[1] + redr[2] + redr[3];
     const float bc = b ? b[co] : 0.f;
     dbeta[co] = r;
     dgamma[co] = (dot + r * (bc - mean[co])) / sd;
@@ -145,6 +243,33 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ dz, i
       part[(size_t)blockIdx.x * Cout + co] = acc;
     }
     __syncthreads();
+  }
+}
+
+// bf16, Cout % 8 == 0: a thread reads 8 channels (16 bytes) of a row; (Cout/8) threads cover a row,
+// the remaining factor of the block strides over rows.  Requires Cout/8 <= 256.
+__global__ __launch_bounds__(256) void colsum_bf16x8_kernel(const uint4* __restrict__ dz, int M, int Cout,
+                                                            int rows_per_block, float* __restrict__ part) {
+  __shared__ float red[256][9];
+  const int c8 = Cout >> 3;
+  const int lanes = 256 / c8;
+  const int tc = threadIdx.x % c8, tr = threadIdx.x / c8;
+  const int m0 = blockIdx.x * rows_per_block;
+  const int m1 = min(M, m0 + rows_per_block);
+  float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (tr < lanes)
+    for (int m = m0 + tr; m < m1; m += lanes) {
+      const uint4 v = dz[(size_t)m * c8 + tc];
+      a[0] += bf16_lo(v.x); a[1] += bf16_hi(v.x); a[2] += bf16_lo(v.y); a[3] += bf16_hi(v.y);
+      a[4] += bf16_lo(v.z); a[5] += bf16_hi(v.z); a[6] += bf16_lo(v.w); a[7] += bf16_hi(v.w);
+    }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[threadIdx.x][e] = a[e];
+  __syncthreads();
+  for (int c = threadIdx.x; c < Cout; c += 256) {
+    float acc = 0.f;
+    for (int l = 0; l < lanes; ++l) acc += red[l * c8 + (c >> 3)][c & 7];
+    part[(size_t)blockIdx.x * Cout + c] = acc;
   }
 }
 
@@ -235,6 +360,60 @@ __global__ __launch_bounds__(256) void bn_bwd_kernel(const T* __restrict__ dz, c
   }
 }
 
+// bf16, Cout % 8 == 0, Cout <= 2048: 16 bytes (8 channels) per thread per row, as colsum_bf16x8_kernel.
+__global__ __launch_bounds__(256) void bn_bwd_bf16x8_kernel(const uint4* __restrict__ dz, const uint4* __restrict__ y,
+                                                            const float* __restrict__ gamma,
+                                                            const float* __restrict__ mean,
+                                                            const float* __restrict__ var, float eps, int M,
+                                                            int Cout, int rows_per_block, uint4* __restrict__ dy,
+                                                            float* __restrict__ part) {
+  __shared__ float red0[256][9];
+  __shared__ float red1[256][9];
+  const int c8 = Cout >> 3;
+  const int lanes = 256 / c8;
+  const int tc = threadIdx.x % c8, tr = threadIdx.x / c8;
+  const int m0 = blockIdx.x * rows_per_block;
+  const int m1 = min(M, m0 + rows_per_block);
+  float a0[8], a1[8], sc[8], mu[8], isd[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    a0[e] = 0.f; a1[e] = 0.f;
+    const int c = min(tc * 8 + e, Cout - 1);
+    isd[e] = 1.f / sqrtf(var[c] + eps);
+    sc[e] = gamma[c] * isd[e];
+    mu[e] = mean[c];
+  }
+  if (tr < lanes)
+    for (int m = m0 + tr; m < m1; m += lanes) {
+      const size_t idx = (size_t)m * c8 + tc;
+      const uint4 g4 = dz[idx], y4 = y[idx];
+      const uint32_t gw[4] = {g4.x, g4.y, g4.z, g4.w}, yw[4] = {y4.x, y4.y, y4.z, y4.w};
+      uint32_t ow[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float g0 = bf16_lo(gw[e]), g1 = bf16_hi(gw[e]);
+        const float y0 = bf16_lo(yw[e]), y1 = bf16_hi(yw[e]);
+        ow[e] = pack_bf16x2(sc[2 * e] * g0, sc[2 * e + 1] * g1);
+        a0[2 * e] += g0; a0[2 * e + 1] += g1;
+        a1[2 * e] += g0 * ((y0 - mu[2 * e]) * isd[2 * e]);
+        a1[2 * e + 1] += g1 * ((y1 - mu[2 * e + 1]) * isd[2 * e + 1]);
+      }
+      dy[idx] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+    }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { red0[threadIdx.x][e] = a0[e]; red1[threadIdx.x][e] = a1[e]; }
+  __syncthreads();
+  for (int c = threadIdx.x; c < Cout; c += 256) {
+    float s0 = 0.f, s1 = 0.f;
+    for (int l = 0; l < lanes; ++l) {
+      s0 += red0[l * c8 + (c >> 3)][c & 7];
+      s1 += red1[l * c8 + (c >> 3)][c & 7];
+    }
+    part[((size_t)blockIdx.x * 2 + 0) * Cout + c] = s0;
+    part[((size_t)blockIdx.x * 2 + 1) * Cout + c] = s1;
+  }
+}
+
 __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __restrict__ part, int parts,
                                                               const float* __restrict__ gamma,
                                                               const float* __restrict__ var, float eps,
@@ -277,14 +456,14 @@ hipError_t launch_fold_back(const Geom& g, int dtype, const float* dwf_part, int
                             const float* r_part, int nrpart, const void* W, const float* b,
                             const float* gamma, const float* mean, const float* var, int identity,
                             void* dW, float* db, float* dgamma, float* dbeta, hipStream_t st) {
-  if (dtype == CONVBN_BF16)
-    hipLaunchKernelGGL(fold_back_kernel<bf16_t>, dim3(g.Cout), dim3(256), 0, st, dwf_part, nsplit,
-                       r_part, nrpart, (const bf16_t*)W, b, gamma, mean, var, g.eps, identity, g.Cout,
-                       g.K, (bf16_t*)dW, db, dgamma, dbeta);
-  else
-    hipLaunchKernelGGL(fold_back_kernel<float>, dim3(g.Cout), dim3(256), 0, st, dwf_part, nsplit,
-                       r_part, nrpart, (const float*)W, b, gamma, mean, var, g.eps, identity, g.Cout,
-                       g.K, (float*)dW, db, dgamma, dbeta);
+#define FB_LAUNCH(T, VEC)                                                                         \
+  hipLaunchKernelGGL((fold_back_kernel<T, VEC>), dim3(g.Cout), dim3(256), 0, st, dwf_part, nsplit, \
+                     r_part, nrpart, (const T*)W, b, gamma, mean, var, g.eps, identity, g.Cout,    \
+                     g.K, (T*)dW, db, dgamma, dbeta)
+  const bool vec = g.K % 4 == 0;
+  if (dtype == CONVBN_BF16) { if (vec) FB_LAUNCH(bf16_t, true); else FB_LAUNCH(bf16_t, false); }
+  else { if (vec) FB_LAUNCH(float, true); else FB_LAUNCH(float, false); }
+#undef FB_LAUNCH
   return hipGetLastError();
 }
 
@@ -293,7 +472,10 @@ int colsum_parts(const Geom& g) { return g.M < 256 * 64 ? ceil_div(g.M, 64) : 25
 hipError_t launch_colsum(const Geom& g, int dtype, const void* dz, float* r_part, hipStream_t st) {
   const int parts = colsum_parts(g);
   const int rpb = rows_per_block_for(g.M, parts);
-  if (dtype == CONVBN_BF16)
+  if (dtype == CONVBN_BF16 && g.Cout % 8 == 0 && g.Cout <= 2048)
+    hipLaunchKernelGGL(colsum_bf16x8_kernel, dim3(parts), dim3(256), 0, st, (const uint4*)dz, g.M, g.Cout,
+                       rpb, r_part);
+  else if (dtype == CONVBN_BF16)
     hipLaunchKernelGGL(colsum_kernel<bf16_t>, dim3(parts), dim3(256), 0, st, (const bf16_t*)dz, g.M,
                        g.Cout, rpb, r_part);
   else
@@ -329,7 +511,10 @@ hipError_t launch_bn_bwd(const Geom& g, int dtype, const void* dz, const void* y
                          const float* mean, const float* var, void* dy, float* part, hipStream_t st) {
   const int parts = bn_bwd_parts(g);
   const int rpb = rows_per_block_for(g.M, parts);
-  if (dtype == CONVBN_BF16)
+  if (dtype == CONVBN_BF16 && g.Cout % 8 == 0 && g.Cout <= 2048)
+    hipLaunchKernelGGL(bn_bwd_bf16x8_kernel, dim3(parts), dim3(256), 0, st, (const uint4*)dz, (const uint4*)y,
+                       gamma, mean, var, g.eps, g.M, g.Cout, rpb, (uint4*)dy, part);
+  else if (dtype == CONVBN_BF16)
     hipLaunchKernelGGL(bn_bwd_kernel<bf16_t>, dim3(parts), dim3(256), 0, st, (const bf16_t*)dz,
                        (const bf16_t*)y, gamma, mean, var, g.eps, g.M, g.Cout, rpb, (bf16_t*)dy, part);
   else

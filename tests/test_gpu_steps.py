@@ -1,0 +1,113 @@
+"""GPU parity of every single step of the Tune-mode block (the hot-path rows: fold, forward
+conv, input gradient, weight gradient + channel sums, fold-back), each called through its own
+C-ABI entry point and compared with the corresponding oracle function."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2305_11624_amd import synth
+from paper_2305_11624_amd.synth import BlockShape
+
+from helpers import TOL, dims_of, rel_err
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [
+    BlockShape("s_3x3", 3, 64, 20, 18, 72, 3, 1, 1, "bf16", 51),
+    BlockShape("s_1x1", 2, 128, 14, 14, 256, 1, 1, 0, "bf16", 52),
+    BlockShape("s_3x3_s2", 2, 64, 17, 17, 64, 3, 2, 1, "bf16", 53),
+    BlockShape("s_1x1_s2", 2, 64, 16, 16, 128, 1, 2, 0, "bf16", 54),
+    BlockShape("s_deep7", 8, 256, 7, 7, 256, 3, 1, 1, "bf16", 55),
+    BlockShape("s_f32", 2, 12, 10, 10, 20, 3, 1, 1, "f32", 56),
+]
+
+
+def _np(t):
+    return None if t is None else t.double().numpy()
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: s.name)
+def test_each_step_against_oracle(shape):
+    from paper_2305_11624_amd import binding as B
+    inp = synth.make_inputs(shape, bias=True)
+    s = shape
+    d = dims_of(s)
+    desc = B.desc_from_shape(s, eps=inp["eps"])
+    dt = B.torch_dtype(desc)
+    tol = TOL[s.dtype]
+    dev = "cuda"
+    x = B.act_to_device(inp["x"], dt)
+    W = B.weight_to_device(inp["W"], dt)
+    dz = B.act_to_device(inp["dy"], dt)
+    b, gamma, beta = (B.vec_to_device(inp[k]) for k in ("b", "gamma", "beta"))
+    mean, var = B.vec_to_device(inp["rmean"]), B.vec_to_device(inp["rvar"])
+    a = {k: _np(inp[k]) for k in ("x", "W", "b", "gamma", "beta", "rmean", "rvar", "dy")}
+    eps = inp["eps"]
+
+    # a1 fold
+    w_fprop = torch.full((s.Cout, s.k, s.k, s.Cin), float("nan"), dtype=dt, device=dev)
+    w_t = torch.full((s.Cin, s.k, s.k, s.Cout), float("nan"), dtype=dt, device=dev)
+    bfold = torch.full((s.Cout,), float("nan"), dtype=torch.float32, device=dev)
+    B.convbn_fold(desc, W, b, gamma, beta, mean, var, w_fprop, w_t, bfold)
+    Wf, bf = oracle.fold(d, a["W"], a["b"], a["gamma"], a["beta"], a["rmean"], a["rvar"], eps)
+    assert rel_err(B.weight_from_device(w_fprop), Wf) <= tol
+    assert rel_err(B.folded_from_device(w_t), Wf) <= tol
+    assert torch.equal(B.weight_from_device(w_fprop), B.folded_from_device(w_t))   # same values, two orders
+    assert rel_err(bfold.double().cpu(), bf) <= 1e-5
+
+    # The later steps are checked with the GPU's own (rounded) w' as the oracle's weight, so
+    # that each step's error is its own.
+    Wf_gpu = B.weight_from_device(w_fprop).numpy()
+    bf_gpu = bfold.double().cpu().numpy()
+
+    def ws(pass_):
+        n = B.convbn_conv_workspace_bytes(desc, pass_)
+        return torch.empty(max(n, 16), dtype=torch.uint8, device=dev)
+
+    # a2 forward conv
+    z = torch.full((s.N, s.Hout, s.Wout, s.Cout), float("nan"), dtype=dt, device=dev)
+    B.convbn_conv_fprop(desc, x, w_fprop, bfold, z, ws(B.PASS_FWD))
+    assert rel_err(B.act_from_device(z), oracle.conv_fwd(d, a["x"], Wf_gpu, bf_gpu)) <= tol
+
+    # a3 input gradient
+    dx = torch.full((s.N, s.Hin, s.Win, s.Cin), float("nan"), dtype=dt, device=dev)
+    B.convbn_conv_dgrad(desc, dz, w_t, dx, ws(B.PASS_BWD))
+    assert rel_err(B.act_from_device(dx), oracle.conv_dgrad(d, Wf_gpu, a["dy"])) <= tol
+
+    # a4 weight gradient partials and channel-sum partials
+    ns, nr = B.convbn_wgrad_parts(desc), B.convbn_rsum_parts(desc)
+    P = s.Cout * s.K
+    dw_part = torch.full((ns, s.Cout, s.k, s.k, s.Cin), float("nan"), dtype=torch.float32, device=dev)
+    r_part = torch.full((nr, s.Cout), float("nan"), dtype=torch.float32, device=dev)
+    B.convbn_conv_wgrad(desc, x, dz, dw_part, r_part)
+    dwf = dw_part.double().sum(0).cpu().permute(0, 3, 1, 2).contiguous()
+    dwf_ref = oracle.conv_wgrad(d, a["x"], a["dy"])
+    assert rel_err(dwf, dwf_ref) <= (1e-4 if s.dtype == "f32" else 1e-5)      # fp32 accumulation of exact products
+    r_ref = a["dy"].sum(axis=(0, 2, 3))
+    assert rel_err(r_part.double().sum(0).cpu(), r_ref) <= 1e-5
+
+    # a5 fold-back, from the GPU's own partials
+    dW = torch.full((s.Cout, s.k, s.k, s.Cin), float("nan"), dtype=dt, device=dev)
+    db, dgamma, dbeta = (torch.full((s.Cout,), float("nan"), dtype=torch.float32, device=dev) for _ in range(3))
+    B.convbn_fold_back(desc, dw_part, r_part, W, b, gamma, mean, var, dW, db, dgamma, dbeta)
+    sd = np.sqrt(a["rvar"] + eps)
+    sc = a["gamma"] / sd
+    dwf_np = dwf.numpy()
+    assert rel_err(B.weight_from_device(dW), sc[:, None, None, None] * dwf_np) <= tol
+    r_np = r_part.double().sum(0).cpu().numpy()
+    dgamma_ref = ((dwf_np * a["W"]).sum(axis=(1, 2, 3)) + r_np * (a["b"] - a["rmean"])) / sd
+    assert rel_err(dgamma.double().cpu(), dgamma_ref) <= 1e-4
+    assert rel_err(dbeta.double().cpu(), r_np) <= 1e-6
+    assert rel_err(db.double().cpu(), sc * r_np) <= 1e-5
+
+
+def test_outputs_are_deterministic():
+    """Partial sums are combined in a fixed order: two runs give identical bits."""
+    from paper_2305_11624_amd.runner import BlockRun
+    inp = synth.make_inputs(BlockShape("det", 4, 64, 28, 28, 64, 3, 1, 1, "bf16", 57))
+    r1, r2 = BlockRun(inp, "tune"), BlockRun(inp, "tune")
+    r1.step(); r2.step(); r1.step()
+    a, b = r1.results(), r2.results()
+    for k in ("Z", "dX", "dW", "dgamma", "dbeta"):
+        assert torch.equal(a[k], b[k]), k
