@@ -115,8 +115,8 @@ def kernel_times(pool, reps):
                                             w["w_fprop"], w["w_t"], w["bfold"]),
         "fprop": lambda r, w: B.convbn_conv_fprop(d, r.x, w["w_fprop"], w["bfold"], r.z, w["ws_f"]),
         "dgrad": lambda r, w: B.convbn_conv_dgrad(d, r.dz, w["w_t"], r.dx, w["ws_d"]),
-        "wgrad": lambda r, w: B.convbn_conv_wgrad(d, r.x, r.dz, w["dw_part"], None),
-        "wgrad+rsum": lambda r, w: B.convbn_conv_wgrad(d, r.x, r.dz, w["dw_part"], w["r_part"]),
+        "wgrad": lambda r, w: B.convbn_conv_wgrad(d, r.x, r.dz, w["dw_part"], None, w["ws_d"]),
+        "wgrad+rsum": lambda r, w: B.convbn_conv_wgrad(d, r.x, r.dz, w["dw_part"], w["r_part"], w["ws_d"]),
         "fold_back": lambda r, w: B.convbn_fold_back(d, w["dw_part"], w["r_part"], r.W, r.b,
                                                      r.gamma, r.mean, r.var, r.dW, r.db,
                                                      r.dgamma, r.dbeta),

@@ -148,8 +148,9 @@ convbn_status convbn_fold(const convbn_desc *desc, const void *W, const float *b
                           const float *var, void *w_fprop, void *w_folded, float *b_folded,
                           void *stream);
 
-/* Workspace bytes convbn_conv_fprop (pass = CONVBN_PASS_FWD) or convbn_conv_dgrad
- * (CONVBN_PASS_BWD) need; 0 for most shapes (then ws may be NULL). */
+/* Workspace bytes convbn_conv_fprop (pass = CONVBN_PASS_FWD) or convbn_conv_dgrad /
+ * convbn_conv_wgrad (CONVBN_PASS_BWD, enough for either) need; 0 for most shapes (then ws
+ * may be NULL). */
 size_t convbn_conv_workspace_bytes(const convbn_desc *desc, int pass);
 
 /* Forward convolution  z = w (*) x + bias  (Sec. 3.1; cross-correlation, zero padding).
@@ -170,7 +171,8 @@ int32_t convbn_wgrad_parts(const convbn_desc *desc);
 int32_t convbn_rsum_parts(const convbn_desc *desc);
 /* r_part is nullable (then only the weight-gradient kernel runs). */
 convbn_status convbn_conv_wgrad(const convbn_desc *desc, const void *x, const void *dz,
-                                float *dw_part, float *r_part, void *stream);
+                                float *dw_part, float *r_part, void *ws, size_t ws_bytes,
+                                void *stream);
 
 /* Fold-back (Table 2, row "Tune", last four lines): from the partial sums of dw' and r,
  *   dW = s dw',  db = s r (nullable with b),  dgamma = (<dw'_c, w_c> + r_c (b_c - mu_c))/sqrt(var_c+eps),

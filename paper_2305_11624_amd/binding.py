@@ -88,7 +88,7 @@ def lib():
         L.convbn_rsum_parts.restype = C.c_int32
         L.convbn_rsum_parts.argtypes = [dp]
         L.convbn_conv_wgrad.restype = C.c_int
-        L.convbn_conv_wgrad.argtypes = [dp, vp, vp, fp, fp, vp]
+        L.convbn_conv_wgrad.argtypes = [dp, vp, vp, fp, fp, vp, C.c_size_t, vp]
         L.convbn_fold_back.restype = C.c_int
         L.convbn_fold_back.argtypes = [dp, fp, fp, vp, fp, fp, fp, fp, vp, fp, fp, fp, vp]
         _lib = L
@@ -243,8 +243,9 @@ def convbn_rsum_parts(desc) -> int:
     return lib().convbn_rsum_parts(C.byref(desc))
 
 
-def convbn_conv_wgrad(desc, x, dz, dw_part, r_part, stream=None, check=True):
-    st = lib().convbn_conv_wgrad(C.byref(desc), _ptr(x), _ptr(dz), _ptr(dw_part), _ptr(r_part),
+def convbn_conv_wgrad(desc, x, dz, dw_part, r_part, ws=None, stream=None, check=True):
+    p, n = _ws(ws)
+    st = lib().convbn_conv_wgrad(C.byref(desc), _ptr(x), _ptr(dz), _ptr(dw_part), _ptr(r_part), p, n,
                                  _stream(stream))
     if check:
         _check(st)

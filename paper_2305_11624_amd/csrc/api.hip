@@ -58,8 +58,21 @@ size_t esize(int dtype) { return dtype == CONVBN_BF16 ? 2 : 4; }
 
 // How the weight-gradient step of a problem runs: number of fp32 partial copies of dw', number of
 // partial r vectors, and whether the weight-gradient kernel produces r itself.
+// bf16 problems whose input-channel count is not a multiple of 8 (a network's first layer: 3
+// channels) run the MFMA kernels on copies padded with zero channels; the copies live in scratch.
+bool needs_cin_pad(const Geom& g, int dtype) {
+  return dtype == CONVBN_BF16 && g.Cin % 8 != 0 && g.Cout % 8 == 0;
+}
+Geom padded_geom(const Geom& g) {
+  Geom q = g;
+  q.Cin = (g.Cin + 7) / 8 * 8;
+  q.K = g.kH * g.kW * q.Cin;
+  return q;
+}
+
 struct WgradWay { int nsplit; int nrpart; bool fused_r; };
-WgradWay wgrad_way(const Geom& g, int dtype) {
+WgradWay wgrad_way(const Geom& g0, int dtype) {
+  const Geom g = needs_cin_pad(g0, dtype) ? padded_geom(g0) : g0;
   if (wgrad_tile_supported(g, dtype)) {
     const int s = wgrad_tile_splits(g);
     return {s, s, true};
@@ -70,6 +83,7 @@ int nsplit_for(const Geom& g, int dtype) { return wgrad_way(g, dtype).nsplit; }
 
 size_t fprop_scratch_bytes(const Geom& g, int dtype);
 size_t dgrad_scratch_bytes(const Geom& g, int dtype);
+size_t wgrad_scratch_bytes(const Geom& g, int dtype);
 
 // Workspace carving.  Every section starts on a 256-byte boundary.
 struct Carve {
@@ -104,7 +118,7 @@ EvalFwdWs carve_eval_fwd(const Geom& g, int dtype, void* ws) {
   return r;
 }
 
-struct TuneBwdWs { void* w_crsk; float* dwf_part; float* r_part; float* conv_scratch; int nsplit; int nrpart; size_t bytes; };
+struct TuneBwdWs { void* w_crsk; float* dwf_part; float* r_part; float* conv_scratch; void* wgrad_scratch; int nsplit; int nrpart; size_t bytes; };
 TuneBwdWs carve_tune_bwd(const Geom& g, int dtype, void* ws) {
   Carve c(ws);
   TuneBwdWs r;
@@ -115,11 +129,12 @@ TuneBwdWs carve_tune_bwd(const Geom& g, int dtype, void* ws) {
   r.dwf_part = (float*)c.take((size_t)r.nsplit * g.Cout * g.K * 4);
   r.r_part = (float*)c.take((size_t)r.nrpart * g.Cout * 4);
   r.conv_scratch = (float*)c.take(dgrad_scratch_bytes(g, dtype));
+  r.wgrad_scratch = c.take(wgrad_scratch_bytes(g, dtype));
   r.bytes = c.off;
   return r;
 }
 
-struct EvalBwdWs { void* dy; void* w_crsk; float* dwf_part; float* bn_part; float* conv_scratch; int nsplit; int nparts; size_t bytes; };
+struct EvalBwdWs { void* dy; void* w_crsk; float* dwf_part; float* bn_part; float* conv_scratch; void* wgrad_scratch; int nsplit; int nparts; size_t bytes; };
 EvalBwdWs carve_eval_bwd(const Geom& g, int dtype, void* ws) {
   Carve c(ws);
   EvalBwdWs r;
@@ -130,6 +145,7 @@ EvalBwdWs carve_eval_bwd(const Geom& g, int dtype, void* ws) {
   r.dwf_part = (float*)c.take((size_t)r.nsplit * g.Cout * g.K * 4);
   r.bn_part = (float*)c.take((size_t)r.nparts * 2 * g.Cout * 4);
   r.conv_scratch = (float*)c.take(dgrad_scratch_bytes(g, dtype));
+  r.wgrad_scratch = c.take(wgrad_scratch_bytes(g, dtype));
   r.bytes = c.off;
   return r;
 }
@@ -163,35 +179,96 @@ convbn_status check_ws(size_t need, void* ws, size_t ws_bytes) {
   return CONVBN_OK;
 }
 
-// Extra fp32 scratch the forward / input-gradient convolution of a problem needs (0 for most).
+// Scratch the three convolutions of a problem need (0 for most): fp32 partial outputs when the
+// reduced channels are split over workgroups, and the zero-padded copies of needs_cin_pad().
+size_t inner_fprop_scratch(const Geom& g, int dtype) {
+  return tile_fprop_supported(g, dtype) ? align_up(tile_fprop_partial_bytes(g), 256) : 0;
+}
+size_t inner_dgrad_scratch(const Geom& g, int dtype) {
+  return tile_dgrad_supported(g, dtype) ? align_up(tile_dgrad_partial_bytes(g), 256) : 0;
+}
 size_t fprop_scratch_bytes(const Geom& g, int dtype) {
-  return tile_fprop_supported(g, dtype) ? tile_fprop_partial_bytes(g) : 0;
+  if (!needs_cin_pad(g, dtype)) return inner_fprop_scratch(g, dtype);
+  const Geom q = padded_geom(g);
+  return align_up((size_t)q.Min * q.Cin * 2, 256) + align_up((size_t)q.Cout * q.K * 2, 256) +
+         inner_fprop_scratch(q, dtype);
 }
 size_t dgrad_scratch_bytes(const Geom& g, int dtype) {
-  return tile_dgrad_supported(g, dtype) ? tile_dgrad_partial_bytes(g) : 0;
+  if (!needs_cin_pad(g, dtype)) return inner_dgrad_scratch(g, dtype);
+  const Geom q = padded_geom(g);
+  return align_up((size_t)q.Cout * q.K * 2, 256) + align_up((size_t)q.Min * q.Cin * 2, 256) +
+         inner_dgrad_scratch(q, dtype);
+}
+size_t wgrad_scratch_bytes(const Geom& g, int dtype) {
+  if (!needs_cin_pad(g, dtype)) return 0;
+  const Geom q = padded_geom(g);
+  return align_up((size_t)q.Min * q.Cin * 2, 256) +
+         align_up((size_t)wgrad_way(g, dtype).nsplit * q.Cout * q.K * 4, 256);
 }
 
-hipError_t run_fprop(const Geom& g, int dtype, const void* x, const void* w_krsc, const float* bias,
+hipError_t fprop_any(const Geom& g, int dtype, const void* x, const void* w_krsc, const float* bias,
                      void* z, float* scratch, hipStream_t st) {
   if (tile_fprop_supported(g, dtype)) return launch_fprop_tile(g, x, w_krsc, bias, z, scratch, st);
   return igemm_supported(g, dtype) ? launch_fprop_igemm(g, x, w_krsc, bias, z, st)
                                    : launch_fprop_direct(g, dtype, x, w_krsc, bias, z, st);
 }
-hipError_t run_dgrad(const Geom& g, int dtype, const void* dz, const void* w_crsk, void* dx,
+hipError_t dgrad_any(const Geom& g, int dtype, const void* dz, const void* w_crsk, void* dx,
                      float* scratch, hipStream_t st) {
   if (tile_dgrad_supported(g, dtype)) return launch_dgrad_tile(g, dz, w_crsk, dx, scratch, st);
   return igemm_supported(g, dtype) ? launch_dgrad_igemm(g, dz, w_crsk, dx, st)
                                    : launch_dgrad_direct(g, dtype, dz, w_crsk, dx, st);
 }
+
+#define TRY(expr)                       \
+  do {                                  \
+    hipError_t e_ = (expr);             \
+    if (e_ != hipSuccess) return e_;    \
+  } while (0)
+
+hipError_t run_fprop(const Geom& g, int dtype, const void* x, const void* w_krsc, const float* bias,
+                     void* z, float* scratch, hipStream_t st) {
+  if (!needs_cin_pad(g, dtype)) return fprop_any(g, dtype, x, w_krsc, bias, z, scratch, st);
+  const Geom q = padded_geom(g);
+  char* s = reinterpret_cast<char*>(scratch);
+  void* xp = s; s += align_up((size_t)q.Min * q.Cin * 2, 256);
+  void* wp = s; s += align_up((size_t)q.Cout * q.K * 2, 256);
+  TRY(launch_repitch(2, (size_t)g.Min, g.Cin, q.Cin, x, xp, st));
+  TRY(launch_repitch(2, (size_t)g.Cout * g.kH * g.kW, g.Cin, q.Cin, w_krsc, wp, st));
+  return fprop_any(q, dtype, xp, wp, bias, z, reinterpret_cast<float*>(s), st);
+}
+hipError_t run_dgrad(const Geom& g, int dtype, const void* dz, const void* w_crsk, void* dx,
+                     float* scratch, hipStream_t st) {
+  if (!needs_cin_pad(g, dtype)) return dgrad_any(g, dtype, dz, w_crsk, dx, scratch, st);
+  const Geom q = padded_geom(g);
+  char* s = reinterpret_cast<char*>(scratch);
+  void* wp = s; s += align_up((size_t)q.Cout * q.K * 2, 256);
+  void* dxp = s; s += align_up((size_t)q.Min * q.Cin * 2, 256);
+  // [Cin][taps*Cout] -> [Cin_p][taps*Cout]: the extra rows are zero
+  const size_t row = (size_t)g.kH * g.kW * g.Cout;
+  TRY(launch_repitch(2, 1, (size_t)g.Cin * row, (size_t)q.Cin * row, w_crsk, wp, st));
+  TRY(dgrad_any(q, dtype, dz, wp, dxp, reinterpret_cast<float*>(s), st));
+  return launch_repitch(2, (size_t)g.Min, q.Cin, g.Cin, dxp, dx, st);
+}
 // dw' partials and, when r_part != nullptr, the partial per-channel sums of dz.
-hipError_t run_wgrad(const Geom& g, int dtype, const void* x, const void* dz, float* part, float* r_part,
-                     hipStream_t st) {
-  const WgradWay way = wgrad_way(g, dtype);
+hipError_t wgrad_any(const Geom& g, int dtype, const void* x, const void* dz, float* part, float* r_part,
+                     const WgradWay& way, hipStream_t st) {
   if (way.fused_r) return launch_wgrad_tile(g, x, dz, part, r_part, st);
   hipError_t e = igemm_supported(g, dtype) ? launch_wgrad_igemm(g, x, dz, part, way.nsplit, st)
                                            : launch_wgrad_direct(g, dtype, x, dz, part, st);
   if (e != hipSuccess || !r_part) return e;
   return launch_colsum(g, dtype, dz, r_part, st);
+}
+hipError_t run_wgrad(const Geom& g, int dtype, const void* x, const void* dz, float* part, float* r_part,
+                     void* scratch, hipStream_t st) {
+  const WgradWay way = wgrad_way(g, dtype);
+  if (!needs_cin_pad(g, dtype)) return wgrad_any(g, dtype, x, dz, part, r_part, way, st);
+  const Geom q = padded_geom(g);
+  char* s = reinterpret_cast<char*>(scratch);
+  void* xp = s; s += align_up((size_t)q.Min * q.Cin * 2, 256);
+  float* pp = reinterpret_cast<float*>(s);
+  TRY(launch_repitch(2, (size_t)g.Min, g.Cin, q.Cin, x, xp, st));
+  TRY(wgrad_any(q, dtype, xp, dz, pp, r_part, way, st));
+  return launch_repitch(4, (size_t)way.nsplit * g.Cout * g.kH * g.kW, q.Cin, g.Cin, pp, part, st);
 }
 
 }  // namespace
@@ -275,7 +352,7 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
     }
     LAUNCH(run_dgrad(g, dt, dz, wt, dx, w.conv_scratch, st));   // dX = w'_rot (*) dZ
   }
-  LAUNCH(run_wgrad(g, dt, x, dz, w.dwf_part, w.r_part, st));   // dw' = dZ (.) X and r = sum dZ (fp32 partials)
+  LAUNCH(run_wgrad(g, dt, x, dz, w.dwf_part, w.r_part, w.wgrad_scratch, st));   // dw' = dZ (.) X and r = sum dZ (fp32 partials)
   LAUNCH(launch_fold_back(g, dt, w.dwf_part, w.nsplit, w.r_part, w.nrpart, W, b, gamma, mean, var, 0,
                           dW, db, dgamma, dbeta, st));
   return CONVBN_OK;
@@ -327,7 +404,7 @@ convbn_status convbn_eval_bwd(const convbn_desc* desc, const void* x, const void
                        nullptr, st));
     LAUNCH(run_dgrad(g, dt, w.dy, w.w_crsk, dx, w.conv_scratch, st));   // dX = w_rot (*) dY
   }
-  LAUNCH(run_wgrad(g, dt, x, w.dy, w.dwf_part, nullptr, st));   // dW = dY (.) X
+  LAUNCH(run_wgrad(g, dt, x, w.dy, w.dwf_part, nullptr, w.wgrad_scratch, st));   // dW = dY (.) X
   LAUNCH(launch_fold_back(g, dt, w.dwf_part, w.nsplit, nullptr, 0, W, nullptr, nullptr, nullptr,
                           nullptr, 1, dW, nullptr, nullptr, nullptr, st));
   return CONVBN_OK;
@@ -351,8 +428,9 @@ convbn_status convbn_fold(const convbn_desc* desc, const void* W, const float* b
 size_t convbn_conv_workspace_bytes(const convbn_desc* desc, int pass) {
   Geom g;
   if (make_geom(desc, &g) != CONVBN_OK) return 0;
-  return align_up(pass == CONVBN_PASS_FWD ? fprop_scratch_bytes(g, desc->dtype)
-                                          : dgrad_scratch_bytes(g, desc->dtype), 256);
+  const size_t bwd = dgrad_scratch_bytes(g, desc->dtype) > wgrad_scratch_bytes(g, desc->dtype)
+                         ? dgrad_scratch_bytes(g, desc->dtype) : wgrad_scratch_bytes(g, desc->dtype);
+  return align_up(pass == CONVBN_PASS_FWD ? fprop_scratch_bytes(g, desc->dtype) : bwd, 256);
 }
 
 convbn_status convbn_conv_fprop(const convbn_desc* desc, const void* x, const void* w,
@@ -390,13 +468,15 @@ int32_t convbn_rsum_parts(const convbn_desc* desc) {
 }
 
 convbn_status convbn_conv_wgrad(const convbn_desc* desc, const void* x, const void* dz,
-                                float* dw_part, float* r_part, void* stream) {
+                                float* dw_part, float* r_part, void* ws, size_t ws_bytes, void* stream) {
   Geom g;
   convbn_status s = make_geom(desc, &g);
   if (s != CONVBN_OK) return s;
   REQUIRE_PTR(x); REQUIRE_PTR(dz); REQUIRE_PTR(dw_part); OPTIONAL_PTR(r_part);
+  s = check_ws(wgrad_scratch_bytes(g, desc->dtype), ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  LAUNCH(run_wgrad(g, desc->dtype, x, dz, dw_part, r_part, st));
+  LAUNCH(run_wgrad(g, desc->dtype, x, dz, dw_part, r_part, ws, st));
   return CONVBN_OK;
 }
 

@@ -76,6 +76,11 @@ hipError_t launch_bn_bwd_finalize(const Geom& g, const float* part, int parts, c
                                   const float* var, float* dgamma, float* dbeta, float* db,
                                   hipStream_t st);
 
+// Copies a [rows][inner_in] matrix of `elem_bytes`-wide elements (2 or 4) into [rows][inner_out]:
+// the first min(inner_in, inner_out) elements of every row, zeros behind them (fold.hip).
+hipError_t launch_repitch(int elem_bytes, size_t rows, size_t inner_in, size_t inner_out, const void* src,
+                          void* dst, hipStream_t st);
+
 // conv_direct.hip : one thread per output element, fp32 accumulation (any shape, both dtypes)
 hipError_t launch_fprop_direct(const Geom& g, int dtype, const void* x, const void* w_krsc,
                                const float* bias, void* z, hipStream_t st);

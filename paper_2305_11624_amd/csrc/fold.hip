@@ -25,37 +25,38 @@ __global__ __launch_bounds__(256) void fold_kernel(const T* __restrict__ W, cons
                                                    int identity, int Cout, int K, int Cin, int taps,
                                                    T* __restrict__ w_krsc, T* __restrict__ w_crsk,
                                                    float* __restrict__ bfold) {
-  __shared__ float s_scale[FOLD_TCO];
   __shared__ T tile[FOLD_TK][FOLD_TCO + 2];
   const int tid = threadIdx.x;
   const int co0 = blockIdx.y * FOLD_TCO;
   const int k0 = blockIdx.x * FOLD_TK;
-  if (tid < FOLD_TCO) {
+  if (blockIdx.x == 0 && tid < FOLD_TCO && bfold) {
     const int co = co0 + tid;
-    float s = 1.f;
     if (co < Cout) {
-      if (!identity) s = gamma[co] / sqrtf(var[co] + eps);
-      if (blockIdx.x == 0 && bfold) {
-        const float bc = b ? b[co] : 0.f;
-        bfold[co] = identity ? bc : (bc - mean[co]) * s + beta[co];
-      }
+      const float s = identity ? 1.f : gamma[co] / sqrtf(var[co] + eps);
+      const float bc = b ? b[co] : 0.f;
+      bfold[co] = identity ? bc : (bc - mean[co]) * s + beta[co];
     }
-    s_scale[tid] = s;
   }
-  __syncthreads();
-  // read + scale: a wave reads 64 consecutive columns of one row; rows tid/64 + 4e
+  // read + scale: a wave reads 64 consecutive columns of one row; rows tid/64 + 4e.  Every
+  // thread derives the scales of its own rows, so all loads of the kernel are issued together.
   {
     const int kc = tid & 63;
     const int k = k0 + kc;
+    T wv[FOLD_TCO / 4];
+    float sv[FOLD_TCO / 4];
+#pragma unroll
+    for (int e = 0; e < FOLD_TCO / 4; ++e) {
+      const int co = co0 + (tid >> 6) + 4 * e;
+      const bool ok = co < Cout && k < K;
+      wv[e] = ok ? W[(size_t)co * K + k] : from_f32<T>(0.f);
+      sv[e] = (ok && !identity) ? gamma[co] / sqrtf(var[co] + eps) : 1.f;
+    }
 #pragma unroll
     for (int e = 0; e < FOLD_TCO / 4; ++e) {
       const int r = (tid >> 6) + 4 * e;
       const int co = co0 + r;
-      T v = from_f32<T>(0.f);
-      if (co < Cout && k < K) {
-        v = from_f32<T>(to_f32(W[(size_t)co * K + k]) * s_scale[r]);
-        if (w_krsc) w_krsc[(size_t)co * K + k] = v;
-      }
+      const T v = from_f32<T>(to_f32(wv[e]) * sv[e]);
+      if (co < Cout && k < K && w_krsc) w_krsc[(size_t)co * K + k] = v;
       tile[kc][r] = v;
     }
   }
@@ -95,15 +96,16 @@ __device__ __forceinline__ void store4(bf16_t* p, const float (&w)[4]) {
 // One block per output channel.  VEC (K % 4 == 0): 64 lanes walk the row four elements at a
 // time while the block's four waves each add up a quarter of the `nsplit` partial copies;
 // the partial sums meet in LDS.  Otherwise one element per thread, all partials in sequence.
-template <typename T, bool VEC>
-__global__ __launch_bounds__(256) void fold_back_kernel(
+template <typename T, bool VEC, int NTHR>
+__global__ __launch_bounds__(NTHR) void fold_back_kernel(
     const float* __restrict__ part, int nsplit, const float* __restrict__ r_part, int nrpart,
     const T* __restrict__ W, const float* __restrict__ b, const float* __restrict__ gamma,
     const float* __restrict__ mean, const float* __restrict__ var, float eps, int identity, int Cout,
     int K, T* __restrict__ dW, float* __restrict__ db, float* __restrict__ dgamma,
     float* __restrict__ dbeta) {
-  __shared__ float4 red4[3][64];
-  __shared__ float red[4];
+  constexpr int NSL = NTHR / 64;           // waves = lanes over the partial copies in the short-row path
+  __shared__ float4 red4[NSL - 1][64];
+  __shared__ float red[NSL];
   const int co = blockIdx.x;
   const int tid = threadIdx.x;
   const size_t P = (size_t)Cout * K;
@@ -117,7 +119,7 @@ __global__ __launch_bounds__(256) void fold_back_kernel(
     // long rows: one float4 column per thread, all partial copies summed in registers, no barriers
     const int K4 = K >> 2;
     const float* row = part + (size_t)co * K;
-    for (int k4 = tid; k4 < K4; k4 += 256) {
+    for (int k4 = tid; k4 < K4; k4 += NTHR) {
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       int sp = 0;
       for (; sp + 3 < nsplit; sp += 4) {
@@ -154,17 +156,17 @@ __global__ __launch_bounds__(256) void fold_back_kernel(
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (live) {
         int sp = sg;
-        for (; sp + 12 < nsplit; sp += 16) {
+        for (; sp + 3 * NSL < nsplit; sp += 4 * NSL) {
           const float4 a0 = ld4(row + (size_t)sp * P + 4 * k4);
-          const float4 a1 = ld4(row + (size_t)(sp + 4) * P + 4 * k4);
-          const float4 a2 = ld4(row + (size_t)(sp + 8) * P + 4 * k4);
-          const float4 a3 = ld4(row + (size_t)(sp + 12) * P + 4 * k4);
+          const float4 a1 = ld4(row + (size_t)(sp + NSL) * P + 4 * k4);
+          const float4 a2 = ld4(row + (size_t)(sp + 2 * NSL) * P + 4 * k4);
+          const float4 a3 = ld4(row + (size_t)(sp + 3 * NSL) * P + 4 * k4);
           v.x += (a0.x + a1.x) + (a2.x + a3.x);
           v.y += (a0.y + a1.y) + (a2.y + a3.y);
           v.z += (a0.z + a1.z) + (a2.z + a3.z);
           v.w += (a0.w + a1.w) + (a2.w + a3.w);
         }
-        for (; sp < nsplit; sp += 4) {
+        for (; sp < nsplit; sp += NSL) {
           const float4 a0 = ld4(row + (size_t)sp * P + 4 * k4);
           v.x += a0.x; v.y += a0.y; v.z += a0.z; v.w += a0.w;
         }
@@ -172,9 +174,12 @@ __global__ __launch_bounds__(256) void fold_back_kernel(
       if (sg > 0) red4[sg - 1][kq] = v;
       __syncthreads();
       if (sg == 0 && live) {
-        const float4 b0 = red4[0][kq], b1 = red4[1][kq], b2 = red4[2][kq];
-        float g4[4] = {v.x + b0.x + b1.x + b2.x, v.y + b0.y + b1.y + b2.y,
-                       v.z + b0.z + b1.z + b2.z, v.w + b0.w + b1.w + b2.w};
+        float g4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int l = 0; l < NSL - 1; ++l) {
+          const float4 bl = red4[l][kq];
+          g4[0] += bl.x; g4[1] += bl.y; g4[2] += bl.z; g4[3] += bl.w;
+        }
         float w4[4];
         load4(W + (size_t)co * K + 4 * k4, w4);
         float o4[4];
@@ -188,7 +193,7 @@ __global__ __launch_bounds__(256) void fold_back_kernel(
       __syncthreads();
     }
   } else {
-    for (int k = tid; k < K; k += 256) {
+    for (int k = tid; k < K; k += NTHR) {
       const size_t idx = (size_t)co * K + k;
       float v = 0.f;
       for (int sp = 0; sp < nsplit; ++sp) v += part[sp * P + idx];
@@ -198,15 +203,16 @@ __global__ __launch_bounds__(256) void fold_back_kernel(
   }
   if (identity) return;
   float r = 0.f;
-  for (int q = tid; q < nrpart; q += 256) r += r_part[(size_t)q * Cout + co];
+  for (int q = tid; q < nrpart; q += NTHR) r += r_part[(size_t)q * Cout + co];
   dot = wave_sum(dot);
   r = wave_sum(r);
-  __shared__ float redr[4];
+  __shared__ float redr[NSL];
   if ((tid & 63) == 0) { red[tid >> 6] = dot; redr[tid >> 6] = r; }
   __syncthreads();
   if (tid == 0) {
-    dot = red[0] + red[1] + red[2] + red[3];
-    r = redr[0] + redr[1] + redr[2] + redr[3];
+    dot = 0.f;
+    r = 0.f;
+    for (int l = 0; l < NSL; ++l) { dot += red[l]; r += redr[l]; }
     const float bc = b ? b[co] : 0.f;
     dbeta[co] = r;
     dgamma[co] = (dot + r * (bc - mean[co])) / sd;
@@ -432,9 +438,31 @@ __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __res
   if (db) db[co] = gamma[co] / sqrtf(var[co] + eps) * a0;
 }
 
+template <typename E>
+__global__ __launch_bounds__(256) void repitch_kernel(const E* __restrict__ src, E* __restrict__ dst, size_t total,
+                                                      size_t inner_in, size_t inner_out) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const size_t row = i / inner_out, c = i - row * inner_out;
+    dst[i] = c < inner_in ? src[row * inner_in + c] : E(0);
+  }
+}
+
 int rows_per_block_for(int M, int parts) { return ceil_div(M, parts); }
 
 }  // namespace
+
+hipError_t launch_repitch(int elem_bytes, size_t rows, size_t inner_in, size_t inner_out, const void* src,
+                          void* dst, hipStream_t st) {
+  const size_t total = rows * inner_out;
+  const int blocks = (int)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+  if (elem_bytes == 2)
+    hipLaunchKernelGGL(repitch_kernel<unsigned short>, dim3(blocks), dim3(256), 0, st, (const unsigned short*)src,
+                       (unsigned short*)dst, total, inner_in, inner_out);
+  else
+    hipLaunchKernelGGL(repitch_kernel<unsigned int>, dim3(blocks), dim3(256), 0, st, (const unsigned int*)src,
+                       (unsigned int*)dst, total, inner_in, inner_out);
+  return hipGetLastError();
+}
 
 hipError_t launch_fold(const Geom& g, int dtype, const void* W, const float* b, const float* gamma,
                        const float* beta, const float* mean, const float* var, int identity,
@@ -456,13 +484,23 @@ hipError_t launch_fold_back(const Geom& g, int dtype, const float* dwf_part, int
                             const float* r_part, int nrpart, const void* W, const float* b,
                             const float* gamma, const float* mean, const float* var, int identity,
                             void* dW, float* db, float* dgamma, float* dbeta, hipStream_t st) {
-#define FB_LAUNCH(T, VEC)                                                                         \
-  hipLaunchKernelGGL((fold_back_kernel<T, VEC>), dim3(g.Cout), dim3(256), 0, st, dwf_part, nsplit, \
-                     r_part, nrpart, (const T*)W, b, gamma, mean, var, g.eps, identity, g.Cout,    \
+#define FB_LAUNCH(T, VEC, NTHR)                                                                          \
+  hipLaunchKernelGGL((fold_back_kernel<T, VEC, NTHR>), dim3(g.Cout), dim3(NTHR), 0, st, dwf_part, nsplit, \
+                     r_part, nrpart, (const T*)W, b, gamma, mean, var, g.eps, identity, g.Cout,           \
                      g.K, (T*)dW, db, dgamma, dbeta)
   const bool vec = g.K % 4 == 0;
-  if (dtype == CONVBN_BF16) { if (vec) FB_LAUNCH(bf16_t, true); else FB_LAUNCH(bf16_t, false); }
-  else { if (vec) FB_LAUNCH(float, true); else FB_LAUNCH(float, false); }
+  // few output channels and many partial copies: a 1024-thread block per channel (16 waves share
+  // the copies) keeps enough loads in flight on the few CUs such a grid occupies
+  const bool wide = vec && g.Cout <= 128 && nsplit >= 16 && (g.K >> 2) < 256;
+  if (dtype == CONVBN_BF16) {
+    if (wide) FB_LAUNCH(bf16_t, true, 1024);
+    else if (vec) FB_LAUNCH(bf16_t, true, 256);
+    else FB_LAUNCH(bf16_t, false, 256);
+  } else {
+    if (wide) FB_LAUNCH(float, true, 1024);
+    else if (vec) FB_LAUNCH(float, true, 256);
+    else FB_LAUNCH(float, false, 256);
+  }
 #undef FB_LAUNCH
   return hipGetLastError();
 }

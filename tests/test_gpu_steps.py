@@ -20,6 +20,7 @@ SHAPES = [
     BlockShape("s_1x1_s2", 2, 64, 16, 16, 128, 1, 2, 0, "bf16", 54),
     BlockShape("s_deep7", 8, 256, 7, 7, 256, 3, 1, 1, "bf16", 55),
     BlockShape("s_f32", 2, 12, 10, 10, 20, 3, 1, 1, "f32", 56),
+    BlockShape("s_stem", 2, 3, 40, 40, 64, 7, 2, 3, "bf16", 58),       # 3 input channels: padded copies
 ]
 
 
@@ -80,7 +81,7 @@ def test_each_step_against_oracle(shape):
     P = s.Cout * s.K
     dw_part = torch.full((ns, s.Cout, s.k, s.k, s.Cin), float("nan"), dtype=torch.float32, device=dev)
     r_part = torch.full((nr, s.Cout), float("nan"), dtype=torch.float32, device=dev)
-    B.convbn_conv_wgrad(desc, x, dz, dw_part, r_part)
+    B.convbn_conv_wgrad(desc, x, dz, dw_part, r_part, ws(B.PASS_BWD))
     dwf = dw_part.double().sum(0).cpu().permute(0, 3, 1, 2).contiguous()
     dwf_ref = oracle.conv_wgrad(d, a["x"], a["dy"])
     assert rel_err(dwf, dwf_ref) <= (1e-4 if s.dtype == "f32" else 1e-5)      # fp32 accumulation of exact products
