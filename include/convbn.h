@@ -182,6 +182,22 @@ convbn_status convbn_fold_back(const convbn_desc *desc, const float *dw_part, co
                                const float *mean, const float *var, void *dW, float *db,
                                float *dgamma, float *dbeta, void *stream);
 
+/* ---- Glue between blocks (not part of the ConvBN block) ------------------------------
+ * What follows a block does not change the block's computation (Sec. 3.1).  These three
+ * calls exist only so that a whole backbone (ResNet-50: ReLU, residual add, 3x3/2 max-pool)
+ * can be chained on the GPU for the end-to-end time / memory measurement (App. D).
+ *   convbn_aux_eltwise, n elements (n % 8 == 0), a is updated in place:
+ *     op 0: a = max(a, 0)            op 1: a = b > 0 ? a : 0   (ReLU backward; b = ReLU output)
+ *     op 2: a = max(a + b, 0)        op 3: a = a + b
+ *   convbn_aux_maxpool_fwd: 3x3 window, stride 2, padding 1 over x [N][H][W][C] -> y
+ *     [N][Ho][Wo][C], Ho = (H-1)/2+1; idx (one byte per output element) records the winner.
+ *   convbn_aux_maxpool_bwd: dx [N][H][W][C] from dy and idx. */
+convbn_status convbn_aux_eltwise(int op, int dtype, void *a, const void *b, size_t n, void *stream);
+convbn_status convbn_aux_maxpool_fwd(int dtype, const void *x, void *y, void *idx, int32_t N,
+                                     int32_t H, int32_t W, int32_t C, void *stream);
+convbn_status convbn_aux_maxpool_bwd(int dtype, const void *dy, const void *idx, void *dx,
+                                     int32_t N, int32_t H, int32_t W, int32_t C, void *stream);
+
 /* Bytes a block must keep alive between its forward and its backward call in
  * addition to X (App. K.1): Eval keeps Y (N Cout Hout Wout elements); Tune keeps
  * w' (kH kW Cin Cout elements), or nothing when `refold` is non-zero. */

@@ -23,7 +23,8 @@ EXPORTS = ["convbn_hout", "convbn_wout", "convbn_workspace_bytes", "convbn_saved
            "convbn_tune_fwd", "convbn_tune_bwd", "convbn_eval_fwd", "convbn_eval_bwd",
            "convbn_last_error", "convbn_fold", "convbn_conv_fprop", "convbn_conv_dgrad",
            "convbn_wgrad_parts", "convbn_rsum_parts", "convbn_conv_wgrad", "convbn_fold_back",
-           "convbn_conv_workspace_bytes"]
+           "convbn_conv_workspace_bytes", "convbn_aux_eltwise", "convbn_aux_maxpool_fwd",
+           "convbn_aux_maxpool_bwd"]
 
 
 class Desc(C.Structure):
@@ -91,6 +92,12 @@ def lib():
         L.convbn_conv_wgrad.argtypes = [dp, vp, vp, fp, fp, vp, C.c_size_t, vp]
         L.convbn_fold_back.restype = C.c_int
         L.convbn_fold_back.argtypes = [dp, fp, fp, vp, fp, fp, fp, fp, vp, fp, fp, fp, vp]
+        L.convbn_aux_eltwise.restype = C.c_int
+        L.convbn_aux_eltwise.argtypes = [C.c_int, C.c_int, vp, vp, C.c_size_t, vp]
+        L.convbn_aux_maxpool_fwd.restype = C.c_int
+        L.convbn_aux_maxpool_fwd.argtypes = [C.c_int, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp]
+        L.convbn_aux_maxpool_bwd.restype = C.c_int
+        L.convbn_aux_maxpool_bwd.argtypes = [C.c_int, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp]
         _lib = L
     return _lib
 
@@ -260,6 +267,29 @@ def convbn_fold_back(desc, dw_part, r_part, W, b, gamma, mean, var, dW, db, dgam
     if check:
         _check(st)
     return st
+
+
+OP_RELU, OP_RELU_BWD, OP_ADD_RELU, OP_ADD = range(4)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    return BF16 if t.dtype == torch.bfloat16 else F32
+
+
+def convbn_aux_eltwise(op, a, b=None, stream=None):
+    _check(lib().convbn_aux_eltwise(op, _dtype_code(a), _ptr(a), _ptr(b), a.numel(), _stream(stream)))
+
+
+def convbn_aux_maxpool_fwd(x, y, idx, stream=None):
+    n, h, w, c = x.shape
+    _check(lib().convbn_aux_maxpool_fwd(_dtype_code(x), _ptr(x), _ptr(y), _ptr(idx), n, h, w, c,
+                                        _stream(stream)))
+
+
+def convbn_aux_maxpool_bwd(dy, idx, dx, stream=None):
+    n, h, w, c = dx.shape
+    _check(lib().convbn_aux_maxpool_bwd(_dtype_code(dx), _ptr(dy), _ptr(idx), _ptr(dx), n, h, w, c,
+                                        _stream(stream)))
 
 
 # ---- layout marshalling between logical NCHW host tensors and the library's

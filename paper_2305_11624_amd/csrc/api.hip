@@ -499,4 +499,34 @@ convbn_status convbn_fold_back(const convbn_desc* desc, const float* dw_part, co
   return CONVBN_OK;
 }
 
+convbn_status convbn_aux_eltwise(int op, int dtype, void* a, const void* b, size_t n, void* stream) {
+  if (op < 0 || op > 3) return fail(CONVBN_ERR_UNSUPPORTED, "unknown elementwise op %d", op);
+  if (dtype != CONVBN_F32 && dtype != CONVBN_BF16) return fail(CONVBN_ERR_UNSUPPORTED, "dtype %d", dtype);
+  REQUIRE_PTR(a);
+  if (op != 0) REQUIRE_PTR(b);
+  if (n % 8 != 0) return fail(CONVBN_ERR_SHAPE, "element count must be a multiple of 8");
+  LAUNCH(launch_eltwise(op, dtype, a, b, n, static_cast<hipStream_t>(stream)));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_aux_maxpool_fwd(int dtype, const void* x, void* y, void* idx, int32_t N, int32_t H,
+                                     int32_t W, int32_t C, void* stream) {
+  if (dtype != CONVBN_F32 && dtype != CONVBN_BF16) return fail(CONVBN_ERR_UNSUPPORTED, "dtype %d", dtype);
+  if (N < 1 || H < 1 || W < 1 || C < 1) return fail(CONVBN_ERR_SHAPE, "non-positive dimension");
+  REQUIRE_PTR(x); REQUIRE_PTR(y); REQUIRE_PTR(idx);
+  LAUNCH(launch_maxpool_fwd(dtype, x, y, static_cast<unsigned char*>(idx), N, H, W, C,
+                            static_cast<hipStream_t>(stream)));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_aux_maxpool_bwd(int dtype, const void* dy, const void* idx, void* dx, int32_t N, int32_t H,
+                                     int32_t W, int32_t C, void* stream) {
+  if (dtype != CONVBN_F32 && dtype != CONVBN_BF16) return fail(CONVBN_ERR_UNSUPPORTED, "dtype %d", dtype);
+  if (N < 1 || H < 1 || W < 1 || C < 1) return fail(CONVBN_ERR_SHAPE, "non-positive dimension");
+  REQUIRE_PTR(dy); REQUIRE_PTR(idx); REQUIRE_PTR(dx);
+  LAUNCH(launch_maxpool_bwd(dtype, dy, static_cast<const unsigned char*>(idx), dx, N, H, W, C,
+                            static_cast<hipStream_t>(stream)));
+  return CONVBN_OK;
+}
+
 }  // extern "C"

@@ -81,6 +81,14 @@ hipError_t launch_bn_bwd_finalize(const Geom& g, const float* part, int parts, c
 hipError_t launch_repitch(int elem_bytes, size_t rows, size_t inner_in, size_t inner_out, const void* src,
                           void* dst, hipStream_t st);
 
+// aux_ops.hip : glue between blocks for the whole-backbone measurement
+//   op: 0 relu (a), 1 relu backward (a = b > 0 ? a : 0), 2 a = relu(a + b), 3 a += b;  n % 8 == 0
+hipError_t launch_eltwise(int op, int dtype, void* a, const void* b, size_t n, hipStream_t st);
+hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, unsigned char* idx, int N, int H, int W, int C,
+                              hipStream_t st);
+hipError_t launch_maxpool_bwd(int dtype, const void* dy, const unsigned char* idx, void* dx, int N, int H, int W,
+                              int C, hipStream_t st);
+
 // conv_direct.hip : one thread per output element, fp32 accumulation (any shape, both dtypes)
 hipError_t launch_fprop_direct(const Geom& g, int dtype, const void* x, const void* w_krsc,
                                const float* bias, void* z, hipStream_t st);

@@ -1,0 +1,141 @@
+"""ResNet-50 backbone (53 ConvBN blocks, ReLU, bottleneck residual adds, 3x3/2 max-pool) chained on
+the GPU through the library, forward + backward with frozen BatchNorm statistics, in Tune or
+Eval mode -- the workload of the paper's end-to-end time / memory table (App. D).
+
+Everything numeric runs in the library's kernels (blocks: convbn_tune_* / convbn_eval_*; glue:
+convbn_aux_*).  PyTorch allocates the buffers, which is also how the peak activation memory is
+measured (caching-allocator high-water mark above the parameters, gradients and workspace).
+"""
+from typing import Dict, List, Optional
+
+import torch
+
+from . import binding as B
+from . import synth
+
+
+class _Block:
+    def __init__(self, shape, device, mode):
+        self.shape, self.mode = shape, mode
+        p = synth.make_params(shape)
+        self.desc = B.desc_from_shape(shape, eps=p["eps"])
+        dt = B.torch_dtype(self.desc)
+        self.dt = dt
+        self.W = B.weight_to_device(p["W"], dt, device)
+        self.gamma, self.beta = B.vec_to_device(p["gamma"], device), B.vec_to_device(p["beta"], device)
+        self.mean, self.var = B.vec_to_device(p["rmean"], device), B.vec_to_device(p["rvar"], device)
+        self.dW = torch.empty_like(self.W)
+        self.dgamma, self.dbeta = torch.empty_like(self.gamma), torch.empty_like(self.beta)
+        m = B.MODE_TUNE if mode == "tune" else B.MODE_EVAL
+        self.ws_bytes = max(B.convbn_workspace_bytes(self.desc, m, B.PASS_FWD),
+                            B.convbn_workspace_bytes(self.desc, m, B.PASS_BWD))
+        # Tune keeps w' unless it is larger than the Y that Eval would keep (then backward re-folds)
+        self.keep_folded = mode == "tune" and shape.P <= shape.A_z
+        self.x = self.saved = None
+
+    def forward(self, x, ws):
+        s = self.shape
+        z = torch.empty((s.N, s.Hout, s.Wout, s.Cout), dtype=self.dt, device=x.device)
+        self.x = x
+        if self.mode == "tune":
+            self.saved = torch.empty((s.Cin, s.k, s.k, s.Cout), dtype=self.dt, device=x.device) \
+                if self.keep_folded else None
+            B.convbn_tune_fwd(self.desc, x, self.W, None, self.gamma, self.beta, self.mean, self.var, z,
+                              self.saved, ws)
+        else:
+            self.saved = torch.empty_like(z)
+            B.convbn_eval_fwd(self.desc, x, self.W, None, self.gamma, self.beta, self.mean, self.var, z,
+                              self.saved, ws)
+        return z
+
+    def backward(self, dz, ws, need_dx=True):
+        dx = torch.empty_like(self.x) if need_dx else None
+        if self.mode == "tune":
+            B.convbn_tune_bwd(self.desc, self.x, self.W, None, self.gamma, self.mean, self.var, self.saved,
+                              dz, dx, self.dW, None, self.dgamma, self.dbeta, ws)
+        else:
+            B.convbn_eval_bwd(self.desc, self.x, self.W, None, self.gamma, self.mean, self.var, self.saved,
+                              dz, dx, self.dW, None, self.dgamma, self.dbeta, ws)
+        self.x = self.saved = None
+        return dx
+
+
+class ResNet50:
+    def __init__(self, N: int = 32, image: int = 224, dtype: str = "bf16", mode: str = "tune",
+                 device: str = "cuda"):
+        assert mode in ("tune", "eval")
+        self.N, self.image, self.mode, self.device = N, image, mode, device
+        shapes = synth.resnet50_blocks(N, image, dtype)
+        self.blocks: Dict[str, _Block] = {s.name: _Block(s, device, mode) for s in shapes}
+        self.order: List[str] = [s.name for s in shapes]
+        self.ws = torch.empty(max(b.ws_bytes for b in self.blocks.values()) + 256, dtype=torch.uint8, device=device)
+        self.dt = self.blocks["stem"].dt
+        self.stages = []
+        for st, nblk in enumerate((3, 4, 6, 3), start=1):
+            self.stages.append([f"l{st}.{i}" for i in range(nblk)])
+        self._tape = None
+
+    def saved_bytes_model(self) -> int:
+        """Analytic bytes kept between forward and backward besides the block inputs."""
+        m = B.MODE_TUNE if self.mode == "tune" else B.MODE_EVAL
+        return sum(B.convbn_saved_bytes(b.desc, m, self.mode == "tune" and not b.keep_folded)
+                   for b in self.blocks.values())
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        """x: [N][image][image][3] device tensor (channels-last).  Returns [N][h][w][2048]."""
+        ws, bl = self.ws, self.blocks
+        z0 = bl["stem"].forward(x, ws)
+        B.convbn_aux_eltwise(B.OP_RELU, z0)
+        n, h, w, c = z0.shape
+        p = torch.empty((n, (h - 1) // 2 + 1, (w - 1) // 2 + 1, c), dtype=self.dt, device=x.device)
+        idx = torch.empty(p.shape, dtype=torch.uint8, device=x.device)
+        B.convbn_aux_maxpool_fwd(z0, p, idx)
+        tape = dict(z0=z0, idx=idx, units=[])
+        cur = p
+        for names in self.stages:
+            for name in names:
+                a = bl[name + ".a"].forward(cur, ws)
+                B.convbn_aux_eltwise(B.OP_RELU, a)
+                b = bl[name + ".b"].forward(a, ws)
+                B.convbn_aux_eltwise(B.OP_RELU, b)
+                c_ = bl[name + ".c"].forward(b, ws)
+                has_ds = (name + ".ds") in bl
+                sc = bl[name + ".ds"].forward(cur, ws) if has_ds else cur
+                B.convbn_aux_eltwise(B.OP_ADD_RELU, c_, sc)
+                tape["units"].append((name, has_ds, a, b, c_))
+                del sc
+                cur = c_
+        self._tape = tape
+        return cur
+
+    def backward(self, dout: torch.Tensor, need_input_grad: bool = False) -> Optional[torch.Tensor]:
+        ws, bl, tape = self.ws, self.blocks, self._tape
+        g = dout.clone()
+        for name, has_ds, a, b, out in reversed(tape["units"]):
+            B.convbn_aux_eltwise(B.OP_RELU_BWD, g, out)
+            gb = bl[name + ".c"].backward(g, ws)
+            B.convbn_aux_eltwise(B.OP_RELU_BWD, gb, b)
+            ga = bl[name + ".b"].backward(gb, ws)
+            del gb
+            B.convbn_aux_eltwise(B.OP_RELU_BWD, ga, a)
+            gin = bl[name + ".a"].backward(ga, ws)
+            del ga
+            if has_ds:
+                gds = bl[name + ".ds"].backward(g, ws)
+                B.convbn_aux_eltwise(B.OP_ADD, gin, gds)
+                del gds
+            else:
+                B.convbn_aux_eltwise(B.OP_ADD, gin, g)
+            g = gin
+        z0, idx = tape["z0"], tape["idx"]
+        gz0 = torch.empty_like(z0)
+        B.convbn_aux_maxpool_bwd(g, idx, gz0)
+        del g
+        B.convbn_aux_eltwise(B.OP_RELU_BWD, gz0, z0)
+        gx = bl["stem"].backward(gz0, ws, need_dx=need_input_grad)
+        self._tape = None
+        return gx
+
+    def grads(self, name: str) -> Dict[str, torch.Tensor]:
+        b = self.blocks[name]
+        return dict(dW=B.weight_from_device(b.dW), dgamma=b.dgamma.double().cpu(), dbeta=b.dbeta.double().cpu())

@@ -125,6 +125,22 @@ def make_inputs(shape: BlockShape, seed: Optional[int] = None, bias: bool = Fals
                 eps=eps)
 
 
+def make_params(shape: BlockShape, seed: Optional[int] = None) -> Dict[str, object]:
+    """Only the parameters of a block (same distributions and draw order as make_inputs, but
+    without the activation-sized tensors): W, gamma, beta, running mean, running var."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(shape.seed if seed is None else seed)
+    s = shape
+    W = torch.randn(s.Cout, s.Cin, s.k, s.k, generator=g) * (2.0 / (s.Cin * s.k * s.k)) ** 0.5
+    gamma = torch.rand(s.Cout, generator=g) + 0.5
+    beta = torch.randn(s.Cout, generator=g) * 0.1
+    rmean = torch.randn(s.Cout, generator=g) * 0.1
+    rvar = torch.rand(s.Cout, generator=g) * 1.5 + 0.5
+    if s.dtype == "bf16":
+        W = round_bf16(W)
+    return dict(shape=s, W=W, gamma=gamma, beta=beta, rmean=rmean, rvar=rvar, eps=1e-5)
+
+
 def resnet50_blocks(N: int = 32, image: int = 224, dtype: str = "bf16") -> List[BlockShape]:
     """The 53 ConvBN blocks of a ResNet-50 backbone (stride on the 3x3 conv of each
     stage's first bottleneck, 1x1 stride-s projection on the shortcut), in forward
