@@ -31,11 +31,16 @@ WORKLOADS = {
     "c1": ["c1"], "c2": ["c2a", "c2b"], "c2a": ["c2a"], "c2b": ["c2b"],
     "c3": ["c3a", "c3b"], "c3a": ["c3a"], "c3b": ["c3b"],
     "all": ["c1", "c2a", "c2b", "c3a", "c3b"],
+    "resnet50": [],          # the whole 53-block backbone, Tune vs Eval (time and activation memory)
 }
 
 # HBM bytes per launch of the dominant kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this script (summaries under profiles/); None where not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # fetched + written bytes per launch (partial-sum traffic of the split reduction included)
+    "fprop@c2b": 24.2e6 + 25.7e6, "dgrad@c2b": 24.2e6 + 25.7e6, "wgrad@c2b": 30.0e6 + 38.8e6,
+    "fprop@c2a": 21.5e6 + 12.8e6, "dgrad@c2a": 21.5e6 + 12.8e6, "wgrad@c2a": 29.8e6 + 29.6e6,
+}
 
 
 def parse():
@@ -50,6 +55,12 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eval", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also launch a plain streaming kernel of known size (in-place ReLU over 256 MiB: "
+                         "reads and writes 268435456 bytes each) so that rocprofv3 --pmc FETCH_SIZE / "
+                         "WRITE_SIZE readings of the other kernels can be scaled to bytes")
+    ap.add_argument("--batch", type=int, default=32, help="batch of the resnet50 workload")
+    ap.add_argument("--image", type=int, default=224, help="image size of the resnet50 workload")
     return ap.parse_args()
 
 
@@ -167,12 +178,118 @@ def cpu_baseline(shapes, seconds):
             "sample": "one fwd+bwd of " + ", ".join(desc) + f" ({secs:.1f} s)"}
 
 
+def backbone_flop(shapes):
+    """Useful convolution FLOPs of one fwd+bwd: fprop + wgrad everywhere, dgrad except for the
+    stem (nothing upstream of the images needs a gradient)."""
+    return sum(s.fwd_flop * (2 if s.name == "stem" else 3) for s in shapes)
+
+
+def run_backbone(mode, N, image, steps, warmup):
+    import torch
+    from paper_2305_11624_amd.resnet50 import ResNet50
+    net = ResNet50(N, image, "bf16", mode)
+    g = torch.Generator(device="cpu").manual_seed(0)
+    x = torch.randn(N, image, image, 3, generator=g).to("cuda", torch.bfloat16)
+    h = image // 32
+    dout = torch.randn(N, h, h, 2048, generator=g).to("cuda", torch.bfloat16)
+    torch.cuda.synchronize()
+    base = torch.cuda.memory_allocated()
+    torch.cuda.reset_peak_memory_stats()
+    for _ in range(max(1, warmup)):
+        net.forward(x)
+        net.backward(dout)
+    torch.cuda.synchronize()
+    peak = torch.cuda.max_memory_allocated() - base
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        net.forward(x)
+        net.backward(dout)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    # forward alone and backward alone, HIP events on the stream the kernels run on
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev[0].record(); net.forward(x); ev[1].record(); net.backward(dout); ev[2].record()
+    torch.cuda.synchronize()
+    out = dict(ms=ms, peak_activation_mb=peak / 1e6, saved_model_mb=net.saved_bytes_model() / 1e6,
+               fwd_ms=ev[0].elapsed_time(ev[1]), bwd_ms=ev[1].elapsed_time(ev[2]),
+               refold_blocks=sum(1 for b in net.blocks.values() if mode == "tune" and not b.keep_folded))
+    del net
+    torch.cuda.empty_cache()
+    return out
+
+
+def backbone_cpu_baseline(image, seconds):
+    """The backbone oracle (fp64, OpenMP direct loops) on one fwd+bwd of a batch sized to
+    roughly `seconds`."""
+    import numpy as np
+    import oracle
+    from oracle.resnet import ResNet50Oracle
+    from paper_2305_11624_amd import synth
+    cores = oracle.num_threads()
+    per_image = backbone_flop(synth.resnet50_blocks(1, image, "bf16"))
+    n = int(max(1, min(8, seconds * 1.5e9 * cores / per_image)))
+    shapes = synth.resnet50_blocks(n, image, "bf16")
+    params = {}
+    for sh in shapes:
+        p = synth.make_params(sh)
+        params[sh.name] = {k: (v.double().numpy() if hasattr(v, "numpy") else v) for k, v in p.items()}
+    stages = [[f"l{st}.{i}" for i in range(k)] for st, k in enumerate((3, 4, 6, 3), start=1)]
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((n, 3, image, image))
+    dout = rng.standard_normal((n, 2048, image // 32, image // 32))
+    ref = ResNet50Oracle(params, stages)
+    t0 = time.perf_counter()
+    ref.forward(x)
+    ref.backward(dout)
+    secs = time.perf_counter() - t0
+    return {"value": backbone_flop(shapes) / secs / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"one fwd+bwd of the backbone with N={n}, {image}x{image} ({secs:.1f} s)"}
+
+
+def main_backbone(a):
+    import torch
+    from paper_2305_11624_amd import binding as B
+    from paper_2305_11624_amd import synth
+    B.lib()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    N, image = a.batch, a.image
+    shapes = synth.resnet50_blocks(N, image, "bf16")
+    flop = backbone_flop(shapes)
+    tune = run_backbone("tune", N, image, a.steps, a.warmup)
+    ev = None if a.no_eval else run_backbone("eval", N, image, a.steps, a.warmup)
+    tf = flop / (tune["ms"] * 1e-3) / 1e12
+    line = {
+        "metric": "ConvBN Tune fwd+bwd TFLOP/s (% bf16 MFMA peak) + activation MB vs Eval",
+        "value": tf, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": tune["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"ResNet-50 backbone, 53 ConvBN blocks + ReLU + residual adds + max-pool, "
+                               f"bf16, N={N}, {image}x{image}x3, frozen BN statistics", "mode": "tune",
+                   "layout": "NHWC", "step": "fwd+bwd of the backbone (no gradient w.r.t. the images)"},
+        "pct_of_bf16_mfma_peak": 100.0 * tf / PEAK_BF16_TFLOPS,
+        "tune": tune, "eval": ev,
+        "eval_ms_per_step": ev["ms"] if ev else None,
+        "tune_speedup_vs_eval": ev["ms"] / tune["ms"] if ev else None,
+        "peak_activation_mb": {"tune": tune["peak_activation_mb"], "eval": ev["peak_activation_mb"] if ev else None},
+        "roofline": {"bound": "mfma", "kernel": "whole backbone step (all kernels)", "achieved": tf,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tf / PEAK_BF16_TFLOPS, "traffic": None},
+    }
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = backbone_cpu_baseline(image, a.cpu_seconds)
+    print(json.dumps(line))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus %d is not supported "
-              "(the block shards over the batch, see DESIGN.md)." % a.gpus, file=sys.stderr)
+              "(the block would shard over the batch; only the one-GPU path is built)." % a.gpus, file=sys.stderr)
         sys.exit(2)
+    if a.workload == "resnet50":
+        return main_backbone(a)
     import torch
     from paper_2305_11624_amd import binding as B
     from paper_2305_11624_amd import synth
@@ -207,7 +324,7 @@ def main():
               key=lambda t: t[2])
     dshape = synth.CONFIGS[dom[0]]
     achieved = dshape.fwd_flop / (dom[2] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": f"{dom[1]} igemm @ {dom[0]}", "achieved": achieved,
+    roofline = {"bound": "mfma", "kernel": f"{dom[1]} convolution @ {dom[0]}", "achieved": achieved,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                 "avg_launch_ms": dom[2],
                 "traffic": MEASURED_TRAFFIC_BYTES.get(f"{dom[1]}@{dom[0]}")}
@@ -240,6 +357,12 @@ def main():
         "per_shape": per_shape,
         "roofline": roofline,
     }
+    if a.traffic_calibration:
+        buf = torch.zeros(256 << 19, dtype=torch.bfloat16, device="cuda")     # 256 MiB
+        for _ in range(3):
+            B.convbn_aux_eltwise(B.OP_RELU, buf)
+        torch.cuda.synchronize()
+        del buf
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(names, a.cpu_seconds)
     print(json.dumps(line))
