@@ -5,18 +5,26 @@
 // (zero rows/columns stand in for the padding), then every tap (i,j) of the kernel window is
 // one MFMA sweep over the SAME LDS tile at a wave-uniform offset of (i*Wv + j) pixels: each
 // input element is fetched from memory once per workgroup instead of once per tap.  The weight
-// tile of the current (tap, channel chunk) streams through a double-buffered LDS stage.
+// slab of every (tap, channel chunk) step streams through an LDS ring.
 //
 // Global -> LDS copies are buffer loads that write LDS directly (16 bytes per lane, lane l of a
-// wave lands at base + 16 l); out-of-range lanes are given an offset beyond the buffer and
-// deliver zeros, which is how padding is materialised without branches.  LDS rows are unpadded;
-// the 16-byte granule g of row r is stored at granule g ^ swz(r) so that the 16-lane groups of
-// a 128-bit LDS read fall on distinct banks.
+// wave lands at base + 16 l); a lane given an offset beyond the buffer delivers zeros, which is
+// how padding is materialised without branches.  LDS rows are padded by one 16-byte granule
+// (row pitch 144 or 80 bytes) so that the 128-bit MFMA operand reads of 16 consecutive rows fall
+// on distinct banks; the operand addresses then are "lane base + wave-uniform step offset +
+// immediate", i.e. one vector add per step.  A 1 KB copy therefore covers RPU whole padded rows
+// (7 or 12) and its last lanes the head of the following row, which the next copy writes again
+// with the same values.
+//
+// Everything a copy needs per lane (row validity, padding, tails) is folded once into a per-lane
+// byte offset; a step only adds a wave-uniform scalar offset (tap, channel chunk) to it.
 //
 //   forward conv   Z  = w' (*) X + b'        (Sec. 3.1 / 3.3)    act = x,  weights [Cout][taps][Cin]
 //   input gradient dX = w'_rot (*) dZ        (Sec. 3.2.1), stride 1: the same sweep over dz with
 //                  the taps reversed and padding k-1-p,          weights [Cin][taps][Cout]
 #include "common.h"
+#include <stdio.h>
+#include <stdlib.h>
 
 namespace convbn {
 
@@ -55,12 +63,24 @@ struct TileParams {
   int M;                 // N*Ho*Wo
   int Hv, Wv;            // rows / columns of one image's (virtually padded) window footprint
   int ntr;               // channel tiles
-  int nhb, hps, spread;  // activation tile ring depth, copy slices per step, steps a prefetch spans
+  int nhb, hps, spread;  // activation tile ring depth, copy units per wave and step, steps a prefetch spans
   int ksplit, chunks_per_split;   // channel chunks are divided over gridDim.y workgroups
   float* part;           // [ksplit][M][R] fp32 partial outputs when ksplit > 1
   int halo_stride;       // bytes per activation tile buffer
+  int tab_off;           // byte offset of the per-lane copy-offset table in LDS (multi-chunk only)
+  int tab_rows;          // live table rows per wave (spread * copies per step)
   FastDiv dHoWo, dWo, dHv, dWv;
 };
+
+#ifndef CONVBN_EXP
+#define CONVBN_EXP 0
+#endif
+#ifdef CONVBN_TRACE
+__device__ unsigned long long g_trace[8 * 128];
+#define TRACE(i) do { if (trace_on) g_trace[trace_base + (i)] = __builtin_amdgcn_s_memtime(); } while (0)
+#else
+#define TRACE(i) do { } while (0)
+#endif
 
 constexpr unsigned OOB = 0x80000000u;   // beyond any buffer: the load returns zeros
 
@@ -70,12 +90,14 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsig
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_off, void* lds_wave_base) {
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)lds_wave_base, 16, (int)byte_off, 0, 0, 0);
+// 1 KB copy: lane l fetches 16 bytes at byte offset voff (per lane) + soff (wave-uniform) of the
+// buffer and writes them to LDS at lds_wave_base + 16 l.
+// The compiler barrier keeps every copy in the instruction stream: the waits below count copies, and
+// two copies into the same LDS range (the dummies) would otherwise be merged as a dead store.
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff, void* lds_wave_base) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)lds_wave_base, 16, (int)voff, (int)soff, 0, 0);
+  asm volatile("" ::: "memory");
 }
-
-constexpr int DIST = 3;   // steps between issuing a copy and consuming it
-constexpr int NBUF = 4;   // weight ring (DIST + 1)
 
 // Workgroup barrier without the memory fence of __syncthreads(): the fence would drain every
 // outstanding copy (vmcnt(0)) and serialise the pipeline.  Ordering of the copies is handled by
@@ -87,46 +109,79 @@ __device__ __forceinline__ void block_barrier() {
 }
 
 template <int N> __device__ __forceinline__ void wait_vm() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
-// Waits until at most 2*(wpw + hps) of this wave's copies are outstanding.
-template <int WPW> __device__ __forceinline__ void wait_two_steps(int hps) {
+// Waits until at most STEPS steps' worth (STEPS * (WPW + hps)) of this wave's copies are outstanding.
+template <int WPW, int STEPS> __device__ __forceinline__ void wait_steps(int hps) {
   switch (hps) {
-    case 0: wait_vm<2 * WPW>(); break;
-    case 1: wait_vm<2 * (WPW + 1)>(); break;
-    case 2: wait_vm<2 * (WPW + 2)>(); break;
-    case 4: wait_vm<2 * (WPW + 4)>(); break;
-    default: wait_vm<2 * (WPW + 8)>(); break;
+    case 0: wait_vm<STEPS * WPW>(); break;
+    case 1: wait_vm<STEPS * (WPW + 1)>(); break;
+    case 2: wait_vm<STEPS * (WPW + 2)>(); break;
+    case 3: wait_vm<STEPS * (WPW + 3)>(); break;
+    case 4: wait_vm<STEPS * (WPW + 4)>(); break;
+    case 5: wait_vm<STEPS * (WPW + 5)>(); break;
+    case 6: wait_vm<STEPS * (WPW + 6)>(); break;
+    case 7: wait_vm<STEPS * (WPW + 7)>(); break;
+    default: wait_vm<STEPS * (WPW + 8)>(); break;
   }
 }
 
-// PSUB: 32-pixel subtiles per wave (tile = 128*PSUB pixels); NCH: 32-channel subtiles (TRC = 32 NCH);
-// CB: channels per LDS chunk.
+// Compile-time layout of one instantiation (shared by the kernel and the host planner).
+template <int NCH, int CB> struct TileCfg {
+  static constexpr int TRC = NCH * 32;         // output channels per workgroup
+  static constexpr int GPR = CB / 8;           // data granules (16 B) per LDS row
+  static constexpr int LPR = GPR + 1;          // lanes per row: data granules + one pad granule
+  static constexpr int RPU = 64 / LPR;         // whole rows per 1 KB copy: 7 (CB 64) / 12 (CB 32)
+  static constexpr int ROWP = LPR * 16;        // row pitch: 144 / 80 bytes
+  static constexpr int UNITB = RPU * ROWP;     // LDS bytes between consecutive copies: 1008 / 960
+  static constexpr int KK = CB / 16;           // MFMA k-steps per channel chunk
+  static constexpr int NBUF = CB == 64 ? 4 : 5;   // weight ring slots
+  static constexpr int DIST = NBUF - 1;        // steps between issuing a copy and its step
+  static constexpr int WUNITS = (TRC + RPU - 1) / RPU;
+  static constexpr int WSLAB = WUNITS * UNITB + 64;   // + room for the last copy's spill lanes
+};
+
+// NW waves, each owning 32 pixels x all TRC = 32 NCH channels; CB channels per LDS chunk; HPS
+// activation copies per wave and step (0: the channels of this workgroup are a single chunk, whose
+// activation tile is fetched once up front).
 //
-// Pipeline.  A "step" is one tap of one channel chunk.  Every step each wave issues exactly
-// hps + WPW copies: hps 1 KB slices of a future chunk's activation tile (or dummies into a scratch
-// KB when there is nothing to fetch) and the weight tile of step it+DIST.  Copies complete in issue
-// order, so "at most 2 steps' worth outstanding" means everything issued DIST steps ago has landed.
-// The activation tile ring has nhb buffers: 1 (single chunk), 2 (next chunk fetched during the
-// first `spread` steps of the current one) or 4 (1x1 windows: one step per chunk, fetched DIST
-// chunks ahead).
-template <int NW, int PSUB, int NCH, int CB>
+// Pipeline.  A "step" is one tap of one channel chunk (KK x NCH MFMAs per wave).  Every step each
+// wave issues exactly HPS + WPW copies: HPS 1 KB units of a future chunk's activation tile (dummies
+// into a scratch KB when there is nothing to fetch) and its share of the weight slab of step
+// it+DIST.  Copies complete in issue order, so "at most DIST-2 steps' worth outstanding" means that
+// everything issued DIST-1 or more steps ago has landed, i.e. the data of steps <= it+1.  The MFMA
+// operands are double-buffered in registers one k-step ahead; only the last k-step of a step reads
+// the next step's LDS data, which is why step it+1 must be resident at the barrier of step it and
+// why the slab written during step it is the one of step it-1 (= it+DIST modulo the ring).
+// The activation ring has nhb buffers: 1 (single chunk), 2 (next chunk fetched during the first
+// `spread` steps of the current one) or NBUF (1x1 windows: one step per chunk, fetched DIST ahead).
+// The step loop is branch-free apart from its back edge: all per-step decisions are scalar selects,
+// and the per-lane copy offsets of the activation tile come from a table in LDS built once per
+// workgroup (row k of wave w = copy unit w + NW k; rows past the tile hold the zero-fill offset).
+template <int NW, int NCH, int CB, int HPS>
 __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
-  constexpr int TP = 32 * NW * PSUB;
-  constexpr int TRC = NCH * 32;
-  constexpr int GPR = CB / 8;            // 16-byte granules per LDS row
-  constexpr int RPU = 64 / GPR;          // rows filled by one wave-wide 1 KB copy
-  constexpr int ROWB = CB * 2;           // bytes per LDS row
-  constexpr int SWZ_SHIFT = (CB == 64) ? 1 : 2;   // rows per 256-byte bank cycle = 2 or 4
-  constexpr int WUNITS = TRC / RPU;      // 1 KB copies per weight tile
-  constexpr int WPW = (WUNITS + NW - 1) / NW;  // per wave (waves beyond WUNITS issue dummies)
+  using Cfg = TileCfg<NCH, CB>;
+  constexpr int TP = 32 * NW;
+  constexpr int TRC = Cfg::TRC, GPR = Cfg::GPR, LPR = Cfg::LPR, RPU = Cfg::RPU, ROWP = Cfg::ROWP;
+  constexpr int UNITB = Cfg::UNITB, KK = Cfg::KK, NBUF = Cfg::NBUF, DIST = Cfg::DIST;
+  constexpr int WUNITS = Cfg::WUNITS, WSLAB = Cfg::WSLAB;
+  constexpr int WPW = (WUNITS + NW - 1) / NW;  // weight copies per wave and step (surplus ones are dummies)
+  constexpr bool MULTI = HPS > 0;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   float* biasl = reinterpret_cast<float*>(smem);               // [TRC] bias of this channel tile (first KB)
-  unsigned char* wbuf = smem + 1024;                           // [NBUF][TRC][CB] bf16
-  unsigned char* scratch = wbuf + NBUF * TRC * ROWB;           // 1 KB target of the dummy copies (zeros only)
+  unsigned char* wbuf = smem + 1024;                           // [NBUF] weight slabs
+  unsigned char* scratch = wbuf + NBUF * WSLAB;                // 1 KB target of the dummy copies (zeros only)
   unsigned char* halo = scratch + 1024;                        // [nhb][halo_stride]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+#ifdef CONVBN_TRACE
+  const int trace_slot = blockIdx.y == 0 ? (blockIdx.x == 0 ? 0 : blockIdx.x == 100 ? 1 : blockIdx.x == 255 ? 2 : blockIdx.x == 300 ? 3 : -1) : -1;
+  const bool trace_on = trace_slot >= 0 && tid == 0;
+  const int trace_base = trace_slot * 128;
+#endif
+  TRACE(0);
   const int ctile = blockIdx.x % p.ntr, ptile = blockIdx.x / p.ntr;
   const int r0 = ctile * TRC;
   const int m0 = ptile * TP;
@@ -143,140 +198,213 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   const __amdgpu_buffer_rsrc_t wgt_rsrc = make_rsrc(p.wgt, p.wgt_bytes);
   const int taps = p.kH * p.kW;
   const int cbeg = blockIdx.y * p.chunks_per_split;                       // first channel chunk of this workgroup
-  const int nchunks = min((p.C + CB - 1) / CB, cbeg + p.chunks_per_split);  // one past its last chunk
-  if (tid < TRC) biasl[tid] = (p.bias && r0 + tid < p.R) ? p.bias[r0 + tid] : 0.f;   // read after many barriers
+  const int nchunks = min(p.C / CB, cbeg + p.chunks_per_split);           // one past its last chunk
+#if CONVBN_EXP == 4
+  const int nsteps = 1;
+#else
+  const int nsteps = (nchunks - cbeg) * taps;
+#endif
+  // bias of this channel tile: fetched now, parked in LDS after the main loop (nothing waits for it)
+  const float bias_v = (tid < TRC && p.bias && r0 + tid < p.R) ? p.bias[r0 + tid] : 0.f;
 
-  // this lane's place inside every 1 KB copy unit
-  const int urow = lane / GPR;
-  const int ugran = lane % GPR;
+  // this lane's place inside every 1 KB copy: row lrow (RPU = the spill row) and granule lgran (GPR = pad)
+  const int lrow = lane / LPR;
+  const int lgran = lane - lrow * LPR;
 
-  // weight tile of step `step` (chunk, tap) -> ring slot step % NBUF
-  auto issue_weights = [&](int chunk, int tap, int step) {
-    const int tw = p.flip ? taps - 1 - tap : tap;
-    unsigned char* dst = wbuf + (step % NBUF) * (TRC * ROWB);
+  // per-lane byte offsets of the weight copies this wave issues every step (step part added as a scalar)
+  unsigned voff_w[WPW];
 #pragma unroll
-    for (int j = 0; j < WPW; ++j) {
-      const int u = wave + NW * j;
-      const int row = u * RPU + urow;
-      const int g = ugran ^ ((row >> SWZ_SHIFT) & (GPR - 1));
-      const int ch = chunk * CB + g * 8;
-      unsigned off = (unsigned)((((r0 + row) * taps + tw) * p.C + ch) * 2);
-      if (u >= WUNITS || chunk >= nchunks || r0 + row >= p.R || ch >= p.C) off = OOB;
-      dma16(wgt_rsrc, off, u < WUNITS ? dst + u * 1024 : scratch);
-    }
-  };
-  // unit u of the activation tile of `chunk` (a dummy if there is no such unit)
-  auto issue_halo_unit = [&](int chunk, int u) {
-    const int pix = u * RPU + urow;
-    const int g = ugran ^ ((pix >> SWZ_SHIFT) & (GPR - 1));
+  for (int j = 0; j < WPW; ++j) {
+    const int u = wave + NW * j;
+    const int row = u * RPU + lrow;
+    const bool ok = u < WUNITS && row < TRC && r0 + row < p.R && lgran < GPR;
+    voff_w[j] = ok ? (unsigned)(((r0 + row) * taps * p.C + lgran * 8) * 2) : OOB;
+  }
+  // byte offset (without the channel chunk) of this lane's 16 bytes of copy unit u of the activation tile
+  auto halo_voff = [&](int u) -> unsigned {
+    const int pix = u * RPU + lrow;
     const int slot = fdiv(pix, p.dWv);
     const int w = pix - slot * p.Wv - p.pw;
     const int v = v_first + slot;
     const int n = fdiv(v, p.dHv);
     const int h = v - n * p.Hv - p.ph;
-    const int ch = chunk * CB + g * 8;
-    unsigned off = (unsigned)((n * p.act_n_stride + h * p.act_h_stride + w * p.act_w_stride + ch) * 2);
-    const bool real = u < hunits && chunk < nchunks;
-    const bool ok = real && pix < npix && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W &&
-                    n < p.N && ch < p.C;
-    if (!ok) off = OOB;
-    dma16(act_rsrc, off, real ? halo + (chunk % p.nhb) * p.halo_stride + u * 1024 : scratch);
+    const bool ok = u < hunits && pix < npix && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W &&
+                    n < p.N && lgran < GPR;
+    return ok ? (unsigned)((n * p.act_n_stride + h * p.act_h_stride + w * p.act_w_stride + lgran * 8) * 2) : OOB;
+  };
+  // this wave's share of the weight slab of (chunk, tap) -> ring slot at byte offset slot_off
+  auto issue_weights = [&](int chunk, int tap, int slot_off) {
+    const unsigned soff = (unsigned)(((p.flip ? taps - 1 - tap : tap) * p.C + chunk * CB) * 2);
+    unsigned char* dst = wbuf + slot_off;
+#pragma unroll
+    for (int j = 0; j < WPW; ++j) {
+      const int u = wave + NW * j;
+      dma16(wgt_rsrc, voff_w[j], soff, u < WUNITS ? dst + u * UNITB : scratch);
+    }
   };
 
-  // LDS pixel row of this lane's output pixels (tap (0,0))
-  int pixidx[PSUB];
-#pragma unroll
-  for (int t = 0; t < PSUB; ++t) {
-    const int m = m0 + wave * (32 * PSUB) + t * 32 + (lane & 31);
-    pixidx[t] = 0;
+  // LDS byte offsets of this lane's MFMA operands: pixel row (tap (0,0)) and weight row, k-half kb
+  const int kb = lane >> 5;
+  unsigned boff;
+  {
+    const int m = m0 + wave * 32 + (lane & 31);
+    int pixidx = 0;
     if (m < p.M) {
       const int n = fdiv(m, p.dHoWo);
       const int rem = m - n * HoWo;
       const int ho = fdiv(rem, p.dWo);
       const int wo = rem - ho * p.Wo;
-      pixidx[t] = (n * p.Hv + ho * p.sh - v_first) * p.Wv + wo * p.sw;
+      pixidx = (n * p.Hv + ho * p.sh - v_first) * p.Wv + wo * p.sw;
     }
+    boff = (unsigned)(pixidx * ROWP + kb * 16);
   }
-  const int kb = lane >> 5;
-  // weight operand: byte offset of granule (2 kk + kb) of row (lane%32) for each kk
-  int woff[CB / 16];
-  {
-    const int row = lane & 31;   // 32 | subtile stride, so the swizzle term depends on the lane only
-#pragma unroll
-    for (int kk = 0; kk < CB / 16; ++kk)
-      woff[kk] = row * ROWB + (((2 * kk + kb) ^ ((row >> SWZ_SHIFT) & (GPR - 1))) * 16);
-  }
+  const unsigned aoff = (unsigned)((lane & 31) * ROWP + kb * 16);
 
-  f32x16 acc[PSUB][NCH];
+  f32x16 acc[NCH];
 #pragma unroll
-  for (int t = 0; t < PSUB; ++t)
+  for (int r = 0; r < NCH; ++r)
 #pragma unroll
-    for (int r = 0; r < NCH; ++r)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[t][r][e] = 0.f;
+    for (int e = 0; e < 16; ++e) acc[r][e] = 0.f;
 
   // ---- prologue: the copies steps -DIST .. -1 would have issued --------------------------------
-  if (p.nhb == 4) {
+  // table row k of this wave: [(k NW + wave) 64 + lane]; rows tab_rows .. tab_rows+HPS-1 are all zero-fill
+  unsigned* const tab_lane = reinterpret_cast<unsigned*>(smem + p.tab_off) + wave * 64 + lane;
+  constexpr int TROW = NW * 64;   // table entries per row
+  if (MULTI) {
+    for (int k = 0; k < p.tab_rows + HPS; ++k) tab_lane[k * TROW] = k < p.tab_rows ? halo_voff(wave + NW * k) : OOB;
+  }
+  const bool ring1x1 = MULTI && p.nhb == NBUF;
+  if (ring1x1) {
+    // 1x1 window, several chunks: chunk of step s -> ring buffer s
     for (int s = 0; s < DIST; ++s) {
-      for (int j = 0; j < p.hps; ++j) issue_halo_unit(cbeg + s, wave + NW * j);
-      issue_weights(cbeg + s, 0, s);
+      const int cs = min(cbeg + s, nchunks - 1);
+#pragma unroll
+      for (int j = 0; j < HPS; ++j) {
+        const int u = wave + NW * j;
+        dma16(act_rsrc, tab_lane[j * TROW], (unsigned)(cs * CB * 2), u < hunits ? halo + s * p.halo_stride + u * UNITB : scratch);
+      }
+      issue_weights(cs, 0, s * WSLAB);
     }
   } else {
-    for (int u = wave; u < hunits; u += NW) issue_halo_unit(cbeg, u);
+    for (int u = wave; u < hunits; u += NW)
+      dma16(act_rsrc, halo_voff(u), (unsigned)(cbeg * CB * 2), halo + u * UNITB);
     for (int s = 0; s < DIST; ++s) {
-      if (s > 0)
-        for (int j = 0; j < p.hps; ++j) issue_halo_unit(nchunks, 0);   // dummies keep the count uniform
-      const int c = s / taps;
-      issue_weights(cbeg + c, s - c * taps, s);
+      if (s > 0) {
+#pragma unroll
+        for (int j = 0; j < HPS; ++j) dma16(act_rsrc, OOB, 0u, scratch);   // dummies keep the count uniform
+      }
+      const int cs = s / taps;
+      issue_weights(min(cbeg + cs, nchunks - 1), s - cs * taps, s * WSLAB);
     }
   }
 
-  // position of the weight prefetch (step it + DIST)
-  int pc = cbeg + DIST / taps, pt = DIST % taps;
-  int it = 0;
-  for (int c = cbeg; c < nchunks; ++c) {
-    int tap = 0;
-    const unsigned char* hb = halo + (c % p.nhb) * p.halo_stride;
-    for (int ti = 0; ti < p.kH; ++ti) {
-      for (int tj = 0; tj < p.kW; ++tj, ++tap, ++it) {
-        wait_two_steps<WPW>(p.hps);
-        block_barrier();   // this step's tiles have landed for every wave; last step's reads are done
-        // activation slices of the chunk nhb-1 ahead, then the weights DIST steps ahead
-        for (int j = 0; j < p.hps; ++j) {
-          const bool live = tap < p.spread;
-          issue_halo_unit(live ? c + p.nhb - 1 : nchunks, wave + NW * (tap * p.hps + j));
-        }
-        issue_weights(pc, pt, it + DIST);
-        if (++pt == taps) { pt = 0; ++pc; }
+  // wave-uniform state: current step (c, tap, tj), byte offsets of its operands inside the rings, and
+  // the copy position (step it + DIST; past the end it re-fetches the last chunk, which nobody reads)
+  int c = cbeg, tap = 0, tj = 0;
+  int toff = 0;                    // (ti Wv + tj) ROWP of the current tap
+  int woff = 0;                    // ring offset of the current step's slab
+  int hslot = 0;
+  int pc = cbeg + DIST / taps, pt = DIST % taps, poff = DIST * WSLAB;
+  const int row_skip = (p.Wv - p.kW + 1) * ROWP;
+  unsigned char* const wlane = wbuf + aoff;
+  unsigned char* const hlane = halo + boff;
+  const unsigned char* ap = wlane;            // operands of step 0
+  const unsigned char* bp = hlane;
 
-        const int tapidx = ti * p.Wv + tj;
-        const unsigned char* wb = wbuf + (it % NBUF) * (TRC * ROWB);
-        int prow[PSUB], pswz[PSUB];
+  bf16x8 fa[2][NCH], fb[2];
+  auto load_frags = [&](int buf, const unsigned char* a, const unsigned char* b, int kk) {
+    fb[buf] = *reinterpret_cast<const bf16x8*>(b + kk * 32);
 #pragma unroll
-        for (int t = 0; t < PSUB; ++t) {
-          const int r = pixidx[t] + tapidx;
-          prow[t] = r * ROWB;
-          pswz[t] = (r >> SWZ_SHIFT) & (GPR - 1);
-        }
+    for (int r = 0; r < NCH; ++r) fa[buf][r] = *reinterpret_cast<const bf16x8*>(a + r * 32 * ROWP + kk * 32);
+  };
+
+  TRACE(1);
+#if CONVBN_EXP == 6
+  wait_vm<0>();
+  if (p.N > 0) return;
+#endif
+  wait_vm<(DIST - 1) * (WPW + HPS)>();   // the activation tile of the first chunk and the slab of step 0 have landed
+  TRACE(2);
+  block_barrier();
+  TRACE(3);
+  load_frags(0, ap, bp, 0);
+
+  for (int it = 0; it < nsteps; ++it) {
+    // ---- position of step it+1 (scalar selects only) -----------------------------------------------
+    const bool row_end = tj + 1 == p.kW;
+    const bool chunk_end = tap + 1 == taps;
+    const int ntj = row_end ? 0 : tj + 1;
+    const int ntap = chunk_end ? 0 : tap + 1;
+    const int ntoff = chunk_end ? 0 : toff + (row_end ? row_skip : ROWP);
+    const int nc = c + (chunk_end ? 1 : 0);
+    int nhslot = hslot + (chunk_end ? 1 : 0);
+    nhslot = nhslot == p.nhb ? 0 : nhslot;
+    const int nhoff = nhslot * p.halo_stride;
+    const int nwoff = woff + WSLAB == NBUF * WSLAB ? 0 : woff + WSLAB;
+    const unsigned char* nap = wlane + nwoff;
+    const unsigned char* nbp = hlane + nhoff + ntoff;
+
+    // offsets of this step's activation copies, fetched before the wait (dummy rows when not fetching)
+    unsigned hv[HPS > 0 ? HPS : 1];
+    bool hlive = false;
+    int fslot = 0;
+    if (MULTI) {
+      hlive = tap < p.spread && c + p.nhb - 1 < nchunks;
+#if CONVBN_EXP == 2
+      hlive = false;
+#endif
+      const int krow = hlive ? tap * HPS : p.tab_rows;
+      const unsigned* trow = tab_lane + krow * TROW;
 #pragma unroll
-        for (int kk = 0; kk < CB / 16; ++kk) {
-          bf16x8 a[NCH], b[PSUB];
+      for (int j = 0; j < HPS; ++j) hv[j] = trow[j * TROW];
+      fslot = hslot + p.nhb - 1;
+      fslot = fslot >= p.nhb ? fslot - p.nhb : fslot;
+    }
+
+    if (it < 36) TRACE(8 + 3 * it);
+    wait_vm<(DIST - 2) * (WPW + HPS)>();
+    if (it < 36) TRACE(9 + 3 * it);
+    block_barrier();   // step it+1's data is resident for every wave; step it-1's slab is free
+    if (it < 36) TRACE(10 + 3 * it);
+
+    // ---- copies: activation units of the chunk nhb-1 ahead, weight slab of step it+DIST -----------
+    if (MULTI) {
+      const unsigned hsoff = (unsigned)((c + p.nhb - 1) * CB * 2);
+      unsigned char* dst = halo + fslot * p.halo_stride;
 #pragma unroll
-          for (int t = 0; t < PSUB; ++t)
-            b[t] = *reinterpret_cast<const bf16x8*>(hb + prow[t] + (((2 * kk + kb) ^ pswz[t]) * 16));
-#pragma unroll
-          for (int r = 0; r < NCH; ++r)
-            a[r] = *reinterpret_cast<const bf16x8*>(wb + r * 32 * ROWB + woff[kk]);
-#pragma unroll
-          for (int t = 0; t < PSUB; ++t)
-#pragma unroll
-            for (int r = 0; r < NCH; ++r)
-              acc[t][r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[r], b[t], acc[t][r], 0, 0, 0);
-        }
+      for (int j = 0; j < HPS; ++j) {
+        const int u = wave + NW * (tap * HPS + j);
+        dma16(act_rsrc, hv[j], hsoff, (hlive && u < hunits) ? dst + u * UNITB : scratch);
       }
     }
+    issue_weights(min(pc, nchunks - 1), pt, poff);
+    const bool pwrap = pt + 1 == taps;
+    pt = pwrap ? 0 : pt + 1;
+    pc += pwrap ? 1 : 0;
+    poff = poff + WSLAB == NBUF * WSLAB ? 0 : poff + WSLAB;
+
+    // ---- KK k-steps: operands of k-step kk+1 (or of the next step's first) load while kk multiplies
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      if (kk + 1 < KK) load_frags((kk + 1) & 1, ap, bp, kk + 1);
+      else load_frags((kk + 1) & 1, nap, nbp, 0);
+#pragma unroll
+      for (int r = 0; r < NCH; ++r)
+        acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][r], fb[kk & 1], acc[r], 0, 0, 0);
+    }
+    // keep the order written above: the NCH+1 operand reads of the following k-step go out before
+    // the NCH multiplies of the current one, so their latency hides behind the matrix pipe
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      __builtin_amdgcn_sched_group_barrier(0x100, NCH + 1, 0);   // LDS reads
+      __builtin_amdgcn_sched_group_barrier(0x008, NCH, 0);       // MFMA
+    }
+    c = nc; tap = ntap; tj = ntj; toff = ntoff; hslot = nhslot; woff = nwoff;
+    ap = nap; bp = nbp;
   }
-  wait_vm<0>();   // trailing dummy copies must not outlive the workgroup's LDS
+  TRACE(4);
+  wait_vm<0>();   // trailing copies must not outlive the workgroup's LDS
+  TRACE(5);
 
   // ---- epilogue -------------------------------------------------------------------------------
   // Accumulator element e of lane l: channel 8*(e/4) + 4*(l/32) + e%4, pixel l%32.  Each wave
@@ -285,10 +413,8 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   // and eight lanes cover one pixel's 128 contiguous bytes.
   if (p.ksplit > 1) {
     // fp32 partial sums of this workgroup's channel chunks; bias and rounding happen in the reduction
-#pragma unroll
-    for (int t = 0; t < PSUB; ++t) {
-      const int m = m0 + wave * (32 * PSUB) + t * 32 + (lane & 31);
-      if (m >= p.M) continue;
+    const int m = m0 + wave * 32 + (lane & 31);
+    if (m < p.M) {
       float* orow = p.part + ((size_t)blockIdx.y * p.M + m) * p.R;
 #pragma unroll
       for (int r = 0; r < NCH; ++r)
@@ -296,46 +422,45 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
         for (int q = 0; q < 4; ++q) {
           const int row = r0 + r * 32 + q * 8 + kb * 4;
           if (row < p.R)
-            *reinterpret_cast<float4*>(orow + row) = make_float4(acc[t][r][q * 4 + 0], acc[t][r][q * 4 + 1],
-                                                                 acc[t][r][q * 4 + 2], acc[t][r][q * 4 + 3]);
+            *reinterpret_cast<float4*>(orow + row) = make_float4(acc[r][q * 4 + 0], acc[r][q * 4 + 1],
+                                                                 acc[r][q * 4 + 2], acc[r][q * 4 + 3]);
         }
     }
     return;
   }
-  block_barrier();   // every wave's copies have landed and every wave is done with the ring
+  if (tid < TRC) biasl[tid] = bias_v;
+  __syncthreads();   // every wave's copies have landed, every wave is done with the ring, the bias is visible
   {
     unsigned char* stage = smem + 1024 + wave * 4096;   // behind the bias, over the (now idle) ring and tiles
     const int px = lane & 31;
     const int psw = (px >> 1) & 7;
+    const int mbase = m0 + wave * 32;
 #pragma unroll
-    for (int t = 0; t < PSUB; ++t) {
-      const int mbase = m0 + wave * (32 * PSUB) + t * 32;
+    for (int rp = 0; rp < NCH / 2; ++rp) {
 #pragma unroll
-      for (int rp = 0; rp < NCH / 2; ++rp) {
+      for (int r2 = 0; r2 < 2; ++r2) {
+        const int r = 2 * rp + r2;
 #pragma unroll
-        for (int r2 = 0; r2 < 2; ++r2) {
-          const int r = 2 * rp + r2;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int ch = r2 * 32 + q * 8 + kb * 4;          // channel inside this 64-channel block
-            const float4 bb = *reinterpret_cast<const float4*>(biasl + r * 32 + q * 8 + kb * 4);
-            const uint2 v = make_uint2(pack_bf16x2(acc[t][r][q * 4 + 0] + bb.x, acc[t][r][q * 4 + 1] + bb.y),
-                                       pack_bf16x2(acc[t][r][q * 4 + 2] + bb.z, acc[t][r][q * 4 + 3] + bb.w));
-            *reinterpret_cast<uint2*>(stage + px * 128 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
-          }
+        for (int q = 0; q < 4; ++q) {
+          const int ch = r2 * 32 + q * 8 + kb * 4;          // channel inside this 64-channel block
+          const float4 bb = *reinterpret_cast<const float4*>(biasl + r * 32 + q * 8 + kb * 4);
+          const uint2 v = make_uint2(pack_bf16x2(acc[r][q * 4 + 0] + bb.x, acc[r][q * 4 + 1] + bb.y),
+                                     pack_bf16x2(acc[r][q * 4 + 2] + bb.z, acc[r][q * 4 + 3] + bb.w));
+          *reinterpret_cast<uint2*>(stage + px * 128 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
         }
+      }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int row = i * 8 + (lane >> 3);
-          const int g = (lane & 7) ^ ((row >> 1) & 7);
-          const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 128 + ((lane & 7) << 4));
-          const int m = mbase + row;
-          const int ch = r0 + rp * 64 + g * 8;
-          if (m < p.M && ch < p.R) *reinterpret_cast<uint4*>(p.out + (size_t)m * p.R + ch) = v;
-        }
+      for (int i = 0; i < 4; ++i) {
+        const int row = i * 8 + (lane >> 3);
+        const int g = (lane & 7) ^ ((row >> 1) & 7);
+        const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 128 + ((lane & 7) << 4));
+        const int m = mbase + row;
+        const int ch = r0 + rp * 64 + g * 8;
+        if (m < p.M && ch < p.R) *reinterpret_cast<uint4*>(p.out + (size_t)m * p.R + ch) = v;
       }
     }
   }
+  TRACE(6);
 }
 
 // out[m][r] = bf16( sum_s part[s][m][r] + bias[r] ), eight channels per thread (R % 8 == 0).
@@ -378,7 +503,7 @@ int max_slots(const TileParams& p, int TP) {
   return best;
 }
 
-struct TilePlan { bool ok; int nw, psub, nch, cb; size_t lds; };
+struct TilePlan { bool ok; int nw, nch, cb, hps; size_t lds; };
 
 // fp32 partial-output bytes a problem needs (0 when the channel chunks are not split).
 size_t partial_bytes(const TileParams& p) {
@@ -387,44 +512,57 @@ size_t partial_bytes(const TileParams& p) {
 
 constexpr size_t LDS_LIMIT = 160 * 1024;
 constexpr size_t LDS_USABLE = LDS_LIMIT - 1024;
-constexpr size_t LDS_TWO_PER_CU = 80 * 1024;   // two workgroups of up to this size share one CU
 
-// Fills nhb / hps / spread / halo_stride for (psub, nch, cb); returns the LDS bytes (0 = impossible).
-size_t plan_lds(TileParams& p, int nw, int psub, int nch, int cb) {
+// Fills ksplit / nhb / hps / spread / halo_stride / tab_off / tab_rows for (nw, nch, cb); returns the
+// LDS bytes (0 = this configuration cannot run the problem).
+template <int NCH, int CB>
+size_t plan_lds_cfg(TileParams& p, int nw) {
+  using Cfg = TileCfg<NCH, CB>;
   const int taps = p.kH * p.kW;
-  if (p.C % cb) return 0;
+  if (p.C % CB) return 0;
   // split the channel chunks over several workgroups when the pixel x channel tiling alone
   // leaves most of the chip idle
-  const int all_chunks = p.C / cb;
-  const long long blocks = (long long)ceil_div(p.M, 32 * nw * psub) * ceil_div(p.R, nch * 32);
+  const int all_chunks = p.C / CB;
+  const long long blocks = (long long)ceil_div(p.M, 32 * nw) * ceil_div(p.R, Cfg::TRC);
   int ks = 1;
   if (blocks < 200 && all_chunks >= 4) {
     ks = (int)((400 + blocks - 1) / blocks);
     if (ks > all_chunks / 2) ks = all_chunks / 2;
     if (ks > 8) ks = 8;
   }
+  if (const char* e = getenv("CONVBN_KSPLIT")) { ks = atoi(e); if (ks < 1) ks = 1; if (ks > all_chunks) ks = all_chunks; }
   p.chunks_per_split = ceil_div(all_chunks, ks);
   p.ksplit = ceil_div(all_chunks, p.chunks_per_split);
   const int nchunks = p.chunks_per_split;
-  const size_t rowb = (size_t)cb * 2;
-  const int rpu = (int)(1024 / rowb);
-  const int slots = max_slots(p, 32 * nw * psub);
-  const int hunits = ceil_div(slots * p.Wv, rpu);
+  const int slots = max_slots(p, 32 * nw);
+  const int hunits = ceil_div(slots * p.Wv, Cfg::RPU);
   const int per_wave = ceil_div(hunits, nw);
-  int nhb, spread, need;
-  if (nchunks == 1) { nhb = 1; spread = 0; need = 0; }
-  else if (taps == 1) { nhb = 4; spread = 1; need = per_wave; }
-  else if (taps > DIST) { nhb = 2; spread = taps - DIST; need = ceil_div(per_wave, spread); }
-  else return 0;
-  int hps = 0;
-  if (need > 0) { hps = 1; while (hps < need) hps *= 2; }
-  if (hps > 8) return 0;
-  if (hps == 0) spread = 0;
+  int nhb, spread, hps;
+  if (nchunks == 1) { nhb = 1; spread = 0; hps = 0; }
+  else {
+    // copies per wave and step: a power of two (the kernel is instantiated for 1, 2, 4, 8), spread over
+    // as few steps as the pipeline leaves between two chunks
+    const int max_spread = taps == 1 ? 1 : taps - Cfg::DIST + 1;
+    if (max_spread < 1) return 0;
+    hps = 1;
+    while (hps < 8 && ceil_div(per_wave, hps) > max_spread) hps *= 2;
+    if (ceil_div(per_wave, hps) > max_spread) return 0;
+    spread = ceil_div(per_wave, hps);
+    nhb = taps == 1 ? Cfg::NBUF : 2;
+  }
   p.nhb = nhb; p.hps = hps; p.spread = spread;
-  p.halo_stride = hunits * 1024;
-  const size_t lds = (size_t)NBUF * nch * 32 * rowb + 2 * 1024 + (size_t)nhb * p.halo_stride;
+  p.tab_rows = spread * hps;
+  p.halo_stride = hunits * Cfg::UNITB + 64;
+  size_t lds = 1024 + (size_t)Cfg::NBUF * Cfg::WSLAB + 1024 + (size_t)nhb * p.halo_stride;
+  p.tab_off = (int)lds;
+  if (nhb > 1) lds += (size_t)(p.tab_rows + hps) * nw * 256;
   const size_t stage = 1024 + (size_t)nw * 4096;   // the epilogue stages 4 KB per wave behind the bias
   return lds < stage ? stage : lds;
+}
+
+size_t plan_lds(TileParams& p, int nw, int nch, int cb) {
+  if (nch == 2) return cb == 64 ? plan_lds_cfg<2, 64>(p, nw) : plan_lds_cfg<2, 32>(p, nw);
+  return cb == 64 ? plan_lds_cfg<4, 64>(p, nw) : plan_lds_cfg<4, 32>(p, nw);
 }
 
 TilePlan make_plan(TileParams& p) {
@@ -437,38 +575,49 @@ TilePlan make_plan(TileParams& p) {
   p.dWv = make_fastdiv(p.Wv);
   pl.nch = p.R > 64 ? 4 : 2;
   // 256-pixel tiles run by eight waves when that still yields ~1.5 workgroups per CU, else
-  // 128-pixel tiles run by four; one 32-pixel subtile per wave either way
+  // 128-pixel tiles run by four; 64-channel chunks when they fit, else 32-channel chunks; the other
+  // tile height is the fallback when neither chunk width fits the LDS
   const long long blocks256 = (long long)ceil_div(p.M, 256) * ceil_div(p.R, pl.nch * 32);
-  pl.nw = (blocks256 >= 384 || p.M >= 4096) ? 8 : 4;
-  pl.psub = 1;
-  // 64-channel chunks when two workgroups still share one CU's LDS, else 32-channel chunks
-  TileParams q = p;
-  size_t lds = p.C > 32 ? plan_lds(q, pl.nw, pl.psub, pl.nch, 64) : 0;
-  pl.cb = 64;
-  if (lds == 0 || lds > LDS_TWO_PER_CU) {
-    TileParams q32 = p;
-    const size_t lds32 = plan_lds(q32, pl.nw, pl.psub, pl.nch, 32);
-    if (lds32 != 0 && (lds == 0 || lds32 <= LDS_TWO_PER_CU || lds > LDS_USABLE)) { q = q32; lds = lds32; pl.cb = 32; }
+  const int nw_first = (blocks256 >= 384 || p.M >= 4096) ? 8 : 4;
+  const int nw_try[2] = {nw_first, 12 - nw_first};
+  const int cb_try[2] = {64, 32};
+  if (const char* e = getenv("CONVBN_TILE")) {   // nw,cb override while tuning
+    int a = 0, b = 0;
+    if (sscanf(e, "%d,%d", &a, &b) == 2) {
+      TileParams q = p;
+      const size_t lds = plan_lds(q, a, pl.nch, b);
+      if (lds != 0 && lds <= LDS_USABLE) {
+        p = q; pl.nw = a; pl.cb = b; pl.lds = lds; pl.hps = p.hps; p.ntr = ceil_div(p.R, pl.nch * 32); pl.ok = true;
+        return pl;
+      }
+    }
   }
-  if (lds == 0 || lds > LDS_USABLE) return pl;
-  p = q;
-  pl.lds = lds;
-  p.ntr = ceil_div(p.R, pl.nch * 32);
-  pl.ok = true;
+  for (int nw : nw_try)
+    for (int cb : cb_try) {
+      if (p.C < cb) continue;
+      TileParams q = p;
+      const size_t lds = plan_lds(q, nw, pl.nch, cb);
+      if (lds == 0 || lds > LDS_USABLE) continue;
+      p = q;
+      pl.nw = nw; pl.cb = cb; pl.lds = lds; pl.hps = p.hps;
+      p.ntr = ceil_div(p.R, pl.nch * 32);
+      pl.ok = true;
+      return pl;
+    }
   return pl;
 }
 
-template <int NW, int PSUB, int NCH, int CB>
+template <int NW, int NCH, int CB, int HPS>
 hipError_t launch_inst(const TileParams& p, const TilePlan& pl, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_tile_kernel<NW, PSUB, NCH, CB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_tile_kernel<NW, NCH, CB, HPS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_USABLE);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int ptiles = ceil_div(p.M, 32 * NW * PSUB);
-  hipLaunchKernelGGL((conv_tile_kernel<NW, PSUB, NCH, CB>), dim3(p.ntr * ptiles, p.ksplit), dim3(64 * NW), pl.lds, st, p);
+  const int ptiles = ceil_div(p.M, 32 * NW);
+  hipLaunchKernelGGL((conv_tile_kernel<NW, NCH, CB, HPS>), dim3(p.ntr * ptiles, p.ksplit), dim3(64 * NW), pl.lds, st, p);
   hipError_t le = hipGetLastError();
   if (le != hipSuccess || p.ksplit == 1) return le;
   const size_t MR = (size_t)p.M * p.R;
@@ -478,13 +627,26 @@ hipError_t launch_inst(const TileParams& p, const TilePlan& pl, hipStream_t st) 
 }
 
 hipError_t launch_plan(const TileParams& p, const TilePlan& pl, hipStream_t st) {
-#define CASE(NWV, PS, NC, CBV) \
-  if (pl.nw == NWV && pl.psub == PS && pl.nch == NC && pl.cb == CBV) return launch_inst<NWV, PS, NC, CBV>(p, pl, st);
-  CASE(4, 1, 2, 32) CASE(4, 1, 2, 64) CASE(4, 1, 4, 32) CASE(4, 1, 4, 64)
-  CASE(8, 1, 2, 32) CASE(8, 1, 2, 64) CASE(8, 1, 4, 32) CASE(8, 1, 4, 64)
-  CASE(4, 2, 2, 32) CASE(4, 2, 2, 64) CASE(4, 2, 4, 32) CASE(4, 2, 4, 64)
+  if (getenv("CONVBN_DBG"))
+    fprintf(stderr, "tile plan: nw %d nch %d cb %d hps %d lds %zu | M %d R %d C %d taps %d ksplit %d cps %d nhb %d spread %d tab_rows %d halo_stride %d tab_off %d\n",
+            pl.nw, pl.nch, pl.cb, pl.hps, pl.lds, p.M, p.R, p.C, p.kH * p.kW, p.ksplit, p.chunks_per_split, p.nhb, p.spread, p.tab_rows, p.halo_stride, p.tab_off);
+#define CASE(NWV, NC, CBV, H) \
+  if (pl.nw == NWV && pl.nch == NC && pl.cb == CBV && pl.hps == H) return launch_inst<NWV, NC, CBV, H>(p, pl, st);
+#define CASES(NWV, NC, CBV) CASE(NWV, NC, CBV, 0) CASE(NWV, NC, CBV, 1) CASE(NWV, NC, CBV, 2) CASE(NWV, NC, CBV, 4) CASE(NWV, NC, CBV, 8)
+  CASES(4, 2, 32) CASES(4, 2, 64) CASES(4, 4, 32) CASES(4, 4, 64)
+  CASES(8, 2, 32) CASES(8, 2, 64) CASES(8, 4, 32) CASES(8, 4, 64)
+#undef CASES
 #undef CASE
   return hipErrorInvalidValue;
+}
+
+// A 1x1 window with stride 1 and no padding is a plain matrix product over all N*H*W pixels: present
+// the activations as one image of M rows and one column, so a pixel tile is exactly its own rows.
+void flatten_pointwise(TileParams& q, int M, int C) {
+  q.N = 1; q.H = M; q.W = 1; q.Ho = M; q.Wo = 1;
+  q.act_n_stride = 0; q.act_h_stride = C; q.act_w_stride = 0;
+  q.sh = q.sw = 1; q.ph = q.pw = 0;
+  q.Hv = M; q.Wv = 1;
 }
 
 bool fprop_params(const Geom& g, TileParams* p) {
@@ -507,6 +669,7 @@ bool fprop_params(const Geom& g, TileParams* p) {
   q.wgt_bytes = (unsigned)((size_t)g.Cout * g.K * 2);
   q.Hv = (q.Ho - 1) * q.sh + q.kH;
   q.Wv = (q.Wo - 1) * q.sw + q.kW;
+  if (g.kH == 1 && g.kW == 1 && g.ph == 0 && g.pw == 0 && g.sh == 1 && g.sw == 1) flatten_pointwise(q, g.M, g.Cin);
   return true;
 }
 
@@ -526,6 +689,7 @@ bool dgrad_params(const Geom& g, TileParams* p) {
   q.wgt_bytes = (unsigned)((size_t)g.Cout * g.K * 2);
   q.Hv = (q.Ho - 1) + q.kH;
   q.Wv = (q.Wo - 1) + q.kW;
+  if (g.kH == 1 && g.kW == 1 && g.ph == 0 && g.pw == 0) flatten_pointwise(q, g.Min, g.Cout);
   return true;
 }
 
@@ -576,5 +740,11 @@ hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, 
   p.part = partials;
   return launch_plan(p, pl, st);
 }
+
+#ifdef CONVBN_TRACE
+extern "C" int convbn_debug_trace(unsigned long long* host_out) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace), sizeof(g_trace));
+}
+#endif
 
 }  // namespace convbn

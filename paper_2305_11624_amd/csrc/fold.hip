@@ -29,36 +29,42 @@ __global__ __launch_bounds__(256) void fold_kernel(const T* __restrict__ W, cons
   const int tid = threadIdx.x;
   const int co0 = blockIdx.y * FOLD_TCO;
   const int k0 = blockIdx.x * FOLD_TK;
-  if (blockIdx.x == 0 && tid < FOLD_TCO && bfold) {
+  // Every load of the kernel (weights, the per-row BN vectors, the inputs of b') is issued before the
+  // first use, so the kernel pays one memory round trip, not one per dependent stage.
+  const bool do_bias = blockIdx.x == 0 && tid < FOLD_TCO && bfold && co0 + tid < Cout;
+  float bg = 1.f, bv = 1.f, bm = 0.f, bb = 0.f, bc = 0.f;
+  if (do_bias) {
     const int co = co0 + tid;
-    if (co < Cout) {
-      const float s = identity ? 1.f : gamma[co] / sqrtf(var[co] + eps);
-      const float bc = b ? b[co] : 0.f;
-      bfold[co] = identity ? bc : (bc - mean[co]) * s + beta[co];
-    }
+    if (!identity) { bg = gamma[co]; bv = var[co]; bm = mean[co]; bb = beta[co]; }
+    if (b) bc = b[co];
   }
-  // read + scale: a wave reads 64 consecutive columns of one row; rows tid/64 + 4e.  Every
-  // thread derives the scales of its own rows, so all loads of the kernel are issued together.
+  // read + scale: a wave reads 64 consecutive columns of one row; rows tid/64 + 4e
   {
     const int kc = tid & 63;
     const int k = k0 + kc;
     T wv[FOLD_TCO / 4];
-    float sv[FOLD_TCO / 4];
+    float gv[FOLD_TCO / 4], vv[FOLD_TCO / 4];
 #pragma unroll
     for (int e = 0; e < FOLD_TCO / 4; ++e) {
       const int co = co0 + (tid >> 6) + 4 * e;
       const bool ok = co < Cout && k < K;
       wv[e] = ok ? W[(size_t)co * K + k] : from_f32<T>(0.f);
-      sv[e] = (ok && !identity) ? gamma[co] / sqrtf(var[co] + eps) : 1.f;
+      gv[e] = (ok && !identity) ? gamma[co] : 1.f;
+      vv[e] = (ok && !identity) ? var[co] : 1.f - eps;
     }
 #pragma unroll
     for (int e = 0; e < FOLD_TCO / 4; ++e) {
       const int r = (tid >> 6) + 4 * e;
       const int co = co0 + r;
-      const T v = from_f32<T>(to_f32(wv[e]) * sv[e]);
+      const float sc = identity ? 1.f : gv[e] / sqrtf(vv[e] + eps);
+      const T v = from_f32<T>(to_f32(wv[e]) * sc);
       if (co < Cout && k < K && w_krsc) w_krsc[(size_t)co * K + k] = v;
       tile[kc][r] = v;
     }
+  }
+  if (do_bias) {
+    const float sc = identity ? 1.f : bg / sqrtf(bv + eps);
+    bfold[co0 + tid] = identity ? bc : (bc - bm) * sc + bb;
   }
   if (!w_crsk) return;
   __syncthreads();
@@ -420,19 +426,32 @@ __global__ __launch_bounds__(256) void bn_bwd_bf16x8_kernel(const uint4* __restr
   }
 }
 
-__global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __restrict__ part, int parts,
-                                                              const float* __restrict__ gamma,
-                                                              const float* __restrict__ var, float eps,
-                                                              int Cout, float* __restrict__ dgamma,
-                                                              float* __restrict__ dbeta,
-                                                              float* __restrict__ db) {
-  const int co = blockIdx.x * 256 + threadIdx.x;
-  if (co >= Cout) return;
+// Sums the per-workgroup partial (dbeta, dgamma) rows: 64 channels per workgroup, 16 waves each take
+// every 16th partial row, then a fixed-order reduction through LDS (deterministic).
+__global__ __launch_bounds__(1024) void bn_bwd_finalize_kernel(const float* __restrict__ part, int parts,
+                                                               const float* __restrict__ gamma,
+                                                               const float* __restrict__ var, float eps,
+                                                               int Cout, float* __restrict__ dgamma,
+                                                               float* __restrict__ dbeta,
+                                                               float* __restrict__ db) {
+  __shared__ float red[2][16][64];
+  const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int co = blockIdx.x * 64 + lane;
   float a0 = 0.f, a1 = 0.f;
-  for (int p = 0; p < parts; ++p) {
-    a0 += part[((size_t)p * 2 + 0) * Cout + co];
-    a1 += part[((size_t)p * 2 + 1) * Cout + co];
+  if (co < Cout) {
+#pragma unroll 4
+    for (int p = slice; p < parts; p += 16) {
+      a0 += part[((size_t)p * 2 + 0) * Cout + co];
+      a1 += part[((size_t)p * 2 + 1) * Cout + co];
+    }
   }
+  red[0][slice][lane] = a0;
+  red[1][slice][lane] = a1;
+  __syncthreads();
+  if (slice != 0 || co >= Cout) return;
+  a0 = 0.f; a1 = 0.f;
+#pragma unroll
+  for (int q = 0; q < 16; ++q) { a0 += red[0][q][lane]; a1 += red[1][q][lane]; }
   dbeta[co] = a0;
   dgamma[co] = a1;
   if (db) db[co] = gamma[co] / sqrtf(var[co] + eps) * a0;
@@ -564,7 +583,7 @@ hipError_t launch_bn_bwd(const Geom& g, int dtype, const void* dz, const void* y
 hipError_t launch_bn_bwd_finalize(const Geom& g, const float* part, int parts, const float* gamma,
                                   const float* var, float* dgamma, float* dbeta, float* db,
                                   hipStream_t st) {
-  hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(g.Cout, 256)), dim3(256), 0, st, part, parts,
+  hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(g.Cout, 64)), dim3(1024), 0, st, part, parts,
                      gamma, var, g.eps, g.Cout, dgamma, dbeta, db);
   return hipGetLastError();
 }
