@@ -525,8 +525,8 @@ size_t plan_lds_cfg(TileParams& p, int nw) {
   const int all_chunks = p.C / CB;
   const long long blocks = (long long)ceil_div(p.M, 32 * nw) * ceil_div(p.R, Cfg::TRC);
   int ks = 1;
-  if (blocks < 200 && all_chunks >= 4) {
-    ks = (int)((400 + blocks - 1) / blocks);
+  if (blocks < 160 && all_chunks >= 4) {
+    ks = (int)((200 + blocks - 1) / blocks);
     if (ks > all_chunks / 2) ks = all_chunks / 2;
     if (ks > 8) ks = 8;
   }

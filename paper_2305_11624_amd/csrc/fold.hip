@@ -83,6 +83,72 @@ __global__ __launch_bounds__(256) void fold_kernel(const T* __restrict__ W, cons
   }
 }
 
+// bf16 fast path (K and Cout multiples of 8): 64 x 64 tiles, every global access is a 16-byte vector --
+// rows of W are read and written back eight columns per thread, the transposed copy leaves through an
+// LDS tile as rows of 64 consecutive output channels.
+__global__ __launch_bounds__(256) void fold_bf16x8_kernel(const bf16_t* __restrict__ W, const float* __restrict__ b,
+                                                          const float* __restrict__ gamma,
+                                                          const float* __restrict__ beta,
+                                                          const float* __restrict__ mean,
+                                                          const float* __restrict__ var, float eps, int identity,
+                                                          int Cout, int K, int Cin, int taps,
+                                                          bf16_t* __restrict__ w_krsc, bf16_t* __restrict__ w_crsk,
+                                                          float* __restrict__ bfold) {
+  __shared__ __attribute__((aligned(16))) unsigned short tile[64][72];   // [k][co], 144-byte rows
+  const int tid = threadIdx.x;
+  const int co0 = blockIdx.y * 64;
+  const int k0 = blockIdx.x * 64;
+  const bool do_bias = blockIdx.x == 0 && tid < 64 && bfold && co0 + tid < Cout;
+  float bg = 1.f, bv = 1.f, bm = 0.f, bb = 0.f, bc = 0.f;
+  if (do_bias) {
+    const int co = co0 + tid;
+    if (!identity) { bg = gamma[co]; bv = var[co]; bm = mean[co]; bb = beta[co]; }
+    if (b) bc = b[co];
+  }
+  const int kv = (tid & 7) * 8, r = tid >> 3;
+  uint4 wv[2];
+  float gv[2], vv[2];
+  bool ok[2];
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    const int co = co0 + r + 32 * e;
+    ok[e] = co < Cout && k0 + kv < K;
+    wv[e] = ok[e] ? *reinterpret_cast<const uint4*>(W + (size_t)co * K + k0 + kv) : make_uint4(0u, 0u, 0u, 0u);
+    gv[e] = (ok[e] && !identity) ? gamma[co] : 1.f;
+    vv[e] = (ok[e] && !identity) ? var[co] : 1.f - eps;
+  }
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    const float sc = identity ? 1.f : gv[e] / sqrtf(vv[e] + eps);
+    const uint32_t in[4] = {wv[e].x, wv[e].y, wv[e].z, wv[e].w};
+    uint32_t out[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      out[i] = pack_bf16x2(bf16_lo(in[i]) * sc, bf16_hi(in[i]) * sc);
+      tile[kv + 2 * i][r + 32 * e] = (unsigned short)(out[i] & 0xffffu);
+      tile[kv + 2 * i + 1][r + 32 * e] = (unsigned short)(out[i] >> 16);
+    }
+    if (ok[e] && w_krsc)
+      *reinterpret_cast<uint4*>(w_krsc + (size_t)(co0 + r + 32 * e) * K + k0 + kv) = make_uint4(out[0], out[1], out[2], out[3]);
+  }
+  if (do_bias) {
+    const float sc = identity ? 1.f : bg / sqrtf(bv + eps);
+    bfold[co0 + tid] = identity ? bc : (bc - bm) * sc + bb;
+  }
+  __syncthreads();
+  if (!w_crsk) return;
+  const int kl = tid >> 2, c16 = (tid & 3) * 16;
+  const int k = k0 + kl;
+  if (k < K) {
+    const int tap = k / Cin, ci = k - tap * Cin;
+    bf16_t* dst = w_crsk + ((size_t)ci * taps + tap) * Cout + co0 + c16;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+      if (co0 + c16 + 8 * h < Cout)
+        *reinterpret_cast<uint4*>(dst + 8 * h) = *reinterpret_cast<const uint4*>(&tile[kl][c16 + 8 * h]);
+  }
+}
+
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
 __device__ __forceinline__ void load4(const float* p, float (&w)[4]) {
   const float4 v = ld4(p);
@@ -488,7 +554,11 @@ hipError_t launch_fold(const Geom& g, int dtype, const void* W, const float* b, 
                        void* w_krsc, void* w_crsk, float* bfold, hipStream_t st) {
   dim3 grid(ceil_div(g.K, FOLD_TK), ceil_div(g.Cout, FOLD_TCO));
   const int taps = g.kH * g.kW;
-  if (dtype == CONVBN_BF16)
+  if (dtype == CONVBN_BF16 && g.K % 8 == 0 && g.Cout % 8 == 0)
+    hipLaunchKernelGGL(fold_bf16x8_kernel, dim3(ceil_div(g.K, 64), ceil_div(g.Cout, 64)), dim3(256), 0, st,
+                       (const bf16_t*)W, b, gamma, beta, mean, var, g.eps, identity, g.Cout, g.K, g.Cin, taps,
+                       (bf16_t*)w_krsc, (bf16_t*)w_crsk, bfold);
+  else if (dtype == CONVBN_BF16)
     hipLaunchKernelGGL(fold_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)W, b, gamma, beta,
                        mean, var, g.eps, identity, g.Cout, g.K, g.Cin, taps, (bf16_t*)w_krsc,
                        (bf16_t*)w_crsk, bfold);
