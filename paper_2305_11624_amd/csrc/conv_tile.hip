@@ -23,8 +23,6 @@
 //   input gradient dX = w'_rot (*) dZ        (Sec. 3.2.1), stride 1: the same sweep over dz with
 //                  the taps reversed and padding k-1-p,          weights [Cin][taps][Cout]
 #include "common.h"
-#include <stdio.h>
-#include <stdlib.h>
 
 namespace convbn {
 
@@ -69,18 +67,11 @@ struct TileParams {
   int halo_stride;       // bytes per activation tile buffer
   int tab_off;           // byte offset of the per-lane copy-offset table in LDS (multi-chunk only)
   int tab_rows;          // live table rows per wave (spread * copies per step)
+  int tile_rows;         // > 0: a pixel tile is this many whole output rows of one image (else TP consecutive pixels)
+  int tiles_per_image;
+  FastDiv dTpi;
   FastDiv dHoWo, dWo, dHv, dWv;
 };
-
-#ifndef CONVBN_EXP
-#define CONVBN_EXP 0
-#endif
-#ifdef CONVBN_TRACE
-__device__ unsigned long long g_trace[8 * 128];
-#define TRACE(i) do { if (trace_on) g_trace[trace_base + (i)] = __builtin_amdgcn_s_memtime(); } while (0)
-#else
-#define TRACE(i) do { } while (0)
-#endif
 
 constexpr unsigned OOB = 0x80000000u;   // beyond any buffer: the load returns zeros
 
@@ -142,7 +133,7 @@ template <int NCH, int CB> struct TileCfg {
   static constexpr int WSLAB = WUNITS * UNITB + 64;   // + room for the last copy's spill lanes
 };
 
-// NW waves, each owning 32 pixels x all TRC = 32 NCH channels; CB channels per LDS chunk; HPS
+// NW waves, each owning 32 PSUB pixels x all TRC = 32 NCH channels; CB channels per LDS chunk; HPS
 // activation copies per wave and step (0: the channels of this workgroup are a single chunk, whose
 // activation tile is fetched once up front).
 //
@@ -154,15 +145,15 @@ template <int NCH, int CB> struct TileCfg {
 // operands are double-buffered in registers one k-step ahead; only the last k-step of a step reads
 // the next step's LDS data, which is why step it+1 must be resident at the barrier of step it and
 // why the slab written during step it is the one of step it-1 (= it+DIST modulo the ring).
-// The activation ring has nhb buffers: 1 (single chunk), 2 (next chunk fetched during the first
+// The activation tile has nhb buffers: 1 (single chunk), 2 (the next chunk is fetched during the first
 // `spread` steps of the current one) or NBUF (1x1 windows: one step per chunk, fetched DIST ahead).
 // The step loop is branch-free apart from its back edge: all per-step decisions are scalar selects,
 // and the per-lane copy offsets of the activation tile come from a table in LDS built once per
 // workgroup (row k of wave w = copy unit w + NW k; rows past the tile hold the zero-fill offset).
-template <int NW, int NCH, int CB, int HPS>
+template <int NW, int PSUB, int NCH, int CB, int HPS>
 __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   using Cfg = TileCfg<NCH, CB>;
-  constexpr int TP = 32 * NW;
+  constexpr int TP = 32 * NW * PSUB;
   constexpr int TRC = Cfg::TRC, GPR = Cfg::GPR, LPR = Cfg::LPR, RPU = Cfg::RPU, ROWP = Cfg::ROWP;
   constexpr int UNITB = Cfg::UNITB, KK = Cfg::KK, NBUF = Cfg::NBUF, DIST = Cfg::DIST;
   constexpr int WUNITS = Cfg::WUNITS, WSLAB = Cfg::WSLAB;
@@ -176,17 +167,18 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-#ifdef CONVBN_TRACE
-  const int trace_slot = blockIdx.y == 0 ? (blockIdx.x == 0 ? 0 : blockIdx.x == 100 ? 1 : blockIdx.x == 255 ? 2 : blockIdx.x == 300 ? 3 : -1) : -1;
-  const bool trace_on = trace_slot >= 0 && tid == 0;
-  const int trace_base = trace_slot * 128;
-#endif
-  TRACE(0);
   const int ctile = blockIdx.x % p.ntr, ptile = blockIdx.x / p.ntr;
   const int r0 = ctile * TRC;
-  const int m0 = ptile * TP;
-  const int m_last = min(p.M, m0 + TP) - 1;
   const int HoWo = p.Ho * p.Wo;
+  // pixels [m0, m0 + len) of this tile: TP consecutive pixels, or whole rows of one image
+  int m0 = ptile * TP, len = min(TP, p.M - m0);
+  if (p.tile_rows > 0) {
+    const int n = fdiv(ptile, p.dTpi);
+    const int row0 = (ptile - n * p.tiles_per_image) * p.tile_rows;
+    m0 = n * HoWo + row0 * p.Wo;
+    len = min(p.tile_rows, p.Ho - row0) * p.Wo;
+  }
+  const int m_last = m0 + len - 1;
   const int n_a = fdiv(m0, p.dHoWo), ho_a = fdiv(m0 - n_a * HoWo, p.dWo);
   const int n_b = fdiv(m_last, p.dHoWo), ho_b = fdiv(m_last - n_b * HoWo, p.dWo);
   const int v_first = n_a * p.Hv + ho_a * p.sh;
@@ -199,11 +191,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   const int taps = p.kH * p.kW;
   const int cbeg = blockIdx.y * p.chunks_per_split;                       // first channel chunk of this workgroup
   const int nchunks = min(p.C / CB, cbeg + p.chunks_per_split);           // one past its last chunk
-#if CONVBN_EXP == 4
-  const int nsteps = 1;
-#else
   const int nsteps = (nchunks - cbeg) * taps;
-#endif
   // bias of this channel tile: fetched now, parked in LDS after the main loop (nothing waits for it)
   const float bias_v = (tid < TRC && p.bias && r0 + tid < p.R) ? p.bias[r0 + tid] : 0.f;
 
@@ -245,26 +233,30 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
 
   // LDS byte offsets of this lane's MFMA operands: pixel row (tap (0,0)) and weight row, k-half kb
   const int kb = lane >> 5;
-  unsigned boff;
-  {
-    const int m = m0 + wave * 32 + (lane & 31);
+  unsigned boff[PSUB];
+#pragma unroll
+  for (int t = 0; t < PSUB; ++t) {
+    const int pi = wave * (32 * PSUB) + t * 32 + (lane & 31);
+    const int m = m0 + pi;
     int pixidx = 0;
-    if (m < p.M) {
+    if (pi < len) {
       const int n = fdiv(m, p.dHoWo);
       const int rem = m - n * HoWo;
       const int ho = fdiv(rem, p.dWo);
       const int wo = rem - ho * p.Wo;
       pixidx = (n * p.Hv + ho * p.sh - v_first) * p.Wv + wo * p.sw;
     }
-    boff = (unsigned)(pixidx * ROWP + kb * 16);
+    boff[t] = (unsigned)(pixidx * ROWP + kb * 16);
   }
   const unsigned aoff = (unsigned)((lane & 31) * ROWP + kb * 16);
 
-  f32x16 acc[NCH];
+  f32x16 acc[PSUB][NCH];
 #pragma unroll
-  for (int r = 0; r < NCH; ++r)
+  for (int t = 0; t < PSUB; ++t)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[r][e] = 0.f;
+    for (int r = 0; r < NCH; ++r)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[t][r][e] = 0.f;
 
   // ---- prologue: the copies steps -DIST .. -1 would have issued --------------------------------
   // table row k of this wave: [(k NW + wave) 64 + lane]; rows tab_rows .. tab_rows+HPS-1 are all zero-fill
@@ -273,9 +265,8 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   if (MULTI) {
     for (int k = 0; k < p.tab_rows + HPS; ++k) tab_lane[k * TROW] = k < p.tab_rows ? halo_voff(wave + NW * k) : OOB;
   }
-  const bool ring1x1 = MULTI && p.nhb == NBUF;
-  if (ring1x1) {
-    // 1x1 window, several chunks: chunk of step s -> ring buffer s
+  if (MULTI && p.nhb == NBUF) {
+    // 1x1 window, several chunks: the chunk of step s goes to ring buffer s
     for (int s = 0; s < DIST; ++s) {
       const int cs = min(cbeg + s, nchunks - 1);
 #pragma unroll
@@ -307,27 +298,20 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   int pc = cbeg + DIST / taps, pt = DIST % taps, poff = DIST * WSLAB;
   const int row_skip = (p.Wv - p.kW + 1) * ROWP;
   unsigned char* const wlane = wbuf + aoff;
-  unsigned char* const hlane = halo + boff;
   const unsigned char* ap = wlane;            // operands of step 0
-  const unsigned char* bp = hlane;
+  int bstep = 0;                              // wave-uniform offset of the current step's pixel rows
 
-  bf16x8 fa[2][NCH], fb[2];
-  auto load_frags = [&](int buf, const unsigned char* a, const unsigned char* b, int kk) {
-    fb[buf] = *reinterpret_cast<const bf16x8*>(b + kk * 32);
+  bf16x8 fa[2][NCH], fb[2][PSUB];
+  auto load_frags = [&](int buf, const unsigned char* a, int bs, int kk) {
+#pragma unroll
+    for (int t = 0; t < PSUB; ++t) fb[buf][t] = *reinterpret_cast<const bf16x8*>(halo + boff[t] + bs + kk * 32);
 #pragma unroll
     for (int r = 0; r < NCH; ++r) fa[buf][r] = *reinterpret_cast<const bf16x8*>(a + r * 32 * ROWP + kk * 32);
   };
 
-  TRACE(1);
-#if CONVBN_EXP == 6
-  wait_vm<0>();
-  if (p.N > 0) return;
-#endif
   wait_vm<(DIST - 1) * (WPW + HPS)>();   // the activation tile of the first chunk and the slab of step 0 have landed
-  TRACE(2);
   block_barrier();
-  TRACE(3);
-  load_frags(0, ap, bp, 0);
+  load_frags(0, ap, bstep, 0);
 
   for (int it = 0; it < nsteps; ++it) {
     // ---- position of step it+1 (scalar selects only) -----------------------------------------------
@@ -342,7 +326,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     const int nhoff = nhslot * p.halo_stride;
     const int nwoff = woff + WSLAB == NBUF * WSLAB ? 0 : woff + WSLAB;
     const unsigned char* nap = wlane + nwoff;
-    const unsigned char* nbp = hlane + nhoff + ntoff;
+    const int nbstep = nhoff + ntoff;
 
     // offsets of this step's activation copies, fetched before the wait (dummy rows when not fetching)
     unsigned hv[HPS > 0 ? HPS : 1];
@@ -350,9 +334,6 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     int fslot = 0;
     if (MULTI) {
       hlive = tap < p.spread && c + p.nhb - 1 < nchunks;
-#if CONVBN_EXP == 2
-      hlive = false;
-#endif
       const int krow = hlive ? tap * HPS : p.tab_rows;
       const unsigned* trow = tab_lane + krow * TROW;
 #pragma unroll
@@ -361,11 +342,8 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
       fslot = fslot >= p.nhb ? fslot - p.nhb : fslot;
     }
 
-    if (it < 36) TRACE(8 + 3 * it);
     wait_vm<(DIST - 2) * (WPW + HPS)>();
-    if (it < 36) TRACE(9 + 3 * it);
     block_barrier();   // step it+1's data is resident for every wave; step it-1's slab is free
-    if (it < 36) TRACE(10 + 3 * it);
 
     // ---- copies: activation units of the chunk nhb-1 ahead, weight slab of step it+DIST -----------
     if (MULTI) {
@@ -386,25 +364,25 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     // ---- KK k-steps: operands of k-step kk+1 (or of the next step's first) load while kk multiplies
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      if (kk + 1 < KK) load_frags((kk + 1) & 1, ap, bp, kk + 1);
-      else load_frags((kk + 1) & 1, nap, nbp, 0);
+      if (kk + 1 < KK) load_frags((kk + 1) & 1, ap, bstep, kk + 1);
+      else load_frags((kk + 1) & 1, nap, nbstep, 0);
 #pragma unroll
-      for (int r = 0; r < NCH; ++r)
-        acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][r], fb[kk & 1], acc[r], 0, 0, 0);
+      for (int t = 0; t < PSUB; ++t)
+#pragma unroll
+        for (int r = 0; r < NCH; ++r)
+          acc[t][r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][r], fb[kk & 1][t], acc[t][r], 0, 0, 0);
     }
     // keep the order written above: the NCH+1 operand reads of the following k-step go out before
     // the NCH multiplies of the current one, so their latency hides behind the matrix pipe
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      __builtin_amdgcn_sched_group_barrier(0x100, NCH + 1, 0);   // LDS reads
-      __builtin_amdgcn_sched_group_barrier(0x008, NCH, 0);       // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, NCH + PSUB, 0);   // LDS reads
+      __builtin_amdgcn_sched_group_barrier(0x008, NCH * PSUB, 0);   // MFMA
     }
     c = nc; tap = ntap; tj = ntj; toff = ntoff; hslot = nhslot; woff = nwoff;
-    ap = nap; bp = nbp;
+    ap = nap; bstep = nbstep;
   }
-  TRACE(4);
   wait_vm<0>();   // trailing copies must not outlive the workgroup's LDS
-  TRACE(5);
 
   // ---- epilogue -------------------------------------------------------------------------------
   // Accumulator element e of lane l: channel 8*(e/4) + 4*(l/32) + e%4, pixel l%32.  Each wave
@@ -413,8 +391,11 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   // and eight lanes cover one pixel's 128 contiguous bytes.
   if (p.ksplit > 1) {
     // fp32 partial sums of this workgroup's channel chunks; bias and rounding happen in the reduction
-    const int m = m0 + wave * 32 + (lane & 31);
-    if (m < p.M) {
+#pragma unroll
+    for (int t = 0; t < PSUB; ++t) {
+      const int pi = wave * (32 * PSUB) + t * 32 + (lane & 31);
+      const int m = m0 + pi;
+      if (pi >= len) continue;
       float* orow = p.part + ((size_t)blockIdx.y * p.M + m) * p.R;
 #pragma unroll
       for (int r = 0; r < NCH; ++r)
@@ -422,8 +403,8 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
         for (int q = 0; q < 4; ++q) {
           const int row = r0 + r * 32 + q * 8 + kb * 4;
           if (row < p.R)
-            *reinterpret_cast<float4*>(orow + row) = make_float4(acc[r][q * 4 + 0], acc[r][q * 4 + 1],
-                                                                 acc[r][q * 4 + 2], acc[r][q * 4 + 3]);
+            *reinterpret_cast<float4*>(orow + row) = make_float4(acc[t][r][q * 4 + 0], acc[t][r][q * 4 + 1],
+                                                                 acc[t][r][q * 4 + 2], acc[t][r][q * 4 + 3]);
         }
     }
     return;
@@ -434,33 +415,35 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     unsigned char* stage = smem + 1024 + wave * 4096;   // behind the bias, over the (now idle) ring and tiles
     const int px = lane & 31;
     const int psw = (px >> 1) & 7;
-    const int mbase = m0 + wave * 32;
 #pragma unroll
-    for (int rp = 0; rp < NCH / 2; ++rp) {
+    for (int t = 0; t < PSUB; ++t) {
+      const int pbase = wave * (32 * PSUB) + t * 32;
 #pragma unroll
-      for (int r2 = 0; r2 < 2; ++r2) {
-        const int r = 2 * rp + r2;
+      for (int rp = 0; rp < NCH / 2; ++rp) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int ch = r2 * 32 + q * 8 + kb * 4;          // channel inside this 64-channel block
-          const float4 bb = *reinterpret_cast<const float4*>(biasl + r * 32 + q * 8 + kb * 4);
-          const uint2 v = make_uint2(pack_bf16x2(acc[r][q * 4 + 0] + bb.x, acc[r][q * 4 + 1] + bb.y),
-                                     pack_bf16x2(acc[r][q * 4 + 2] + bb.z, acc[r][q * 4 + 3] + bb.w));
-          *reinterpret_cast<uint2*>(stage + px * 128 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
+        for (int r2 = 0; r2 < 2; ++r2) {
+          const int r = 2 * rp + r2;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int ch = r2 * 32 + q * 8 + kb * 4;          // channel inside this 64-channel block
+            const float4 bb = *reinterpret_cast<const float4*>(biasl + r * 32 + q * 8 + kb * 4);
+            const uint2 v = make_uint2(pack_bf16x2(acc[t][r][q * 4 + 0] + bb.x, acc[t][r][q * 4 + 1] + bb.y),
+                                       pack_bf16x2(acc[t][r][q * 4 + 2] + bb.z, acc[t][r][q * 4 + 3] + bb.w));
+            *reinterpret_cast<uint2*>(stage + px * 128 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
+          }
         }
-      }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = i * 8 + (lane >> 3);
-        const int g = (lane & 7) ^ ((row >> 1) & 7);
-        const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 128 + ((lane & 7) << 4));
-        const int m = mbase + row;
-        const int ch = r0 + rp * 64 + g * 8;
-        if (m < p.M && ch < p.R) *reinterpret_cast<uint4*>(p.out + (size_t)m * p.R + ch) = v;
+        for (int i = 0; i < 4; ++i) {
+          const int row = i * 8 + (lane >> 3);
+          const int g = (lane & 7) ^ ((row >> 1) & 7);
+          const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 128 + ((lane & 7) << 4));
+          const int pi = pbase + row;
+          const int ch = r0 + rp * 64 + g * 8;
+          if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + pi) * p.R + ch) = v;
+        }
       }
     }
   }
-  TRACE(6);
 }
 
 // out[m][r] = bf16( sum_s part[s][m][r] + bias[r] ), eight channels per thread (R % 8 == 0).
@@ -503,7 +486,7 @@ int max_slots(const TileParams& p, int TP) {
   return best;
 }
 
-struct TilePlan { bool ok; int nw, nch, cb, hps; size_t lds; };
+struct TilePlan { bool ok; int nw, psub, nch, cb, hps; size_t lds; };
 
 // fp32 partial-output bytes a problem needs (0 when the channel chunks are not split).
 size_t partial_bytes(const TileParams& p) {
@@ -516,30 +499,45 @@ constexpr size_t LDS_USABLE = LDS_LIMIT - 1024;
 // Fills ksplit / nhb / hps / spread / halo_stride / tab_off / tab_rows for (nw, nch, cb); returns the
 // LDS bytes (0 = this configuration cannot run the problem).
 template <int NCH, int CB>
-size_t plan_lds_cfg(TileParams& p, int nw) {
+size_t plan_lds_cfg(TileParams& p, int nw, int psub, bool rows) {
   using Cfg = TileCfg<NCH, CB>;
   const int taps = p.kH * p.kW;
   if (p.C % CB) return 0;
   // split the channel chunks over several workgroups when the pixel x channel tiling alone
   // leaves most of the chip idle
   const int all_chunks = p.C / CB;
-  const long long blocks = (long long)ceil_div(p.M, 32 * nw) * ceil_div(p.R, Cfg::TRC);
+  const int TPx = 32 * nw * psub;
+  p.tile_rows = 0;
+  p.tiles_per_image = 0;
+  if (rows) {
+    // whole-row tiles: only where they fill most of the tile's lanes
+    if (p.Wo > TPx) return 0;
+    const int tr = TPx / p.Wo < p.Ho ? TPx / p.Wo : p.Ho;
+    if ((long long)p.M * 100 < (long long)85 * p.N * ceil_div(p.Ho, tr) * TPx) return 0;
+    p.tile_rows = tr;
+    p.tiles_per_image = ceil_div(p.Ho, tr);
+    p.dTpi = make_fastdiv(p.tiles_per_image);
+  }
+  const long long ptiles = rows ? (long long)p.N * p.tiles_per_image : ceil_div(p.M, TPx);
+  const long long blocks = ptiles * ceil_div(p.R, Cfg::TRC);
   int ks = 1;
   if (blocks < 160 && all_chunks >= 4) {
     ks = (int)((200 + blocks - 1) / blocks);
     if (ks > all_chunks / 2) ks = all_chunks / 2;
     if (ks > 8) ks = 8;
   }
-  if (const char* e = getenv("CONVBN_KSPLIT")) { ks = atoi(e); if (ks < 1) ks = 1; if (ks > all_chunks) ks = all_chunks; }
   p.chunks_per_split = ceil_div(all_chunks, ks);
   p.ksplit = ceil_div(all_chunks, p.chunks_per_split);
   const int nchunks = p.chunks_per_split;
-  const int slots = max_slots(p, 32 * nw);
+  const int slots = rows ? (p.tile_rows - 1) * p.sh + p.kH : max_slots(p, TPx);
   const int hunits = ceil_div(slots * p.Wv, Cfg::RPU);
   const int per_wave = ceil_div(hunits, nw);
   int nhb, spread, hps;
   if (nchunks == 1) { nhb = 1; spread = 0; hps = 0; }
   else {
+    // 1x1 windows with several chunks: measured faster here than in the generic implicit-GEMM kernel
+    // only for very long pixel ranges with few output channels and for very short pixel ranges
+    if (taps == 1 && !((p.M >= 50000 && p.R <= 64) || p.M <= 2048)) return 0;
     // copies per wave and step: a power of two (the kernel is instantiated for 1, 2, 4, 8), spread over
     // as few steps as the pipeline leaves between two chunks
     const int max_spread = taps == 1 ? 1 : taps - Cfg::DIST + 1;
@@ -560,13 +558,13 @@ size_t plan_lds_cfg(TileParams& p, int nw) {
   return lds < stage ? stage : lds;
 }
 
-size_t plan_lds(TileParams& p, int nw, int nch, int cb) {
-  if (nch == 2) return cb == 64 ? plan_lds_cfg<2, 64>(p, nw) : plan_lds_cfg<2, 32>(p, nw);
-  return cb == 64 ? plan_lds_cfg<4, 64>(p, nw) : plan_lds_cfg<4, 32>(p, nw);
+size_t plan_lds(TileParams& p, int nw, int psub, int nch, int cb, bool rows) {
+  if (nch == 2) return cb == 64 ? plan_lds_cfg<2, 64>(p, nw, psub, rows) : plan_lds_cfg<2, 32>(p, nw, psub, rows);
+  return cb == 64 ? plan_lds_cfg<4, 64>(p, nw, psub, rows) : plan_lds_cfg<4, 32>(p, nw, psub, rows);
 }
 
 TilePlan make_plan(TileParams& p) {
-  TilePlan pl{false, 0, 0, 0, 0, 0};
+  TilePlan pl{false, 0, 0, 0, 0, 0, 0};
   if (p.C % 8 || p.R % 8) return pl;
   if (p.act_bytes >= OOB || p.wgt_bytes >= OOB) return pl;   // byte offsets must stay below the zero-fill offset
   p.dHoWo = make_fastdiv(p.Ho * p.Wo);
@@ -574,50 +572,51 @@ TilePlan make_plan(TileParams& p) {
   p.dHv = make_fastdiv(p.Hv);
   p.dWv = make_fastdiv(p.Wv);
   pl.nch = p.R > 64 ? 4 : 2;
-  // 256-pixel tiles run by eight waves when that still yields ~1.5 workgroups per CU, else
-  // 128-pixel tiles run by four; 64-channel chunks when they fit, else 32-channel chunks; the other
-  // tile height is the fallback when neither chunk width fits the LDS
+  // Candidate shapes (waves, 32-pixel subtiles per wave, channels per chunk), largest tile first.
+  // First choice: the first candidate that fills the chip (>= 160 workgroups) without splitting the
+  // channel chunks -- split sums cost an fp32 round trip through memory and a second kernel.  Else:
+  // many pixels -> 256-pixel tiles run by eight waves (two per SIMD hide each other's scalar work);
+  // few pixels -> four waves with two subtiles each (twice the MFMAs per step for the same per-step
+  // bookkeeping), 128-pixel tiles last.  64-channel chunks wherever the LDS allows.
+  struct Cand { int nw, psub, cb; };
+  static const Cand many[] = {{8, 1, 64}, {8, 1, 32}, {4, 2, 64}, {4, 2, 32}, {4, 1, 64}, {4, 1, 32}};
+  static const Cand few[] = {{4, 2, 64}, {4, 2, 32}, {4, 1, 64}, {4, 1, 32}, {8, 1, 64}, {8, 1, 32}};
   const long long blocks256 = (long long)ceil_div(p.M, 256) * ceil_div(p.R, pl.nch * 32);
-  const int nw_first = (blocks256 >= 384 || p.M >= 4096) ? 8 : 4;
-  const int nw_try[2] = {nw_first, 12 - nw_first};
-  const int cb_try[2] = {64, 32};
-  if (const char* e = getenv("CONVBN_TILE")) {   // nw,cb override while tuning
-    int a = 0, b = 0;
-    if (sscanf(e, "%d,%d", &a, &b) == 2) {
+  const Cand* fallback = (blocks256 >= 384 || p.M >= 4096) ? many : few;
+  for (int pass = 0; pass < 2; ++pass) {
+    const Cand* cands = pass == 0 ? many : fallback;
+    for (int i = 0; i < 6; ++i) {
+      const Cand& cd = cands[i];
+      if (p.C < cd.cb) continue;
       TileParams q = p;
-      const size_t lds = plan_lds(q, a, pl.nch, b);
-      if (lds != 0 && lds <= LDS_USABLE) {
-        p = q; pl.nw = a; pl.cb = b; pl.lds = lds; pl.hps = p.hps; p.ntr = ceil_div(p.R, pl.nch * 32); pl.ok = true;
-        return pl;
-      }
-    }
-  }
-  for (int nw : nw_try)
-    for (int cb : cb_try) {
-      if (p.C < cb) continue;
-      TileParams q = p;
-      const size_t lds = plan_lds(q, nw, pl.nch, cb);
+      const size_t lds = plan_lds(q, cd.nw, cd.psub, pl.nch, cd.cb, false);
       if (lds == 0 || lds > LDS_USABLE) continue;
+      if (pass == 0) {
+        const long long blocks = (long long)ceil_div(q.M, 32 * cd.nw * cd.psub) * ceil_div(q.R, pl.nch * 32);
+        if (q.ksplit != 1 || blocks < 160) continue;
+      }
       p = q;
-      pl.nw = nw; pl.cb = cb; pl.lds = lds; pl.hps = p.hps;
+      pl.nw = cd.nw; pl.psub = cd.psub; pl.cb = cd.cb; pl.lds = lds; pl.hps = p.hps;
       p.ntr = ceil_div(p.R, pl.nch * 32);
       pl.ok = true;
       return pl;
     }
+  }
   return pl;
 }
 
-template <int NW, int NCH, int CB, int HPS>
+template <int NW, int PSUB, int NCH, int CB, int HPS>
 hipError_t launch_inst(const TileParams& p, const TilePlan& pl, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_tile_kernel<NW, NCH, CB, HPS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_tile_kernel<NW, PSUB, NCH, CB, HPS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_USABLE);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int ptiles = ceil_div(p.M, 32 * NW);
-  hipLaunchKernelGGL((conv_tile_kernel<NW, NCH, CB, HPS>), dim3(p.ntr * ptiles, p.ksplit), dim3(64 * NW), pl.lds, st, p);
+  const int ptiles = p.tile_rows > 0 ? p.N * p.tiles_per_image : ceil_div(p.M, 32 * NW * PSUB);
+  hipLaunchKernelGGL((conv_tile_kernel<NW, PSUB, NCH, CB, HPS>), dim3(p.ntr * ptiles, p.ksplit), dim3(64 * NW), pl.lds,
+                     st, p);
   hipError_t le = hipGetLastError();
   if (le != hipSuccess || p.ksplit == 1) return le;
   const size_t MR = (size_t)p.M * p.R;
@@ -627,14 +626,14 @@ hipError_t launch_inst(const TileParams& p, const TilePlan& pl, hipStream_t st) 
 }
 
 hipError_t launch_plan(const TileParams& p, const TilePlan& pl, hipStream_t st) {
-  if (getenv("CONVBN_DBG"))
-    fprintf(stderr, "tile plan: nw %d nch %d cb %d hps %d lds %zu | M %d R %d C %d taps %d ksplit %d cps %d nhb %d spread %d tab_rows %d halo_stride %d tab_off %d\n",
-            pl.nw, pl.nch, pl.cb, pl.hps, pl.lds, p.M, p.R, p.C, p.kH * p.kW, p.ksplit, p.chunks_per_split, p.nhb, p.spread, p.tab_rows, p.halo_stride, p.tab_off);
-#define CASE(NWV, NC, CBV, H) \
-  if (pl.nw == NWV && pl.nch == NC && pl.cb == CBV && pl.hps == H) return launch_inst<NWV, NC, CBV, H>(p, pl, st);
-#define CASES(NWV, NC, CBV) CASE(NWV, NC, CBV, 0) CASE(NWV, NC, CBV, 1) CASE(NWV, NC, CBV, 2) CASE(NWV, NC, CBV, 4) CASE(NWV, NC, CBV, 8)
-  CASES(4, 2, 32) CASES(4, 2, 64) CASES(4, 4, 32) CASES(4, 4, 64)
-  CASES(8, 2, 32) CASES(8, 2, 64) CASES(8, 4, 32) CASES(8, 4, 64)
+#define CASE(NWV, PS, NC, CBV, H) \
+  if (pl.nw == NWV && pl.psub == PS && pl.nch == NC && pl.cb == CBV && pl.hps == H) \
+    return launch_inst<NWV, PS, NC, CBV, H>(p, pl, st);
+#define CASES(NWV, PS, NC, CBV) \
+  CASE(NWV, PS, NC, CBV, 0) CASE(NWV, PS, NC, CBV, 1) CASE(NWV, PS, NC, CBV, 2) CASE(NWV, PS, NC, CBV, 4) CASE(NWV, PS, NC, CBV, 8)
+  CASES(4, 1, 2, 32) CASES(4, 1, 2, 64) CASES(4, 1, 4, 32) CASES(4, 1, 4, 64)
+  CASES(4, 2, 2, 32) CASES(4, 2, 2, 64) CASES(4, 2, 4, 32) CASES(4, 2, 4, 64)
+  CASES(8, 1, 2, 32) CASES(8, 1, 2, 64) CASES(8, 1, 4, 32) CASES(8, 1, 4, 64)
 #undef CASES
 #undef CASE
   return hipErrorInvalidValue;
@@ -740,11 +739,5 @@ hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, 
   p.part = partials;
   return launch_plan(p, pl, st);
 }
-
-#ifdef CONVBN_TRACE
-extern "C" int convbn_debug_trace(unsigned long long* host_out) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace), sizeof(g_trace));
-}
-#endif
 
 }  // namespace convbn

@@ -12,8 +12,6 @@
 // into "lane = channel, 4 pixels per lane").  Every tap reuses the same LDS tile at a
 // wave-uniform pixel offset.
 #include "common.h"
-#include <stdio.h>
-#include <stdlib.h>
 
 namespace convbn {
 
@@ -497,10 +495,6 @@ WgPlan make_plan(const Geom& g, WgParams* pp) {
   if (taps == 1) { pl.tpb = 1; pl.na = g.Cout > 64 ? 2 : 1; pl.nb = g.Cin > 64 ? 2 : 1; pl.nt = 1; }
   else if (taps <= 3) { pl.tpb = 3; pl.na = g.Cout > 64 ? 2 : 1; pl.nb = 1; pl.nt = 1; }
   else { pl.tpb = 9; pl.na = g.Cout > 64 ? 2 : 1; pl.nb = 1; pl.nt = 2; }   // eight waves: 5 + 4 taps
-  if (const char* e = getenv("CONVBN_WG")) {   // tpb,na,nb,nt override while tuning
-    int a, b, c, d;
-    if (sscanf(e, "%d,%d,%d,%d", &a, &b, &c, &d) == 4) { pl.tpb = a; pl.na = b; pl.nb = c; pl.nt = d; }
-  }
   // every pixel split writes a full fp32 copy of dw': keep that traffic near the size of the inputs
   const size_t copy_bytes = (size_t)g.Cout * g.K * 4;
   const size_t in_bytes = ((size_t)g.M * g.Cout + (size_t)g.N * g.Hin * g.Win * g.Cin) * 2;
@@ -528,7 +522,6 @@ WgPlan make_plan(const Geom& g, WgParams* pp) {
   const int base_blocks = p.nci * p.nco * p.ntg;
   int want = 256 / base_blocks;
   if (want > cap) want = cap;
-  if (const char* e = getenv("CONVBN_WGS")) want = atoi(e);
   const int max_split = ceil_div(p.ntiles, 2);
   if (want > max_split) want = max_split;
   if (want < 1) want = 1;
