@@ -581,6 +581,19 @@ TilePlan make_plan(TileParams& p) {
   struct Cand { int nw, psub, cb; };
   static const Cand many[] = {{8, 1, 64}, {8, 1, 32}, {4, 2, 64}, {4, 2, 32}, {4, 1, 64}, {4, 1, 32}};
   static const Cand few[] = {{4, 2, 64}, {4, 2, 32}, {4, 1, 64}, {4, 1, 32}, {8, 1, 64}, {8, 1, 32}};
+  // whole-row tiles first where they apply (wide images): a smaller activation tile for the same pixels
+  {
+    TileParams q = p;
+    const size_t lds = p.C >= 64 ? plan_lds(q, 8, 1, pl.nch, 64, true) : 0;
+    if (lds != 0 && lds <= LDS_USABLE && q.ksplit == 1 &&
+        (long long)q.N * q.tiles_per_image * ceil_div(q.R, pl.nch * 32) >= 160) {
+      p = q;
+      pl.nw = 8; pl.psub = 1; pl.cb = 64; pl.lds = lds; pl.hps = p.hps;
+      p.ntr = ceil_div(p.R, pl.nch * 32);
+      pl.ok = true;
+      return pl;
+    }
+  }
   const long long blocks256 = (long long)ceil_div(p.M, 256) * ceil_div(p.R, pl.nch * 32);
   const Cand* fallback = (blocks256 >= 384 || p.M >= 4096) ? many : few;
   for (int pass = 0; pass < 2; ++pass) {
