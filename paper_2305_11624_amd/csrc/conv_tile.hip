@@ -133,7 +133,8 @@ template <int NCH, int CB> struct TileCfg {
   static constexpr int WSLAB = WUNITS * UNITB + 64;   // + room for the last copy's spill lanes
 };
 
-// NW waves, each owning 32 PSUB pixels x all TRC = 32 NCH channels; CB channels per LDS chunk; HPS
+// NW waves as NW/NWC pixel groups x NWC channel groups, each wave owning 32 PSUB pixels x 32 NCH/NWC of
+// the workgroup's TRC = 32 NCH channels; CB channels per LDS chunk; HPS
 // activation copies per wave and step (0: the channels of this workgroup are a single chunk, whose
 // activation tile is fetched once up front).
 //
@@ -150,10 +151,13 @@ template <int NCH, int CB> struct TileCfg {
 // The step loop is branch-free apart from its back edge: all per-step decisions are scalar selects,
 // and the per-lane copy offsets of the activation tile come from a table in LDS built once per
 // workgroup (row k of wave w = copy unit w + NW k; rows past the tile hold the zero-fill offset).
-template <int NW, int PSUB, int NCH, int CB, int HPS>
+template <int NW, int NWC, int PSUB, int NCH, int CB, int HPS>
 __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   using Cfg = TileCfg<NCH, CB>;
-  constexpr int TP = 32 * NW * PSUB;
+  constexpr int NWP = NW / NWC;            // waves along the pixels
+  constexpr int NCW = NCH / NWC;           // 32-channel subtiles per wave
+  static_assert(NW % NWC == 0 && NCH % NWC == 0 && NCW % 2 == 0, "channel groups must split the tile evenly");
+  constexpr int TP = 32 * NWP * PSUB;
   constexpr int TRC = Cfg::TRC, GPR = Cfg::GPR, LPR = Cfg::LPR, RPU = Cfg::RPU, ROWP = Cfg::ROWP;
   constexpr int UNITB = Cfg::UNITB, KK = Cfg::KK, NBUF = Cfg::NBUF, DIST = Cfg::DIST;
   constexpr int WUNITS = Cfg::WUNITS, WSLAB = Cfg::WSLAB;
@@ -167,6 +171,8 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wp = wave % NWP;               // pixel group and channel group of this wave
+  const int cw0 = (wave / NWP) * NCW;      // its first 32-channel subtile
   const int ctile = blockIdx.x % p.ntr, ptile = blockIdx.x / p.ntr;
   const int r0 = ctile * TRC;
   const int HoWo = p.Ho * p.Wo;
@@ -236,7 +242,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   unsigned boff[PSUB];
 #pragma unroll
   for (int t = 0; t < PSUB; ++t) {
-    const int pi = wave * (32 * PSUB) + t * 32 + (lane & 31);
+    const int pi = wp * (32 * PSUB) + t * 32 + (lane & 31);
     const int m = m0 + pi;
     int pixidx = 0;
     if (pi < len) {
@@ -248,13 +254,13 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     }
     boff[t] = (unsigned)(pixidx * ROWP + kb * 16);
   }
-  const unsigned aoff = (unsigned)((lane & 31) * ROWP + kb * 16);
+  const unsigned aoff = (unsigned)((cw0 * 32 + (lane & 31)) * ROWP + kb * 16);
 
-  f32x16 acc[PSUB][NCH];
+  f32x16 acc[PSUB][NCW];
 #pragma unroll
   for (int t = 0; t < PSUB; ++t)
 #pragma unroll
-    for (int r = 0; r < NCH; ++r)
+    for (int r = 0; r < NCW; ++r)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[t][r][e] = 0.f;
 
@@ -301,12 +307,12 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   const unsigned char* ap = wlane;            // operands of step 0
   int bstep = 0;                              // wave-uniform offset of the current step's pixel rows
 
-  bf16x8 fa[2][NCH], fb[2][PSUB];
+  bf16x8 fa[2][NCW], fb[2][PSUB];
   auto load_frags = [&](int buf, const unsigned char* a, int bs, int kk) {
 #pragma unroll
     for (int t = 0; t < PSUB; ++t) fb[buf][t] = *reinterpret_cast<const bf16x8*>(halo + boff[t] + bs + kk * 32);
 #pragma unroll
-    for (int r = 0; r < NCH; ++r) fa[buf][r] = *reinterpret_cast<const bf16x8*>(a + r * 32 * ROWP + kk * 32);
+    for (int r = 0; r < NCW; ++r) fa[buf][r] = *reinterpret_cast<const bf16x8*>(a + r * 32 * ROWP + kk * 32);
   };
 
   wait_vm<(DIST - 1) * (WPW + HPS)>();   // the activation tile of the first chunk and the slab of step 0 have landed
@@ -369,15 +375,15 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
 #pragma unroll
       for (int t = 0; t < PSUB; ++t)
 #pragma unroll
-        for (int r = 0; r < NCH; ++r)
+        for (int r = 0; r < NCW; ++r)
           acc[t][r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][r], fb[kk & 1][t], acc[t][r], 0, 0, 0);
     }
     // keep the order written above: the NCH+1 operand reads of the following k-step go out before
     // the NCH multiplies of the current one, so their latency hides behind the matrix pipe
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      __builtin_amdgcn_sched_group_barrier(0x100, NCH + PSUB, 0);   // LDS reads
-      __builtin_amdgcn_sched_group_barrier(0x008, NCH * PSUB, 0);   // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, NCW + PSUB, 0);   // LDS reads
+      __builtin_amdgcn_sched_group_barrier(0x008, NCW * PSUB, 0);   // MFMA
     }
     c = nc; tap = ntap; tj = ntj; toff = ntoff; hslot = nhslot; woff = nwoff;
     ap = nap; bstep = nbstep;
@@ -393,15 +399,15 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     // fp32 partial sums of this workgroup's channel chunks; bias and rounding happen in the reduction
 #pragma unroll
     for (int t = 0; t < PSUB; ++t) {
-      const int pi = wave * (32 * PSUB) + t * 32 + (lane & 31);
+      const int pi = wp * (32 * PSUB) + t * 32 + (lane & 31);
       const int m = m0 + pi;
       if (pi >= len) continue;
       float* orow = p.part + ((size_t)blockIdx.y * p.M + m) * p.R;
 #pragma unroll
-      for (int r = 0; r < NCH; ++r)
+      for (int r = 0; r < NCW; ++r)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int row = r0 + r * 32 + q * 8 + kb * 4;
+          const int row = r0 + (cw0 + r) * 32 + q * 8 + kb * 4;
           if (row < p.R)
             *reinterpret_cast<float4*>(orow + row) = make_float4(acc[t][r][q * 4 + 0], acc[t][r][q * 4 + 1],
                                                                  acc[t][r][q * 4 + 2], acc[t][r][q * 4 + 3]);
@@ -417,16 +423,16 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     const int psw = (px >> 1) & 7;
 #pragma unroll
     for (int t = 0; t < PSUB; ++t) {
-      const int pbase = wave * (32 * PSUB) + t * 32;
+      const int pbase = wp * (32 * PSUB) + t * 32;
 #pragma unroll
-      for (int rp = 0; rp < NCH / 2; ++rp) {
+      for (int rp = 0; rp < NCW / 2; ++rp) {
 #pragma unroll
         for (int r2 = 0; r2 < 2; ++r2) {
           const int r = 2 * rp + r2;
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int ch = r2 * 32 + q * 8 + kb * 4;          // channel inside this 64-channel block
-            const float4 bb = *reinterpret_cast<const float4*>(biasl + r * 32 + q * 8 + kb * 4);
+            const float4 bb = *reinterpret_cast<const float4*>(biasl + (cw0 + r) * 32 + q * 8 + kb * 4);
             const uint2 v = make_uint2(pack_bf16x2(acc[t][r][q * 4 + 0] + bb.x, acc[t][r][q * 4 + 1] + bb.y),
                                        pack_bf16x2(acc[t][r][q * 4 + 2] + bb.z, acc[t][r][q * 4 + 3] + bb.w));
             *reinterpret_cast<uint2*>(stage + px * 128 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
@@ -438,7 +444,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
           const int g = (lane & 7) ^ ((row >> 1) & 7);
           const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 128 + ((lane & 7) << 4));
           const int pi = pbase + row;
-          const int ch = r0 + rp * 64 + g * 8;
+          const int ch = r0 + (cw0 / 2 + rp) * 64 + g * 8;
           if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + pi) * p.R + ch) = v;
         }
       }
@@ -486,7 +492,7 @@ int max_slots(const TileParams& p, int TP) {
   return best;
 }
 
-struct TilePlan { bool ok; int nw, psub, nch, cb, hps; size_t lds; };
+struct TilePlan { bool ok; int nw, nwc, psub, nch, cb, hps; size_t lds; };
 
 // fp32 partial-output bytes a problem needs (0 when the channel chunks are not split).
 size_t partial_bytes(const TileParams& p) {
@@ -499,14 +505,14 @@ constexpr size_t LDS_USABLE = LDS_LIMIT - 1024;
 // Fills ksplit / nhb / hps / spread / halo_stride / tab_off / tab_rows for (nw, nch, cb); returns the
 // LDS bytes (0 = this configuration cannot run the problem).
 template <int NCH, int CB>
-size_t plan_lds_cfg(TileParams& p, int nw, int psub, bool rows) {
+size_t plan_lds_cfg(TileParams& p, int nw, int nwc, int psub, bool rows) {
   using Cfg = TileCfg<NCH, CB>;
   const int taps = p.kH * p.kW;
   if (p.C % CB) return 0;
   // split the channel chunks over several workgroups when the pixel x channel tiling alone
   // leaves most of the chip idle
   const int all_chunks = p.C / CB;
-  const int TPx = 32 * nw * psub;
+  const int TPx = 32 * (nw / nwc) * psub;
   p.tile_rows = 0;
   p.tiles_per_image = 0;
   if (rows) {
@@ -558,13 +564,14 @@ size_t plan_lds_cfg(TileParams& p, int nw, int psub, bool rows) {
   return lds < stage ? stage : lds;
 }
 
-size_t plan_lds(TileParams& p, int nw, int psub, int nch, int cb, bool rows) {
-  if (nch == 2) return cb == 64 ? plan_lds_cfg<2, 64>(p, nw, psub, rows) : plan_lds_cfg<2, 32>(p, nw, psub, rows);
-  return cb == 64 ? plan_lds_cfg<4, 64>(p, nw, psub, rows) : plan_lds_cfg<4, 32>(p, nw, psub, rows);
+size_t plan_lds(TileParams& p, int nw, int nwc, int psub, int nch, int cb, bool rows) {
+  if (nwc > 1 && nch != 4) return 0;   // channel groups need two 32-channel subtiles per wave
+  if (nch == 2) return cb == 64 ? plan_lds_cfg<2, 64>(p, nw, nwc, psub, rows) : plan_lds_cfg<2, 32>(p, nw, nwc, psub, rows);
+  return cb == 64 ? plan_lds_cfg<4, 64>(p, nw, nwc, psub, rows) : plan_lds_cfg<4, 32>(p, nw, nwc, psub, rows);
 }
 
 TilePlan make_plan(TileParams& p) {
-  TilePlan pl{false, 0, 0, 0, 0, 0, 0};
+  TilePlan pl{false, 0, 0, 0, 0, 0, 0, 0};
   if (p.C % 8 || p.R % 8) return pl;
   if (p.act_bytes >= OOB || p.wgt_bytes >= OOB) return pl;   // byte offsets must stay below the zero-fill offset
   p.dHoWo = make_fastdiv(p.Ho * p.Wo);
@@ -576,19 +583,25 @@ TilePlan make_plan(TileParams& p) {
   // First choice: the first candidate that fills the chip (>= 160 workgroups) without splitting the
   // channel chunks -- split sums cost an fp32 round trip through memory and a second kernel.  Else:
   // many pixels -> 256-pixel tiles run by eight waves (two per SIMD hide each other's scalar work);
-  // few pixels -> four waves with two subtiles each (twice the MFMAs per step for the same per-step
-  // bookkeeping), 128-pixel tiles last.  64-channel chunks wherever the LDS allows.
-  struct Cand { int nw, psub, cb; };
-  static const Cand many[] = {{8, 1, 64}, {8, 1, 32}, {4, 2, 64}, {4, 2, 32}, {4, 1, 64}, {4, 1, 32}};
-  static const Cand few[] = {{4, 2, 64}, {4, 2, 32}, {4, 1, 64}, {4, 1, 32}, {8, 1, 64}, {8, 1, 32}};
+  // few pixels -> 64-pixel tiles with the channels split over two wave groups (no split sums for up
+  // to ~3000 pixels), then four waves with two subtiles each.  64-channel chunks wherever the LDS allows.
+  struct Cand { int nw, nwc, psub, cb; };
+  // (8,1,1): 256 px, eight waves.  (4,1,2): 256 px, four waves x two subtiles.  (4,1,1): 128 px.
+  // (8,2,1) / (4,2,1): 128 / 64 px with the channels split over two wave groups -- small pixel tiles
+  // that still give every wave a 32 x 64 block, for deep reductions over few pixels.
+  static const Cand many[] = {{8, 1, 1, 64}, {8, 1, 1, 32}, {4, 1, 2, 64}, {4, 1, 2, 32}, {4, 1, 1, 64}, {4, 1, 1, 32},
+                              {8, 2, 1, 64}, {8, 2, 1, 32}, {4, 2, 1, 64}, {4, 2, 1, 32}};
+  static const Cand few[] = {{4, 2, 1, 64}, {4, 2, 1, 32}, {4, 1, 2, 64}, {4, 1, 2, 32}, {4, 1, 1, 64}, {4, 1, 1, 32},
+                             {8, 1, 1, 64}, {8, 1, 1, 32}, {8, 2, 1, 64}, {8, 2, 1, 32}};
+  constexpr int NCAND = 10;
   // whole-row tiles first where they apply (wide images): a smaller activation tile for the same pixels
   {
     TileParams q = p;
-    const size_t lds = p.C >= 64 ? plan_lds(q, 8, 1, pl.nch, 64, true) : 0;
+    const size_t lds = p.C >= 64 ? plan_lds(q, 8, 1, 1, pl.nch, 64, true) : 0;
     if (lds != 0 && lds <= LDS_USABLE && q.ksplit == 1 &&
         (long long)q.N * q.tiles_per_image * ceil_div(q.R, pl.nch * 32) >= 160) {
       p = q;
-      pl.nw = 8; pl.psub = 1; pl.cb = 64; pl.lds = lds; pl.hps = p.hps;
+      pl.nw = 8; pl.nwc = 1; pl.psub = 1; pl.cb = 64; pl.lds = lds; pl.hps = p.hps;
       p.ntr = ceil_div(p.R, pl.nch * 32);
       pl.ok = true;
       return pl;
@@ -598,18 +611,18 @@ TilePlan make_plan(TileParams& p) {
   const Cand* fallback = (blocks256 >= 384 || p.M >= 4096) ? many : few;
   for (int pass = 0; pass < 2; ++pass) {
     const Cand* cands = pass == 0 ? many : fallback;
-    for (int i = 0; i < 6; ++i) {
+    for (int i = 0; i < NCAND; ++i) {
       const Cand& cd = cands[i];
       if (p.C < cd.cb) continue;
       TileParams q = p;
-      const size_t lds = plan_lds(q, cd.nw, cd.psub, pl.nch, cd.cb, false);
+      const size_t lds = plan_lds(q, cd.nw, cd.nwc, cd.psub, pl.nch, cd.cb, false);
       if (lds == 0 || lds > LDS_USABLE) continue;
       if (pass == 0) {
-        const long long blocks = (long long)ceil_div(q.M, 32 * cd.nw * cd.psub) * ceil_div(q.R, pl.nch * 32);
+        const long long blocks = (long long)ceil_div(q.M, 32 * (cd.nw / cd.nwc) * cd.psub) * ceil_div(q.R, pl.nch * 32);
         if (q.ksplit != 1 || blocks < 160) continue;
       }
       p = q;
-      pl.nw = cd.nw; pl.psub = cd.psub; pl.cb = cd.cb; pl.lds = lds; pl.hps = p.hps;
+      pl.nw = cd.nw; pl.nwc = cd.nwc; pl.psub = cd.psub; pl.cb = cd.cb; pl.lds = lds; pl.hps = p.hps;
       p.ntr = ceil_div(p.R, pl.nch * 32);
       pl.ok = true;
       return pl;
@@ -618,18 +631,18 @@ TilePlan make_plan(TileParams& p) {
   return pl;
 }
 
-template <int NW, int PSUB, int NCH, int CB, int HPS>
+template <int NW, int NWC, int PSUB, int NCH, int CB, int HPS>
 hipError_t launch_inst(const TileParams& p, const TilePlan& pl, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_tile_kernel<NW, PSUB, NCH, CB, HPS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_tile_kernel<NW, NWC, PSUB, NCH, CB, HPS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_USABLE);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int ptiles = p.tile_rows > 0 ? p.N * p.tiles_per_image : ceil_div(p.M, 32 * NW * PSUB);
-  hipLaunchKernelGGL((conv_tile_kernel<NW, PSUB, NCH, CB, HPS>), dim3(p.ntr * ptiles, p.ksplit), dim3(64 * NW), pl.lds,
-                     st, p);
+  const int ptiles = p.tile_rows > 0 ? p.N * p.tiles_per_image : ceil_div(p.M, 32 * (NW / NWC) * PSUB);
+  hipLaunchKernelGGL((conv_tile_kernel<NW, NWC, PSUB, NCH, CB, HPS>), dim3(p.ntr * ptiles, p.ksplit), dim3(64 * NW),
+                     pl.lds, st, p);
   hipError_t le = hipGetLastError();
   if (le != hipSuccess || p.ksplit == 1) return le;
   const size_t MR = (size_t)p.M * p.R;
@@ -639,14 +652,16 @@ hipError_t launch_inst(const TileParams& p, const TilePlan& pl, hipStream_t st) 
 }
 
 hipError_t launch_plan(const TileParams& p, const TilePlan& pl, hipStream_t st) {
-#define CASE(NWV, PS, NC, CBV, H) \
-  if (pl.nw == NWV && pl.psub == PS && pl.nch == NC && pl.cb == CBV && pl.hps == H) \
-    return launch_inst<NWV, PS, NC, CBV, H>(p, pl, st);
-#define CASES(NWV, PS, NC, CBV) \
-  CASE(NWV, PS, NC, CBV, 0) CASE(NWV, PS, NC, CBV, 1) CASE(NWV, PS, NC, CBV, 2) CASE(NWV, PS, NC, CBV, 4) CASE(NWV, PS, NC, CBV, 8)
-  CASES(4, 1, 2, 32) CASES(4, 1, 2, 64) CASES(4, 1, 4, 32) CASES(4, 1, 4, 64)
-  CASES(4, 2, 2, 32) CASES(4, 2, 2, 64) CASES(4, 2, 4, 32) CASES(4, 2, 4, 64)
-  CASES(8, 1, 2, 32) CASES(8, 1, 2, 64) CASES(8, 1, 4, 32) CASES(8, 1, 4, 64)
+#define CASE(NWV, WC, PS, NC, CBV, H) \
+  if (pl.nw == NWV && pl.nwc == WC && pl.psub == PS && pl.nch == NC && pl.cb == CBV && pl.hps == H) \
+    return launch_inst<NWV, WC, PS, NC, CBV, H>(p, pl, st);
+#define CASES(NWV, WC, PS, NC, CBV) \
+  CASE(NWV, WC, PS, NC, CBV, 0) CASE(NWV, WC, PS, NC, CBV, 1) CASE(NWV, WC, PS, NC, CBV, 2) CASE(NWV, WC, PS, NC, CBV, 4) \
+  CASE(NWV, WC, PS, NC, CBV, 8)
+  CASES(4, 1, 1, 2, 32) CASES(4, 1, 1, 2, 64) CASES(4, 1, 1, 4, 32) CASES(4, 1, 1, 4, 64)
+  CASES(4, 1, 2, 2, 32) CASES(4, 1, 2, 2, 64) CASES(4, 1, 2, 4, 32) CASES(4, 1, 2, 4, 64)
+  CASES(8, 1, 1, 2, 32) CASES(8, 1, 1, 2, 64) CASES(8, 1, 1, 4, 32) CASES(8, 1, 1, 4, 64)
+  CASES(4, 2, 1, 4, 32) CASES(4, 2, 1, 4, 64) CASES(8, 2, 1, 4, 32) CASES(8, 2, 1, 4, 64)
 #undef CASES
 #undef CASE
   return hipErrorInvalidValue;
