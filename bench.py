@@ -37,9 +37,8 @@ WORKLOADS = {
 # HBM bytes per launch of the dominant kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this script (summaries under profiles/); None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # fetched + written bytes per launch (partial-sum traffic of the split reduction included; for the
-    # split c2b passes the reduction kernel's own 25.7 + 3.2 MB come on top)
-    "fprop@c2b": 23.4e6 + 25.7e6, "dgrad@c2b": 23.4e6 + 25.7e6, "wgrad@c2b": 29.1e6 + 37.8e6,
+    # fetched + written bytes per launch
+    "fprop@c2b": 26.0e6 + 3.2e6, "dgrad@c2b": 26.0e6 + 3.2e6, "wgrad@c2b": 29.1e6 + 37.8e6,
     "fprop@c2a": 19.5e6 + 12.9e6, "dgrad@c2a": 19.5e6 + 12.9e6, "wgrad@c2a": 29.8e6 + 29.6e6,
 }
 
@@ -325,8 +324,7 @@ def main():
               key=lambda t: t[2])
     dshape = synth.CONFIGS[dom[0]]
     achieved = dshape.fwd_flop / (dom[2] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": f"{dom[1]} @ {dom[0]}" + (" (conv_tile_kernel + reduce_partials_kernel)"
-                                                        if dom[0] == "c2b" and dom[1] != "wgrad" else ""), "achieved": achieved,
+    roofline = {"bound": "mfma", "kernel": f"{dom[1]} @ {dom[0]}", "achieved": achieved,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                 "avg_launch_ms": dom[2],
                 "traffic": MEASURED_TRAFFIC_BYTES.get(f"{dom[1]}@{dom[0]}")}
