@@ -133,7 +133,7 @@ template <int NCH, int CB> struct TileCfg {
   static constexpr int WSLAB = WUNITS * UNITB + 64;   // + room for the last copy's spill lanes
 };
 
-// NW waves as NW/NWC pixel groups x NWC channel groups, each wave owning 32 PSUB pixels x 32 NCH/NWC of
+// NW waves as NW/NWC pixel groups x NWC channel groups, each wave owning 32 pixels x 32 NCH/NWC of
 // the workgroup's TRC = 32 NCH channels; CB channels per LDS chunk; HPS
 // activation copies per wave and step (0: the channels of this workgroup are a single chunk, whose
 // activation tile is fetched once up front).
@@ -151,13 +151,13 @@ template <int NCH, int CB> struct TileCfg {
 // The step loop is branch-free apart from its back edge: all per-step decisions are scalar selects,
 // and the per-lane copy offsets of the activation tile come from a table in LDS built once per
 // workgroup (row k of wave w = copy unit w + NW k; rows past the tile hold the zero-fill offset).
-template <int NW, int NWC, int PSUB, int NCH, int CB, int HPS>
+template <int NW, int NWC, int NCH, int CB, int HPS>
 __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   using Cfg = TileCfg<NCH, CB>;
   constexpr int NWP = NW / NWC;            // waves along the pixels
   constexpr int NCW = NCH / NWC;           // 32-channel subtiles per wave
   static_assert(NW % NWC == 0 && NCH % NWC == 0 && NCW % 2 == 0, "channel groups must split the tile evenly");
-  constexpr int TP = 32 * NWP * PSUB;
+  constexpr int TP = 32 * NWP;
   constexpr int TRC = Cfg::TRC, GPR = Cfg::GPR, LPR = Cfg::LPR, RPU = Cfg::RPU, ROWP = Cfg::ROWP;
   constexpr int UNITB = Cfg::UNITB, KK = Cfg::KK, NBUF = Cfg::NBUF, DIST = Cfg::DIST;
   constexpr int WUNITS = Cfg::WUNITS, WSLAB = Cfg::WSLAB;
@@ -239,10 +239,9 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
 
   // LDS byte offsets of this lane's MFMA operands: pixel row (tap (0,0)) and weight row, k-half kb
   const int kb = lane >> 5;
-  unsigned boff[PSUB];
-#pragma unroll
-  for (int t = 0; t < PSUB; ++t) {
-    const int pi = wp * (32 * PSUB) + t * 32 + (lane & 31);
+  unsigned boff;
+  {
+    const int pi = wp * 32 + (lane & 31);
     const int m = m0 + pi;
     int pixidx = 0;
     if (pi < len) {
@@ -252,17 +251,15 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
       const int wo = rem - ho * p.Wo;
       pixidx = (n * p.Hv + ho * p.sh - v_first) * p.Wv + wo * p.sw;
     }
-    boff[t] = (unsigned)(pixidx * ROWP + kb * 16);
+    boff = (unsigned)(pixidx * ROWP + kb * 16);
   }
   const unsigned aoff = (unsigned)((cw0 * 32 + (lane & 31)) * ROWP + kb * 16);
 
-  f32x16 acc[PSUB][NCW];
+  f32x16 acc[NCW];
 #pragma unroll
-  for (int t = 0; t < PSUB; ++t)
+  for (int r = 0; r < NCW; ++r)
 #pragma unroll
-    for (int r = 0; r < NCW; ++r)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[t][r][e] = 0.f;
+    for (int e = 0; e < 16; ++e) acc[r][e] = 0.f;
 
   // ---- prologue: the copies steps -DIST .. -1 would have issued --------------------------------
   // table row k of this wave: [(k NW + wave) 64 + lane]; rows tab_rows .. tab_rows+HPS-1 are all zero-fill
@@ -307,10 +304,9 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   const unsigned char* ap = wlane;            // operands of step 0
   int bstep = 0;                              // wave-uniform offset of the current step's pixel rows
 
-  bf16x8 fa[2][NCW], fb[2][PSUB];
+  bf16x8 fa[2][NCW], fb[2];
   auto load_frags = [&](int buf, const unsigned char* a, int bs, int kk) {
-#pragma unroll
-    for (int t = 0; t < PSUB; ++t) fb[buf][t] = *reinterpret_cast<const bf16x8*>(halo + boff[t] + bs + kk * 32);
+    fb[buf] = *reinterpret_cast<const bf16x8*>(halo + boff + bs + kk * 32);
 #pragma unroll
     for (int r = 0; r < NCW; ++r) fa[buf][r] = *reinterpret_cast<const bf16x8*>(a + r * 32 * ROWP + kk * 32);
   };
@@ -373,17 +369,15 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
       if (kk + 1 < KK) load_frags((kk + 1) & 1, ap, bstep, kk + 1);
       else load_frags((kk + 1) & 1, nap, nbstep, 0);
 #pragma unroll
-      for (int t = 0; t < PSUB; ++t)
-#pragma unroll
-        for (int r = 0; r < NCW; ++r)
-          acc[t][r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][r], fb[kk & 1][t], acc[t][r], 0, 0, 0);
+      for (int r = 0; r < NCW; ++r)
+        acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][r], fb[kk & 1], acc[r], 0, 0, 0);
     }
     // keep the order written above: the NCH+1 operand reads of the following k-step go out before
     // the NCH multiplies of the current one, so their latency hides behind the matrix pipe
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      __builtin_amdgcn_sched_group_barrier(0x100, NCW + PSUB, 0);   // LDS reads
-      __builtin_amdgcn_sched_group_barrier(0x008, NCW * PSUB, 0);   // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, NCW + 1, 0);   // LDS reads
+      __builtin_amdgcn_sched_group_barrier(0x008, NCW, 0);       // MFMA
     }
     c = nc; tap = ntap; tj = ntj; toff = ntoff; hslot = nhslot; woff = nwoff;
     ap = nap; bstep = nbstep;
@@ -397,20 +391,17 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   // and eight lanes cover one pixel's 128 contiguous bytes.
   if (p.ksplit > 1) {
     // fp32 partial sums of this workgroup's channel chunks; bias and rounding happen in the reduction
-#pragma unroll
-    for (int t = 0; t < PSUB; ++t) {
-      const int pi = wp * (32 * PSUB) + t * 32 + (lane & 31);
-      const int m = m0 + pi;
-      if (pi >= len) continue;
-      float* orow = p.part + ((size_t)blockIdx.y * p.M + m) * p.R;
+    const int pi = wp * 32 + (lane & 31);
+    if (pi < len) {
+      float* orow = p.part + ((size_t)blockIdx.y * p.M + m0 + pi) * p.R;
 #pragma unroll
       for (int r = 0; r < NCW; ++r)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int row = r0 + (cw0 + r) * 32 + q * 8 + kb * 4;
           if (row < p.R)
-            *reinterpret_cast<float4*>(orow + row) = make_float4(acc[t][r][q * 4 + 0], acc[t][r][q * 4 + 1],
-                                                                 acc[t][r][q * 4 + 2], acc[t][r][q * 4 + 3]);
+            *reinterpret_cast<float4*>(orow + row) = make_float4(acc[r][q * 4 + 0], acc[r][q * 4 + 1],
+                                                                 acc[r][q * 4 + 2], acc[r][q * 4 + 3]);
         }
     }
     return;
@@ -421,32 +412,29 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     unsigned char* stage = smem + 1024 + wave * 4096;   // behind the bias, over the (now idle) ring and tiles
     const int px = lane & 31;
     const int psw = (px >> 1) & 7;
+    const int pbase = wp * 32;
 #pragma unroll
-    for (int t = 0; t < PSUB; ++t) {
-      const int pbase = wp * (32 * PSUB) + t * 32;
+    for (int rp = 0; rp < NCW / 2; ++rp) {
 #pragma unroll
-      for (int rp = 0; rp < NCW / 2; ++rp) {
+      for (int r2 = 0; r2 < 2; ++r2) {
+        const int r = 2 * rp + r2;
 #pragma unroll
-        for (int r2 = 0; r2 < 2; ++r2) {
-          const int r = 2 * rp + r2;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int ch = r2 * 32 + q * 8 + kb * 4;          // channel inside this 64-channel block
-            const float4 bb = *reinterpret_cast<const float4*>(biasl + (cw0 + r) * 32 + q * 8 + kb * 4);
-            const uint2 v = make_uint2(pack_bf16x2(acc[t][r][q * 4 + 0] + bb.x, acc[t][r][q * 4 + 1] + bb.y),
-                                       pack_bf16x2(acc[t][r][q * 4 + 2] + bb.z, acc[t][r][q * 4 + 3] + bb.w));
-            *reinterpret_cast<uint2*>(stage + px * 128 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
-          }
+        for (int q = 0; q < 4; ++q) {
+          const int ch = r2 * 32 + q * 8 + kb * 4;          // channel inside this 64-channel block
+          const float4 bb = *reinterpret_cast<const float4*>(biasl + (cw0 + r) * 32 + q * 8 + kb * 4);
+          const uint2 v = make_uint2(pack_bf16x2(acc[r][q * 4 + 0] + bb.x, acc[r][q * 4 + 1] + bb.y),
+                                     pack_bf16x2(acc[r][q * 4 + 2] + bb.z, acc[r][q * 4 + 3] + bb.w));
+          *reinterpret_cast<uint2*>(stage + px * 128 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
         }
+      }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int row = i * 8 + (lane >> 3);
-          const int g = (lane & 7) ^ ((row >> 1) & 7);
-          const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 128 + ((lane & 7) << 4));
-          const int pi = pbase + row;
-          const int ch = r0 + (cw0 / 2 + rp) * 64 + g * 8;
-          if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + pi) * p.R + ch) = v;
-        }
+      for (int i = 0; i < 4; ++i) {
+        const int row = i * 8 + (lane >> 3);
+        const int g = (lane & 7) ^ ((row >> 1) & 7);
+        const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 128 + ((lane & 7) << 4));
+        const int pi = pbase + row;
+        const int ch = r0 + (cw0 / 2 + rp) * 64 + g * 8;
+        if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + pi) * p.R + ch) = v;
       }
     }
   }
@@ -492,7 +480,7 @@ int max_slots(const TileParams& p, int TP) {
   return best;
 }
 
-struct TilePlan { bool ok; int nw, nwc, psub, nch, cb, hps; size_t lds; };
+struct TilePlan { bool ok; int nw, nwc, nch, cb, hps; size_t lds; };
 
 // fp32 partial-output bytes a problem needs (0 when the channel chunks are not split).
 size_t partial_bytes(const TileParams& p) {
@@ -505,14 +493,14 @@ constexpr size_t LDS_USABLE = LDS_LIMIT - 1024;
 // Fills ksplit / nhb / hps / spread / halo_stride / tab_off / tab_rows for (nw, nch, cb); returns the
 // LDS bytes (0 = this configuration cannot run the problem).
 template <int NCH, int CB>
-size_t plan_lds_cfg(TileParams& p, int nw, int nwc, int psub, bool rows) {
+size_t plan_lds_cfg(TileParams& p, int nw, int nwc, bool rows) {
   using Cfg = TileCfg<NCH, CB>;
   const int taps = p.kH * p.kW;
   if (p.C % CB) return 0;
   // split the channel chunks over several workgroups when the pixel x channel tiling alone
   // leaves most of the chip idle
   const int all_chunks = p.C / CB;
-  const int TPx = 32 * (nw / nwc) * psub;
+  const int TPx = 32 * (nw / nwc);
   p.tile_rows = 0;
   p.tiles_per_image = 0;
   if (rows) {
@@ -564,14 +552,14 @@ size_t plan_lds_cfg(TileParams& p, int nw, int nwc, int psub, bool rows) {
   return lds < stage ? stage : lds;
 }
 
-size_t plan_lds(TileParams& p, int nw, int nwc, int psub, int nch, int cb, bool rows) {
+size_t plan_lds(TileParams& p, int nw, int nwc, int nch, int cb, bool rows) {
   if (nwc > 1 && nch != 4) return 0;   // channel groups need two 32-channel subtiles per wave
-  if (nch == 2) return cb == 64 ? plan_lds_cfg<2, 64>(p, nw, nwc, psub, rows) : plan_lds_cfg<2, 32>(p, nw, nwc, psub, rows);
-  return cb == 64 ? plan_lds_cfg<4, 64>(p, nw, nwc, psub, rows) : plan_lds_cfg<4, 32>(p, nw, nwc, psub, rows);
+  if (nch == 2) return cb == 64 ? plan_lds_cfg<2, 64>(p, nw, nwc, rows) : plan_lds_cfg<2, 32>(p, nw, nwc, rows);
+  return cb == 64 ? plan_lds_cfg<4, 64>(p, nw, nwc, rows) : plan_lds_cfg<4, 32>(p, nw, nwc, rows);
 }
 
 TilePlan make_plan(TileParams& p) {
-  TilePlan pl{false, 0, 0, 0, 0, 0, 0, 0};
+  TilePlan pl{false, 0, 0, 0, 0, 0, 0};
   if (p.C % 8 || p.R % 8) return pl;
   if (p.act_bytes >= OOB || p.wgt_bytes >= OOB) return pl;   // byte offsets must stay below the zero-fill offset
   p.dHoWo = make_fastdiv(p.Ho * p.Wo);
@@ -579,29 +567,28 @@ TilePlan make_plan(TileParams& p) {
   p.dHv = make_fastdiv(p.Hv);
   p.dWv = make_fastdiv(p.Wv);
   pl.nch = p.R > 64 ? 4 : 2;
-  // Candidate shapes (waves, 32-pixel subtiles per wave, channels per chunk), largest tile first.
-  // First choice: the first candidate that fills the chip (>= 160 workgroups) without splitting the
-  // channel chunks -- split sums cost an fp32 round trip through memory and a second kernel.  Else:
-  // many pixels -> 256-pixel tiles run by eight waves (two per SIMD hide each other's scalar work);
-  // few pixels -> 64-pixel tiles with the channels split over two wave groups (no split sums for up
-  // to ~3000 pixels), then four waves with two subtiles each.  64-channel chunks wherever the LDS allows.
-  struct Cand { int nw, nwc, psub, cb; };
-  // (8,1,1): 256 px, eight waves.  (4,1,2): 256 px, four waves x two subtiles.  (4,1,1): 128 px.
-  // (8,2,1) / (4,2,1): 128 / 64 px with the channels split over two wave groups -- small pixel tiles
-  // that still give every wave a 32 x 64 block, for deep reductions over few pixels.
-  static const Cand many[] = {{8, 1, 1, 64}, {8, 1, 1, 32}, {4, 1, 2, 64}, {4, 1, 2, 32}, {4, 1, 1, 64}, {4, 1, 1, 32},
-                              {8, 2, 1, 64}, {8, 2, 1, 32}, {4, 2, 1, 64}, {4, 2, 1, 32}};
-  static const Cand few[] = {{4, 2, 1, 64}, {4, 2, 1, 32}, {4, 1, 2, 64}, {4, 1, 2, 32}, {4, 1, 1, 64}, {4, 1, 1, 32},
-                             {8, 1, 1, 64}, {8, 1, 1, 32}, {8, 2, 1, 64}, {8, 2, 1, 32}};
-  constexpr int NCAND = 10;
-  // whole-row tiles first where they apply (wide images): a smaller activation tile for the same pixels
+  // Candidate shapes (waves, channel groups, channels per chunk):
+  //   (8,1): 256 pixels, eight waves -- two per SIMD hide each other's scalar work; many pixels.
+  //   (4,1): 128 pixels, four waves.
+  //   (4,2): 64 pixels, the four waves split the 128 channels two ways -- a small pixel tile that still
+  //          gives every wave a 32 x 64 block; deep reductions over few pixels (no split sums up to
+  //          ~3000 pixels), and the stride-2 3x3 layers whose window tiles would not fit otherwise.
+  // First choice: whole-row tiles where they apply (wide images: a smaller activation tile for the
+  // same pixels).  Then the first candidate that fills the chip (>= 160 workgroups) without splitting
+  // the channel chunks -- split sums cost an fp32 round trip through memory and a second kernel.
+  // Else the first that fits, largest tile first for many pixels, smallest first for few.
+  // 64-channel chunks wherever the LDS allows.
+  struct Cand { int nw, nwc, cb; };
+  static const Cand many[] = {{8, 1, 64}, {8, 1, 32}, {4, 1, 64}, {4, 1, 32}, {4, 2, 64}, {4, 2, 32}};
+  static const Cand few[] = {{4, 2, 64}, {4, 2, 32}, {4, 1, 64}, {4, 1, 32}, {8, 1, 64}, {8, 1, 32}};
+  constexpr int NCAND = 6;
   {
     TileParams q = p;
-    const size_t lds = p.C >= 64 ? plan_lds(q, 8, 1, 1, pl.nch, 64, true) : 0;
+    const size_t lds = p.C >= 64 ? plan_lds(q, 8, 1, pl.nch, 64, true) : 0;
     if (lds != 0 && lds <= LDS_USABLE && q.ksplit == 1 &&
         (long long)q.N * q.tiles_per_image * ceil_div(q.R, pl.nch * 32) >= 160) {
       p = q;
-      pl.nw = 8; pl.nwc = 1; pl.psub = 1; pl.cb = 64; pl.lds = lds; pl.hps = p.hps;
+      pl.nw = 8; pl.nwc = 1; pl.cb = 64; pl.lds = lds; pl.hps = p.hps;
       p.ntr = ceil_div(p.R, pl.nch * 32);
       pl.ok = true;
       return pl;
@@ -615,14 +602,14 @@ TilePlan make_plan(TileParams& p) {
       const Cand& cd = cands[i];
       if (p.C < cd.cb) continue;
       TileParams q = p;
-      const size_t lds = plan_lds(q, cd.nw, cd.nwc, cd.psub, pl.nch, cd.cb, false);
+      const size_t lds = plan_lds(q, cd.nw, cd.nwc, pl.nch, cd.cb, false);
       if (lds == 0 || lds > LDS_USABLE) continue;
       if (pass == 0) {
-        const long long blocks = (long long)ceil_div(q.M, 32 * (cd.nw / cd.nwc) * cd.psub) * ceil_div(q.R, pl.nch * 32);
+        const long long blocks = (long long)ceil_div(q.M, 32 * (cd.nw / cd.nwc)) * ceil_div(q.R, pl.nch * 32);
         if (q.ksplit != 1 || blocks < 160) continue;
       }
       p = q;
-      pl.nw = cd.nw; pl.nwc = cd.nwc; pl.psub = cd.psub; pl.cb = cd.cb; pl.lds = lds; pl.hps = p.hps;
+      pl.nw = cd.nw; pl.nwc = cd.nwc; pl.cb = cd.cb; pl.lds = lds; pl.hps = p.hps;
       p.ntr = ceil_div(p.R, pl.nch * 32);
       pl.ok = true;
       return pl;
@@ -631,18 +618,18 @@ TilePlan make_plan(TileParams& p) {
   return pl;
 }
 
-template <int NW, int NWC, int PSUB, int NCH, int CB, int HPS>
+template <int NW, int NWC, int NCH, int CB, int HPS>
 hipError_t launch_inst(const TileParams& p, const TilePlan& pl, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_tile_kernel<NW, NWC, PSUB, NCH, CB, HPS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_tile_kernel<NW, NWC, NCH, CB, HPS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_USABLE);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int ptiles = p.tile_rows > 0 ? p.N * p.tiles_per_image : ceil_div(p.M, 32 * (NW / NWC) * PSUB);
-  hipLaunchKernelGGL((conv_tile_kernel<NW, NWC, PSUB, NCH, CB, HPS>), dim3(p.ntr * ptiles, p.ksplit), dim3(64 * NW),
-                     pl.lds, st, p);
+  const int ptiles = p.tile_rows > 0 ? p.N * p.tiles_per_image : ceil_div(p.M, 32 * (NW / NWC));
+  hipLaunchKernelGGL((conv_tile_kernel<NW, NWC, NCH, CB, HPS>), dim3(p.ntr * ptiles, p.ksplit), dim3(64 * NW), pl.lds, st,
+                     p);
   hipError_t le = hipGetLastError();
   if (le != hipSuccess || p.ksplit == 1) return le;
   const size_t MR = (size_t)p.M * p.R;
@@ -652,16 +639,14 @@ hipError_t launch_inst(const TileParams& p, const TilePlan& pl, hipStream_t st) 
 }
 
 hipError_t launch_plan(const TileParams& p, const TilePlan& pl, hipStream_t st) {
-#define CASE(NWV, WC, PS, NC, CBV, H) \
-  if (pl.nw == NWV && pl.nwc == WC && pl.psub == PS && pl.nch == NC && pl.cb == CBV && pl.hps == H) \
-    return launch_inst<NWV, WC, PS, NC, CBV, H>(p, pl, st);
-#define CASES(NWV, WC, PS, NC, CBV) \
-  CASE(NWV, WC, PS, NC, CBV, 0) CASE(NWV, WC, PS, NC, CBV, 1) CASE(NWV, WC, PS, NC, CBV, 2) CASE(NWV, WC, PS, NC, CBV, 4) \
-  CASE(NWV, WC, PS, NC, CBV, 8)
-  CASES(4, 1, 1, 2, 32) CASES(4, 1, 1, 2, 64) CASES(4, 1, 1, 4, 32) CASES(4, 1, 1, 4, 64)
-  CASES(4, 1, 2, 2, 32) CASES(4, 1, 2, 2, 64) CASES(4, 1, 2, 4, 32) CASES(4, 1, 2, 4, 64)
-  CASES(8, 1, 1, 2, 32) CASES(8, 1, 1, 2, 64) CASES(8, 1, 1, 4, 32) CASES(8, 1, 1, 4, 64)
-  CASES(4, 2, 1, 4, 32) CASES(4, 2, 1, 4, 64) CASES(8, 2, 1, 4, 32) CASES(8, 2, 1, 4, 64)
+#define CASE(NWV, WC, NC, CBV, H) \
+  if (pl.nw == NWV && pl.nwc == WC && pl.nch == NC && pl.cb == CBV && pl.hps == H) \
+    return launch_inst<NWV, WC, NC, CBV, H>(p, pl, st);
+#define CASES(NWV, WC, NC, CBV) \
+  CASE(NWV, WC, NC, CBV, 0) CASE(NWV, WC, NC, CBV, 1) CASE(NWV, WC, NC, CBV, 2) CASE(NWV, WC, NC, CBV, 4) CASE(NWV, WC, NC, CBV, 8)
+  CASES(4, 1, 2, 32) CASES(4, 1, 2, 64) CASES(4, 1, 4, 32) CASES(4, 1, 4, 64)
+  CASES(8, 1, 2, 32) CASES(8, 1, 2, 64) CASES(8, 1, 4, 32) CASES(8, 1, 4, 64)
+  CASES(4, 2, 4, 32) CASES(4, 2, 4, 64)
 #undef CASES
 #undef CASE
   return hipErrorInvalidValue;
