@@ -57,7 +57,13 @@ struct TileParams {
   int act_n_stride, act_h_stride, act_w_stride;
   int Ho, Wo, R;
   int kH, kW, sh, sw, ph, pw;
-  int flip;              // weight tap order reversed
+  int wrow;              // elements per output-channel row of the weight tensor (its taps x C)
+  // window position (ti, tj) reads tap wt0 + ti wt_row + tj wt_col of the weight tensor (forward: the same
+  // position; input gradient: the rotated one; strided input gradient: every stride-th tap, rotated)
+  int wt0, wt_row, wt_col;
+  int no_split;          // the output is strided: no split sums (their reduction assumes a dense output)
+  int out_strided;       // output pixel (n, ho, wo) lives at out_base + n out_n + ho out_h + wo out_w (elements)
+  int out_base, out_n, out_h, out_w;
   int M;                 // N*Ho*Wo
   int Hv, Wv;            // rows / columns of one image's (virtually padded) window footprint
   int ntr;               // channel tiles
@@ -212,7 +218,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     const int u = wave + NW * j;
     const int row = u * RPU + lrow;
     const bool ok = u < WUNITS && row < TRC && r0 + row < p.R && lgran < GPR;
-    voff_w[j] = ok ? (unsigned)(((r0 + row) * taps * p.C + lgran * 8) * 2) : OOB;
+    voff_w[j] = ok ? (unsigned)(((r0 + row) * p.wrow + lgran * 8) * 2) : OOB;
   }
   // byte offset (without the channel chunk) of this lane's 16 bytes of copy unit u of the activation tile
   auto halo_voff = [&](int u) -> unsigned {
@@ -227,8 +233,8 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     return ok ? (unsigned)((n * p.act_n_stride + h * p.act_h_stride + w * p.act_w_stride + lgran * 8) * 2) : OOB;
   };
   // this wave's share of the weight slab of (chunk, tap) -> ring slot at byte offset slot_off
-  auto issue_weights = [&](int chunk, int tap, int slot_off) {
-    const unsigned soff = (unsigned)(((p.flip ? taps - 1 - tap : tap) * p.C + chunk * CB) * 2);
+  auto issue_weights = [&](int chunk, int wtap, int slot_off) {
+    const unsigned soff = (unsigned)((wtap * p.C + chunk * CB) * 2);
     unsigned char* dst = wbuf + slot_off;
 #pragma unroll
     for (int j = 0; j < WPW; ++j) {
@@ -277,7 +283,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
         const int u = wave + NW * j;
         dma16(act_rsrc, tab_lane[j * TROW], (unsigned)(cs * CB * 2), u < hunits ? halo + s * p.halo_stride + u * UNITB : scratch);
       }
-      issue_weights(cs, 0, s * WSLAB);
+      issue_weights(cs, p.wt0, s * WSLAB);
     }
   } else {
     for (int u = wave; u < hunits; u += NW)
@@ -287,8 +293,8 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
 #pragma unroll
         for (int j = 0; j < HPS; ++j) dma16(act_rsrc, OOB, 0u, scratch);   // dummies keep the count uniform
       }
-      const int cs = s / taps;
-      issue_weights(min(cbeg + cs, nchunks - 1), s - cs * taps, s * WSLAB);
+      const int cs = s / taps, ti = (s - cs * taps) / p.kW, tj = s - cs * taps - ti * p.kW;
+      issue_weights(min(cbeg + cs, nchunks - 1), p.wt0 + ti * p.wt_row + tj * p.wt_col, s * WSLAB);
     }
   }
 
@@ -299,6 +305,8 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   int woff = 0;                    // ring offset of the current step's slab
   int hslot = 0;
   int pc = cbeg + DIST / taps, pt = DIST % taps, poff = DIST * WSLAB;
+  int ptj = pt % p.kW, pwt = p.wt0 + (pt / p.kW) * p.wt_row + ptj * p.wt_col;   // column and weight tap of the copy position
+  const int wt_next_row = p.wt_row - (p.kW - 1) * p.wt_col;
   const int row_skip = (p.Wv - p.kW + 1) * ROWP;
   unsigned char* const wlane = wbuf + aoff;
   const unsigned char* ap = wlane;            // operands of step 0
@@ -357,8 +365,10 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
         dma16(act_rsrc, hv[j], hsoff, (hlive && u < hunits) ? dst + u * UNITB : scratch);
       }
     }
-    issue_weights(min(pc, nchunks - 1), pt, poff);
-    const bool pwrap = pt + 1 == taps;
+    issue_weights(min(pc, nchunks - 1), pwt, poff);
+    const bool pwrap = pt + 1 == taps, prow = ptj + 1 == p.kW;
+    pwt = pwrap ? p.wt0 : pwt + (prow ? wt_next_row : p.wt_col);
+    ptj = prow ? 0 : ptj + 1;
     pt = pwrap ? 0 : pt + 1;
     pc += pwrap ? 1 : 0;
     poff = poff + WSLAB == NBUF * WSLAB ? 0 : poff + WSLAB;
@@ -434,7 +444,15 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
         const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 128 + ((lane & 7) << 4));
         const int pi = pbase + row;
         const int ch = r0 + (cw0 / 2 + rp) * 64 + g * 8;
-        if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + pi) * p.R + ch) = v;
+        size_t o = (size_t)(m0 + pi) * p.R;
+        if (p.out_strided) {
+          const int m = m0 + pi;
+          const int n = fdiv(m, p.dHoWo);
+          const int rem = m - n * HoWo;
+          const int ho = fdiv(rem, p.dWo);
+          o = (size_t)p.out_base + (size_t)n * p.out_n + (size_t)ho * p.out_h + (size_t)(rem - ho * p.Wo) * p.out_w;
+        }
+        if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + o + ch) = v;
       }
     }
   }
@@ -515,7 +533,7 @@ size_t plan_lds_cfg(TileParams& p, int nw, int nwc, bool rows) {
   const long long ptiles = rows ? (long long)p.N * p.tiles_per_image : ceil_div(p.M, TPx);
   const long long blocks = ptiles * ceil_div(p.R, Cfg::TRC);
   int ks = 1;
-  if (blocks < 160 && all_chunks >= 4) {
+  if (blocks < 160 && all_chunks >= 4 && !p.no_split) {
     ks = (int)((200 + blocks - 1) / blocks);
     if (ks > all_chunks / 2) ks = all_chunks / 2;
     if (ks > 8) ks = 8;
@@ -665,7 +683,9 @@ bool fprop_params(const Geom& g, TileParams* p) {
   TileParams& q = *p;
   q = TileParams{};
   q.N = g.N; q.C = g.Cin; q.Ho = g.Hout; q.Wo = g.Wout; q.R = g.Cout; q.M = g.M;
-  q.kH = g.kH; q.kW = g.kW; q.flip = 0;
+  q.kH = g.kH; q.kW = g.kW;
+  q.wt0 = 0; q.wt_row = g.kW; q.wt_col = 1;
+  q.wrow = g.kH * g.kW * q.C;
   if (g.kH == 1 && g.kW == 1 && g.ph == 0 && g.pw == 0) {
     // a 1x1 window with stride s reads the s-subsampled grid: slide with stride 1 over that grid
     q.H = g.Hout; q.W = g.Wout; q.sh = 1; q.sw = 1; q.ph = 0; q.pw = 0;
@@ -693,7 +713,9 @@ bool dgrad_params(const Geom& g, TileParams* p) {
   q.N = g.N; q.C = g.Cout; q.H = g.Hout; q.W = g.Wout;
   q.Ho = g.Hin; q.Wo = g.Win; q.R = g.Cin; q.M = g.Min;
   q.kH = g.kH; q.kW = g.kW; q.sh = 1; q.sw = 1;
-  q.ph = g.kH - 1 - g.ph; q.pw = g.kW - 1 - g.pw; q.flip = 1;
+  q.ph = g.kH - 1 - g.ph; q.pw = g.kW - 1 - g.pw;
+  q.wt0 = g.kH * g.kW - 1; q.wt_row = -g.kW; q.wt_col = -1;   // rotated kernel
+  q.wrow = g.kH * g.kW * q.C;
   q.act_n_stride = g.Hout * g.Wout * g.Cout;
   q.act_h_stride = g.Wout * g.Cout;
   q.act_w_stride = g.Cout;
@@ -703,6 +725,54 @@ bool dgrad_params(const Geom& g, TileParams* p) {
   q.Wv = (q.Wo - 1) + q.kW;
   if (g.kH == 1 && g.kW == 1 && g.ph == 0 && g.pw == 0) flatten_pointwise(q, g.Min, g.Cout);
   return true;
+}
+
+// Input gradient of a strided convolution, one residue class of input positions at a time
+// (Sec. 3.2.1: dX = w'_rot (*) dZ): the positions h = sh hq + a, w = sw wq + b only receive the taps
+// i = i0 + sh ti, j = j0 + sw tj with i0 = (a + ph) mod sh, j0 = (b + pw) mod sw, and
+//   dX[n, h, w] = sum_{ti,tj} w'[i, j] . dZ[n, hq + dh0 - ti, wq + dw0 - tj],   dh0 = (a + ph - i0) / sh,
+// which is a stride-1 sweep over dZ with a (kh x kw) window, padding (kh-1-dh0, kw-1-dw0) and the taps
+// taken in reverse -- no multiplications with the zeros a dilated dZ would contain.  The result is
+// written to the class's positions of dX.
+enum ClassKind { CLASS_RUN, CLASS_NO_PIXELS, CLASS_ZERO, CLASS_UNSUPPORTED };
+ClassKind dgrad_class_params(const Geom& g, int a, int b, TileParams* p) {
+  const int Hq = a < g.Hin ? (g.Hin - a + g.sh - 1) / g.sh : 0;
+  const int Wq = b < g.Win ? (g.Win - b + g.sw - 1) / g.sw : 0;
+  if (Hq == 0 || Wq == 0) return CLASS_NO_PIXELS;
+  const int i0 = (a + g.ph) % g.sh, j0 = (b + g.pw) % g.sw;
+  const int kh = i0 < g.kH ? (g.kH - i0 + g.sh - 1) / g.sh : 0;
+  const int kw = j0 < g.kW ? (g.kW - j0 + g.sw - 1) / g.sw : 0;
+  if (kh == 0 || kw == 0) return CLASS_ZERO;   // no tap reaches these positions
+  const int dh0 = (a + g.ph - i0) / g.sh, dw0 = (b + g.pw - j0) / g.sw;
+  if (kh - 1 - dh0 < 0 || kw - 1 - dw0 < 0) return CLASS_UNSUPPORTED;
+  TileParams& q = *p;
+  q = TileParams{};
+  q.N = g.N; q.C = g.Cout; q.H = g.Hout; q.W = g.Wout;
+  q.Ho = Hq; q.Wo = Wq; q.R = g.Cin; q.M = g.N * Hq * Wq;
+  q.kH = kh; q.kW = kw; q.sh = 1; q.sw = 1;
+  q.ph = kh - 1 - dh0; q.pw = kw - 1 - dw0;
+  q.wt0 = (i0 + g.sh * (kh - 1)) * g.kW + j0 + g.sw * (kw - 1);
+  q.wt_row = -g.sh * g.kW; q.wt_col = -g.sw;
+  q.act_n_stride = g.Hout * g.Wout * g.Cout;
+  q.act_h_stride = g.Wout * g.Cout;
+  q.act_w_stride = g.Cout;
+  q.act_bytes = (unsigned)((size_t)g.M * g.Cout * 2);
+  q.wgt_bytes = (unsigned)((size_t)g.Cout * g.K * 2);
+  q.Hv = (q.Ho - 1) + q.kH;
+  q.Wv = (q.Wo - 1) + q.kW;
+  q.wrow = g.kH * g.kW * g.Cout;
+  q.no_split = 1;
+  q.out_strided = 1;
+  q.out_base = (a * g.Win + b) * g.Cin;
+  q.out_n = g.Hin * g.Win * g.Cin;
+  q.out_h = g.sh * g.Win * g.Cin;
+  q.out_w = g.sw * g.Cin;
+  return CLASS_RUN;
+}
+
+__global__ __launch_bounds__(256) void zero_fill_kernel(uint4* __restrict__ p, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
+    p[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
 }  // namespace
@@ -716,7 +786,14 @@ bool tile_fprop_supported(const Geom& g, int dtype) {
 bool tile_dgrad_supported(const Geom& g, int dtype) {
   if (dtype != CONVBN_BF16) return false;
   TileParams p;
-  return dgrad_params(g, &p) && make_plan(p).ok;
+  if (g.sh == 1 && g.sw == 1) return dgrad_params(g, &p) && make_plan(p).ok;
+  if ((size_t)g.Min * g.Cin * 2 >= OOB || g.Cin % 8) return false;
+  for (int a = 0; a < g.sh; ++a)
+    for (int b = 0; b < g.sw; ++b) {
+      const ClassKind k = dgrad_class_params(g, a, b, &p);
+      if (k == CLASS_UNSUPPORTED || (k == CLASS_RUN && !make_plan(p).ok)) return false;
+    }
+  return true;
 }
 
 size_t tile_fprop_partial_bytes(const Geom& g) {
@@ -727,6 +804,7 @@ size_t tile_fprop_partial_bytes(const Geom& g) {
 
 size_t tile_dgrad_partial_bytes(const Geom& g) {
   TileParams p;
+  if (g.sh != 1 || g.sw != 1) return 0;   // the residue-class launches do not split their sums
   if (!dgrad_params(g, &p) || !make_plan(p).ok) return 0;
   return partial_bytes(p);
 }
@@ -745,6 +823,29 @@ hipError_t launch_fprop_tile(const Geom& g, const void* x, const void* w_krsc, c
 hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, void* dx,
                              float* partials, hipStream_t st) {
   TileParams p;
+  if (g.sh != 1 || g.sw != 1) {
+    bool zero_first = false;
+    for (int a = 0; a < g.sh; ++a)
+      for (int b = 0; b < g.sw; ++b) zero_first |= dgrad_class_params(g, a, b, &p) == CLASS_ZERO;
+    if (zero_first) {   // positions no tap reaches: clear dX once, the other classes overwrite theirs
+      const size_t n16 = (size_t)g.Min * g.Cin * 2 / 16;
+      const int blocks = (int)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
+      hipLaunchKernelGGL(zero_fill_kernel, dim3(blocks), dim3(256), 0, st, (uint4*)dx, n16);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+    for (int a = 0; a < g.sh; ++a)
+      for (int b = 0; b < g.sw; ++b) {
+        if (dgrad_class_params(g, a, b, &p) != CLASS_RUN) continue;
+        const TilePlan pl = make_plan(p);
+        if (!pl.ok) return hipErrorInvalidValue;
+        p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = nullptr; p.out = (bf16_t*)dx;
+        p.part = nullptr;
+        hipError_t e = launch_plan(p, pl, st);
+        if (e != hipSuccess) return e;
+      }
+    return hipSuccess;
+  }
   dgrad_params(g, &p);
   const TilePlan pl = make_plan(p);
   if (p.ksplit > 1 && !partials) return hipErrorInvalidValue;
