@@ -24,6 +24,8 @@
 //                  the taps reversed and padding k-1-p,          weights [Cin][taps][Cout]
 #include "common.h"
 
+#include <type_traits>
+
 namespace convbn {
 
 namespace {
@@ -73,6 +75,7 @@ struct TileParams {
   int halo_stride;       // bytes per activation tile buffer
   int tab_off;           // byte offset of the per-lane copy-offset table in LDS (multi-chunk only)
   int tab_rows;          // live table rows per wave (spread * copies per step)
+  int ucap;              // copy units per activation tile buffer; unit ucap is a spare KB that takes the surplus copies
   int tile_rows;         // > 0: a pixel tile is this many whole output rows of one image (else TP consecutive pixels)
   int tiles_per_image;
   FastDiv dTpi;
@@ -169,6 +172,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   constexpr int WUNITS = Cfg::WUNITS, WSLAB = Cfg::WSLAB;
   constexpr int WPW = (WUNITS + NW - 1) / NW;  // weight copies per wave and step (surplus ones are dummies)
   constexpr bool MULTI = HPS > 0;
+  constexpr int CPS = HPS + WPW;               // copies per wave and step
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   float* biasl = reinterpret_cast<float*>(smem);               // [TRC] bias of this channel tile (first KB)
   unsigned char* wbuf = smem + 1024;                           // [NBUF] weight slabs
@@ -211,14 +215,18 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   const int lrow = lane / LPR;
   const int lgran = lane - lrow * LPR;
 
-  // per-lane byte offsets of the weight copies this wave issues every step (step part added as a scalar)
+  // the weight copies this wave issues every step: per-lane byte offsets (the step's part is added as a
+  // scalar) and LDS offsets inside a slab.  A surplus copy repeats unit u - WUNITS (same bytes, same place).
   unsigned voff_w[WPW];
+  int wu_off[WPW];
 #pragma unroll
   for (int j = 0; j < WPW; ++j) {
-    const int u = wave + NW * j;
+    int u = wave + NW * j;
+    u = u < WUNITS ? u : u - WUNITS;
     const int row = u * RPU + lrow;
-    const bool ok = u < WUNITS && row < TRC && r0 + row < p.R && lgran < GPR;
+    const bool ok = row < TRC && r0 + row < p.R && lgran < GPR;
     voff_w[j] = ok ? (unsigned)(((r0 + row) * p.wrow + lgran * 8) * 2) : OOB;
+    wu_off[j] = u * UNITB;
   }
   // byte offset (without the channel chunk) of this lane's 16 bytes of copy unit u of the activation tile
   auto halo_voff = [&](int u) -> unsigned {
@@ -237,10 +245,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     const unsigned soff = (unsigned)((wtap * p.C + chunk * CB) * 2);
     unsigned char* dst = wbuf + slot_off;
 #pragma unroll
-    for (int j = 0; j < WPW; ++j) {
-      const int u = wave + NW * j;
-      dma16(wgt_rsrc, voff_w[j], soff, u < WUNITS ? dst + u * UNITB : scratch);
-    }
+    for (int j = 0; j < WPW; ++j) dma16(wgt_rsrc, voff_w[j], soff, dst + wu_off[j]);
   };
 
   // LDS byte offsets of this lane's MFMA operands: pixel row (tap (0,0)) and weight row, k-half kb
@@ -298,18 +303,26 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     }
   }
 
-  // wave-uniform state: current step (c, tap, tj), byte offsets of its operands inside the rings, and
-  // the copy position (step it + DIST; past the end it re-fetches the last chunk, which nobody reads)
-  int c = cbeg, tap = 0, tj = 0;
-  int toff = 0;                    // (ti Wv + tj) ROWP of the current tap
-  int woff = 0;                    // ring offset of the current step's slab
-  int hslot = 0;
-  int pc = cbeg + DIST / taps, pt = DIST % taps, poff = DIST * WSLAB;
-  int ptj = pt % p.kW, pwt = p.wt0 + (pt / p.kW) * p.wt_row + ptj * p.wt_col;   // column and weight tap of the copy position
-  const int wt_next_row = p.wt_row - (p.kW - 1) * p.wt_col;
-  const int row_skip = (p.Wv - p.kW + 1) * ROWP;
+  // Per-tap tables, lane t = window position t (at most 64 taps): byte offset of the tap inside the
+  // activation tile and byte offset of its weights inside a weight row.  A step reads its entries with one
+  // lane-select each instead of tracking rows and columns in scalar registers: with one or two waves per
+  // SIMD the scalar bookkeeping of a step, not the matrix pipe, is what bounds the loop.
+  int vt_toff, vt_wt;
+  {
+    const int t = lane < taps ? lane : 0;
+    const int ti = t / p.kW, tj = t - ti * p.kW;
+    vt_toff = (ti * p.Wv + tj) * ROWP;
+    vt_wt = (p.wt0 + ti * p.wt_row + tj * p.wt_col) * p.C * 2;
+  }
+  // wave-uniform state: current step (chunk c, window position tap), offsets of its activation tile (hoff)
+  // and of the tile buffer being refilled (foff: the previous chunk's), and the copy position (step
+  // it + DIST; past the end it re-fetches the last chunk, which nobody reads).  The weight ring needs no
+  // state: the loop is unrolled NBUF times, so every step knows its slab at compile time.
+  int c = cbeg, tap = 0;
+  int hoff = 0, foff = (p.nhb - 1) * p.halo_stride;
+  const int hlimit = p.nhb * p.halo_stride;
+  int pc = cbeg + DIST / taps, pt = DIST % taps;
   unsigned char* const wlane = wbuf + aoff;
-  const unsigned char* ap = wlane;            // operands of step 0
   int bstep = 0;                              // wave-uniform offset of the current step's pixel rows
 
   bf16x8 fa[2][NCW], fb[2];
@@ -321,76 +334,83 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
 
   wait_vm<(DIST - 1) * (WPW + HPS)>();   // the activation tile of the first chunk and the slab of step 0 have landed
   block_barrier();
-  load_frags(0, ap, bstep, 0);
+  load_frags(0, wlane, bstep, 0);
 
-  for (int it = 0; it < nsteps; ++it) {
-    // ---- position of step it+1 (scalar selects only) -----------------------------------------------
-    const bool row_end = tj + 1 == p.kW;
+  auto step = [&](auto slot) {
+    constexpr int S = decltype(slot)::value;            // ring slot of this step's slab
+    constexpr int SN = (S + 1) % NBUF;                  // ... of the next step's
+    constexpr int SF = (S + NBUF - 1) % NBUF;           // ... of the one refilled now (step it + DIST)
+    // ---- position of the next step ------------------------------------------------------------------
     const bool chunk_end = tap + 1 == taps;
-    const int ntj = row_end ? 0 : tj + 1;
     const int ntap = chunk_end ? 0 : tap + 1;
-    const int ntoff = chunk_end ? 0 : toff + (row_end ? row_skip : ROWP);
-    const int nc = c + (chunk_end ? 1 : 0);
-    int nhslot = hslot + (chunk_end ? 1 : 0);
-    nhslot = nhslot == p.nhb ? 0 : nhslot;
-    const int nhoff = nhslot * p.halo_stride;
-    const int nwoff = woff + WSLAB == NBUF * WSLAB ? 0 : woff + WSLAB;
-    const unsigned char* nap = wlane + nwoff;
-    const int nbstep = nhoff + ntoff;
+    int nhoff = hoff + (chunk_end ? p.halo_stride : 0);
+    nhoff = nhoff == hlimit ? 0 : nhoff;
+    const int nbstep = nhoff + __builtin_amdgcn_readlane(vt_toff, ntap);
 
-    // offsets of this step's activation copies, fetched before the wait (dummy rows when not fetching)
+    // offsets of this step's activation copies, fetched before the wait (zero-fill rows when not fetching)
     unsigned hv[HPS > 0 ? HPS : 1];
-    bool hlive = false;
-    int fslot = 0;
+    int ku = 0;                                         // first copy unit of this step
     if (MULTI) {
-      hlive = tap < p.spread && c + p.nhb - 1 < nchunks;
+      const bool hlive = tap < p.spread && c + p.nhb - 1 < nchunks;
       const int krow = hlive ? tap * HPS : p.tab_rows;
       const unsigned* trow = tab_lane + krow * TROW;
 #pragma unroll
       for (int j = 0; j < HPS; ++j) hv[j] = trow[j * TROW];
-      fslot = hslot + p.nhb - 1;
-      fslot = fslot >= p.nhb ? fslot - p.nhb : fslot;
+      ku = wave + NW * krow;
     }
 
     wait_vm<(DIST - 2) * (WPW + HPS)>();
-    block_barrier();   // step it+1's data is resident for every wave; step it-1's slab is free
+    block_barrier();   // the next step's data is resident for every wave; the previous step's slab is free
 
-    // ---- copies: activation units of the chunk nhb-1 ahead, weight slab of step it+DIST -----------
-    if (MULTI) {
-      const unsigned hsoff = (unsigned)((c + p.nhb - 1) * CB * 2);
-      unsigned char* dst = halo + fslot * p.halo_stride;
-#pragma unroll
-      for (int j = 0; j < HPS; ++j) {
-        const int u = wave + NW * (tap * HPS + j);
-        dma16(act_rsrc, hv[j], hsoff, (hlive && u < hunits) ? dst + u * UNITB : scratch);
+    // ---- copies (activation units of the chunk nhb-1 ahead, weight slab of step it+DIST) are issued
+    // between the multiplies: a wave stalls on every copy it hands to the memory pipe, and the matrix
+    // pipe keeps working through those stalls only if it has been fed first.  Units past the tile go to
+    // the spare KB behind it (unit ucap), so no copy needs a branch or a select.
+    const unsigned hsoff = (unsigned)((c + p.nhb - 1) * CB * 2);
+    unsigned char* const hdst = halo + foff;
+    const unsigned wsoff = (unsigned)(__builtin_amdgcn_readlane(vt_wt, pt) + min(pc, nchunks - 1) * (CB * 2));
+    auto issue_copy = [&](int idx) {   // copy idx of this step: HPS activation units, then WPW weight units
+      if (idx < HPS) {
+        dma16(act_rsrc, hv[idx < HPS ? idx : 0], hsoff, hdst + min(ku + NW * idx, p.ucap) * UNITB);
+      } else {
+        const int j = idx - HPS < WPW ? idx - HPS : 0;
+        dma16(wgt_rsrc, voff_w[j], wsoff, wbuf + SF * WSLAB + wu_off[j]);
       }
-    }
-    issue_weights(min(pc, nchunks - 1), pwt, poff);
-    const bool pwrap = pt + 1 == taps, prow = ptj + 1 == p.kW;
-    pwt = pwrap ? p.wt0 : pwt + (prow ? wt_next_row : p.wt_col);
-    ptj = prow ? 0 : ptj + 1;
+    };
+    const bool pwrap = pt + 1 == taps;
     pt = pwrap ? 0 : pt + 1;
     pc += pwrap ? 1 : 0;
-    poff = poff + WSLAB == NBUF * WSLAB ? 0 : poff + WSLAB;
 
-    // ---- KK k-steps: operands of k-step kk+1 (or of the next step's first) load while kk multiplies
+    // ---- KK k-steps: operands of k-step kk+1 (or of the next step's first) load while kk multiplies.
+    // The scheduling barriers pin the order written here: operand reads of the following k-step, one
+    // multiply, this k-step's share of the copies, the remaining multiplies.
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      if (kk + 1 < KK) load_frags((kk + 1) & 1, ap, bstep, kk + 1);
-      else load_frags((kk + 1) & 1, nap, nbstep, 0);
+      if (kk + 1 < KK) load_frags((kk + 1) & 1, wlane + S * WSLAB, bstep, kk + 1);
+      else load_frags((kk + 1) & 1, wlane + SN * WSLAB, nbstep, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][0], fb[kk & 1], acc[0], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int r = 0; r < NCW; ++r)
+      for (int idx = (kk * CPS) / KK; idx < ((kk + 1) * CPS) / KK; ++idx) issue_copy(idx);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int r = 1; r < NCW; ++r)
         acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][r], fb[kk & 1], acc[r], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    // keep the order written above: the NCH+1 operand reads of the following k-step go out before
-    // the NCH multiplies of the current one, so their latency hides behind the matrix pipe
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      __builtin_amdgcn_sched_group_barrier(0x100, NCW + 1, 0);   // LDS reads
-      __builtin_amdgcn_sched_group_barrier(0x008, NCW, 0);       // MFMA
-    }
-    c = nc; tap = ntap; tj = ntj; toff = ntoff; hslot = nhslot; woff = nwoff;
-    ap = nap; bstep = nbstep;
+    c += chunk_end ? 1 : 0;
+    tap = ntap;
+    foff = chunk_end ? hoff : foff;
+    hoff = nhoff;
+    bstep = nbstep;
+  };
+  for (int left = nsteps;;) {
+    step(std::integral_constant<int, 0>{}); if (--left == 0) break;
+    step(std::integral_constant<int, 1>{}); if (--left == 0) break;
+    step(std::integral_constant<int, 2>{}); if (--left == 0) break;
+    step(std::integral_constant<int, 3>{}); if (--left == 0) break;
+    if constexpr (NBUF == 5) { step(std::integral_constant<int, 4>{}); if (--left == 0) break; }
   }
   wait_vm<0>();   // trailing copies must not outlive the workgroup's LDS
 
@@ -562,7 +582,8 @@ size_t plan_lds_cfg(TileParams& p, int nw, int nwc, bool rows) {
   }
   p.nhb = nhb; p.hps = hps; p.spread = spread;
   p.tab_rows = spread * hps;
-  p.halo_stride = hunits * Cfg::UNITB + 64;
+  p.ucap = hunits;
+  p.halo_stride = (hunits + (nchunks > 1 ? 1 : 0)) * Cfg::UNITB + 64;
   size_t lds = 1024 + (size_t)Cfg::NBUF * Cfg::WSLAB + 1024 + (size_t)nhb * p.halo_stride;
   p.tab_off = (int)lds;
   if (nhb > 1) lds += (size_t)(p.tab_rows + hps) * nw * 256;
@@ -684,6 +705,7 @@ bool fprop_params(const Geom& g, TileParams* p) {
   q = TileParams{};
   q.N = g.N; q.C = g.Cin; q.Ho = g.Hout; q.Wo = g.Wout; q.R = g.Cout; q.M = g.M;
   q.kH = g.kH; q.kW = g.kW;
+  if (g.kH * g.kW > 64) return false;   // the kernel keeps one table entry per tap in a lane
   q.wt0 = 0; q.wt_row = g.kW; q.wt_col = 1;
   q.wrow = g.kH * g.kW * q.C;
   if (g.kH == 1 && g.kW == 1 && g.ph == 0 && g.pw == 0) {
@@ -714,6 +736,7 @@ bool dgrad_params(const Geom& g, TileParams* p) {
   q.Ho = g.Hin; q.Wo = g.Win; q.R = g.Cin; q.M = g.Min;
   q.kH = g.kH; q.kW = g.kW; q.sh = 1; q.sw = 1;
   q.ph = g.kH - 1 - g.ph; q.pw = g.kW - 1 - g.pw;
+  if (g.kH * g.kW > 64) return false;
   q.wt0 = g.kH * g.kW - 1; q.wt_row = -g.kW; q.wt_col = -1;   // rotated kernel
   q.wrow = g.kH * g.kW * q.C;
   q.act_n_stride = g.Hout * g.Wout * g.Cout;
@@ -744,7 +767,7 @@ ClassKind dgrad_class_params(const Geom& g, int a, int b, TileParams* p) {
   const int kw = j0 < g.kW ? (g.kW - j0 + g.sw - 1) / g.sw : 0;
   if (kh == 0 || kw == 0) return CLASS_ZERO;   // no tap reaches these positions
   const int dh0 = (a + g.ph - i0) / g.sh, dw0 = (b + g.pw - j0) / g.sw;
-  if (kh - 1 - dh0 < 0 || kw - 1 - dw0 < 0) return CLASS_UNSUPPORTED;
+  if (kh - 1 - dh0 < 0 || kw - 1 - dw0 < 0 || kh * kw > 64) return CLASS_UNSUPPORTED;
   TileParams& q = *p;
   q = TileParams{};
   q.N = g.N; q.C = g.Cout; q.H = g.Hout; q.W = g.Wout;
