@@ -314,16 +314,49 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     vt_toff = (ti * p.Wv + tj) * ROWP;
     vt_wt = (p.wt0 + ti * p.wt_row + tj * p.wt_col) * p.C * 2;
   }
-  // wave-uniform state: current step (chunk c, window position tap), offsets of its activation tile (hoff)
-  // and of the tile buffer being refilled (foff: the previous chunk's), and the copy position (step
-  // it + DIST; past the end it re-fetches the last chunk, which nobody reads).  The weight ring needs no
-  // state: the loop is unrolled NBUF times, so every step knows its slab at compile time.
-  int c = cbeg, tap = 0;
-  int hoff = 0, foff = (p.nhb - 1) * p.halo_stride;
+  // Wave-uniform bookkeeping.  A position is (window position, chunk, offset of the chunk's activation tile
+  // buffer, offset of the buffer being refilled = the previous chunk's).  The weight ring needs no state: the
+  // loop is unrolled NBUF times, so every step knows its slab at compile time.  Everything a step needs
+  // from the scalar unit -- its operand offsets and the descriptors of its copies -- is computed during
+  // the PREVIOUS step, in the shadow of that step's multiplies.
+  struct Pos { int tap, c, hoff, foff; };
   const int hlimit = p.nhb * p.halo_stride;
-  int pc = cbeg + DIST / taps, pt = DIST % taps;
+  auto advance = [&](const Pos& q) {
+    const bool e = q.tap + 1 == taps;
+    const int h = q.hoff + (e ? p.halo_stride : 0);
+    return Pos{e ? 0 : q.tap + 1, q.c + (e ? 1 : 0), h == hlimit ? 0 : h, e ? q.hoff : q.foff};
+  };
+  auto bstep_of = [&](const Pos& q) { return q.hoff + __builtin_amdgcn_readlane(vt_toff, q.tap); };
+  // copies of one step: HPS activation units of the chunk nhb-1 ahead (per-lane offsets from the LDS table,
+  // zero-fill rows when there is nothing to fetch) and the weight slab of the step DIST ahead
+  struct Copies { unsigned hv[HPS > 0 ? HPS : 1]; int ku; unsigned hsoff; int hbase; unsigned wsoff; };
+  auto act_copies = [&](const Pos& q, Copies& d) {
+    if (MULTI) {
+      const bool hlive = q.tap < p.spread && q.c + p.nhb - 1 < nchunks;
+      const int krow = hlive ? q.tap * HPS : p.tab_rows;
+      const unsigned* trow = tab_lane + krow * TROW;
+#pragma unroll
+      for (int j = 0; j < HPS; ++j) d.hv[j] = trow[j * TROW];
+      d.ku = wave + NW * krow;
+      d.hsoff = (unsigned)((q.c + p.nhb - 1) * CB * 2);
+      d.hbase = q.foff;
+    }
+  };
+  int pc = cbeg + DIST / taps, pt = DIST % taps;   // copy position: step it + DIST (past the end it re-fetches
+  auto wgt_copies = [&](Copies& d) {               // the last chunk, which nobody reads)
+    d.wsoff = (unsigned)__builtin_amdgcn_readfirstlane(__builtin_amdgcn_readlane(vt_wt, pt) + min(pc, nchunks - 1) * (CB * 2));
+    const bool pwrap = pt + 1 == taps;
+    pt = pwrap ? 0 : pt + 1;
+    pc += pwrap ? 1 : 0;
+  };
+
+  Pos P{0, cbeg, 0, (p.nhb - 1) * p.halo_stride};
+  Pos Pn = advance(P);
+  int bstep = 0, nbstep = bstep_of(Pn);           // offsets of the current / next step's pixel rows
+  Copies cp;
+  act_copies(P, cp);
+  wgt_copies(cp);
   unsigned char* const wlane = wbuf + aoff;
-  int bstep = 0;                              // wave-uniform offset of the current step's pixel rows
 
   bf16x8 fa[2][NCW], fb[2];
   auto load_frags = [&](int buf, const unsigned char* a, int bs, int kk) {
@@ -340,50 +373,26 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     constexpr int S = decltype(slot)::value;            // ring slot of this step's slab
     constexpr int SN = (S + 1) % NBUF;                  // ... of the next step's
     constexpr int SF = (S + NBUF - 1) % NBUF;           // ... of the one refilled now (step it + DIST)
-    // ---- position of the next step ------------------------------------------------------------------
-    const bool chunk_end = tap + 1 == taps;
-    const int ntap = chunk_end ? 0 : tap + 1;
-    int nhoff = hoff + (chunk_end ? p.halo_stride : 0);
-    nhoff = nhoff == hlimit ? 0 : nhoff;
-    const int nbstep = nhoff + __builtin_amdgcn_readlane(vt_toff, ntap);
-
-    // offsets of this step's activation copies, fetched before the wait (zero-fill rows when not fetching)
-    unsigned hv[HPS > 0 ? HPS : 1];
-    int ku = 0;                                         // first copy unit of this step
-    if (MULTI) {
-      const bool hlive = tap < p.spread && c + p.nhb - 1 < nchunks;
-      const int krow = hlive ? tap * HPS : p.tab_rows;
-      const unsigned* trow = tab_lane + krow * TROW;
-#pragma unroll
-      for (int j = 0; j < HPS; ++j) hv[j] = trow[j * TROW];
-      ku = wave + NW * krow;
-    }
-
     wait_vm<(DIST - 2) * (WPW + HPS)>();
     block_barrier();   // the next step's data is resident for every wave; the previous step's slab is free
 
-    // ---- copies (activation units of the chunk nhb-1 ahead, weight slab of step it+DIST) are issued
-    // between the multiplies: a wave stalls on every copy it hands to the memory pipe, and the matrix
-    // pipe keeps working through those stalls only if it has been fed first.  Units past the tile go to
-    // the spare KB behind it (unit ucap), so no copy needs a branch or a select.
-    const unsigned hsoff = (unsigned)((c + p.nhb - 1) * CB * 2);
-    unsigned char* const hdst = halo + foff;
-    const unsigned wsoff = (unsigned)(__builtin_amdgcn_readlane(vt_wt, pt) + min(pc, nchunks - 1) * (CB * 2));
+    // Copies are issued between the multiplies: a wave stalls on every copy it hands to the memory pipe,
+    // and the matrix pipe keeps working through those stalls only if it has been fed first.  Units past
+    // the tile go to the spare KB behind it (unit ucap), so no copy needs a branch or a select.
     auto issue_copy = [&](int idx) {   // copy idx of this step: HPS activation units, then WPW weight units
       if (idx < HPS) {
-        dma16(act_rsrc, hv[idx < HPS ? idx : 0], hsoff, hdst + min(ku + NW * idx, p.ucap) * UNITB);
+        dma16(act_rsrc, cp.hv[idx < HPS ? idx : 0], cp.hsoff, halo + cp.hbase + min(cp.ku + NW * idx, p.ucap) * UNITB);
       } else {
         const int j = idx - HPS < WPW ? idx - HPS : 0;
-        dma16(wgt_rsrc, voff_w[j], wsoff, wbuf + SF * WSLAB + wu_off[j]);
+        dma16(wgt_rsrc, voff_w[j], cp.wsoff, wbuf + SF * WSLAB + wu_off[j]);
       }
     };
-    const bool pwrap = pt + 1 == taps;
-    pt = pwrap ? 0 : pt + 1;
-    pc += pwrap ? 1 : 0;
-
-    // ---- KK k-steps: operands of k-step kk+1 (or of the next step's first) load while kk multiplies.
-    // The scheduling barriers pin the order written here: operand reads of the following k-step, one
-    // multiply, this k-step's share of the copies, the remaining multiplies.
+    // KK k-steps: operands of k-step kk+1 (or of the next step's first) load while kk multiplies.  The
+    // scheduling barriers pin the order written here: operand reads of the following k-step, one multiply,
+    // this k-step's share of the copies, the remaining multiplies, a share of the next step's bookkeeping.
+    Pos P2 = Pn;
+    int n2bstep = 0;
+    Copies ncp = cp;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       if (kk + 1 < KK) load_frags((kk + 1) & 1, wlane + S * WSLAB, bstep, kk + 1);
@@ -398,12 +407,14 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
       for (int r = 1; r < NCW; ++r)
         acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][r], fb[kk & 1], acc[r], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
+      if (kk == 0) { P2 = advance(Pn); n2bstep = bstep_of(P2); }
+      if (kk == (KK > 2 ? 1 : 0)) act_copies(Pn, ncp);
+      if (kk == KK - 1) wgt_copies(ncp);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    c += chunk_end ? 1 : 0;
-    tap = ntap;
-    foff = chunk_end ? hoff : foff;
-    hoff = nhoff;
-    bstep = nbstep;
+    P = Pn; Pn = P2;
+    bstep = nbstep; nbstep = n2bstep;
+    cp = ncp;
   };
   for (int left = nsteps;;) {
     step(std::integral_constant<int, 0>{}); if (--left == 0) break;
