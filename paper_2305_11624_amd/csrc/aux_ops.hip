@@ -118,6 +118,84 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const T* __restrict__ 
   }
 }
 
+// bf16, C % 8 == 0: a thread owns eight channels of one pixel (16-byte accesses, no 64-bit divisions).
+__global__ __launch_bounds__(256) void maxpool_fwd_bf16x8_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
+                                                                 unsigned char* __restrict__ idx, int N, int H, int W,
+                                                                 int C8, int Ho, int Wo) {
+  const unsigned total = (unsigned)N * Ho * Wo * C8;
+  for (unsigned i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+    const unsigned c8 = i % C8;
+    unsigned r = i / C8;
+    const int wo = (int)(r % Wo); r /= Wo;
+    const int ho = (int)(r % Ho);
+    const int n = (int)(r / Ho);
+    float best[8];
+    int bi[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { best[e] = -INFINITY; bi[e] = 0; }
+#pragma unroll
+    for (int di = 0; di < 3; ++di) {
+      const int h = ho * 2 + di - 1;
+      if (h < 0 || h >= H) continue;
+#pragma unroll
+      for (int dj = 0; dj < 3; ++dj) {
+        const int w = wo * 2 + dj - 1;
+        if (w < 0 || w >= W) continue;
+        const uint4 v = *reinterpret_cast<const uint4*>(x + ((((size_t)n * H + h) * W + w) * C8 + c8) * 8);
+        const float f[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                            bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (f[e] > best[e]) { best[e] = f[e]; bi[e] = di * 3 + dj; }
+      }
+    }
+    // the maximum is one of the inputs: packing it back to bf16 is exact
+    *reinterpret_cast<uint4*>(y + (size_t)i * 8) =
+        make_uint4(pack_bf16x2(best[0], best[1]), pack_bf16x2(best[2], best[3]), pack_bf16x2(best[4], best[5]),
+                   pack_bf16x2(best[6], best[7]));
+    *reinterpret_cast<uint2*>(idx + (size_t)i * 8) =
+        make_uint2((unsigned)bi[0] | (unsigned)bi[1] << 8 | (unsigned)bi[2] << 16 | (unsigned)bi[3] << 24,
+                   (unsigned)bi[4] | (unsigned)bi[5] << 8 | (unsigned)bi[6] << 16 | (unsigned)bi[7] << 24);
+  }
+}
+
+__global__ __launch_bounds__(256) void maxpool_bwd_bf16x8_kernel(const bf16_t* __restrict__ dy,
+                                                                 const unsigned char* __restrict__ idx,
+                                                                 bf16_t* __restrict__ dx, int N, int H, int W, int C8,
+                                                                 int Ho, int Wo) {
+  const unsigned total = (unsigned)N * H * W * C8;
+  for (unsigned i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+    const unsigned c8 = i % C8;
+    unsigned r = i / C8;
+    const int w = (int)(r % W); r /= W;
+    const int h = (int)(r % H);
+    const int n = (int)(r / H);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // windows ho with ho*2 - 1 <= h <= ho*2 + 1
+    for (int ho = h / 2; ho <= (h + 1) / 2; ++ho) {
+      if (ho >= Ho) continue;
+      const int di = h - (ho * 2 - 1);
+      for (int wo = w / 2; wo <= (w + 1) / 2; ++wo) {
+        if (wo >= Wo) continue;
+        const unsigned code = (unsigned)(di * 3 + (w - (wo * 2 - 1)));
+        const size_t o = ((((size_t)n * Ho + ho) * Wo + wo) * C8 + c8) * 8;
+        const uint2 k = *reinterpret_cast<const uint2*>(idx + o);
+        const uint4 v = *reinterpret_cast<const uint4*>(dy + o);
+        const float f[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                            bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const unsigned ke = ((e < 4 ? k.x : k.y) >> (8 * (e & 3))) & 0xffu;
+          if (ke == code) acc[e] += f[e];
+        }
+      }
+    }
+    *reinterpret_cast<uint4*>(dx + (size_t)i * 8) =
+        make_uint4(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]), pack_bf16x2(acc[4], acc[5]),
+                   pack_bf16x2(acc[6], acc[7]));
+  }
+}
+
 int blocks_for(size_t work) {
   const size_t b = (work + 255) / 256;
   return (int)(b < 8192 ? (b ? b : 1) : 8192);
@@ -142,7 +220,10 @@ hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, unsigned char* 
                               hipStream_t st) {
   const int Ho = (H + 2 - 3) / 2 + 1, Wo = (W + 2 - 3) / 2 + 1;
   const size_t total = (size_t)N * Ho * Wo * C;
-  if (dtype == CONVBN_BF16)
+  if (dtype == CONVBN_BF16 && C % 8 == 0 && total / 8 < 0xffffffffull && (size_t)N * H * W * C / 8 < 0xffffffffull)
+    hipLaunchKernelGGL(maxpool_fwd_bf16x8_kernel, dim3(blocks_for(total / 8)), dim3(256), 0, st, (const bf16_t*)x,
+                       (bf16_t*)y, idx, N, H, W, C / 8, Ho, Wo);
+  else if (dtype == CONVBN_BF16)
     hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const bf16_t*)x,
                        (bf16_t*)y, idx, N, H, W, C, Ho, Wo);
   else
@@ -155,7 +236,10 @@ hipError_t launch_maxpool_bwd(int dtype, const void* dy, const unsigned char* id
                               int C, hipStream_t st) {
   const int Ho = (H + 2 - 3) / 2 + 1, Wo = (W + 2 - 3) / 2 + 1;
   const size_t total = (size_t)N * H * W * C;
-  if (dtype == CONVBN_BF16)
+  if (dtype == CONVBN_BF16 && C % 8 == 0 && total / 8 < 0xffffffffull)
+    hipLaunchKernelGGL(maxpool_bwd_bf16x8_kernel, dim3(blocks_for(total / 8)), dim3(256), 0, st, (const bf16_t*)dy,
+                       idx, (bf16_t*)dx, N, H, W, C / 8, Ho, Wo);
+  else if (dtype == CONVBN_BF16)
     hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const bf16_t*)dy,
                        idx, (bf16_t*)dx, N, H, W, C, Ho, Wo);
   else

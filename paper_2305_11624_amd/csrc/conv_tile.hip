@@ -578,9 +578,9 @@ size_t plan_lds_cfg(TileParams& p, int nw, int nwc, bool rows) {
   int nhb, spread, hps;
   if (nchunks == 1) { nhb = 1; spread = 0; hps = 0; }
   else {
-    // 1x1 windows with several chunks: measured faster here than in the generic implicit-GEMM kernel
-    // only for very long pixel ranges with few output channels and for very short pixel ranges
-    if (taps == 1 && !((p.M >= 50000 && p.R <= 64) || p.M <= 2048)) return 0;
+    // 1x1 windows with several chunks: the generic implicit-GEMM kernel is only faster for mid-sized pixel
+    // counts with many more output than input channels (many channel tiles re-reading a short reduction)
+    if (taps == 1 && p.M > 2048 && p.M <= 8192 && p.R >= 2 * p.C) return 0;
     // copies per wave and step: a power of two (the kernel is instantiated for 1, 2, 4, 8), spread over
     // as few steps as the pipeline leaves between two chunks
     const int max_spread = taps == 1 ? 1 : taps - Cfg::DIST + 1;
