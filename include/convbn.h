@@ -107,7 +107,10 @@ convbn_status convbn_tune_fwd(const convbn_desc *desc, const void *x, const void
  *        w_folded (nullable: the buffer convbn_tune_fwd filled; NULL = fold again
  *        into the workspace)
  *   out: dx (nullable = skip the input-gradient pass), dW, db (must be NULL exactly
- *        when b is NULL), dgamma, dbeta
+ *        when b is NULL), dgamma, dbeta.
+ *        Input gradient only (the frozen-model use of Sec. 4.3): dW, db, dgamma and
+ *        dbeta all NULL and dx given -- the weight-gradient and fold-back passes are
+ *        skipped.  Any other mix of NULLs is CONVBN_ERR_NULL.
  */
 convbn_status convbn_tune_bwd(const convbn_desc *desc, const void *x, const void *W,
                               const float *b, const float *gamma, const float *mean,
@@ -127,7 +130,8 @@ convbn_status convbn_eval_fwd(const convbn_desc *desc, const void *x, const void
  *   dY = s dZ;  dgamma = sum dZ (Y - mu)/sqrt(var+eps);  dbeta = sum dZ;
  *   dX = w_rot (*) dY;  dW = dY (.) X;  db = sum dY.
  *   in : x, W, b (nullable; only its NULL-ness matters), gamma, mean, var, y_saved, dz
- *   out: dx (nullable), dW, db (NULL exactly when b is NULL), dgamma, dbeta */
+ *   out: dx (nullable), dW, db (NULL exactly when b is NULL), dgamma, dbeta;
+ *        or dx alone (dW, db, dgamma, dbeta all NULL), as for convbn_tune_bwd */
 convbn_status convbn_eval_bwd(const convbn_desc *desc, const void *x, const void *W,
                               const float *b, const float *gamma, const float *mean,
                               const float *var, const void *y_saved, const void *dz, void *dx,

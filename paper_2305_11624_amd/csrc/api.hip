@@ -335,9 +335,15 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
   convbn_status s = make_geom(desc, &g);
   if (s != CONVBN_OK) return s;
   REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
-  REQUIRE_PTR(dz); REQUIRE_PTR(dW); REQUIRE_PTR(dgamma); REQUIRE_PTR(dbeta);
+  REQUIRE_PTR(dz);
   OPTIONAL_PTR(b); OPTIONAL_PTR(w_folded); OPTIONAL_PTR(dx); OPTIONAL_PTR(db);
-  if ((b == nullptr) != (db == nullptr))
+  OPTIONAL_PTR(dW); OPTIONAL_PTR(dgamma); OPTIONAL_PTR(dbeta);
+  const bool params = dW != nullptr;   // false: input gradient only (Sec. 4.3's adversarial-example use)
+  if (!params && (dgamma || dbeta || db || !dx))
+    return fail(CONVBN_ERR_NULL, "without dW only dx may be asked for (dgamma, dbeta, db NULL, dx given)");
+  if (params && (!dgamma || !dbeta))
+    return fail(CONVBN_ERR_NULL, "dgamma and dbeta are required together with dW");
+  if (params && (b == nullptr) != (db == nullptr))
     return fail(CONVBN_ERR_NULL, "db must be given exactly when b is given");
   const int dt = desc->dtype;
   s = check_ws(carve_tune_bwd(g, dt, nullptr).bytes, ws, ws_bytes);
@@ -352,6 +358,7 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
     }
     LAUNCH(run_dgrad(g, dt, dz, wt, dx, w.conv_scratch, st));   // dX = w'_rot (*) dZ
   }
+  if (!params) return CONVBN_OK;
   LAUNCH(run_wgrad(g, dt, x, dz, w.dwf_part, w.r_part, w.wgrad_scratch, st));   // dw' = dZ (.) X and r = sum dZ (fp32 partials)
   LAUNCH(launch_fold_back(g, dt, w.dwf_part, w.nsplit, w.r_part, w.nrpart, W, b, gamma, mean, var, 0,
                           dW, db, dgamma, dbeta, st));
@@ -386,9 +393,15 @@ convbn_status convbn_eval_bwd(const convbn_desc* desc, const void* x, const void
   convbn_status s = make_geom(desc, &g);
   if (s != CONVBN_OK) return s;
   REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
-  REQUIRE_PTR(y_saved); REQUIRE_PTR(dz); REQUIRE_PTR(dW); REQUIRE_PTR(dgamma); REQUIRE_PTR(dbeta);
+  REQUIRE_PTR(y_saved); REQUIRE_PTR(dz);
   OPTIONAL_PTR(b); OPTIONAL_PTR(dx); OPTIONAL_PTR(db);
-  if ((b == nullptr) != (db == nullptr))
+  OPTIONAL_PTR(dW); OPTIONAL_PTR(dgamma); OPTIONAL_PTR(dbeta);
+  const bool params = dW != nullptr;   // false: input gradient only
+  if (!params && (dgamma || dbeta || db || !dx))
+    return fail(CONVBN_ERR_NULL, "without dW only dx may be asked for (dgamma, dbeta, db NULL, dx given)");
+  if (params && (!dgamma || !dbeta))
+    return fail(CONVBN_ERR_NULL, "dgamma and dbeta are required together with dW");
+  if (params && (b == nullptr) != (db == nullptr))
     return fail(CONVBN_ERR_NULL, "db must be given exactly when b is given");
   const int dt = desc->dtype;
   s = check_ws(carve_eval_bwd(g, dt, nullptr).bytes, ws, ws_bytes);
@@ -397,13 +410,14 @@ convbn_status convbn_eval_bwd(const convbn_desc* desc, const void* x, const void
   hipStream_t st = static_cast<hipStream_t>(stream);
   // dY = s dZ, partial per-channel sums of dZ and dZ (Y-mu)/sqrt(var+eps)
   LAUNCH(launch_bn_bwd(g, dt, dz, y_saved, gamma, mean, var, w.dy, w.bn_part, st));
-  LAUNCH(launch_bn_bwd_finalize(g, w.bn_part, w.nparts, gamma, var, dgamma, dbeta, db, st));
+  if (params) LAUNCH(launch_bn_bwd_finalize(g, w.bn_part, w.nparts, gamma, var, dgamma, dbeta, db, st));
   if (dx) {
     // the input-gradient pass reads the weight as [Cin][kH][kW][Cout]
     LAUNCH(launch_fold(g, dt, W, nullptr, nullptr, nullptr, nullptr, nullptr, 1, nullptr, w.w_crsk,
                        nullptr, st));
     LAUNCH(run_dgrad(g, dt, w.dy, w.w_crsk, dx, w.conv_scratch, st));   // dX = w_rot (*) dY
   }
+  if (!params) return CONVBN_OK;
   LAUNCH(run_wgrad(g, dt, x, w.dy, w.dwf_part, nullptr, w.wgrad_scratch, st));   // dW = dY (.) X
   LAUNCH(launch_fold_back(g, dt, w.dwf_part, w.nsplit, nullptr, 0, W, nullptr, nullptr, nullptr,
                           nullptr, 1, dW, nullptr, nullptr, nullptr, st));

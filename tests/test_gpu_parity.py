@@ -39,6 +39,7 @@ F32_SHAPES = [
     BlockShape("f32_1x1", 3, 6, 5, 7, 10, 1, 1, 0, "f32", 22),
     BlockShape("f32_7x7", 1, 3, 20, 20, 8, 7, 2, 3, "f32", 23),
     BlockShape("f32_nopad", 2, 4, 8, 8, 4, 3, 1, 0, "f32", 24),
+    BlockShape("f32_linear_bn", 33, 20, 1, 1, 12, 1, 1, 0, "f32", 25),
 ]
 
 
@@ -59,6 +60,8 @@ BF16_SHAPES = [
     BlockShape("b_3x3_s2", 2, 32, 15, 15, 40, 3, 2, 1, "bf16", 35),
     BlockShape("b_7x7_cin8", 1, 8, 30, 30, 16, 7, 2, 3, "bf16", 36),
     BlockShape("b_small7", 4, 128, 7, 7, 160, 3, 1, 1, "bf16", 37),
+    # a Linear layer followed by BatchNorm is the 1x1 block on a 1x1 image (Sec. 3.2.1, closing remark)
+    BlockShape("b_linear_bn", 200, 512, 1, 1, 264, 1, 1, 0, "bf16", 44),
     # direct path (channels not multiples of 8), incl. a stem-like 7x7/2 with Cin=3
     BlockShape("b_stem", 2, 3, 32, 32, 64, 7, 2, 3, "bf16", 38),
     BlockShape("b_odd_ch", 2, 12, 9, 9, 20, 3, 1, 1, "bf16", 39),
@@ -111,3 +114,34 @@ def test_tune_matches_eval_on_gpu():
     for k in ("Z", "dX", "dW", "dgamma", "dbeta"):
         ref = e[k].numpy()
         compare({k: t[k]}, {k: ref}, "bf16", keys=(k,), tag=f"tune-vs-eval/{k}")
+
+
+@pytest.mark.parametrize("mode", ["tune", "eval"])
+@pytest.mark.parametrize("shape", [BlockShape("b_dxonly", 2, 64, 14, 14, 72, 3, 1, 1, "bf16", 45),
+                                   BlockShape("f32_dxonly", 2, 5, 9, 8, 7, 3, 2, 1, "f32", 46)],
+                         ids=lambda s: s.name)
+def test_input_gradient_only(shape, mode):
+    """Backward for the input alone (frozen model, Sec. 4.3): dW, dgamma, dbeta NULL.  dX equals the full
+    backward's bit for bit; any other mix of NULL outputs is refused before anything is launched."""
+    from paper_2305_11624_amd import binding as B
+    from paper_2305_11624_amd.runner import BlockRun
+    inp = synth.make_inputs(shape)
+    ref = oracle_block(inp)
+    full = BlockRun(inp, mode=mode, poison=True)
+    full.step()
+    r = BlockRun(inp, mode=mode, poison=True)
+    r.forward()
+    fn = B.convbn_tune_bwd if mode == "tune" else B.convbn_eval_bwd
+    saved = r.w_folded if mode == "tune" else r.y_saved
+    fn(r.desc, r.x, r.W, None, r.gamma, r.mean, r.var, saved, r.dz, r.dx, None, None, None, None, r.ws_bwd)
+    torch.cuda.synchronize()
+    assert torch.equal(r.dx, full.dx)
+    compare({"dX": B.act_from_device(r.dx)}, ref, shape.dtype, keys=("dX",), tag=f"{shape.name}/{mode}/dx-only")
+    # refused mixes: dW without dgamma, dgamma without dW, nothing at all
+    before = r.dx.clone()
+    for dx, dW, dg, dbt in ((r.dx, r.dW, None, r.dbeta), (r.dx, None, r.dgamma, None), (None, None, None, None)):
+        st = fn(r.desc, r.x, r.W, None, r.gamma, r.mean, r.var, saved, r.dz, dx, dW, None, dg, dbt, r.ws_bwd,
+                check=False)
+        assert st == B.ERR_NULL, st
+    torch.cuda.synchronize()
+    assert torch.equal(r.dx, before)
