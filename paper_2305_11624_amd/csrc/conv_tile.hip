@@ -148,15 +148,17 @@ template <int NCH, int CB> struct TileCfg {
 // activation tile is fetched once up front).
 //
 // Pipeline.  A "step" is one tap of one channel chunk (KK x NCH MFMAs per wave).  Every step each
-// wave issues exactly HPS + WPW copies: HPS 1 KB units of a future chunk's activation tile (dummies
-// into a scratch KB when there is nothing to fetch) and its share of the weight slab of step
+// wave issues exactly HPS + WPW copies: HPS 1 KB units of a future chunk's activation tile (zero-fill
+// copies into a spare KB when there is nothing to fetch) and its share of the weight slab of step
 // it+DIST.  Copies complete in issue order, so "at most DIST-2 steps' worth outstanding" means that
 // everything issued DIST-1 or more steps ago has landed, i.e. the data of steps <= it+1.  The MFMA
 // operands are double-buffered in registers one k-step ahead; only the last k-step of a step reads
 // the next step's LDS data, which is why step it+1 must be resident at the barrier of step it and
 // why the slab written during step it is the one of step it-1 (= it+DIST modulo the ring).
-// The activation tile has nhb buffers: 1 (single chunk), 2 (the next chunk is fetched during the first
-// `spread` steps of the current one) or NBUF (1x1 windows: one step per chunk, fetched DIST ahead).
+// The activation tile has nhb buffers: 1 (single chunk) or a ring -- the tile of chunk c + nhb - 1 is
+// fetched during the first `spread` steps of chunk c and has to land DIST - 1 steps before its first
+// step, so spread <= (nhb - 1) taps - DIST + 1: two buffers for windows of at least DIST taps, more
+// for fewer (1x1 windows: NBUF buffers, one step per chunk).
 // The step loop is branch-free apart from its back edge: all per-step decisions are scalar selects,
 // and the per-lane copy offsets of the activation tile come from a table in LDS built once per
 // workgroup (row k of wave w = copy unit w + NW k; rows past the tile hold the zero-fill offset).
@@ -279,7 +281,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   if (MULTI) {
     for (int k = 0; k < p.tab_rows + HPS; ++k) tab_lane[k * TROW] = k < p.tab_rows ? halo_voff(wave + NW * k) : OOB;
   }
-  if (MULTI && p.nhb == NBUF) {
+  if (MULTI && taps == 1) {
     // 1x1 window, several chunks: the chunk of step s goes to ring buffer s
     for (int s = 0; s < DIST; ++s) {
       const int cs = min(cbeg + s, nchunks - 1);
@@ -291,8 +293,11 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
       issue_weights(cs, p.wt0, s * WSLAB);
     }
   } else {
-    for (int u = wave; u < hunits; u += NW)
-      dma16(act_rsrc, halo_voff(u), (unsigned)(cbeg * CB * 2), halo + u * UNITB);
+    // the tiles of the first nhb - 1 chunks (one unless the window has fewer taps than the pipeline is deep)
+    for (int hb = 0; hb < (MULTI ? p.nhb - 1 : 1); ++hb)
+      for (int u = wave; u < hunits; u += NW)
+        dma16(act_rsrc, halo_voff(u), (unsigned)(min(cbeg + hb, nchunks - 1) * CB * 2),
+              halo + hb * p.halo_stride + u * UNITB);
     for (int s = 0; s < DIST; ++s) {
       if (s > 0) {
 #pragma unroll
@@ -583,13 +588,14 @@ size_t plan_lds_cfg(TileParams& p, int nw, int nwc, bool rows) {
     if (taps == 1 && p.M > 2048 && p.M <= 8192 && p.R >= 2 * p.C) return 0;
     // copies per wave and step: a power of two (the kernel is instantiated for 1, 2, 4, 8), spread over
     // as few steps as the pipeline leaves between two chunks
-    const int max_spread = taps == 1 ? 1 : taps - Cfg::DIST + 1;
-    if (max_spread < 1) return 0;
+    nhb = 2;
+    while ((nhb - 1) * taps - Cfg::DIST + 1 < 1) ++nhb;
+    const int room = (nhb - 1) * taps - Cfg::DIST + 1;
+    const int max_spread = room < taps ? room : taps;
     hps = 1;
     while (hps < 8 && ceil_div(per_wave, hps) > max_spread) hps *= 2;
     if (ceil_div(per_wave, hps) > max_spread) return 0;
     spread = ceil_div(per_wave, hps);
-    nhb = taps == 1 ? Cfg::NBUF : 2;
   }
   p.nhb = nhb; p.hps = hps; p.spread = spread;
   p.tab_rows = spread * hps;

@@ -145,3 +145,30 @@ def test_input_gradient_only(shape, mode):
         assert st == B.ERR_NULL, st
     torch.cuda.synchronize()
     assert torch.equal(r.dx, before)
+
+
+STRIDED = [
+    # strided input gradients run as one stride-1 sweep per residue class of input positions when the
+    # reduction (Cout) fits one channel chunk: odd sizes, classes without taps (1x1), even and large
+    # windows, stride 3, no padding, rows / columns no window reaches
+    BlockShape("b_s2_3x3", 2, 64, 15, 13, 64, 3, 2, 1, "bf16", 61),
+    BlockShape("b_s2_1x1", 2, 72, 14, 11, 64, 1, 2, 0, "bf16", 62),
+    BlockShape("b_s2_5x5", 2, 16, 17, 17, 64, 5, 2, 2, "bf16", 63),
+    BlockShape("b_s2_2x2", 3, 24, 12, 12, 32, 2, 2, 0, "bf16", 64),
+    BlockShape("b_s3_3x3", 2, 32, 16, 16, 64, 3, 3, 0, "bf16", 65),
+    BlockShape("b_s3_5x5", 2, 40, 19, 14, 64, 5, 3, 1, "bf16", 66),
+    BlockShape("b_s2_nopad", 2, 64, 10, 10, 32, 3, 2, 0, "bf16", 67),
+    # several channel chunks with 1-, 2- and 4-tap class windows (fewer taps than the copy pipeline is
+    # deep: the activation tiles then sit in a ring of three or more buffers)
+    BlockShape("b_s2_3x3_deep", 2, 64, 15, 13, 192, 3, 2, 1, "bf16", 69),
+    BlockShape("b_s3_5x5_deep", 2, 40, 19, 14, 128, 5, 3, 1, "bf16", 70),
+    # more than 64 taps: the tile kernel keeps one table entry per tap in a lane and declines
+    BlockShape("b_9x9", 1, 8, 20, 20, 16, 9, 1, 4, "bf16", 68),
+]
+
+
+@pytest.mark.parametrize("shape", STRIDED, ids=lambda s: s.name)
+def test_bf16_strided_and_large_windows(shape):
+    inp = synth.make_inputs(shape)
+    ref = oracle_block(inp)
+    compare(_run(inp, "tune"), ref, "bf16", tag=f"{shape.name}/tune")
