@@ -21,7 +21,9 @@
 //
 //   forward conv   Z  = w' (*) X + b'        (Sec. 3.1 / 3.3)    act = x,  weights [Cout][taps][Cin]
 //   input gradient dX = w'_rot (*) dZ        (Sec. 3.2.1), stride 1: the same sweep over dz with
-//                  the taps reversed and padding k-1-p,          weights [Cin][taps][Cout]
+//                  the taps reversed and padding k-1-p,          weights [Cin][taps][Cout];
+//                  strided: one such sweep per residue class of input positions (see
+//                  dgrad_class_params), written to that class's positions of dX
 #include "common.h"
 
 #include <type_traits>
