@@ -165,9 +165,12 @@ __device__ __forceinline__ void store4(bf16_t* p, const float (&w)[4]) {
   *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3]));
 }
 
-// One block per output channel.  VEC (K % 4 == 0): 64 lanes walk the row four elements at a
-// time while the block's four waves each add up a quarter of the `nsplit` partial copies;
-// the partial sums meet in LDS.  Otherwise one element per thread, all partials in sequence.
+// One block per output channel.  VEC (K % 4 == 0): a thread owns float4 columns of the row.  The
+// `nsplit` partial copies of a column lie far apart in memory, so every load is a latency round trip of
+// its own.  Short rows (fewer than 256 columns): a thread keeps sixteen copies of one column in
+// flight, the copies are divided over as many thread groups as fit the block, and the groups meet in
+// LDS.  Long rows: a column per thread, four copies in flight, columns in sequence.  Otherwise one
+// element per thread, all partials in sequence.
 template <typename T, bool VEC, int NTHR>
 __global__ __launch_bounds__(NTHR) void fold_back_kernel(
     const float* __restrict__ part, int nsplit, const float* __restrict__ r_part, int nrpart,
@@ -175,8 +178,8 @@ __global__ __launch_bounds__(NTHR) void fold_back_kernel(
     const float* __restrict__ mean, const float* __restrict__ var, float eps, int identity, int Cout,
     int K, T* __restrict__ dW, float* __restrict__ db, float* __restrict__ dgamma,
     float* __restrict__ dbeta) {
-  constexpr int NSL = NTHR / 64;           // waves = lanes over the partial copies in the short-row path
-  __shared__ float4 red4[NSL - 1][64];
+  constexpr int NSL = NTHR / 64;
+  __shared__ float4 red4[VEC ? NTHR : 1];
   __shared__ float red[NSL];
   const int co = blockIdx.x;
   const int tid = threadIdx.x;
@@ -187,12 +190,25 @@ __global__ __launch_bounds__(NTHR) void fold_back_kernel(
     s = gamma[co] / sd;
   }
   float dot = 0.f;
+  const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto finish = [&](int k4, const float4& v) {   // dW = s dw', <dw', w> of one float4 column
+    const float g4[4] = {v.x, v.y, v.z, v.w};
+    float w4[4], o4[4];
+    load4(W + (size_t)co * K + 4 * k4, w4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      o4[e] = s * g4[e];
+      dot += g4[e] * w4[e];
+    }
+    store4(dW + (size_t)co * K + 4 * k4, o4);
+  };
   if (VEC && (K >> 2) >= 256) {
-    // long rows: one float4 column per thread, all partial copies summed in registers, no barriers
+    // long rows: one float4 column per thread at a time, all partial copies summed in registers, no
+    // barriers (many such blocks share a CU, which keeps enough loads in flight)
     const int K4 = K >> 2;
     const float* row = part + (size_t)co * K;
     for (int k4 = tid; k4 < K4; k4 += NTHR) {
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      float4 v = zero4;
       int sp = 0;
       for (; sp + 3 < nsplit; sp += 4) {
         const float4 a0 = ld4(row + (size_t)sp * P + 4 * k4);
@@ -208,61 +224,37 @@ __global__ __launch_bounds__(NTHR) void fold_back_kernel(
         const float4 a0 = ld4(row + (size_t)sp * P + 4 * k4);
         v.x += a0.x; v.y += a0.y; v.z += a0.z; v.w += a0.w;
       }
-      const float g4[4] = {v.x, v.y, v.z, v.w};
-      float w4[4], o4[4];
-      load4(W + (size_t)co * K + 4 * k4, w4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        o4[e] = s * g4[e];
-        dot += g4[e] * w4[e];
-      }
-      store4(dW + (size_t)co * K + 4 * k4, o4);
+      finish(k4, v);
     }
   } else if (VEC) {
-    const int kq = tid & 63, sg = tid >> 6;
+    // short rows (fewer than 256 columns): thread -> (column c, group g of the partial copies)
     const int K4 = K >> 2;
-    const float* row = part + (size_t)co * K;
-    for (int base = 0; base < K4; base += 64) {
-      const int k4 = base + kq;
-      const bool live = k4 < K4;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (live) {
-        int sp = sg;
-        for (; sp + 3 * NSL < nsplit; sp += 4 * NSL) {
-          const float4 a0 = ld4(row + (size_t)sp * P + 4 * k4);
-          const float4 a1 = ld4(row + (size_t)(sp + NSL) * P + 4 * k4);
-          const float4 a2 = ld4(row + (size_t)(sp + 2 * NSL) * P + 4 * k4);
-          const float4 a3 = ld4(row + (size_t)(sp + 3 * NSL) * P + 4 * k4);
-          v.x += (a0.x + a1.x) + (a2.x + a3.x);
-          v.y += (a0.y + a1.y) + (a2.y + a3.y);
-          v.z += (a0.z + a1.z) + (a2.z + a3.z);
-          v.w += (a0.w + a1.w) + (a2.w + a3.w);
-        }
-        for (; sp < nsplit; sp += NSL) {
-          const float4 a0 = ld4(row + (size_t)sp * P + 4 * k4);
-          v.x += a0.x; v.y += a0.y; v.z += a0.z; v.w += a0.w;
+    const int G = NTHR / K4;
+    const int c = tid % K4, g = tid / K4;
+    float4 v = zero4;
+    if (g < G) {
+      const float* col = part + (size_t)co * K + 4 * c;
+      for (int sp0 = g; sp0 < nsplit; sp0 += 16 * G) {
+        float4 a[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) a[j] = sp0 + j * G < nsplit ? ld4(col + (size_t)(sp0 + j * G) * P) : zero4;
+#pragma unroll
+        for (int j = 0; j < 16; j += 4) {
+          v.x += (a[j].x + a[j + 1].x) + (a[j + 2].x + a[j + 3].x);
+          v.y += (a[j].y + a[j + 1].y) + (a[j + 2].y + a[j + 3].y);
+          v.z += (a[j].z + a[j + 1].z) + (a[j + 2].z + a[j + 3].z);
+          v.w += (a[j].w + a[j + 1].w) + (a[j + 2].w + a[j + 3].w);
         }
       }
-      if (sg > 0) red4[sg - 1][kq] = v;
-      __syncthreads();
-      if (sg == 0 && live) {
-        float g4[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int l = 0; l < NSL - 1; ++l) {
-          const float4 bl = red4[l][kq];
-          g4[0] += bl.x; g4[1] += bl.y; g4[2] += bl.z; g4[3] += bl.w;
-        }
-        float w4[4];
-        load4(W + (size_t)co * K + 4 * k4, w4);
-        float o4[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          o4[e] = s * g4[e];
-          dot += g4[e] * w4[e];
-        }
-        store4(dW + (size_t)co * K + 4 * k4, o4);
+    }
+    red4[tid] = v;
+    __syncthreads();
+    if (g == 0) {
+      for (int l = 1; l < G; ++l) {
+        const float4 o = red4[l * K4 + c];
+        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
       }
-      __syncthreads();
+      finish(c, v);
     }
   } else {
     for (int k = tid; k < K; k += NTHR) {
