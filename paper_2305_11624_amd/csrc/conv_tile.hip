@@ -114,21 +114,6 @@ template <int N> __device__ __forceinline__ void wait_vm() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
-// Waits until at most STEPS steps' worth (STEPS * (WPW + hps)) of this wave's copies are outstanding.
-template <int WPW, int STEPS> __device__ __forceinline__ void wait_steps(int hps) {
-  switch (hps) {
-    case 0: wait_vm<STEPS * WPW>(); break;
-    case 1: wait_vm<STEPS * (WPW + 1)>(); break;
-    case 2: wait_vm<STEPS * (WPW + 2)>(); break;
-    case 3: wait_vm<STEPS * (WPW + 3)>(); break;
-    case 4: wait_vm<STEPS * (WPW + 4)>(); break;
-    case 5: wait_vm<STEPS * (WPW + 5)>(); break;
-    case 6: wait_vm<STEPS * (WPW + 6)>(); break;
-    case 7: wait_vm<STEPS * (WPW + 7)>(); break;
-    default: wait_vm<STEPS * (WPW + 8)>(); break;
-  }
-}
-
 // Compile-time layout of one instantiation (shared by the kernel and the host planner).
 template <int NCH, int CB> struct TileCfg {
   static constexpr int TRC = NCH * 32;         // output channels per workgroup
@@ -588,15 +573,17 @@ size_t plan_lds_cfg(TileParams& p, int nw, int nwc, bool rows) {
     // 1x1 windows with several chunks: the generic implicit-GEMM kernel is only faster for mid-sized pixel
     // counts with many more output than input channels (many channel tiles re-reading a short reduction)
     if (taps == 1 && p.M > 2048 && p.M <= 8192 && p.R >= 2 * p.C) return 0;
-    // copies per wave and step: a power of two (the kernel is instantiated for 1, 2, 4, 8), spread over
-    // as few steps as the pipeline leaves between two chunks
+    // copies per wave and step (the kernel is instantiated for 1, 2, 3, 4, 6, 8), spread over as few
+    // steps as the pipeline leaves between two chunks
     nhb = 2;
     while ((nhb - 1) * taps - Cfg::DIST + 1 < 1) ++nhb;
     const int room = (nhb - 1) * taps - Cfg::DIST + 1;
     const int max_spread = room < taps ? room : taps;
-    hps = 1;
-    while (hps < 8 && ceil_div(per_wave, hps) > max_spread) hps *= 2;
-    if (ceil_div(per_wave, hps) > max_spread) return 0;
+    static const int hps_values[] = {1, 2, 3, 4, 6, 8};
+    hps = 0;
+    for (int v : hps_values)
+      if (ceil_div(per_wave, v) <= max_spread) { hps = v; break; }
+    if (hps == 0) return 0;
     spread = ceil_div(per_wave, hps);
   }
   p.nhb = nhb; p.hps = hps; p.spread = spread;
@@ -701,7 +688,8 @@ hipError_t launch_plan(const TileParams& p, const TilePlan& pl, hipStream_t st) 
   if (pl.nw == NWV && pl.nwc == WC && pl.nch == NC && pl.cb == CBV && pl.hps == H) \
     return launch_inst<NWV, WC, NC, CBV, H>(p, pl, st);
 #define CASES(NWV, WC, NC, CBV) \
-  CASE(NWV, WC, NC, CBV, 0) CASE(NWV, WC, NC, CBV, 1) CASE(NWV, WC, NC, CBV, 2) CASE(NWV, WC, NC, CBV, 4) CASE(NWV, WC, NC, CBV, 8)
+  CASE(NWV, WC, NC, CBV, 0) CASE(NWV, WC, NC, CBV, 1) CASE(NWV, WC, NC, CBV, 2) CASE(NWV, WC, NC, CBV, 3) \
+  CASE(NWV, WC, NC, CBV, 4) CASE(NWV, WC, NC, CBV, 6) CASE(NWV, WC, NC, CBV, 8)
   CASES(4, 1, 2, 32) CASES(4, 1, 2, 64) CASES(4, 1, 4, 32) CASES(4, 1, 4, 64)
   CASES(8, 1, 2, 32) CASES(8, 1, 2, 64) CASES(8, 1, 4, 32) CASES(8, 1, 4, 64)
   CASES(4, 2, 4, 32) CASES(4, 2, 4, 64)
