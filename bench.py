@@ -59,6 +59,8 @@ def parse():
                     help="also launch a plain streaming kernel of known size (in-place ReLU over 256 MiB: "
                          "reads and writes 268435456 bytes each) so that rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE readings of the other kernels can be scaled to bytes")
+    ap.add_argument("--group-fold", action="store_true",
+                    help="resnet50 workload: also run Tune mode with all blocks folded in one launch")
     ap.add_argument("--batch", type=int, default=32, help="batch of the resnet50 workload")
     ap.add_argument("--image", type=int, default=224, help="image size of the resnet50 workload")
     return ap.parse_args()
@@ -184,10 +186,10 @@ def backbone_flop(shapes):
     return sum(s.fwd_flop * (2 if s.name == "stem" else 3) for s in shapes)
 
 
-def run_backbone(mode, N, image, steps, warmup):
+def run_backbone(mode, N, image, steps, warmup, group_fold=False):
     import torch
     from paper_2305_11624_amd.resnet50 import ResNet50
-    net = ResNet50(N, image, "bf16", mode)
+    net = ResNet50(N, image, "bf16", mode, group_fold=group_fold)
     g = torch.Generator(device="cpu").manual_seed(0)
     x = torch.randn(N, image, image, 3, generator=g).to("cuda", torch.bfloat16)
     h = image // 32
@@ -213,6 +215,20 @@ def run_backbone(mode, N, image, steps, warmup):
     out = dict(ms=ms, peak_activation_mb=peak / 1e6, saved_model_mb=net.saved_bytes_model() / 1e6,
                fwd_ms=ev[0].elapsed_time(ev[1]), bwd_ms=ev[1].elapsed_time(ev[2]),
                refold_blocks=sum(1 for b in net.blocks.values() if mode == "tune" and not b.keep_folded))
+    if group_fold:
+        # the grouped fold alone: every block's w -> w' (both orders) and b' in one launch
+        items, n, table, grid = net._group
+        byts = sum(3 * b.shape.Cout * b.shape.K * 2 + 24 * b.shape.Cout for b, _ in items)
+        from paper_2305_11624_amd import binding as B
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        e[0].record()
+        for _ in range(20):
+            B.convbn_fold_group(n, table, grid)
+        e[1].record()
+        torch.cuda.synchronize()
+        fms = e[0].elapsed_time(e[1]) / 20
+        out.update(fold_group_blocks=n, fold_group_ms=fms, fold_group_mb=byts / 1e6, fold_group_gbs=byts / fms / 1e6,
+                   saved_model_mb=net.group_bytes / 1e6, refold_blocks=0)
     del net
     torch.cuda.empty_cache()
     return out
@@ -260,6 +276,7 @@ def main_backbone(a):
     flop = backbone_flop(shapes)
     tune = run_backbone("tune", N, image, a.steps, a.warmup)
     ev = None if a.no_eval else run_backbone("eval", N, image, a.steps, a.warmup)
+    grouped = run_backbone("tune", N, image, a.steps, a.warmup, group_fold=True) if a.group_fold else None
     tf = flop / (tune["ms"] * 1e-3) / 1e12
     line = {
         "metric": "ConvBN Tune fwd+bwd TFLOP/s (% bf16 MFMA peak) + activation MB vs Eval",
@@ -270,7 +287,7 @@ def main_backbone(a):
                                f"bf16, N={N}, {image}x{image}x3, frozen BN statistics", "mode": "tune",
                    "layout": "NHWC", "step": "fwd+bwd of the backbone (no gradient w.r.t. the images)"},
         "pct_of_bf16_mfma_peak": 100.0 * tf / PEAK_BF16_TFLOPS,
-        "tune": tune, "eval": ev,
+        "tune": tune, "eval": ev, "tune_group_fold": grouped,
         "eval_ms_per_step": ev["ms"] if ev else None,
         "tune_speedup_vs_eval": ev["ms"] / tune["ms"] if ev else None,
         "peak_activation_mb": {"tune": tune["peak_activation_mb"], "eval": ev["peak_activation_mb"] if ev else None},

@@ -152,6 +152,32 @@ convbn_status convbn_fold(const convbn_desc *desc, const void *W, const float *b
                           const float *var, void *w_fprop, void *w_folded, float *b_folded,
                           void *stream);
 
+/* The folds of several blocks in ONE launch (Sec. 3.3: in Tune mode every training step starts by
+ * folding each block's BatchNorm into its weights; a fold moves little data, so one launch per
+ * block is bound by the launches).  Built for callers that own a whole network.
+ *   convbn_fold_item: one block's convbn_fold arguments (device pointers; identity != 0 folds
+ *     with s = 1, b' = b: the plain re-ordering of the weights the Eval-mode backward needs).
+ *   convbn_fold_group_plan: HOST side.  Checks the n items (bf16 blocks with Cout and
+ *     Cin*kH*kW multiples of 8; others are CONVBN_ERR_UNSUPPORTED: fold them with convbn_fold)
+ *     and writes a table of convbn_fold_group_table_bytes(n) bytes into HOST memory
+ *     `table_host`, and the launch size into *grid_blocks.  Launches nothing.  The caller
+ *     copies the table to device memory (16-byte aligned) once; it stays valid while the
+ *     pointers in the items do.
+ *   convbn_fold_group: runs the table (`table_dev`, DEVICE memory) on `stream`; results are
+ *     bit-identical to n convbn_fold calls. */
+typedef struct {
+  const convbn_desc *desc;
+  const void *W;
+  const float *b, *gamma, *beta, *mean, *var; /* b, beta nullable as for convbn_fold */
+  void *w_fprop, *w_folded;                  /* each nullable = not wanted */
+  float *b_folded;                           /* nullable */
+  int32_t identity;
+} convbn_fold_item;
+size_t convbn_fold_group_table_bytes(int n);
+convbn_status convbn_fold_group_plan(int n, const convbn_fold_item *items, void *table_host,
+                                     size_t table_bytes, int *grid_blocks);
+convbn_status convbn_fold_group(int n, const void *table_dev, int grid_blocks, void *stream);
+
 /* Workspace bytes convbn_conv_fprop (pass = CONVBN_PASS_FWD) or convbn_conv_dgrad /
  * convbn_conv_wgrad (CONVBN_PASS_BWD, enough for either) need; 0 for most shapes (then ws
  * may be NULL). */

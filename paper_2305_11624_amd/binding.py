@@ -24,7 +24,8 @@ EXPORTS = ["convbn_hout", "convbn_wout", "convbn_workspace_bytes", "convbn_saved
            "convbn_last_error", "convbn_fold", "convbn_conv_fprop", "convbn_conv_dgrad",
            "convbn_wgrad_parts", "convbn_rsum_parts", "convbn_conv_wgrad", "convbn_fold_back",
            "convbn_conv_workspace_bytes", "convbn_aux_eltwise", "convbn_aux_maxpool_fwd",
-           "convbn_aux_maxpool_bwd"]
+           "convbn_aux_maxpool_bwd", "convbn_fold_group_table_bytes", "convbn_fold_group_plan",
+           "convbn_fold_group"]
 
 
 class Desc(C.Structure):
@@ -34,6 +35,13 @@ class Desc(C.Structure):
                 ("stride_h", C.c_int32), ("stride_w", C.c_int32),
                 ("pad_h", C.c_int32), ("pad_w", C.c_int32),
                 ("eps", C.c_float), ("dtype", C.c_int32), ("layout", C.c_int32)]
+
+
+class FoldItem(C.Structure):
+    """Mirror of convbn_fold_item."""
+    _fields_ = [("desc", C.POINTER(Desc)), ("W", C.c_void_p), ("b", C.c_void_p), ("gamma", C.c_void_p),
+                ("beta", C.c_void_p), ("mean", C.c_void_p), ("var", C.c_void_p), ("w_fprop", C.c_void_p),
+                ("w_folded", C.c_void_p), ("b_folded", C.c_void_p), ("identity", C.c_int32)]
 
 
 class ConvBNError(RuntimeError):
@@ -78,6 +86,12 @@ def lib():
                                       C.c_size_t, vp]
         L.convbn_fold.restype = C.c_int
         L.convbn_fold.argtypes = [dp, vp, fp, fp, fp, fp, fp, vp, vp, fp, vp]
+        L.convbn_fold_group_table_bytes.restype = C.c_size_t
+        L.convbn_fold_group_table_bytes.argtypes = [C.c_int]
+        L.convbn_fold_group_plan.restype = C.c_int
+        L.convbn_fold_group_plan.argtypes = [C.c_int, C.POINTER(FoldItem), vp, C.c_size_t, C.POINTER(C.c_int)]
+        L.convbn_fold_group.restype = C.c_int
+        L.convbn_fold_group.argtypes = [C.c_int, vp, C.c_int, vp]
         L.convbn_conv_fprop.restype = C.c_int
         L.convbn_conv_fprop.argtypes = [dp, vp, vp, fp, vp, vp, C.c_size_t, vp]
         L.convbn_conv_dgrad.restype = C.c_int
@@ -215,6 +229,36 @@ def convbn_fold(desc, W, b, gamma, beta, mean, var, w_fprop, w_folded, b_folded,
     st = lib().convbn_fold(C.byref(desc), _ptr(W), _ptr(b), _ptr(gamma), _ptr(beta), _ptr(mean),
                            _ptr(var), _ptr(w_fprop), _ptr(w_folded), _ptr(b_folded),
                            _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_fold_group_plan(blocks, device="cuda", check=True):
+    """blocks: list of dicts with desc, W, b, gamma, beta, mean, var, w_fprop, w_folded, b_folded (tensors
+    or None) and identity.  Returns (n, table tensor on the device, grid_blocks)."""
+    n = len(blocks)
+    items = (FoldItem * n)()
+    for it, blk in zip(items, blocks):
+        it.desc = C.pointer(blk["desc"])
+        for k in ("W", "b", "gamma", "beta", "mean", "var", "w_fprop", "w_folded", "b_folded"):
+            t = blk.get(k)
+            setattr(it, k, None if t is None else t.data_ptr())
+        it.identity = int(blk.get("identity", 0))
+    nbytes = lib().convbn_fold_group_table_bytes(n)
+    host = (C.c_ubyte * nbytes)()
+    grid = C.c_int(0)
+    st = lib().convbn_fold_group_plan(n, items, C.cast(host, C.c_void_p), nbytes, C.byref(grid))
+    if check:
+        _check(st)
+    elif st != OK:
+        return st
+    table = torch.frombuffer(bytearray(host), dtype=torch.uint8).to(device)
+    return n, table, grid.value
+
+
+def convbn_fold_group(n, table, grid_blocks, stream=None, check=True):
+    st = lib().convbn_fold_group(n, _ptr(table), grid_blocks, _stream(stream))
     if check:
         _check(st)
     return st

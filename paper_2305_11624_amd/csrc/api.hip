@@ -424,6 +424,46 @@ convbn_status convbn_eval_bwd(const convbn_desc* desc, const void* x, const void
   return CONVBN_OK;
 }
 
+size_t convbn_fold_group_table_bytes(int n) { return n > 0 ? (size_t)n * fold_group_item_bytes() : 0; }
+
+convbn_status convbn_fold_group_plan(int n, const convbn_fold_item* items, void* table_host, size_t table_bytes,
+                                     int* grid_blocks) {
+  if (n <= 0) return fail(CONVBN_ERR_SHAPE, "a fold group needs at least one block");
+  if (!items || !table_host || !grid_blocks) return fail(CONVBN_ERR_NULL, "items, table_host and grid_blocks are required");
+  if (table_bytes < convbn_fold_group_table_bytes(n))
+    return fail(CONVBN_ERR_WORKSPACE, "table_host holds %zu bytes, %zu are needed", table_bytes,
+                convbn_fold_group_table_bytes(n));
+  int total = 0;
+  for (int i = 0; i < n; ++i) {
+    const convbn_fold_item& it = items[i];
+    Geom g;
+    convbn_status s = make_geom(it.desc, &g);
+    if (s != CONVBN_OK) return s;
+    const void* W = it.W; const float* b = it.b; const float* gamma = it.gamma; const float* beta = it.beta;
+    const float* mean = it.mean; const float* var = it.var;
+    void* w_fprop = it.w_fprop; void* w_folded = it.w_folded; float* b_folded = it.b_folded;
+    REQUIRE_PTR(W);
+    if (!it.identity) { REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var); }
+    OPTIONAL_PTR(b); OPTIONAL_PTR(beta); OPTIONAL_PTR(w_fprop); OPTIONAL_PTR(w_folded); OPTIONAL_PTR(b_folded);
+    if (b_folded && !it.identity && !beta) return fail(CONVBN_ERR_NULL, "beta is required when b_folded is wanted");
+    int blocks = 0;
+    if (!fold_group_item(g, it.desc->dtype, W, b, gamma, beta, mean, var, it.identity, w_fprop, w_folded, b_folded,
+                         total, static_cast<char*>(table_host) + (size_t)i * fold_group_item_bytes(), &blocks))
+      return fail(CONVBN_ERR_UNSUPPORTED, "block %d: a fold group takes bf16 blocks whose Cout and Cin*kH*kW are "
+                  "multiples of 8 (fold the others with convbn_fold)", i);
+    total += blocks;
+  }
+  *grid_blocks = total;
+  return CONVBN_OK;
+}
+
+convbn_status convbn_fold_group(int n, const void* table_dev, int grid_blocks, void* stream) {
+  if (n <= 0 || grid_blocks <= 0) return fail(CONVBN_ERR_SHAPE, "empty fold group");
+  REQUIRE_PTR(table_dev);
+  LAUNCH(launch_fold_group(table_dev, n, grid_blocks, static_cast<hipStream_t>(stream)));
+  return CONVBN_OK;
+}
+
 convbn_status convbn_fold(const convbn_desc* desc, const void* W, const float* b, const float* gamma,
                           const float* beta, const float* mean, const float* var, void* w_fprop,
                           void* w_folded, float* b_folded, void* stream) {

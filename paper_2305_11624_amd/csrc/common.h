@@ -56,6 +56,14 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 hipError_t launch_fold(const Geom& g, int dtype, const void* W, const float* b, const float* gamma,
                        const float* beta, const float* mean, const float* var, int identity,
                        void* w_krsc, void* w_crsk, float* bfold, hipStream_t st);
+// Grouped fold: fold_group_item() writes one table entry (fold_group_item_bytes() bytes, host memory) for a
+// bf16 block with K and Cout multiples of 8 (false otherwise) and returns its number of workgroups;
+// launch_fold_group() runs a table that has been copied to device memory.
+size_t fold_group_item_bytes();
+bool fold_group_item(const Geom& g, int dtype, const void* W, const float* b, const float* gamma, const float* beta,
+                     const float* mean, const float* var, int identity, void* w_krsc, void* w_crsk, float* bfold,
+                     int first_block, void* item_out, int* blocks);
+hipError_t launch_fold_group(const void* items_dev, int n, int grid_blocks, hipStream_t st);
 // Sums `nsplit` fp32 partial copies of dJ/dw' ([nsplit][Cout][K]) and `nrpart` partial
 // row-sum vectors ([nrpart][Cout]); writes dW, db, dgamma, dbeta (Table 2 "Tune").
 // identity != 0 (Eval path): dW = sum of partials only, other outputs untouched.

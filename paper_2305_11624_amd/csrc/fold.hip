@@ -6,6 +6,8 @@
 //   bn_bwd      dY = s dZ and the per-channel sums of Table 2, row "Eval"
 #include "common.h"
 
+#include <cstring>
+
 namespace convbn {
 
 namespace {
@@ -86,19 +88,23 @@ __global__ __launch_bounds__(256) void fold_kernel(const T* __restrict__ W, cons
 // bf16 fast path (K and Cout multiples of 8): 64 x 64 tiles, every global access is a 16-byte vector --
 // rows of W are read and written back eight columns per thread, the transposed copy leaves through an
 // LDS tile as rows of 64 consecutive output channels.
-__global__ __launch_bounds__(256) void fold_bf16x8_kernel(const bf16_t* __restrict__ W, const float* __restrict__ b,
-                                                          const float* __restrict__ gamma,
-                                                          const float* __restrict__ beta,
-                                                          const float* __restrict__ mean,
-                                                          const float* __restrict__ var, float eps, int identity,
-                                                          int Cout, int K, int Cin, int taps,
-                                                          bf16_t* __restrict__ w_krsc, bf16_t* __restrict__ w_crsk,
-                                                          float* __restrict__ bfold) {
-  __shared__ __attribute__((aligned(16))) unsigned short tile[64][72];   // [k][co], 144-byte rows
+struct FoldArgs {
+  const bf16_t* W; const float* b; const float* gamma; const float* beta; const float* mean; const float* var;
+  bf16_t* w_krsc; bf16_t* w_crsk; float* bfold;
+  float eps; int identity, Cout, K, Cin, taps;
+};
+// One 64 x 64 tile (bx along K, by along Cout) of one block's fold.
+__device__ __forceinline__ void fold_tile_bf16x8(const FoldArgs& a, int bx, int by, unsigned short (*tile)[72]) {
+  const bf16_t* __restrict__ W = a.W;
+  const float* __restrict__ b = a.b; const float* __restrict__ gamma = a.gamma; const float* __restrict__ beta = a.beta;
+  const float* __restrict__ mean = a.mean; const float* __restrict__ var = a.var;
+  bf16_t* __restrict__ w_krsc = a.w_krsc; bf16_t* __restrict__ w_crsk = a.w_crsk; float* __restrict__ bfold = a.bfold;
+  const float eps = a.eps;
+  const int identity = a.identity, Cout = a.Cout, K = a.K, Cin = a.Cin, taps = a.taps;
   const int tid = threadIdx.x;
-  const int co0 = blockIdx.y * 64;
-  const int k0 = blockIdx.x * 64;
-  const bool do_bias = blockIdx.x == 0 && tid < 64 && bfold && co0 + tid < Cout;
+  const int co0 = by * 64;
+  const int k0 = bx * 64;
+  const bool do_bias = bx == 0 && tid < 64 && bfold && co0 + tid < Cout;
   float bg = 1.f, bv = 1.f, bm = 0.f, bb = 0.f, bc = 0.f;
   if (do_bias) {
     const int co = co0 + tid;
@@ -147,6 +153,27 @@ __global__ __launch_bounds__(256) void fold_bf16x8_kernel(const bf16_t* __restri
       if (co0 + c16 + 8 * h < Cout)
         *reinterpret_cast<uint4*>(dst + 8 * h) = *reinterpret_cast<const uint4*>(&tile[kl][c16 + 8 * h]);
   }
+}
+
+__global__ __launch_bounds__(256) void fold_bf16x8_kernel(FoldArgs a) {
+  __shared__ __attribute__((aligned(16))) unsigned short tile[64][72];   // [k][co], 144-byte rows
+  fold_tile_bf16x8(a, blockIdx.x, blockIdx.y, tile);
+}
+
+// The folds of several blocks in one launch (Sec. 3.3: a training step starts by folding every block's
+// BatchNorm into its weights; one launch per block would be bound by the launches, not by memory).
+// items[i] covers blocks [first_block, first_block + tiles): tile t of item i is (t % tiles_k, t / tiles_k).
+struct FoldGroupItem { FoldArgs a; int first_block, tiles_k; };
+__global__ __launch_bounds__(256) void fold_group_kernel(const FoldGroupItem* __restrict__ items, int n) {
+  __shared__ __attribute__((aligned(16))) unsigned short tile[64][72];
+  int lo = 0, hi = n - 1;   // last item whose first_block <= blockIdx.x
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (items[mid].first_block <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+  }
+  const FoldGroupItem it = items[lo];
+  const int t = blockIdx.x - it.first_block;
+  fold_tile_bf16x8(it.a, t % it.tiles_k, t / it.tiles_k, tile);
 }
 
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
@@ -548,8 +575,8 @@ hipError_t launch_fold(const Geom& g, int dtype, const void* W, const float* b, 
   const int taps = g.kH * g.kW;
   if (dtype == CONVBN_BF16 && g.K % 8 == 0 && g.Cout % 8 == 0)
     hipLaunchKernelGGL(fold_bf16x8_kernel, dim3(ceil_div(g.K, 64), ceil_div(g.Cout, 64)), dim3(256), 0, st,
-                       (const bf16_t*)W, b, gamma, beta, mean, var, g.eps, identity, g.Cout, g.K, g.Cin, taps,
-                       (bf16_t*)w_krsc, (bf16_t*)w_crsk, bfold);
+                       FoldArgs{(const bf16_t*)W, b, gamma, beta, mean, var, (bf16_t*)w_krsc, (bf16_t*)w_crsk, bfold,
+                                g.eps, identity, g.Cout, g.K, g.Cin, taps});
   else if (dtype == CONVBN_BF16)
     hipLaunchKernelGGL(fold_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)W, b, gamma, beta,
                        mean, var, g.eps, identity, g.Cout, g.K, g.Cin, taps, (bf16_t*)w_krsc,
@@ -558,6 +585,27 @@ hipError_t launch_fold(const Geom& g, int dtype, const void* W, const float* b, 
     hipLaunchKernelGGL(fold_kernel<float>, grid, dim3(256), 0, st, (const float*)W, b, gamma, beta,
                        mean, var, g.eps, identity, g.Cout, g.K, g.Cin, taps, (float*)w_krsc,
                        (float*)w_crsk, bfold);
+  return hipGetLastError();
+}
+
+size_t fold_group_item_bytes() { return sizeof(FoldGroupItem); }
+
+bool fold_group_item(const Geom& g, int dtype, const void* W, const float* b, const float* gamma, const float* beta,
+                     const float* mean, const float* var, int identity, void* w_krsc, void* w_crsk, float* bfold,
+                     int first_block, void* item_out, int* blocks) {
+  if (dtype != CONVBN_BF16 || g.K % 8 != 0 || g.Cout % 8 != 0) return false;
+  FoldGroupItem it{};
+  it.a = FoldArgs{(const bf16_t*)W, b, gamma, beta, mean, var, (bf16_t*)w_krsc, (bf16_t*)w_crsk, bfold,
+                  g.eps, identity, g.Cout, g.K, g.Cin, g.kH * g.kW};
+  it.first_block = first_block;
+  it.tiles_k = ceil_div(g.K, 64);
+  *blocks = it.tiles_k * ceil_div(g.Cout, 64);
+  memcpy(item_out, &it, sizeof(it));
+  return true;
+}
+
+hipError_t launch_fold_group(const void* items_dev, int n, int grid_blocks, hipStream_t st) {
+  hipLaunchKernelGGL(fold_group_kernel, dim3(grid_blocks), dim3(256), 0, st, (const FoldGroupItem*)items_dev, n);
   return hipGetLastError();
 }
 

@@ -32,12 +32,17 @@ class _Block:
         # Tune keeps w' unless it is larger than the Y that Eval would keep (then backward re-folds)
         self.keep_folded = mode == "tune" and shape.P <= shape.A_z
         self.x = self.saved = None
+        self.grouped = None      # buffers of the network's grouped fold (Tune mode, optional)
 
     def forward(self, x, ws):
         s = self.shape
         z = torch.empty((s.N, s.Hout, s.Wout, s.Cout), dtype=self.dt, device=x.device)
         self.x = x
-        if self.mode == "tune":
+        if self.grouped is not None:
+            # w' of this block was produced by the network's grouped fold: only the convolution is left
+            B.convbn_conv_fprop(self.desc, x, self.grouped["w_fprop"], self.grouped["b_folded"], z, ws)
+            self.saved = self.grouped["w_folded"]
+        elif self.mode == "tune":
             self.saved = torch.empty((s.Cin, s.k, s.k, s.Cout), dtype=self.dt, device=x.device) \
                 if self.keep_folded else None
             B.convbn_tune_fwd(self.desc, x, self.W, None, self.gamma, self.beta, self.mean, self.var, z,
@@ -62,9 +67,14 @@ class _Block:
 
 class ResNet50:
     def __init__(self, N: int = 32, image: int = 224, dtype: str = "bf16", mode: str = "tune",
-                 device: str = "cuda"):
+                 device: str = "cuda", group_fold: bool = False):
+        """group_fold (Tune mode): fold all blocks in one launch at the start of forward instead of one
+        launch per block.  Faster, but every w' (in both orders) then lives for the whole step."""
         assert mode in ("tune", "eval")
         self.N, self.image, self.mode, self.device = N, image, mode, device
+        self.group_fold = group_fold and mode == "tune"
+        self._group = None
+        self.group_bytes = 0
         shapes = synth.resnet50_blocks(N, image, dtype)
         self.blocks: Dict[str, _Block] = {s.name: _Block(s, device, mode) for s in shapes}
         self.order: List[str] = [s.name for s in shapes]
@@ -75,6 +85,38 @@ class ResNet50:
             self.stages.append([f"l{st}.{i}" for i in range(nblk)])
         self._tape = None
 
+    def fold_group_table(self, alloc=True):
+        """(n, table, grid, bytes moved) of the grouped fold over every block the group takes (all but
+        blocks whose channel counts are not multiples of 8, i.e. the stem)."""
+        items, byts = [], 0
+        for name in self.order:
+            b = self.blocks[name]
+            s = b.shape
+            if s.Cout % 8 or s.K % 8:
+                continue
+            P = s.Cout * s.K
+            g = dict(w_fprop=torch.empty(P, dtype=self.dt, device=self.device),
+                     w_folded=torch.empty(P, dtype=self.dt, device=self.device),
+                     b_folded=torch.empty(s.Cout, dtype=torch.float32, device=self.device))
+            items.append((b, g))
+            byts += 3 * P * 2 + 24 * s.Cout
+        n, table, grid = B.convbn_fold_group_plan(
+            [dict(desc=b.desc, W=b.W, b=None, gamma=b.gamma, beta=b.beta, mean=b.mean, var=b.var, **g)
+             for b, g in items], device=self.device)
+        return items, n, table, grid, byts
+
+    def _fold_all(self):
+        # the buffers and the table are made once (the table holds pointers); `group_bytes` is what they
+        # add to the memory a Tune-mode step keeps -- the caller adds it to the measured peak
+        if self._group is None:
+            items, n, table, grid, _ = self.fold_group_table()
+            self._group = (items, n, table, grid)
+            self.group_bytes = sum(sum(t.numel() * t.element_size() for t in g.values()) for _, g in items)
+        items, n, table, grid = self._group
+        B.convbn_fold_group(n, table, grid)
+        for b, g in items:
+            b.grouped = g
+
     def saved_bytes_model(self) -> int:
         """Analytic bytes kept between forward and backward besides the block inputs."""
         m = B.MODE_TUNE if self.mode == "tune" else B.MODE_EVAL
@@ -84,6 +126,8 @@ class ResNet50:
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         """x: [N][image][image][3] device tensor (channels-last).  Returns [N][h][w][2048]."""
         ws, bl = self.ws, self.blocks
+        if self.group_fold:
+            self._fold_all()
         z0 = bl["stem"].forward(x, ws)
         B.convbn_aux_eltwise(B.OP_RELU, z0)
         n, h, w, c = z0.shape
@@ -134,6 +178,9 @@ class ResNet50:
         B.convbn_aux_eltwise(B.OP_RELU_BWD, gz0, z0)
         gx = bl["stem"].backward(gz0, ws, need_dx=need_input_grad)
         self._tape = None
+        if self._group is not None:
+            for b, _ in self._group[0]:
+                b.grouped = None
         return gx
 
     def grads(self, name: str) -> Dict[str, torch.Tensor]:

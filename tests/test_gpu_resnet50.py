@@ -138,3 +138,25 @@ def test_glue_kernels(dtype, shape):
         assert np.abs(got - dx_ref).max() <= 1e-6 * np.abs(dx_ref).max()
     else:
         assert np.abs(got - dx_ref).max() <= 2e-2 * np.abs(dx_ref).max()
+
+
+def test_backbone_grouped_fold_is_bit_identical():
+    """Folding all blocks in one launch changes nothing in the numbers of a Tune-mode step."""
+    from paper_2305_11624_amd.resnet50 import ResNet50
+    g = torch.Generator(device="cpu").manual_seed(5)
+    x = torch.randn(2, 64, 64, 3, generator=g).to("cuda", torch.bfloat16)
+    dout = torch.randn(2, 2, 2, 2048, generator=g).to("cuda", torch.bfloat16)
+    outs = []
+    for grouped in (False, True):
+        net = ResNet50(2, 64, "bf16", "tune", group_fold=grouped)
+        y = net.forward(x).clone()
+        net.backward(dout)
+        torch.cuda.synchronize()
+        outs.append((y, {k: net.blocks[k].dW.clone() for k in ("stem", "l1.0.b", "l3.2.c", "l4.0.ds")},
+                     {k: net.blocks[k].dgamma.clone() for k in ("l2.1.a", "l4.2.c")}))
+        del net
+    assert torch.equal(outs[0][0], outs[1][0])
+    for k in outs[0][1]:
+        assert torch.equal(outs[0][1][k], outs[1][1][k]), k
+    for k in outs[0][2]:
+        assert torch.equal(outs[0][2][k], outs[1][2][k]), k

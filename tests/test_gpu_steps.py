@@ -112,3 +112,56 @@ def test_outputs_are_deterministic():
     a, b = r1.results(), r2.results()
     for k in ("Z", "dX", "dW", "dgamma", "dbeta"):
         assert torch.equal(a[k], b[k]), k
+
+
+def test_fold_group_matches_single_folds():
+    """Several blocks folded in one launch: bit-identical to one convbn_fold call per block, including an
+    identity (re-ordering only) item; shapes the group does not take are refused on the host."""
+    from paper_2305_11624_amd import binding as B
+    shapes = [BlockShape("g_3x3", 2, 64, 8, 8, 72, 3, 1, 1, "bf16", 81),
+              BlockShape("g_1x1", 2, 256, 4, 4, 200, 1, 1, 0, "bf16", 82),
+              BlockShape("g_7x7", 1, 8, 16, 16, 64, 7, 2, 3, "bf16", 83),
+              BlockShape("g_big", 1, 512, 4, 4, 512, 3, 1, 1, "bf16", 84)]
+    blocks, refs = [], []
+    for i, sh in enumerate(shapes):
+        inp = synth.make_inputs(sh, bias=(i == 0))
+        d = B.desc_from_shape(sh, eps=inp["eps"])
+        W = B.weight_to_device(inp["W"], torch.bfloat16, "cuda")
+        vec = {k: B.vec_to_device(inp[k], "cuda") for k in ("b", "gamma", "beta", "rmean", "rvar")}
+        P = sh.Cout * sh.K
+        identity = int(i == 2)
+        outs = [dict(w_fprop=torch.full((P,), float("nan"), dtype=torch.bfloat16, device="cuda"),
+                     w_folded=torch.full((P,), float("nan"), dtype=torch.bfloat16, device="cuda"),
+                     b_folded=torch.full((sh.Cout,), float("nan"), dtype=torch.float32, device="cuda")) for _ in range(2)]
+        if identity:   # re-ordering only: what the Eval-mode backward asks for
+            for o in outs:
+                o["w_fprop"] = o["b_folded"] = None
+        common = dict(desc=d, W=W, b=vec["b"], gamma=vec["gamma"], beta=vec["beta"], mean=vec["rmean"], var=vec["rvar"],
+                      identity=identity)
+        blocks.append(dict(common, **outs[0]))
+        refs.append(dict(common, **outs[1]))
+    n, table, grid = B.convbn_fold_group_plan(blocks)
+    B.convbn_fold_group(n, table, grid)
+    for r in refs:
+        if r["identity"]:   # the re-ordering [Cout][kH][kW][Cin] -> [Cin][kH][kW][Cout], exact
+            d = r["desc"]
+            r["w_folded"] = r["W"].reshape(d.Cout, d.kH, d.kW, d.Cin).permute(3, 1, 2, 0).contiguous().flatten()
+        else:
+            B.convbn_fold(r["desc"], r["W"], r["b"], r["gamma"], r["beta"], r["mean"], r["var"], r["w_fprop"],
+                          r["w_folded"], r["b_folded"])
+    torch.cuda.synchronize()
+    for blk, r in zip(blocks, refs):
+        for k in ("w_fprop", "w_folded", "b_folded"):
+            if r[k] is None:
+                continue
+            assert not torch.isnan(blk[k].float()).any(), k
+            assert torch.equal(blk[k], r[k]), (blk["desc"].Cout, k)
+    # a block the group does not take (Cout not a multiple of 8) is refused before anything is launched
+    sh = BlockShape("g_odd", 1, 8, 6, 6, 12, 3, 1, 1, "bf16", 85)
+    inp = synth.make_inputs(sh)
+    d = B.desc_from_shape(sh, eps=inp["eps"])
+    bad = dict(desc=d, W=B.weight_to_device(inp["W"], torch.bfloat16, "cuda"), b=None,
+               gamma=B.vec_to_device(inp["gamma"], "cuda"), beta=B.vec_to_device(inp["beta"], "cuda"),
+               mean=B.vec_to_device(inp["rmean"], "cuda"), var=B.vec_to_device(inp["rvar"], "cuda"),
+               w_fprop=None, w_folded=None, b_folded=None)
+    assert B.convbn_fold_group_plan([bad], check=False) == B.ERR_UNSUPPORTED
