@@ -118,6 +118,13 @@ hipError_t launch_wgrad_igemm(const Geom& g, const void* x, const void* dz, floa
 
 // conv_tile.hip : bf16 MFMA convolution with the input window tile resident in LDS
 // (every input element is fetched once per block and reused by all taps).
+// conv_pw.hip: persistent weight-stationary kernel for 1x1 / stride-1 convolutions over long pixel ranges
+bool pw_fprop_supported(const Geom& g, int dtype);
+bool pw_dgrad_supported(const Geom& g, int dtype);
+hipError_t launch_fprop_pw(const Geom& g, const void* x, const void* w_krsc, const float* bias, void* z,
+                           hipStream_t st);
+hipError_t launch_dgrad_pw(const Geom& g, const void* dz, const void* w_crsk, void* dx, hipStream_t st);
+
 bool tile_fprop_supported(const Geom& g, int dtype);
 bool tile_dgrad_supported(const Geom& g, int dtype);
 // Some problems split the reduced channels over several workgroups and need fp32 partial-output

@@ -62,6 +62,10 @@ BF16_SHAPES = [
     BlockShape("b_small7", 4, 128, 7, 7, 160, 3, 1, 1, "bf16", 37),
     # a Linear layer followed by BatchNorm is the 1x1 block on a 1x1 image (Sec. 3.2.1, closing remark)
     BlockShape("b_linear_bn", 200, 512, 1, 1, 264, 1, 1, 0, "bf16", 44),
+    # long pixel ranges (more than 512 tiles of 128 pixels, ragged last tile): the persistent pointwise
+    # kernel, 32- and 64-channel chunks, one and several chunks, ragged channel tiles, forward and dgrad
+    BlockShape("b_pw_long32", 8, 32, 95, 97, 96, 1, 1, 0, "bf16", 47),
+    BlockShape("b_pw_long64", 8, 64, 95, 97, 128, 1, 1, 0, "bf16", 48),
     # direct path (channels not multiples of 8), incl. a stem-like 7x7/2 with Cin=3
     BlockShape("b_stem", 2, 3, 32, 32, 64, 7, 2, 3, "bf16", 38),
     BlockShape("b_odd_ch", 2, 12, 9, 9, 20, 3, 1, 1, "bf16", 39),
