@@ -1,11 +1,11 @@
-// Pointwise (1x1, stride 1, unpadded) bf16 convolution over a long pixel range as a persistent,
+// Pointwise (1x1, stride 1, unpadded) bf16 convolution as a persistent,
 // weight-stationary streaming product
 //     out[m][r] = sum_c act[m][c] wgt[r][c] (+ bias[r]),     m over all N*H*W pixels:
 //   forward conv   Z  = w' (*) X + b'   (Sec. 3.1 / 3.3)   act = x,   wgt = w' as [Cout][Cin]
 //   input gradient dX = w'_rot (*) dZ   (Sec. 3.2.1)       act = dz,  wgt = w' as [Cin][Cout]
 //
-// On the 56 x 56 stage such a layer moves tens of MB of activations for a few GFLOP: it is bound by
-// memory, and a kernel that hands every pixel tile to a workgroup of its own pays that workgroup's
+// Most of these layers move many MB of activations for a few GFLOP: they are bound by memory (or by the
+// global->LDS copy path), and a kernel that hands every pixel tile to a workgroup of its own pays that workgroup's
 // start-up (weights, tables, first copies in flight) and drain (stores) once per tile, with the memory
 // idle in between.  Here a workgroup keeps its [TRC][C] block of the weights in LDS for its whole life
 // and walks over pixel tiles g, g + G, g + 2G, ...: [TP pixels][CB channels] activation slabs stream
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(64 * NW) void conv_pw_kernel(PwParams p) {
 }
 
 constexpr size_t LDS_USABLE = 159 * 1024;
-constexpr int MIN_TILES = 512;   // fewer pixel tiles than two per CU: the per-tile kernels are as good
+constexpr int MIN_WORK = 128;   // (pixel tiles x channel tiles) below which the per-tile kernels are used
 
 struct PwPlan { bool ok; int nch, cb; size_t lds; };
 
@@ -276,7 +276,7 @@ PwPlan make_plan(PwParams& p) {
   for (int cb : {64, 32}) {
     PwParams q = p;
     const size_t lds = cb == 64 ? plan_cfg<4, 64>(q, pl.nch) : plan_cfg<4, 32>(q, pl.nch);
-    if (lds == 0 || lds > LDS_USABLE || q.ntiles < MIN_TILES) continue;
+    if (lds == 0 || lds > LDS_USABLE || q.ntiles * q.ntr < MIN_WORK) continue;
     p = q;
     pl.cb = cb; pl.lds = lds; pl.ok = true;
     return pl;
