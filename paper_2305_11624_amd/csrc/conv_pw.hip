@@ -272,15 +272,18 @@ PwPlan make_plan(PwParams& p) {
   PwPlan pl{false, 0, 0, 0};
   if (p.C % 16 || p.R % 8) return pl;
   if ((size_t)p.M * p.C * 2 >= OOB || (size_t)p.M * p.R * 2 >= OOB || (size_t)p.R * p.C * 2 >= OOB) return pl;
-  pl.nch = p.R > 64 ? 4 : 2;
-  for (int cb : {64, 32}) {
-    PwParams q = p;
-    const size_t lds = cb == 64 ? plan_cfg<4, 64>(q, pl.nch) : plan_cfg<4, 32>(q, pl.nch);
-    if (lds == 0 || lds > LDS_USABLE || q.ntiles * q.ntr < MIN_WORK) continue;
-    p = q;
-    pl.cb = cb; pl.lds = lds; pl.ok = true;
-    return pl;
-  }
+  // 128 output channels per workgroup where the weight block then still fits next to the ring, else 64
+  for (int nch : {p.R > 64 ? 4 : 2, 2})
+    for (int cb : {64, 32}) {
+      PwParams q = p;
+      const size_t lds = cb == 64 ? plan_cfg<4, 64>(q, nch) : plan_cfg<4, 32>(q, nch);
+      if (lds == 0 || lds > LDS_USABLE || q.ntiles * q.ntr < MIN_WORK) continue;
+      // the narrower block doubles the passes over the activations: measured to pay only with many tiles
+      if (nch == 2 && p.R > 64 && q.ntiles < MIN_WORK) continue;
+      p = q;
+      pl.nch = nch; pl.cb = cb; pl.lds = lds; pl.ok = true;
+      return pl;
+    }
   return pl;
 }
 
