@@ -119,10 +119,15 @@ __device__ __forceinline__ bf16x8 join(s16x4 a, s16x4 b) {
 // TPB taps per workgroup.  Waves 0..3 form a 2x2 grid over the channel tile, each owning NA
 // co-subtiles x NB ci-subtiles (32 channels each); with NT = 2 a second group of four waves takes
 // the upper half of the taps, so eight waves share one LDS tile and hold twice the accumulators.
+// A single tap (1x1 windows) with NT = 2: the second group takes the upper half of every tile's pixels
+// instead and the two groups add their accumulators through LDS at the end -- what eight waves buy
+// there is the copies: each wave hands the memory pipe half as many.
 template <int TPB, int NA, int NB, int NT>
 __global__ __launch_bounds__(256 * NT) void wgrad_tile_kernel(WgParams p) {
   constexpr int NWAVES = 4 * NT;
   constexpr int TH = (TPB + NT - 1) / NT;    // taps per wave
+  constexpr bool KSPLIT = TPB == 1 && NT == 2;   // one tap, two wave groups: they split the tile's pixels
+  constexpr int KS = KSPLIT ? TP / 32 : TP / 16;  // 16-pixel steps per wave and tile
   constexpr int CO_T = 64 * NA, CI_T = 64 * NB;
   constexpr int NZS = NA, NXS = NB;          // 64-channel LDS sub-tiles of dZ / of the window
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -229,11 +234,12 @@ __global__ __launch_bounds__(256 * NT) void wgrad_tile_kernel(WgParams p) {
   };
 
   // taps of this group, as pixel offsets into the window tile
-  const int th = wave >> 2;                    // which half of the tap group this wave multiplies
+  const int th = wave >> 2;                    // which half of the tap group (or of the pixels) this wave multiplies
+  const int kbeg = KSPLIT ? th * KS : 0;       // its first 16-pixel step of a tile
   int tapno[TH], tapoff[TH];
 #pragma unroll
   for (int t = 0; t < TH; ++t) {
-    const int tl = th * TH + t;                // tap inside the group
+    const int tl = KSPLIT ? t : th * TH + t;   // tap inside the group
     const int tap = tg * TPB + tl;
     const int i = fdiv(tap, p.dkW);
     const bool live = tl < TPB && tap < taps;
@@ -288,13 +294,13 @@ __global__ __launch_bounds__(256 * NT) void wgrad_tile_kernel(WgParams p) {
 
     // byte offset of this lane's window-tile rows (tap (0,0)) for its two pixels of every step,
     // read before the next copies start
-    int ptv[TP / 16][2];
+    int ptv[KS][2];
     {
       const int* ptab = pt_base(buf);
 #pragma unroll
-      for (int k = 0; k < TP / 16; ++k) {
-        ptv[k][0] = ptab[k * 16 + kb * 8 + eprime] * ROWB;
-        ptv[k][1] = ptab[k * 16 + kb * 8 + eprime + 4] * ROWB;
+      for (int k = 0; k < KS; ++k) {
+        ptv[k][0] = ptab[(kbeg + k) * 16 + kb * 8 + eprime] * ROWB;
+        ptv[k][1] = ptab[(kbeg + k) * 16 + kb * 8 + eprime + 4] * ROWB;
       }
     }
     if (do_r && tid < 256) {
@@ -314,7 +320,7 @@ __global__ __launch_bounds__(256 * NT) void wgrad_tile_kernel(WgParams p) {
     // settle every compiler-tracked LDS read here, so that no compiler-inserted wait lands inside
     // the hand-counted pipeline below
 #pragma unroll
-    for (int k = 0; k < TP / 16; ++k) { pin1(ptv[k][0]); pin1(ptv[k][1]); }
+    for (int k = 0; k < KS; ++k) { pin1(ptv[k][0]); pin1(ptv[k][1]); }
 #pragma unroll
     for (int s2 = 0; s2 < NZS; ++s2)
 #pragma unroll
@@ -327,7 +333,7 @@ __global__ __launch_bounds__(256 * NT) void wgrad_tile_kernel(WgParams p) {
     }
 
     // lane-constant parts of the operand addresses
-    const unsigned zlane = lds_off(zs_base(buf, 0)) + (kb * 8 + eprime) * ROWB + chq * 2;
+    const unsigned zlane = lds_off(zs_base(buf, 0)) + (kbeg * 16 + kb * 8 + eprime) * ROWB + chq * 2;
     const unsigned xlane = lds_off(xs_base(buf, 0)) + chq * 2;
 
     auto issue_g0 = [&](int k, int set) {
@@ -375,23 +381,45 @@ __global__ __launch_bounds__(256 * NT) void wgrad_tile_kernel(WgParams p) {
     issue_g0(0, 0);
     issue_g1(0, 0);
 #pragma unroll
-    for (int k = 0; k < TP / 16; ++k) {
+    for (int k = 0; k < KS; ++k) {
       const int set = k & 1;
       wait_lgkm<N1>();                       // group 0 of step k is in (the youngest N1 reads are group 1)
       mma(set, 0, H0);
-      if (k + 1 < TP / 16) { issue_g0(k + 1, set ^ 1); wait_lgkm<N0>(); }
+      if (k + 1 < KS) { issue_g0(k + 1, set ^ 1); wait_lgkm<N0>(); }
       else wait_lgkm<0>();                   // group 1 of step k is in
       mma(set, H0, NF);
-      if (k + 1 < TP / 16) issue_g1(k + 1, set ^ 1);
+      if (k + 1 < KS) issue_g1(k + 1, set ^ 1);
     }
   }
 
+  if (KSPLIT) {
+    // the upper-half group hands its sums to the lower-half group through LDS (stage 0 is free now)
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem) + (wave & 3) * (NA * NB * 16 * 64) + lane;
+    if (th == 1) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) red[((b * NA + a) * 16 + e) * 64] = acc[0][b][a][e];
+    }
+    __syncthreads();
+    if (th == 0) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[0][b][a][e] += red[((b * NA + a) * 16 + e) * 64];
+    }
+  }
   // ---- epilogue: partial dw' ------------------------------------------------------------------
   // accumulator element e of lane l: ci row 8*(e/4) + 4*(l/32) + e%4, co column l%32
 #pragma unroll
   for (int t = 0; t < TH; ++t) {
     const int tap = tapno[t];
-    if (tap < 0) continue;
+    if (tap < 0 || (KSPLIT && th != 0)) continue;
 #pragma unroll
     for (int a = 0; a < NA; ++a) {
       const int co = co0 + (wco + a) * 32 + (lane & 31);
@@ -492,7 +520,7 @@ WgPlan make_plan(const Geom& g, WgParams* pp) {
   if (!base_params(g, &p)) return pl;
   const int taps = g.kH * g.kW;
   // accumulator shape by window size and channel counts
-  if (taps == 1) { pl.tpb = 1; pl.na = g.Cout > 64 ? 2 : 1; pl.nb = g.Cin > 64 ? 2 : 1; pl.nt = 1; }
+  if (taps == 1) { pl.tpb = 1; pl.na = g.Cout > 64 ? 2 : 1; pl.nb = g.Cin > 64 ? 2 : 1; pl.nt = 2; }   // eight waves: two pixel halves
   else if (taps <= 3) { pl.tpb = 3; pl.na = g.Cout > 64 ? 2 : 1; pl.nb = 1; pl.nt = 1; }
   else { pl.tpb = 9; pl.na = g.Cout > 64 ? 2 : 1; pl.nb = 1; pl.nt = 2; }   // eight waves: 5 + 4 taps
   // every pixel split writes a full fp32 copy of dw': keep that traffic near the size of the inputs
@@ -566,7 +594,7 @@ hipError_t launch_wgrad_tile(const Geom& g, const void* x, const void* dz, float
 #define CASE(T, A, B, W) \
   if (pl.tpb == T && pl.na == A && pl.nb == B && pl.nt == W) return launch_inst<T, A, B, W>(p, pl, st);
   CASE(9, 1, 1, 2) CASE(9, 2, 1, 2) CASE(3, 1, 1, 1) CASE(3, 2, 1, 1)
-  CASE(1, 2, 2, 1) CASE(1, 1, 2, 1) CASE(1, 2, 1, 1) CASE(1, 1, 1, 1)
+  CASE(1, 2, 2, 2) CASE(1, 1, 2, 2) CASE(1, 2, 1, 2) CASE(1, 1, 1, 2)
 #undef CASE
   return hipErrorInvalidValue;
 }
