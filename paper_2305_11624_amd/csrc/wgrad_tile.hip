@@ -117,8 +117,9 @@ __device__ __forceinline__ bf16x8 join(s16x4 a, s16x4 b) {
 }
 
 // TPB taps per workgroup.  Waves 0..3 form a 2x2 grid over the channel tile, each owning NA
-// co-subtiles x NB ci-subtiles (32 channels each); with NT = 2 a second group of four waves takes
-// the upper half of the taps, so eight waves share one LDS tile and hold twice the accumulators.
+// co-subtiles x NB ci-subtiles (32 channels each); with NT > 1 further groups of four waves take
+// the following taps, so eight or twelve waves share one LDS tile, hold more accumulators and -- what
+// matters most -- each hand the memory pipe fewer of the tile's copies.
 // A single tap (1x1 windows) with NT = 2: the second group takes the upper half of every tile's pixels
 // instead and the two groups add their accumulators through LDS at the end -- what eight waves buy
 // there is the copies: each wave hands the memory pipe half as many.
@@ -522,7 +523,7 @@ WgPlan make_plan(const Geom& g, WgParams* pp) {
   // accumulator shape by window size and channel counts
   if (taps == 1) { pl.tpb = 1; pl.na = g.Cout > 64 ? 2 : 1; pl.nb = g.Cin > 64 ? 2 : 1; pl.nt = 2; }   // eight waves: two pixel halves
   else if (taps <= 3) { pl.tpb = 3; pl.na = g.Cout > 64 ? 2 : 1; pl.nb = 1; pl.nt = 1; }
-  else { pl.tpb = 9; pl.na = g.Cout > 64 ? 2 : 1; pl.nb = 1; pl.nt = 2; }   // eight waves: 5 + 4 taps
+  else { pl.tpb = 9; pl.na = g.Cout > 64 ? 2 : 1; pl.nb = 1; pl.nt = 3; }   // twelve waves: 3 + 3 + 3 taps
   // every pixel split writes a full fp32 copy of dw': keep that traffic near the size of the inputs
   const size_t copy_bytes = (size_t)g.Cout * g.K * 4;
   const size_t in_bytes = ((size_t)g.M * g.Cout + (size_t)g.N * g.Hin * g.Win * g.Cin) * 2;
@@ -593,7 +594,7 @@ hipError_t launch_wgrad_tile(const Geom& g, const void* x, const void* dz, float
   p.x = (const bf16_t*)x; p.dz = (const bf16_t*)dz; p.part = dwf_part; p.r_part = r_part;
 #define CASE(T, A, B, W) \
   if (pl.tpb == T && pl.na == A && pl.nb == B && pl.nt == W) return launch_inst<T, A, B, W>(p, pl, st);
-  CASE(9, 1, 1, 2) CASE(9, 2, 1, 2) CASE(3, 1, 1, 1) CASE(3, 2, 1, 1)
+  CASE(9, 1, 1, 3) CASE(9, 2, 1, 3) CASE(3, 1, 1, 1) CASE(3, 2, 1, 1)
   CASE(1, 2, 2, 2) CASE(1, 1, 2, 2) CASE(1, 2, 1, 2) CASE(1, 1, 1, 2)
 #undef CASE
   return hipErrorInvalidValue;
