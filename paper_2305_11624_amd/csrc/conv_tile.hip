@@ -614,6 +614,7 @@ TilePlan make_plan(TileParams& p) {
   pl.nch = p.R > 64 ? 4 : 2;
   // Candidate shapes (waves, channel groups, channels per chunk):
   //   (8,1): 256 pixels, eight waves -- two per SIMD hide each other's scalar work; many pixels.
+  //   (16,1): 512 pixels, whole-row tiles only.
   //   (4,1): 128 pixels, four waves.
   //   (4,2): 64 pixels, the four waves split the 128 channels two ways -- a small pixel tile that still
   //          gives every wave a 32 x 64 block; deep reductions over few pixels (no split sums up to
@@ -628,12 +629,26 @@ TilePlan make_plan(TileParams& p) {
   static const Cand few[] = {{4, 2, 64}, {4, 2, 32}, {4, 1, 64}, {4, 1, 32}, {8, 1, 64}, {8, 1, 32}};
   constexpr int NCAND = 6;
   {
-    TileParams q = p;
-    const size_t lds = p.C >= 64 ? plan_lds(q, 8, 1, pl.nch, 64, true) : 0;
-    if (lds != 0 && lds <= LDS_USABLE && q.ksplit == 1 &&
-        (long long)q.N * q.tiles_per_image * ceil_div(q.R, pl.nch * 32) >= 160) {
-      p = q;
-      pl.nw = 8; pl.nwc = 1; pl.cb = 64; pl.lds = lds; pl.hps = p.hps;
+    // Whole-row tiles of 8 or 16 waves.  Workgroups of this size run one per CU, in rounds; a round costs a
+    // fixed start-up and drain (the tile's copies and stores go at memory speed with the matrix pipe idle)
+    // plus its steps, which take twice as long with four waves per SIMD as with two -- so the larger tile
+    // wins where it saves rounds (N = 32, 56 x 56: 224 workgroups in one round instead of 448 in two).
+    TileParams best{};
+    size_t best_lds = 0;
+    long long best_cost = 0;
+    int best_nw = 0;
+    for (int nw : {8, 16}) {
+      TileParams q = p;
+      const size_t lds = p.C >= 64 ? plan_lds(q, nw, 1, pl.nch, 64, true) : 0;
+      const long long wgs = (long long)q.N * q.tiles_per_image * ceil_div(q.R, pl.nch * 32);
+      if (lds == 0 || lds > LDS_USABLE || q.ksplit != 1 || wgs < 160) continue;
+      const long long steps = (long long)p.kH * p.kW * (p.C / 64);
+      const long long cost = ceil_div((int)wgs, 256) * (8000 + steps * 260 * (nw / 4));
+      if (best_nw == 0 || cost < best_cost) { best = q; best_lds = lds; best_cost = cost; best_nw = nw; }
+    }
+    if (best_nw != 0) {
+      p = best;
+      pl.nw = best_nw; pl.nwc = 1; pl.cb = 64; pl.lds = best_lds; pl.hps = p.hps;
       p.ntr = ceil_div(p.R, pl.nch * 32);
       pl.ok = true;
       return pl;
@@ -692,7 +707,7 @@ hipError_t launch_plan(const TileParams& p, const TilePlan& pl, hipStream_t st) 
   CASE(NWV, WC, NC, CBV, 4) CASE(NWV, WC, NC, CBV, 6) CASE(NWV, WC, NC, CBV, 8)
   CASES(4, 1, 2, 32) CASES(4, 1, 2, 64) CASES(4, 1, 4, 32) CASES(4, 1, 4, 64)
   CASES(8, 1, 2, 32) CASES(8, 1, 2, 64) CASES(8, 1, 4, 32) CASES(8, 1, 4, 64)
-  CASES(4, 2, 4, 32) CASES(4, 2, 4, 64)
+  CASES(4, 2, 4, 32) CASES(4, 2, 4, 64) CASES(16, 1, 2, 64) CASES(16, 1, 4, 64)
 #undef CASES
 #undef CASE
   return hipErrorInvalidValue;
