@@ -639,6 +639,7 @@ TilePlan make_plan(TileParams& p) {
     int best_nw = 0;
     for (int nw : {8, 16}) {
       TileParams q = p;
+      if (nw == 16 && pl.nch != 2) continue;   // sixteen waves are built for 64 output channels per workgroup
       const size_t lds = p.C >= 64 ? plan_lds(q, nw, 1, pl.nch, 64, true) : 0;
       const long long wgs = (long long)q.N * q.tiles_per_image * ceil_div(q.R, pl.nch * 32);
       if (lds == 0 || lds > LDS_USABLE || q.ksplit != 1 || wgs < 160) continue;
@@ -707,7 +708,7 @@ hipError_t launch_plan(const TileParams& p, const TilePlan& pl, hipStream_t st) 
   CASE(NWV, WC, NC, CBV, 4) CASE(NWV, WC, NC, CBV, 6) CASE(NWV, WC, NC, CBV, 8)
   CASES(4, 1, 2, 32) CASES(4, 1, 2, 64) CASES(4, 1, 4, 32) CASES(4, 1, 4, 64)
   CASES(8, 1, 2, 32) CASES(8, 1, 2, 64) CASES(8, 1, 4, 32) CASES(8, 1, 4, 64)
-  CASES(4, 2, 4, 32) CASES(4, 2, 4, 64) CASES(16, 1, 2, 64) CASES(16, 1, 4, 64)
+  CASES(4, 2, 4, 32) CASES(4, 2, 4, 64) CASES(16, 1, 2, 64)
 #undef CASES
 #undef CASE
   return hipErrorInvalidValue;
