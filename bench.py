@@ -39,7 +39,7 @@ WORKLOADS = {
 MEASURED_TRAFFIC_BYTES = {
     # fetched + written bytes per launch
     "fprop@c2b": 26.0e6 + 3.2e6, "dgrad@c2b": 26.0e6 + 3.2e6, "wgrad@c2b": 29.1e6 + 37.8e6,
-    "fprop@c2a": 19.5e6 + 12.9e6, "dgrad@c2a": 19.5e6 + 12.9e6, "wgrad@c2a": 29.8e6 + 29.6e6,
+    "fprop@c2a": 16.3e6 + 12.9e6, "dgrad@c2a": 16.3e6 + 12.9e6, "wgrad@c2a": 29.8e6 + 29.6e6,
 }
 
 
