@@ -22,6 +22,10 @@
  *       fold, one convolution, six backward equations.  Present only so the
  *       test-suite can assert Tune == Eval (Sec. 3.4.1) inside the oracle.
  *
+ * The same two routes exist for the TransposedConv-BN block (end of file), pinned
+ * by the adjoint identity against the convolution above, a library cross-check,
+ * finite differences and Tune == Eval.
+ *
  * Parity pins (tests marked "not gpu"): library conv2d+batch_norm with autograd
  * on the CPU as an independent special-case check, 1x1 == matrix product,
  * delta kernel, single-pixel impulse response, central finite differences for
@@ -262,6 +266,214 @@ void cbo_tune_bwd(const cb_dims *d, const double *X, const double *W, const doub
       dW[o * row + t] = s * dWf[o * row + t];
       dot += dWf[o * row + t] * W[o * row + t];
     }
+    const double r = dbeta[o];
+    if (db) db[o] = s * r;
+    dgamma[o] = dot / sd + r * ((b ? b[o] : 0.0) - mu[o]) / sd;
+  }
+}
+
+/* ------------------------------------------------- transposed convolution --- */
+/*
+ * TransposedConv-BN block (Sec. 3.2.1, closing remark: the associative law
+ * gamma . (w (*) X) = (gamma . w) (*) X also holds for transposed convolution,
+ * so Tune mode applies to it).  The paper gives no formula for the operator;
+ * the usual definition is taken: a transposed convolution is the adjoint of the
+ * cross-correlation of Sec. 3.1 with respect to its input.  The weight is
+ * W[Cin][Cout][kH][kW], the BatchNorm acts on the Cout output channels, and
+ *   Y[n,o,h*sh - ph + i, w*sw - pw + j] += W[c,o,i,j] * X[n,c,h,w]   (+ b[o]),
+ * with Hout = (Hin-1) sh - 2 ph + kH (no output padding, dilation 1, groups 1).
+ * The cb_dims fields keep their names: Cin/Hin/Win describe X, Cout the output.
+ */
+int cbo_thout(const cb_dims *d) { return (d->Hin - 1) * d->sh - 2 * d->ph + d->kH; }
+int cbo_twout(const cb_dims *d) { return (d->Win - 1) * d->sw - 2 * d->pw + d->kW; }
+
+#define TWI(c, o, i, j) ((((size_t)(c) * d->Cout + (o)) * d->kH + (i)) * d->kW + (j))
+
+/* Y = transposed convolution of X with W (+ b): every input pixel spreads a
+ * kernel-shaped patch into the output.  One thread owns one (n, o) plane. */
+void cbo_tconv_fwd(const cb_dims *d, const double *X, const double *W, const double *b, double *Y) {
+  const int Ho = cbo_thout(d), Wo = cbo_twout(d);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int o = 0; o < d->Cout; ++o) {
+      for (int ho = 0; ho < Ho; ++ho)
+        for (int wo = 0; wo < Wo; ++wo) Y[YI(n, o, ho, wo)] = b ? b[o] : 0.0;
+      for (int c = 0; c < d->Cin; ++c)
+        for (int h = 0; h < d->Hin; ++h)
+          for (int w = 0; w < d->Win; ++w) {
+            const double x = X[XI(n, c, h, w)];
+            for (int i = 0; i < d->kH; ++i) {
+              const int ho = h * d->sh - d->ph + i;
+              if (ho < 0 || ho >= Ho) continue;
+              for (int j = 0; j < d->kW; ++j) {
+                const int wo = w * d->sw - d->pw + j;
+                if (wo < 0 || wo >= Wo) continue;
+                Y[YI(n, o, ho, wo)] += W[TWI(c, o, i, j)] * x;
+              }
+            }
+          }
+    }
+}
+
+/* dJ/dX of the transposed convolution: each X[n,c,h,w] entered Y[n,o,ho,wo] with
+ * weight W[c,o,i,j], so it collects W * dY over the same index pairs. */
+void cbo_tconv_dgrad(const cb_dims *d, const double *W, const double *dY, double *dX) {
+  const int Ho = cbo_thout(d), Wo = cbo_twout(d);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int c = 0; c < d->Cin; ++c)
+      for (int h = 0; h < d->Hin; ++h)
+        for (int w = 0; w < d->Win; ++w) {
+          double acc = 0.0;
+          for (int o = 0; o < d->Cout; ++o)
+            for (int i = 0; i < d->kH; ++i) {
+              const int ho = h * d->sh - d->ph + i;
+              if (ho < 0 || ho >= Ho) continue;
+              for (int j = 0; j < d->kW; ++j) {
+                const int wo = w * d->sw - d->pw + j;
+                if (wo < 0 || wo >= Wo) continue;
+                acc += W[TWI(c, o, i, j)] * dY[YI(n, o, ho, wo)];
+              }
+            }
+          dX[XI(n, c, h, w)] = acc;
+        }
+}
+
+/* dJ/dW of the transposed convolution, summed over the batch and all positions. */
+void cbo_tconv_wgrad(const cb_dims *d, const double *X, const double *dY, double *dW) {
+  const int Ho = cbo_thout(d), Wo = cbo_twout(d);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int c = 0; c < d->Cin; ++c)
+    for (int o = 0; o < d->Cout; ++o)
+      for (int i = 0; i < d->kH; ++i)
+        for (int j = 0; j < d->kW; ++j) {
+          double acc = 0.0;
+          for (int n = 0; n < d->N; ++n)
+            for (int h = 0; h < d->Hin; ++h) {
+              const int ho = h * d->sh - d->ph + i;
+              if (ho < 0 || ho >= Ho) continue;
+              for (int w = 0; w < d->Win; ++w) {
+                const int wo = w * d->sw - d->pw + j;
+                if (wo < 0 || wo >= Wo) continue;
+                acc += X[XI(n, c, h, w)] * dY[YI(n, o, ho, wo)];
+              }
+            }
+          dW[TWI(c, o, i, j)] = acc;
+        }
+}
+
+/* Per-channel sum of A (times T if given) over a [N][Cout][Ho][Wo] tensor. */
+static void plane_sum(const cb_dims *d, int Ho, int Wo, const double *A, const double *T, double *out) {
+#pragma omp parallel for schedule(static)
+  for (int o = 0; o < d->Cout; ++o) {
+    double acc = 0.0;
+    for (int n = 0; n < d->N; ++n)
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          acc += T ? A[idx] * T[idx] : A[idx];
+        }
+    out[o] = acc;
+  }
+}
+
+/* Eval mode of the transposed block: Y = tconv(X, W) + b kept, then the frozen
+ * BatchNorm of Sec. 3.1 on the Cout channels.  This is the definition. */
+void cbo_teval_fwd(const cb_dims *d, const double *X, const double *W, const double *b,
+                   const double *gamma, const double *beta, const double *mu, const double *var,
+                   double eps, double *Y, double *Z) {
+  const int Ho = cbo_thout(d), Wo = cbo_twout(d);
+  cbo_tconv_fwd(d, X, W, b, Y);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int o = 0; o < d->Cout; ++o) {
+      const double sd = sqrt(var[o] + eps);
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          Z[idx] = gamma[o] * ((Y[idx] - mu[o]) / sd) + beta[o];
+        }
+    }
+}
+
+/* Eval backward of the transposed block (Table 2 row "Eval" with the transposed
+ * operator in place of the convolution).  scratch_dY: N*Cout*Hout*Wout doubles. */
+void cbo_teval_bwd(const cb_dims *d, const double *X, const double *W, const double *gamma,
+                   const double *mu, const double *var, double eps, const double *Y,
+                   const double *G, double *scratch_dY, double *dX, double *dW, double *db,
+                   double *dgamma, double *dbeta) {
+  const int Ho = cbo_thout(d), Wo = cbo_twout(d);
+  double *dY = scratch_dY;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int o = 0; o < d->Cout; ++o) {
+      const double sd = sqrt(var[o] + eps);
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          dY[idx] = gamma[o] / sd * G[idx];
+        }
+    }
+  if (dX) cbo_tconv_dgrad(d, W, dY, dX);
+  cbo_tconv_wgrad(d, X, dY, dW);
+  if (db) plane_sum(d, Ho, Wo, dY, NULL, db);
+#pragma omp parallel for schedule(static)
+  for (int o = 0; o < d->Cout; ++o) {
+    const double sd = sqrt(var[o] + eps);
+    double acc = 0.0;
+    for (int n = 0; n < d->N; ++n)
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          acc += G[idx] * ((Y[idx] - mu[o]) / sd);
+        }
+    dgamma[o] = acc;
+  }
+  plane_sum(d, Ho, Wo, G, NULL, dbeta);
+}
+
+/* Tune mode of the transposed block (Sec. 3.3 with the scale on the weight's
+ * output-channel index, which is its second one here): fold, one transposed
+ * convolution, and Table 2's "Tune" backward lines with the sums of <dW', w>
+ * running over (Cin, kH, kW) for each output channel. */
+void cbo_tfold(const cb_dims *d, const double *W, const double *b, const double *gamma,
+               const double *beta, const double *mu, const double *var, double eps, double *Wf,
+               double *bf) {
+  for (int o = 0; o < d->Cout; ++o) {
+    const double s = gamma[o] / sqrt(var[o] + eps);
+    for (int c = 0; c < d->Cin; ++c)
+      for (int i = 0; i < d->kH; ++i)
+        for (int j = 0; j < d->kW; ++j) Wf[TWI(c, o, i, j)] = s * W[TWI(c, o, i, j)];
+    bf[o] = ((b ? b[o] : 0.0) - mu[o]) * s + beta[o];
+  }
+}
+
+void cbo_ttune_fwd(const cb_dims *d, const double *X, const double *W, const double *b,
+                   const double *gamma, const double *beta, const double *mu, const double *var,
+                   double eps, double *Wf, double *bf, double *Z) {
+  cbo_tfold(d, W, b, gamma, beta, mu, var, eps, Wf, bf);
+  cbo_tconv_fwd(d, X, Wf, bf, Z);
+}
+
+void cbo_ttune_bwd(const cb_dims *d, const double *X, const double *W, const double *b,
+                   const double *gamma, const double *mu, const double *var, double eps,
+                   const double *Wf, const double *G, double *dX, double *dWf, double *dW,
+                   double *db, double *dgamma, double *dbeta) {
+  const int Ho = cbo_thout(d), Wo = cbo_twout(d);
+  if (dX) cbo_tconv_dgrad(d, Wf, G, dX);
+  cbo_tconv_wgrad(d, X, G, dWf);
+  plane_sum(d, Ho, Wo, G, NULL, dbeta);
+  for (int o = 0; o < d->Cout; ++o) {
+    const double sd = sqrt(var[o] + eps);
+    const double s = gamma[o] / sd;
+    double dot = 0.0;
+    for (int c = 0; c < d->Cin; ++c)
+      for (int i = 0; i < d->kH; ++i)
+        for (int j = 0; j < d->kW; ++j) {
+          const size_t t = TWI(c, o, i, j);
+          dW[t] = s * dWf[t];
+          dot += dWf[t] * W[t];
+        }
     const double r = dbeta[o];
     if (db) db[o] = s * r;
     dgamma[o] = dot / sd + r * ((b ? b[o] : 0.0) - mu[o]) / sd;

@@ -172,3 +172,101 @@ def tune_bwd(d, X, W, b, gamma, mu, var, eps, Wf, G, need_dx=True):
                          C.c_double(eps), _p(Wf), _p(G), _p(dX), _p(dWf), _p(dW), _p(db),
                          _p(dgamma), _p(dbeta))
     return dict(dX=dX, dWf=dWf, dW=dW, db=db, dgamma=dgamma, dbeta=dbeta)
+
+
+# ---- TransposedConv-BN block (Sec. 3.2.1, closing remark).  W is [Cin, Cout, kH, kW]. ----
+
+def tconv_out_hw(d: Dims):
+    lib = _load()
+    cd = d.c()
+    lib.cbo_thout.restype = C.c_int
+    lib.cbo_twout.restype = C.c_int
+    return int(lib.cbo_thout(C.byref(cd))), int(lib.cbo_twout(C.byref(cd)))
+
+
+def _tshapes(d: Dims):
+    ho, wo = tconv_out_hw(d)
+    return ((d.N, d.Cin, d.Hin, d.Win), (d.Cin, d.Cout, d.kH, d.kW), (d.N, d.Cout, ho, wo),
+            (d.Cout,))
+
+
+def tconv_fwd(d, X, W, b=None):
+    xs, ws, ys, vs = _tshapes(d)
+    X, W, b = _f64(X, xs), _f64(W, ws), _f64(b, vs)
+    Y = np.empty(ys)
+    cd = d.c()
+    _load().cbo_tconv_fwd(C.byref(cd), _p(X), _p(W), _p(b), _p(Y))
+    return Y
+
+
+def tconv_dgrad(d, W, dY):
+    xs, ws, ys, _ = _tshapes(d)
+    W, dY = _f64(W, ws), _f64(dY, ys)
+    dX = np.empty(xs)
+    cd = d.c()
+    _load().cbo_tconv_dgrad(C.byref(cd), _p(W), _p(dY), _p(dX))
+    return dX
+
+
+def tconv_wgrad(d, X, dY):
+    xs, ws, ys, _ = _tshapes(d)
+    X, dY = _f64(X, xs), _f64(dY, ys)
+    dW = np.empty(ws)
+    cd = d.c()
+    _load().cbo_tconv_wgrad(C.byref(cd), _p(X), _p(dY), _p(dW))
+    return dW
+
+
+def teval_fwd(d, X, W, b, gamma, beta, mu, var, eps):
+    """Returns (Y, Z) of the transposed block in Eval mode."""
+    xs, ws, ys, vs = _tshapes(d)
+    X, W, b = _f64(X, xs), _f64(W, ws), _f64(b, vs)
+    gamma, beta, mu, var = (_f64(v, vs) for v in (gamma, beta, mu, var))
+    Y, Z = np.empty(ys), np.empty(ys)
+    cd = d.c()
+    _load().cbo_teval_fwd(C.byref(cd), _p(X), _p(W), _p(b), _p(gamma), _p(beta), _p(mu), _p(var),
+                          C.c_double(eps), _p(Y), _p(Z))
+    return Y, Z
+
+
+def teval_bwd(d, X, W, b, gamma, mu, var, eps, Y, G, need_dx=True):
+    xs, ws, ys, vs = _tshapes(d)
+    X, W, Y, G = _f64(X, xs), _f64(W, ws), _f64(Y, ys), _f64(G, ys)
+    gamma, mu, var = (_f64(v, vs) for v in (gamma, mu, var))
+    dX = np.empty(xs) if need_dx else None
+    dW = np.empty(ws)
+    db = np.empty(vs) if b is not None else None
+    dgamma, dbeta = np.empty(vs), np.empty(vs)
+    scratch = np.empty(ys)
+    cd = d.c()
+    _load().cbo_teval_bwd(C.byref(cd), _p(X), _p(W), _p(gamma), _p(mu), _p(var), C.c_double(eps),
+                          _p(Y), _p(G), _p(scratch), _p(dX), _p(dW), _p(db), _p(dgamma), _p(dbeta))
+    return dict(dX=dX, dW=dW, db=db, dgamma=dgamma, dbeta=dbeta)
+
+
+def ttune_fwd(d, X, W, b, gamma, beta, mu, var, eps):
+    """Returns (Wf, bf, Z) of the transposed block in Tune mode."""
+    xs, ws, ys, vs = _tshapes(d)
+    X, W, b = _f64(X, xs), _f64(W, ws), _f64(b, vs)
+    gamma, beta, mu, var = (_f64(v, vs) for v in (gamma, beta, mu, var))
+    Wf, bf, Z = np.empty(ws), np.empty(vs), np.empty(ys)
+    cd = d.c()
+    _load().cbo_ttune_fwd(C.byref(cd), _p(X), _p(W), _p(b), _p(gamma), _p(beta), _p(mu), _p(var),
+                          C.c_double(eps), _p(Wf), _p(bf), _p(Z))
+    return Wf, bf, Z
+
+
+def ttune_bwd(d, X, W, b, gamma, mu, var, eps, Wf, G, need_dx=True):
+    xs, ws, ys, vs = _tshapes(d)
+    X, W, Wf, G = _f64(X, xs), _f64(W, ws), _f64(Wf, ws), _f64(G, ys)
+    b = _f64(b, vs)
+    gamma, mu, var = (_f64(v, vs) for v in (gamma, mu, var))
+    dX = np.empty(xs) if need_dx else None
+    dWf, dW = np.empty(ws), np.empty(ws)
+    db = np.empty(vs) if b is not None else None
+    dgamma, dbeta = np.empty(vs), np.empty(vs)
+    cd = d.c()
+    _load().cbo_ttune_bwd(C.byref(cd), _p(X), _p(W), _p(b), _p(gamma), _p(mu), _p(var),
+                          C.c_double(eps), _p(Wf), _p(G), _p(dX), _p(dWf), _p(dW), _p(db),
+                          _p(dgamma), _p(dbeta))
+    return dict(dX=dX, dWf=dWf, dW=dW, db=db, dgamma=dgamma, dbeta=dbeta)
