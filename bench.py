@@ -32,7 +32,12 @@ WORKLOADS = {
     "c3": ["c3a", "c3b"], "c3a": ["c3a"], "c3b": ["c3b"],
     "all": ["c1", "c2a", "c2b", "c3a", "c3b"],
     "resnet50": [],          # the whole 53-block backbone, Tune vs Eval (time and activation memory)
+    "tconv": [],             # TransposedConv-BN up-sampling blocks in Tune mode
 }
+
+# 2x up-sampling blocks of an encoder-decoder network (stand-ins for the paper's UNet rows): name, N, Cin, Hin,
+# Win, Cout, window, stride, padding
+TCONV_SHAPES = [("up_k2", 32, 256, 28, 28, 128, 2, 2, 0), ("up_k4", 32, 512, 14, 14, 256, 4, 2, 1)]
 
 # HBM bytes per launch of the dominant kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this script (summaries under profiles/); None where not measured.
@@ -299,6 +304,96 @@ def main_backbone(a):
     print(json.dumps(line))
 
 
+def main_tconv(a):
+    """TransposedConv-BN blocks in Tune mode: whole-step time, the three convolution kernels timed one by one
+    through the step entry points of the convolution each block is the adjoint of, and the CPU oracle."""
+    import torch
+    import oracle
+    from paper_2305_11624_amd import binding as B
+    from paper_2305_11624_amd import synth
+    from paper_2305_11624_amd.runner import TconvRun
+    B.lib()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    shapes = [synth.BlockShape(n, N, ci, h, w, co, k, st, pd, "bf16", 90 + i)
+              for i, (n, N, ci, h, w, co, k, st, pd) in enumerate(TCONV_SHAPES)]
+    flops = [3.0 * 2.0 * s.N * s.Hin * s.Win * s.Cin * s.Cout * s.k * s.k for s in shapes]
+    inputs = [synth.make_tconv_inputs(s) for s in shapes]
+    pools = []
+    for inp in inputs:
+        first = TconvRun(inp)
+        count = max(2, min(32, -(-a.pool_mb * (1 << 20) // max(1, tensor_bytes(first)))))
+        pools.append([first] + [TconvRun(inp) for _ in range(count - 1)])
+    ms = time_steps(pools, a.steps, a.warmup)
+    per_shape = {}
+    best = None
+    for s, fl, pool in zip(shapes, flops, pools):
+        r0 = pool[0]
+        ho, wo = synth.tconv_out(s)
+        d = B.make_desc(s.N, s.Cout, ho, wo, s.Cin, s.k, s.k, s.stride, s.pad, dtype=B.BF16)   # the adjoint convolution
+        P = s.Cin * s.Cout * s.k * s.k
+        dev = r0.x.device
+        w_swap = torch.zeros(P, dtype=r0.dt, device=dev)
+        ws_f = torch.empty(max(16, B.convbn_conv_workspace_bytes(d, B.PASS_FWD)), dtype=torch.uint8, device=dev)
+        ws_b = torch.empty(max(16, B.convbn_conv_workspace_bytes(d, B.PASS_BWD)), dtype=torch.uint8, device=dev)
+        part = torch.empty(B.convbn_wgrad_parts(d) * P, dtype=torch.float32, device=dev)
+        r0.forward()                                            # fills w_folded (read by the input-gradient pass)
+        calls = {
+            "forward (transposed conv)": lambda r: B.convbn_conv_dgrad(d, r.x, w_swap, r.z, ws_b),
+            "input gradient (conv)": lambda r: B.convbn_conv_fprop(d, r.dz, r0.w_folded, None, r.dx, ws_f),
+            "weight gradient": lambda r: B.convbn_conv_wgrad(d, r.dz, r.x, part, None, ws_b),
+        }
+        kt = {}
+        for name, fn in calls.items():
+            for i in range(min(3, len(pool))):
+                fn(pool[i])
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(a.kernel_reps):
+                fn(pool[i % len(pool)])
+            e1.record()
+            torch.cuda.synchronize()
+            kt[name] = e0.elapsed_time(e1) / a.kernel_reps
+            if best is None or kt[name] > best[2]:
+                best = (s.name, name, kt[name], fl / 3.0)
+        per_shape[s.name] = {"kernel_ms": {k: round(v, 5) for k, v in kt.items()},
+                             "conv_tflops": {k: round(fl / 3.0 / (v * 1e-3) / 1e12, 1) for k, v in kt.items()}}
+    achieved = best[3] / (best[2] * 1e-3) / 1e12
+    line = {
+        "metric": "TransposedConv-BN Tune fwd+bwd TFLOP/s", "value": sum(flops) / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "TransposedConv-BN up-sampling blocks, bf16: " + ", ".join(
+            f"{s.name} x[{s.N},{s.Cin},{s.Hin},{s.Win}] {s.k}x{s.k} {s.Cin}->{s.Cout} s{s.stride} p{s.pad}"
+            for s in shapes), "mode": "tune", "layout": "NHWC", "step": "fwd+bwd of every shape"},
+        "per_shape": per_shape,
+        "roofline": {"bound": "mfma", "kernel": f"{best[1]} @ {best[0]}", "achieved": achieved,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                     "avg_launch_ms": best[2], "traffic": None},
+    }
+    if not a.no_cpu_baseline:
+        cores = oracle.num_threads()
+        fl, secs, desc = 0.0, 0.0, []
+        for s, f1 in zip(shapes, flops):
+            n = int(max(1, min(s.N, a.cpu_seconds / len(shapes) * 0.6e9 * cores / (f1 / s.N))))
+            inp = synth.make_tconv_inputs(replace(s, N=n))
+            d = oracle.Dims(n, s.Cin, s.Hin, s.Win, s.Cout, s.k, s.k, s.stride, s.stride, s.pad, s.pad)
+            f = lambda t: None if t is None else t.double().numpy()
+            v = {k: f(inp[k]) for k in ("x", "W", "b", "gamma", "beta", "rmean", "rvar", "dy")}
+            t0 = time.perf_counter()
+            Y, _ = oracle.teval_fwd(d, v["x"], v["W"], v["b"], v["gamma"], v["beta"], v["rmean"], v["rvar"], inp["eps"])
+            oracle.teval_bwd(d, v["x"], v["W"], v["b"], v["gamma"], v["rmean"], v["rvar"], inp["eps"], Y, v["dy"])
+            secs += time.perf_counter() - t0
+            fl += f1 * n / s.N
+            desc.append(f"{s.name} with N={n} of {s.N}")
+        line["cpu_baseline"] = {"value": fl / secs / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+                                "sample": "one fwd+bwd of " + ", ".join(desc) + f" ({secs:.1f} s)"}
+    print(json.dumps(line))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -307,6 +402,8 @@ def main():
         sys.exit(2)
     if a.workload == "resnet50":
         return main_backbone(a)
+    if a.workload == "tconv":
+        return main_tconv(a)
     import torch
     from paper_2305_11624_amd import binding as B
     from paper_2305_11624_amd import synth

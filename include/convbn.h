@@ -138,6 +138,38 @@ convbn_status convbn_eval_bwd(const convbn_desc *desc, const void *x, const void
                               void *dW, float *db, float *dgamma, float *dbeta, void *ws,
                               size_t ws_bytes, void *stream);
 
+/* ---- TransposedConv-BN block in Tune mode ----------------------------------------
+ * Sec. 3.2.1 (last paragraph): scaling the weight along its output-channel index is
+ * associative with a transposed convolution as well, so Tune mode covers
+ * TransposedConv-BN blocks.  The operator is the adjoint of the convolution above with
+ * respect to its input (dilation 1, groups 1, no output padding):
+ *     Y[n, co, h sh - ph + i, w sw - pw + j] += W[ci, co, i, j] X[n, ci, h, w]   (+ b[co])
+ *     Hout = (Hin - 1) stride_h - 2 pad_h + kH, likewise Wout; BatchNorm over the Cout channels.
+ * The descriptor's fields keep their meaning (N, Cin, Hin, Win describe x; Cout, the
+ * window, stride and padding the operator).  Layout (channels-last as everywhere):
+ *     x, dx  [N][Hin][Win][Cin]        z, dz  [N][Hout][Wout][Cout]
+ *     W, dW, w_folded  [Cin][kH][kW][Cout]      (logical [Cin, Cout, kH, kW])
+ * Tune mode: w' = s w with s on the Cout index, b' as above; forward is ONE transposed
+ * convolution with (w', b'); backward is Table 2's "Tune" row with the transposed
+ * operator: dX = w' (*) dZ (a plain convolution), dw'[ci,co,i,j] = sum X dZ, r = sum dZ,
+ * dW = s dw', dgamma_co = (sum_{ci,i,j} dw' w + r (b - mu)) / sqrt(var + eps), dbeta = r,
+ * db = s r.  Arguments, NULL rules and error behaviour are those of convbn_tune_fwd /
+ * convbn_tune_bwd; w_folded (nullable) is w' in the order of W.  Shapes whose padding
+ * leaves no output are CONVBN_ERR_SHAPE. */
+int32_t convbn_tconv_hout(const convbn_desc *desc);
+int32_t convbn_tconv_wout(const convbn_desc *desc);
+/* pass: CONVBN_PASS_FWD / CONVBN_PASS_BWD.  0 for an invalid descriptor. */
+size_t convbn_tconv_workspace_bytes(const convbn_desc *desc, int pass);
+convbn_status convbn_tconv_tune_fwd(const convbn_desc *desc, const void *x, const void *W,
+                                    const float *b, const float *gamma, const float *beta,
+                                    const float *mean, const float *var, void *z, void *w_folded,
+                                    void *ws, size_t ws_bytes, void *stream);
+convbn_status convbn_tconv_tune_bwd(const convbn_desc *desc, const void *x, const void *W,
+                                    const float *b, const float *gamma, const float *mean,
+                                    const float *var, const void *w_folded, const void *dz,
+                                    void *dx, void *dW, float *db, float *dgamma, float *dbeta,
+                                    void *ws, size_t ws_bytes, void *stream);
+
 /* ---- The individual steps of the Tune-mode block (each is one kernel) -------------
  * convbn_tune_fwd is convbn_fold followed by convbn_conv_fprop; convbn_tune_bwd is
  * convbn_conv_dgrad, convbn_conv_wgrad and convbn_fold_back.  They are exported so that

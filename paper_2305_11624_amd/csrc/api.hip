@@ -215,12 +215,12 @@ hipError_t fprop_any(const Geom& g, int dtype, const void* x, const void* w_krsc
   return igemm_supported(g, dtype) ? launch_fprop_igemm(g, x, w_krsc, bias, z, st)
                                    : launch_fprop_direct(g, dtype, x, w_krsc, bias, z, st);
 }
-hipError_t dgrad_any(const Geom& g, int dtype, const void* dz, const void* w_crsk, void* dx,
+hipError_t dgrad_any(const Geom& g, int dtype, const void* dz, const void* w_crsk, const float* bias, void* dx,
                      float* scratch, hipStream_t st) {
-  if (pw_dgrad_supported(g, dtype)) return launch_dgrad_pw(g, dz, w_crsk, dx, st);
-  if (tile_dgrad_supported(g, dtype)) return launch_dgrad_tile(g, dz, w_crsk, dx, scratch, st);
-  return igemm_supported(g, dtype) ? launch_dgrad_igemm(g, dz, w_crsk, dx, st)
-                                   : launch_dgrad_direct(g, dtype, dz, w_crsk, dx, st);
+  if (pw_dgrad_supported(g, dtype)) return launch_dgrad_pw(g, dz, w_crsk, bias, dx, st);
+  if (tile_dgrad_supported(g, dtype)) return launch_dgrad_tile(g, dz, w_crsk, bias, dx, scratch, st);
+  return igemm_supported(g, dtype) ? launch_dgrad_igemm(g, dz, w_crsk, bias, dx, st)
+                                   : launch_dgrad_direct(g, dtype, dz, w_crsk, bias, dx, st);
 }
 
 #define TRY(expr)                       \
@@ -242,7 +242,7 @@ hipError_t run_fprop(const Geom& g, int dtype, const void* x, const void* w_krsc
 }
 hipError_t run_dgrad(const Geom& g, int dtype, const void* dz, const void* w_crsk, void* dx,
                      float* scratch, hipStream_t st) {
-  if (!needs_cin_pad(g, dtype)) return dgrad_any(g, dtype, dz, w_crsk, dx, scratch, st);
+  if (!needs_cin_pad(g, dtype)) return dgrad_any(g, dtype, dz, w_crsk, nullptr, dx, scratch, st);
   const Geom q = padded_geom(g);
   char* s = reinterpret_cast<char*>(scratch);
   void* wp = s; s += align_up((size_t)q.Cout * q.K * 2, 256);
@@ -250,7 +250,7 @@ hipError_t run_dgrad(const Geom& g, int dtype, const void* dz, const void* w_crs
   // [Cin][taps*Cout] -> [Cin_p][taps*Cout]: the extra rows are zero
   const size_t row = (size_t)g.kH * g.kW * g.Cout;
   TRY(launch_repitch(2, 1, (size_t)g.Cin * row, (size_t)q.Cin * row, w_crsk, wp, st));
-  TRY(dgrad_any(q, dtype, dz, wp, dxp, reinterpret_cast<float*>(s), st));
+  TRY(dgrad_any(q, dtype, dz, wp, nullptr, dxp, reinterpret_cast<float*>(s), st));
   return launch_repitch(2, (size_t)g.Min, q.Cin, g.Cin, dxp, dx, st);
 }
 // dw' partials and, when r_part != nullptr, the partial per-channel sums of dz.
@@ -273,6 +273,64 @@ hipError_t run_wgrad(const Geom& g, int dtype, const void* x, const void* dz, fl
   TRY(launch_repitch(2, (size_t)g.Min, g.Cin, q.Cin, x, xp, st));
   TRY(wgrad_any(q, dtype, xp, dz, pp, r_part, way, st));
   return launch_repitch(4, (size_t)way.nsplit * g.Cout * g.kH * g.kW, q.Cin, g.Cin, pp, part, st);
+}
+
+// ---- TransposedConv-BN block (Sec. 3.2.1) ----------------------------------------------------------
+// A transposed convolution is the adjoint of a convolution with the same window, stride and padding that
+// maps the block's OUTPUT (Cout channels, Hout x Wout) back to its input.  `g` is that convolution: the
+// block's forward pass is its input-gradient kernel, the block's input gradient its forward kernel, and
+// the weight gradient is its weight gradient with the two feature maps exchanged.
+convbn_status make_tgeom(const convbn_desc* d, Geom* g) {
+  if (!d) return fail(CONVBN_ERR_NULL, "descriptor is NULL");
+  if (d->N < 1 || d->Cin < 1 || d->Hin < 1 || d->Win < 1 || d->Cout < 1 || d->kH < 1 || d->kW < 1)
+    return fail(CONVBN_ERR_SHAPE, "non-positive dimension in descriptor");
+  if (d->stride_h < 1 || d->stride_w < 1) return fail(CONVBN_ERR_SHAPE, "stride must be >= 1");
+  if (d->pad_h < 0 || d->pad_w < 0) return fail(CONVBN_ERR_SHAPE, "padding must be >= 0");
+  const long long ho = (long long)(d->Hin - 1) * d->stride_h - 2LL * d->pad_h + d->kH;
+  const long long wo = (long long)(d->Win - 1) * d->stride_w - 2LL * d->pad_w + d->kW;
+  if (ho < 1 || wo < 1) return fail(CONVBN_ERR_SHAPE, "padding removes the whole output of the transposed convolution");
+  if (ho > 0x7fffffffLL || wo > 0x7fffffffLL) return fail(CONVBN_ERR_UNSUPPORTED, "output size overflows");
+  convbn_desc c = *d;
+  c.Cin = d->Cout; c.Cout = d->Cin; c.Hin = (int32_t)ho; c.Win = (int32_t)wo;
+  const convbn_status s = make_geom(&c, g);
+  if (s != CONVBN_OK) return s;
+  if (g->Hout != d->Hin || g->Wout != d->Win) return fail(CONVBN_ERR_SHAPE, "inconsistent transposed geometry");
+  return CONVBN_OK;
+}
+// the block's output seen as rows of Cout channels (for the per-channel sums of dZ)
+Geom tconv_out_rows(const Geom& g) {
+  Geom r = g;
+  r.M = g.Min;
+  r.Cout = g.Cin;
+  return r;
+}
+// bf16 blocks whose output-channel count is not a multiple of 8 run the forward pass on the any-shape kernel
+bool tconv_fwd_direct(const Geom& g, int dtype) { return needs_cin_pad(g, dtype); }
+
+struct TconvFwdWs { void* w_swap; float* bfold; float* conv_scratch; size_t bytes; };
+TconvFwdWs carve_tconv_fwd(const Geom& g, int dtype, void* ws) {
+  Carve c(ws);
+  TconvFwdWs r;
+  r.w_swap = c.take((size_t)g.Cout * g.K * esize(dtype));
+  r.bfold = (float*)c.take((size_t)g.Cin * 4);
+  r.conv_scratch = (float*)c.take(tconv_fwd_direct(g, dtype) ? 0 : inner_dgrad_scratch(g, dtype));
+  r.bytes = c.off;
+  return r;
+}
+struct TconvBwdWs { void* w_same; float* dwf_part; float* r_part; float* dot_part; float* conv_scratch; void* wgrad_scratch; int nsplit; int nrpart; size_t bytes; };
+TconvBwdWs carve_tconv_bwd(const Geom& g, int dtype, void* ws) {
+  Carve c(ws);
+  TconvBwdWs r;
+  r.nsplit = nsplit_for(g, dtype);
+  r.nrpart = colsum_parts(tconv_out_rows(g));
+  r.w_same = c.take((size_t)g.Cout * g.K * esize(dtype));
+  r.dwf_part = (float*)c.take((size_t)r.nsplit * g.Cout * g.K * 4);
+  r.r_part = (float*)c.take((size_t)r.nrpart * g.Cin * 4);
+  r.dot_part = (float*)c.take((size_t)fold_back_t_chunks(g.Cout, g.kH * g.kW) * g.Cin * 4);
+  r.conv_scratch = (float*)c.take(fprop_scratch_bytes(g, dtype));
+  r.wgrad_scratch = c.take(wgrad_scratch_bytes(g, dtype));
+  r.bytes = c.off;
+  return r;
 }
 
 }  // namespace
@@ -425,6 +483,86 @@ convbn_status convbn_eval_bwd(const convbn_desc* desc, const void* x, const void
   LAUNCH(run_wgrad(g, dt, x, w.dy, w.dwf_part, nullptr, w.wgrad_scratch, st));   // dW = dY (.) X
   LAUNCH(launch_fold_back(g, dt, w.dwf_part, w.nsplit, nullptr, 0, W, nullptr, nullptr, nullptr,
                           nullptr, 1, dW, nullptr, nullptr, nullptr, st));
+  return CONVBN_OK;
+}
+
+int32_t convbn_tconv_hout(const convbn_desc* desc) {
+  Geom g;
+  return make_tgeom(desc, &g) == CONVBN_OK ? g.Hin : 0;
+}
+
+int32_t convbn_tconv_wout(const convbn_desc* desc) {
+  Geom g;
+  return make_tgeom(desc, &g) == CONVBN_OK ? g.Win : 0;
+}
+
+size_t convbn_tconv_workspace_bytes(const convbn_desc* desc, int pass) {
+  Geom g;
+  if (make_tgeom(desc, &g) != CONVBN_OK) return 0;
+  return pass == CONVBN_PASS_FWD ? carve_tconv_fwd(g, desc->dtype, nullptr).bytes
+                                 : carve_tconv_bwd(g, desc->dtype, nullptr).bytes;
+}
+
+convbn_status convbn_tconv_tune_fwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                                    const float* gamma, const float* beta, const float* mean, const float* var,
+                                    void* z, void* w_folded, void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  convbn_status s = make_tgeom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(beta); REQUIRE_PTR(mean);
+  REQUIRE_PTR(var); REQUIRE_PTR(z);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(w_folded);
+  const int dt = desc->dtype;
+  s = check_ws(carve_tconv_fwd(g, dt, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const TconvFwdWs w = carve_tconv_fwd(g, dt, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // w' = s w in both orders, b'; then Z = (transposed convolution of X with w') + b'
+  LAUNCH(launch_fold_t(dt, g.Cout, g.Cin, g.kH * g.kW, W, b, gamma, beta, mean, var, g.eps, w_folded, w.w_swap,
+                       w.bfold, st));
+  if (tconv_fwd_direct(g, dt)) LAUNCH(launch_dgrad_direct(g, dt, x, w.w_swap, w.bfold, z, st));
+  else LAUNCH(dgrad_any(g, dt, x, w.w_swap, w.bfold, z, w.conv_scratch, st));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_tconv_tune_bwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                                    const float* gamma, const float* mean, const float* var, const void* w_folded,
+                                    const void* dz, void* dx, void* dW, float* db, float* dgamma, float* dbeta,
+                                    void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  convbn_status s = make_tgeom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
+  REQUIRE_PTR(dz);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(w_folded); OPTIONAL_PTR(dx); OPTIONAL_PTR(db);
+  OPTIONAL_PTR(dW); OPTIONAL_PTR(dgamma); OPTIONAL_PTR(dbeta);
+  const bool params = dW != nullptr;   // false: input gradient only
+  if (!params && (dgamma || dbeta || db || !dx))
+    return fail(CONVBN_ERR_NULL, "without dW only dx may be asked for (dgamma, dbeta, db NULL, dx given)");
+  if (params && (!dgamma || !dbeta))
+    return fail(CONVBN_ERR_NULL, "dgamma and dbeta are required together with dW");
+  if (params && (b == nullptr) != (db == nullptr))
+    return fail(CONVBN_ERR_NULL, "db must be given exactly when b is given");
+  const int dt = desc->dtype;
+  s = check_ws(carve_tconv_bwd(g, dt, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const TconvBwdWs w = carve_tconv_bwd(g, dt, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int taps = g.kH * g.kW;
+  if (dx) {
+    const void* wf = w_folded;
+    if (!wf) {  // nothing was kept: fold again, in the order this pass reads
+      LAUNCH(launch_fold_t(dt, g.Cout, g.Cin, taps, W, b, gamma, nullptr, mean, var, g.eps, w.w_same, nullptr, nullptr, st));
+      wf = w.w_same;
+    }
+    LAUNCH(run_fprop(g, dt, dz, wf, nullptr, dx, w.conv_scratch, st));   // dX = w' (*) dZ: a plain convolution
+  }
+  if (!params) return CONVBN_OK;
+  // dw'[ci][tap][co] = sum X[ci] dZ[co]: the associated convolution's weight gradient with dZ as its input
+  LAUNCH(run_wgrad(g, dt, dz, x, w.dwf_part, nullptr, w.wgrad_scratch, st));
+  LAUNCH(launch_colsum(tconv_out_rows(g), dt, dz, w.r_part, st));       // r = sum dZ
+  LAUNCH(launch_fold_back_t(dt, g.Cout, g.Cin, taps, w.dwf_part, w.nsplit, w.r_part, w.nrpart, W, b, gamma, mean,
+                            var, g.eps, w.dot_part, dW, db, dgamma, dbeta, st));
   return CONVBN_OK;
 }
 

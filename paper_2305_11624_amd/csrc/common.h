@@ -71,6 +71,16 @@ hipError_t launch_fold_back(const Geom& g, int dtype, const float* dwf_part, int
                             const float* r_part, int nrpart, const void* W, const float* b,
                             const float* gamma, const float* mean, const float* var, int identity,
                             void* dW, float* db, float* dgamma, float* dbeta, hipStream_t st);
+// fold_t.hip : fold / fold-back of the transposed block, weight [Ci][taps][Co] with the scale on co.
+// w_same ([Ci][taps][Co]), w_swap ([Co][taps][Ci]) and bfold may each be NULL (skipped).
+hipError_t launch_fold_t(int dtype, int Ci, int Co, int taps, const void* W, const float* b, const float* gamma,
+                         const float* beta, const float* mean, const float* var, float eps, void* w_same,
+                         void* w_swap, float* bfold, hipStream_t st);
+int fold_back_t_chunks(int Ci, int taps);   // rows of dot_part ([chunks][Co] fp32 scratch)
+hipError_t launch_fold_back_t(int dtype, int Ci, int Co, int taps, const float* dwf_part, int nsplit,
+                              const float* r_part, int nrpart, const void* W, const float* b, const float* gamma,
+                              const float* mean, const float* var, float eps, float* dot_part, void* dW, float* db,
+                              float* dgamma, float* dbeta, hipStream_t st);
 int colsum_parts(const Geom& g);
 hipError_t launch_colsum(const Geom& g, int dtype, const void* dz, float* r_part, hipStream_t st);
 hipError_t launch_bn_affine_fwd(const Geom& g, int dtype, const void* y, const float* gamma,
@@ -101,7 +111,7 @@ hipError_t launch_maxpool_bwd(int dtype, const void* dy, const unsigned char* id
 hipError_t launch_fprop_direct(const Geom& g, int dtype, const void* x, const void* w_krsc,
                                const float* bias, void* z, hipStream_t st);
 hipError_t launch_dgrad_direct(const Geom& g, int dtype, const void* dz, const void* w_crsk,
-                               void* dx, hipStream_t st);
+                               const float* bias /*[Cin] or null*/, void* dx, hipStream_t st);
 int wgrad_direct_splits(const Geom& g);
 hipError_t launch_wgrad_direct(const Geom& g, int dtype, const void* x, const void* dz,
                                float* dwf_part /*[splits][Cout][K]*/, hipStream_t st);
@@ -111,7 +121,7 @@ bool igemm_supported(const Geom& g, int dtype);
 int wgrad_splits(const Geom& g);
 hipError_t launch_fprop_igemm(const Geom& g, const void* x, const void* w_krsc, const float* bias,
                               void* z, hipStream_t st);
-hipError_t launch_dgrad_igemm(const Geom& g, const void* dz, const void* w_crsk, void* dx,
+hipError_t launch_dgrad_igemm(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
                               hipStream_t st);
 hipError_t launch_wgrad_igemm(const Geom& g, const void* x, const void* dz, float* dwf_part,
                               int nsplit, hipStream_t st);
@@ -123,7 +133,8 @@ bool pw_fprop_supported(const Geom& g, int dtype);
 bool pw_dgrad_supported(const Geom& g, int dtype);
 hipError_t launch_fprop_pw(const Geom& g, const void* x, const void* w_krsc, const float* bias, void* z,
                            hipStream_t st);
-hipError_t launch_dgrad_pw(const Geom& g, const void* dz, const void* w_crsk, void* dx, hipStream_t st);
+hipError_t launch_dgrad_pw(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
+                           hipStream_t st);
 
 bool tile_fprop_supported(const Geom& g, int dtype);
 bool tile_dgrad_supported(const Geom& g, int dtype);
@@ -133,7 +144,9 @@ size_t tile_fprop_partial_bytes(const Geom& g);
 size_t tile_dgrad_partial_bytes(const Geom& g);
 hipError_t launch_fprop_tile(const Geom& g, const void* x, const void* w_krsc, const float* bias,
                              void* z, float* partials, hipStream_t st);
-hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, void* dx,
+// The input-gradient launchers take an optional per-input-channel bias: a transposed convolution's forward
+// pass is this kernel (Sec. 3.2.1), and its folded bias b' is added here.
+hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
                              float* partials, hipStream_t st);
 
 // wgrad_tile.hip : bf16 MFMA weight gradient with LDS-resident pixel tiles; also produces the

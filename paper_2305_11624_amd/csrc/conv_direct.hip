@@ -41,6 +41,7 @@ __global__ __launch_bounds__(256) void fprop_direct_kernel(const T* __restrict__
 template <typename T>
 __global__ __launch_bounds__(256) void dgrad_direct_kernel(const T* __restrict__ dz,
                                                            const T* __restrict__ w,
+                                                           const float* __restrict__ bias,
                                                            T* __restrict__ dx, Geom g) {
   const size_t total = (size_t)g.Min * g.Cin;
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(256) void dgrad_direct_kernel(const T* __restrict__
   m /= g.Win;
   const int h = m % g.Hin;
   const int n = m / g.Hin;
-  float acc = 0.f;
+  float acc = bias ? bias[ci] : 0.f;
   for (int i = 0; i < g.kH; ++i) {
     const int hz = h + g.ph - i;
     if (hz < 0 || hz % g.sh != 0) continue;
@@ -119,15 +120,15 @@ hipError_t launch_fprop_direct(const Geom& g, int dtype, const void* x, const vo
 }
 
 hipError_t launch_dgrad_direct(const Geom& g, int dtype, const void* dz, const void* w_crsk,
-                               void* dx, hipStream_t st) {
+                               const float* bias, void* dx, hipStream_t st) {
   const size_t total = (size_t)g.Min * g.Cin;
   const dim3 grid((unsigned)((total + 255) / 256));
   if (dtype == CONVBN_BF16)
     hipLaunchKernelGGL(dgrad_direct_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)dz,
-                       (const bf16_t*)w_crsk, (bf16_t*)dx, g);
+                       (const bf16_t*)w_crsk, bias, (bf16_t*)dx, g);
   else
     hipLaunchKernelGGL(dgrad_direct_kernel<float>, grid, dim3(256), 0, st, (const float*)dz,
-                       (const float*)w_crsk, (float*)dx, g);
+                       (const float*)w_crsk, bias, (float*)dx, g);
   return hipGetLastError();
 }
 

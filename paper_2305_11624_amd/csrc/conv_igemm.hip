@@ -23,7 +23,7 @@ constexpr int LDK = BK + 8;   // padded LDS row (144 B): 16-lane b128 reads hit 
 struct IgemmParams {
   const bf16_t* act;   // fprop: x ; dgrad: dz ; wgrad: x
   const bf16_t* wgt;   // fprop: w' [Cout][K] ; dgrad: w'^T [Cin][taps*Cout] ; wgrad: dz
-  const float* bias;   // fprop only (nullable)
+  const float* bias;   // per output row of fprop / dgrad (nullable)
   void* out;
   Geom g;
   int red_per_split;   // wgrad: pixels per blockIdx.y slice (multiple of BK)
@@ -391,7 +391,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p) {
                      (size_t)col * R + row;
           *reinterpret_cast<float4*>(o) = make_float4(v0, v1, v2, v3);
         } else {
-          if (PASS == PASS_FPROP && p.bias) {
+          if (p.bias) {
             const float4 bb = *reinterpret_cast<const float4*>(p.bias + row);
             v0 += bb.x; v1 += bb.y; v2 += bb.z; v3 += bb.w;
           }
@@ -451,9 +451,9 @@ hipError_t launch_fprop_igemm(const Geom& g, const void* x, const void* w_krsc, 
   return launch_pass<PASS_FPROP>(p, g.Cout, g.M, 1, st);
 }
 
-hipError_t launch_dgrad_igemm(const Geom& g, const void* dz, const void* w_crsk, void* dx,
+hipError_t launch_dgrad_igemm(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
                               hipStream_t st) {
-  IgemmParams p{(const bf16_t*)dz, (const bf16_t*)w_crsk, nullptr, dx, g, 0};
+  IgemmParams p{(const bf16_t*)dz, (const bf16_t*)w_crsk, bias, dx, g, 0};
   return launch_pass<PASS_DGRAD>(p, g.Cin, g.Min, 1, st);
 }
 

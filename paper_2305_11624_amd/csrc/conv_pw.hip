@@ -346,11 +346,12 @@ hipError_t launch_fprop_pw(const Geom& g, const void* x, const void* w_krsc, con
   p.act = (const bf16_t*)x; p.wgt = (const bf16_t*)w_krsc; p.bias = bias; p.out = (bf16_t*)z;
   return launch_plan(p, pl, st);
 }
-hipError_t launch_dgrad_pw(const Geom& g, const void* dz, const void* w_crsk, void* dx, hipStream_t st) {
+hipError_t launch_dgrad_pw(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
+                           hipStream_t st) {
   PwParams p = dgrad_params(g);
   const PwPlan pl = make_plan(p);
   if (!pl.ok) return hipErrorInvalidValue;
-  p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = nullptr; p.out = (bf16_t*)dx;
+  p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
   return launch_plan(p, pl, st);
 }
 

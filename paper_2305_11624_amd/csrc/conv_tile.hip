@@ -816,9 +816,19 @@ ClassKind dgrad_class_params(const Geom& g, int a, int b, TileParams* p) {
   return CLASS_RUN;
 }
 
-__global__ __launch_bounds__(256) void zero_fill_kernel(uint4* __restrict__ p, size_t n16) {
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
-    p[i] = make_uint4(0u, 0u, 0u, 0u);
+// Every pixel row of out ([pixels][R] bf16, R % 8 == 0) := bf16(bias) (zeros without a bias).
+__global__ __launch_bounds__(256) void fill_rows_kernel(uint4* __restrict__ out, size_t n16, int R,
+                                                        const float* __restrict__ bias) {
+  const int r8 = R >> 3;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (bias) {
+      const float* bb = bias + (size_t)(i % r8) * 8;
+      v = make_uint4(pack_bf16x2(bb[0], bb[1]), pack_bf16x2(bb[2], bb[3]), pack_bf16x2(bb[4], bb[5]),
+                     pack_bf16x2(bb[6], bb[7]));
+    }
+    out[i] = v;
+  }
 }
 
 }  // namespace
@@ -866,17 +876,17 @@ hipError_t launch_fprop_tile(const Geom& g, const void* x, const void* w_krsc, c
   return launch_plan(p, pl, st);
 }
 
-hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, void* dx,
+hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
                              float* partials, hipStream_t st) {
   TileParams p;
   if (g.sh != 1 || g.sw != 1) {
     bool zero_first = false;
     for (int a = 0; a < g.sh; ++a)
       for (int b = 0; b < g.sw; ++b) zero_first |= dgrad_class_params(g, a, b, &p) == CLASS_ZERO;
-    if (zero_first) {   // positions no tap reaches: clear dX once, the other classes overwrite theirs
+    if (zero_first) {   // positions no tap reaches hold the bias alone: fill dX once, the other classes overwrite theirs
       const size_t n16 = (size_t)g.Min * g.Cin * 2 / 16;
       const int blocks = (int)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
-      hipLaunchKernelGGL(zero_fill_kernel, dim3(blocks), dim3(256), 0, st, (uint4*)dx, n16);
+      hipLaunchKernelGGL(fill_rows_kernel, dim3(blocks), dim3(256), 0, st, (uint4*)dx, n16, g.Cin, bias);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
     }
@@ -885,7 +895,7 @@ hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, 
         if (dgrad_class_params(g, a, b, &p) != CLASS_RUN) continue;
         const TilePlan pl = make_plan(p);
         if (!pl.ok) return hipErrorInvalidValue;
-        p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = nullptr; p.out = (bf16_t*)dx;
+        p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
         p.part = nullptr;
         hipError_t e = launch_plan(p, pl, st);
         if (e != hipSuccess) return e;
@@ -895,7 +905,7 @@ hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, 
   dgrad_params(g, &p);
   const TilePlan pl = make_plan(p);
   if (p.ksplit > 1 && !partials) return hipErrorInvalidValue;
-  p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = nullptr; p.out = (bf16_t*)dx;
+  p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
   p.part = partials;
   return launch_plan(p, pl, st);
 }

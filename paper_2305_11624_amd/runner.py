@@ -92,3 +92,61 @@ class BlockRun:
             db=f(self.db), dgamma=f(self.dgamma), dbeta=f(self.dbeta),
             Wf=B.folded_from_device(self.w_folded) if self.w_folded is not None else None,
             Y=B.act_from_device(self.y_saved) if self.y_saved is not None else None)
+
+
+class TconvRun:
+    """One TransposedConv-BN block on the GPU in Tune mode (inputs from synth.make_tconv_inputs)."""
+
+    def __init__(self, inp: Dict[str, object], keep_folded: bool = True, need_dx: bool = True,
+                 params: bool = True, device: str = "cuda", poison: bool = False):
+        s = inp["shape"]
+        self.shape, self.keep_folded = s, keep_folded
+        self.desc = B.desc_from_shape(s, eps=inp["eps"])
+        dt = B.torch_dtype(self.desc)
+        self.dt = dt
+        ho, wo = B.convbn_tconv_hout(self.desc), B.convbn_tconv_wout(self.desc)
+        self.x = B.act_to_device(inp["x"], dt, device)
+        self.W = B.weight_to_device(inp["W"], dt, device)        # [Cin, Cout, k, k] -> [Cin][k][k][Cout]
+        self.dz = B.act_to_device(inp["dy"], dt, device)
+        self.b = B.vec_to_device(inp["b"], device)
+        self.gamma, self.beta = B.vec_to_device(inp["gamma"], device), B.vec_to_device(inp["beta"], device)
+        self.mean, self.var = B.vec_to_device(inp["rmean"], device), B.vec_to_device(inp["rvar"], device)
+
+        def out(shape, dtype):
+            t = torch.empty(shape, dtype=dtype, device=device)
+            if poison:
+                t.fill_(float("nan"))
+            return t
+
+        self.z = out((s.N, ho, wo, s.Cout), dt)
+        self.dx = out((s.N, s.Hin, s.Win, s.Cin), dt) if need_dx else None
+        self.dW = out((s.Cin, s.k, s.k, s.Cout), dt) if params else None
+        self.db = out((s.Cout,), torch.float32) if (self.b is not None and params) else None
+        self.dgamma = out((s.Cout,), torch.float32) if params else None
+        self.dbeta = out((s.Cout,), torch.float32) if params else None
+        self.ws_fwd = BlockRun._ws(B.convbn_tconv_workspace_bytes(self.desc, B.PASS_FWD), device)
+        self.ws_bwd = BlockRun._ws(B.convbn_tconv_workspace_bytes(self.desc, B.PASS_BWD), device)
+        self.w_folded = out((s.Cin, s.k, s.k, s.Cout), dt) if keep_folded else None
+
+    def forward(self, stream=None):
+        B.convbn_tconv_tune_fwd(self.desc, self.x, self.W, self.b, self.gamma, self.beta, self.mean, self.var,
+                                self.z, self.w_folded, self.ws_fwd, stream)
+
+    def backward(self, stream=None):
+        B.convbn_tconv_tune_bwd(self.desc, self.x, self.W, self.b, self.gamma, self.mean, self.var,
+                                self.w_folded, self.dz, self.dx, self.dW, self.db, self.dgamma, self.dbeta,
+                                self.ws_bwd, stream)
+
+    def step(self, stream=None):
+        self.forward(stream)
+        self.backward(stream)
+
+    def results(self) -> Dict[str, Optional[torch.Tensor]]:
+        torch.cuda.synchronize()
+        f = lambda t: None if t is None else t.detach().to("cpu", torch.float64)
+        return dict(
+            Z=B.act_from_device(self.z),
+            dX=B.act_from_device(self.dx) if self.dx is not None else None,
+            dW=B.weight_from_device(self.dW) if self.dW is not None else None,
+            db=f(self.db), dgamma=f(self.dgamma), dbeta=f(self.dbeta),
+            Wf=B.weight_from_device(self.w_folded) if self.w_folded is not None else None)

@@ -125,6 +125,41 @@ def make_inputs(shape: BlockShape, seed: Optional[int] = None, bias: bool = Fals
                 eps=eps)
 
 
+def tconv_out(shape: BlockShape):
+    """(Hout, Wout) of a transposed convolution with the shape's window, stride and padding."""
+    return ((shape.Hin - 1) * shape.stride - 2 * shape.pad + shape.k,
+            (shape.Win - 1) * shape.stride - 2 * shape.pad + shape.k)
+
+
+def make_tconv_inputs(shape: BlockShape, seed: Optional[int] = None, bias: bool = False,
+                      wide_scale: bool = False) -> Dict[str, object]:
+    """Tensors of a TransposedConv-BN block (Sec. 3.2.1): the shape's fields describe the block's input and
+    its operator, W is the logical [Cin, Cout, k, k] ~ N(0, 2 stride^2 / (Cin k^2)) (every output pixel sums
+    about Cin (k/stride)^2 products), dy has the transposed convolution's output size.  Same draw order and
+    distributions as make_inputs otherwise."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(shape.seed if seed is None else seed)
+    s = shape
+    ho, wo = tconv_out(s)
+    x = torch.randn(s.N, s.Cin, s.Hin, s.Win, generator=g)
+    W = torch.randn(s.Cin, s.Cout, s.k, s.k, generator=g) * (2.0 * s.stride ** 2 / (s.Cin * s.k * s.k)) ** 0.5
+    gamma = torch.rand(s.Cout, generator=g) + 0.5
+    beta = torch.randn(s.Cout, generator=g) * 0.1
+    rmean = torch.randn(s.Cout, generator=g) * 0.1
+    rvar = torch.rand(s.Cout, generator=g) * 1.5 + 0.5
+    dy = torch.randn(s.N, s.Cout, ho, wo, generator=g)
+    b = torch.randn(s.Cout, generator=g) * 0.1 if bias else None
+    eps = 1e-5
+    if wide_scale:
+        scale = torch.rand(s.Cout, generator=g) * 30.0
+        scale[:: max(1, s.Cout // 4)] = 0.0
+        gamma = scale * torch.sqrt(rvar + eps)
+    if s.dtype == "bf16":
+        x, W, dy = round_bf16(x), round_bf16(W), round_bf16(dy)
+    return dict(shape=s, x=x, W=W, b=b, gamma=gamma, beta=beta, rmean=rmean, rvar=rvar, dy=dy,
+                eps=eps)
+
+
 def make_params(shape: BlockShape, seed: Optional[int] = None) -> Dict[str, object]:
     """Only the parameters of a block (same distributions and draw order as make_inputs, but
     without the activation-sized tensors): W, gamma, beta, running mean, running var."""
