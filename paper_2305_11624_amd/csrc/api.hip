@@ -312,7 +312,7 @@ TconvFwdWs carve_tconv_fwd(const Geom& g, int dtype, void* ws) {
   Carve c(ws);
   TconvFwdWs r;
   r.w_swap = c.take((size_t)g.Cout * g.K * esize(dtype));
-  r.bfold = (float*)c.take((size_t)g.Cin * 4);
+  r.bfold = (float*)c.take((size_t)g.Cin * g.kH * g.kW * 4);   // room for one copy per tap (the single-product forward)
   r.conv_scratch = (float*)c.take(tconv_fwd_direct(g, dtype) ? 0 : inner_dgrad_scratch(g, dtype));
   r.bytes = c.off;
   return r;
@@ -518,9 +518,11 @@ convbn_status convbn_tconv_tune_fwd(const convbn_desc* desc, const void* x, cons
   const TconvFwdWs w = carve_tconv_fwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
   // w' = s w in both orders, b'; then Z = (transposed convolution of X with w') + b'
-  LAUNCH(launch_fold_t(dt, g.Cout, g.Cin, g.kH * g.kW, W, b, gamma, beta, mean, var, g.eps, w_folded, w.w_swap,
-                       w.bfold, st));
-  if (tconv_fwd_direct(g, dt)) LAUNCH(launch_dgrad_direct(g, dt, x, w.w_swap, w.bfold, z, st));
+  const bool one_product = pw_tconv_supported(g, dt);   // stride = window: a product with a depth-to-space store
+  LAUNCH(launch_fold_t(dt, g.Cout, g.Cin, g.kH * g.kW, W, b, gamma, beta, mean, var, g.eps, one_product, w_folded,
+                       w.w_swap, w.bfold, st));
+  if (one_product) LAUNCH(launch_tconv_pw(g, x, w.w_swap, w.bfold, z, st));
+  else if (tconv_fwd_direct(g, dt)) LAUNCH(launch_dgrad_direct(g, dt, x, w.w_swap, w.bfold, z, st));
   else LAUNCH(dgrad_any(g, dt, x, w.w_swap, w.bfold, z, w.conv_scratch, st));
   return CONVBN_OK;
 }
@@ -552,7 +554,8 @@ convbn_status convbn_tconv_tune_bwd(const convbn_desc* desc, const void* x, cons
   if (dx) {
     const void* wf = w_folded;
     if (!wf) {  // nothing was kept: fold again, in the order this pass reads
-      LAUNCH(launch_fold_t(dt, g.Cout, g.Cin, taps, W, b, gamma, nullptr, mean, var, g.eps, w.w_same, nullptr, nullptr, st));
+      LAUNCH(launch_fold_t(dt, g.Cout, g.Cin, taps, W, b, gamma, nullptr, mean, var, g.eps, 0, w.w_same, nullptr,
+                           nullptr, st));
       wf = w.w_same;
     }
     LAUNCH(run_fprop(g, dt, dz, wf, nullptr, dx, w.conv_scratch, st));   // dX = w' (*) dZ: a plain convolution

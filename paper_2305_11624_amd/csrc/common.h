@@ -72,10 +72,11 @@ hipError_t launch_fold_back(const Geom& g, int dtype, const float* dwf_part, int
                             const float* gamma, const float* mean, const float* var, int identity,
                             void* dW, float* db, float* dgamma, float* dbeta, hipStream_t st);
 // fold_t.hip : fold / fold-back of the transposed block, weight [Ci][taps][Co] with the scale on co.
-// w_same ([Ci][taps][Co]), w_swap ([Co][taps][Ci]) and bfold may each be NULL (skipped).
+// w_same ([Ci][taps][Co]), w_swap ([Co][taps][Ci]) and bfold may each be NULL (skipped).  tap_major != 0:
+// w_swap is [taps][Co][Ci] and bfold [taps][Co] (b' repeated for every tap) instead.
 hipError_t launch_fold_t(int dtype, int Ci, int Co, int taps, const void* W, const float* b, const float* gamma,
-                         const float* beta, const float* mean, const float* var, float eps, void* w_same,
-                         void* w_swap, float* bfold, hipStream_t st);
+                         const float* beta, const float* mean, const float* var, float eps, int tap_major,
+                         void* w_same, void* w_swap, float* bfold, hipStream_t st);
 int fold_back_t_chunks(int Ci, int taps);   // rows of dot_part ([chunks][Co] fp32 scratch)
 hipError_t launch_fold_back_t(int dtype, int Ci, int Co, int taps, const float* dwf_part, int nsplit,
                               const float* r_part, int nrpart, const void* W, const float* b, const float* gamma,
@@ -134,6 +135,12 @@ bool pw_dgrad_supported(const Geom& g, int dtype);
 hipError_t launch_fprop_pw(const Geom& g, const void* x, const void* w_krsc, const float* bias, void* z,
                            hipStream_t st);
 hipError_t launch_dgrad_pw(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
+                           hipStream_t st);
+// Forward of a transposed convolution whose stride equals its window (no padding), as one product with a
+// depth-to-space store; g is the convolution the block is the adjoint of.  w_tap_major is [taps][g.Cin][g.Cout]
+// (rows (tap, co)), bias_per_tap [taps][g.Cin] (the folded bias repeated per tap).
+bool pw_tconv_supported(const Geom& g, int dtype);
+hipError_t launch_tconv_pw(const Geom& g, const void* x, const void* w_tap_major, const float* bias_per_tap, void* z,
                            hipStream_t st);
 
 bool tile_fprop_supported(const Geom& g, int dtype);

@@ -26,6 +26,20 @@ namespace convbn {
 
 namespace {
 
+struct PwDiv { unsigned mul, shr; int d; };   // exact n / d for 0 <= n < 2^31
+PwDiv make_div(int d) {
+  PwDiv f{0u, 0u, d};
+  if (d <= 1) return f;
+  unsigned sh = 0;
+  while ((1ull << (sh + 1)) < (unsigned long long)d) ++sh;   // 2^sh < d <= 2^(sh+1)
+  f.shr = sh;
+  f.mul = (unsigned)((((unsigned long long)1 << (32 + sh)) + d - 1) / d);
+  return f;
+}
+__device__ __forceinline__ int pdiv(int n, const PwDiv& f) {
+  return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.mul) >> f.shr);
+}
+
 struct PwParams {
   const bf16_t* act;     // [M][C]
   const bf16_t* wgt;     // [R][C]
@@ -38,6 +52,11 @@ struct PwParams {
   int ntiles, nchunks;
   int wpitch;            // LDS bytes per weight row: 2 C + 16
   int wtile_bytes;       // TRC rows of wpitch bytes, rounded up to whole 1 KB copies
+  // Depth-to-space output (d2s_co > 0): the R channels are (tap, co) pairs, tap = (a, b) of a kh x kw window, and
+  // channel block tap of pixel (n, h, w) is stored at pixel (n, h kh + a, w kw + b) of an [N][H kh][W kw][co] tensor --
+  // a transposed convolution whose stride equals its window (Sec. 3.2.1) is exactly this product.
+  int d2s_co, d2s_kh, d2s_kw, d2s_H, d2s_W;
+  PwDiv d_co, d_kw, d_HW, d_W;
 };
 
 constexpr unsigned OOB = 0x80000000u;   // beyond any buffer: the load returns zeros
@@ -229,7 +248,17 @@ __global__ __launch_bounds__(64 * NW) void conv_pw_kernel(PwParams p) {
           const uint4 v = *reinterpret_cast<const uint4*>(st + row * 128 + ((lane & 7) << 4));
           const int pi = wave * 32 + row;
           const int ch = r0 + rp * 64 + g * 8;
-          if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + pi) * p.R + ch) = v;
+          size_t o = (size_t)(m0 + pi) * p.R + ch;
+          if (p.d2s_co > 0) {
+            const int tap = pdiv(r0 + rp * 64, p.d_co);          // the whole 64-channel block is one tap's
+            const int ta = pdiv(tap, p.d_kw), tb = tap - ta * p.d2s_kw;
+            const int m = m0 + pi;
+            const int n = pdiv(m, p.d_HW), rem = m - n * (p.d2s_H * p.d2s_W);
+            const int h = pdiv(rem, p.d_W), w = rem - h * p.d2s_W;
+            o = (((size_t)n * (p.d2s_H * p.d2s_kh) + h * p.d2s_kh + ta) * (p.d2s_W * p.d2s_kw) + w * p.d2s_kw + tb) *
+                    p.d2s_co + (ch - tap * p.d2s_co);
+          }
+          if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + o) = v;
         }
       }
       m0 += tile_stride;
@@ -326,7 +355,37 @@ PwParams dgrad_params(const Geom& g) {
   return p;
 }
 
+// forward of a transposed convolution whose stride equals its window (no padding): g is the convolution it is
+// the adjoint of, so the product runs over g's OUTPUT pixels with g.Cout reduced and taps x g.Cin produced channels
+bool d2s_shape(const Geom& g) {
+  return g.kH == g.sh && g.kW == g.sw && g.ph == 0 && g.pw == 0 && g.kH * g.kW > 1 && g.Cin % 64 == 0 &&
+         g.Hin == g.Hout * g.kH && g.Win == g.Wout * g.kW;
+}
+PwParams d2s_params(const Geom& g) {
+  PwParams p{};
+  p.M = g.M; p.C = g.Cout; p.R = g.kH * g.kW * g.Cin;
+  p.act_bytes = (unsigned)((size_t)g.M * g.Cout * 2);
+  p.wgt_bytes = (unsigned)((size_t)p.R * g.Cout * 2);
+  p.d2s_co = g.Cin; p.d2s_kh = g.kH; p.d2s_kw = g.kW; p.d2s_H = g.Hout; p.d2s_W = g.Wout;
+  p.d_co = make_div(g.Cin); p.d_kw = make_div(g.kW); p.d_HW = make_div(g.Hout * g.Wout); p.d_W = make_div(g.Wout);
+  return p;
+}
+
 }  // namespace
+
+bool pw_tconv_supported(const Geom& g, int dtype) {
+  if (dtype != CONVBN_BF16 || !d2s_shape(g)) return false;
+  PwParams p = d2s_params(g);
+  return make_plan(p).ok;
+}
+hipError_t launch_tconv_pw(const Geom& g, const void* x, const void* w_tap_major, const float* bias_per_tap, void* z,
+                           hipStream_t st) {
+  PwParams p = d2s_params(g);
+  const PwPlan pl = make_plan(p);
+  if (!pl.ok) return hipErrorInvalidValue;
+  p.act = (const bf16_t*)x; p.wgt = (const bf16_t*)w_tap_major; p.bias = bias_per_tap; p.out = (bf16_t*)z;
+  return launch_plan(p, pl, st);
+}
 
 bool pw_fprop_supported(const Geom& g, int dtype) {
   if (dtype != CONVBN_BF16 || !pointwise(g)) return false;

@@ -3,7 +3,8 @@
 // the weight's OUTPUT-channel index, which is the innermost one of the transposed block's weight):
 //   W      [Ci][taps][Co]     (the channels-last order of the logical [Ci, Co, kH, kW])
 //   fold   w_same[ci][tap][co] = s[co] W[ci][tap][co]      read by the backward's input-gradient pass
-//          w_swap[co][tap][ci] = s[co] W[ci][tap][co]      read by the forward pass
+//          w_swap[co][tap][ci] = s[co] W[ci][tap][co]      read by the forward pass (or [tap][co][ci] where the
+//                                                          forward pass is a single product, see conv_pw.hip)
 //          b'[co] = (b[co] - mu[co]) s[co] + beta[co]
 //   back   dW[ci][tap][co] = s[co] dw'[ci][tap][co],  dgamma[co] = (sum_{ci,tap} dw' W + r (b - mu)) / sqrt(var + eps),
 //          dbeta = r, db = s r
@@ -21,15 +22,16 @@ template <typename T>
 __global__ __launch_bounds__(256) void fold_t_kernel(const T* __restrict__ W, const float* __restrict__ b,
                                                      const float* __restrict__ gamma, const float* __restrict__ beta,
                                                      const float* __restrict__ mean, const float* __restrict__ var,
-                                                     float eps, int Ci, int Co, int taps, T* __restrict__ w_same,
-                                                     T* __restrict__ w_swap, float* __restrict__ bfold) {
+                                                     float eps, int Ci, int Co, int taps, int tap_major,
+                                                     T* __restrict__ w_same, T* __restrict__ w_swap,
+                                                     float* __restrict__ bfold) {
   __shared__ float tile[TT][TT + 1];
   const int tx = threadIdx.x % TT, ty = threadIdx.x / TT;   // ty in [0, 8)
   const int co0 = blockIdx.x * TT, ci0 = blockIdx.y * TT, tap = blockIdx.z;
   const int co = co0 + tx;
   const float s = co < Co ? gamma[co] / sqrtf(var[co] + eps) : 0.f;
-  if (bfold && blockIdx.y == 0 && tap == 0 && ty == 0 && co < Co)
-    bfold[co] = ((b ? b[co] : 0.f) - mean[co]) * s + beta[co];
+  if (bfold && blockIdx.y == 0 && (tap == 0 || tap_major) && ty == 0 && co < Co)
+    bfold[(tap_major ? tap * Co : 0) + co] = ((b ? b[co] : 0.f) - mean[co]) * s + beta[co];
 #pragma unroll
   for (int e = 0; e < TT / 8; ++e) {
     const int ci = ci0 + ty + 8 * e;
@@ -48,7 +50,8 @@ __global__ __launch_bounds__(256) void fold_t_kernel(const T* __restrict__ W, co
 #pragma unroll
   for (int e = 0; e < TT / 8; ++e) {
     const int oc = co0 + ty + 8 * e, ic = ci0 + tx;
-    if (oc < Co && ic < Ci) w_swap[((size_t)oc * taps + tap) * Ci + ic] = from_f32<T>(tile[tx][ty + 8 * e]);
+    if (oc < Co && ic < Ci)
+      w_swap[(tap_major ? (size_t)tap * Co + oc : (size_t)oc * taps + tap) * Ci + ic] = from_f32<T>(tile[tx][ty + 8 * e]);
   }
 }
 
@@ -171,15 +174,15 @@ __global__ __launch_bounds__(256) void fold_back_t_finish_kernel(const float* __
 }  // namespace
 
 hipError_t launch_fold_t(int dtype, int Ci, int Co, int taps, const void* W, const float* b, const float* gamma,
-                         const float* beta, const float* mean, const float* var, float eps, void* w_same,
-                         void* w_swap, float* bfold, hipStream_t st) {
+                         const float* beta, const float* mean, const float* var, float eps, int tap_major,
+                         void* w_same, void* w_swap, float* bfold, hipStream_t st) {
   const dim3 grid(ceil_div(Co, TT), ceil_div(Ci, TT), taps);
   if (dtype == CONVBN_BF16)
     hipLaunchKernelGGL(fold_t_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)W, b, gamma, beta, mean, var, eps,
-                       Ci, Co, taps, (bf16_t*)w_same, (bf16_t*)w_swap, bfold);
+                       Ci, Co, taps, tap_major, (bf16_t*)w_same, (bf16_t*)w_swap, bfold);
   else
     hipLaunchKernelGGL(fold_t_kernel<float>, grid, dim3(256), 0, st, (const float*)W, b, gamma, beta, mean, var, eps,
-                       Ci, Co, taps, (float*)w_same, (float*)w_swap, bfold);
+                       Ci, Co, taps, tap_major, (float*)w_same, (float*)w_swap, bfold);
   return hipGetLastError();
 }
 

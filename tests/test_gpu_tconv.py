@@ -48,12 +48,15 @@ BF16 = [
     BlockShape("t_k2s3", 2, 32, 6, 6, 40, 2, 3, 0, "bf16", 76),      # stride > window: output positions no tap reaches
     BlockShape("t_odd_out", 2, 64, 8, 8, 20, 2, 2, 0, "bf16", 77),   # output channels not a multiple of 8
     BlockShape("t_odd_in", 2, 12, 8, 8, 32, 3, 2, 1, "bf16", 78),    # input channels not a multiple of 8
+    # stride = window over enough pixels for the single-product forward (depth-to-space store), ragged last tile
+    BlockShape("t_d2s_k2", 6, 64, 37, 37, 64, 2, 2, 0, "bf16", 79),
+    BlockShape("t_d2s_k3", 2, 32, 41, 41, 64, 3, 3, 0, "bf16", 80),
 ]
 
 
 @pytest.mark.parametrize("shape", BF16, ids=lambda s: s.name)
 def test_bf16_shapes(shape):
-    inp = synth.make_tconv_inputs(shape, bias=shape.name in ("t_k2s3", "t_k4s2p1"))
+    inp = synth.make_tconv_inputs(shape, bias=shape.name in ("t_k2s3", "t_k4s2p1", "t_d2s_k2", "t_d2s_k3"))
     compare(_run(inp), oracle_tconv_block(inp), "bf16", keys=KEYS, tag=shape.name)
 
 
