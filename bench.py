@@ -362,6 +362,17 @@ def main_tconv(a):
         per_shape[s.name] = {"kernel_ms": {k: round(v, 5) for k, v in kt.items()},
                              "conv_tflops": {k: round(fl / 3.0 / (v * 1e-3) / 1e12, 1) for k, v in kt.items()}}
     achieved = best[3] / (best[2] * 1e-3) / 1e12
+    saved_tune = sum(p[0].saved_bytes() for p in pools)
+    ms_eval, saved_eval = None, None
+    if not a.no_eval:
+        counts = [len(p) for p in pools]
+        del pools, pool, r0
+        torch.cuda.empty_cache()
+        epools = [[TconvRun(inp, mode="eval") for _ in range(n)] for inp, n in zip(inputs, counts)]
+        ms_eval = time_steps(epools, a.steps, a.warmup)
+        saved_eval = sum(p[0].saved_bytes() for p in epools)
+        del epools
+        torch.cuda.empty_cache()
     line = {
         "metric": "TransposedConv-BN Tune fwd+bwd TFLOP/s", "value": sum(flops) / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True,
@@ -369,6 +380,8 @@ def main_tconv(a):
         "config": {"workload": "TransposedConv-BN up-sampling blocks, bf16: " + ", ".join(
             f"{s.name} x[{s.N},{s.Cin},{s.Hin},{s.Win}] {s.k}x{s.k} {s.Cin}->{s.Cout} s{s.stride} p{s.pad}"
             for s in shapes), "mode": "tune", "layout": "NHWC", "step": "fwd+bwd of every shape"},
+        "eval_ms_per_step": ms_eval, "tune_speedup_vs_eval": (ms_eval / ms) if ms_eval else None,
+        "saved_activation_mb": {"tune": saved_tune / 1e6, "eval": saved_eval / 1e6 if saved_eval is not None else None},
         "per_shape": per_shape,
         "roofline": {"bound": "mfma", "kernel": f"{best[1]} @ {best[0]}", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,

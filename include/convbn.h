@@ -158,8 +158,10 @@ convbn_status convbn_eval_bwd(const convbn_desc *desc, const void *x, const void
  * leaves no output are CONVBN_ERR_SHAPE. */
 int32_t convbn_tconv_hout(const convbn_desc *desc);
 int32_t convbn_tconv_wout(const convbn_desc *desc);
-/* pass: CONVBN_PASS_FWD / CONVBN_PASS_BWD.  0 for an invalid descriptor. */
-size_t convbn_tconv_workspace_bytes(const convbn_desc *desc, int pass);
+/* As convbn_workspace_bytes / convbn_saved_bytes, for the transposed block (Eval keeps Y, which has
+ * the size of the block's output; Tune keeps w').  0 for an invalid descriptor. */
+size_t convbn_tconv_workspace_bytes(const convbn_desc *desc, int mode, int pass);
+size_t convbn_tconv_saved_bytes(const convbn_desc *desc, int mode, int refold);
 convbn_status convbn_tconv_tune_fwd(const convbn_desc *desc, const void *x, const void *W,
                                     const float *b, const float *gamma, const float *beta,
                                     const float *mean, const float *var, void *z, void *w_folded,
@@ -169,6 +171,20 @@ convbn_status convbn_tconv_tune_bwd(const convbn_desc *desc, const void *x, cons
                                     const float *var, const void *w_folded, const void *dz,
                                     void *dx, void *dW, float *db, float *dgamma, float *dbeta,
                                     void *ws, size_t ws_bytes, void *stream);
+
+/* Eval mode of the transposed block (Sec. 3.1 with the transposed operator): Y = transposed
+ * convolution + b stored in y_saved, then the per-channel affine as a separate pass; backward through
+ * dY = s dZ as in Table 2's "Eval" row.  The comparison path for the two calls above; arguments as
+ * convbn_eval_fwd / convbn_eval_bwd with W, dW in [Cin][kH][kW][Cout] order. */
+convbn_status convbn_tconv_eval_fwd(const convbn_desc *desc, const void *x, const void *W,
+                                    const float *b, const float *gamma, const float *beta,
+                                    const float *mean, const float *var, void *z, void *y_saved,
+                                    void *ws, size_t ws_bytes, void *stream);
+convbn_status convbn_tconv_eval_bwd(const convbn_desc *desc, const void *x, const void *W,
+                                    const float *b, const float *gamma, const float *mean,
+                                    const float *var, const void *y_saved, const void *dz, void *dx,
+                                    void *dW, float *db, float *dgamma, float *dbeta, void *ws,
+                                    size_t ws_bytes, void *stream);
 
 /* ---- The individual steps of the Tune-mode block (each is one kernel) -------------
  * convbn_tune_fwd is convbn_fold followed by convbn_conv_fprop; convbn_tune_bwd is

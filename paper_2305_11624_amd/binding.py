@@ -26,7 +26,8 @@ EXPORTS = ["convbn_hout", "convbn_wout", "convbn_workspace_bytes", "convbn_saved
            "convbn_conv_workspace_bytes", "convbn_aux_eltwise", "convbn_aux_maxpool_fwd",
            "convbn_aux_maxpool_bwd", "convbn_fold_group_table_bytes", "convbn_fold_group_plan",
            "convbn_fold_group", "convbn_tconv_hout", "convbn_tconv_wout", "convbn_tconv_workspace_bytes",
-           "convbn_tconv_tune_fwd", "convbn_tconv_tune_bwd"]
+           "convbn_tconv_tune_fwd", "convbn_tconv_tune_bwd", "convbn_tconv_saved_bytes",
+           "convbn_tconv_eval_fwd", "convbn_tconv_eval_bwd"]
 
 
 class Desc(C.Structure):
@@ -80,16 +81,6 @@ def lib():
         L.convbn_tune_bwd.restype = C.c_int
         L.convbn_tune_bwd.argtypes = [dp, vp, vp, fp, fp, fp, fp, vp, vp, vp, vp, fp, fp, fp, vp,
                                       C.c_size_t, vp]
-        L.convbn_tconv_hout.restype = C.c_int32
-        L.convbn_tconv_hout.argtypes = [dp]
-        L.convbn_tconv_wout.restype = C.c_int32
-        L.convbn_tconv_wout.argtypes = [dp]
-        L.convbn_tconv_workspace_bytes.restype = C.c_size_t
-        L.convbn_tconv_workspace_bytes.argtypes = [dp, C.c_int]
-        L.convbn_tconv_tune_fwd.restype = C.c_int
-        L.convbn_tconv_tune_fwd.argtypes = L.convbn_tune_fwd.argtypes
-        L.convbn_tconv_tune_bwd.restype = C.c_int
-        L.convbn_tconv_tune_bwd.argtypes = L.convbn_tune_bwd.argtypes
         L.convbn_eval_fwd.restype = C.c_int
         L.convbn_eval_fwd.argtypes = [dp, vp, vp, fp, fp, fp, fp, fp, vp, vp, vp, C.c_size_t, vp]
         L.convbn_eval_bwd.restype = C.c_int
@@ -123,6 +114,22 @@ def lib():
         L.convbn_aux_maxpool_fwd.argtypes = [C.c_int, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp]
         L.convbn_aux_maxpool_bwd.restype = C.c_int
         L.convbn_aux_maxpool_bwd.argtypes = [C.c_int, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp]
+        L.convbn_tconv_hout.restype = C.c_int32
+        L.convbn_tconv_hout.argtypes = [dp]
+        L.convbn_tconv_wout.restype = C.c_int32
+        L.convbn_tconv_wout.argtypes = [dp]
+        L.convbn_tconv_workspace_bytes.restype = C.c_size_t
+        L.convbn_tconv_workspace_bytes.argtypes = [dp, C.c_int, C.c_int]
+        L.convbn_tconv_saved_bytes.restype = C.c_size_t
+        L.convbn_tconv_saved_bytes.argtypes = [dp, C.c_int, C.c_int]
+        L.convbn_tconv_eval_fwd.restype = C.c_int
+        L.convbn_tconv_eval_fwd.argtypes = L.convbn_eval_fwd.argtypes
+        L.convbn_tconv_eval_bwd.restype = C.c_int
+        L.convbn_tconv_eval_bwd.argtypes = L.convbn_eval_bwd.argtypes
+        L.convbn_tconv_tune_fwd.restype = C.c_int
+        L.convbn_tconv_tune_fwd.argtypes = L.convbn_tune_fwd.argtypes
+        L.convbn_tconv_tune_bwd.restype = C.c_int
+        L.convbn_tconv_tune_bwd.argtypes = L.convbn_tune_bwd.argtypes
         _lib = L
     return _lib
 
@@ -356,8 +363,32 @@ def convbn_tconv_wout(desc: Desc) -> int:
     return int(lib().convbn_tconv_wout(C.byref(desc)))
 
 
-def convbn_tconv_workspace_bytes(desc: Desc, pass_: int) -> int:
-    return int(lib().convbn_tconv_workspace_bytes(C.byref(desc), pass_))
+def convbn_tconv_workspace_bytes(desc: Desc, mode: int, pass_: int) -> int:
+    return int(lib().convbn_tconv_workspace_bytes(C.byref(desc), mode, pass_))
+
+
+def convbn_tconv_saved_bytes(desc: Desc, mode: int, refold: bool = False) -> int:
+    return int(lib().convbn_tconv_saved_bytes(C.byref(desc), mode, int(refold)))
+
+
+def convbn_tconv_eval_fwd(desc, x, W, b, gamma, beta, mean, var, z, y_saved, ws, stream=None, check=True):
+    p, n = _ws(ws)
+    st = lib().convbn_tconv_eval_fwd(C.byref(desc), _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(beta),
+                                     _ptr(mean), _ptr(var), _ptr(z), _ptr(y_saved), p, n, _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_tconv_eval_bwd(desc, x, W, b, gamma, mean, var, y_saved, dz, dx, dW, db, dgamma, dbeta, ws,
+                          stream=None, check=True):
+    p, n = _ws(ws)
+    st = lib().convbn_tconv_eval_bwd(C.byref(desc), _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(mean),
+                                     _ptr(var), _ptr(y_saved), _ptr(dz), _ptr(dx), _ptr(dW), _ptr(db),
+                                     _ptr(dgamma), _ptr(dbeta), p, n, _stream(stream))
+    if check:
+        _check(st)
+    return st
 
 
 def convbn_tconv_tune_fwd(desc, x, W, b, gamma, beta, mean, var, z, w_folded, ws, stream=None,

@@ -333,6 +333,22 @@ TconvBwdWs carve_tconv_bwd(const Geom& g, int dtype, void* ws) {
   return r;
 }
 
+// Eval comparison path of the transposed block: Y kept, separate affine; backward through dY
+struct TconvEvalBwdWs { void* dy; float* dwf_part; float* bn_part; float* conv_scratch; void* wgrad_scratch; int nsplit; int nparts; size_t bytes; };
+TconvEvalBwdWs carve_tconv_eval_bwd(const Geom& g, int dtype, void* ws) {
+  Carve c(ws);
+  TconvEvalBwdWs r;
+  r.nsplit = nsplit_for(g, dtype);
+  r.nparts = bn_bwd_parts(tconv_out_rows(g));
+  r.dy = c.take((size_t)g.Min * g.Cin * esize(dtype));
+  r.dwf_part = (float*)c.take((size_t)r.nsplit * g.Cout * g.K * 4);
+  r.bn_part = (float*)c.take((size_t)r.nparts * 2 * g.Cin * 4);
+  r.conv_scratch = (float*)c.take(fprop_scratch_bytes(g, dtype));
+  r.wgrad_scratch = c.take(wgrad_scratch_bytes(g, dtype));
+  r.bytes = c.off;
+  return r;
+}
+
 }  // namespace
 
 extern "C" {
@@ -496,11 +512,19 @@ int32_t convbn_tconv_wout(const convbn_desc* desc) {
   return make_tgeom(desc, &g) == CONVBN_OK ? g.Win : 0;
 }
 
-size_t convbn_tconv_workspace_bytes(const convbn_desc* desc, int pass) {
+size_t convbn_tconv_workspace_bytes(const convbn_desc* desc, int mode, int pass) {
   Geom g;
   if (make_tgeom(desc, &g) != CONVBN_OK) return 0;
-  return pass == CONVBN_PASS_FWD ? carve_tconv_fwd(g, desc->dtype, nullptr).bytes
-                                 : carve_tconv_bwd(g, desc->dtype, nullptr).bytes;
+  if (pass == CONVBN_PASS_FWD) return carve_tconv_fwd(g, desc->dtype, nullptr).bytes;   // the same for both modes
+  if (mode == CONVBN_MODE_TUNE) return carve_tconv_bwd(g, desc->dtype, nullptr).bytes;
+  return mode == CONVBN_MODE_EVAL ? carve_tconv_eval_bwd(g, desc->dtype, nullptr).bytes : 0;
+}
+
+size_t convbn_tconv_saved_bytes(const convbn_desc* desc, int mode, int refold) {
+  Geom g;
+  if (make_tgeom(desc, &g) != CONVBN_OK) return 0;
+  if (mode == CONVBN_MODE_EVAL) return (size_t)g.Min * g.Cin * esize(desc->dtype);   // Y: the block's output size
+  return refold ? 0 : (size_t)g.Cout * g.K * esize(desc->dtype);
 }
 
 convbn_status convbn_tconv_tune_fwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
@@ -566,6 +590,65 @@ convbn_status convbn_tconv_tune_bwd(const convbn_desc* desc, const void* x, cons
   LAUNCH(launch_colsum(tconv_out_rows(g), dt, dz, w.r_part, st));       // r = sum dZ
   LAUNCH(launch_fold_back_t(dt, g.Cout, g.Cin, taps, w.dwf_part, w.nsplit, w.r_part, w.nrpart, W, b, gamma, mean,
                             var, g.eps, w.dot_part, dW, db, dgamma, dbeta, st));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_tconv_eval_fwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                                    const float* gamma, const float* beta, const float* mean, const float* var,
+                                    void* z, void* y_saved, void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  convbn_status s = make_tgeom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(beta); REQUIRE_PTR(mean);
+  REQUIRE_PTR(var); REQUIRE_PTR(z); REQUIRE_PTR(y_saved);
+  OPTIONAL_PTR(b);
+  const int dt = desc->dtype;
+  s = check_ws(carve_tconv_fwd(g, dt, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const TconvFwdWs w = carve_tconv_fwd(g, dt, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool one_product = pw_tconv_supported(g, dt);
+  // the weight in the order the forward kernel reads (no scaling), Y = transposed convolution + b, then Z from Y
+  LAUNCH(launch_fold_t(dt, g.Cout, g.Cin, g.kH * g.kW, W, b, nullptr, nullptr, nullptr, nullptr, g.eps, one_product,
+                       nullptr, w.w_swap, w.bfold, st));
+  if (one_product) LAUNCH(launch_tconv_pw(g, x, w.w_swap, w.bfold, y_saved, st));
+  else if (tconv_fwd_direct(g, dt)) LAUNCH(launch_dgrad_direct(g, dt, x, w.w_swap, w.bfold, y_saved, st));
+  else LAUNCH(dgrad_any(g, dt, x, w.w_swap, w.bfold, y_saved, w.conv_scratch, st));
+  LAUNCH(launch_bn_affine_fwd(tconv_out_rows(g), dt, y_saved, gamma, beta, mean, var, z, st));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_tconv_eval_bwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                                    const float* gamma, const float* mean, const float* var, const void* y_saved,
+                                    const void* dz, void* dx, void* dW, float* db, float* dgamma, float* dbeta,
+                                    void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  convbn_status s = make_tgeom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
+  REQUIRE_PTR(y_saved); REQUIRE_PTR(dz);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(dx); OPTIONAL_PTR(db);
+  OPTIONAL_PTR(dW); OPTIONAL_PTR(dgamma); OPTIONAL_PTR(dbeta);
+  const bool params = dW != nullptr;
+  if (!params && (dgamma || dbeta || db || !dx))
+    return fail(CONVBN_ERR_NULL, "without dW only dx may be asked for (dgamma, dbeta, db NULL, dx given)");
+  if (params && (!dgamma || !dbeta))
+    return fail(CONVBN_ERR_NULL, "dgamma and dbeta are required together with dW");
+  if (params && (b == nullptr) != (db == nullptr))
+    return fail(CONVBN_ERR_NULL, "db must be given exactly when b is given");
+  const int dt = desc->dtype;
+  s = check_ws(carve_tconv_eval_bwd(g, dt, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const TconvEvalBwdWs w = carve_tconv_eval_bwd(g, dt, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Geom rows = tconv_out_rows(g);
+  LAUNCH(launch_bn_bwd(rows, dt, dz, y_saved, gamma, mean, var, w.dy, w.bn_part, st));   // dY = s dZ and the channel sums
+  if (params) LAUNCH(launch_bn_bwd_finalize(rows, w.bn_part, w.nparts, gamma, var, dgamma, dbeta, db, st));
+  if (dx) LAUNCH(run_fprop(g, dt, w.dy, W, nullptr, dx, w.conv_scratch, st));            // dX = w (*) dY
+  if (!params) return CONVBN_OK;
+  LAUNCH(run_wgrad(g, dt, w.dy, x, w.dwf_part, nullptr, w.wgrad_scratch, st));           // dW = sum X dY
+  LAUNCH(launch_fold_back_t(dt, g.Cout, g.Cin, g.kH * g.kW, w.dwf_part, w.nsplit, nullptr, 0, W, nullptr, nullptr,
+                            nullptr, nullptr, g.eps, nullptr, dW, nullptr, nullptr, nullptr, st));
   return CONVBN_OK;
 }
 

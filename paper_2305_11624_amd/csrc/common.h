@@ -73,11 +73,12 @@ hipError_t launch_fold_back(const Geom& g, int dtype, const float* dwf_part, int
                             void* dW, float* db, float* dgamma, float* dbeta, hipStream_t st);
 // fold_t.hip : fold / fold-back of the transposed block, weight [Ci][taps][Co] with the scale on co.
 // w_same ([Ci][taps][Co]), w_swap ([Co][taps][Ci]) and bfold may each be NULL (skipped).  tap_major != 0:
-// w_swap is [taps][Co][Ci] and bfold [taps][Co] (b' repeated for every tap) instead.
+// w_swap is [taps][Co][Ci] and bfold [taps][Co] (b' repeated for every tap) instead.  gamma == NULL: s = 1, b' = b.
 hipError_t launch_fold_t(int dtype, int Ci, int Co, int taps, const void* W, const float* b, const float* gamma,
                          const float* beta, const float* mean, const float* var, float eps, int tap_major,
                          void* w_same, void* w_swap, float* bfold, hipStream_t st);
 int fold_back_t_chunks(int Ci, int taps);   // rows of dot_part ([chunks][Co] fp32 scratch)
+// gamma == NULL (Eval path): dW = sum of the partial copies only; dot_part and the other outputs are not touched.
 hipError_t launch_fold_back_t(int dtype, int Ci, int Co, int taps, const float* dwf_part, int nsplit,
                               const float* r_part, int nrpart, const void* W, const float* b, const float* gamma,
                               const float* mean, const float* var, float eps, float* dot_part, void* dW, float* db,

@@ -29,9 +29,10 @@ __global__ __launch_bounds__(256) void fold_t_kernel(const T* __restrict__ W, co
   const int tx = threadIdx.x % TT, ty = threadIdx.x / TT;   // ty in [0, 8)
   const int co0 = blockIdx.x * TT, ci0 = blockIdx.y * TT, tap = blockIdx.z;
   const int co = co0 + tx;
-  const float s = co < Co ? gamma[co] / sqrtf(var[co] + eps) : 0.f;
+  // gamma == nullptr (the Eval comparison path): s = 1 and b' = b, i.e. a pure reordering of the weight
+  const float s = co < Co ? (gamma ? gamma[co] / sqrtf(var[co] + eps) : 1.f) : 0.f;
   if (bfold && blockIdx.y == 0 && (tap == 0 || tap_major) && ty == 0 && co < Co)
-    bfold[(tap_major ? tap * Co : 0) + co] = ((b ? b[co] : 0.f) - mean[co]) * s + beta[co];
+    bfold[(tap_major ? tap * Co : 0) + co] = gamma ? ((b ? b[co] : 0.f) - mean[co]) * s + beta[co] : (b ? b[co] : 0.f);
 #pragma unroll
   for (int e = 0; e < TT / 8; ++e) {
     const int ci = ci0 + ty + 8 * e;
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(256) void fold_back_t_kernel(const float* __restric
   if (col < Co) {
     float s[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) s[e] = gamma[col + e] / sqrtf(var[col + e] + eps);
+    for (int e = 0; e < 4; ++e) s[e] = gamma ? gamma[col + e] / sqrtf(var[col + e] + eps) : 1.f;   // null: plain sum
     for (int r = r0 + wave; r < r1; r += 4) {
       const size_t idx = (size_t)r * Co + col;
       float w[4], dw[4] = {0.f, 0.f, 0.f, 0.f};
@@ -104,6 +105,7 @@ __global__ __launch_bounds__(256) void fold_back_t_kernel(const float* __restric
       store4(dW + idx, o);
     }
   }
+  if (!dot_part) return;
 #pragma unroll
   for (int e = 0; e < 4; ++e) red[wave][lane * 4 + e] = dot[e];
   __syncthreads();
@@ -127,7 +129,7 @@ __global__ __launch_bounds__(256) void fold_back_t_scalar_kernel(const float* __
   const size_t P = (size_t)rows * Co;
   float dot = 0.f;
   if (co < Co) {
-    const float s = gamma[co] / sqrtf(var[co] + eps);
+    const float s = gamma ? gamma[co] / sqrtf(var[co] + eps) : 1.f;
     for (int r = r0 + rl; r < r1; r += 4) {
       const size_t idx = (size_t)r * Co + co;
       float dw = 0.f;
@@ -136,6 +138,7 @@ __global__ __launch_bounds__(256) void fold_back_t_scalar_kernel(const float* __
       dot += dw * to_f32(W[idx]);
     }
   }
+  if (!dot_part) return;
   red[rl][c] = dot;
   __syncthreads();
   if (rl == 0 && co < Co) dot_part[(size_t)blockIdx.y * Co + co] = red[0][c] + red[1][c] + red[2][c] + red[3][c];
@@ -202,7 +205,7 @@ hipError_t launch_fold_back_t(int dtype, int Ci, int Co, int taps, const float* 
   else { if (vec) FBT(fold_back_t_kernel, float); else FBT(fold_back_t_scalar_kernel, float); }
 #undef FBT
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || !gamma) return e;   // no gamma: dW = sum of the partial copies, nothing else
   hipLaunchKernelGGL(fold_back_t_finish_kernel, dim3(ceil_div(Co, 16)), dim3(256), 0, st, dot_part, chunks, r_part,
                      nrpart, b, gamma, mean, var, eps, Co, db, dgamma, dbeta);
   return hipGetLastError();

@@ -95,12 +95,13 @@ class BlockRun:
 
 
 class TconvRun:
-    """One TransposedConv-BN block on the GPU in Tune mode (inputs from synth.make_tconv_inputs)."""
+    """One TransposedConv-BN block on the GPU in `mode` ("tune" or "eval"; inputs from synth.make_tconv_inputs)."""
 
-    def __init__(self, inp: Dict[str, object], keep_folded: bool = True, need_dx: bool = True,
+    def __init__(self, inp: Dict[str, object], mode: str = "tune", keep_folded: bool = True, need_dx: bool = True,
                  params: bool = True, device: str = "cuda", poison: bool = False):
+        assert mode in ("tune", "eval")
         s = inp["shape"]
-        self.shape, self.keep_folded = s, keep_folded
+        self.shape, self.mode, self.keep_folded = s, mode, keep_folded
         self.desc = B.desc_from_shape(s, eps=inp["eps"])
         dt = B.torch_dtype(self.desc)
         self.dt = dt
@@ -124,18 +125,33 @@ class TconvRun:
         self.db = out((s.Cout,), torch.float32) if (self.b is not None and params) else None
         self.dgamma = out((s.Cout,), torch.float32) if params else None
         self.dbeta = out((s.Cout,), torch.float32) if params else None
-        self.ws_fwd = BlockRun._ws(B.convbn_tconv_workspace_bytes(self.desc, B.PASS_FWD), device)
-        self.ws_bwd = BlockRun._ws(B.convbn_tconv_workspace_bytes(self.desc, B.PASS_BWD), device)
-        self.w_folded = out((s.Cin, s.k, s.k, s.Cout), dt) if keep_folded else None
+        m = B.MODE_TUNE if mode == "tune" else B.MODE_EVAL
+        self.ws_fwd = BlockRun._ws(B.convbn_tconv_workspace_bytes(self.desc, m, B.PASS_FWD), device)
+        self.ws_bwd = BlockRun._ws(B.convbn_tconv_workspace_bytes(self.desc, m, B.PASS_BWD), device)
+        self.w_folded = out((s.Cin, s.k, s.k, s.Cout), dt) if (keep_folded and mode == "tune") else None
+        self.y_saved = out((s.N, ho, wo, s.Cout), dt) if mode == "eval" else None
+
+    def saved_bytes(self) -> int:
+        m = B.MODE_TUNE if self.mode == "tune" else B.MODE_EVAL
+        return B.convbn_tconv_saved_bytes(self.desc, m, not self.keep_folded)
 
     def forward(self, stream=None):
-        B.convbn_tconv_tune_fwd(self.desc, self.x, self.W, self.b, self.gamma, self.beta, self.mean, self.var,
-                                self.z, self.w_folded, self.ws_fwd, stream)
+        if self.mode == "tune":
+            B.convbn_tconv_tune_fwd(self.desc, self.x, self.W, self.b, self.gamma, self.beta, self.mean, self.var,
+                                    self.z, self.w_folded, self.ws_fwd, stream)
+        else:
+            B.convbn_tconv_eval_fwd(self.desc, self.x, self.W, self.b, self.gamma, self.beta, self.mean, self.var,
+                                    self.z, self.y_saved, self.ws_fwd, stream)
 
     def backward(self, stream=None):
-        B.convbn_tconv_tune_bwd(self.desc, self.x, self.W, self.b, self.gamma, self.mean, self.var,
-                                self.w_folded, self.dz, self.dx, self.dW, self.db, self.dgamma, self.dbeta,
-                                self.ws_bwd, stream)
+        if self.mode == "tune":
+            B.convbn_tconv_tune_bwd(self.desc, self.x, self.W, self.b, self.gamma, self.mean, self.var,
+                                    self.w_folded, self.dz, self.dx, self.dW, self.db, self.dgamma, self.dbeta,
+                                    self.ws_bwd, stream)
+        else:
+            B.convbn_tconv_eval_bwd(self.desc, self.x, self.W, self.b, self.gamma, self.mean, self.var,
+                                    self.y_saved, self.dz, self.dx, self.dW, self.db, self.dgamma, self.dbeta,
+                                    self.ws_bwd, stream)
 
     def step(self, stream=None):
         self.forward(stream)
@@ -149,4 +165,5 @@ class TconvRun:
             dX=B.act_from_device(self.dx) if self.dx is not None else None,
             dW=B.weight_from_device(self.dW) if self.dW is not None else None,
             db=f(self.db), dgamma=f(self.dgamma), dbeta=f(self.dbeta),
-            Wf=B.weight_from_device(self.w_folded) if self.w_folded is not None else None)
+            Wf=B.weight_from_device(self.w_folded) if self.w_folded is not None else None,
+            Y=B.act_from_device(self.y_saved) if self.y_saved is not None else None)

@@ -1,5 +1,5 @@
-"""GPU parity of the TransposedConv-BN block in Tune mode (Sec. 3.2.1, closing remark) against the fp64
-Eval-mode definition of the CPU oracle, through the C ABI."""
+"""GPU parity of the TransposedConv-BN block (Sec. 3.2.1, closing remark), Tune mode and the Eval comparison
+path, against the fp64 Eval-mode definition of the CPU oracle, through the C ABI."""
 import pytest
 import torch
 
@@ -11,6 +11,7 @@ from helpers import compare, oracle_tconv_block
 pytestmark = pytest.mark.gpu
 
 KEYS = ("Z", "dX", "dW", "db", "dgamma", "dbeta", "Wf")
+EVAL_KEYS = ("Z", "dX", "dW", "db", "dgamma", "dbeta", "Y")
 
 
 def _run(inp, **kw):
@@ -34,7 +35,9 @@ F32 = [
 @pytest.mark.parametrize("shape", F32, ids=lambda s: s.name)
 def test_fp32_shapes(shape):
     inp = synth.make_tconv_inputs(shape, bias=True)
-    compare(_run(inp), oracle_tconv_block(inp), "f32", keys=KEYS, tag=shape.name)
+    ref = oracle_tconv_block(inp)
+    compare(_run(inp), ref, "f32", keys=KEYS, tag=shape.name)
+    compare(_run(inp, mode="eval"), ref, "f32", keys=EVAL_KEYS, tag=shape.name + "/eval")
 
 
 BF16 = [
@@ -57,7 +60,9 @@ BF16 = [
 @pytest.mark.parametrize("shape", BF16, ids=lambda s: s.name)
 def test_bf16_shapes(shape):
     inp = synth.make_tconv_inputs(shape, bias=shape.name in ("t_k2s3", "t_k4s2p1", "t_d2s_k2", "t_d2s_k3"))
-    compare(_run(inp), oracle_tconv_block(inp), "bf16", keys=KEYS, tag=shape.name)
+    ref = oracle_tconv_block(inp)
+    compare(_run(inp), ref, "bf16", keys=KEYS, tag=shape.name)
+    compare(_run(inp, mode="eval"), ref, "bf16", keys=EVAL_KEYS, tag=shape.name + "/eval")
 
 
 def test_refold_and_input_gradient_only():
@@ -68,6 +73,7 @@ def test_refold_and_input_gradient_only():
     res = _run(inp, params=False)
     compare(res, ref, "bf16", keys=("Z", "dX"), tag="t_dx_only")
     assert res["dW"] is None and res["dgamma"] is None
+    compare(_run(inp, mode="eval", params=False), ref, "bf16", keys=("Z", "dX"), tag="t_dx_only/eval")
 
 
 def test_wide_scale_with_zero_channels():
@@ -86,7 +92,7 @@ def test_decoder_block_full_size():
 
 def test_errors():
     d = B.make_desc(1, 8, 2, 2, 8, 1, 1, stride=1, pad=1, dtype=B.BF16)   # padding removes the whole output
-    assert B.convbn_tconv_workspace_bytes(d, B.PASS_FWD) == 0
+    assert B.convbn_tconv_workspace_bytes(d, B.MODE_TUNE, B.PASS_FWD) == 0
     x = torch.zeros(64, device="cuda", dtype=torch.bfloat16)
     v = torch.zeros(8, device="cuda")
     st = B.convbn_tconv_tune_fwd(d, x, x, None, v, v, v, v, x, None, None, check=False)

@@ -113,3 +113,47 @@ def test_resnet50_saving_matches_paper_appendix_d(batch, image, eval_gb, tune_gb
     predicted = (ev - tu) / 2 ** 30
     measured = eval_gb - tune_gb
     assert abs(predicted - measured) / measured < 0.04, (predicted, measured)
+
+
+def test_transposed_block_queries_and_validation():
+    """Output size of the transposed convolution (Hout = (Hin-1) s - 2 p + k), workspace queries and the host-side
+    argument checks of its two entry points (nothing is launched: every call fails validation)."""
+    d = B.make_desc(32, 256, 28, 28, 128, 2, 2, 2, 0)
+    assert (B.convbn_tconv_hout(d), B.convbn_tconv_wout(d)) == (56, 56)
+    d4 = B.make_desc(32, 512, 14, 14, 256, 4, 4, 2, 1)
+    assert (B.convbn_tconv_hout(d4), B.convbn_tconv_wout(d4)) == (28, 28)
+    d3 = B.make_desc(2, 8, 5, 7, 8, 3, 3, 1, 1)
+    assert (B.convbn_tconv_hout(d3), B.convbn_tconv_wout(d3)) == (5, 7)
+    T, E = B.MODE_TUNE, B.MODE_EVAL
+    for m in (T, E):
+        for p in (B.PASS_FWD, B.PASS_BWD):
+            assert B.convbn_tconv_workspace_bytes(d, m, p) % 256 == 0 and B.convbn_tconv_workspace_bytes(d, m, p) > 0
+    # forward keeps the transposed scaled weight in the workspace; backward at least one fp32 copy of dw'
+    assert B.convbn_tconv_workspace_bytes(d, T, B.PASS_FWD) >= 256 * 128 * 4 * 2
+    assert B.convbn_tconv_workspace_bytes(d, T, B.PASS_BWD) >= 256 * 128 * 4 * 4
+    # Eval backward additionally holds dY; what stays alive between the passes: Y (Eval) against w' (Tune)
+    assert B.convbn_tconv_workspace_bytes(d, E, B.PASS_BWD) >= 32 * 56 * 56 * 128 * 2
+    assert B.convbn_tconv_saved_bytes(d, E) == 32 * 56 * 56 * 128 * 2
+    assert B.convbn_tconv_saved_bytes(d, T) == 256 * 128 * 4 * 2 and B.convbn_tconv_saved_bytes(d, T, True) == 0
+    L = B.lib()
+    ok = C.c_void_p(4096)
+    need = B.convbn_tconv_workspace_bytes(d, T, B.PASS_FWD)
+    fwd = lambda desc, x=ok, ws=ok, n=need: L.convbn_tconv_tune_fwd(desc, x, ok, None, ok, ok, ok, ok, ok, None, ws, n, None)
+    assert fwd(None) == B.ERR_NULL
+    assert fwd(C.byref(d), x=None) == B.ERR_NULL
+    assert fwd(C.byref(d), x=C.c_void_p(4100)) == B.ERR_UNSUPPORTED
+    assert fwd(C.byref(d), ws=None, n=0) == B.ERR_WORKSPACE
+    assert fwd(C.byref(d), n=need - 1) == B.ERR_WORKSPACE
+    gone = B.make_desc(1, 8, 2, 2, 8, 1, 1, 1, 1)           # padding removes the whole output
+    assert fwd(C.byref(gone)) == B.ERR_SHAPE and B.convbn_tconv_hout(gone) == 0
+    assert B.convbn_tconv_workspace_bytes(gone, T, B.PASS_FWD) == 0
+    needb = B.convbn_tconv_workspace_bytes(d, T, B.PASS_BWD)
+    bwd = lambda dx, dW, db, dg, dbt: L.convbn_tconv_tune_bwd(C.byref(d), ok, ok, None, ok, ok, ok, None, ok, dx, dW, db,
+                                                             dg, dbt, ok, needb, None)
+    assert bwd(ok, ok, ok, ok, ok) == B.ERR_NULL             # db given without b
+    assert bwd(ok, ok, None, None, ok) == B.ERR_NULL         # dgamma missing
+    assert bwd(None, None, None, None, None) == B.ERR_NULL   # nothing asked for
+    assert bwd(ok, None, None, ok, None) == B.ERR_NULL       # dgamma without dW
+    assert L.convbn_tconv_eval_fwd(C.byref(d), ok, ok, None, ok, ok, ok, ok, ok, None, ok, need, None) == B.ERR_NULL   # y_saved
+    assert L.convbn_tconv_eval_bwd(C.byref(d), ok, ok, None, ok, ok, ok, None, ok, ok, ok, None, ok, ok, ok, 1 << 40,
+                                   None) == B.ERR_NULL                                                                   # y_saved
