@@ -434,7 +434,9 @@ int wgrad_splits(const Geom& g) {
   int want = ceil_div(512, tiles);
   const int maxs = ceil_div(g.M, 4 * BK);
   if (want > maxs) want = maxs;
-  if (want > 64) want = 64;
+  // at most 64 slices, except where so few tiles exist that 64 slices leave CUs idle (a 7x7 stem: 2 tiles)
+  const int cap = tiles * 64 >= 256 ? 64 : ceil_div(256, tiles);
+  if (want > cap) want = cap;
   if (want < 1) want = 1;
   // make slices multiples of BK and drop empty ones
   const int per = ceil_div(ceil_div(g.M, want), BK) * BK;
