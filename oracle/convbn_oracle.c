@@ -22,9 +22,10 @@
  *       fold, one convolution, six backward equations.  Present only so the
  *       test-suite can assert Tune == Eval (Sec. 3.4.1) inside the oracle.
  *
- * The same two routes exist for the TransposedConv-BN block (end of file), pinned
- * by the adjoint identity against the convolution above, a library cross-check,
- * finite differences and Tune == Eval.
+ * The same two routes exist for the TransposedConv-BN block and for the depthwise
+ * ConvBN block (end of file), pinned by identities against the convolution above
+ * (adjoint; block-diagonal dense weight), a library cross-check, finite
+ * differences and Tune == Eval.
  *
  * Parity pins (tests marked "not gpu"): library conv2d+batch_norm with autograd
  * on the CPU as an independent special-case check, 1x1 == matrix product,
@@ -477,5 +478,167 @@ void cbo_ttune_bwd(const cb_dims *d, const double *X, const double *W, const dou
     const double r = dbeta[o];
     if (db) db[o] = s * r;
     dgamma[o] = dot / sd + r * ((b ? b[o] : 0.0) - mu[o]) / sd;
+  }
+}
+
+/* --------------------------------------------------- depthwise convolution --- */
+/*
+ * Depthwise ConvBN block: a convolution with as many groups as channels (every
+ * output channel sees only its own input channel), followed by the frozen
+ * BatchNorm of Sec. 3.1.  The scale of Sec. 3.3 is per output channel, so the fold
+ * is unchanged; only the contraction differs (the experiments' GhostNet / MobileNet
+ * style layers, Sec. 4).  W is [C][kH][kW]; cb_dims.Cin == cb_dims.Cout == C.
+ *   Y[n,c,ho,wo] = b[c] + sum_{i,j} W[c,i,j] X[n,c,ho sh + i - ph, wo sw + j - pw]
+ */
+#define DWI(c, i, j) (((size_t)(c) * d->kH + (i)) * d->kW + (j))
+
+void cbo_dw_fwd(const cb_dims *d, const double *X, const double *W, const double *b, double *Y) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int c = 0; c < d->Cout; ++c)
+      for (int ho = 0; ho < Ho; ++ho)
+        for (int wo = 0; wo < Wo; ++wo) {
+          double acc = b ? b[c] : 0.0;
+          for (int i = 0; i < d->kH; ++i) {
+            const int h = ho * d->sh + i - d->ph;
+            if (h < 0 || h >= d->Hin) continue;
+            for (int j = 0; j < d->kW; ++j) {
+              const int w = wo * d->sw + j - d->pw;
+              if (w < 0 || w >= d->Win) continue;
+              acc += W[DWI(c, i, j)] * X[XI(n, c, h, w)];
+            }
+          }
+          Y[YI(n, c, ho, wo)] = acc;
+        }
+}
+
+/* dJ/dX: the transpose of the loop above (scatter form, one thread per (n, c) plane). */
+void cbo_dw_dgrad(const cb_dims *d, const double *W, const double *dY, double *dX) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+  memset(dX, 0, sizeof(double) * (size_t)d->N * d->Cin * d->Hin * d->Win);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int c = 0; c < d->Cout; ++c)
+      for (int ho = 0; ho < Ho; ++ho)
+        for (int wo = 0; wo < Wo; ++wo) {
+          const double g = dY[YI(n, c, ho, wo)];
+          for (int i = 0; i < d->kH; ++i) {
+            const int h = ho * d->sh + i - d->ph;
+            if (h < 0 || h >= d->Hin) continue;
+            for (int j = 0; j < d->kW; ++j) {
+              const int w = wo * d->sw + j - d->pw;
+              if (w < 0 || w >= d->Win) continue;
+              dX[XI(n, c, h, w)] += W[DWI(c, i, j)] * g;
+            }
+          }
+        }
+}
+
+void cbo_dw_wgrad(const cb_dims *d, const double *X, const double *dY, double *dW) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+#pragma omp parallel for schedule(static)
+  for (int c = 0; c < d->Cout; ++c)
+    for (int i = 0; i < d->kH; ++i)
+      for (int j = 0; j < d->kW; ++j) {
+        double acc = 0.0;
+        for (int n = 0; n < d->N; ++n)
+          for (int ho = 0; ho < Ho; ++ho) {
+            const int h = ho * d->sh + i - d->ph;
+            if (h < 0 || h >= d->Hin) continue;
+            for (int wo = 0; wo < Wo; ++wo) {
+              const int w = wo * d->sw + j - d->pw;
+              if (w < 0 || w >= d->Win) continue;
+              acc += dY[YI(n, c, ho, wo)] * X[XI(n, c, h, w)];
+            }
+          }
+        dW[DWI(c, i, j)] = acc;
+      }
+}
+
+/* Eval mode (the definition) and Tune mode (Sec. 3.3, Table 2 "Tune") of the depthwise block. */
+void cbo_dw_eval_fwd(const cb_dims *d, const double *X, const double *W, const double *b,
+                     const double *gamma, const double *beta, const double *mu, const double *var,
+                     double eps, double *Y, double *Z) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+  cbo_dw_fwd(d, X, W, b, Y);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int o = 0; o < d->Cout; ++o) {
+      const double sd = sqrt(var[o] + eps);
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          Z[idx] = gamma[o] * ((Y[idx] - mu[o]) / sd) + beta[o];
+        }
+    }
+}
+
+void cbo_dw_eval_bwd(const cb_dims *d, const double *X, const double *W, const double *gamma,
+                     const double *mu, const double *var, double eps, const double *Y,
+                     const double *G, double *scratch_dY, double *dX, double *dW, double *db,
+                     double *dgamma, double *dbeta) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+  double *dY = scratch_dY;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int o = 0; o < d->Cout; ++o) {
+      const double sd = sqrt(var[o] + eps);
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          dY[idx] = gamma[o] / sd * G[idx];
+        }
+    }
+  if (dX) cbo_dw_dgrad(d, W, dY, dX);
+  cbo_dw_wgrad(d, X, dY, dW);
+  if (db) plane_sum(d, Ho, Wo, dY, NULL, db);
+#pragma omp parallel for schedule(static)
+  for (int o = 0; o < d->Cout; ++o) {
+    const double sd = sqrt(var[o] + eps);
+    double acc = 0.0;
+    for (int n = 0; n < d->N; ++n)
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          acc += G[idx] * ((Y[idx] - mu[o]) / sd);
+        }
+    dgamma[o] = acc;
+  }
+  plane_sum(d, Ho, Wo, G, NULL, dbeta);
+}
+
+void cbo_dw_tune_fwd(const cb_dims *d, const double *X, const double *W, const double *b,
+                     const double *gamma, const double *beta, const double *mu, const double *var,
+                     double eps, double *Wf, double *bf, double *Z) {
+  const size_t row = (size_t)d->kH * d->kW;
+  for (int c = 0; c < d->Cout; ++c) {
+    const double s = gamma[c] / sqrt(var[c] + eps);
+    for (size_t t = 0; t < row; ++t) Wf[c * row + t] = s * W[c * row + t];
+    bf[c] = ((b ? b[c] : 0.0) - mu[c]) * s + beta[c];
+  }
+  cbo_dw_fwd(d, X, Wf, bf, Z);
+}
+
+void cbo_dw_tune_bwd(const cb_dims *d, const double *X, const double *W, const double *b,
+                     const double *gamma, const double *mu, const double *var, double eps,
+                     const double *Wf, const double *G, double *dX, double *dWf, double *dW,
+                     double *db, double *dgamma, double *dbeta) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+  const size_t row = (size_t)d->kH * d->kW;
+  if (dX) cbo_dw_dgrad(d, Wf, G, dX);
+  cbo_dw_wgrad(d, X, G, dWf);
+  plane_sum(d, Ho, Wo, G, NULL, dbeta);
+  for (int c = 0; c < d->Cout; ++c) {
+    const double sd = sqrt(var[c] + eps);
+    const double s = gamma[c] / sd;
+    double dot = 0.0;
+    for (size_t t = 0; t < row; ++t) {
+      dW[c * row + t] = s * dWf[c * row + t];
+      dot += dWf[c * row + t] * W[c * row + t];
+    }
+    const double r = dbeta[c];
+    if (db) db[c] = s * r;
+    dgamma[c] = dot / sd + r * ((b ? b[c] : 0.0) - mu[c]) / sd;
   }
 }
