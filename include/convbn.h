@@ -186,6 +186,33 @@ convbn_status convbn_tconv_eval_bwd(const convbn_desc *desc, const void *x, cons
                                     void *dW, float *db, float *dgamma, float *dbeta, void *ws,
                                     size_t ws_bytes, void *stream);
 
+/* ---- Depthwise ConvBN block -------------------------------------------------------
+ * A convolution with one filter per channel (groups = channels, Cin == Cout == C; CONVBN_ERR_SHAPE
+ * otherwise) followed by the frozen BatchNorm.  The scale of Sec. 3.3 is per output channel, so Tune
+ * mode is unchanged: w'[c] = s_c w[c], b' as above, one (depthwise) convolution, and Table 2's "Tune"
+ * backward with <dw'_c, w_c> summed over the window only.  Layout:
+ *     x, dx [N][Hin][Win][C]      z, dz, y [N][Hout][Wout][C]      W, dW [C][kH][kW]
+ *     w_folded [kH][kW][C]        (w' tap-major: the order the kernels read)
+ * Arguments, NULL rules and error behaviour as for the dense block's four calls. */
+size_t convbn_dw_workspace_bytes(const convbn_desc *desc, int mode, int pass);
+size_t convbn_dw_saved_bytes(const convbn_desc *desc, int mode, int refold);
+convbn_status convbn_dw_tune_fwd(const convbn_desc *desc, const void *x, const void *W, const float *b,
+                                 const float *gamma, const float *beta, const float *mean,
+                                 const float *var, void *z, void *w_folded, void *ws, size_t ws_bytes,
+                                 void *stream);
+convbn_status convbn_dw_tune_bwd(const convbn_desc *desc, const void *x, const void *W, const float *b,
+                                 const float *gamma, const float *mean, const float *var,
+                                 const void *w_folded, const void *dz, void *dx, void *dW, float *db,
+                                 float *dgamma, float *dbeta, void *ws, size_t ws_bytes, void *stream);
+convbn_status convbn_dw_eval_fwd(const convbn_desc *desc, const void *x, const void *W, const float *b,
+                                 const float *gamma, const float *beta, const float *mean,
+                                 const float *var, void *z, void *y_saved, void *ws, size_t ws_bytes,
+                                 void *stream);
+convbn_status convbn_dw_eval_bwd(const convbn_desc *desc, const void *x, const void *W, const float *b,
+                                 const float *gamma, const float *mean, const float *var,
+                                 const void *y_saved, const void *dz, void *dx, void *dW, float *db,
+                                 float *dgamma, float *dbeta, void *ws, size_t ws_bytes, void *stream);
+
 /* ---- The individual steps of the Tune-mode block (each is one kernel) -------------
  * convbn_tune_fwd is convbn_fold followed by convbn_conv_fprop; convbn_tune_bwd is
  * convbn_conv_dgrad, convbn_conv_wgrad and convbn_fold_back.  They are exported so that

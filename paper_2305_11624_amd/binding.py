@@ -27,7 +27,8 @@ EXPORTS = ["convbn_hout", "convbn_wout", "convbn_workspace_bytes", "convbn_saved
            "convbn_aux_maxpool_bwd", "convbn_fold_group_table_bytes", "convbn_fold_group_plan",
            "convbn_fold_group", "convbn_tconv_hout", "convbn_tconv_wout", "convbn_tconv_workspace_bytes",
            "convbn_tconv_tune_fwd", "convbn_tconv_tune_bwd", "convbn_tconv_saved_bytes",
-           "convbn_tconv_eval_fwd", "convbn_tconv_eval_bwd"]
+           "convbn_tconv_eval_fwd", "convbn_tconv_eval_bwd", "convbn_dw_workspace_bytes", "convbn_dw_saved_bytes",
+           "convbn_dw_tune_fwd", "convbn_dw_tune_bwd", "convbn_dw_eval_fwd", "convbn_dw_eval_bwd"]
 
 
 class Desc(C.Structure):
@@ -130,6 +131,13 @@ def lib():
         L.convbn_tconv_tune_fwd.argtypes = L.convbn_tune_fwd.argtypes
         L.convbn_tconv_tune_bwd.restype = C.c_int
         L.convbn_tconv_tune_bwd.argtypes = L.convbn_tune_bwd.argtypes
+        for name in ("convbn_dw_workspace_bytes", "convbn_dw_saved_bytes"):
+            getattr(L, name).restype = C.c_size_t
+            getattr(L, name).argtypes = [dp, C.c_int, C.c_int]
+        for name, like in (("convbn_dw_tune_fwd", L.convbn_tune_fwd), ("convbn_dw_tune_bwd", L.convbn_tune_bwd),
+                           ("convbn_dw_eval_fwd", L.convbn_eval_fwd), ("convbn_dw_eval_bwd", L.convbn_eval_bwd)):
+            getattr(L, name).restype = C.c_int
+            getattr(L, name).argtypes = like.argtypes
         _lib = L
     return _lib
 
@@ -411,6 +419,52 @@ def convbn_tconv_tune_bwd(desc, x, W, b, gamma, mean, var, w_folded, dz, dx, dW,
     if check:
         _check(st)
     return st
+
+
+def convbn_dw_workspace_bytes(desc: Desc, mode: int, pass_: int) -> int:
+    return int(lib().convbn_dw_workspace_bytes(C.byref(desc), mode, pass_))
+
+
+def convbn_dw_saved_bytes(desc: Desc, mode: int, refold: bool = False) -> int:
+    return int(lib().convbn_dw_saved_bytes(C.byref(desc), mode, int(refold)))
+
+
+def _block_fwd(fn, desc, x, W, b, gamma, beta, mean, var, z, keep, ws, stream, check):
+    p, n = _ws(ws)
+    st = fn(C.byref(desc), _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(beta), _ptr(mean), _ptr(var), _ptr(z),
+            _ptr(keep), p, n, _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def _block_bwd(fn, desc, x, W, b, gamma, mean, var, kept, dz, dx, dW, db, dgamma, dbeta, ws, stream, check):
+    p, n = _ws(ws)
+    st = fn(C.byref(desc), _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(mean), _ptr(var), _ptr(kept), _ptr(dz),
+            _ptr(dx), _ptr(dW), _ptr(db), _ptr(dgamma), _ptr(dbeta), p, n, _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_dw_tune_fwd(desc, x, W, b, gamma, beta, mean, var, z, w_folded, ws, stream=None, check=True):
+    return _block_fwd(lib().convbn_dw_tune_fwd, desc, x, W, b, gamma, beta, mean, var, z, w_folded, ws, stream, check)
+
+
+def convbn_dw_tune_bwd(desc, x, W, b, gamma, mean, var, w_folded, dz, dx, dW, db, dgamma, dbeta, ws, stream=None,
+                       check=True):
+    return _block_bwd(lib().convbn_dw_tune_bwd, desc, x, W, b, gamma, mean, var, w_folded, dz, dx, dW, db, dgamma,
+                      dbeta, ws, stream, check)
+
+
+def convbn_dw_eval_fwd(desc, x, W, b, gamma, beta, mean, var, z, y_saved, ws, stream=None, check=True):
+    return _block_fwd(lib().convbn_dw_eval_fwd, desc, x, W, b, gamma, beta, mean, var, z, y_saved, ws, stream, check)
+
+
+def convbn_dw_eval_bwd(desc, x, W, b, gamma, mean, var, y_saved, dz, dx, dW, db, dgamma, dbeta, ws, stream=None,
+                       check=True):
+    return _block_bwd(lib().convbn_dw_eval_bwd, desc, x, W, b, gamma, mean, var, y_saved, dz, dx, dW, db, dgamma,
+                      dbeta, ws, stream, check)
 
 
 # ---- channels-last device buffers (pure permutes and casts) -------------------

@@ -349,6 +349,42 @@ TconvEvalBwdWs carve_tconv_eval_bwd(const Geom& g, int dtype, void* ws) {
   return r;
 }
 
+// ---- depthwise block -----------------------------------------------------------------------------------
+convbn_status make_dwgeom(const convbn_desc* d, Geom* g) {
+  const convbn_status s = make_geom(d, g);
+  if (s != CONVBN_OK) return s;
+  if (d->Cin != d->Cout) return fail(CONVBN_ERR_SHAPE, "a depthwise block has Cin == Cout (one filter per channel)");
+  return CONVBN_OK;
+}
+struct DwFwdWs { void* wf; float* bfold; size_t bytes; };
+DwFwdWs carve_dw_fwd(const Geom& g, int dtype, void* ws) {
+  Carve c(ws);
+  DwFwdWs r;
+  r.wf = c.take((size_t)g.kH * g.kW * g.Cin * esize(dtype));
+  r.bfold = (float*)c.take((size_t)g.Cin * 4);
+  r.bytes = c.off;
+  return r;
+}
+struct DwBwdWs { void* wf; void* dy; float* part; float* r_part; float* sums; float* bn_part; int slices; int nparts; size_t bytes; };
+DwBwdWs carve_dw_bwd(const Geom& g, int dtype, int mode, void* ws) {
+  Carve c(ws);
+  DwBwdWs r;
+  const int taps = g.kH * g.kW;
+  r.slices = dw_wgrad_slices(g, dtype);
+  r.nparts = bn_bwd_parts(g);
+  r.wf = c.take((size_t)taps * g.Cin * esize(dtype));
+  r.part = (float*)c.take((size_t)r.slices * taps * g.Cin * 4);
+  r.r_part = (float*)c.take((size_t)r.slices * g.Cin * 4);
+  r.sums = (float*)c.take((size_t)(taps + 1) * g.Cin * 4);
+  r.dy = nullptr; r.bn_part = nullptr;
+  if (mode == CONVBN_MODE_EVAL) {
+    r.dy = c.take((size_t)g.M * g.Cout * esize(dtype));
+    r.bn_part = (float*)c.take((size_t)r.nparts * 2 * g.Cout * 4);
+  }
+  r.bytes = c.off;
+  return r;
+}
+
 }  // namespace
 
 extern "C" {
@@ -649,6 +685,135 @@ convbn_status convbn_tconv_eval_bwd(const convbn_desc* desc, const void* x, cons
   LAUNCH(run_wgrad(g, dt, w.dy, x, w.dwf_part, nullptr, w.wgrad_scratch, st));           // dW = sum X dY
   LAUNCH(launch_fold_back_t(dt, g.Cout, g.Cin, g.kH * g.kW, w.dwf_part, w.nsplit, nullptr, 0, W, nullptr, nullptr,
                             nullptr, nullptr, g.eps, nullptr, dW, nullptr, nullptr, nullptr, st));
+  return CONVBN_OK;
+}
+
+size_t convbn_dw_workspace_bytes(const convbn_desc* desc, int mode, int pass) {
+  Geom g;
+  if (make_dwgeom(desc, &g) != CONVBN_OK) return 0;
+  if (mode != CONVBN_MODE_TUNE && mode != CONVBN_MODE_EVAL) return 0;
+  return pass == CONVBN_PASS_FWD ? carve_dw_fwd(g, desc->dtype, nullptr).bytes
+                                 : carve_dw_bwd(g, desc->dtype, mode, nullptr).bytes;
+}
+
+size_t convbn_dw_saved_bytes(const convbn_desc* desc, int mode, int refold) {
+  Geom g;
+  if (make_dwgeom(desc, &g) != CONVBN_OK) return 0;
+  if (mode == CONVBN_MODE_EVAL) return (size_t)g.M * g.Cout * esize(desc->dtype);
+  return refold ? 0 : (size_t)g.kH * g.kW * g.Cin * esize(desc->dtype);
+}
+
+convbn_status convbn_dw_tune_fwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                                 const float* gamma, const float* beta, const float* mean, const float* var,
+                                 void* z, void* w_folded, void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  convbn_status s = make_dwgeom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(beta); REQUIRE_PTR(mean);
+  REQUIRE_PTR(var); REQUIRE_PTR(z);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(w_folded);
+  const int dt = desc->dtype;
+  s = check_ws(carve_dw_fwd(g, dt, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const DwFwdWs w = carve_dw_fwd(g, dt, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  void* wf = w_folded ? w_folded : w.wf;
+  LAUNCH(launch_dw_fold(g, dt, W, b, gamma, beta, mean, var, wf, w.bfold, st));   // w' = s w (tap-major), b'
+  LAUNCH(launch_dw_fprop(g, dt, x, wf, w.bfold, z, st));                          // Z = w' (*) X + b'
+  return CONVBN_OK;
+}
+
+convbn_status convbn_dw_tune_bwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                                 const float* gamma, const float* mean, const float* var, const void* w_folded,
+                                 const void* dz, void* dx, void* dW, float* db, float* dgamma, float* dbeta,
+                                 void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  convbn_status s = make_dwgeom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
+  REQUIRE_PTR(dz);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(w_folded); OPTIONAL_PTR(dx); OPTIONAL_PTR(db);
+  OPTIONAL_PTR(dW); OPTIONAL_PTR(dgamma); OPTIONAL_PTR(dbeta);
+  const bool params = dW != nullptr;
+  if (!params && (dgamma || dbeta || db || !dx))
+    return fail(CONVBN_ERR_NULL, "without dW only dx may be asked for (dgamma, dbeta, db NULL, dx given)");
+  if (params && (!dgamma || !dbeta))
+    return fail(CONVBN_ERR_NULL, "dgamma and dbeta are required together with dW");
+  if (params && (b == nullptr) != (db == nullptr))
+    return fail(CONVBN_ERR_NULL, "db must be given exactly when b is given");
+  const int dt = desc->dtype;
+  s = check_ws(carve_dw_bwd(g, dt, CONVBN_MODE_TUNE, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const DwBwdWs w = carve_dw_bwd(g, dt, CONVBN_MODE_TUNE, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (dx) {
+    const void* wf = w_folded;
+    if (!wf) {
+      LAUNCH(launch_dw_fold(g, dt, W, b, gamma, nullptr, mean, var, w.wf, nullptr, st));
+      wf = w.wf;
+    }
+    LAUNCH(launch_dw_dgrad(g, dt, dz, wf, dx, st));                                // dX = w'_rot (*) dZ
+  }
+  if (!params) return CONVBN_OK;
+  LAUNCH(launch_dw_wgrad(g, dt, x, dz, w.part, w.r_part, st));                     // dw' = dZ (.) X, r = sum dZ
+  LAUNCH(launch_dw_fold_back(g, dt, w.part, w.r_part, w.slices, w.sums, W, b, gamma, mean, var, dW, db, dgamma,
+                             dbeta, st));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_dw_eval_fwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                                 const float* gamma, const float* beta, const float* mean, const float* var,
+                                 void* z, void* y_saved, void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  convbn_status s = make_dwgeom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(beta); REQUIRE_PTR(mean);
+  REQUIRE_PTR(var); REQUIRE_PTR(z); REQUIRE_PTR(y_saved);
+  OPTIONAL_PTR(b);
+  const int dt = desc->dtype;
+  s = check_ws(carve_dw_fwd(g, dt, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const DwFwdWs w = carve_dw_fwd(g, dt, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  LAUNCH(launch_dw_fold(g, dt, W, b, nullptr, nullptr, nullptr, nullptr, w.wf, w.bfold, st));   // reorder only
+  LAUNCH(launch_dw_fprop(g, dt, x, w.wf, w.bfold, y_saved, st));                                 // Y = w (*) X + b
+  LAUNCH(launch_bn_affine_fwd(g, dt, y_saved, gamma, beta, mean, var, z, st));                   // Z from Y
+  return CONVBN_OK;
+}
+
+convbn_status convbn_dw_eval_bwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                                 const float* gamma, const float* mean, const float* var, const void* y_saved,
+                                 const void* dz, void* dx, void* dW, float* db, float* dgamma, float* dbeta,
+                                 void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  convbn_status s = make_dwgeom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
+  REQUIRE_PTR(y_saved); REQUIRE_PTR(dz);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(dx); OPTIONAL_PTR(db);
+  OPTIONAL_PTR(dW); OPTIONAL_PTR(dgamma); OPTIONAL_PTR(dbeta);
+  const bool params = dW != nullptr;
+  if (!params && (dgamma || dbeta || db || !dx))
+    return fail(CONVBN_ERR_NULL, "without dW only dx may be asked for (dgamma, dbeta, db NULL, dx given)");
+  if (params && (!dgamma || !dbeta))
+    return fail(CONVBN_ERR_NULL, "dgamma and dbeta are required together with dW");
+  if (params && (b == nullptr) != (db == nullptr))
+    return fail(CONVBN_ERR_NULL, "db must be given exactly when b is given");
+  const int dt = desc->dtype;
+  s = check_ws(carve_dw_bwd(g, dt, CONVBN_MODE_EVAL, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const DwBwdWs w = carve_dw_bwd(g, dt, CONVBN_MODE_EVAL, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  LAUNCH(launch_bn_bwd(g, dt, dz, y_saved, gamma, mean, var, w.dy, w.bn_part, st));
+  if (params) LAUNCH(launch_bn_bwd_finalize(g, w.bn_part, w.nparts, gamma, var, dgamma, dbeta, db, st));
+  if (dx) {
+    LAUNCH(launch_dw_fold(g, dt, W, nullptr, nullptr, nullptr, nullptr, nullptr, w.wf, nullptr, st));
+    LAUNCH(launch_dw_dgrad(g, dt, w.dy, w.wf, dx, st));
+  }
+  if (!params) return CONVBN_OK;
+  LAUNCH(launch_dw_wgrad(g, dt, x, w.dy, w.part, nullptr, st));
+  LAUNCH(launch_dw_fold_back(g, dt, w.part, nullptr, w.slices, w.sums, W, nullptr, nullptr, nullptr, nullptr, dW,
+                             nullptr, nullptr, nullptr, st));
   return CONVBN_OK;
 }
 

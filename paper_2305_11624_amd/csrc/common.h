@@ -109,6 +109,22 @@ hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, unsigned char* 
 hipError_t launch_maxpool_bwd(int dtype, const void* dy, const unsigned char* idx, void* dx, int N, int H, int W,
                               int C, hipStream_t st);
 
+// depthwise.hip : the depthwise block (groups = channels; g.Cin == g.Cout), plain vector kernels.
+// wf is the folded filter in tap-major order [kH kW][C]; gamma == NULL means s = 1 (Eval comparison path).
+hipError_t launch_dw_fold(const Geom& g, int dtype, const void* W, const float* b, const float* gamma,
+                          const float* beta, const float* mean, const float* var, void* wf, float* bfold,
+                          hipStream_t st);
+hipError_t launch_dw_fprop(const Geom& g, int dtype, const void* x, const void* wf, const float* bias, void* z,
+                           hipStream_t st);
+hipError_t launch_dw_dgrad(const Geom& g, int dtype, const void* dz, const void* wf, void* dx, hipStream_t st);
+int dw_wgrad_slices(const Geom& g, int dtype);
+// part [slices][taps][C], r_part [slices][C] (nullable), sums [(taps + 1)][C]: fp32 scratch
+hipError_t launch_dw_wgrad(const Geom& g, int dtype, const void* x, const void* dz, float* part, float* r_part,
+                           hipStream_t st);
+hipError_t launch_dw_fold_back(const Geom& g, int dtype, const float* part, const float* r_part, int slices,
+                               float* sums, const void* W, const float* b, const float* gamma, const float* mean,
+                               const float* var, void* dW, float* db, float* dgamma, float* dbeta, hipStream_t st);
+
 // conv_direct.hip : one thread per output element, fp32 accumulation (any shape, both dtypes)
 hipError_t launch_fprop_direct(const Geom& g, int dtype, const void* x, const void* w_krsc,
                                const float* bias, void* z, hipStream_t st);

@@ -1,0 +1,327 @@
+// Depthwise ConvBN block in Tune mode: one filter per channel (groups = channels), BatchNorm folded into
+// the filter exactly as for the dense block (Sec. 3.3: the scale is per output channel, so
+// w'[c] = s_c w[c], b' = (b - mu) s + beta), backward by Table 2's "Tune" row.
+//
+// A depthwise convolution has 2 k^2 FLOP per output element against 2-4 bytes of traffic: it is bound by
+// memory, not by the matrix cores, so these are plain vector kernels: channels-last tensors, a thread owns
+// VEC consecutive channels of one pixel (bf16: 8 channels = one 16-byte access, consecutive threads =
+// consecutive channels), the k^2 window positions are re-read through the caches.
+//   x, dx [N][H][W][C]   z, dz [N][Ho][Wo][C]   W, dW [C][kH][kW]   folded filter wf [kH kW][C] (tap-major)
+#include "common.h"
+
+namespace convbn {
+
+namespace {
+
+template <typename T, int VEC> struct Vec;
+template <> struct Vec<float, 1> {
+  static __device__ __forceinline__ void load(const float* p, float (&v)[1]) { v[0] = *p; }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[1]) { *p = v[0]; }
+};
+template <> struct Vec<bf16_t, 1> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[1]) { v[0] = (float)*p; }
+  static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[1]) { *p = (bf16_t)v[0]; }
+};
+template <> struct Vec<bf16_t, 8> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
+    const uint4 t = *reinterpret_cast<const uint4*>(p);
+    v[0] = bf16_lo(t.x); v[1] = bf16_hi(t.x); v[2] = bf16_lo(t.y); v[3] = bf16_hi(t.y);
+    v[4] = bf16_lo(t.z); v[5] = bf16_hi(t.z); v[6] = bf16_lo(t.w); v[7] = bf16_hi(t.w);
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
+    *reinterpret_cast<uint4*>(p) = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
+                                              pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+  }
+};
+
+// wf[tap][c] = s_c W[c][tap], bfold[c] = (b - mu) s + beta.  gamma == nullptr: s = 1, b' = b.
+template <typename T>
+__global__ __launch_bounds__(256) void dw_fold_kernel(const T* __restrict__ W, const float* __restrict__ b,
+                                                      const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                      const float* __restrict__ mean, const float* __restrict__ var,
+                                                      float eps, int C, int taps, T* __restrict__ wf,
+                                                      float* __restrict__ bfold) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  const float s = gamma ? gamma[c] / sqrtf(var[c] + eps) : 1.f;
+  if (wf)
+    for (int t = 0; t < taps; ++t) wf[(size_t)t * C + c] = from_f32<T>(to_f32(W[(size_t)c * taps + t]) * s);
+  if (bfold) bfold[c] = gamma ? ((b ? b[c] : 0.f) - mean[c]) * s + beta[c] : (b ? b[c] : 0.f);
+}
+
+// Z[m][c] = b'[c] + sum_tap wf[tap][c] X[window position][c]
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void dw_fprop_kernel(const T* __restrict__ x, const T* __restrict__ wf,
+                                                       const float* __restrict__ bias, T* __restrict__ z, Geom g) {
+  const int cgs = g.Cin / VEC;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)g.M * cgs) return;
+  const int c = (int)(idx % cgs) * VEC;
+  int m = (int)(idx / cgs);
+  const int wo = m % g.Wout;
+  m /= g.Wout;
+  const int ho = m % g.Hout, n = m / g.Hout;
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = bias ? bias[c + e] : 0.f;
+  for (int i = 0; i < g.kH; ++i) {
+    const int h = ho * g.sh + i - g.ph;
+    if ((unsigned)h >= (unsigned)g.Hin) continue;
+    for (int j = 0; j < g.kW; ++j) {
+      const int w = wo * g.sw + j - g.pw;
+      if ((unsigned)w >= (unsigned)g.Win) continue;
+      float xv[VEC], wv[VEC];
+      Vec<T, VEC>::load(x + (((size_t)n * g.Hin + h) * g.Win + w) * g.Cin + c, xv);
+      Vec<T, VEC>::load(wf + (size_t)(i * g.kW + j) * g.Cin + c, wv);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] += xv[e] * wv[e];
+    }
+  }
+  Vec<T, VEC>::store(z + idx * VEC, acc);
+}
+
+// dX[m'][c] = sum_tap wf[tap][c] dZ[(h + ph - i)/sh, (w + pw - j)/sw][c] over the taps whose quotients are exact
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void dw_dgrad_kernel(const T* __restrict__ dz, const T* __restrict__ wf,
+                                                       T* __restrict__ dx, Geom g) {
+  const int cgs = g.Cin / VEC;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)g.Min * cgs) return;
+  const int c = (int)(idx % cgs) * VEC;
+  int m = (int)(idx / cgs);
+  const int w = m % g.Win;
+  m /= g.Win;
+  const int h = m % g.Hin, n = m / g.Hin;
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+  for (int i = 0; i < g.kH; ++i) {
+    const int hz = h + g.ph - i;
+    if (hz < 0 || hz % g.sh != 0) continue;
+    const int ho = hz / g.sh;
+    if (ho >= g.Hout) continue;
+    for (int j = 0; j < g.kW; ++j) {
+      const int wz = w + g.pw - j;
+      if (wz < 0 || wz % g.sw != 0) continue;
+      const int wo = wz / g.sw;
+      if (wo >= g.Wout) continue;
+      float gv[VEC], wv[VEC];
+      Vec<T, VEC>::load(dz + (((size_t)n * g.Hout + ho) * g.Wout + wo) * g.Cin + c, gv);
+      Vec<T, VEC>::load(wf + (size_t)(i * g.kW + j) * g.Cin + c, wv);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] += gv[e] * wv[e];
+    }
+  }
+  Vec<T, VEC>::store(dx + idx * VEC, acc);
+}
+
+constexpr int WG_TAPS = 9;     // window positions a weight-gradient workgroup accumulates at once
+constexpr int WG_CG = 32;      // channel groups per workgroup (x 8 pixel lanes = 256 threads)
+
+// Partial sums over one slice of the output pixels (blockIdx.y) for WG_TAPS window positions starting at
+// tap0 = WG_TAPS blockIdx.z:  part[slice][tap][c] = sum_m dZ[m][c] X[window position of m][c], and (first tap
+// chunk only) r_part[slice][c] = sum_m dZ[m][c].  Thread -> channel group tid % 32, pixel lane tid / 32.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void dw_wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dz,
+                                                       float* __restrict__ part, float* __restrict__ r_part, Geom g,
+                                                       int px_per_slice) {
+  __shared__ float red[8][WG_CG * VEC];
+  const int cgs = g.Cin / VEC;
+  const int tx = threadIdx.x % WG_CG, ty = threadIdx.x / WG_CG;
+  const int cg = blockIdx.x * WG_CG + tx;
+  const bool live = cg < cgs;
+  const int c = cg * VEC;
+  const int taps = g.kH * g.kW, tap0 = blockIdx.z * WG_TAPS;
+  const int m0 = blockIdx.y * px_per_slice, m1 = min(g.M, m0 + px_per_slice);
+  float acc[WG_TAPS][VEC], racc[VEC];
+#pragma unroll
+  for (int t = 0; t < WG_TAPS; ++t)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[t][e] = 0.f;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) racc[e] = 0.f;
+  if (live)
+    for (int m = m0 + ty; m < m1; m += 8) {
+      const int wo = m % g.Wout;
+      const int q = m / g.Wout;
+      const int ho = q % g.Hout, n = q / g.Hout;
+      float gv[VEC];
+      Vec<T, VEC>::load(dz + (size_t)m * g.Cin + c, gv);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) racc[e] += gv[e];
+#pragma unroll
+      for (int t = 0; t < WG_TAPS; ++t) {
+        const int tap = tap0 + t;
+        if (tap >= taps) break;
+        const int i = tap / g.kW, j = tap - i * g.kW;
+        const int h = ho * g.sh + i - g.ph, w = wo * g.sw + j - g.pw;
+        if ((unsigned)h >= (unsigned)g.Hin || (unsigned)w >= (unsigned)g.Win) continue;
+        float xv[VEC];
+        Vec<T, VEC>::load(x + (((size_t)n * g.Hin + h) * g.Win + w) * g.Cin + c, xv);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[t][e] += gv[e] * xv[e];
+      }
+    }
+  // reduce the eight pixel lanes, one window position at a time (t == WG_TAPS: the channel sums)
+  const int ncol = WG_CG * VEC;
+#pragma unroll
+  for (int t = 0; t <= WG_TAPS; ++t) {
+    const int tap = tap0 + t;
+    if (t < WG_TAPS && tap >= taps) continue;
+    if (t == WG_TAPS && (blockIdx.z != 0 || !r_part)) continue;
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) red[ty][tx * VEC + e] = t < WG_TAPS ? acc[t < WG_TAPS ? t : 0][e] : racc[e];
+    __syncthreads();
+    for (int col = threadIdx.x; col < ncol; col += 256) {
+      const int cc = blockIdx.x * ncol + col;
+      if (cc >= g.Cin) continue;
+      float v = 0.f;
+#pragma unroll
+      for (int l = 0; l < 8; ++l) v += red[l][col];
+      if (t < WG_TAPS) part[((size_t)blockIdx.y * taps + tap) * g.Cin + cc] = v;
+      else r_part[(size_t)blockIdx.y * g.Cin + cc] = v;
+    }
+  }
+}
+
+// sums[row][c] = sum over slices of part[slice][row][c] (rows 0..taps-1) and of r_part[slice][c] (row taps).
+// grid (ceil(C/64), taps + 1), thread -> channel tid % 64, slice lane tid / 64
+__global__ __launch_bounds__(256) void dw_reduce_kernel(const float* __restrict__ part, const float* __restrict__ r_part,
+                                                        int slices, int taps, int C, float* __restrict__ sums) {
+  __shared__ float red[4][64];
+  const int cl = threadIdx.x & 63, l = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl, row = blockIdx.y;
+  float v = 0.f;
+  if (c < C && (row < taps || r_part))
+    for (int s = l; s < slices; s += 4)
+      v += row < taps ? part[((size_t)s * taps + row) * C + c] : r_part[(size_t)s * C + c];
+  red[l][cl] = v;
+  __syncthreads();
+  if (l == 0 && c < C) sums[(size_t)row * C + c] = red[0][cl] + red[1][cl] + red[2][cl] + red[3][cl];
+}
+
+// dW[c][tap] = s dw', dgamma = (sum_tap dw' w + r (b - mu)) / sqrt(var + eps), dbeta = r, db = s r.
+// gamma == nullptr (Eval path): dW = dw' only.
+template <typename T>
+__global__ __launch_bounds__(256) void dw_fold_back_kernel(const float* __restrict__ sums, const T* __restrict__ W,
+                                                           const float* __restrict__ b, const float* __restrict__ gamma,
+                                                           const float* __restrict__ mean, const float* __restrict__ var,
+                                                           float eps, int C, int taps, T* __restrict__ dW,
+                                                           float* __restrict__ db, float* __restrict__ dgamma,
+                                                           float* __restrict__ dbeta) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  const float sd = gamma ? sqrtf(var[c] + eps) : 1.f;
+  const float s = gamma ? gamma[c] / sd : 1.f;
+  float dot = 0.f;
+  for (int t = 0; t < taps; ++t) {
+    const float dw = sums[(size_t)t * C + c];
+    dW[(size_t)c * taps + t] = from_f32<T>(s * dw);
+    dot += dw * to_f32(W[(size_t)c * taps + t]);
+  }
+  if (!gamma) return;
+  const float r = sums[(size_t)taps * C + c];
+  dgamma[c] = (dot + r * ((b ? b[c] : 0.f) - mean[c])) / sd;
+  dbeta[c] = r;
+  if (db) db[c] = s * r;
+}
+
+bool vec8(const Geom& g, int dtype) { return dtype == CONVBN_BF16 && g.Cin % 8 == 0; }
+
+}  // namespace
+
+hipError_t launch_dw_fold(const Geom& g, int dtype, const void* W, const float* b, const float* gamma,
+                          const float* beta, const float* mean, const float* var, void* wf, float* bfold,
+                          hipStream_t st) {
+  const int C = g.Cin, taps = g.kH * g.kW;
+  if (dtype == CONVBN_BF16)
+    hipLaunchKernelGGL(dw_fold_kernel<bf16_t>, dim3(ceil_div(C, 256)), dim3(256), 0, st, (const bf16_t*)W, b, gamma,
+                       beta, mean, var, g.eps, C, taps, (bf16_t*)wf, bfold);
+  else
+    hipLaunchKernelGGL(dw_fold_kernel<float>, dim3(ceil_div(C, 256)), dim3(256), 0, st, (const float*)W, b, gamma, beta,
+                       mean, var, g.eps, C, taps, (float*)wf, bfold);
+  return hipGetLastError();
+}
+
+hipError_t launch_dw_fprop(const Geom& g, int dtype, const void* x, const void* wf, const float* bias, void* z,
+                           hipStream_t st) {
+  const int vec = vec8(g, dtype) ? 8 : 1;
+  const size_t total = (size_t)g.M * (g.Cin / vec);
+  const dim3 grid((unsigned)((total + 255) / 256));
+  if (vec == 8)
+    hipLaunchKernelGGL((dw_fprop_kernel<bf16_t, 8>), grid, dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)wf, bias,
+                       (bf16_t*)z, g);
+  else if (dtype == CONVBN_BF16)
+    hipLaunchKernelGGL((dw_fprop_kernel<bf16_t, 1>), grid, dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)wf, bias,
+                       (bf16_t*)z, g);
+  else
+    hipLaunchKernelGGL((dw_fprop_kernel<float, 1>), grid, dim3(256), 0, st, (const float*)x, (const float*)wf, bias,
+                       (float*)z, g);
+  return hipGetLastError();
+}
+
+hipError_t launch_dw_dgrad(const Geom& g, int dtype, const void* dz, const void* wf, void* dx, hipStream_t st) {
+  const int vec = vec8(g, dtype) ? 8 : 1;
+  const size_t total = (size_t)g.Min * (g.Cin / vec);
+  const dim3 grid((unsigned)((total + 255) / 256));
+  if (vec == 8)
+    hipLaunchKernelGGL((dw_dgrad_kernel<bf16_t, 8>), grid, dim3(256), 0, st, (const bf16_t*)dz, (const bf16_t*)wf,
+                       (bf16_t*)dx, g);
+  else if (dtype == CONVBN_BF16)
+    hipLaunchKernelGGL((dw_dgrad_kernel<bf16_t, 1>), grid, dim3(256), 0, st, (const bf16_t*)dz, (const bf16_t*)wf,
+                       (bf16_t*)dx, g);
+  else
+    hipLaunchKernelGGL((dw_dgrad_kernel<float, 1>), grid, dim3(256), 0, st, (const float*)dz, (const float*)wf,
+                       (float*)dx, g);
+  return hipGetLastError();
+}
+
+// pixel slices of the weight-gradient reduction: enough workgroups to fill the chip a few times over
+int dw_wgrad_slices(const Geom& g, int dtype) {
+  const int vec = vec8(g, dtype) ? 8 : 1;
+  const int cblocks = ceil_div(g.Cin / vec, WG_CG) * ceil_div(g.kH * g.kW, WG_TAPS);
+  int want = ceil_div(1024, cblocks);
+  const int maxs = ceil_div(g.M, 64);
+  if (want > maxs) want = maxs;
+  if (want > 512) want = 512;
+  if (want < 1) want = 1;
+  return ceil_div(g.M, ceil_div(g.M, want));
+}
+
+hipError_t launch_dw_wgrad(const Geom& g, int dtype, const void* x, const void* dz, float* part, float* r_part,
+                           hipStream_t st) {
+  const int vec = vec8(g, dtype) ? 8 : 1;
+  const int slices = dw_wgrad_slices(g, dtype);
+  const int pps = ceil_div(g.M, slices);
+  const dim3 grid(ceil_div(g.Cin / vec, WG_CG), slices, ceil_div(g.kH * g.kW, WG_TAPS));
+  if (vec == 8)
+    hipLaunchKernelGGL((dw_wgrad_kernel<bf16_t, 8>), grid, dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)dz, part,
+                       r_part, g, pps);
+  else if (dtype == CONVBN_BF16)
+    hipLaunchKernelGGL((dw_wgrad_kernel<bf16_t, 1>), grid, dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)dz, part,
+                       r_part, g, pps);
+  else
+    hipLaunchKernelGGL((dw_wgrad_kernel<float, 1>), grid, dim3(256), 0, st, (const float*)x, (const float*)dz, part,
+                       r_part, g, pps);
+  return hipGetLastError();
+}
+
+hipError_t launch_dw_fold_back(const Geom& g, int dtype, const float* part, const float* r_part, int slices,
+                               float* sums, const void* W, const float* b, const float* gamma, const float* mean,
+                               const float* var, void* dW, float* db, float* dgamma, float* dbeta, hipStream_t st) {
+  const int C = g.Cin, taps = g.kH * g.kW;
+  hipLaunchKernelGGL(dw_reduce_kernel, dim3(ceil_div(C, 64), taps + 1), dim3(256), 0, st, part, r_part, slices, taps, C,
+                     sums);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (dtype == CONVBN_BF16)
+    hipLaunchKernelGGL(dw_fold_back_kernel<bf16_t>, dim3(ceil_div(C, 256)), dim3(256), 0, st, sums, (const bf16_t*)W, b,
+                       gamma, mean, var, g.eps, C, taps, (bf16_t*)dW, db, dgamma, dbeta);
+  else
+    hipLaunchKernelGGL(dw_fold_back_kernel<float>, dim3(ceil_div(C, 256)), dim3(256), 0, st, sums, (const float*)W, b,
+                       gamma, mean, var, g.eps, C, taps, (float*)dW, db, dgamma, dbeta);
+  return hipGetLastError();
+}
+
+}  // namespace convbn

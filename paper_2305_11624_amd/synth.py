@@ -160,6 +160,33 @@ def make_tconv_inputs(shape: BlockShape, seed: Optional[int] = None, bias: bool 
                 eps=eps)
 
 
+def make_dw_inputs(shape: BlockShape, seed: Optional[int] = None, bias: bool = False,
+                   wide_scale: bool = False) -> Dict[str, object]:
+    """Tensors of a depthwise ConvBN block (Cin == Cout, one filter per channel): W is the logical [C, 1, k, k]
+    ~ N(0, 2/k^2) (fan-in k^2); everything else as make_inputs."""
+    assert shape.Cin == shape.Cout
+    g = torch.Generator(device="cpu")
+    g.manual_seed(shape.seed if seed is None else seed)
+    s = shape
+    x = torch.randn(s.N, s.Cin, s.Hin, s.Win, generator=g)
+    W = torch.randn(s.Cout, 1, s.k, s.k, generator=g) * (2.0 / (s.k * s.k)) ** 0.5
+    gamma = torch.rand(s.Cout, generator=g) + 0.5
+    beta = torch.randn(s.Cout, generator=g) * 0.1
+    rmean = torch.randn(s.Cout, generator=g) * 0.1
+    rvar = torch.rand(s.Cout, generator=g) * 1.5 + 0.5
+    dy = torch.randn(s.N, s.Cout, s.Hout, s.Wout, generator=g)
+    b = torch.randn(s.Cout, generator=g) * 0.1 if bias else None
+    eps = 1e-5
+    if wide_scale:
+        scale = torch.rand(s.Cout, generator=g) * 30.0
+        scale[:: max(1, s.Cout // 4)] = 0.0
+        gamma = scale * torch.sqrt(rvar + eps)
+    if s.dtype == "bf16":
+        x, W, dy = round_bf16(x), round_bf16(W), round_bf16(dy)
+    return dict(shape=s, x=x, W=W, b=b, gamma=gamma, beta=beta, rmean=rmean, rvar=rvar, dy=dy,
+                eps=eps)
+
+
 def make_params(shape: BlockShape, seed: Optional[int] = None) -> Dict[str, object]:
     """Only the parameters of a block (same distributions and draw order as make_inputs, but
     without the activation-sized tensors): W, gamma, beta, running mean, running var."""

@@ -42,6 +42,19 @@ def oracle_tconv_block(inp, need_dx=True):
     return g
 
 
+def oracle_dw_block(inp, need_dx=True):
+    """Eval-mode definition of the depthwise ConvBN block in fp64 (plus the folded filter of its Tune route)."""
+    d = dims_of(inp["shape"])
+    a = {k: _np(inp[k]) for k in ("x", "W", "b", "gamma", "beta", "rmean", "rvar", "dy")}
+    Y, Z = oracle.dw_eval_fwd(d, a["x"], a["W"], a["b"], a["gamma"], a["beta"], a["rmean"], a["rvar"], inp["eps"])
+    g = oracle.dw_eval_bwd(d, a["x"], a["W"], a["b"], a["gamma"], a["rmean"], a["rvar"], inp["eps"], Y, a["dy"],
+                           need_dx=need_dx)
+    Wf, bf, _ = oracle.dw_tune_fwd(d, a["x"], a["W"], a["b"], a["gamma"], a["beta"], a["rmean"], a["rvar"],
+                                   inp["eps"])
+    g.update(Y=Y, Z=Z, Wf=Wf, bf=bf)
+    return g
+
+
 def rel_err(got, ref):
     got = got.numpy() if hasattr(got, "numpy") else np.asarray(got)
     assert got.shape == ref.shape, (got.shape, ref.shape)
