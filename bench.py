@@ -33,7 +33,13 @@ WORKLOADS = {
     "all": ["c1", "c2a", "c2b", "c3a", "c3b"],
     "resnet50": [],          # the whole 53-block backbone, Tune vs Eval (time and activation memory)
     "tconv": [],             # TransposedConv-BN up-sampling blocks in Tune mode
+    "depthwise": [],         # depthwise ConvBN blocks in Tune mode (memory-bound)
 }
+
+# depthwise 3x3 layers of an inverted-residual network at N = 32 (stand-ins for the mobile-network rows of the
+# paper's model tables): name, N, C, H, W, window, stride, padding
+DW_SHAPES = [("dw_112_s2", 32, 96, 112, 112, 3, 2, 1), ("dw_56", 32, 144, 56, 56, 3, 1, 1),
+             ("dw_14", 32, 576, 14, 14, 3, 1, 1)]
 
 # 2x up-sampling blocks of an encoder-decoder network (stand-ins for the UNet rows of Sec. 4.3): name, N, Cin, Hin,
 # Win, Cout, window, stride, padding
@@ -407,6 +413,104 @@ def main_tconv(a):
     print(json.dumps(line))
 
 
+def main_depthwise(a):
+    """Depthwise ConvBN blocks in Tune mode.  They are bound by memory traffic, so the figure of merit is the
+    algorithmic bytes of a step (x read by the forward pass and the weight gradient, z written, dz read by both
+    gradient passes, dx written: 3 A_x + 3 A_z elements) over its time, against the HBM peak."""
+    import torch
+    import oracle
+    from paper_2305_11624_amd import binding as B
+    from paper_2305_11624_amd import synth
+    from paper_2305_11624_amd.runner import DepthwiseRun
+    B.lib()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    shapes = [synth.BlockShape(n, N, c, h, w, c, k, st, pd, "bf16", 110 + i)
+              for i, (n, N, c, h, w, k, st, pd) in enumerate(DW_SHAPES)]
+    inputs = [synth.make_dw_inputs(s) for s in shapes]
+    step_bytes = [2.0 * (3 * s.A_x + 3 * s.A_z) for s in shapes]
+
+    def pools_of(mode, **kw):
+        out = []
+        for inp in inputs:
+            first = DepthwiseRun(inp, mode=mode, **kw)
+            count = max(2, min(32, -(-a.pool_mb * (1 << 20) // max(1, tensor_bytes(first)))))
+            out.append([first] + [DepthwiseRun(inp, mode=mode, **kw) for _ in range(count - 1)])
+        return out
+
+    def timed(fn, pool):
+        for i in range(min(3, len(pool))):
+            fn(pool[i])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(a.kernel_reps):
+            fn(pool[i % len(pool)])
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / a.kernel_reps
+
+    pools = pools_of("tune")
+    ms = time_steps(pools, a.steps, a.warmup)
+    saved_tune = sum(p[0].saved_bytes() for p in pools)
+    per_shape, best = {}, None
+    for s, pool in zip(shapes, pools):
+        fwd = timed(lambda r: r.forward(), pool)
+        bwd = timed(lambda r: r.backward(), pool)
+        # passes: forward reads x and writes z; backward reads dz twice and x once and writes dx
+        fb, bb = 2.0 * (s.A_x + s.A_z), 2.0 * (2 * s.A_x + 2 * s.A_z)
+        per_shape[s.name] = {"pass_ms": {"forward (fold + conv)": round(fwd, 5), "backward (dgrad + wgrad + fold-back)": round(bwd, 5)},
+                             "pass_gbs": {"forward": round(fb / (fwd * 1e-3) / 1e9, 1), "backward": round(bb / (bwd * 1e-3) / 1e9, 1)}}
+        for name, t, nb in (("forward", fwd, fb), ("backward", bwd, bb)):
+            if best is None or t > best[2]:
+                best = (s.name, name, t, nb)
+    del pools, pool
+    torch.cuda.empty_cache()
+    ms_eval, saved_eval = None, None
+    if not a.no_eval:
+        epools = pools_of("eval")
+        ms_eval = time_steps(epools, a.steps, a.warmup)
+        saved_eval = sum(p[0].saved_bytes() for p in epools)
+        del epools
+        torch.cuda.empty_cache()
+    achieved = best[3] / (best[2] * 1e-3) / 1e9
+    line = {
+        "metric": "Depthwise ConvBN Tune fwd+bwd GB/s (algorithmic bytes)", "value": sum(step_bytes) / (ms * 1e-3) / 1e9,
+        "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "depthwise ConvBN blocks, bf16: " + ", ".join(
+            f"{s.name} x[{s.N},{s.Cin},{s.Hin},{s.Win}] {s.k}x{s.k} s{s.stride} p{s.pad}" for s in shapes),
+            "mode": "tune", "layout": "NHWC", "step": "fwd+bwd of every shape"},
+        "pct_of_hbm_peak": 100.0 * sum(step_bytes) / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "eval_ms_per_step": ms_eval, "tune_speedup_vs_eval": (ms_eval / ms) if ms_eval else None,
+        "saved_activation_mb": {"tune": saved_tune / 1e6, "eval": saved_eval / 1e6 if saved_eval is not None else None},
+        "per_shape": per_shape,
+        "roofline": {"bound": "hbm", "kernel": f"{best[1]} pass @ {best[0]}", "achieved": achieved, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS, "avg_launch_ms": best[2], "traffic": None},
+    }
+    if not a.no_cpu_baseline:
+        cores = oracle.num_threads()
+        nb, secs, desc = 0.0, 0.0, []
+        for s, b1 in zip(shapes, step_bytes):
+            flop1 = 3.0 * 2.0 * s.A_z * s.k * s.k
+            n = int(max(1, min(s.N, a.cpu_seconds / len(shapes) * 0.3e9 * cores / (flop1 / s.N))))
+            inp = synth.make_dw_inputs(replace(s, N=n))
+            d = oracle.Dims(n, s.Cin, s.Hin, s.Win, s.Cout, s.k, s.k, s.stride, s.stride, s.pad, s.pad)
+            f = lambda t: None if t is None else t.double().numpy()
+            v = {k: f(inp[k]) for k in ("x", "W", "b", "gamma", "beta", "rmean", "rvar", "dy")}
+            t0 = time.perf_counter()
+            Y, _ = oracle.dw_eval_fwd(d, v["x"], v["W"], v["b"], v["gamma"], v["beta"], v["rmean"], v["rvar"], inp["eps"])
+            oracle.dw_eval_bwd(d, v["x"], v["W"], v["b"], v["gamma"], v["rmean"], v["rvar"], inp["eps"], Y, v["dy"])
+            secs += time.perf_counter() - t0
+            nb += b1 * n / s.N
+            desc.append(f"{s.name} with N={n} of {s.N}")
+        line["cpu_baseline"] = {"value": nb / secs / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+                                "sample": "one fwd+bwd of " + ", ".join(desc) + f" ({secs:.1f} s)"}
+    print(json.dumps(line))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -417,6 +521,8 @@ def main():
         return main_backbone(a)
     if a.workload == "tconv":
         return main_tconv(a)
+    if a.workload == "depthwise":
+        return main_depthwise(a)
     import torch
     from paper_2305_11624_amd import binding as B
     from paper_2305_11624_amd import synth

@@ -9,6 +9,8 @@
 //   x, dx [N][H][W][C]   z, dz [N][Ho][Wo][C]   W, dW [C][kH][kW]   folded filter wf [kH kW][C] (tap-major)
 #include "common.h"
 
+#include <type_traits>
+
 namespace convbn {
 
 namespace {
@@ -115,6 +117,89 @@ __global__ __launch_bounds__(256) void dw_dgrad_kernel(const T* __restrict__ dz,
   Vec<T, VEC>::store(dx + idx * VEC, acc);
 }
 
+// 3x3 windows, stride S, bf16, C % 8 == 0: a thread owns 8 channels of SEG consecutive outputs of one output
+// row.  It first issues every load of the 3 x ((SEG-1) S + 3) input patch those outputs need (kept packed, 16
+// bytes each, so all of them are in flight together and the memory latency is paid once per thread), keeps the
+// filter (9 x 8 values) in registers, and pays the index arithmetic once per segment: the generic kernel above
+// spends its time on integer divisions, on re-reading the filter and on nine dependent trips to memory.
+//   out[n][ho][wo][c] = bias[c] + sum_{i,j} wf[tap(i,j)][c] in[n][ho S + i - ph][wo S + j - pw][c]
+// FLIP (input gradient of a stride-1 convolution): tap(i,j) is the rotated one, in = dZ, ph = 2 - ph.
+constexpr int row_seg(int S) { return S == 1 ? 4 : 3; }
+
+__device__ __forceinline__ void unpack8(const uint4& t, float (&v)[8]) {
+  v[0] = bf16_lo(t.x); v[1] = bf16_hi(t.x); v[2] = bf16_lo(t.y); v[3] = bf16_hi(t.y);
+  v[4] = bf16_lo(t.z); v[5] = bf16_hi(t.z); v[6] = bf16_lo(t.w); v[7] = bf16_hi(t.w);
+}
+
+template <int S, bool FLIP>
+__global__ __launch_bounds__(256) void dw_row3_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ wf,
+                                                      const float* __restrict__ bias, bf16_t* __restrict__ out, int N,
+                                                      int Hi, int Wi, int Ho, int Wo, int C, int ph, int pw, int nseg) {
+  constexpr int K = 3, SEG = row_seg(S), NC = (SEG - 1) * S + K;
+  const int cgs = C >> 3;
+  const unsigned id = blockIdx.x * 256u + threadIdx.x;
+  if (id >= (unsigned)N * Ho * nseg * cgs) return;
+  const int cg = id % cgs;
+  unsigned t = id / cgs;
+  const int sg = t % nseg;
+  t /= nseg;
+  const int ho = t % Ho, n = t / Ho;
+  const int c = cg * 8;
+  const int wo0 = sg * SEG;
+  // the input patch, then the filter: every load is issued before the first use
+  uint4 xr[K][NC];
+#pragma unroll
+  for (int i = 0; i < K; ++i) {
+    const int h = ho * S + i - ph;
+    const bool rok = (unsigned)h < (unsigned)Hi;
+    const bf16_t* rowp = in + ((size_t)n * Hi + (rok ? h : 0)) * Wi * C + c;
+#pragma unroll
+    for (int q = 0; q < NC; ++q) {
+      const int w = wo0 * S + q - pw;
+      xr[i][q] = (rok && (unsigned)w < (unsigned)Wi) ? *reinterpret_cast<const uint4*>(rowp + (size_t)w * C)
+                                                     : make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+  float wv[K * K][8], bv[8];
+#pragma unroll
+  for (int q = 0; q < K * K; ++q) Vec<bf16_t, 8>::load(wf + (size_t)(FLIP ? K * K - 1 - q : q) * C + c, wv[q]);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) bv[e] = bias ? bias[c + e] : 0.f;
+  bf16_t* orow = out + ((size_t)n * Ho + ho) * Wo * C + c;
+#pragma unroll
+  for (int o = 0; o < SEG; ++o) {
+    if (wo0 + o >= Wo) break;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = bv[e];
+#pragma unroll
+    for (int i = 0; i < K; ++i)
+#pragma unroll
+      for (int j = 0; j < K; ++j) {
+        float xv[8];
+        unpack8(xr[i][o * S + j], xv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += xv[e] * wv[i * K + j][e];
+      }
+    Vec<bf16_t, 8>::store(orow + (size_t)(wo0 + o) * C, acc);
+  }
+}
+
+bool row3_shape(const Geom& g, int dtype) {
+  return dtype == CONVBN_BF16 && g.Cin % 8 == 0 && g.kH == 3 && g.kW == 3 && g.sh == g.sw && (g.sh == 1 || g.sh == 2) &&
+         (size_t)g.N * (g.Hin > g.Hout ? g.Hin : g.Hout) * ceil_div(g.Win > g.Wout ? g.Win : g.Wout, 3) * (g.Cin / 8) <
+             0xffffffffull;
+}
+template <int S, bool FLIP>
+hipError_t launch_row3(const void* in, const void* wf, const float* bias, void* out, int N, int Hi, int Wi, int Ho,
+                       int Wo, int C, int ph, int pw, hipStream_t st) {
+  const int nseg = ceil_div(Wo, row_seg(S));
+  const size_t total = (size_t)N * Ho * nseg * (C / 8);
+  hipLaunchKernelGGL((dw_row3_kernel<S, FLIP>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t*)in,
+                     (const bf16_t*)wf, bias, (bf16_t*)out, N, Hi, Wi, Ho, Wo, C, ph, pw, nseg);
+  return hipGetLastError();
+}
+
 constexpr int WG_TAPS = 9;     // window positions a weight-gradient workgroup accumulates at once
 constexpr int WG_CG = 32;      // channel groups per workgroup (x 8 pixel lanes = 256 threads)
 
@@ -186,19 +271,23 @@ __global__ __launch_bounds__(256) void dw_wgrad_kernel(const T* __restrict__ x, 
 }
 
 // sums[row][c] = sum over slices of part[slice][row][c] (rows 0..taps-1) and of r_part[slice][c] (row taps).
-// grid (ceil(C/64), taps + 1), thread -> channel tid % 64, slice lane tid / 64
+// grid (ceil(C/16), taps + 1), thread -> channel tid % 16, slice lane tid / 16
 __global__ __launch_bounds__(256) void dw_reduce_kernel(const float* __restrict__ part, const float* __restrict__ r_part,
                                                         int slices, int taps, int C, float* __restrict__ sums) {
-  __shared__ float red[4][64];
-  const int cl = threadIdx.x & 63, l = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + cl, row = blockIdx.y;
+  __shared__ float red[16][17];
+  const int cl = threadIdx.x & 15, l = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + cl, row = blockIdx.y;
   float v = 0.f;
   if (c < C && (row < taps || r_part))
-    for (int s = l; s < slices; s += 4)
+    for (int s = l; s < slices; s += 16)
       v += row < taps ? part[((size_t)s * taps + row) * C + c] : r_part[(size_t)s * C + c];
   red[l][cl] = v;
   __syncthreads();
-  if (l == 0 && c < C) sums[(size_t)row * C + c] = red[0][cl] + red[1][cl] + red[2][cl] + red[3][cl];
+  if (l != 0 || c >= C) return;
+  v = 0.f;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) v += red[k][cl];
+  sums[(size_t)row * C + c] = v;
 }
 
 // dW[c][tap] = s dw', dgamma = (sum_tap dw' w + r (b - mu)) / sqrt(var + eps), dbeta = r, db = s r.
@@ -246,6 +335,10 @@ hipError_t launch_dw_fold(const Geom& g, int dtype, const void* W, const float* 
 
 hipError_t launch_dw_fprop(const Geom& g, int dtype, const void* x, const void* wf, const float* bias, void* z,
                            hipStream_t st) {
+  if (row3_shape(g, dtype)) {
+    if (g.sh == 1) return launch_row3<1, false>(x, wf, bias, z, g.N, g.Hin, g.Win, g.Hout, g.Wout, g.Cin, g.ph, g.pw, st);
+    return launch_row3<2, false>(x, wf, bias, z, g.N, g.Hin, g.Win, g.Hout, g.Wout, g.Cin, g.ph, g.pw, st);
+  }
   const int vec = vec8(g, dtype) ? 8 : 1;
   const size_t total = (size_t)g.M * (g.Cin / vec);
   const dim3 grid((unsigned)((total + 255) / 256));
@@ -262,6 +355,8 @@ hipError_t launch_dw_fprop(const Geom& g, int dtype, const void* x, const void* 
 }
 
 hipError_t launch_dw_dgrad(const Geom& g, int dtype, const void* dz, const void* wf, void* dx, hipStream_t st) {
+  if (row3_shape(g, dtype) && g.sh == 1 && g.ph <= 2 && g.pw <= 2)   // the same sweep over dZ with the rotated filter
+    return launch_row3<1, true>(dz, wf, nullptr, dx, g.N, g.Hout, g.Wout, g.Hin, g.Win, g.Cin, 2 - g.ph, 2 - g.pw, st);
   const int vec = vec8(g, dtype) ? 8 : 1;
   const size_t total = (size_t)g.Min * (g.Cin / vec);
   const dim3 grid((unsigned)((total + 255) / 256));
@@ -311,7 +406,7 @@ hipError_t launch_dw_fold_back(const Geom& g, int dtype, const float* part, cons
                                float* sums, const void* W, const float* b, const float* gamma, const float* mean,
                                const float* var, void* dW, float* db, float* dgamma, float* dbeta, hipStream_t st) {
   const int C = g.Cin, taps = g.kH * g.kW;
-  hipLaunchKernelGGL(dw_reduce_kernel, dim3(ceil_div(C, 64), taps + 1), dim3(256), 0, st, part, r_part, slices, taps, C,
+  hipLaunchKernelGGL(dw_reduce_kernel, dim3(ceil_div(C, 16), taps + 1), dim3(256), 0, st, part, r_part, slices, taps, C,
                      sums);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
