@@ -117,8 +117,8 @@ __global__ __launch_bounds__(256) void dw_dgrad_kernel(const T* __restrict__ dz,
   Vec<T, VEC>::store(dx + idx * VEC, acc);
 }
 
-// 3x3 windows, stride S, bf16, C % 8 == 0: a thread owns 8 channels of SEG consecutive outputs of one output
-// row.  It first issues every load of the 3 x ((SEG-1) S + 3) input patch those outputs need (kept packed, 16
+// 3x3 windows, stride S, bf16, C % 8 == 0: a thread owns 8 channels of SEG vertically consecutive outputs of one
+// output column.  It first issues every load of the ((SEG-1) S + 3) x 3 input patch those outputs need (kept packed, 16
 // bytes each, so all of them are in flight together and the memory latency is paid once per thread), keeps the
 // filter (9 x 8 values) in registers, and pays the index arithmetic once per segment: the generic kernel above
 // spends its time on integer divisions, on re-reading the filter and on nine dependent trips to memory.
@@ -135,28 +135,30 @@ template <int S, bool FLIP>
 __global__ __launch_bounds__(256) void dw_row3_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ wf,
                                                       const float* __restrict__ bias, bf16_t* __restrict__ out, int N,
                                                       int Hi, int Wi, int Ho, int Wo, int C, int ph, int pw, int nseg) {
-  constexpr int K = 3, SEG = row_seg(S), NC = (SEG - 1) * S + K;
+  // the SEG outputs are consecutive along H: consecutive threads are then consecutive (channel group, column)
+  // pairs of one row and every load of the wave is one contiguous kilobyte
+  constexpr int K = 3, SEG = row_seg(S), NR = (SEG - 1) * S + K;
   const int cgs = C >> 3;
   const unsigned id = blockIdx.x * 256u + threadIdx.x;
-  if (id >= (unsigned)N * Ho * nseg * cgs) return;
+  if (id >= (unsigned)N * nseg * Wo * cgs) return;
   const int cg = id % cgs;
   unsigned t = id / cgs;
-  const int sg = t % nseg;
-  t /= nseg;
-  const int ho = t % Ho, n = t / Ho;
+  const int wo = t % Wo;
+  t /= Wo;
+  const int sg = t % nseg, n = t / nseg;
   const int c = cg * 8;
-  const int wo0 = sg * SEG;
+  const int ho0 = sg * SEG;
   // the input patch, then the filter: every load is issued before the first use
-  uint4 xr[K][NC];
+  uint4 xr[NR][K];
 #pragma unroll
-  for (int i = 0; i < K; ++i) {
-    const int h = ho * S + i - ph;
+  for (int q = 0; q < NR; ++q) {
+    const int h = ho0 * S + q - ph;
     const bool rok = (unsigned)h < (unsigned)Hi;
     const bf16_t* rowp = in + ((size_t)n * Hi + (rok ? h : 0)) * Wi * C + c;
 #pragma unroll
-    for (int q = 0; q < NC; ++q) {
-      const int w = wo0 * S + q - pw;
-      xr[i][q] = (rok && (unsigned)w < (unsigned)Wi) ? *reinterpret_cast<const uint4*>(rowp + (size_t)w * C)
+    for (int j = 0; j < K; ++j) {
+      const int w = wo * S + j - pw;
+      xr[q][j] = (rok && (unsigned)w < (unsigned)Wi) ? *reinterpret_cast<const uint4*>(rowp + (size_t)w * C)
                                                      : make_uint4(0u, 0u, 0u, 0u);
     }
   }
@@ -165,23 +167,90 @@ __global__ __launch_bounds__(256) void dw_row3_kernel(const bf16_t* __restrict__
   for (int q = 0; q < K * K; ++q) Vec<bf16_t, 8>::load(wf + (size_t)(FLIP ? K * K - 1 - q : q) * C + c, wv[q]);
 #pragma unroll
   for (int e = 0; e < 8; ++e) bv[e] = bias ? bias[c + e] : 0.f;
-  bf16_t* orow = out + ((size_t)n * Ho + ho) * Wo * C + c;
+  // every patch element is widened once and multiplied into each output that covers it
+  float acc[SEG][8];
+#pragma unroll
+  for (int o = 0; o < SEG; ++o)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[o][e] = bv[e];
+#pragma unroll
+  for (int q = 0; q < NR; ++q)
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      float xv[8];
+      unpack8(xr[q][j], xv);
+#pragma unroll
+      for (int o = 0; o < SEG; ++o) {
+        const int i = q - o * S;
+        if (i < 0 || i >= K) continue;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[o][e] += xv[e] * wv[i * K + j][e];
+      }
+    }
+#pragma unroll
+  for (int o = 0; o < SEG; ++o)
+    if (ho0 + o < Ho) Vec<bf16_t, 8>::store(out + (((size_t)n * Ho + ho0 + o) * Wo + wo) * C + c, acc[o]);
+}
+
+// Input gradient of a 3x3 stride-2 depthwise convolution, same thread shape as the row kernel: 8 channels of 4
+// consecutive dX pixels of one row (first pixel even).  dX[h][w] = sum over the taps (i, j) with h + ph - i and
+// w + pw - j even of wf[i][j] dZ[(h + ph - i)/2][(w + pw - j)/2]: at most two dZ rows (which ones depends on the
+// parity of h: rows that do not qualify are loaded as zeros) and exactly three dZ columns, the even ones among
+// w0 + pw - 2 .. w0 + pw + 3, whose parity pattern is the same for every thread.
+__global__ __launch_bounds__(256) void dw_dgrad_s2_row3_kernel(const bf16_t* __restrict__ dz, const bf16_t* __restrict__ wf,
+                                                               bf16_t* __restrict__ dx, int N, int Hin, int Win, int Ho,
+                                                               int Wo, int C, int ph, int pw, int nseg) {
+  constexpr int K = 3, SEG = 4;
+  const int cgs = C >> 3;
+  const unsigned id = blockIdx.x * 256u + threadIdx.x;
+  if (id >= (unsigned)N * Hin * nseg * cgs) return;
+  const int cg = id % cgs;
+  unsigned t = id / cgs;
+  const int sg = t % nseg;
+  t /= nseg;
+  const int h = t % Hin, n = t / Hin;
+  const int c = cg * 8;
+  const int w0 = sg * SEG;
+  const int base = w0 + pw - 2;                 // smallest w + pw - j of the segment
+  const int par = base & 1;                     // its parity: the same for every thread (w0 is even)
+  const int wo_first = (base + par) >> 1;       // first of the three dZ columns (may be negative: zeros)
+  uint4 gr[K][3];
+#pragma unroll
+  for (int i = 0; i < K; ++i) {
+    const int hz = h + ph - i;
+    const bool rok = hz >= 0 && (hz & 1) == 0 && (hz >> 1) < Ho;
+    const bf16_t* rowp = dz + ((size_t)n * Ho + (rok ? hz >> 1 : 0)) * Wo * C + c;
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+      const int wo = wo_first + q;
+      gr[i][q] = (rok && (unsigned)wo < (unsigned)Wo) ? *reinterpret_cast<const uint4*>(rowp + (size_t)wo * C)
+                                                      : make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+  float wv[K * K][8];
+#pragma unroll
+  for (int q = 0; q < K * K; ++q) Vec<bf16_t, 8>::load(wf + (size_t)q * C + c, wv[q]);
+  bf16_t* orow = dx + ((size_t)n * Hin + h) * Win * C + c;
 #pragma unroll
   for (int o = 0; o < SEG; ++o) {
-    if (wo0 + o >= Wo) break;
+    if (w0 + o >= Win) break;
     float acc[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = bv[e];
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
 #pragma unroll
-    for (int i = 0; i < K; ++i)
+    for (int j = 0; j < K; ++j) {
+      const int d = o + 2 - j;                  // w + pw - j = base + d
+      if ((d & 1) != par) continue;             // odd: this tap does not reach the pixel
+      const int q = (d - par) >> 1;             // 0 .. 2 (d = 5 only with par = 1)
 #pragma unroll
-      for (int j = 0; j < K; ++j) {
-        float xv[8];
-        unpack8(xr[i][o * S + j], xv);
+      for (int i = 0; i < K; ++i) {
+        float gv[8];
+        unpack8(q == 0 ? gr[i][0] : q == 1 ? gr[i][1] : gr[i][2], gv);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] += xv[e] * wv[i * K + j][e];
+        for (int e = 0; e < 8; ++e) acc[e] += gv[e] * wv[i * K + j][e];
       }
-    Vec<bf16_t, 8>::store(orow + (size_t)(wo0 + o) * C, acc);
+    }
+    Vec<bf16_t, 8>::store(orow + (size_t)(w0 + o) * C, acc);
   }
 }
 
@@ -193,11 +262,123 @@ bool row3_shape(const Geom& g, int dtype) {
 template <int S, bool FLIP>
 hipError_t launch_row3(const void* in, const void* wf, const float* bias, void* out, int N, int Hi, int Wi, int Ho,
                        int Wo, int C, int ph, int pw, hipStream_t st) {
-  const int nseg = ceil_div(Wo, row_seg(S));
-  const size_t total = (size_t)N * Ho * nseg * (C / 8);
+  const int nseg = ceil_div(Ho, row_seg(S));
+  const size_t total = (size_t)N * nseg * Wo * (C / 8);
   hipLaunchKernelGGL((dw_row3_kernel<S, FLIP>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t*)in,
                      (const bf16_t*)wf, bias, (bf16_t*)out, N, Hi, Wi, Ho, Wo, C, ph, pw, nseg);
   return hipGetLastError();
+}
+
+// Weight gradient for the shapes of the row kernel.  An item is SEG vertically consecutive outputs of one column; a
+// thread owns 8 channels and every L-th item of its workgroup's slice of the items (L = threads / channel groups
+// of the workgroup), loads an item's dZ values and input patch up front and accumulates the 9 x 8 products and
+// the channel sums in registers; the L lanes are then summed through LDS.  Outputs as dw_wgrad_kernel.
+template <int S>
+__global__ __launch_bounds__(256) void dw_wgrad_row3_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dz,
+                                                            float* __restrict__ part, float* __restrict__ r_part, int N,
+                                                            int Hi, int Wi, int Ho, int Wo, int C, int ph, int pw,
+                                                            int nseg, int cgb, int items_per_slice) {
+  constexpr int K = 3, SEG = row_seg(S), NR = (SEG - 1) * S + K;
+  __shared__ float red[256 * 8];
+  const int cgs = C >> 3;
+  const int L = 256 / cgb;
+  const int tx = threadIdx.x % cgb, lane = threadIdx.x / cgb;
+  const int cg = blockIdx.x * cgb + tx;
+  const bool live = lane < L && cg < cgs;
+  const int c = cg * 8;
+  const int nitems = N * nseg * Wo;
+  const int it0 = blockIdx.y * items_per_slice, it1 = min(nitems, it0 + items_per_slice);
+  float acc[K * K][8], racc[8];
+#pragma unroll
+  for (int q = 0; q < K * K; ++q)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) racc[e] = 0.f;
+  if (live)
+    for (int it = it0 + lane; it < it1; it += L) {
+      const int wo = it % Wo;
+      const int t = it / Wo;
+      const int sg = t % nseg, n = t / nseg;
+      const int ho0 = sg * SEG;
+      uint4 gr[SEG], xr[NR][K];
+#pragma unroll
+      for (int o = 0; o < SEG; ++o)
+        gr[o] = ho0 + o < Ho ? *reinterpret_cast<const uint4*>(dz + (((size_t)n * Ho + ho0 + o) * Wo + wo) * C + c)
+                             : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+      for (int q = 0; q < NR; ++q) {
+        const int h = ho0 * S + q - ph;
+        const bool rok = (unsigned)h < (unsigned)Hi;
+        const bf16_t* rowp = x + ((size_t)n * Hi + (rok ? h : 0)) * Wi * C + c;
+#pragma unroll
+        for (int jj = 0; jj < K; ++jj) {
+          const int w = wo * S + jj - pw;
+          xr[q][jj] = (rok && (unsigned)w < (unsigned)Wi) ? *reinterpret_cast<const uint4*>(rowp + (size_t)w * C)
+                                                          : make_uint4(0u, 0u, 0u, 0u);
+        }
+      }
+      float gv[SEG][8];
+#pragma unroll
+      for (int o = 0; o < SEG; ++o) {
+        unpack8(gr[o], gv[o]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) racc[e] += gv[o][e];
+      }
+#pragma unroll
+      for (int q = 0; q < NR; ++q)
+#pragma unroll
+        for (int jj = 0; jj < K; ++jj) {
+          float xv[8];
+          unpack8(xr[q][jj], xv);
+#pragma unroll
+          for (int o = 0; o < SEG; ++o) {
+            const int i = q - o * S;
+            if (i < 0 || i >= K) continue;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[i * K + jj][e] += gv[o][e] * xv[e];
+          }
+        }
+    }
+  // sum the lanes: one window position at a time (q == 9: the channel sums)
+  const int ncol = cgb * 8;
+#pragma unroll
+  for (int q = 0; q <= K * K; ++q) {
+    if (q == K * K && !r_part) continue;
+    __syncthreads();
+    if (lane < L) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) red[lane * ncol + tx * 8 + e] = q < K * K ? acc[q < K * K ? q : 0][e] : racc[e];
+    }
+    __syncthreads();
+    for (int col = threadIdx.x; col < ncol; col += 256) {
+      const int cc = blockIdx.x * ncol + col;
+      if (cc >= C) continue;
+      float v = 0.f;
+      for (int l = 0; l < L; ++l) v += red[l * ncol + col];
+      if (q < K * K) part[((size_t)blockIdx.y * (K * K) + q) * C + cc] = v;
+      else r_part[(size_t)blockIdx.y * C + cc] = v;
+    }
+  }
+}
+
+// workgroup shape of the kernel above: x-blocks, channel groups per block, slices of the items
+struct RowWgPlan { int nxb, cgb, nseg, slices, items_per_slice; };
+RowWgPlan row_wg_plan(const Geom& g) {
+  RowWgPlan p;
+  const int cgs = g.Cin / 8;
+  p.nxb = ceil_div(cgs, 64);
+  p.cgb = ceil_div(cgs, p.nxb);
+  p.nseg = ceil_div(g.Hout, row_seg(g.sh));
+  const int L = 256 / p.cgb;
+  const int nitems = g.N * p.nseg * g.Wout;
+  int want = ceil_div(256, p.nxb);                       // about one workgroup per CU
+  const int maxs = ceil_div(nitems, 2 * L);              // at least two items per thread
+  if (want > maxs) want = maxs;
+  if (want < 1) want = 1;
+  p.items_per_slice = ceil_div(nitems, want);
+  p.slices = ceil_div(nitems, p.items_per_slice);
+  return p;
 }
 
 constexpr int WG_TAPS = 9;     // window positions a weight-gradient workgroup accumulates at once
@@ -357,6 +538,13 @@ hipError_t launch_dw_fprop(const Geom& g, int dtype, const void* x, const void* 
 hipError_t launch_dw_dgrad(const Geom& g, int dtype, const void* dz, const void* wf, void* dx, hipStream_t st) {
   if (row3_shape(g, dtype) && g.sh == 1 && g.ph <= 2 && g.pw <= 2)   // the same sweep over dZ with the rotated filter
     return launch_row3<1, true>(dz, wf, nullptr, dx, g.N, g.Hout, g.Wout, g.Hin, g.Win, g.Cin, 2 - g.ph, 2 - g.pw, st);
+  if (row3_shape(g, dtype) && g.sh == 2) {
+    const int nseg = ceil_div(g.Win, 4);
+    const size_t total = (size_t)g.N * g.Hin * nseg * (g.Cin / 8);
+    hipLaunchKernelGGL(dw_dgrad_s2_row3_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t*)dz,
+                       (const bf16_t*)wf, (bf16_t*)dx, g.N, g.Hin, g.Win, g.Hout, g.Wout, g.Cin, g.ph, g.pw, nseg);
+    return hipGetLastError();
+  }
   const int vec = vec8(g, dtype) ? 8 : 1;
   const size_t total = (size_t)g.Min * (g.Cin / vec);
   const dim3 grid((unsigned)((total + 255) / 256));
@@ -374,6 +562,7 @@ hipError_t launch_dw_dgrad(const Geom& g, int dtype, const void* dz, const void*
 
 // pixel slices of the weight-gradient reduction: enough workgroups to fill the chip a few times over
 int dw_wgrad_slices(const Geom& g, int dtype) {
+  if (row3_shape(g, dtype)) return row_wg_plan(g).slices;
   const int vec = vec8(g, dtype) ? 8 : 1;
   const int cblocks = ceil_div(g.Cin / vec, WG_CG) * ceil_div(g.kH * g.kW, WG_TAPS);
   int want = ceil_div(1024, cblocks);
@@ -386,6 +575,16 @@ int dw_wgrad_slices(const Geom& g, int dtype) {
 
 hipError_t launch_dw_wgrad(const Geom& g, int dtype, const void* x, const void* dz, float* part, float* r_part,
                            hipStream_t st) {
+  if (row3_shape(g, dtype)) {
+    const RowWgPlan p = row_wg_plan(g);
+    const dim3 grid(p.nxb, p.slices);
+#define ROWWG(SV) \
+    hipLaunchKernelGGL((dw_wgrad_row3_kernel<SV>), grid, dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)dz, part, \
+                       r_part, g.N, g.Hin, g.Win, g.Hout, g.Wout, g.Cin, g.ph, g.pw, p.nseg, p.cgb, p.items_per_slice)
+    if (g.sh == 1) ROWWG(1); else ROWWG(2);
+#undef ROWWG
+    return hipGetLastError();
+  }
   const int vec = vec8(g, dtype) ? 8 : 1;
   const int slices = dw_wgrad_slices(g, dtype);
   const int pps = ceil_div(g.M, slices);
