@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void dw_dgrad_kernel(const T* __restrict__ dz,
 // spends its time on integer divisions, on re-reading the filter and on nine dependent trips to memory.
 //   out[n][ho][wo][c] = bias[c] + sum_{i,j} wf[tap(i,j)][c] in[n][ho S + i - ph][wo S + j - pw][c]
 // FLIP (input gradient of a stride-1 convolution): tap(i,j) is the rotated one, in = dZ, ph = 2 - ph.
-constexpr int row_seg(int S) { return S == 1 ? 4 : 3; }
+constexpr int patch_seg(int S) { return S == 1 ? 4 : 3; }
 
 __device__ __forceinline__ void unpack8(const uint4& t, float (&v)[8]) {
   v[0] = bf16_lo(t.x); v[1] = bf16_hi(t.x); v[2] = bf16_lo(t.y); v[3] = bf16_hi(t.y);
@@ -132,12 +132,12 @@ __device__ __forceinline__ void unpack8(const uint4& t, float (&v)[8]) {
 }
 
 template <int S, bool FLIP>
-__global__ __launch_bounds__(256) void dw_row3_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ wf,
+__global__ __launch_bounds__(256) void dw_patch3_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ wf,
                                                       const float* __restrict__ bias, bf16_t* __restrict__ out, int N,
                                                       int Hi, int Wi, int Ho, int Wo, int C, int ph, int pw, int nseg) {
   // the SEG outputs are consecutive along H: consecutive threads are then consecutive (channel group, column)
   // pairs of one row and every load of the wave is one contiguous kilobyte
-  constexpr int K = 3, SEG = row_seg(S), NR = (SEG - 1) * S + K;
+  constexpr int K = 3, SEG = patch_seg(S), NR = (SEG - 1) * S + K;
   const int cgs = C >> 3;
   const unsigned id = blockIdx.x * 256u + threadIdx.x;
   if (id >= (unsigned)N * nseg * Wo * cgs) return;
@@ -192,12 +192,12 @@ __global__ __launch_bounds__(256) void dw_row3_kernel(const bf16_t* __restrict__
     if (ho0 + o < Ho) Vec<bf16_t, 8>::store(out + (((size_t)n * Ho + ho0 + o) * Wo + wo) * C + c, acc[o]);
 }
 
-// Input gradient of a 3x3 stride-2 depthwise convolution, same thread shape as the row kernel: 8 channels of 4
+// Input gradient of a 3x3 stride-2 depthwise convolution, same idea as the patch kernel: 8 channels of 4
 // consecutive dX pixels of one row (first pixel even).  dX[h][w] = sum over the taps (i, j) with h + ph - i and
 // w + pw - j even of wf[i][j] dZ[(h + ph - i)/2][(w + pw - j)/2]: at most two dZ rows (which ones depends on the
 // parity of h: rows that do not qualify are loaded as zeros) and exactly three dZ columns, the even ones among
 // w0 + pw - 2 .. w0 + pw + 3, whose parity pattern is the same for every thread.
-__global__ __launch_bounds__(256) void dw_dgrad_s2_row3_kernel(const bf16_t* __restrict__ dz, const bf16_t* __restrict__ wf,
+__global__ __launch_bounds__(256) void dw_dgrad_s2_patch3_kernel(const bf16_t* __restrict__ dz, const bf16_t* __restrict__ wf,
                                                                bf16_t* __restrict__ dx, int N, int Hin, int Win, int Ho,
                                                                int Wo, int C, int ph, int pw, int nseg) {
   constexpr int K = 3, SEG = 4;
@@ -254,31 +254,31 @@ __global__ __launch_bounds__(256) void dw_dgrad_s2_row3_kernel(const bf16_t* __r
   }
 }
 
-bool row3_shape(const Geom& g, int dtype) {
+bool patch3_shape(const Geom& g, int dtype) {
   return dtype == CONVBN_BF16 && g.Cin % 8 == 0 && g.kH == 3 && g.kW == 3 && g.sh == g.sw && (g.sh == 1 || g.sh == 2) &&
          (size_t)g.N * (g.Hin > g.Hout ? g.Hin : g.Hout) * ceil_div(g.Win > g.Wout ? g.Win : g.Wout, 3) * (g.Cin / 8) <
              0xffffffffull;
 }
 template <int S, bool FLIP>
-hipError_t launch_row3(const void* in, const void* wf, const float* bias, void* out, int N, int Hi, int Wi, int Ho,
+hipError_t launch_patch3(const void* in, const void* wf, const float* bias, void* out, int N, int Hi, int Wi, int Ho,
                        int Wo, int C, int ph, int pw, hipStream_t st) {
-  const int nseg = ceil_div(Ho, row_seg(S));
+  const int nseg = ceil_div(Ho, patch_seg(S));
   const size_t total = (size_t)N * nseg * Wo * (C / 8);
-  hipLaunchKernelGGL((dw_row3_kernel<S, FLIP>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t*)in,
+  hipLaunchKernelGGL((dw_patch3_kernel<S, FLIP>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t*)in,
                      (const bf16_t*)wf, bias, (bf16_t*)out, N, Hi, Wi, Ho, Wo, C, ph, pw, nseg);
   return hipGetLastError();
 }
 
-// Weight gradient for the shapes of the row kernel.  An item is SEG vertically consecutive outputs of one column; a
+// Weight gradient for the shapes of the patch kernel.  An item is SEG vertically consecutive outputs of one column; a
 // thread owns 8 channels and every L-th item of its workgroup's slice of the items (L = threads / channel groups
 // of the workgroup), loads an item's dZ values and input patch up front and accumulates the 9 x 8 products and
 // the channel sums in registers; the L lanes are then summed through LDS.  Outputs as dw_wgrad_kernel.
 template <int S>
-__global__ __launch_bounds__(256) void dw_wgrad_row3_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dz,
+__global__ __launch_bounds__(256) void dw_wgrad_patch3_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dz,
                                                             float* __restrict__ part, float* __restrict__ r_part, int N,
                                                             int Hi, int Wi, int Ho, int Wo, int C, int ph, int pw,
                                                             int nseg, int cgb, int items_per_slice) {
-  constexpr int K = 3, SEG = row_seg(S), NR = (SEG - 1) * S + K;
+  constexpr int K = 3, SEG = patch_seg(S), NR = (SEG - 1) * S + K;
   __shared__ float red[256 * 8];
   const int cgs = C >> 3;
   const int L = 256 / cgb;
@@ -363,13 +363,13 @@ __global__ __launch_bounds__(256) void dw_wgrad_row3_kernel(const bf16_t* __rest
 }
 
 // workgroup shape of the kernel above: x-blocks, channel groups per block, slices of the items
-struct RowWgPlan { int nxb, cgb, nseg, slices, items_per_slice; };
-RowWgPlan row_wg_plan(const Geom& g) {
-  RowWgPlan p;
+struct PatchWgPlan { int nxb, cgb, nseg, slices, items_per_slice; };
+PatchWgPlan patch_wg_plan(const Geom& g) {
+  PatchWgPlan p;
   const int cgs = g.Cin / 8;
   p.nxb = ceil_div(cgs, 64);
   p.cgb = ceil_div(cgs, p.nxb);
-  p.nseg = ceil_div(g.Hout, row_seg(g.sh));
+  p.nseg = ceil_div(g.Hout, patch_seg(g.sh));
   const int L = 256 / p.cgb;
   const int nitems = g.N * p.nseg * g.Wout;
   int want = ceil_div(256, p.nxb);                       // about one workgroup per CU
@@ -516,9 +516,9 @@ hipError_t launch_dw_fold(const Geom& g, int dtype, const void* W, const float* 
 
 hipError_t launch_dw_fprop(const Geom& g, int dtype, const void* x, const void* wf, const float* bias, void* z,
                            hipStream_t st) {
-  if (row3_shape(g, dtype)) {
-    if (g.sh == 1) return launch_row3<1, false>(x, wf, bias, z, g.N, g.Hin, g.Win, g.Hout, g.Wout, g.Cin, g.ph, g.pw, st);
-    return launch_row3<2, false>(x, wf, bias, z, g.N, g.Hin, g.Win, g.Hout, g.Wout, g.Cin, g.ph, g.pw, st);
+  if (patch3_shape(g, dtype)) {
+    if (g.sh == 1) return launch_patch3<1, false>(x, wf, bias, z, g.N, g.Hin, g.Win, g.Hout, g.Wout, g.Cin, g.ph, g.pw, st);
+    return launch_patch3<2, false>(x, wf, bias, z, g.N, g.Hin, g.Win, g.Hout, g.Wout, g.Cin, g.ph, g.pw, st);
   }
   const int vec = vec8(g, dtype) ? 8 : 1;
   const size_t total = (size_t)g.M * (g.Cin / vec);
@@ -536,12 +536,12 @@ hipError_t launch_dw_fprop(const Geom& g, int dtype, const void* x, const void* 
 }
 
 hipError_t launch_dw_dgrad(const Geom& g, int dtype, const void* dz, const void* wf, void* dx, hipStream_t st) {
-  if (row3_shape(g, dtype) && g.sh == 1 && g.ph <= 2 && g.pw <= 2)   // the same sweep over dZ with the rotated filter
-    return launch_row3<1, true>(dz, wf, nullptr, dx, g.N, g.Hout, g.Wout, g.Hin, g.Win, g.Cin, 2 - g.ph, 2 - g.pw, st);
-  if (row3_shape(g, dtype) && g.sh == 2) {
+  if (patch3_shape(g, dtype) && g.sh == 1 && g.ph <= 2 && g.pw <= 2)   // the same sweep over dZ with the rotated filter
+    return launch_patch3<1, true>(dz, wf, nullptr, dx, g.N, g.Hout, g.Wout, g.Hin, g.Win, g.Cin, 2 - g.ph, 2 - g.pw, st);
+  if (patch3_shape(g, dtype) && g.sh == 2) {
     const int nseg = ceil_div(g.Win, 4);
     const size_t total = (size_t)g.N * g.Hin * nseg * (g.Cin / 8);
-    hipLaunchKernelGGL(dw_dgrad_s2_row3_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t*)dz,
+    hipLaunchKernelGGL(dw_dgrad_s2_patch3_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t*)dz,
                        (const bf16_t*)wf, (bf16_t*)dx, g.N, g.Hin, g.Win, g.Hout, g.Wout, g.Cin, g.ph, g.pw, nseg);
     return hipGetLastError();
   }
@@ -562,7 +562,7 @@ hipError_t launch_dw_dgrad(const Geom& g, int dtype, const void* dz, const void*
 
 // pixel slices of the weight-gradient reduction: enough workgroups to fill the chip a few times over
 int dw_wgrad_slices(const Geom& g, int dtype) {
-  if (row3_shape(g, dtype)) return row_wg_plan(g).slices;
+  if (patch3_shape(g, dtype)) return patch_wg_plan(g).slices;
   const int vec = vec8(g, dtype) ? 8 : 1;
   const int cblocks = ceil_div(g.Cin / vec, WG_CG) * ceil_div(g.kH * g.kW, WG_TAPS);
   int want = ceil_div(1024, cblocks);
@@ -575,14 +575,14 @@ int dw_wgrad_slices(const Geom& g, int dtype) {
 
 hipError_t launch_dw_wgrad(const Geom& g, int dtype, const void* x, const void* dz, float* part, float* r_part,
                            hipStream_t st) {
-  if (row3_shape(g, dtype)) {
-    const RowWgPlan p = row_wg_plan(g);
+  if (patch3_shape(g, dtype)) {
+    const PatchWgPlan p = patch_wg_plan(g);
     const dim3 grid(p.nxb, p.slices);
-#define ROWWG(SV) \
-    hipLaunchKernelGGL((dw_wgrad_row3_kernel<SV>), grid, dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)dz, part, \
+#define PATCHWG(SV) \
+    hipLaunchKernelGGL((dw_wgrad_patch3_kernel<SV>), grid, dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)dz, part, \
                        r_part, g.N, g.Hin, g.Win, g.Hout, g.Wout, g.Cin, g.ph, g.pw, p.nseg, p.cgb, p.items_per_slice)
-    if (g.sh == 1) ROWWG(1); else ROWWG(2);
-#undef ROWWG
+    if (g.sh == 1) PATCHWG(1); else PATCHWG(2);
+#undef PATCHWG
     return hipGetLastError();
   }
   const int vec = vec8(g, dtype) ? 8 : 1;

@@ -157,3 +157,34 @@ def test_transposed_block_queries_and_validation():
     assert L.convbn_tconv_eval_fwd(C.byref(d), ok, ok, None, ok, ok, ok, ok, ok, None, ok, need, None) == B.ERR_NULL   # y_saved
     assert L.convbn_tconv_eval_bwd(C.byref(d), ok, ok, None, ok, ok, ok, None, ok, ok, ok, None, ok, ok, ok, 1 << 40,
                                    None) == B.ERR_NULL                                                                   # y_saved
+
+
+def test_depthwise_block_queries_and_validation():
+    """Workspace / saved-bytes queries and host-side argument checks of the depthwise entry points."""
+    d = B.make_desc(32, 144, 56, 56, 144, 3, 3, 1, 1)
+    T, E = B.MODE_TUNE, B.MODE_EVAL
+    for m in (T, E):
+        for p in (B.PASS_FWD, B.PASS_BWD):
+            assert B.convbn_dw_workspace_bytes(d, m, p) % 256 == 0 and B.convbn_dw_workspace_bytes(d, m, p) > 0
+    assert B.convbn_dw_workspace_bytes(d, E, B.PASS_BWD) >= 32 * 56 * 56 * 144 * 2      # dY
+    assert B.convbn_dw_saved_bytes(d, E) == 32 * 56 * 56 * 144 * 2                      # Y
+    assert B.convbn_dw_saved_bytes(d, T) == 9 * 144 * 2 and B.convbn_dw_saved_bytes(d, T, True) == 0
+    bad = B.make_desc(2, 16, 8, 8, 32, 3, 3, 1, 1)                                      # not one filter per channel
+    assert B.convbn_dw_workspace_bytes(bad, T, B.PASS_FWD) == 0 and B.convbn_dw_saved_bytes(bad, T) == 0
+    L = B.lib()
+    ok = C.c_void_p(4096)
+    need = B.convbn_dw_workspace_bytes(d, T, B.PASS_FWD)
+    fwd = lambda desc, x=ok, ws=ok, n=need: L.convbn_dw_tune_fwd(desc, x, ok, None, ok, ok, ok, ok, ok, None, ws, n, None)
+    assert fwd(C.byref(bad)) == B.ERR_SHAPE
+    assert fwd(None) == B.ERR_NULL
+    assert fwd(C.byref(d), x=None) == B.ERR_NULL
+    assert fwd(C.byref(d), x=C.c_void_p(4100)) == B.ERR_UNSUPPORTED
+    assert fwd(C.byref(d), ws=None, n=0) == B.ERR_WORKSPACE
+    assert fwd(C.byref(d), n=need - 1) == B.ERR_WORKSPACE
+    needb = B.convbn_dw_workspace_bytes(d, T, B.PASS_BWD)
+    bwd = lambda dx, dW, db, dg, dbt: L.convbn_dw_tune_bwd(C.byref(d), ok, ok, None, ok, ok, ok, None, ok, dx, dW, db, dg,
+                                                          dbt, ok, needb, None)
+    assert bwd(ok, ok, ok, ok, ok) == B.ERR_NULL             # db given without b
+    assert bwd(ok, ok, None, None, ok) == B.ERR_NULL         # dgamma missing
+    assert bwd(None, None, None, None, None) == B.ERR_NULL   # nothing asked for
+    assert L.convbn_dw_eval_fwd(C.byref(d), ok, ok, None, ok, ok, ok, ok, ok, None, ok, need, None) == B.ERR_NULL   # y_saved
