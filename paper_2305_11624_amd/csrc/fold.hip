@@ -287,7 +287,14 @@ __global__ __launch_bounds__(NTHR) void fold_back_kernel(
     for (int k = tid; k < K; k += NTHR) {
       const size_t idx = (size_t)co * K + k;
       float v = 0.f;
-      for (int sp = 0; sp < nsplit; ++sp) v += part[sp * P + idx];
+      int sp = 0;
+      for (; sp + 7 < nsplit; sp += 8) {   // eight copies in flight: each load is a round trip of its own
+        float a[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a[j] = part[(sp + j) * P + idx];
+        v += ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+      }
+      for (; sp < nsplit; ++sp) v += part[sp * P + idx];
       dW[idx] = from_f32<T>(s * v);
       dot += v * to_f32(W[idx]);
     }
