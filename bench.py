@@ -145,6 +145,11 @@ def kernel_times(pool, reps):
                                                      r.gamma, r.mean, r.var, r.dW, r.db,
                                                      r.dgamma, r.dbeta),
     }
+    # the ablation of the fold (unfolded weight, scale applied in the convolution's epilogue): where it is built
+    if B.convbn_tune_fwd_scale_epilogue(d, r0.x, r0.W, r0.b, r0.gamma, r0.beta, r0.mean, r0.var, r0.z,
+                                        check=False) == B.OK:
+        calls["fprop_scale_epilogue"] = lambda r, w: B.convbn_tune_fwd_scale_epilogue(
+            d, r.x, r.W, r.b, r.gamma, r.beta, r.mean, r.var, r.z)
     out = {}
     for name, fn in calls.items():
         for i in range(min(3, len(pool))):

@@ -138,6 +138,17 @@ convbn_status convbn_eval_bwd(const convbn_desc *desc, const void *x, const void
                               void *dW, float *db, float *dgamma, float *dbeta, void *ws,
                               size_t ws_bytes, void *stream);
 
+/* Ablation of the fold (the forward of Sec. 3.3 without materialising w'): since the scale is per output
+ * channel, Z = s (w (*) X) + b' -- the convolution reads the UNFOLDED W and its epilogue applies s and b',
+ * which it works out from gamma, beta, mean, var (and b) itself.  One launch, no workspace, the same Z up to
+ * rounding (w' is never rounded to bf16 here).  Backward still needs w' (convbn_tune_bwd with
+ * w_folded == NULL folds it again).  Built as a measurement, for the kernel plans of the benchmark's 3x3
+ * and 1x1 shapes; CONVBN_ERR_UNSUPPORTED otherwise (nothing is launched). */
+convbn_status convbn_tune_fwd_scale_epilogue(const convbn_desc *desc, const void *x, const void *W,
+                                             const float *b, const float *gamma, const float *beta,
+                                             const float *mean, const float *var, void *z,
+                                             void *stream);
+
 /* ---- TransposedConv-BN block in Tune mode ----------------------------------------
  * Sec. 3.2.1 (last paragraph): scaling the weight along its output-channel index is
  * associative with a transposed convolution as well, so Tune mode covers

@@ -28,7 +28,8 @@ EXPORTS = ["convbn_hout", "convbn_wout", "convbn_workspace_bytes", "convbn_saved
            "convbn_fold_group", "convbn_tconv_hout", "convbn_tconv_wout", "convbn_tconv_workspace_bytes",
            "convbn_tconv_tune_fwd", "convbn_tconv_tune_bwd", "convbn_tconv_saved_bytes",
            "convbn_tconv_eval_fwd", "convbn_tconv_eval_bwd", "convbn_dw_workspace_bytes", "convbn_dw_saved_bytes",
-           "convbn_dw_tune_fwd", "convbn_dw_tune_bwd", "convbn_dw_eval_fwd", "convbn_dw_eval_bwd"]
+           "convbn_dw_tune_fwd", "convbn_dw_tune_bwd", "convbn_dw_eval_fwd", "convbn_dw_eval_bwd",
+           "convbn_tune_fwd_scale_epilogue"]
 
 
 class Desc(C.Structure):
@@ -138,6 +139,8 @@ def lib():
                            ("convbn_dw_eval_fwd", L.convbn_eval_fwd), ("convbn_dw_eval_bwd", L.convbn_eval_bwd)):
             getattr(L, name).restype = C.c_int
             getattr(L, name).argtypes = like.argtypes
+        L.convbn_tune_fwd_scale_epilogue.restype = C.c_int
+        L.convbn_tune_fwd_scale_epilogue.argtypes = [dp, vp, vp, fp, fp, fp, fp, fp, vp, vp]
         _lib = L
     return _lib
 
@@ -416,6 +419,14 @@ def convbn_tconv_tune_bwd(desc, x, W, b, gamma, mean, var, w_folded, dz, dx, dW,
     st = lib().convbn_tconv_tune_bwd(C.byref(desc), _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(mean),
                                      _ptr(var), _ptr(w_folded), _ptr(dz), _ptr(dx), _ptr(dW), _ptr(db),
                                      _ptr(dgamma), _ptr(dbeta), p, n, _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_tune_fwd_scale_epilogue(desc, x, W, b, gamma, beta, mean, var, z, stream=None, check=True):
+    st = lib().convbn_tune_fwd_scale_epilogue(C.byref(desc), _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(beta),
+                                              _ptr(mean), _ptr(var), _ptr(z), _stream(stream))
     if check:
         _check(st)
     return st

@@ -817,6 +817,28 @@ convbn_status convbn_dw_eval_bwd(const convbn_desc* desc, const void* x, const v
   return CONVBN_OK;
 }
 
+convbn_status convbn_tune_fwd_scale_epilogue(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                                             const float* gamma, const float* beta, const float* mean,
+                                             const float* var, void* z, void* stream) {
+  Geom g;
+  convbn_status s = make_geom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(beta); REQUIRE_PTR(mean);
+  REQUIRE_PTR(var); REQUIRE_PTR(z);
+  OPTIONAL_PTR(b);
+  const int dt = desc->dtype;
+  const BnEpilogue bn{gamma, beta, mean, var, b, g.eps};
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // Z = s (w (*) X) + b': the unfolded weight goes straight into the convolution, one launch in all
+  if (pw_fprop_scaled_supported(g, dt)) { LAUNCH(launch_fprop_pw(g, x, W, nullptr, z, st, &bn)); return CONVBN_OK; }
+  if (!pw_fprop_supported(g, dt) && tile_fprop_scaled_supported(g, dt)) {
+    LAUNCH(launch_fprop_tile(g, x, W, nullptr, z, nullptr, st, &bn));
+    return CONVBN_OK;
+  }
+  return fail(CONVBN_ERR_UNSUPPORTED, "the scale-in-the-epilogue forward is built for a few plans of the LDS-tile "
+              "kernels only (the benchmark's 3x3 and 1x1 shapes): use convbn_tune_fwd");
+}
+
 size_t convbn_fold_group_table_bytes(int n) { return n > 0 ? (size_t)n * fold_group_item_bytes() : 0; }
 
 convbn_status convbn_fold_group_plan(int n, const convbn_fold_item* items, void* table_host, size_t table_bytes,

@@ -46,6 +46,18 @@ struct Geom {
   float eps;
 };
 
+// Per-channel epilogue of a forward convolution that is given the UNFOLDED weight: Z = s (w (*) X) + b' with
+// s = gamma / sqrt(var + eps) and b' = (b - mu) s + beta worked out by the kernel itself -- the same forward
+// result as folding the weight first (Sec. 3.3), without materialising w'.  gamma == nullptr: not used.
+struct BnEpilogue {
+  const float* gamma;
+  const float* beta;
+  const float* mean;
+  const float* var;
+  const float* b;   // convolution bias or nullptr
+  float eps;
+};
+
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -148,9 +160,10 @@ hipError_t launch_wgrad_igemm(const Geom& g, const void* x, const void* dz, floa
 // (every input element is fetched once per block and reused by all taps).
 // conv_pw.hip: persistent weight-stationary kernel for 1x1 / stride-1 convolutions over long pixel ranges
 bool pw_fprop_supported(const Geom& g, int dtype);
+bool pw_fprop_scaled_supported(const Geom& g, int dtype);     // ... with a BnEpilogue
 bool pw_dgrad_supported(const Geom& g, int dtype);
 hipError_t launch_fprop_pw(const Geom& g, const void* x, const void* w_krsc, const float* bias, void* z,
-                           hipStream_t st);
+                           hipStream_t st, const BnEpilogue* bn = nullptr);
 hipError_t launch_dgrad_pw(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
                            hipStream_t st);
 // Forward of a transposed convolution whose stride equals its window (no padding), as one product with a
@@ -161,13 +174,14 @@ hipError_t launch_tconv_pw(const Geom& g, const void* x, const void* w_tap_major
                            hipStream_t st);
 
 bool tile_fprop_supported(const Geom& g, int dtype);
+bool tile_fprop_scaled_supported(const Geom& g, int dtype);   // ... with a BnEpilogue
 bool tile_dgrad_supported(const Geom& g, int dtype);
 // Some problems split the reduced channels over several workgroups and need fp32 partial-output
 // storage of this many bytes (0 otherwise), passed as `partials`.
 size_t tile_fprop_partial_bytes(const Geom& g);
 size_t tile_dgrad_partial_bytes(const Geom& g);
 hipError_t launch_fprop_tile(const Geom& g, const void* x, const void* w_krsc, const float* bias,
-                             void* z, float* partials, hipStream_t st);
+                             void* z, float* partials, hipStream_t st, const BnEpilogue* bn = nullptr);
 // The input-gradient launchers take an optional per-input-channel bias: a transposed convolution's forward
 // pass is this kernel (Sec. 3.2.1), and its folded bias b' is added here.
 hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,

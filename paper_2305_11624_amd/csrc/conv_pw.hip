@@ -44,6 +44,7 @@ struct PwParams {
   const bf16_t* act;     // [M][C]
   const bf16_t* wgt;     // [R][C]
   const float* bias;     // [R] or null
+  BnEpilogue bn;         // bn.gamma != null: the weight is unfolded, the epilogue applies s and b' (bias unused)
   bf16_t* out;           // [M][R]
   unsigned act_bytes, wgt_bytes;
   int M, C, R;
@@ -98,7 +99,8 @@ template <int NW, int CB> struct PwCfg {
   static constexpr int SLOT = AUNITS * UNITB + 64;
 };
 
-template <int NW, int NCH, int CB>
+// SC: unfolded weight, BatchNorm scale and folded bias applied by the epilogue (an instantiation of its own).
+template <int NW, int NCH, int CB, bool SC = false>
 __global__ __launch_bounds__(64 * NW) void conv_pw_kernel(PwParams p) {
   using Cfg = PwCfg<NW, CB>;
   constexpr int TP = Cfg::TP, TRC = 32 * NCH, GPR = Cfg::GPR, LPR = Cfg::LPR, RPU = Cfg::RPU, ROWP = Cfg::ROWP;
@@ -121,7 +123,16 @@ __global__ __launch_bounds__(64 * NW) void conv_pw_kernel(PwParams p) {
   const __amdgpu_buffer_rsrc_t act_rsrc = make_rsrc(p.act, p.act_bytes);
   const __amdgpu_buffer_rsrc_t wgt_rsrc = make_rsrc(p.wgt, p.wgt_bytes);
 
-  if (tid < TRC) biasl[tid] = (p.bias && r0 + tid < p.R) ? p.bias[r0 + tid] : 0.f;
+  if (tid < TRC) {
+    float bias_v = (p.bias && r0 + tid < p.R) ? p.bias[r0 + tid] : 0.f, scale_v = 1.f;
+    if (SC && r0 + tid < p.R) {
+      const int ch = r0 + tid;
+      scale_v = p.bn.gamma[ch] / sqrtf(p.bn.var[ch] + p.bn.eps);
+      bias_v = ((p.bn.b ? p.bn.b[ch] : 0.f) - p.bn.mean[ch]) * scale_v + p.bn.beta[ch];
+    }
+    biasl[tid] = bias_v;
+    if (SC) biasl[128 + tid] = scale_v;   // scales behind the (at most 128) biases
+  }
 
   // ---- the weight block: LDS byte o of the tile is row o / wpitch, byte o % wpitch (the last 16: pad)
   for (int u = wave; u * 1024 < p.wtile_bytes; u += NW) {
@@ -234,8 +245,15 @@ __global__ __launch_bounds__(64 * NW) void conv_pw_kernel(PwParams p) {
           for (int q = 0; q < 4; ++q) {
             const int ch = r2 * 32 + q * 8 + kb * 4;
             const float4 bb = *reinterpret_cast<const float4*>(biasl + r * 32 + q * 8 + kb * 4);
-            const uint2 v = make_uint2(pack_bf16x2(acc[r][q * 4 + 0] + bb.x, acc[r][q * 4 + 1] + bb.y),
-                                       pack_bf16x2(acc[r][q * 4 + 2] + bb.z, acc[r][q * 4 + 3] + bb.w));
+            uint2 v;
+            if constexpr (SC) {   // unfolded weight: the BatchNorm scale is applied here
+              const float4 sc = *reinterpret_cast<const float4*>(biasl + 128 + r * 32 + q * 8 + kb * 4);
+              v = make_uint2(pack_bf16x2(fmaf(acc[r][q * 4 + 0], sc.x, bb.x), fmaf(acc[r][q * 4 + 1], sc.y, bb.y)),
+                             pack_bf16x2(fmaf(acc[r][q * 4 + 2], sc.z, bb.z), fmaf(acc[r][q * 4 + 3], sc.w, bb.w)));
+            } else {
+              v = make_uint2(pack_bf16x2(acc[r][q * 4 + 0] + bb.x, acc[r][q * 4 + 1] + bb.y),
+                             pack_bf16x2(acc[r][q * 4 + 2] + bb.z, acc[r][q * 4 + 3] + bb.w));
+            }
             *reinterpret_cast<uint2*>(st + px * 128 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[r][q * 4 + e] = 0.f;
@@ -316,20 +334,25 @@ PwPlan make_plan(PwParams& p) {
   return pl;
 }
 
-template <int NW, int NCH, int CB>
+template <int NW, int NCH, int CB, bool SC = false>
 hipError_t launch_inst(const PwParams& p, const PwPlan& pl, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_pw_kernel<NW, NCH, CB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_pw_kernel<NW, NCH, CB, SC>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_USABLE);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((conv_pw_kernel<NW, NCH, CB>), dim3(p.ntr * p.groups), dim3(64 * NW), pl.lds, st, p);
+  hipLaunchKernelGGL((conv_pw_kernel<NW, NCH, CB, SC>), dim3(p.ntr * p.groups), dim3(64 * NW), pl.lds, st, p);
   return hipGetLastError();
 }
 
 hipError_t launch_plan(const PwParams& p, const PwPlan& pl, hipStream_t st) {
+  if (p.bn.gamma) {   // the ablation is built for 64-channel chunks
+    if (pl.nch == 2 && pl.cb == 64) return launch_inst<4, 2, 64, true>(p, pl, st);
+    if (pl.nch == 4 && pl.cb == 64) return launch_inst<4, 4, 64, true>(p, pl, st);
+    return hipErrorInvalidValue;
+  }
   if (pl.nch == 2 && pl.cb == 64) return launch_inst<4, 2, 64>(p, pl, st);
   if (pl.nch == 2 && pl.cb == 32) return launch_inst<4, 2, 32>(p, pl, st);
   if (pl.nch == 4 && pl.cb == 64) return launch_inst<4, 4, 64>(p, pl, st);
@@ -387,6 +410,12 @@ hipError_t launch_tconv_pw(const Geom& g, const void* x, const void* w_tap_major
   return launch_plan(p, pl, st);
 }
 
+bool pw_fprop_scaled_supported(const Geom& g, int dtype) {
+  if (dtype != CONVBN_BF16 || !pointwise(g)) return false;
+  PwParams p = fprop_params(g);
+  const PwPlan pl = make_plan(p);
+  return pl.ok && pl.cb == 64;
+}
 bool pw_fprop_supported(const Geom& g, int dtype) {
   if (dtype != CONVBN_BF16 || !pointwise(g)) return false;
   PwParams p = fprop_params(g);
@@ -398,10 +427,11 @@ bool pw_dgrad_supported(const Geom& g, int dtype) {
   return make_plan(p).ok;
 }
 hipError_t launch_fprop_pw(const Geom& g, const void* x, const void* w_krsc, const float* bias, void* z,
-                           hipStream_t st) {
+                           hipStream_t st, const BnEpilogue* bn) {
   PwParams p = fprop_params(g);
   const PwPlan pl = make_plan(p);
   if (!pl.ok) return hipErrorInvalidValue;
+  if (bn) p.bn = *bn;
   p.act = (const bf16_t*)x; p.wgt = (const bf16_t*)w_krsc; p.bias = bias; p.out = (bf16_t*)z;
   return launch_plan(p, pl, st);
 }

@@ -55,6 +55,7 @@ struct TileParams {
   const bf16_t* act;     // activations, channels-last, explicit strides (elements)
   const bf16_t* wgt;     // [R][taps][C]
   const float* bias;     // [R] or null
+  BnEpilogue bn;         // bn.gamma != null: the weight is unfolded, the epilogue applies s and b' (bias unused)
   bf16_t* out;           // [M][R]
   unsigned act_bytes, wgt_bytes;
   int N, H, W, C;        // activation grid the window slides over
@@ -149,7 +150,9 @@ template <int NCH, int CB> struct TileCfg {
 // The step loop is branch-free apart from its back edge: all per-step decisions are scalar selects,
 // and the per-lane copy offsets of the activation tile come from a table in LDS built once per
 // workgroup (row k of wave w = copy unit w + NW k; rows past the tile hold the zero-fill offset).
-template <int NW, int NWC, int NCH, int CB, int HPS>
+// SC: the weight is unfolded and the epilogue applies the BatchNorm scale and folded bias it works out itself (an
+// instantiation of its own, so the default kernels carry none of it).
+template <int NW, int NWC, int NCH, int CB, int HPS, bool SC = false>
 __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   using Cfg = TileCfg<NCH, CB>;
   constexpr int NWP = NW / NWC;            // waves along the pixels
@@ -198,7 +201,13 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   const int nchunks = min(p.C / CB, cbeg + p.chunks_per_split);           // one past its last chunk
   const int nsteps = (nchunks - cbeg) * taps;
   // bias of this channel tile: fetched now, parked in LDS after the main loop (nothing waits for it)
-  const float bias_v = (tid < TRC && p.bias && r0 + tid < p.R) ? p.bias[r0 + tid] : 0.f;
+  float bias_v = (tid < TRC && p.bias && r0 + tid < p.R) ? p.bias[r0 + tid] : 0.f;
+  float scale_v = 1.f;
+  if (SC && tid < TRC && r0 + tid < p.R) {
+    const int ch = r0 + tid;
+    scale_v = p.bn.gamma[ch] / sqrtf(p.bn.var[ch] + p.bn.eps);
+    bias_v = ((p.bn.b ? p.bn.b[ch] : 0.f) - p.bn.mean[ch]) * scale_v + p.bn.beta[ch];
+  }
 
   // this lane's place inside every 1 KB copy: row lrow (RPU = the spill row) and granule lgran (GPR = pad)
   const int lrow = lane / LPR;
@@ -439,7 +448,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     }
     return;
   }
-  if (tid < TRC) biasl[tid] = bias_v;
+  if (tid < TRC) { biasl[tid] = bias_v; if (SC) biasl[128 + tid] = scale_v; }   // scales behind the (at most 128) biases
   __syncthreads();   // every wave's copies have landed, every wave is done with the ring, the bias is visible
   {
     unsigned char* stage = smem + 1024 + wave * 4096;   // behind the bias, over the (now idle) ring and tiles
@@ -455,8 +464,15 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
         for (int q = 0; q < 4; ++q) {
           const int ch = r2 * 32 + q * 8 + kb * 4;          // channel inside this 64-channel block
           const float4 bb = *reinterpret_cast<const float4*>(biasl + (cw0 + r) * 32 + q * 8 + kb * 4);
-          const uint2 v = make_uint2(pack_bf16x2(acc[r][q * 4 + 0] + bb.x, acc[r][q * 4 + 1] + bb.y),
-                                     pack_bf16x2(acc[r][q * 4 + 2] + bb.z, acc[r][q * 4 + 3] + bb.w));
+          uint2 v;
+          if constexpr (SC) {   // unfolded weight: the BatchNorm scale is applied here
+            const float4 sc = *reinterpret_cast<const float4*>(biasl + 128 + (cw0 + r) * 32 + q * 8 + kb * 4);
+            v = make_uint2(pack_bf16x2(fmaf(acc[r][q * 4 + 0], sc.x, bb.x), fmaf(acc[r][q * 4 + 1], sc.y, bb.y)),
+                           pack_bf16x2(fmaf(acc[r][q * 4 + 2], sc.z, bb.z), fmaf(acc[r][q * 4 + 3], sc.w, bb.w)));
+          } else {
+            v = make_uint2(pack_bf16x2(acc[r][q * 4 + 0] + bb.x, acc[r][q * 4 + 1] + bb.y),
+                           pack_bf16x2(acc[r][q * 4 + 2] + bb.z, acc[r][q * 4 + 3] + bb.w));
+          }
           *reinterpret_cast<uint2*>(stage + px * 128 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
         }
       }
@@ -679,17 +695,17 @@ TilePlan make_plan(TileParams& p) {
   return pl;
 }
 
-template <int NW, int NWC, int NCH, int CB, int HPS>
+template <int NW, int NWC, int NCH, int CB, int HPS, bool SC = false>
 hipError_t launch_inst(const TileParams& p, const TilePlan& pl, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_tile_kernel<NW, NWC, NCH, CB, HPS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_tile_kernel<NW, NWC, NCH, CB, HPS, SC>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_USABLE);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int ptiles = p.tile_rows > 0 ? p.N * p.tiles_per_image : ceil_div(p.M, 32 * (NW / NWC));
-  hipLaunchKernelGGL((conv_tile_kernel<NW, NWC, NCH, CB, HPS>), dim3(p.ntr * ptiles, p.ksplit), dim3(64 * NW), pl.lds, st,
+  hipLaunchKernelGGL((conv_tile_kernel<NW, NWC, NCH, CB, HPS, SC>), dim3(p.ntr * ptiles, p.ksplit), dim3(64 * NW), pl.lds, st,
                      p);
   hipError_t le = hipGetLastError();
   if (le != hipSuccess || p.ksplit == 1) return le;
@@ -699,7 +715,19 @@ hipError_t launch_inst(const TileParams& p, const TilePlan& pl, hipStream_t st) 
   return hipGetLastError();
 }
 
+// The scale-in-the-epilogue ablation is built for the plans of the 3x3 benchmark shapes only.
+bool scaled_plan(const TilePlan& pl) {
+  return (pl.nw == 16 && pl.nwc == 1 && pl.nch == 2 && pl.cb == 64 && pl.hps == 0) ||
+         (pl.nw == 8 && pl.nwc == 1 && pl.nch == 2 && pl.cb == 64 && pl.hps == 0) ||
+         (pl.nw == 4 && pl.nwc == 2 && pl.nch == 4 && pl.cb == 64 && pl.hps == 1);
+}
+
 hipError_t launch_plan(const TileParams& p, const TilePlan& pl, hipStream_t st) {
+  if (p.bn.gamma) {
+    if (pl.nw == 16 && pl.hps == 0) return launch_inst<16, 1, 2, 64, 0, true>(p, pl, st);
+    if (pl.nw == 8 && pl.hps == 0) return launch_inst<8, 1, 2, 64, 0, true>(p, pl, st);
+    return launch_inst<4, 2, 4, 64, 1, true>(p, pl, st);
+  }
 #define CASE(NWV, WC, NC, CBV, H) \
   if (pl.nw == NWV && pl.nwc == WC && pl.nch == NC && pl.cb == CBV && pl.hps == H) \
     return launch_inst<NWV, WC, NC, CBV, H>(p, pl, st);
@@ -852,6 +880,14 @@ bool tile_dgrad_supported(const Geom& g, int dtype) {
   return true;
 }
 
+bool tile_fprop_scaled_supported(const Geom& g, int dtype) {
+  if (dtype != CONVBN_BF16) return false;
+  TileParams p;
+  if (!fprop_params(g, &p)) return false;
+  const TilePlan pl = make_plan(p);
+  return pl.ok && p.ksplit == 1 && scaled_plan(pl);
+}
+
 size_t tile_fprop_partial_bytes(const Geom& g) {
   TileParams p;
   if (!fprop_params(g, &p) || !make_plan(p).ok) return 0;
@@ -866,11 +902,13 @@ size_t tile_dgrad_partial_bytes(const Geom& g) {
 }
 
 hipError_t launch_fprop_tile(const Geom& g, const void* x, const void* w_krsc, const float* bias,
-                             void* z, float* partials, hipStream_t st) {
+                             void* z, float* partials, hipStream_t st, const BnEpilogue* bn) {
   TileParams p;
   fprop_params(g, &p);
   const TilePlan pl = make_plan(p);
-  if (p.ksplit > 1 && !partials) return hipErrorInvalidValue;
+  if (p.ksplit > 1 && (!partials || bn)) return hipErrorInvalidValue;   // split sums add the bias in their reduction
+  if (bn && !scaled_plan(pl)) return hipErrorInvalidValue;
+  if (bn) p.bn = *bn;
   p.act = (const bf16_t*)x; p.wgt = (const bf16_t*)w_krsc; p.bias = bias; p.out = (bf16_t*)z;
   p.part = partials;
   return launch_plan(p, pl, st);

@@ -165,3 +165,28 @@ def test_fold_group_matches_single_folds():
                mean=B.vec_to_device(inp["rmean"], "cuda"), var=B.vec_to_device(inp["rvar"], "cuda"),
                w_fprop=None, w_folded=None, b_folded=None)
     assert B.convbn_fold_group_plan([bad], check=False) == B.ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("name", ["c2a", "c2b", "c1"])
+def test_scale_in_the_epilogue_forward_matches_the_oracle(name):
+    """Forward with the unfolded weight and the BatchNorm scale applied in the convolution's epilogue (the ablation
+    of folding first): the same Z as the definition, for a batch small enough for the oracle."""
+    import dataclasses
+    from paper_2305_11624_amd import binding as B, synth
+    from paper_2305_11624_amd.runner import BlockRun
+    from helpers import compare, oracle_block
+    shape = dataclasses.replace(synth.CONFIGS[name], N={"c2a": 4, "c2b": 64, "c1": 16}[name])
+    inp = synth.make_inputs(shape, bias=True, wide_scale=(name == "c2a"))
+    ref = oracle_block(inp, need_dx=False)
+    r = BlockRun(inp, "tune", poison=True)
+    B.convbn_tune_fwd_scale_epilogue(r.desc, r.x, r.W, r.b, r.gamma, r.beta, r.mean, r.var, r.z)
+    torch.cuda.synchronize()
+    compare({"Z": B.act_from_device(r.z)}, ref, "bf16", keys=("Z",), tag=name + "/scale-epilogue")
+
+
+def test_scale_in_the_epilogue_forward_refuses_other_shapes():
+    from paper_2305_11624_amd import binding as B
+    d = B.make_desc(2, 3, 32, 32, 64, 7, 7, 2, 3)     # the 3-channel stem runs on the generic kernels
+    x = torch.zeros(1 << 16, device="cuda", dtype=torch.bfloat16)
+    v = torch.zeros(64, device="cuda")
+    assert B.convbn_tune_fwd_scale_epilogue(d, x, x, None, v, v, v, v, x, check=False) == B.ERR_UNSUPPORTED
