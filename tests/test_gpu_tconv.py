@@ -54,12 +54,14 @@ BF16 = [
     # stride = window over enough pixels for the single-product forward (depth-to-space store), ragged last tile
     BlockShape("t_d2s_k2", 6, 64, 37, 37, 64, 2, 2, 0, "bf16", 79),
     BlockShape("t_d2s_k3", 2, 32, 41, 41, 64, 3, 3, 0, "bf16", 80),
+    # 1x1 over a long pixel range: the persistent 1x1 kernel in its input-gradient role, with the folded bias
+    BlockShape("t_k1_long", 8, 64, 48, 48, 64, 1, 1, 0, "bf16", 84),
 ]
 
 
 @pytest.mark.parametrize("shape", BF16, ids=lambda s: s.name)
 def test_bf16_shapes(shape):
-    inp = synth.make_tconv_inputs(shape, bias=shape.name in ("t_k2s3", "t_k4s2p1", "t_d2s_k2", "t_d2s_k3"))
+    inp = synth.make_tconv_inputs(shape, bias=shape.name in ("t_k2s3", "t_k4s2p1", "t_d2s_k2", "t_d2s_k3", "t_k1_long"))
     ref = oracle_tconv_block(inp)
     compare(_run(inp), ref, "bf16", keys=KEYS, tag=shape.name)
     compare(_run(inp, mode="eval"), ref, "bf16", keys=EVAL_KEYS, tag=shape.name + "/eval")
