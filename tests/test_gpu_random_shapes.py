@@ -1,0 +1,82 @@
+"""Seeded sweep of randomly drawn (valid) shapes through the three blocks, each against the oracle: windows 1-7,
+strides 1-3, all paddings, channel counts that do and do not fit the MFMA tiles, ragged images.  Catches planner
+corner cases the hand-picked shapes miss; every draw is reproducible from the seed."""
+import random
+
+import pytest
+
+from paper_2305_11624_amd import synth
+from paper_2305_11624_amd.synth import BlockShape
+
+from helpers import compare, oracle_block, oracle_dw_block, oracle_tconv_block
+
+pytestmark = pytest.mark.gpu
+
+CHANS = [8, 16, 24, 32, 40, 64, 72, 96, 128, 136, 192, 256, 320, 512]
+
+
+def _bounded(n, h, cin, work):
+    """Shrink until the oracle's multiply count `work(n, h, cin)` is small."""
+    while work(n, h, cin) > 2e9:
+        if n > 1:
+            n -= 1
+        elif h > 8:
+            h //= 2
+        else:
+            cin = max(8, cin // 2)
+    return n, h, cin
+
+
+def test_dense_block_random_shapes():
+    from paper_2305_11624_amd.runner import BlockRun
+    rng = random.Random(20230511)
+    for it in range(48):
+        k = rng.choice([1, 1, 3, 3, 3, 5, 7])
+        s = rng.choice([1, 1, 2])
+        p = rng.randint(0, k // 2)
+        cin, cout = rng.choice(CHANS), rng.choice(CHANS)
+        h, w = rng.randint(max(k, 4), 48), rng.randint(max(k, 4), 48)
+        n, h, cin = _bounded(rng.randint(1, 8), h, cin, lambda n_, h_, c_: n_ * h_ * w * c_ * cout * k * k)
+        h = max(h, k)
+        shape = BlockShape(f"r{it}", n, cin, h, w, cout, k, s, p, "bf16", 4000 + it)
+        mode, keep, bias = rng.choice(["tune", "tune", "eval"]), rng.random() < 0.7, rng.random() < 0.5
+        inp = synth.make_inputs(shape, bias=bias)
+        r = BlockRun(inp, mode=mode, keep_folded=keep, poison=True)
+        r.step()
+        compare(r.results(), oracle_block(inp), "bf16", tag=f"{shape} {mode} keep={keep}")
+
+
+def test_transposed_block_random_shapes():
+    from paper_2305_11624_amd.runner import TconvRun
+    rng = random.Random(20230512)
+    for it in range(32):
+        k = rng.choice([1, 2, 2, 3, 4, 4])
+        s = rng.choice([1, 2, 2, 3]) if k > 1 else 1
+        p = rng.randint(0, (k - 1) // 2)
+        cin, cout = rng.choice(CHANS[:12]), rng.choice(CHANS[:12])
+        h, w = rng.randint(3, 40), rng.randint(3, 40)
+        n, h, cin = _bounded(rng.randint(1, 8), h, cin, lambda n_, h_, c_: n_ * h_ * w * c_ * cout * k * k)
+        h = max(h, 3)
+        shape = BlockShape(f"rt{it}", n, cin, h, w, cout, k, s, p, "bf16", 5000 + it)
+        mode, keep, bias = rng.choice(["tune", "tune", "eval"]), rng.random() < 0.7, rng.random() < 0.5
+        inp = synth.make_tconv_inputs(shape, bias=bias)
+        r = TconvRun(inp, mode=mode, keep_folded=keep, poison=True)
+        r.step()
+        compare(r.results(), oracle_tconv_block(inp), "bf16", tag=f"{shape} {mode} keep={keep}")
+
+
+def test_depthwise_block_random_shapes():
+    from paper_2305_11624_amd.runner import DepthwiseRun
+    rng = random.Random(20230513)
+    for it in range(32):
+        k = rng.choice([1, 3, 3, 3, 5, 7])
+        s = rng.choice([1, 1, 2])
+        p = rng.randint(0, k // 2)
+        c = rng.choice(CHANS[:12] + [12, 20, 144, 576])
+        h, w = rng.randint(max(k, 4), 60), rng.randint(max(k, 4), 60)
+        shape = BlockShape(f"rd{it}", rng.randint(1, 8), c, h, w, c, k, s, p, "bf16", 6000 + it)
+        mode, keep, bias = rng.choice(["tune", "tune", "eval"]), rng.random() < 0.7, rng.random() < 0.5
+        inp = synth.make_dw_inputs(shape, bias=bias)
+        r = DepthwiseRun(inp, mode=mode, keep_folded=keep, poison=True)
+        r.step()
+        compare(r.results(), oracle_dw_block(inp), "bf16", tag=f"{shape} {mode} keep={keep}")
