@@ -191,6 +191,8 @@ size_t inner_dgrad_scratch(const Geom& g, int dtype) {
 }
 size_t fprop_scratch_bytes(const Geom& g, int dtype) {
   if (!needs_cin_pad(g, dtype)) return inner_fprop_scratch(g, dtype);
+  if (stem_fprop_supported(g, dtype))
+    return align_up(stem_packed_weight_bytes(g), 256) + align_up(stem_input_copy_bytes(g), 256);
   const Geom q = padded_geom(g);
   return align_up((size_t)q.Min * q.Cin * 2, 256) + align_up((size_t)q.Cout * q.K * 2, 256) +
          inner_fprop_scratch(q, dtype);
@@ -232,6 +234,14 @@ hipError_t dgrad_any(const Geom& g, int dtype, const void* dz, const void* w_crs
 hipError_t run_fprop(const Geom& g, int dtype, const void* x, const void* w_krsc, const float* bias,
                      void* z, float* scratch, hipStream_t st) {
   if (!needs_cin_pad(g, dtype)) return fprop_any(g, dtype, x, w_krsc, bias, z, scratch, st);
+  if (stem_fprop_supported(g, dtype)) {   // a first layer: its own kernel; the scratch holds the padded weight
+    char* sp = reinterpret_cast<char*>(scratch);
+    void* wpad = sp;
+    sp += align_up(stem_packed_weight_bytes(g), 256);
+    if (stem_input_copy_bytes(g) == 0) return launch_fprop_stem(g, x, w_krsc, wpad, bias, z, st);
+    TRY(launch_repitch(2, (size_t)g.Min, g.Cin, 4, x, sp, st));   // ... and a 4-channel copy of the input
+    return launch_fprop_stem(g, sp, w_krsc, wpad, bias, z, st);
+  }
   const Geom q = padded_geom(g);
   char* s = reinterpret_cast<char*>(scratch);
   void* xp = s; s += align_up((size_t)q.Min * q.Cin * 2, 256);

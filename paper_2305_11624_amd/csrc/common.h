@@ -146,6 +146,14 @@ int wgrad_direct_splits(const Geom& g);
 hipError_t launch_wgrad_direct(const Geom& g, int dtype, const void* x, const void* dz,
                                float* dwf_part /*[splits][Cout][K]*/, hipStream_t st);
 
+// conv_stem.hip : forward convolution of a first layer (at most 4 input channels), bf16 MFMA, operands read
+// straight from the raw input patch.  w is the weight as [Cout][kH][kW][Cin].
+bool stem_fprop_supported(const Geom& g, int dtype);
+size_t stem_packed_weight_bytes(const Geom& g);   // scratch for the weight padded to 8 window columns x 4 channels
+size_t stem_input_copy_bytes(const Geom& g);      // scratch for a 4-channel copy of the input (0: read as it is)
+hipError_t launch_fprop_stem(const Geom& g, const void* x, const void* w, void* wpad, const float* bias, void* z,
+                             hipStream_t st);
+
 // conv_igemm.hip : bf16 MFMA implicit GEMM
 bool igemm_supported(const Geom& g, int dtype);
 int wgrad_splits(const Geom& g);

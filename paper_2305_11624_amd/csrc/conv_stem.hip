@@ -1,0 +1,274 @@
+// Forward convolution of a network's first layer (Sec. 3.1's Y = w (*) X + b with at most four input
+// channels, e.g. the 7x7 / stride-2 stem of a ResNet on RGB images), bf16 MFMA with fp32 accumulation.
+//
+// With 3 input channels the reduction index (tap, channel) has no 16-byte runs for the generic kernels to
+// gather, and padding the channels to 8 makes them multiply and fetch mostly zeros.  Here the pixels are
+// widened to 4 channels (8 bytes) on their way into LDS and the reduction index is ordered (window row i, window column
+// j padded to 8, channel c padded to 4): the 8 consecutive reduction elements an MFMA lane needs -- two
+// window columns x four channels -- are then 16 contiguous bytes of the input row, for every output pixel.
+// So no im2col is ever materialised: the operand fragments are read straight from the raw input patch in
+// LDS (output pixel wo, window columns j..j+1 -> patch bytes (wo sw + j) 8 ..), consecutive lanes 8 sw bytes
+// apart.  The weights (Cout x kH x 8 x 4, zero-padded) stay resident in LDS; a workgroup is persistent and
+// walks tiles of 128 consecutive pixels of one output row: patch in (kH rows x (127 sw + 8) pixels), kH x 2
+// MFMA k-steps, staged 16-byte stores out.
+#include "common.h"
+
+namespace convbn {
+
+namespace {
+
+constexpr int TPX = 128;            // output pixels per tile (32 per wave)
+constexpr int KROW = 32;            // reduction elements per window row: 8 columns x 4 channels
+
+struct StemParams {
+  const bf16_t* x;      // X3: [N][H][W][3] (W % 4 == 0); else [N][H][W][4]
+  const bf16_t* w;      // [Cout][kH][8][4]: the weight zero-padded to 8 window columns and 4 channels
+  const float* bias;    // [Cout] or null
+  bf16_t* z;            // [N][Ho][Wo][Cout]
+  int N, H, W, Cin, Cout, kH, kW, sh, sw, ph, pw, Ho, Wo;
+  int ntw, ntiles;      // tiles per output row, tiles in all
+  int wpitch;           // LDS bytes per weight row: kH * 64 + 16
+  int prow;             // LDS bytes per patch row: ((TPX - 1) sw + 8) * 8
+  int pcols;            // pixels per patch row (X3: a multiple of 4, with up to 3 leading pixels of alignment)
+};
+
+constexpr int ppt(bool x3) { return x3 ? 3 : 8; }   // most patch items a thread fetches per tile
+
+// NCO: 32-channel fragments per workgroup (Cout = 32 NCO); KH: window rows (0 = run-time, any number); X3: the
+// input has 3 channels and is fetched four pixels (24 contiguous bytes) at a time, else 4 channels, one pixel
+// (8 bytes) at a time.
+template <int NCO, int KH, bool X3>
+__global__ __launch_bounds__(256) void stem_fprop_kernel(StemParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float* biasl = reinterpret_cast<float*>(smem);                       // [Cout] (first 512 bytes)
+  unsigned char* wl = smem + 512;                                      // [Cout][wpitch]
+  unsigned char* patch = wl + 32 * NCO * p.wpitch;                     // [kH][prow]; reused to stage the output tile
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kb = lane >> 5, px = lane & 31;
+  const int kH = KH > 0 ? KH : p.kH;
+
+  // ---- resident weights: rows of the padded [Cout][kH][8][4] block, 16 bytes per load
+  const int wrow_g = kH * KROW / 8;   // 16-byte granules per weight row
+  for (int e = tid; e < 32 * NCO * wrow_g; e += 256) {
+    const int co = e / wrow_g, gq = e - co * wrow_g;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (co < p.Cout) v = *reinterpret_cast<const uint4*>(p.w + ((size_t)co * wrow_g + gq) * 8);
+    *reinterpret_cast<uint4*>(wl + co * p.wpitch + gq * 16) = v;
+  }
+  if (tid < 32 * NCO) biasl[tid] = (p.bias && tid < p.Cout) ? p.bias[tid] : 0.f;
+
+  // patch item e = tid + 256 k of a tile: (row i, pixel -- X3: group of four pixels -- q), the same for every tile
+  constexpr int PPT = ppt(X3);
+  constexpr int PXI = X3 ? 4 : 1;                 // pixels per item
+  constexpr int NLD = X3 ? 3 : 1;                 // 8-byte loads per item
+  const int icols = p.pcols / PXI;
+  const int npatch = kH * icols;
+  int pi[PPT], pq[PPT];
+#pragma unroll
+  for (int k = 0; k < PPT; ++k) {
+    const int e = tid + 256 * k;
+    pi[k] = e / icols;
+    pq[k] = (e - pi[k] * icols) * PXI;
+  }
+  // first patch pixel of a tile: wo0 sw - pw, X3: rounded down to a multiple of four pixels
+  auto patch_start = [&](int ws) {
+    const int wbase = ws * TPX * p.sw - p.pw;
+    return X3 ? (wbase >> 2) << 2 : wbase;
+  };
+  // fetch of a tile's patch into registers (zeros outside the image); the tile after the current one is
+  // always in flight while the current one is multiplied
+  uint2 pv[PPT][NLD];
+  auto fetch = [&](int tile) {
+    const int ws = tile % p.ntw;
+    const int row = tile / p.ntw;
+    const int ho = row % p.Ho, n = row / p.Ho;
+    const int wstart = patch_start(ws);
+#pragma unroll
+    for (int k = 0; k < PPT; ++k) {
+      const int h = ho * p.sh + pi[k] - p.ph, w = wstart + pq[k];
+#pragma unroll
+      for (int j = 0; j < NLD; ++j) pv[k][j] = make_uint2(0u, 0u);
+      if (tid + 256 * k < npatch && tile < p.ntiles && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W) {
+        const uint2* src = reinterpret_cast<const uint2*>(p.x + (((size_t)n * p.H + h) * p.W + w) * (X3 ? 3 : 4));
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) pv[k][j] = src[j];
+      }
+    }
+  };
+  // registers -> LDS, every pixel as 4 channels (X3: the 12 values of four pixels spread over 4 x 8 bytes)
+  auto stash = [&]() {
+#pragma unroll
+    for (int k = 0; k < PPT; ++k) {
+      if (tid + 256 * k >= npatch) continue;
+      unsigned char* dst = patch + pi[k] * p.prow + pq[k] * 8;
+      if constexpr (X3) {
+        const uint2 a = pv[k][0], b = pv[k][1], c = pv[k][2];
+        *reinterpret_cast<uint4*>(dst) = make_uint4(a.x, a.y & 0xffffu, (a.y >> 16) | (b.x << 16), b.x >> 16);
+        *reinterpret_cast<uint4*>(dst + 16) = make_uint4(b.y, c.x & 0xffffu, (c.x >> 16) | (c.y << 16), c.y >> 16);
+      } else {
+        *reinterpret_cast<uint2*>(dst) = pv[k][0];
+      }
+    }
+  };
+  fetch(blockIdx.x);
+
+  for (int tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x) {
+    const int ws = tile % p.ntw;
+    const int row = tile / p.ntw;
+    const int ho = row % p.Ho, n = row / p.Ho;
+    const int wo0 = ws * TPX;
+    __syncthreads();   // the previous tile's staged output has been read
+    stash();
+    fetch(tile + gridDim.x);
+    __syncthreads();   // patch (and, first pass, weights and bias) visible
+
+    f32x16 acc[NCO];
+#pragma unroll
+    for (int f = 0; f < NCO; ++f)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[f][e] = 0.f;
+    // lane's pixel: wo0 + 32 wave + px; its window starts at patch pixel (32 wave + px) sw (+ the alignment pixels)
+    const int lead = wo0 * p.sw - p.pw - patch_start(ws);
+    const unsigned char* prow0 = patch + ((wave * 32 + px) * p.sw + 2 * kb + lead) * 8;
+    const unsigned char* wrow0 = wl + px * p.wpitch + kb * 16;
+    auto kstep = [&](int i, int jh) {   // window row i, columns 4 jh .. 4 jh + 3: lanes kb = 0 / 1 take two each
+      const unsigned char* bp = prow0 + i * p.prow + jh * 32;
+      const uint2 b0 = *reinterpret_cast<const uint2*>(bp);
+      const uint2 b1 = *reinterpret_cast<const uint2*>(bp + 8);
+      const bf16x8 fb = __builtin_bit_cast(bf16x8, make_uint4(b0.x, b0.y, b1.x, b1.y));
+#pragma unroll
+      for (int f = 0; f < NCO; ++f) {
+        const bf16x8 fa = *reinterpret_cast<const bf16x8*>(wrow0 + f * 32 * p.wpitch + (i * 2 + jh) * 32);
+        acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[f], 0, 0, 0);
+      }
+    };
+    if (KH > 0) {
+#pragma unroll
+      for (int i = 0; i < KH; ++i) { kstep(i, 0); kstep(i, 1); }
+    } else {
+      for (int i = 0; i < kH; ++i) { kstep(i, 0); kstep(i, 1); }
+    }
+    __syncthreads();   // every wave is done with the patch: its memory now stages the output tile
+    // ---- epilogue: accumulator element e of lane l is channel 8 (e / 4) + 4 (l / 32) + e % 4 of pixel l % 32.
+    // Each wave rounds its 32 pixels x Cout channels into its own LDS block ([pixel][Cout], 16-byte granules
+    // swizzled by pixel) and reads it back row-wise: every global store is 16 bytes per lane.
+    constexpr int ROWB = 32 * NCO * 2;          // bytes per staged pixel row
+    constexpr int GR = ROWB / 16;               // 16-byte granules per row
+    unsigned char* st = patch + wave * 32 * ROWB;
+    const int psw = (px >> 1) & (GR - 1);
+#pragma unroll
+    for (int f = 0; f < NCO; ++f)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int ch = f * 32 + q * 8 + kb * 4;
+        const float4 bb = *reinterpret_cast<const float4*>(biasl + ch);
+        const uint2 v = make_uint2(pack_bf16x2(acc[f][q * 4 + 0] + bb.x, acc[f][q * 4 + 1] + bb.y),
+                                   pack_bf16x2(acc[f][q * 4 + 2] + bb.z, acc[f][q * 4 + 3] + bb.w));
+        *reinterpret_cast<uint2*>(st + px * ROWB + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
+      }
+    // (a wave reads only what it wrote itself: no workgroup barrier needed, the LDS counter orders it)
+    constexpr int RPP = 64 / GR;                // pixel rows covered by one pass of the wave
+#pragma unroll
+    for (int pass = 0; pass < 32 / RPP; ++pass) {
+      const int r = pass * RPP + lane / GR;
+      const int g = (lane % GR) ^ ((r >> 1) & (GR - 1));
+      const uint4 v = *reinterpret_cast<const uint4*>(st + r * ROWB + ((lane % GR) << 4));
+      const int wo = wo0 + wave * 32 + r;
+      const int ch = g * 8;
+      if (wo < p.Wo && ch < p.Cout)
+        *reinterpret_cast<uint4*>(p.z + (((size_t)n * p.Ho + ho) * p.Wo + wo) * p.Cout + ch) = v;
+    }
+  }
+}
+
+// wp[co][i][j][c] (8 columns, 4 channels) = w[co][i][j][c] where it exists, else 0
+__global__ __launch_bounds__(256) void stem_pack_weights_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wp,
+                                                                int Cout, int kH, int kW, int Cin) {
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= Cout * kH * KROW) return;
+  const int c = e & 3, j = (e >> 2) & 7, t = e >> 5;   // t = co kH + i
+  wp[e] = (j < kW && c < Cin) ? w[((size_t)t * kW + j) * Cin + c] : from_f32<bf16_t>(0.f);
+}
+
+bool stem_shape(const Geom& g, int dtype) {
+  return dtype == CONVBN_BF16 && g.Cin <= 4 && g.kW <= 8 && g.kH <= 16 && g.Cout % 8 == 0 && g.Cout <= 128 && g.sw <= 4;
+}
+
+struct StemPlan { bool ok; bool x3; int nco; size_t lds; int grid; };
+StemPlan stem_plan(const Geom& g, StemParams* pp) {
+  StemPlan pl{false, false, 0, 0, 0};
+  StemParams& p = *pp;
+  p = StemParams{};
+  p.N = g.N; p.H = g.Hin; p.W = g.Win; p.Cin = g.Cin; p.Cout = g.Cout; p.kH = g.kH; p.kW = g.kW;
+  p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.Ho = g.Hout; p.Wo = g.Wout;
+  p.ntw = ceil_div(g.Wout, TPX);
+  p.ntiles = g.N * g.Hout * p.ntw;
+  p.wpitch = g.kH * KROW * 2 + 16;
+  const bool x3 = g.Cin == 3 && g.Win % 4 == 0;
+  p.pcols = (TPX - 1) * g.sw + 8;
+  if (x3) p.pcols = (p.pcols + 3 + 3) / 4 * 4;   // up to 3 leading pixels, whole groups of four
+  p.prow = p.pcols * 8;
+  pl.nco = ceil_div(g.Cout, 32);
+  if (pl.nco != 1 && pl.nco != 2 && pl.nco != 4) return pl;
+  if (g.kH * (p.pcols / (x3 ? 4 : 1)) > 256 * ppt(x3)) return pl;   // the patch is fetched in at most ppt() rounds
+  const size_t stage = (size_t)4 * 32 * 32 * pl.nco * 2;            // the output tile is staged over the patch
+  const size_t patch = (size_t)g.kH * p.prow;
+  pl.lds = 512 + (size_t)32 * pl.nco * p.wpitch + (patch > stage ? patch : stage);
+  if (pl.lds > 64 * 1024) return pl;   // two or more workgroups per CU hide each other's phases
+  const int per_cu = (int)(160 * 1024 / pl.lds) < 4 ? (int)(160 * 1024 / pl.lds) : 4;
+  pl.grid = p.ntiles < 256 * per_cu ? p.ntiles : 256 * per_cu;
+  pl.x3 = x3;
+  pl.ok = true;
+  return pl;
+}
+
+}  // namespace
+
+// 3-channel inputs whose rows are whole groups of four pixels, and 4-channel inputs, are read as they are; others
+// need a copy widened to 4 channels ([N][H][W][4]) of this many bytes (0: none)
+size_t stem_input_copy_bytes(const Geom& g) {
+  return (g.Cin == 4 || (g.Cin == 3 && g.Win % 4 == 0)) ? 0 : (size_t)g.Min * 4 * 2;
+}
+
+bool stem_fprop_supported(const Geom& g, int dtype) {
+  if (!stem_shape(g, dtype)) return false;
+  StemParams p;
+  return stem_plan(g, &p).ok;
+}
+
+size_t stem_packed_weight_bytes(const Geom& g) { return (size_t)g.Cout * g.kH * KROW * 2; }
+
+// x: the input as it is, or its 4-channel copy where stem_input_copy_bytes() != 0; w: the (folded) weight in its own
+// [Cout][kH][kW][Cin] order; wpad: stem_packed_weight_bytes() of scratch for its zero-padded copy
+hipError_t launch_fprop_stem(const Geom& g, const void* x, const void* w, void* wpad, const float* bias, void* z,
+                             hipStream_t st) {
+  StemParams p;
+  const StemPlan pl = stem_plan(g, &p);
+  if (!pl.ok) return hipErrorInvalidValue;
+  const int nel = g.Cout * g.kH * KROW;
+  hipLaunchKernelGGL(stem_pack_weights_kernel, dim3(ceil_div(nel, 256)), dim3(256), 0, st, (const bf16_t*)w,
+                     (bf16_t*)wpad, g.Cout, g.kH, g.kW, g.Cin);
+  hipError_t pe = hipGetLastError();
+  if (pe != hipSuccess) return pe;
+  p.x = (const bf16_t*)x; p.w = (const bf16_t*)wpad; p.bias = bias; p.z = (bf16_t*)z;
+#define STEM(NC, KHV, X3V)                                                                                              \
+  do {                                                                                                             \
+    static bool attr_set = false;                                                                                  \
+    if (!attr_set) {                                                                                               \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stem_fprop_kernel<NC, KHV, X3V>),          \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);                   \
+      if (e != hipSuccess) return e;                                                                               \
+      attr_set = true;                                                                                             \
+    }                                                                                                              \
+    hipLaunchKernelGGL((stem_fprop_kernel<NC, KHV, X3V>), dim3(pl.grid), dim3(256), pl.lds, st, p);                \
+  } while (0)
+  if (pl.nco == 2 && g.kH == 7 && pl.x3) STEM(2, 7, true);   // the usual 7x7 RGB stem with 64 channels: rows unrolled
+  else if (pl.x3) { if (pl.nco == 1) STEM(1, 0, true); else if (pl.nco == 2) STEM(2, 0, true); else STEM(4, 0, true); }
+  else if (pl.nco == 1) STEM(1, 0, false);
+  else if (pl.nco == 2) STEM(2, 0, false);
+  else STEM(4, 0, false);
+#undef STEM
+  return hipGetLastError();
+}
+
+}  // namespace convbn

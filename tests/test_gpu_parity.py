@@ -69,6 +69,12 @@ BF16_SHAPES = [
     # direct path (channels not multiples of 8), incl. a stem-like 7x7/2 with Cin=3
     BlockShape("b_stem", 2, 3, 32, 32, 64, 7, 2, 3, "bf16", 38),
     BlockShape("b_odd_ch", 2, 12, 9, 9, 20, 3, 1, 1, "bf16", 39),
+    # first-layer kernel: rows that are not whole groups of four pixels (4-channel copy), a 4-channel and a
+    # 1-channel input, 32 and 128 output channels, 3x3 and 5x5 windows, stride 1, two tiles per output row
+    BlockShape("b_stem_w30", 2, 3, 30, 30, 64, 7, 2, 3, "bf16", 40),
+    BlockShape("b_stem_c4", 2, 4, 24, 24, 32, 3, 1, 1, "bf16", 41),
+    BlockShape("b_stem_c1", 2, 1, 20, 28, 128, 5, 2, 2, "bf16", 42),
+    BlockShape("b_stem_wide", 1, 3, 23, 300, 64, 7, 2, 3, "bf16", 43),
 ]
 
 
