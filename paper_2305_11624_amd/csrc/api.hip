@@ -72,6 +72,10 @@ Geom padded_geom(const Geom& g) {
 
 struct WgradWay { int nsplit; int nrpart; bool fused_r; };
 WgradWay wgrad_way(const Geom& g0, int dtype) {
+  if (needs_cin_pad(g0, dtype) && stem_wgrad_supported(g0, dtype)) {   // a first layer: its own kernel
+    const int s = stem_wgrad_slices(g0);
+    return {s, s, true};
+  }
   const Geom g = needs_cin_pad(g0, dtype) ? padded_geom(g0) : g0;
   if (wgrad_tile_supported(g, dtype)) {
     const int s = wgrad_tile_splits(g);
@@ -205,6 +209,7 @@ size_t dgrad_scratch_bytes(const Geom& g, int dtype) {
 }
 size_t wgrad_scratch_bytes(const Geom& g, int dtype) {
   if (!needs_cin_pad(g, dtype)) return 0;
+  if (stem_wgrad_supported(g, dtype)) return align_up(stem_input_copy_bytes(g), 256);
   const Geom q = padded_geom(g);
   return align_up((size_t)q.Min * q.Cin * 2, 256) +
          align_up((size_t)wgrad_way(g, dtype).nsplit * q.Cout * q.K * 4, 256);
@@ -276,6 +281,11 @@ hipError_t run_wgrad(const Geom& g, int dtype, const void* x, const void* dz, fl
                      void* scratch, hipStream_t st) {
   const WgradWay way = wgrad_way(g, dtype);
   if (!needs_cin_pad(g, dtype)) return wgrad_any(g, dtype, x, dz, part, r_part, way, st);
+  if (stem_wgrad_supported(g, dtype)) {
+    if (stem_input_copy_bytes(g) == 0) return launch_wgrad_stem(g, x, dz, part, r_part, st);
+    TRY(launch_repitch(2, (size_t)g.Min, g.Cin, 4, x, scratch, st));   // a 4-channel copy of the input
+    return launch_wgrad_stem(g, scratch, dz, part, r_part, st);
+  }
   const Geom q = padded_geom(g);
   char* s = reinterpret_cast<char*>(scratch);
   void* xp = s; s += align_up((size_t)q.Min * q.Cin * 2, 256);

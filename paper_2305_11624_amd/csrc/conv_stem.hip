@@ -190,6 +190,219 @@ __global__ __launch_bounds__(256) void stem_pack_weights_kernel(const bf16_t* __
   wp[e] = (j < kW && c < Cin) ? w[((size_t)t * kW + j) * Cin + c] : from_f32<bf16_t>(0.f);
 }
 
+// ---- weight gradient of a first layer ------------------------------------------------------------------
+// dw'[co][i][j][c] = sum over output pixels of dZ[pixel][co] X[pixel's window (i, j)][c]  and  r[co] = sum dZ
+// (Sec. 3.2.1, App. B), with the same operand trick as the forward kernel: the reduced index is the pixel, so
+// both MFMA operands are read with the transposing LDS load (ds_read_tr16_b64: a lane supplies the address of 8
+// bytes -- here one padded input pixel (window column j, 4 channels) resp. 4 output channels of one pixel -- and
+// receives 4 consecutive pixels of one row of the operand).  Rows of the left operand are the 32 (j, c) pairs of
+// one window row, taken straight from the raw input patch: lane address = patch pixel (pixel sw + j).
+// A persistent workgroup walks tiles of 128 pixels of one output row; wave w owns window rows w and w + 4 for
+// all output channels and keeps their sums in registers over all its tiles; the partial sums of every workgroup
+// go to memory once, as fp32 slices for the fold-back.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ s16x4 read_tr(const unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
+}
+__device__ __forceinline__ bf16x8 join(s16x4 a, s16x4 b) {
+  s16x8 v = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+struct StemWgParams {
+  const bf16_t* x;      // X3: [N][H][W][3] (W % 4 == 0); else [N][H][W][4]
+  const bf16_t* dz;     // [N][Ho][Wo][Cout]
+  float* part;          // [slices][Cout][kH kW Cin]
+  float* r_part;        // [slices][Cout] or null
+  int N, H, W, Cin, Cout, kH, kW, sh, sw, ph, pw, Ho, Wo;
+  int ntw, ntiles, prow, pcols;
+  int zpitch;           // LDS bytes per dZ pixel row: 2 Cout + 16
+};
+
+template <int NCO, bool X3>
+__global__ __launch_bounds__(256) void stem_wgrad_kernel(StemWgParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* patch = smem;                                   // [kH][prow]
+  unsigned char* zt = smem + (p.kH * p.prow + 15) / 16 * 16;      // [TPX][zpitch]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kb = lane >> 5;
+  const int eprime = (lane & 15) >> 2;                           // pixel (of 4) this lane addresses in a transposing read
+  const int quad = ((lane >> 4) & 1) * 4 + (lane & 3);           // its 8-byte quad inside the 32-row operand block
+  constexpr int PPT = ppt(X3), PXI = X3 ? 4 : 1, NLD = X3 ? 3 : 1;
+  constexpr int NRW = 2;                                         // window rows per wave: w and w + 4 (kH <= 8)
+  constexpr int ZG = 32 * NCO * 2 / 16;                          // 16-byte granules per dZ pixel row
+  constexpr int ZPT = TPX * ZG / 256;                            // granules per thread and tile
+
+  const int icols = p.pcols / PXI;
+  const int npatch = p.kH * icols;
+  int pi[PPT], pq[PPT];
+#pragma unroll
+  for (int k = 0; k < PPT; ++k) {
+    const int e = tid + 256 * k;
+    pi[k] = e / icols;
+    pq[k] = (e - pi[k] * icols) * PXI;
+  }
+  auto patch_start = [&](int ws) {
+    const int wbase = ws * TPX * p.sw - p.pw;
+    return X3 ? (wbase >> 2) << 2 : wbase;
+  };
+  uint2 pv[PPT][NLD];
+  uint4 zv[ZPT];
+  auto fetch = [&](int tile) {
+    const int ws = tile % p.ntw;
+    const int row = tile / p.ntw;
+    const int ho = row % p.Ho, n = row / p.Ho;
+    const int wstart = patch_start(ws);
+#pragma unroll
+    for (int k = 0; k < PPT; ++k) {
+      const int h = ho * p.sh + pi[k] - p.ph, w = wstart + pq[k];
+#pragma unroll
+      for (int j = 0; j < NLD; ++j) pv[k][j] = make_uint2(0u, 0u);
+      if (tid + 256 * k < npatch && tile < p.ntiles && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W) {
+        const uint2* src = reinterpret_cast<const uint2*>(p.x + (((size_t)n * p.H + h) * p.W + w) * (X3 ? 3 : 4));
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) pv[k][j] = src[j];
+      }
+    }
+    // dZ rows of the tile's pixels (zeros past the end of the output row: such pixels then add nothing)
+#pragma unroll
+    for (int k = 0; k < ZPT; ++k) {
+      const int e = tid + 256 * k;
+      const int px = e / ZG, gq = e - px * ZG;
+      const int wo = ws * TPX + px;
+      zv[k] = make_uint4(0u, 0u, 0u, 0u);
+      if (tile < p.ntiles && wo < p.Wo && gq * 8 < p.Cout)
+        zv[k] = *reinterpret_cast<const uint4*>(p.dz + (((size_t)n * p.Ho + ho) * p.Wo + wo) * p.Cout + gq * 8);
+    }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int k = 0; k < PPT; ++k) {
+      if (tid + 256 * k >= npatch) continue;
+      unsigned char* dst = patch + pi[k] * p.prow + pq[k] * 8;
+      if constexpr (X3) {
+        const uint2 a = pv[k][0], b = pv[k][1], c = pv[k][2];
+        *reinterpret_cast<uint4*>(dst) = make_uint4(a.x, a.y & 0xffffu, (a.y >> 16) | (b.x << 16), b.x >> 16);
+        *reinterpret_cast<uint4*>(dst + 16) = make_uint4(b.y, c.x & 0xffffu, (c.x >> 16) | (c.y << 16), c.y >> 16);
+      } else {
+        *reinterpret_cast<uint2*>(dst) = pv[k][0];
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < ZPT; ++k) {
+      const int e = tid + 256 * k;
+      const int px = e / ZG, gq = e - px * ZG;
+      *reinterpret_cast<uint4*>(zt + px * p.zpitch + gq * 16) = zv[k];
+    }
+  };
+
+  f32x16 acc[NRW][NCO];
+#pragma unroll
+  for (int t = 0; t < NRW; ++t)
+#pragma unroll
+    for (int f = 0; f < NCO; ++f)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[t][f][e] = 0.f;
+  // channel sums: thread -> channel tid % Cout' (Cout' = 32 NCO), every (256 / Cout')-th pixel
+  constexpr int CW = 32 * NCO, RL = 256 / CW;
+  const int rc = tid % CW, rl = tid / CW;
+  float racc = 0.f;
+
+  fetch(blockIdx.x);
+  for (int tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x) {
+    const int ws = tile % p.ntw;
+    __syncthreads();   // the previous tile has been read
+    stash();
+    fetch(tile + gridDim.x);
+    __syncthreads();   // patch and dZ tile visible
+    const int lead = ws * TPX * p.sw - p.pw - patch_start(ws);
+#pragma unroll
+    for (int px = rl; px < TPX; px += RL)
+      racc += bf16_bits_to_f32(*reinterpret_cast<const unsigned short*>(zt + px * p.zpitch + rc * 2));
+    // lane-constant parts of the operand addresses
+    const unsigned char* zl = zt + (kb * 8 + eprime) * p.zpitch + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
+    const unsigned char* xl = patch + (((kb * 8 + eprime) * p.sw + quad + lead) * 8);
+    for (int k = 0; k < TPX / 16; ++k) {
+      bf16x8 zf[NCO];
+#pragma unroll
+      for (int f = 0; f < NCO; ++f)
+        zf[f] = join(read_tr(zl + (k * 16) * p.zpitch + f * 64), read_tr(zl + (k * 16 + 4) * p.zpitch + f * 64));
+#pragma unroll
+      for (int t = 0; t < NRW; ++t) {
+        const int i = wave + 4 * t;
+        if (i >= p.kH) break;
+        const unsigned char* xr = xl + i * p.prow + (k * 16) * p.sw * 8;
+        const bf16x8 xf = join(read_tr(xr), read_tr(xr + 4 * p.sw * 8));
+#pragma unroll
+        for (int f = 0; f < NCO; ++f) acc[t][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, zf[f], acc[t][f], 0, 0, 0);
+      }
+    }
+  }
+  // ---- this workgroup's slice.  Accumulator element e of lane l: operand row 8 (e / 4) + 4 (l / 32) + e % 4 =
+  // window column 2 (e / 4) + l / 32, channel e % 4; output channel f 32 + l % 32.
+  const int K = p.kH * p.kW * p.Cin;
+#pragma unroll
+  for (int t = 0; t < NRW; ++t) {
+    const int i = wave + 4 * t;
+    if (i >= p.kH) break;
+#pragma unroll
+    for (int f = 0; f < NCO; ++f) {
+      const int co = f * 32 + (lane & 31);
+      if (co >= p.Cout) continue;
+      float* orow = p.part + ((size_t)blockIdx.x * p.Cout + co) * K + (size_t)i * p.kW * p.Cin;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int j = 2 * q + kb;
+        if (j >= p.kW) continue;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (c < p.Cin) orow[j * p.Cin + c] = acc[t][f][q * 4 + c];
+      }
+    }
+  }
+  if (p.r_part) {
+    __syncthreads();   // every wave is done with the tiles: reuse the patch memory
+    float* red = reinterpret_cast<float*>(smem);
+    red[tid] = racc;
+    __syncthreads();
+    if (tid < CW && tid < p.Cout) {
+      float v = 0.f;
+#pragma unroll
+      for (int l = 0; l < RL; ++l) v += red[l * CW + tid];
+      p.r_part[(size_t)blockIdx.x * p.Cout + tid] = v;
+    }
+  }
+}
+
+struct StemWgPlan { bool ok; bool x3; int nco; size_t lds; int grid; };
+StemWgPlan stem_wg_plan(const Geom& g, StemWgParams* pp) {
+  StemWgPlan pl{false, false, 0, 0, 0};
+  StemWgParams& p = *pp;
+  p = StemWgParams{};
+  if (g.kH > 8) return pl;   // two window rows per wave
+  p.N = g.N; p.H = g.Hin; p.W = g.Win; p.Cin = g.Cin; p.Cout = g.Cout; p.kH = g.kH; p.kW = g.kW;
+  p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.Ho = g.Hout; p.Wo = g.Wout;
+  p.ntw = ceil_div(g.Wout, TPX);
+  p.ntiles = g.N * g.Hout * p.ntw;
+  const bool x3 = g.Cin == 3 && g.Win % 4 == 0;
+  p.pcols = (TPX - 1) * g.sw + 8;
+  if (x3) p.pcols = (p.pcols + 3 + 3) / 4 * 4;
+  p.prow = p.pcols * 8;
+  pl.nco = ceil_div(g.Cout, 32);
+  if (pl.nco != 1 && pl.nco != 2 && pl.nco != 4) return pl;
+  if (g.kH * (p.pcols / (x3 ? 4 : 1)) > 256 * ppt(x3)) return pl;
+  p.zpitch = 32 * pl.nco * 2 + 16;
+  pl.lds = align_up((size_t)g.kH * p.prow, 16) + (size_t)TPX * p.zpitch;
+  if (pl.lds < 1024) pl.lds = 1024;   // the channel sums meet in the first KB at the end
+  if (pl.lds > 64 * 1024) return pl;
+  // one workgroup per CU: every workgroup writes a full fp32 slice of dw', which the fold-back has to sum
+  pl.grid = p.ntiles < 256 ? p.ntiles : 256;
+  pl.x3 = x3;
+  pl.ok = true;
+  return pl;
+}
+
 bool stem_shape(const Geom& g, int dtype) {
   return dtype == CONVBN_BF16 && g.Cin <= 4 && g.kW <= 8 && g.kH <= 16 && g.Cout % 8 == 0 && g.Cout <= 128 && g.sw <= 4;
 }
@@ -228,6 +441,28 @@ StemPlan stem_plan(const Geom& g, StemParams* pp) {
 // need a copy widened to 4 channels ([N][H][W][4]) of this many bytes (0: none)
 size_t stem_input_copy_bytes(const Geom& g) {
   return (g.Cin == 4 || (g.Cin == 3 && g.Win % 4 == 0)) ? 0 : (size_t)g.Min * 4 * 2;
+}
+
+bool stem_wgrad_supported(const Geom& g, int dtype) {
+  if (!stem_shape(g, dtype)) return false;
+  StemWgParams p;
+  return stem_wg_plan(g, &p).ok;
+}
+int stem_wgrad_slices(const Geom& g) {
+  StemWgParams p;
+  return stem_wg_plan(g, &p).grid;
+}
+// x as for launch_fprop_stem; part [slices][Cout][K] and r_part [slices][Cout] (nullable): fp32 partial sums
+hipError_t launch_wgrad_stem(const Geom& g, const void* x, const void* dz, float* part, float* r_part, hipStream_t st) {
+  StemWgParams p;
+  const StemWgPlan pl = stem_wg_plan(g, &p);
+  if (!pl.ok) return hipErrorInvalidValue;
+  p.x = (const bf16_t*)x; p.dz = (const bf16_t*)dz; p.part = part; p.r_part = r_part;
+#define STEMWG(NC, X3V) hipLaunchKernelGGL((stem_wgrad_kernel<NC, X3V>), dim3(pl.grid), dim3(256), pl.lds, st, p)
+  if (pl.x3) { if (pl.nco == 1) STEMWG(1, true); else if (pl.nco == 2) STEMWG(2, true); else STEMWG(4, true); }
+  else { if (pl.nco == 1) STEMWG(1, false); else if (pl.nco == 2) STEMWG(2, false); else STEMWG(4, false); }
+#undef STEMWG
+  return hipGetLastError();
 }
 
 bool stem_fprop_supported(const Geom& g, int dtype) {
