@@ -186,7 +186,7 @@ def test_scale_in_the_epilogue_forward_matches_the_oracle(name):
 
 def test_scale_in_the_epilogue_forward_refuses_other_shapes():
     from paper_2305_11624_amd import binding as B
-    d = B.make_desc(2, 3, 32, 32, 64, 7, 7, 2, 3)     # the 3-channel stem runs on the generic kernels
+    d = B.make_desc(2, 3, 32, 32, 64, 7, 7, 2, 3)     # a first layer (3 input channels) has kernels of its own, without this variant
     x = torch.zeros(1 << 16, device="cuda", dtype=torch.bfloat16)
     v = torch.zeros(64, device="cuda")
     assert B.convbn_tune_fwd_scale_epilogue(d, x, x, None, v, v, v, v, x, check=False) == B.ERR_UNSUPPORTED
