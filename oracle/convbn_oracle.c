@@ -22,10 +22,10 @@
  *       fold, one convolution, six backward equations.  Present only so the
  *       test-suite can assert Tune == Eval (Sec. 3.4.1) inside the oracle.
  *
- * The same two routes exist for the TransposedConv-BN block and for the depthwise
- * ConvBN block (end of file), pinned by identities against the convolution above
- * (adjoint; block-diagonal dense weight), a library cross-check, finite
- * differences and Tune == Eval.
+ * The same two routes exist for the TransposedConv-BN block, for the depthwise
+ * ConvBN block and for the grouped ConvBN block (end of file), pinned by identities
+ * against the convolution above (adjoint; block-diagonal dense weight), a library
+ * cross-check, finite differences and Tune == Eval.
  *
  * Parity pins (tests marked "not gpu"): library conv2d+batch_norm with autograd
  * on the CPU as an independent special-case check, 1x1 == matrix product,
@@ -640,5 +640,180 @@ void cbo_dw_tune_bwd(const cb_dims *d, const double *X, const double *W, const d
     const double r = dbeta[c];
     if (db) db[c] = s * r;
     dgamma[c] = dot / sd + r * ((b ? b[c] : 0.0) - mu[c]) / sd;
+  }
+}
+
+/* ------------------------------------------------------ grouped convolution --- */
+/*
+ * Grouped ConvBN block: the channels are split into `groups` equal parts and every
+ * output channel sees only the input channels of its own part (the ResNeXt / RegNet
+ * style layers among the experiments' models, Sec. 4 and App. E).  The BatchNorm of
+ * Sec. 3.1 and the per-output-channel scale of Sec. 3.3 are unchanged; only the
+ * contraction differs.  With cg = Cin / groups and og = Cout / groups, W is
+ * [Cout][cg][kH][kW] and output channel o reads input channels (o / og) cg .. + cg - 1:
+ *   Y[n,o,ho,wo] = b[o] + sum_{q<cg,i,j} W[o,q,i,j] X[n,(o/og) cg + q, ho sh + i - ph, wo sw + j - pw]
+ */
+#define GWI(o, q, i, j) ((((size_t)(o) * cg + (q)) * d->kH + (i)) * d->kW + (j))
+
+void cbo_g_fwd(const cb_dims *d, int groups, const double *X, const double *W, const double *b, double *Y) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+  const int cg = d->Cin / groups, og = d->Cout / groups;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int o = 0; o < d->Cout; ++o)
+      for (int ho = 0; ho < Ho; ++ho)
+        for (int wo = 0; wo < Wo; ++wo) {
+          double acc = b ? b[o] : 0.0;
+          const int c0 = (o / og) * cg;
+          for (int q = 0; q < cg; ++q)
+            for (int i = 0; i < d->kH; ++i) {
+              const int h = ho * d->sh + i - d->ph;
+              if (h < 0 || h >= d->Hin) continue;
+              for (int j = 0; j < d->kW; ++j) {
+                const int w = wo * d->sw + j - d->pw;
+                if (w < 0 || w >= d->Win) continue;
+                acc += W[GWI(o, q, i, j)] * X[XI(n, c0 + q, h, w)];
+              }
+            }
+          Y[YI(n, o, ho, wo)] = acc;
+        }
+}
+
+/* dJ/dX: the transpose of the loop above (scatter form; one thread per (n, group): the
+ * input channels of a group receive contributions from that group's outputs only). */
+void cbo_g_dgrad(const cb_dims *d, int groups, const double *W, const double *dY, double *dX) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+  const int cg = d->Cin / groups, og = d->Cout / groups;
+  memset(dX, 0, sizeof(double) * (size_t)d->N * d->Cin * d->Hin * d->Win);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int g = 0; g < groups; ++g)
+      for (int oo = 0; oo < og; ++oo) {
+        const int o = g * og + oo;
+        for (int ho = 0; ho < Ho; ++ho)
+          for (int wo = 0; wo < Wo; ++wo) {
+            const double gy = dY[YI(n, o, ho, wo)];
+            for (int q = 0; q < cg; ++q)
+              for (int i = 0; i < d->kH; ++i) {
+                const int h = ho * d->sh + i - d->ph;
+                if (h < 0 || h >= d->Hin) continue;
+                for (int j = 0; j < d->kW; ++j) {
+                  const int w = wo * d->sw + j - d->pw;
+                  if (w < 0 || w >= d->Win) continue;
+                  dX[XI(n, g * cg + q, h, w)] += W[GWI(o, q, i, j)] * gy;
+                }
+              }
+          }
+      }
+}
+
+void cbo_g_wgrad(const cb_dims *d, int groups, const double *X, const double *dY, double *dW) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+  const int cg = d->Cin / groups, og = d->Cout / groups;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int o = 0; o < d->Cout; ++o)
+    for (int q = 0; q < cg; ++q)
+      for (int i = 0; i < d->kH; ++i)
+        for (int j = 0; j < d->kW; ++j) {
+          const int c = (o / og) * cg + q;
+          double acc = 0.0;
+          for (int n = 0; n < d->N; ++n)
+            for (int ho = 0; ho < Ho; ++ho) {
+              const int h = ho * d->sh + i - d->ph;
+              if (h < 0 || h >= d->Hin) continue;
+              for (int wo = 0; wo < Wo; ++wo) {
+                const int w = wo * d->sw + j - d->pw;
+                if (w < 0 || w >= d->Win) continue;
+                acc += dY[YI(n, o, ho, wo)] * X[XI(n, c, h, w)];
+              }
+            }
+          dW[GWI(o, q, i, j)] = acc;
+        }
+}
+
+/* Eval mode (the definition) and Tune mode (Sec. 3.3, Table 2 "Tune") of the grouped block. */
+void cbo_g_eval_fwd(const cb_dims *d, int groups, const double *X, const double *W, const double *b,
+                    const double *gamma, const double *beta, const double *mu, const double *var,
+                    double eps, double *Y, double *Z) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+  cbo_g_fwd(d, groups, X, W, b, Y);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int o = 0; o < d->Cout; ++o) {
+      const double sd = sqrt(var[o] + eps);
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          Z[idx] = gamma[o] * ((Y[idx] - mu[o]) / sd) + beta[o];
+        }
+    }
+}
+
+void cbo_g_eval_bwd(const cb_dims *d, int groups, const double *X, const double *W, const double *gamma,
+                    const double *mu, const double *var, double eps, const double *Y,
+                    const double *G, double *scratch_dY, double *dX, double *dW, double *db,
+                    double *dgamma, double *dbeta) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+  double *dY = scratch_dY;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < d->N; ++n)
+    for (int o = 0; o < d->Cout; ++o) {
+      const double sd = sqrt(var[o] + eps);
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          dY[idx] = gamma[o] / sd * G[idx];
+        }
+    }
+  if (dX) cbo_g_dgrad(d, groups, W, dY, dX);
+  cbo_g_wgrad(d, groups, X, dY, dW);
+  if (db) plane_sum(d, Ho, Wo, dY, NULL, db);
+#pragma omp parallel for schedule(static)
+  for (int o = 0; o < d->Cout; ++o) {
+    const double sd = sqrt(var[o] + eps);
+    double acc = 0.0;
+    for (int n = 0; n < d->N; ++n)
+      for (int h = 0; h < Ho; ++h)
+        for (int w = 0; w < Wo; ++w) {
+          const size_t idx = YI(n, o, h, w);
+          acc += G[idx] * ((Y[idx] - mu[o]) / sd);
+        }
+    dgamma[o] = acc;
+  }
+  plane_sum(d, Ho, Wo, G, NULL, dbeta);
+}
+
+void cbo_g_tune_fwd(const cb_dims *d, int groups, const double *X, const double *W, const double *b,
+                    const double *gamma, const double *beta, const double *mu, const double *var,
+                    double eps, double *Wf, double *bf, double *Z) {
+  const size_t row = (size_t)(d->Cin / groups) * d->kH * d->kW;
+  for (int o = 0; o < d->Cout; ++o) {
+    const double s = gamma[o] / sqrt(var[o] + eps);
+    for (size_t t = 0; t < row; ++t) Wf[o * row + t] = s * W[o * row + t];
+    bf[o] = ((b ? b[o] : 0.0) - mu[o]) * s + beta[o];
+  }
+  cbo_g_fwd(d, groups, X, Wf, bf, Z);
+}
+
+void cbo_g_tune_bwd(const cb_dims *d, int groups, const double *X, const double *W, const double *b,
+                    const double *gamma, const double *mu, const double *var, double eps,
+                    const double *Wf, const double *G, double *dX, double *dWf, double *dW,
+                    double *db, double *dgamma, double *dbeta) {
+  const int Ho = cbo_hout(d), Wo = cbo_wout(d);
+  const size_t row = (size_t)(d->Cin / groups) * d->kH * d->kW;
+  if (dX) cbo_g_dgrad(d, groups, Wf, G, dX);
+  cbo_g_wgrad(d, groups, X, G, dWf);
+  plane_sum(d, Ho, Wo, G, NULL, dbeta);
+  for (int o = 0; o < d->Cout; ++o) {
+    const double sd = sqrt(var[o] + eps);
+    const double s = gamma[o] / sd;
+    double dot = 0.0;
+    for (size_t t = 0; t < row; ++t) {
+      dW[o * row + t] = s * dWf[o * row + t];
+      dot += dWf[o * row + t] * W[o * row + t];
+    }
+    const double r = dbeta[o];
+    if (db) db[o] = s * r;
+    dgamma[o] = dot / sd + r * ((b ? b[o] : 0.0) - mu[o]) / sd;
   }
 }

@@ -358,3 +358,93 @@ def dw_tune_bwd(d, X, W, b, gamma, mu, var, eps, Wf, G, need_dx=True):
                             C.c_double(eps), _p(Wf), _p(G), _p(dX), _p(dWf), _p(dW), _p(db),
                             _p(dgamma), _p(dbeta))
     return dict(dX=dX, dWf=dWf, dW=dW, db=db, dgamma=dgamma, dbeta=dbeta)
+
+
+# ---- grouped ConvBN block.  W is [Cout, Cin/groups, kH, kW]; output channel o reads the input channels of
+# ---- group o // (Cout/groups). ----
+
+def _gshapes(d: Dims, groups: int):
+    assert groups >= 1 and d.Cin % groups == 0 and d.Cout % groups == 0, "groups must divide both channel counts"
+    ho, wo = out_hw(d)
+    return ((d.N, d.Cin, d.Hin, d.Win), (d.Cout, d.Cin // groups, d.kH, d.kW), (d.N, d.Cout, ho, wo), (d.Cout,))
+
+
+def g_fwd(d, groups, X, W, b=None):
+    xs, ws, ys, vs = _gshapes(d, groups)
+    X, W, b = _f64(X, xs), _f64(W, ws), _f64(b, vs)
+    Y = np.empty(ys)
+    cd = d.c()
+    _load().cbo_g_fwd(C.byref(cd), C.c_int(groups), _p(X), _p(W), _p(b), _p(Y))
+    return Y
+
+
+def g_dgrad(d, groups, W, dY):
+    xs, ws, ys, _ = _gshapes(d, groups)
+    W, dY = _f64(W, ws), _f64(dY, ys)
+    dX = np.empty(xs)
+    cd = d.c()
+    _load().cbo_g_dgrad(C.byref(cd), C.c_int(groups), _p(W), _p(dY), _p(dX))
+    return dX
+
+
+def g_wgrad(d, groups, X, dY):
+    xs, ws, ys, _ = _gshapes(d, groups)
+    X, dY = _f64(X, xs), _f64(dY, ys)
+    dW = np.empty(ws)
+    cd = d.c()
+    _load().cbo_g_wgrad(C.byref(cd), C.c_int(groups), _p(X), _p(dY), _p(dW))
+    return dW
+
+
+def g_eval_fwd(d, groups, X, W, b, gamma, beta, mu, var, eps):
+    xs, ws, ys, vs = _gshapes(d, groups)
+    X, W, b = _f64(X, xs), _f64(W, ws), _f64(b, vs)
+    gamma, beta, mu, var = (_f64(v, vs) for v in (gamma, beta, mu, var))
+    Y, Z = np.empty(ys), np.empty(ys)
+    cd = d.c()
+    _load().cbo_g_eval_fwd(C.byref(cd), C.c_int(groups), _p(X), _p(W), _p(b), _p(gamma), _p(beta), _p(mu),
+                           _p(var), C.c_double(eps), _p(Y), _p(Z))
+    return Y, Z
+
+
+def g_eval_bwd(d, groups, X, W, b, gamma, mu, var, eps, Y, G, need_dx=True):
+    xs, ws, ys, vs = _gshapes(d, groups)
+    X, W, Y, G = _f64(X, xs), _f64(W, ws), _f64(Y, ys), _f64(G, ys)
+    gamma, mu, var = (_f64(v, vs) for v in (gamma, mu, var))
+    dX = np.empty(xs) if need_dx else None
+    dW = np.empty(ws)
+    db = np.empty(vs) if b is not None else None
+    dgamma, dbeta = np.empty(vs), np.empty(vs)
+    scratch = np.empty(ys)
+    cd = d.c()
+    _load().cbo_g_eval_bwd(C.byref(cd), C.c_int(groups), _p(X), _p(W), _p(gamma), _p(mu), _p(var),
+                           C.c_double(eps), _p(Y), _p(G), _p(scratch), _p(dX), _p(dW), _p(db), _p(dgamma),
+                           _p(dbeta))
+    return dict(dX=dX, dW=dW, db=db, dgamma=dgamma, dbeta=dbeta)
+
+
+def g_tune_fwd(d, groups, X, W, b, gamma, beta, mu, var, eps):
+    xs, ws, ys, vs = _gshapes(d, groups)
+    X, W, b = _f64(X, xs), _f64(W, ws), _f64(b, vs)
+    gamma, beta, mu, var = (_f64(v, vs) for v in (gamma, beta, mu, var))
+    Wf, bf, Z = np.empty(ws), np.empty(vs), np.empty(ys)
+    cd = d.c()
+    _load().cbo_g_tune_fwd(C.byref(cd), C.c_int(groups), _p(X), _p(W), _p(b), _p(gamma), _p(beta), _p(mu),
+                           _p(var), C.c_double(eps), _p(Wf), _p(bf), _p(Z))
+    return Wf, bf, Z
+
+
+def g_tune_bwd(d, groups, X, W, b, gamma, mu, var, eps, Wf, G, need_dx=True):
+    xs, ws, ys, vs = _gshapes(d, groups)
+    X, W, Wf, G = _f64(X, xs), _f64(W, ws), _f64(Wf, ws), _f64(G, ys)
+    b = _f64(b, vs)
+    gamma, mu, var = (_f64(v, vs) for v in (gamma, mu, var))
+    dX = np.empty(xs) if need_dx else None
+    dWf, dW = np.empty(ws), np.empty(ws)
+    db = np.empty(vs) if b is not None else None
+    dgamma, dbeta = np.empty(vs), np.empty(vs)
+    cd = d.c()
+    _load().cbo_g_tune_bwd(C.byref(cd), C.c_int(groups), _p(X), _p(W), _p(b), _p(gamma), _p(mu), _p(var),
+                           C.c_double(eps), _p(Wf), _p(G), _p(dX), _p(dWf), _p(dW), _p(db), _p(dgamma),
+                           _p(dbeta))
+    return dict(dX=dX, dWf=dWf, dW=dW, db=db, dgamma=dgamma, dbeta=dbeta)
