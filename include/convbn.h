@@ -224,6 +224,39 @@ convbn_status convbn_dw_eval_bwd(const convbn_desc *desc, const void *x, const v
                                  const void *y_saved, const void *dz, void *dx, void *dW, float *db,
                                  float *dgamma, float *dbeta, void *ws, size_t ws_bytes, void *stream);
 
+/* ---- Grouped ConvBN block ----------------------------------------------------------
+ * A convolution whose channels are split into `groups` equal parts, an output channel reading only
+ * the input channels of its own part (the grouped layers of the ResNeXt / RegNet style models in
+ * Sec. 4 and App. E), followed by the frozen BatchNorm.  groups must divide Cin and Cout
+ * (CONVBN_ERR_SHAPE otherwise); with cg = Cin / groups and og = Cout / groups output channel o reads
+ * input channels (o / og) cg .. (o / og) cg + cg - 1.  The scale of Sec. 3.3 is per output channel,
+ * so Tune mode is unchanged: w'[o] = s_o w[o], b' as above, one (grouped) convolution, and Table 2's
+ * "Tune" backward with <dw'_o, w_o> summed over the cg kH kW weights of channel o.  Layout:
+ *     x, dx [N][Hin][Win][Cin]     z, dz, y [N][Hout][Wout][Cout]     W, dW [Cout][kH][kW][cg]
+ *     w_folded [cg][kH][kW][Cout]  (w' in the order the input-gradient pass reads)
+ * groups = 1 is the dense block, groups = Cin = Cout the depthwise one (each has faster calls of
+ * its own above).  Arguments, NULL rules and error behaviour as for the dense block's four calls. */
+size_t convbn_grouped_workspace_bytes(const convbn_desc *desc, int groups, int mode, int pass);
+size_t convbn_grouped_saved_bytes(const convbn_desc *desc, int groups, int mode, int refold);
+convbn_status convbn_grouped_tune_fwd(const convbn_desc *desc, int groups, const void *x, const void *W,
+                                      const float *b, const float *gamma, const float *beta,
+                                      const float *mean, const float *var, void *z, void *w_folded,
+                                      void *ws, size_t ws_bytes, void *stream);
+convbn_status convbn_grouped_tune_bwd(const convbn_desc *desc, int groups, const void *x, const void *W,
+                                      const float *b, const float *gamma, const float *mean,
+                                      const float *var, const void *w_folded, const void *dz, void *dx,
+                                      void *dW, float *db, float *dgamma, float *dbeta, void *ws,
+                                      size_t ws_bytes, void *stream);
+convbn_status convbn_grouped_eval_fwd(const convbn_desc *desc, int groups, const void *x, const void *W,
+                                      const float *b, const float *gamma, const float *beta,
+                                      const float *mean, const float *var, void *z, void *y_saved,
+                                      void *ws, size_t ws_bytes, void *stream);
+convbn_status convbn_grouped_eval_bwd(const convbn_desc *desc, int groups, const void *x, const void *W,
+                                      const float *b, const float *gamma, const float *mean,
+                                      const float *var, const void *y_saved, const void *dz, void *dx,
+                                      void *dW, float *db, float *dgamma, float *dbeta, void *ws,
+                                      size_t ws_bytes, void *stream);
+
 /* ---- The individual steps of the Tune-mode block (each is one kernel) -------------
  * convbn_tune_fwd is convbn_fold followed by convbn_conv_fprop; convbn_tune_bwd is
  * convbn_conv_dgrad, convbn_conv_wgrad and convbn_fold_back.  They are exported so that

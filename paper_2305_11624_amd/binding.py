@@ -29,7 +29,8 @@ EXPORTS = ["convbn_hout", "convbn_wout", "convbn_workspace_bytes", "convbn_saved
            "convbn_tconv_tune_fwd", "convbn_tconv_tune_bwd", "convbn_tconv_saved_bytes",
            "convbn_tconv_eval_fwd", "convbn_tconv_eval_bwd", "convbn_dw_workspace_bytes", "convbn_dw_saved_bytes",
            "convbn_dw_tune_fwd", "convbn_dw_tune_bwd", "convbn_dw_eval_fwd", "convbn_dw_eval_bwd",
-           "convbn_tune_fwd_scale_epilogue"]
+           "convbn_tune_fwd_scale_epilogue", "convbn_grouped_workspace_bytes", "convbn_grouped_saved_bytes",
+           "convbn_grouped_tune_fwd", "convbn_grouped_tune_bwd", "convbn_grouped_eval_fwd", "convbn_grouped_eval_bwd"]
 
 
 class Desc(C.Structure):
@@ -139,6 +140,13 @@ def lib():
                            ("convbn_dw_eval_fwd", L.convbn_eval_fwd), ("convbn_dw_eval_bwd", L.convbn_eval_bwd)):
             getattr(L, name).restype = C.c_int
             getattr(L, name).argtypes = like.argtypes
+        for name in ("convbn_grouped_workspace_bytes", "convbn_grouped_saved_bytes"):
+            getattr(L, name).restype = C.c_size_t
+            getattr(L, name).argtypes = [dp, C.c_int, C.c_int, C.c_int]
+        for name, like in (("convbn_grouped_tune_fwd", L.convbn_tune_fwd), ("convbn_grouped_tune_bwd", L.convbn_tune_bwd),
+                           ("convbn_grouped_eval_fwd", L.convbn_eval_fwd), ("convbn_grouped_eval_bwd", L.convbn_eval_bwd)):
+            getattr(L, name).restype = C.c_int
+            getattr(L, name).argtypes = [like.argtypes[0], C.c_int] + list(like.argtypes[1:])
         L.convbn_tune_fwd_scale_epilogue.restype = C.c_int
         L.convbn_tune_fwd_scale_epilogue.argtypes = [dp, vp, vp, fp, fp, fp, fp, fp, vp, vp]
         _lib = L
@@ -476,6 +484,56 @@ def convbn_dw_eval_bwd(desc, x, W, b, gamma, mean, var, y_saved, dz, dx, dW, db,
                        check=True):
     return _block_bwd(lib().convbn_dw_eval_bwd, desc, x, W, b, gamma, mean, var, y_saved, dz, dx, dW, db, dgamma,
                       dbeta, ws, stream, check)
+
+
+# ---- grouped block: the same calls with the number of groups after the descriptor ----
+
+def convbn_grouped_workspace_bytes(desc: Desc, groups: int, mode: int, pass_: int) -> int:
+    return int(lib().convbn_grouped_workspace_bytes(C.byref(desc), groups, mode, pass_))
+
+
+def convbn_grouped_saved_bytes(desc: Desc, groups: int, mode: int, refold: bool = False) -> int:
+    return int(lib().convbn_grouped_saved_bytes(C.byref(desc), groups, mode, int(refold)))
+
+
+def _gblock_fwd(fn, desc, groups, x, W, b, gamma, beta, mean, var, z, keep, ws, stream, check):
+    p, n = _ws(ws)
+    st = fn(C.byref(desc), groups, _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(beta), _ptr(mean), _ptr(var), _ptr(z),
+            _ptr(keep), p, n, _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def _gblock_bwd(fn, desc, groups, x, W, b, gamma, mean, var, kept, dz, dx, dW, db, dgamma, dbeta, ws, stream, check):
+    p, n = _ws(ws)
+    st = fn(C.byref(desc), groups, _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(mean), _ptr(var), _ptr(kept), _ptr(dz),
+            _ptr(dx), _ptr(dW), _ptr(db), _ptr(dgamma), _ptr(dbeta), p, n, _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_grouped_tune_fwd(desc, groups, x, W, b, gamma, beta, mean, var, z, w_folded, ws, stream=None, check=True):
+    return _gblock_fwd(lib().convbn_grouped_tune_fwd, desc, groups, x, W, b, gamma, beta, mean, var, z, w_folded, ws,
+                       stream, check)
+
+
+def convbn_grouped_tune_bwd(desc, groups, x, W, b, gamma, mean, var, w_folded, dz, dx, dW, db, dgamma, dbeta, ws,
+                            stream=None, check=True):
+    return _gblock_bwd(lib().convbn_grouped_tune_bwd, desc, groups, x, W, b, gamma, mean, var, w_folded, dz, dx, dW, db,
+                       dgamma, dbeta, ws, stream, check)
+
+
+def convbn_grouped_eval_fwd(desc, groups, x, W, b, gamma, beta, mean, var, z, y_saved, ws, stream=None, check=True):
+    return _gblock_fwd(lib().convbn_grouped_eval_fwd, desc, groups, x, W, b, gamma, beta, mean, var, z, y_saved, ws,
+                       stream, check)
+
+
+def convbn_grouped_eval_bwd(desc, groups, x, W, b, gamma, mean, var, y_saved, dz, dx, dW, db, dgamma, dbeta, ws,
+                            stream=None, check=True):
+    return _gblock_bwd(lib().convbn_grouped_eval_bwd, desc, groups, x, W, b, gamma, mean, var, y_saved, dz, dx, dW, db,
+                       dgamma, dbeta, ws, stream, check)
 
 
 # ---- channels-last device buffers (pure permutes and casts) -------------------

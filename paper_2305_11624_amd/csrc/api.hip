@@ -405,6 +405,46 @@ DwBwdWs carve_dw_bwd(const Geom& g, int dtype, int mode, void* ws) {
   return r;
 }
 
+// ---- grouped block -------------------------------------------------------------------------------------
+convbn_status make_ggeom(const convbn_desc* d, int groups, Geom* g, Geom* gf) {
+  const convbn_status s = make_geom(d, g);
+  if (s != CONVBN_OK) return s;
+  if (groups < 1 || d->Cin % groups != 0 || d->Cout % groups != 0)
+    return fail(CONVBN_ERR_SHAPE, "groups = %d must be >= 1 and divide Cin and Cout", groups);
+  // the weight as the fold and the fold-back see it: a [Cout][kH kW cg] matrix
+  *gf = *g;
+  gf->Cin = d->Cin / groups;
+  gf->K = d->kH * d->kW * gf->Cin;
+  return CONVBN_OK;
+}
+struct GFwdWs { void* w_krsc; float* bfold; size_t bytes; };
+GFwdWs carve_g_fwd(const Geom& gf, int dtype, void* ws) {
+  Carve c(ws);
+  GFwdWs r;
+  r.w_krsc = c.take((size_t)gf.Cout * gf.K * esize(dtype));
+  r.bfold = (float*)c.take((size_t)gf.Cout * 4);
+  r.bytes = c.off;
+  return r;
+}
+struct GBwdWs { void* w_crsk; void* dy; float* part; float* r_part; float* bn_part; int slices; int nrpart; int nparts; size_t bytes; };
+GBwdWs carve_g_bwd(const Geom& g, const Geom& gf, int groups, int dtype, int mode, void* ws) {
+  Carve c(ws);
+  GBwdWs r;
+  r.slices = g_wgrad_slices(g, groups, dtype);
+  r.nrpart = g_wgrad_makes_rsum(g, groups, dtype) ? r.slices : colsum_parts(g);
+  r.nparts = bn_bwd_parts(g);
+  r.w_crsk = c.take((size_t)gf.Cout * gf.K * esize(dtype));
+  r.part = (float*)c.take((size_t)r.slices * gf.Cout * gf.K * 4);
+  r.r_part = (float*)c.take((size_t)r.nrpart * g.Cout * 4);
+  r.dy = nullptr; r.bn_part = nullptr;
+  if (mode == CONVBN_MODE_EVAL) {
+    r.dy = c.take((size_t)g.M * g.Cout * esize(dtype));
+    r.bn_part = (float*)c.take((size_t)r.nparts * 2 * g.Cout * 4);
+  }
+  r.bytes = c.off;
+  return r;
+}
+
 }  // namespace
 
 extern "C" {
@@ -834,6 +874,136 @@ convbn_status convbn_dw_eval_bwd(const convbn_desc* desc, const void* x, const v
   LAUNCH(launch_dw_wgrad(g, dt, x, w.dy, w.part, nullptr, st));
   LAUNCH(launch_dw_fold_back(g, dt, w.part, nullptr, w.slices, w.sums, W, nullptr, nullptr, nullptr, nullptr, dW,
                              nullptr, nullptr, nullptr, st));
+  return CONVBN_OK;
+}
+
+size_t convbn_grouped_workspace_bytes(const convbn_desc* desc, int groups, int mode, int pass) {
+  Geom g, gf;
+  if (make_ggeom(desc, groups, &g, &gf) != CONVBN_OK) return 0;
+  if (mode != CONVBN_MODE_TUNE && mode != CONVBN_MODE_EVAL) return 0;
+  return pass == CONVBN_PASS_FWD ? carve_g_fwd(gf, desc->dtype, nullptr).bytes
+                                 : carve_g_bwd(g, gf, groups, desc->dtype, mode, nullptr).bytes;
+}
+
+size_t convbn_grouped_saved_bytes(const convbn_desc* desc, int groups, int mode, int refold) {
+  Geom g, gf;
+  if (make_ggeom(desc, groups, &g, &gf) != CONVBN_OK) return 0;
+  if (mode == CONVBN_MODE_EVAL) return (size_t)g.M * g.Cout * esize(desc->dtype);
+  return refold ? 0 : (size_t)gf.Cout * gf.K * esize(desc->dtype);
+}
+
+convbn_status convbn_grouped_tune_fwd(const convbn_desc* desc, int groups, const void* x, const void* W,
+                                      const float* b, const float* gamma, const float* beta, const float* mean,
+                                      const float* var, void* z, void* w_folded, void* ws, size_t ws_bytes,
+                                      void* stream) {
+  Geom g, gf;
+  convbn_status s = make_ggeom(desc, groups, &g, &gf);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(beta); REQUIRE_PTR(mean);
+  REQUIRE_PTR(var); REQUIRE_PTR(z);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(w_folded);
+  const int dt = desc->dtype;
+  s = check_ws(carve_g_fwd(gf, dt, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const GFwdWs w = carve_g_fwd(gf, dt, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // w' = s w in both orders ([Cout][taps][cg] for this pass, [cg][taps][Cout] kept for backward), b'
+  LAUNCH(launch_fold(gf, dt, W, b, gamma, beta, mean, var, 0, w.w_krsc, w_folded, w.bfold, st));
+  LAUNCH(launch_g_fprop(g, groups, dt, x, w.w_krsc, w.bfold, z, st));              // Z = w' (*) X + b'
+  return CONVBN_OK;
+}
+
+convbn_status convbn_grouped_tune_bwd(const convbn_desc* desc, int groups, const void* x, const void* W,
+                                      const float* b, const float* gamma, const float* mean, const float* var,
+                                      const void* w_folded, const void* dz, void* dx, void* dW, float* db,
+                                      float* dgamma, float* dbeta, void* ws, size_t ws_bytes, void* stream) {
+  Geom g, gf;
+  convbn_status s = make_ggeom(desc, groups, &g, &gf);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
+  REQUIRE_PTR(dz);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(w_folded); OPTIONAL_PTR(dx); OPTIONAL_PTR(db);
+  OPTIONAL_PTR(dW); OPTIONAL_PTR(dgamma); OPTIONAL_PTR(dbeta);
+  const bool params = dW != nullptr;
+  if (!params && (dgamma || dbeta || db || !dx))
+    return fail(CONVBN_ERR_NULL, "without dW only dx may be asked for (dgamma, dbeta, db NULL, dx given)");
+  if (params && (!dgamma || !dbeta))
+    return fail(CONVBN_ERR_NULL, "dgamma and dbeta are required together with dW");
+  if (params && (b == nullptr) != (db == nullptr))
+    return fail(CONVBN_ERR_NULL, "db must be given exactly when b is given");
+  const int dt = desc->dtype;
+  s = check_ws(carve_g_bwd(g, gf, groups, dt, CONVBN_MODE_TUNE, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const GBwdWs w = carve_g_bwd(g, gf, groups, dt, CONVBN_MODE_TUNE, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (dx) {
+    const void* wf = w_folded;
+    if (!wf) {   // not kept: fold again (Sec. 3.3 recomputes w' from the parameters)
+      LAUNCH(launch_fold(gf, dt, W, b, gamma, nullptr, mean, var, 0, nullptr, w.w_crsk, nullptr, st));
+      wf = w.w_crsk;
+    }
+    LAUNCH(launch_g_dgrad(g, groups, dt, dz, wf, dx, st));                          // dX = w'_rot (*) dZ
+  }
+  if (!params) return CONVBN_OK;
+  const bool own_r = g_wgrad_makes_rsum(g, groups, dt);
+  LAUNCH(launch_g_wgrad(g, groups, dt, x, dz, w.part, own_r ? w.r_part : nullptr, st));   // dw' = dZ (.) X
+  if (!own_r) LAUNCH(launch_colsum(g, dt, dz, w.r_part, st));                              // r = sum dZ
+  LAUNCH(launch_fold_back(gf, dt, w.part, w.slices, w.r_part, w.nrpart, W, b, gamma, mean, var, 0, dW, db, dgamma,
+                          dbeta, st));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_grouped_eval_fwd(const convbn_desc* desc, int groups, const void* x, const void* W,
+                                      const float* b, const float* gamma, const float* beta, const float* mean,
+                                      const float* var, void* z, void* y_saved, void* ws, size_t ws_bytes,
+                                      void* stream) {
+  Geom g, gf;
+  convbn_status s = make_ggeom(desc, groups, &g, &gf);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(beta); REQUIRE_PTR(mean);
+  REQUIRE_PTR(var); REQUIRE_PTR(z); REQUIRE_PTR(y_saved);
+  OPTIONAL_PTR(b);
+  const int dt = desc->dtype;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  (void)ws; (void)ws_bytes;
+  LAUNCH(launch_g_fprop(g, groups, dt, x, W, b, y_saved, st));                        // Y = w (*) X + b
+  LAUNCH(launch_bn_affine_fwd(g, dt, y_saved, gamma, beta, mean, var, z, st));        // Z from Y
+  return CONVBN_OK;
+}
+
+convbn_status convbn_grouped_eval_bwd(const convbn_desc* desc, int groups, const void* x, const void* W,
+                                      const float* b, const float* gamma, const float* mean, const float* var,
+                                      const void* y_saved, const void* dz, void* dx, void* dW, float* db,
+                                      float* dgamma, float* dbeta, void* ws, size_t ws_bytes, void* stream) {
+  Geom g, gf;
+  convbn_status s = make_ggeom(desc, groups, &g, &gf);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
+  REQUIRE_PTR(y_saved); REQUIRE_PTR(dz);
+  OPTIONAL_PTR(b); OPTIONAL_PTR(dx); OPTIONAL_PTR(db);
+  OPTIONAL_PTR(dW); OPTIONAL_PTR(dgamma); OPTIONAL_PTR(dbeta);
+  const bool params = dW != nullptr;
+  if (!params && (dgamma || dbeta || db || !dx))
+    return fail(CONVBN_ERR_NULL, "without dW only dx may be asked for (dgamma, dbeta, db NULL, dx given)");
+  if (params && (!dgamma || !dbeta))
+    return fail(CONVBN_ERR_NULL, "dgamma and dbeta are required together with dW");
+  if (params && (b == nullptr) != (db == nullptr))
+    return fail(CONVBN_ERR_NULL, "db must be given exactly when b is given");
+  const int dt = desc->dtype;
+  s = check_ws(carve_g_bwd(g, gf, groups, dt, CONVBN_MODE_EVAL, nullptr).bytes, ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  const GBwdWs w = carve_g_bwd(g, gf, groups, dt, CONVBN_MODE_EVAL, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  LAUNCH(launch_bn_bwd(g, dt, dz, y_saved, gamma, mean, var, w.dy, w.bn_part, st));   // dY = s dZ, sums for dgamma, dbeta
+  if (params) LAUNCH(launch_bn_bwd_finalize(g, w.bn_part, w.nparts, gamma, var, dgamma, dbeta, db, st));
+  if (dx) {
+    LAUNCH(launch_fold(gf, dt, W, nullptr, nullptr, nullptr, nullptr, nullptr, 1, nullptr, w.w_crsk, nullptr, st));
+    LAUNCH(launch_g_dgrad(g, groups, dt, w.dy, w.w_crsk, dx, st));
+  }
+  if (!params) return CONVBN_OK;
+  LAUNCH(launch_g_wgrad(g, groups, dt, x, w.dy, w.part, nullptr, st));
+  LAUNCH(launch_fold_back(gf, dt, w.part, w.slices, nullptr, 0, W, nullptr, nullptr, nullptr, nullptr, 1, dW, nullptr,
+                          nullptr, nullptr, st));
   return CONVBN_OK;
 }
 

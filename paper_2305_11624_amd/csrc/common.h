@@ -137,6 +137,18 @@ hipError_t launch_dw_fold_back(const Geom& g, int dtype, const float* part, cons
                                float* sums, const void* W, const float* b, const float* gamma, const float* mean,
                                const float* var, void* dW, float* db, float* dgamma, float* dbeta, hipStream_t st);
 
+// conv_grouped.hip : the three contractions of a grouped block (groups divides g.Cin and g.Cout; cg = Cin / groups).
+// w_krsc is [Cout][kH][kW][cg], w_crsk [cg][kH][kW][Cout]; part [slices][Cout][kH kW cg] fp32.  Where
+// g_wgrad_makes_rsum() the weight-gradient launch also writes r_part [slices][Cout] (else it ignores it).
+hipError_t launch_g_fprop(const Geom& g, int groups, int dtype, const void* x, const void* w_krsc, const float* bias,
+                          void* z, hipStream_t st);
+hipError_t launch_g_dgrad(const Geom& g, int groups, int dtype, const void* dz, const void* w_crsk, void* dx,
+                          hipStream_t st);
+int g_wgrad_slices(const Geom& g, int groups, int dtype);
+bool g_wgrad_makes_rsum(const Geom& g, int groups, int dtype);
+hipError_t launch_g_wgrad(const Geom& g, int groups, int dtype, const void* x, const void* dz, float* part,
+                          float* r_part, hipStream_t st);
+
 // conv_direct.hip : one thread per output element, fp32 accumulation (any shape, both dtypes)
 hipError_t launch_fprop_direct(const Geom& g, int dtype, const void* x, const void* w_krsc,
                                const float* bias, void* z, hipStream_t st);

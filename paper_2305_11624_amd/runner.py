@@ -241,3 +241,80 @@ class DepthwiseRun:
             Wf=f(self.w_folded).permute(2, 0, 1).reshape(s.Cout, 1, s.k, s.k).contiguous()
             if self.w_folded is not None else None,
             Y=B.act_from_device(self.y_saved) if self.y_saved is not None else None)
+
+
+class GroupedRun:
+    """One grouped ConvBN block on the GPU in `mode` ("tune" or "eval"; inputs from synth.make_grouped_inputs)."""
+
+    def __init__(self, inp: Dict[str, object], mode: str = "tune", keep_folded: bool = True, need_dx: bool = True,
+                 params: bool = True, device: str = "cuda", poison: bool = False):
+        assert mode in ("tune", "eval")
+        s = inp["shape"]
+        self.groups = G = int(inp["groups"])
+        self.shape, self.mode, self.keep_folded = s, mode, keep_folded
+        self.desc = B.desc_from_shape(s, eps=inp["eps"])
+        dt = B.torch_dtype(self.desc)
+        self.dt = dt
+        cg = s.Cin // G
+        self.x = B.act_to_device(inp["x"], dt, device)
+        self.W = B.weight_to_device(inp["W"], dt, device)              # [Cout, cg, k, k] -> [Cout][k][k][cg]
+        self.dz = B.act_to_device(inp["dy"], dt, device)
+        self.b = B.vec_to_device(inp["b"], device)
+        self.gamma, self.beta = B.vec_to_device(inp["gamma"], device), B.vec_to_device(inp["beta"], device)
+        self.mean, self.var = B.vec_to_device(inp["rmean"], device), B.vec_to_device(inp["rvar"], device)
+
+        def out(shape, dtype):
+            t = torch.empty(shape, dtype=dtype, device=device)
+            if poison:
+                t.fill_(float("nan"))
+            return t
+
+        self.z = out((s.N, s.Hout, s.Wout, s.Cout), dt)
+        self.dx = out((s.N, s.Hin, s.Win, s.Cin), dt) if need_dx else None
+        self.dW = out((s.Cout, s.k, s.k, cg), dt) if params else None
+        self.db = out((s.Cout,), torch.float32) if (self.b is not None and params) else None
+        self.dgamma = out((s.Cout,), torch.float32) if params else None
+        self.dbeta = out((s.Cout,), torch.float32) if params else None
+        m = B.MODE_TUNE if mode == "tune" else B.MODE_EVAL
+        self.ws_fwd = BlockRun._ws(B.convbn_grouped_workspace_bytes(self.desc, G, m, B.PASS_FWD), device)
+        self.ws_bwd = BlockRun._ws(B.convbn_grouped_workspace_bytes(self.desc, G, m, B.PASS_BWD), device)
+        self.w_folded = out((cg, s.k, s.k, s.Cout), dt) if (keep_folded and mode == "tune") else None
+        self.y_saved = out((s.N, s.Hout, s.Wout, s.Cout), dt) if mode == "eval" else None
+
+    def saved_bytes(self) -> int:
+        m = B.MODE_TUNE if self.mode == "tune" else B.MODE_EVAL
+        return B.convbn_grouped_saved_bytes(self.desc, self.groups, m, not self.keep_folded)
+
+    def forward(self, stream=None):
+        if self.mode == "tune":
+            B.convbn_grouped_tune_fwd(self.desc, self.groups, self.x, self.W, self.b, self.gamma, self.beta, self.mean,
+                                      self.var, self.z, self.w_folded, self.ws_fwd, stream)
+        else:
+            B.convbn_grouped_eval_fwd(self.desc, self.groups, self.x, self.W, self.b, self.gamma, self.beta, self.mean,
+                                      self.var, self.z, self.y_saved, self.ws_fwd, stream)
+
+    def backward(self, stream=None):
+        if self.mode == "tune":
+            B.convbn_grouped_tune_bwd(self.desc, self.groups, self.x, self.W, self.b, self.gamma, self.mean, self.var,
+                                      self.w_folded, self.dz, self.dx, self.dW, self.db, self.dgamma, self.dbeta,
+                                      self.ws_bwd, stream)
+        else:
+            B.convbn_grouped_eval_bwd(self.desc, self.groups, self.x, self.W, self.b, self.gamma, self.mean, self.var,
+                                      self.y_saved, self.dz, self.dx, self.dW, self.db, self.dgamma, self.dbeta,
+                                      self.ws_bwd, stream)
+
+    def step(self, stream=None):
+        self.forward(stream)
+        self.backward(stream)
+
+    def results(self) -> Dict[str, Optional[torch.Tensor]]:
+        torch.cuda.synchronize()
+        f = lambda t: None if t is None else t.detach().to("cpu", torch.float64)
+        return dict(
+            Z=B.act_from_device(self.z),
+            dX=B.act_from_device(self.dx) if self.dx is not None else None,
+            dW=B.weight_from_device(self.dW) if self.dW is not None else None,
+            db=f(self.db), dgamma=f(self.dgamma), dbeta=f(self.dbeta),
+            # [cg][kH][kW][Cout] -> logical [Cout, cg, kH, kW]
+            Wf=f(self.w_folded).permute(3, 0, 1, 2).contiguous() if self.w_folded is not None else None,
+            Y=B.act_from_device(self.y_saved) if self.y_saved is not None else None)

@@ -187,6 +187,36 @@ def make_dw_inputs(shape: BlockShape, seed: Optional[int] = None, bias: bool = F
                 eps=eps)
 
 
+def make_grouped_inputs(shape: BlockShape, groups: int, seed: Optional[int] = None, bias: bool = False,
+                        wide_scale: bool = False, batch: Optional[int] = None) -> Dict[str, object]:
+    """Tensors of a grouped ConvBN block (`groups` divides Cin and Cout): W is the logical
+    [Cout, Cin/groups, k, k] ~ N(0, 2 / fan-in) with fan-in (Cin/groups) k^2; everything else as make_inputs."""
+    if batch is not None:
+        shape = replace(shape, N=batch)
+    assert shape.Cin % groups == 0 and shape.Cout % groups == 0
+    g = torch.Generator(device="cpu")
+    g.manual_seed(shape.seed if seed is None else seed)
+    s = shape
+    cg = s.Cin // groups
+    x = torch.randn(s.N, s.Cin, s.Hin, s.Win, generator=g)
+    W = torch.randn(s.Cout, cg, s.k, s.k, generator=g) * (2.0 / (cg * s.k * s.k)) ** 0.5
+    gamma = torch.rand(s.Cout, generator=g) + 0.5
+    beta = torch.randn(s.Cout, generator=g) * 0.1
+    rmean = torch.randn(s.Cout, generator=g) * 0.1
+    rvar = torch.rand(s.Cout, generator=g) * 1.5 + 0.5
+    dy = torch.randn(s.N, s.Cout, s.Hout, s.Wout, generator=g)
+    b = torch.randn(s.Cout, generator=g) * 0.1 if bias else None
+    eps = 1e-5
+    if wide_scale:
+        scale = torch.rand(s.Cout, generator=g) * 30.0
+        scale[:: max(1, s.Cout // 4)] = 0.0
+        gamma = scale * torch.sqrt(rvar + eps)
+    if s.dtype == "bf16":
+        x, W, dy = round_bf16(x), round_bf16(W), round_bf16(dy)
+    return dict(shape=s, groups=groups, x=x, W=W, b=b, gamma=gamma, beta=beta, rmean=rmean, rvar=rvar, dy=dy,
+                eps=eps)
+
+
 def make_params(shape: BlockShape, seed: Optional[int] = None) -> Dict[str, object]:
     """Only the parameters of a block (same distributions and draw order as make_inputs, but
     without the activation-sized tensors): W, gamma, beta, running mean, running var."""

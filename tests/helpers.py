@@ -55,6 +55,19 @@ def oracle_dw_block(inp, need_dx=True):
     return g
 
 
+def oracle_grouped_block(inp, need_dx=True):
+    """Eval-mode definition of the grouped ConvBN block in fp64 (plus the folded weight of its Tune route)."""
+    d, G = dims_of(inp["shape"]), inp["groups"]
+    a = {k: _np(inp[k]) for k in ("x", "W", "b", "gamma", "beta", "rmean", "rvar", "dy")}
+    Y, Z = oracle.g_eval_fwd(d, G, a["x"], a["W"], a["b"], a["gamma"], a["beta"], a["rmean"], a["rvar"], inp["eps"])
+    g = oracle.g_eval_bwd(d, G, a["x"], a["W"], a["b"], a["gamma"], a["rmean"], a["rvar"], inp["eps"], Y, a["dy"],
+                          need_dx=need_dx)
+    Wf, bf, _ = oracle.g_tune_fwd(d, G, a["x"], a["W"], a["b"], a["gamma"], a["beta"], a["rmean"], a["rvar"],
+                                  inp["eps"])
+    g.update(Y=Y, Z=Z, Wf=Wf, bf=bf)
+    return g
+
+
 def rel_err(got, ref):
     got = got.numpy() if hasattr(got, "numpy") else np.asarray(got)
     assert got.shape == ref.shape, (got.shape, ref.shape)

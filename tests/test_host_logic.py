@@ -188,3 +188,37 @@ def test_depthwise_block_queries_and_validation():
     assert bwd(ok, ok, None, None, ok) == B.ERR_NULL         # dgamma missing
     assert bwd(None, None, None, None, None) == B.ERR_NULL   # nothing asked for
     assert L.convbn_dw_eval_fwd(C.byref(d), ok, ok, None, ok, ok, ok, ok, ok, None, ok, need, None) == B.ERR_NULL   # y_saved
+
+
+def test_grouped_block_queries_and_validation():
+    """Workspace / saved-bytes queries and host-side argument checks of the grouped entry points."""
+    d = B.make_desc(32, 128, 56, 56, 128, 3, 3, 1, 1)
+    T, E = B.MODE_TUNE, B.MODE_EVAL
+    G = 32
+    for m in (T, E):
+        for p in (B.PASS_FWD, B.PASS_BWD):
+            assert B.convbn_grouped_workspace_bytes(d, G, m, p) % 256 == 0 and B.convbn_grouped_workspace_bytes(d, G, m, p) > 0
+    assert B.convbn_grouped_workspace_bytes(d, G, E, B.PASS_BWD) >= 32 * 56 * 56 * 128 * 2      # dY
+    assert B.convbn_grouped_saved_bytes(d, G, E) == 32 * 56 * 56 * 128 * 2                      # Y
+    assert B.convbn_grouped_saved_bytes(d, G, T) == 128 * 9 * 4 * 2 and B.convbn_grouped_saved_bytes(d, G, T, True) == 0
+    assert B.convbn_grouped_saved_bytes(d, 1, T) == B.convbn_saved_bytes(d, T)                  # one group: the dense block
+    for bad_g in (0, -1, 3, 256):
+        assert B.convbn_grouped_workspace_bytes(d, bad_g, T, B.PASS_FWD) == 0 and B.convbn_grouped_saved_bytes(d, bad_g, T) == 0
+    L = B.lib()
+    ok = C.c_void_p(4096)
+    need = B.convbn_grouped_workspace_bytes(d, G, T, B.PASS_FWD)
+    fwd = lambda desc, g=G, x=ok, ws=ok, n=need: L.convbn_grouped_tune_fwd(desc, g, x, ok, None, ok, ok, ok, ok, ok, None,
+                                                                         ws, n, None)
+    assert fwd(C.byref(d), g=3) == B.ERR_SHAPE
+    assert fwd(None) == B.ERR_NULL
+    assert fwd(C.byref(d), x=None) == B.ERR_NULL
+    assert fwd(C.byref(d), x=C.c_void_p(4100)) == B.ERR_UNSUPPORTED
+    assert fwd(C.byref(d), ws=None, n=0) == B.ERR_WORKSPACE
+    assert fwd(C.byref(d), n=need - 1) == B.ERR_WORKSPACE
+    needb = B.convbn_grouped_workspace_bytes(d, G, T, B.PASS_BWD)
+    bwd = lambda dx, dW, db, dg, dbt: L.convbn_grouped_tune_bwd(C.byref(d), G, ok, ok, None, ok, ok, ok, None, ok, dx, dW,
+                                                               db, dg, dbt, ok, needb, None)
+    assert bwd(ok, ok, ok, ok, ok) == B.ERR_NULL             # db given without b
+    assert bwd(ok, ok, None, None, ok) == B.ERR_NULL         # dgamma missing
+    assert bwd(None, None, None, None, None) == B.ERR_NULL   # nothing asked for
+    assert L.convbn_grouped_eval_fwd(C.byref(d), G, ok, ok, None, ok, ok, ok, ok, ok, None, ok, need, None) == B.ERR_NULL   # y_saved
