@@ -34,12 +34,19 @@ WORKLOADS = {
     "resnet50": [],          # the whole 53-block backbone, Tune vs Eval (time and activation memory)
     "tconv": [],             # TransposedConv-BN up-sampling blocks in Tune mode
     "depthwise": [],         # depthwise ConvBN blocks in Tune mode (memory-bound)
+    "grouped": [],           # grouped ConvBN blocks in Tune mode (memory-bound)
 }
 
 # depthwise 3x3 layers of an inverted-residual network at N = 32 (stand-ins for the mobile-network rows of the
 # paper's model tables): name, N, C, H, W, window, stride, padding
 DW_SHAPES = [("dw_112_s2", 32, 96, 112, 112, 3, 2, 1), ("dw_56", 32, 144, 56, 56, 3, 1, 1),
              ("dw_14", 32, 576, 14, 14, 3, 1, 1)]
+
+# grouped 3x3 layers of an aggregated-transform network (32 groups of 4, 8, 16, 32 channels in its four stages) at
+# N = 32 (stand-ins for the ResNeXt / RegNet rows of the paper's model tables): name, N, C, H, W, window, stride,
+# padding, groups
+GROUPED_SHAPES = [("gx_56", 32, 128, 56, 56, 3, 1, 1, 32), ("gx_28", 32, 256, 28, 28, 3, 1, 1, 32),
+                  ("gx_14", 32, 512, 14, 14, 3, 1, 1, 32), ("gx_7", 32, 1024, 7, 7, 3, 1, 1, 32)]
 
 # 2x up-sampling blocks of an encoder-decoder network (stand-ins for the UNet rows of Sec. 4.3): name, N, Cin, Hin,
 # Win, Cout, window, stride, padding
@@ -418,24 +425,35 @@ def main_tconv(a):
     print(json.dumps(line))
 
 
-def main_depthwise(a):
-    """Depthwise ConvBN blocks in Tune mode.  They are bound by memory traffic, so the figure of merit is the
-    algorithmic bytes of a step (x read by the forward pass and the weight gradient, z written, dz read by both
-    gradient passes, dx written: 3 A_x + 3 A_z elements) over its time, against the HBM peak."""
+def main_depthwise(a, kind="depthwise"):
+    """Depthwise (or, kind = "grouped", grouped) ConvBN blocks in Tune mode.  With at most 2 k^2 cg FLOP per output
+    element they are bound by memory traffic, so the figure of merit is the algorithmic bytes of a step (x read by the
+    forward pass and the weight gradient, z written, dz read by both gradient passes, dx written: 3 A_x + 3 A_z
+    elements) over its time, against the HBM peak."""
     import torch
     import oracle
     from paper_2305_11624_amd import binding as B
     from paper_2305_11624_amd import synth
-    from paper_2305_11624_amd.runner import DepthwiseRun
+    from paper_2305_11624_amd.runner import DepthwiseRun, GroupedRun
     B.lib()
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    shapes = [synth.BlockShape(n, N, c, h, w, c, k, st, pd, "bf16", 110 + i)
-              for i, (n, N, c, h, w, k, st, pd) in enumerate(DW_SHAPES)]
-    inputs = [synth.make_dw_inputs(s) for s in shapes]
+    grouped = kind == "grouped"
+    if grouped:
+        shapes = [synth.BlockShape(n, N, c, h, w, c, k, st, pd, "bf16", 130 + i)
+                  for i, (n, N, c, h, w, k, st, pd, _) in enumerate(GROUPED_SHAPES)]
+        groups = [t[-1] for t in GROUPED_SHAPES]
+        inputs = [synth.make_grouped_inputs(s, g) for s, g in zip(shapes, groups)]
+        DepthwiseRun = GroupedRun
+    else:
+        shapes = [synth.BlockShape(n, N, c, h, w, c, k, st, pd, "bf16", 110 + i)
+                  for i, (n, N, c, h, w, k, st, pd) in enumerate(DW_SHAPES)]
+        groups = [s.Cin for s in shapes]
+        inputs = [synth.make_dw_inputs(s) for s in shapes]
     step_bytes = [2.0 * (3 * s.A_x + 3 * s.A_z) for s in shapes]
+    step_flop = [3.0 * 2.0 * s.A_z * s.k * s.k * (s.Cin // g) for s, g in zip(shapes, groups)]
 
     def pools_of(mode, **kw):
         out = []
@@ -482,13 +500,15 @@ def main_depthwise(a):
         torch.cuda.empty_cache()
     achieved = best[3] / (best[2] * 1e-3) / 1e9
     line = {
-        "metric": "Depthwise ConvBN Tune fwd+bwd GB/s (algorithmic bytes)", "value": sum(step_bytes) / (ms * 1e-3) / 1e9,
+        "metric": ("Grouped" if grouped else "Depthwise") + " ConvBN Tune fwd+bwd GB/s (algorithmic bytes)", "value": sum(step_bytes) / (ms * 1e-3) / 1e9,
         "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "depthwise ConvBN blocks, bf16: " + ", ".join(
-            f"{s.name} x[{s.N},{s.Cin},{s.Hin},{s.Win}] {s.k}x{s.k} s{s.stride} p{s.pad}" for s in shapes),
+        "config": {"workload": kind + " ConvBN blocks, bf16: " + ", ".join(
+            f"{s.name} x[{s.N},{s.Cin},{s.Hin},{s.Win}] {s.k}x{s.k} s{s.stride} p{s.pad}" + (f" groups {g}" if grouped else "")
+            for s, g in zip(shapes, groups)),
             "mode": "tune", "layout": "NHWC", "step": "fwd+bwd of every shape"},
         "pct_of_hbm_peak": 100.0 * sum(step_bytes) / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "useful_tflops": sum(step_flop) / (ms * 1e-3) / 1e12,
         "eval_ms_per_step": ms_eval, "tune_speedup_vs_eval": (ms_eval / ms) if ms_eval else None,
         "saved_activation_mb": {"tune": saved_tune / 1e6, "eval": saved_eval / 1e6 if saved_eval is not None else None},
         "per_shape": per_shape,
@@ -498,16 +518,19 @@ def main_depthwise(a):
     if not a.no_cpu_baseline:
         cores = oracle.num_threads()
         nb, secs, desc = 0.0, 0.0, []
-        for s, b1 in zip(shapes, step_bytes):
-            flop1 = 3.0 * 2.0 * s.A_z * s.k * s.k
+        for s, b1, flop1, g in zip(shapes, step_bytes, step_flop, groups):
             n = int(max(1, min(s.N, a.cpu_seconds / len(shapes) * 0.3e9 * cores / (flop1 / s.N))))
-            inp = synth.make_dw_inputs(replace(s, N=n))
+            inp = synth.make_grouped_inputs(replace(s, N=n), g) if grouped else synth.make_dw_inputs(replace(s, N=n))
             d = oracle.Dims(n, s.Cin, s.Hin, s.Win, s.Cout, s.k, s.k, s.stride, s.stride, s.pad, s.pad)
             f = lambda t: None if t is None else t.double().numpy()
             v = {k: f(inp[k]) for k in ("x", "W", "b", "gamma", "beta", "rmean", "rvar", "dy")}
             t0 = time.perf_counter()
-            Y, _ = oracle.dw_eval_fwd(d, v["x"], v["W"], v["b"], v["gamma"], v["beta"], v["rmean"], v["rvar"], inp["eps"])
-            oracle.dw_eval_bwd(d, v["x"], v["W"], v["b"], v["gamma"], v["rmean"], v["rvar"], inp["eps"], Y, v["dy"])
+            if grouped:
+                Y, _ = oracle.g_eval_fwd(d, g, v["x"], v["W"], v["b"], v["gamma"], v["beta"], v["rmean"], v["rvar"], inp["eps"])
+                oracle.g_eval_bwd(d, g, v["x"], v["W"], v["b"], v["gamma"], v["rmean"], v["rvar"], inp["eps"], Y, v["dy"])
+            else:
+                Y, _ = oracle.dw_eval_fwd(d, v["x"], v["W"], v["b"], v["gamma"], v["beta"], v["rmean"], v["rvar"], inp["eps"])
+                oracle.dw_eval_bwd(d, v["x"], v["W"], v["b"], v["gamma"], v["rmean"], v["rvar"], inp["eps"], Y, v["dy"])
             secs += time.perf_counter() - t0
             nb += b1 * n / s.N
             desc.append(f"{s.name} with N={n} of {s.N}")
@@ -528,6 +551,8 @@ def main():
         return main_tconv(a)
     if a.workload == "depthwise":
         return main_depthwise(a)
+    if a.workload == "grouped":
+        return main_depthwise(a, kind="grouped")
     import torch
     from paper_2305_11624_amd import binding as B
     from paper_2305_11624_amd import synth
