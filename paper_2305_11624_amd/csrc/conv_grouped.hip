@@ -297,7 +297,7 @@ GcPlan gc_plan(int N, int C, int cg, int in_h, int in_w, int out_h, int out_w, i
       const double work = ((double)(ntr - 1) * rounds(TR) + rounds(last)) * (nchunks / nch);   // wave rounds per image column
       const double fetched = (double)ntr * PR / ((double)out_h * sh);                          // rows fetched / rows there are
       const double score = 1.0 / (work * (1.0 + 0.3 * (fetched - 1.0)));
-      if (score > best) {
+      if (score >= best) {   // ties: more channels per workgroup (longer contiguous loads)
         best = score;
         p.nch = nch; p.TR = TR; p.ntr = ntr; p.PR = PR; p.pitch = pitch;
       }
@@ -335,6 +335,257 @@ hipError_t gc_launch(const GcPlan& pl, const GcParams& p, hipStream_t st) {
   if (p.kH * p.kW == 9) hipLaunchKernelGGL(g_conv_mfma_kernel<9>, dim3(pl.grid), dim3(256), pl.lds, st, p);
   else hipLaunchKernelGGL(g_conv_mfma_kernel<1>, dim3(pl.grid), dim3(256), pl.lds, st, p);
   return hipGetLastError();
+}
+
+// ---- weight gradient on the same chunks -------------------------------------------------------------------
+// dw'[o][tap][q] = sum over pixels of dZ[pixel][o] X[pixel (+) tap][group(o) cg + q] and r[o] = sum dZ (Sec. 3.2.1,
+// App. B).  The reduced index is the pixel, so both MFMA operands come from LDS through the transposing load
+// (ds_read_tr16_b64: a lane supplies the address of 4 channels of one pixel and receives 4 consecutive pixels of
+// one channel): rows = the chunk's 32 input channels at the pixel's window position, columns = its 32 output
+// channels, 16 pixels per step, one accumulator tile per tap.  Only the diagonal cg x cg blocks of the 32 x 32
+// result are wanted; the rest is computed and dropped.  A workgroup keeps its sums in registers over all its tiles
+// and writes one fp32 slice of dw' (and of r) at the end.
+typedef short gs16x4 __attribute__((ext_vector_type(4)));
+typedef short gs16x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ gs16x4 g_read_tr(const unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) gs16x4*)(p));
+}
+__device__ __forceinline__ bf16x8 g_join(gs16x4 a, gs16x4 b) {
+  gs16x8 v = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+constexpr int GW_PPT = 12;   // most 16-byte patch items a thread fetches per tile
+constexpr int GW_ZPT = 8;    // ... and dZ items
+
+struct GwParams {
+  const bf16_t* x;      // [N][Hi][Wi][C]
+  const bf16_t* dz;     // [N][Ho][Wo][C]
+  float* part;          // [nworkers][C][taps cg]
+  float* r_part;        // [nworkers][C] or null
+  int N, Hi, Wi, C, Ho, Wo, kH, kW, sh, sw, ph, pw, cg;
+  int nch, TR, TC, ntr, ntc, ntiles, PR, PC, pitch;
+  int npx, nk;          // pixels per tile, 16-pixel steps per tile
+  int ncg, nworkers;
+};
+
+template <int TAPS>
+__global__ __launch_bounds__(256) void g_wgrad_mfma_kernel(GwParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kb = lane >> 5;
+  const int eprime = (lane & 15) >> 2;                           // pixel (of 4) this lane addresses in a transposing read
+  const int quad = ((lane >> 4) & 1) * 4 + (lane & 3);           // its 4-channel quad inside the 32-channel chunk
+  const int cgrp = blockIdx.x % p.ncg, worker = blockIdx.x / p.ncg;
+  const int cl = wave % p.nch, chunk = cgrp * p.nch + cl;
+  const int nred = 4 / p.nch, wq = wave / p.nch;                 // waves per chunk; this wave's place among them
+  const int npx16 = p.nk * 16;
+  unsigned char* patch = smem;                                                  // [PR][PC][pitch]
+  unsigned char* zt = smem + (size_t)p.PR * p.PC * p.pitch;                     // [npx16][pitch]
+  int* poff = reinterpret_cast<int*>(zt + (size_t)npx16 * p.pitch);             // [npx16] window origin of a tile pixel
+  for (int e = tid; e < npx16; e += 256) {
+    const int r = e / p.TC, c = e - r * p.TC;
+    poff[e] = e < p.npx ? ((r * p.sh) * p.PC + c * p.sw) * p.pitch : 0;
+  }
+
+  const int gpp = p.nch * 4;
+  const int nitems = p.PR * p.PC * gpp, nz = npx16 * gpp;
+  int ipr[GW_PPT], ipc[GW_PPT], zr[GW_ZPT], zc[GW_ZPT];
+#pragma unroll
+  for (int k = 0; k < GW_PPT; ++k) {
+    const int e = tid + 256 * k;
+    const int pix = e / gpp;
+    ipr[k] = pix / p.PC;
+    ipc[k] = (pix - ipr[k] * p.PC) | ((e - pix * gpp) << 16);
+  }
+#pragma unroll
+  for (int k = 0; k < GW_ZPT; ++k) {
+    const int pix = (tid + 256 * k) / gpp;
+    zr[k] = pix < p.npx ? pix / p.TC : (1 << 20);     // never a row of the tile
+    zc[k] = pix - (pix / p.TC) * p.TC;
+  }
+  const int zgq = tid % gpp;                          // the granule (8 channels) of every dZ item of this thread
+  uint4 pv[GW_PPT], zv[GW_ZPT];
+  auto fetch = [&](int tile) {
+    const int tc = tile % p.ntc;
+    const int t2 = tile / p.ntc;
+    const int tr = t2 % p.ntr, n = t2 / p.ntr;
+    const int r0 = tr * p.TR, c0 = tc * p.TC;
+    const int h0 = r0 * p.sh - p.ph, w0 = c0 * p.sw - p.pw;
+#pragma unroll
+    for (int k = 0; k < GW_PPT; ++k) {
+      const int h = h0 + ipr[k], w = w0 + (ipc[k] & 0xffff), gq = ipc[k] >> 16;
+      pv[k] = make_uint4(0u, 0u, 0u, 0u);
+      if (tid + 256 * k < nitems && tile < p.ntiles && (unsigned)h < (unsigned)p.Hi && (unsigned)w < (unsigned)p.Wi)
+        pv[k] = *reinterpret_cast<const uint4*>(p.x + (((size_t)n * p.Hi + h) * p.Wi + w) * p.C + cgrp * p.nch * 32 + gq * 8);
+    }
+#pragma unroll
+    for (int k = 0; k < GW_ZPT; ++k) {
+      zv[k] = make_uint4(0u, 0u, 0u, 0u);
+      if (tid + 256 * k < nz && tile < p.ntiles && r0 + zr[k] < p.Ho && zr[k] < p.TR && c0 + zc[k] < p.Wo)
+        zv[k] = *reinterpret_cast<const uint4*>(p.dz + (((size_t)n * p.Ho + r0 + zr[k]) * p.Wo + c0 + zc[k]) * p.C +
+                                                cgrp * p.nch * 32 + zgq * 8);
+    }
+  };
+  float racc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) racc[j] = 0.f;
+  auto stash = [&]() {
+#pragma unroll
+    for (int k = 0; k < GW_PPT; ++k)
+      if (tid + 256 * k < nitems)
+        *reinterpret_cast<uint4*>(patch + (ipr[k] * p.PC + (ipc[k] & 0xffff)) * p.pitch + (ipc[k] >> 16) * 16) = pv[k];
+#pragma unroll
+    for (int k = 0; k < GW_ZPT; ++k)
+      if (tid + 256 * k < nz) {
+        *reinterpret_cast<uint4*>(zt + ((tid + 256 * k) / gpp) * p.pitch + zgq * 16) = zv[k];
+        racc[0] += bf16_lo(zv[k].x); racc[1] += bf16_hi(zv[k].x); racc[2] += bf16_lo(zv[k].y); racc[3] += bf16_hi(zv[k].y);
+        racc[4] += bf16_lo(zv[k].z); racc[5] += bf16_hi(zv[k].z); racc[6] += bf16_lo(zv[k].w); racc[7] += bf16_hi(zv[k].w);
+      }
+  };
+
+  f32x16 acc[TAPS];
+#pragma unroll
+  for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+
+  fetch(worker);
+  for (int tile = worker; tile < p.ntiles; tile += p.nworkers) {
+    __syncthreads();   // the previous tile has been read
+    stash();
+    fetch(tile + p.nworkers);
+    __syncthreads();   // patch, dZ tile (and, first pass, the offset table) visible
+    for (int k = wq; k < p.nk; k += nred) {
+      const int pa = k * 16 + kb * 8 + eprime;        // the lane's pixel in the first transposing read; + 4 in the second
+      const unsigned char* za = zt + pa * p.pitch + cl * 64 + quad * 8;
+      const bf16x8 zf = g_join(g_read_tr(za), g_read_tr(za + 4 * p.pitch));
+      const unsigned char* xa = patch + poff[pa] + cl * 64 + quad * 8;
+      const unsigned char* xb = patch + poff[pa + 4] + cl * 64 + quad * 8;
+#pragma unroll
+      for (int t = 0; t < TAPS; ++t) {
+        const int i = t / p.kW, j = t - i * p.kW;
+        const int toff = (i * p.PC + j) * p.pitch;
+        const bf16x8 xf = g_join(g_read_tr(xa + toff), g_read_tr(xb + toff));
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, zf, acc[t], 0, 0, 0);
+      }
+    }
+  }
+  __syncthreads();     // every wave is done with the tiles: LDS is reused for the sums
+  float* red = reinterpret_cast<float*>(smem);
+  if (p.r_part) {
+    // thread -> 8 channels (granule zgq) of every gpp-th item: sum the threads of a granule
+#pragma unroll
+    for (int j = 0; j < 8; ++j) red[tid * 8 + j] = racc[j];
+    __syncthreads();
+    if (tid < p.nch * 32) {
+      const int gq = tid >> 3, j = tid & 7;
+      float v = 0.f;
+      for (int t = gq; t < 256; t += gpp) v += red[t * 8 + j];
+      p.r_part[(size_t)worker * p.C + cgrp * p.nch * 32 + tid] = v;
+    }
+    __syncthreads();
+  }
+  // Accumulator element e of lane l: input channel 8 (e / 4) + 4 (l / 32) + e % 4 (local), output channel l % 32 (local).
+  // A run of 4 input channels lies in one group; it is wanted when that is the output channel's group.
+  const int co_l = lane & 31;
+  const int K = TAPS * p.cg;
+  for (int round = 1; round < nred; ++round) {
+    if (wq == round) {
+#pragma unroll
+      for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const int ci0 = 8 * e4 + 4 * kb;
+          if (ci0 / p.cg == co_l / p.cg)
+            *reinterpret_cast<float4*>(red + ((size_t)cl * 32 + co_l) * K + t * p.cg + ci0 % p.cg) =
+                make_float4(acc[t][e4 * 4 + 0], acc[t][e4 * 4 + 1], acc[t][e4 * 4 + 2], acc[t][e4 * 4 + 3]);
+        }
+    }
+    __syncthreads();
+    if (wq == 0) {
+#pragma unroll
+      for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const int ci0 = 8 * e4 + 4 * kb;
+          if (ci0 / p.cg == co_l / p.cg) {
+            const float4 v = *reinterpret_cast<const float4*>(red + ((size_t)cl * 32 + co_l) * K + t * p.cg + ci0 % p.cg);
+            acc[t][e4 * 4 + 0] += v.x; acc[t][e4 * 4 + 1] += v.y; acc[t][e4 * 4 + 2] += v.z; acc[t][e4 * 4 + 3] += v.w;
+          }
+        }
+    }
+    __syncthreads();
+  }
+  if (wq == 0) {
+    float* orow = p.part + ((size_t)worker * p.C + chunk * 32 + co_l) * K;
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const int ci0 = 8 * e4 + 4 * kb;
+        if (ci0 / p.cg == co_l / p.cg)
+          *reinterpret_cast<float4*>(orow + t * p.cg + ci0 % p.cg) =
+              make_float4(acc[t][e4 * 4 + 0], acc[t][e4 * 4 + 1], acc[t][e4 * 4 + 2], acc[t][e4 * 4 + 3]);
+      }
+  }
+}
+
+struct GwPlan { bool ok; size_t lds; int grid; };
+GwPlan gw_plan(const Geom& g, int groups, int dtype, GwParams* pp) {
+  GwPlan pl{false, 0, 0};
+  GwParams& p = *pp;
+  p = GwParams{};
+  const int C = g.Cin, cg = g.Cin / groups, taps = g.kH * g.kW;
+  if (dtype != CONVBN_BF16 || g.Cin != g.Cout || g.sh > 2 || g.sw > 2) return pl;
+  if (C % 32 != 0 || (cg != 4 && cg != 8 && cg != 16 && cg != 32) || (taps != 1 && taps != 9)) return pl;
+  p.N = g.N; p.Hi = g.Hin; p.Wi = g.Win; p.C = C; p.Ho = g.Hout; p.Wo = g.Wout; p.kH = g.kH; p.kW = g.kW;
+  p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.cg = cg;
+  p.ntc = ceil_div(g.Wout, 64);
+  p.TC = ceil_div(g.Wout, p.ntc);
+  p.PC = (p.TC - 1) * g.sw + g.kW;
+  const int nchunks = C / 32;
+  double best = 0;
+  size_t best_lds = 0;
+  for (int nch = 1; nch <= 4; nch *= 2) {
+    if (nchunks % nch != 0) continue;
+    const int pitch = 64 * nch + 16, nred = 4 / nch;
+    const size_t red_bytes = nred > 1 ? (size_t)nch * 32 * taps * cg * 4 : 0;
+    for (int TR = 1; TR <= g.Hout; ++TR) {
+      const int PR = (TR - 1) * g.sh + g.kH;
+      const int nk = ceil_div(TR * p.TC, 16);
+      size_t lds = (size_t)PR * p.PC * pitch + (size_t)nk * 16 * pitch + (size_t)nk * 16 * 4;
+      if (lds > 60 * 1024 || PR * p.PC * nch * 4 > 256 * GW_PPT || nk * 16 * nch * 4 > 256 * GW_ZPT) break;
+      if (lds < red_bytes) lds = red_bytes;
+      if (lds < 8192) lds = 8192;                        // the channel sums of dZ meet in the first 8 KB
+      if (lds > 64 * 1024) continue;
+      const int ntr = ceil_div(g.Hout, TR);
+      if (ceil_div(g.Hout, ntr) != TR) continue;
+      const double work = (double)ntr * ceil_div(nk, nred) * (nchunks / nch);
+      const double fetched = (double)ntr * PR / ((double)g.Hout * g.sh);
+      const double score = 1.0 / (work * (1.0 + 0.3 * (fetched - 1.0)));
+      if (score >= best) {   // ties: more channels per workgroup (longer contiguous loads)
+        best = score; best_lds = lds;
+        p.nch = nch; p.TR = TR; p.ntr = ntr; p.PR = PR; p.pitch = pitch; p.nk = nk;
+      }
+    }
+  }
+  if (best == 0) return pl;
+  p.npx = p.TR * p.TC;
+  p.ntiles = g.N * p.ntr * p.ntc;
+  p.ncg = nchunks / p.nch;
+  // one fp32 slice of dw' per worker: enough workers to fill the chip, not more slices than the fold-back reads cheaply
+  const size_t slice = (size_t)C * taps * cg * 4;
+  int workers = ceil_div(512, p.ncg);
+  const int cap = (int)((size_t)(16 << 20) / slice);
+  if (workers > cap) workers = cap;
+  if (workers > p.ntiles) workers = p.ntiles;
+  if (workers < 1) workers = 1;
+  p.nworkers = workers;
+  pl.lds = best_lds;
+  pl.grid = workers * p.ncg;
+  pl.ok = true;
+  return pl;
 }
 
 int direct_splits(const Geom& g, int cg) {
@@ -390,19 +641,27 @@ hipError_t launch_g_dgrad(const Geom& g, int groups, int dtype, const void* dz, 
 }
 
 int g_wgrad_slices(const Geom& g, int groups, int dtype) {
-  (void)dtype;
+  GwParams gp;
+  if (gw_plan(g, groups, dtype, &gp).ok) return gp.nworkers;
   return direct_splits(g, g.Cin / groups);
 }
 
 bool g_wgrad_makes_rsum(const Geom& g, int groups, int dtype) {
-  (void)g; (void)groups; (void)dtype;
-  return false;
+  GwParams gp;
+  return gw_plan(g, groups, dtype, &gp).ok;
 }
 
 hipError_t launch_g_wgrad(const Geom& g, int groups, int dtype, const void* x, const void* dz, float* part,
                           float* r_part, hipStream_t st) {
-  (void)r_part;
   const int cg = g.Cin / groups, og = g.Cout / groups;
+  GwParams gp;
+  const GwPlan pl = gw_plan(g, groups, dtype, &gp);
+  if (pl.ok) {
+    gp.x = (const bf16_t*)x; gp.dz = (const bf16_t*)dz; gp.part = part; gp.r_part = r_part;
+    if (g.kH * g.kW == 9) hipLaunchKernelGGL(g_wgrad_mfma_kernel<9>, dim3(pl.grid), dim3(256), pl.lds, st, gp);
+    else hipLaunchKernelGGL(g_wgrad_mfma_kernel<1>, dim3(pl.grid), dim3(256), pl.lds, st, gp);
+    return hipGetLastError();
+  }
   const size_t P = (size_t)g.Cout * g.kH * g.kW * cg;
   const int ns = direct_splits(g, cg);
   const int rps = ceil_div(g.M, ns);
