@@ -67,6 +67,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2", choices=sorted(WORKLOADS))
+    ap.add_argument("--only", default=None, help="depthwise / grouped workloads: comma-separated shape names to keep")
     ap.add_argument("--pool-mb", type=int, default=768,
                     help="minimum total size of the rotating buffer pool per shape")
     ap.add_argument("--kernel-reps", type=int, default=50)
@@ -441,15 +442,16 @@ def main_depthwise(a, kind="depthwise"):
         sys.exit(1)
     torch.cuda.set_device(0)
     grouped = kind == "grouped"
+    keep = (lambda rows: [t for t in rows if a.only is None or t[0] in a.only.split(",")])
     if grouped:
         shapes = [synth.BlockShape(n, N, c, h, w, c, k, st, pd, "bf16", 130 + i)
-                  for i, (n, N, c, h, w, k, st, pd, _) in enumerate(GROUPED_SHAPES)]
-        groups = [t[-1] for t in GROUPED_SHAPES]
+                  for i, (n, N, c, h, w, k, st, pd, _) in enumerate(keep(GROUPED_SHAPES))]
+        groups = [t[-1] for t in keep(GROUPED_SHAPES)]
         inputs = [synth.make_grouped_inputs(s, g) for s, g in zip(shapes, groups)]
         DepthwiseRun = GroupedRun
     else:
         shapes = [synth.BlockShape(n, N, c, h, w, c, k, st, pd, "bf16", 110 + i)
-                  for i, (n, N, c, h, w, k, st, pd) in enumerate(DW_SHAPES)]
+                  for i, (n, N, c, h, w, k, st, pd) in enumerate(keep(DW_SHAPES))]
         groups = [s.Cin for s in shapes]
         inputs = [synth.make_dw_inputs(s) for s in shapes]
     step_bytes = [2.0 * (3 * s.A_x + 3 * s.A_z) for s in shapes]

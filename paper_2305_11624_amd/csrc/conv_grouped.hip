@@ -121,8 +121,21 @@ __global__ __launch_bounds__(256) void g_wgrad_direct_kernel(const T* __restrict
 //     one image) for NCH chunks of 32 channels; wave w owns chunk w % NCH and every (4 / NCH)-th group of 32 pixels.
 //   * The input gradient of a stride-1 block is the same kernel on dZ with the taps reversed and the weight read
 //     in its other order.
-constexpr int GC_PPT = 16;                 // most 16-byte patch items a thread fetches per tile
-constexpr size_t GC_PATCH_MAX = 52 * 1024; // patch bytes (+ 10 KB of output staging: two workgroups per CU)
+// n / d for 0 <= n < 65536 and 1 <= d < 65536 with m = 2^32 / d + 1 (exact: the error n (m d - 2^32) stays below 2^32)
+__device__ __forceinline__ int g_div(int n, unsigned m, int d) { return d == 1 ? n : (int)__umulhi((unsigned)n, m); }
+inline unsigned g_magic(int d) { return (unsigned)((1ull << 32) / (unsigned)d + 1); }
+// Workgroups that share cache lines and halo rows -- the chunk groups of one tile, the tiles of neighbouring
+// workers -- get consecutive logical numbers, and consecutive logical numbers run on the same XCD (the hardware
+// deals consecutive workgroup ids round-robin over the 8 XCDs, each with an L2 of its own).
+__device__ __forceinline__ int g_logical_block() {
+  const int per = gridDim.x >> 3;
+  return (gridDim.x & 7) ? (int)blockIdx.x : (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
+}
+
+// Small tiles on purpose: a workgroup's phases (fetch, LDS, multiply, store) run one after the other, and what hides
+// them is other workgroups on the same CU -- four fit with these sizes, and the fetch registers stay few.
+constexpr int GC_PPT = 8;                  // most 16-byte patch items a thread fetches per tile
+constexpr size_t GC_PATCH_MAX = 24 * 1024; // patch bytes (+ 10 KB of output staging)
 
 struct GcParams {
   const bf16_t* in;     // [N][Hi][Wi][C]
@@ -136,6 +149,8 @@ struct GcParams {
   int PR, PC, pitch;    // patch rows, columns, bytes per patch pixel (64 nch + 16)
   int nwt;              // groups of 32 pixels per tile
   int ncg, nworkers;    // channel-chunk groups (C / 32 / nch); workgroups per chunk group
+  int lcg, lgpp;        // log2 of cg and of the 16-byte granules per patch pixel (4 nch)
+  unsigned mTC, mPC;    // g_div multipliers of TC and PC
 };
 
 template <int TAPS>
@@ -143,48 +158,13 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kb = lane >> 5, px = lane & 31;
-  const int cgrp = blockIdx.x % p.ncg, worker = blockIdx.x / p.ncg;
+  const int lb = g_logical_block();
+  const int cgrp = lb % p.ncg, worker = lb / p.ncg;
   const int cl = wave % p.nch;                      // this wave's chunk inside the workgroup's channels
   const int chunk = cgrp * p.nch + cl;              // ... and in the tensor
   const int wstep = 4 / p.nch, wfirst = wave / p.nch;
   unsigned char* patch = smem;
   unsigned char* stage = smem + (size_t)p.PR * p.PC * p.pitch + wave * (32 * 80);   // [32 pixels][64 + 16 bytes]
-
-  // ---- weight fragments: row = lane % 32 (output channel; mode 1: input channel), 8 consecutive reduced channels
-  bf16x8 wf[TAPS][2];
-  {
-    const int row = px, rgrp = row / p.cg;
-#pragma unroll
-    for (int t = 0; t < TAPS; ++t)
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const int k0 = ks * 16 + kb * 8;             // first of the 8 reduced channels (local)
-        const bool lo = k0 / p.cg == rgrp, hi = (k0 + 4) / p.cg == rgrp;
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (p.mode == 0) {
-          const bf16_t* wr = p.w + ((size_t)(chunk * 32 + row) * TAPS + t) * p.cg;
-          if (p.cg == 4) {
-            if (lo || hi) {
-              const uint2 r = *reinterpret_cast<const uint2*>(wr);
-              if (lo) { v.x = r.x; v.y = r.y; } else { v.z = r.x; v.w = r.y; }
-            }
-          } else if (lo) {
-            v = *reinterpret_cast<const uint4*>(wr + (k0 % p.cg));
-          }
-        } else if (lo || hi) {
-          const int tf = TAPS - 1 - t;
-          v = *reinterpret_cast<const uint4*>(p.w + ((size_t)(row % p.cg) * TAPS + tf) * p.C + chunk * 32 + k0);
-          if (!lo) { v.x = 0u; v.y = 0u; }
-          if (!hi) { v.z = 0u; v.w = 0u; }
-        }
-        wf[t][ks] = __builtin_bit_cast(bf16x8, v);
-      }
-  }
-  // bias of the lane's 16 accumulator channels 8 (e / 4) + 4 kb + e % 4
-  float bv[16];
-#pragma unroll
-  for (int e = 0; e < 16; ++e)
-    bv[e] = p.bias ? p.bias[chunk * 32 + 8 * (e >> 2) + 4 * kb + (e & 3)] : 0.f;
 
   // ---- patch items of this thread (the same for every tile): 16-byte granule gq of patch pixel (row pr, column pc)
   const int gpp = p.nch * 4;                        // granules per patch pixel
@@ -193,9 +173,9 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
 #pragma unroll
   for (int k = 0; k < GC_PPT; ++k) {
     const int e = tid + 256 * k;
-    const int pix = e / gpp;
-    ipr[k] = pix / p.PC;
-    ipc[k] = (pix - ipr[k] * p.PC) | ((e - pix * gpp) << 16);
+    const int pix = e >> p.lgpp;
+    ipr[k] = g_div(pix, p.mPC, p.PC);
+    ipc[k] = (pix - ipr[k] * p.PC) | ((e & (gpp - 1)) << 16);
   }
   uint4 pv[GC_PPT];
   auto fetch = [&](int tile) {
@@ -206,9 +186,11 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
 #pragma unroll
     for (int k = 0; k < GC_PPT; ++k) {
       const int h = h0 + ipr[k], w = w0 + (ipc[k] & 0xffff), gq = ipc[k] >> 16;
-      pv[k] = make_uint4(0u, 0u, 0u, 0u);
-      if (tid + 256 * k < nitems && tile < p.ntiles && (unsigned)h < (unsigned)p.Hi && (unsigned)w < (unsigned)p.Wi)
-        pv[k] = *reinterpret_cast<const uint4*>(p.in + (((size_t)n * p.Hi + h) * p.Wi + w) * p.C + cgrp * p.nch * 32 + gq * 8);
+      // branch-free: an item outside the image (or past the last tile) loads the tensor's first bytes and drops them
+      const bool ok = tid + 256 * k < nitems && tile < p.ntiles && (unsigned)h < (unsigned)p.Hi && (unsigned)w < (unsigned)p.Wi;
+      const size_t off = ok ? (((size_t)n * p.Hi + h) * p.Wi + w) * p.C + cgrp * p.nch * 32 + gq * 8 : 0;
+      const uint4 v = *reinterpret_cast<const uint4*>(p.in + off);
+      pv[k] = make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
     }
   };
   auto stash = [&]() {
@@ -218,7 +200,44 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
         *reinterpret_cast<uint4*>(patch + (ipr[k] * p.PC + (ipc[k] & 0xffff)) * p.pitch + (ipc[k] >> 16) * 16) = pv[k];
   };
 
-  fetch(worker);
+  fetch(worker);   // in flight while the weights arrive
+
+  // ---- weight fragments: row = lane % 32 (output channel; mode 1: input channel), 8 consecutive reduced channels
+  bf16x8 wf[TAPS][2];
+  {
+    const int row = px, rgrp = row >> p.lcg;
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const int k0 = ks * 16 + kb * 8;             // first of the 8 reduced channels (local)
+        const bool lo = (k0 >> p.lcg) == rgrp, hi = ((k0 + 4) >> p.lcg) == rgrp;
+        // every address below is inside the weight whatever the masks say: load first, zero afterwards, so that
+        // all loads of the lane are in flight together
+        uint4 v;
+        if (p.mode == 0) {
+          const bf16_t* wr = p.w + ((size_t)(chunk * 32 + row) * TAPS + t) * p.cg;
+          if (p.cg == 4) {
+            const uint2 r = *reinterpret_cast<const uint2*>(wr);
+            v = make_uint4(r.x, r.y, r.x, r.y);
+          } else {
+            v = *reinterpret_cast<const uint4*>(wr + (k0 & (p.cg - 1)));
+          }
+        } else {
+          const int tf = TAPS - 1 - t;
+          v = *reinterpret_cast<const uint4*>(p.w + ((size_t)(row & (p.cg - 1)) * TAPS + tf) * p.C + chunk * 32 + k0);
+        }
+        v.x = lo ? v.x : 0u; v.y = lo ? v.y : 0u;
+        v.z = hi ? v.z : 0u; v.w = hi ? v.w : 0u;
+        wf[t][ks] = __builtin_bit_cast(bf16x8, v);
+      }
+  }
+  // bias of the lane's 16 accumulator channels 8 (e / 4) + 4 kb + e % 4
+  float bv[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e)
+    bv[e] = p.bias ? p.bias[chunk * 32 + 8 * (e >> 2) + 4 * kb + (e & 3)] : 0.f;
+
   for (int tile = worker; tile < p.ntiles; tile += p.nworkers) {
     const int tc = tile % p.ntc;
     const int t2 = tile / p.ntc;
@@ -230,9 +249,9 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
     fetch(tile + p.nworkers);
     __syncthreads();   // patch visible
     for (int wt = wfirst; wt < p.nwt; wt += wstep) {
-      if ((wt * 32) / p.TC >= rows) break;            // nothing but rows past the image in this and later groups
+      if (g_div(wt * 32, p.mTC, p.TC) >= rows) break;            // nothing but rows past the image in this and later groups
       const int pl = wt * 32 + px;
-      int r = pl / p.TC, c = pl - r * p.TC;
+      int r = g_div(pl, p.mTC, p.TC), c = pl - r * p.TC;
       if (r >= rows || c >= cols) { r = 0; c = 0; }   // computed and dropped
       const unsigned char* b0 = patch + ((r * p.sh) * p.PC + c * p.sw) * p.pitch + cl * 64 + kb * 16;
       f32x16 acc;
@@ -258,7 +277,7 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
         const int sp = pass * 16 + (lane >> 2), gq = lane & 3;
         const uint4 v = *reinterpret_cast<const uint4*>(stage + sp * 80 + gq * 16);
         const int p2 = wt * 32 + sp;
-        const int r2 = p2 / p.TC, c2 = p2 - r2 * p.TC;
+        const int r2 = g_div(p2, p.mTC, p.TC), c2 = p2 - r2 * p.TC;
         if (r2 < rows && c2 < cols)
           *reinterpret_cast<uint4*>(p.out + (((size_t)n * p.Ho + r0 + r2) * p.Wo + c0 + c2) * p.C + chunk * 32 + gq * 8) = v;
       }
@@ -278,37 +297,42 @@ GcPlan gc_plan(int N, int C, int cg, int in_h, int in_w, int out_h, int out_w, i
   if (taps != 1 && taps != 9) return pl;
   p.N = N; p.Hi = in_h; p.Wi = in_w; p.C = C; p.Ho = out_h; p.Wo = out_w; p.kH = kH; p.kW = kW;
   p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.cg = cg;
-  p.ntc = ceil_div(out_w, 64);
-  p.TC = ceil_div(out_w, p.ntc);
-  p.PC = (p.TC - 1) * sw + kW;
   const int nchunks = C / 32;
   double best = 0;
-  for (int nch = 1; nch <= 4; nch *= 2) {
-    if (nchunks % nch != 0) continue;
-    const int pitch = 64 * nch + 16;
-    for (int TR = 1; TR <= out_h; ++TR) {
-      const int PR = (TR - 1) * sh + kH;
-      if ((size_t)PR * p.PC * pitch > GC_PATCH_MAX || PR * p.PC * nch * 4 > 256 * GC_PPT) break;
-      const int ntr = ceil_div(out_h, TR);
-      if (ceil_div(out_h, ntr) != TR) continue;         // an evenly split height only
-      const int per_round = 4 / nch;
-      auto rounds = [&](int rows) { return ceil_div(ceil_div(rows * p.TC, 32), per_round); };
-      const int last = out_h - (ntr - 1) * TR;
-      const double work = ((double)(ntr - 1) * rounds(TR) + rounds(last)) * (nchunks / nch);   // wave rounds per image column
-      const double fetched = (double)ntr * PR / ((double)out_h * sh);                          // rows fetched / rows there are
-      const double score = 1.0 / (work * (1.0 + 0.3 * (fetched - 1.0)));
-      if (score >= best) {   // ties: more channels per workgroup (longer contiguous loads)
-        best = score;
-        p.nch = nch; p.TR = TR; p.ntr = ntr; p.PR = PR; p.pitch = pitch;
+  for (int ntc = ceil_div(out_w, 64); ntc <= ceil_div(out_w, 64) + 3 && ntc <= out_w; ++ntc) {
+    const int TC = ceil_div(out_w, ntc);
+    if (ceil_div(out_w, TC) != ntc) continue;
+    const int PC = (TC - 1) * sw + kW;
+    for (int nch = 1; nch <= 4; nch *= 2) {
+      if (nchunks % nch != 0) continue;
+      const int pitch = 64 * nch + 16;
+      for (int TR = 1; TR <= out_h; ++TR) {
+        const int PR = (TR - 1) * sh + kH;
+        if ((size_t)PR * PC * pitch > GC_PATCH_MAX || PR * PC * nch * 4 > 256 * GC_PPT) break;
+        const int ntr = ceil_div(out_h, TR);
+        if (ceil_div(out_h, ntr) != TR) continue;         // an evenly split height only
+        const int per_round = 4 / nch;
+        auto rounds = [&](int rows) { return ceil_div(ceil_div(rows * TC, 32), per_round); };
+        const int last = out_h - (ntr - 1) * TR;
+        const double work = ((double)(ntr - 1) * rounds(TR) + rounds(last)) * ntc * (nchunks / nch);   // wave rounds per image
+        const double fetched = ((double)ntr * PR * ntc * PC) / ((double)out_h * sh * out_w * sw);       // patch pixels / image pixels
+        const double score = 1.0 / (work * (1.0 + 0.3 * (fetched - 1.0)));
+        if (score >= best) {   // ties: more channels per workgroup (longer contiguous loads)
+          best = score;
+          p.nch = nch; p.TR = TR; p.ntr = ntr; p.PR = PR; p.pitch = pitch; p.ntc = ntc; p.TC = TC; p.PC = PC;
+        }
       }
     }
   }
   if (best == 0) return pl;
+  p.lcg = cg == 4 ? 2 : cg == 8 ? 3 : cg == 16 ? 4 : 5;
+  p.lgpp = p.nch == 1 ? 2 : p.nch == 2 ? 3 : 4;
+  p.mTC = g_magic(p.TC); p.mPC = g_magic(p.PC);
   p.nwt = ceil_div(p.TR * p.TC, 32);
   p.ntiles = N * p.ntr * p.ntc;
   p.ncg = nchunks / p.nch;
   pl.lds = (size_t)p.PR * p.PC * p.pitch + 4 * 32 * 80;
-  const int per_cu = pl.lds > 80 * 1024 ? 1 : pl.lds > 52 * 1024 ? 2 : 3;
+  const int per_cu = (int)(160 * 1024 / pl.lds) < 4 ? (int)(160 * 1024 / pl.lds) : 4;
   int workers = ceil_div(256 * per_cu, p.ncg);
   if (workers > p.ntiles) workers = p.ntiles;
   p.nworkers = workers;
@@ -343,8 +367,9 @@ hipError_t gc_launch(const GcPlan& pl, const GcParams& p, hipStream_t st) {
 // (ds_read_tr16_b64: a lane supplies the address of 4 channels of one pixel and receives 4 consecutive pixels of
 // one channel): rows = the chunk's 32 input channels at the pixel's window position, columns = its 32 output
 // channels, 16 pixels per step, one accumulator tile per tap.  Only the diagonal cg x cg blocks of the 32 x 32
-// result are wanted; the rest is computed and dropped.  A workgroup keeps its sums in registers over all its tiles
-// and writes one fp32 slice of dw' (and of r) at the end.
+// result are wanted; the rest is computed and dropped.  The waves that share a chunk divide its taps among them
+// (every wave walks all pixels of a tile for its own taps, so no sums cross waves); a workgroup keeps its sums in
+// registers over all its tiles and writes one fp32 slice of dw' (and of r) at the end.
 typedef short gs16x4 __attribute__((ext_vector_type(4)));
 typedef short gs16x8 __attribute__((ext_vector_type(8)));
 __device__ __forceinline__ gs16x4 g_read_tr(const unsigned char* p) {
@@ -355,8 +380,8 @@ __device__ __forceinline__ bf16x8 g_join(gs16x4 a, gs16x4 b) {
   return __builtin_bit_cast(bf16x8, v);
 }
 
-constexpr int GW_PPT = 12;   // most 16-byte patch items a thread fetches per tile
-constexpr int GW_ZPT = 8;    // ... and dZ items
+constexpr int GW_PPT = 6;    // most 16-byte patch items a thread fetches per tile
+constexpr int GW_ZPT = 4;    // ... and dZ items
 
 struct GwParams {
   const bf16_t* x;      // [N][Hi][Wi][C]
@@ -367,24 +392,29 @@ struct GwParams {
   int nch, TR, TC, ntr, ntc, ntiles, PR, PC, pitch;
   int npx, nk;          // pixels per tile, 16-pixel steps per tile
   int ncg, nworkers;
+  int lcg, lgpp;
+  unsigned mTC, mPC;
 };
 
-template <int TAPS>
+template <int TAPS, int NCH>
 __global__ __launch_bounds__(256) void g_wgrad_mfma_kernel(GwParams p) {
+  constexpr int NRED = 4 / NCH;                       // waves that share a chunk: they divide its taps among them
+  constexpr int TPW = (TAPS + NRED - 1) / NRED;       // taps per wave: wave wq takes taps wq, wq + NRED, ...
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kb = lane >> 5;
   const int eprime = (lane & 15) >> 2;                           // pixel (of 4) this lane addresses in a transposing read
   const int quad = ((lane >> 4) & 1) * 4 + (lane & 3);           // its 4-channel quad inside the 32-channel chunk
-  const int cgrp = blockIdx.x % p.ncg, worker = blockIdx.x / p.ncg;
-  const int cl = wave % p.nch, chunk = cgrp * p.nch + cl;
-  const int nred = 4 / p.nch, wq = wave / p.nch;                 // waves per chunk; this wave's place among them
+  const int lb = g_logical_block();
+  const int cgrp = lb % p.ncg, worker = lb / p.ncg;
+  const int cl = wave % NCH, chunk = cgrp * NCH + cl;
+  const int wq = wave / NCH;                                      // this wave's place among the waves of its chunk
   const int npx16 = p.nk * 16;
   unsigned char* patch = smem;                                                  // [PR][PC][pitch]
   unsigned char* zt = smem + (size_t)p.PR * p.PC * p.pitch;                     // [npx16][pitch]
   int* poff = reinterpret_cast<int*>(zt + (size_t)npx16 * p.pitch);             // [npx16] window origin of a tile pixel
   for (int e = tid; e < npx16; e += 256) {
-    const int r = e / p.TC, c = e - r * p.TC;
+    const int r = g_div(e, p.mTC, p.TC), c = e - r * p.TC;
     poff[e] = e < p.npx ? ((r * p.sh) * p.PC + c * p.sw) * p.pitch : 0;
   }
 
@@ -394,17 +424,18 @@ __global__ __launch_bounds__(256) void g_wgrad_mfma_kernel(GwParams p) {
 #pragma unroll
   for (int k = 0; k < GW_PPT; ++k) {
     const int e = tid + 256 * k;
-    const int pix = e / gpp;
-    ipr[k] = pix / p.PC;
-    ipc[k] = (pix - ipr[k] * p.PC) | ((e - pix * gpp) << 16);
+    const int pix = e >> p.lgpp;
+    ipr[k] = g_div(pix, p.mPC, p.PC);
+    ipc[k] = (pix - ipr[k] * p.PC) | ((e & (gpp - 1)) << 16);
   }
 #pragma unroll
   for (int k = 0; k < GW_ZPT; ++k) {
-    const int pix = (tid + 256 * k) / gpp;
-    zr[k] = pix < p.npx ? pix / p.TC : (1 << 20);     // never a row of the tile
-    zc[k] = pix - (pix / p.TC) * p.TC;
+    const int pix = (tid + 256 * k) >> p.lgpp;
+    const int r = g_div(pix, p.mTC, p.TC);
+    zr[k] = pix < p.npx ? r : (1 << 20);              // never a row of the tile
+    zc[k] = pix - r * p.TC;
   }
-  const int zgq = tid % gpp;                          // the granule (8 channels) of every dZ item of this thread
+  const int zgq = tid & (gpp - 1);                          // the granule (8 channels) of every dZ item of this thread
   uint4 pv[GW_PPT], zv[GW_ZPT];
   auto fetch = [&](int tile) {
     const int tc = tile % p.ntc;
@@ -415,16 +446,17 @@ __global__ __launch_bounds__(256) void g_wgrad_mfma_kernel(GwParams p) {
 #pragma unroll
     for (int k = 0; k < GW_PPT; ++k) {
       const int h = h0 + ipr[k], w = w0 + (ipc[k] & 0xffff), gq = ipc[k] >> 16;
-      pv[k] = make_uint4(0u, 0u, 0u, 0u);
-      if (tid + 256 * k < nitems && tile < p.ntiles && (unsigned)h < (unsigned)p.Hi && (unsigned)w < (unsigned)p.Wi)
-        pv[k] = *reinterpret_cast<const uint4*>(p.x + (((size_t)n * p.Hi + h) * p.Wi + w) * p.C + cgrp * p.nch * 32 + gq * 8);
+      const bool ok = tid + 256 * k < nitems && tile < p.ntiles && (unsigned)h < (unsigned)p.Hi && (unsigned)w < (unsigned)p.Wi;
+      const size_t off = ok ? (((size_t)n * p.Hi + h) * p.Wi + w) * p.C + cgrp * p.nch * 32 + gq * 8 : 0;
+      const uint4 v = *reinterpret_cast<const uint4*>(p.x + off);
+      pv[k] = make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
     }
 #pragma unroll
     for (int k = 0; k < GW_ZPT; ++k) {
-      zv[k] = make_uint4(0u, 0u, 0u, 0u);
-      if (tid + 256 * k < nz && tile < p.ntiles && r0 + zr[k] < p.Ho && zr[k] < p.TR && c0 + zc[k] < p.Wo)
-        zv[k] = *reinterpret_cast<const uint4*>(p.dz + (((size_t)n * p.Ho + r0 + zr[k]) * p.Wo + c0 + zc[k]) * p.C +
-                                                cgrp * p.nch * 32 + zgq * 8);
+      const bool ok = tid + 256 * k < nz && tile < p.ntiles && r0 + zr[k] < p.Ho && zr[k] < p.TR && c0 + zc[k] < p.Wo;
+      const size_t off = ok ? (((size_t)n * p.Ho + r0 + zr[k]) * p.Wo + c0 + zc[k]) * p.C + cgrp * p.nch * 32 + zgq * 8 : 0;
+      const uint4 v = *reinterpret_cast<const uint4*>(p.dz + off);
+      zv[k] = make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
     }
   };
   float racc[8];
@@ -438,17 +470,22 @@ __global__ __launch_bounds__(256) void g_wgrad_mfma_kernel(GwParams p) {
 #pragma unroll
     for (int k = 0; k < GW_ZPT; ++k)
       if (tid + 256 * k < nz) {
-        *reinterpret_cast<uint4*>(zt + ((tid + 256 * k) / gpp) * p.pitch + zgq * 16) = zv[k];
+        *reinterpret_cast<uint4*>(zt + ((tid + 256 * k) >> p.lgpp) * p.pitch + zgq * 16) = zv[k];
         racc[0] += bf16_lo(zv[k].x); racc[1] += bf16_hi(zv[k].x); racc[2] += bf16_lo(zv[k].y); racc[3] += bf16_hi(zv[k].y);
         racc[4] += bf16_lo(zv[k].z); racc[5] += bf16_hi(zv[k].z); racc[6] += bf16_lo(zv[k].w); racc[7] += bf16_hi(zv[k].w);
       }
   };
 
-  f32x16 acc[TAPS];
+  f32x16 acc[TPW];
+  int toff[TPW];                                      // patch offset of the wave's taps
 #pragma unroll
-  for (int t = 0; t < TAPS; ++t)
+  for (int u = 0; u < TPW; ++u) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+    for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
+    const int t = wq + NRED * u;
+    const int i = t / p.kW, j = t - i * p.kW;
+    toff[u] = (i * p.PC + j) * p.pitch;
+  }
 
   fetch(worker);
   for (int tile = worker; tile < p.ntiles; tile += p.nworkers) {
@@ -456,18 +493,18 @@ __global__ __launch_bounds__(256) void g_wgrad_mfma_kernel(GwParams p) {
     stash();
     fetch(tile + p.nworkers);
     __syncthreads();   // patch, dZ tile (and, first pass, the offset table) visible
-    for (int k = wq; k < p.nk; k += nred) {
+    for (int k = 0; k < p.nk; ++k) {
       const int pa = k * 16 + kb * 8 + eprime;        // the lane's pixel in the first transposing read; + 4 in the second
       const unsigned char* za = zt + pa * p.pitch + cl * 64 + quad * 8;
       const bf16x8 zf = g_join(g_read_tr(za), g_read_tr(za + 4 * p.pitch));
       const unsigned char* xa = patch + poff[pa] + cl * 64 + quad * 8;
       const unsigned char* xb = patch + poff[pa + 4] + cl * 64 + quad * 8;
 #pragma unroll
-      for (int t = 0; t < TAPS; ++t) {
-        const int i = t / p.kW, j = t - i * p.kW;
-        const int toff = (i * p.PC + j) * p.pitch;
-        const bf16x8 xf = g_join(g_read_tr(xa + toff), g_read_tr(xb + toff));
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, zf, acc[t], 0, 0, 0);
+      for (int u = 0; u < TPW; ++u) {
+        if (NRED * (u + 1) <= TAPS || wq + NRED * u < TAPS) {   // (a compile-time yes except for the last of a wave's taps)
+          const bf16x8 xf = g_join(g_read_tr(xa + toff[u]), g_read_tr(xb + toff[u]));
+          acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, zf, acc[u], 0, 0, 0);
+        }
       }
     }
   }
@@ -490,44 +527,17 @@ __global__ __launch_bounds__(256) void g_wgrad_mfma_kernel(GwParams p) {
   // A run of 4 input channels lies in one group; it is wanted when that is the output channel's group.
   const int co_l = lane & 31;
   const int K = TAPS * p.cg;
-  for (int round = 1; round < nred; ++round) {
-    if (wq == round) {
+  float* orow = p.part + ((size_t)worker * p.C + chunk * 32 + co_l) * K;
 #pragma unroll
-      for (int t = 0; t < TAPS; ++t)
+  for (int u = 0; u < TPW; ++u) {
+    const int t = wq + NRED * u;
 #pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-          const int ci0 = 8 * e4 + 4 * kb;
-          if (ci0 / p.cg == co_l / p.cg)
-            *reinterpret_cast<float4*>(red + ((size_t)cl * 32 + co_l) * K + t * p.cg + ci0 % p.cg) =
-                make_float4(acc[t][e4 * 4 + 0], acc[t][e4 * 4 + 1], acc[t][e4 * 4 + 2], acc[t][e4 * 4 + 3]);
-        }
+    for (int e4 = 0; e4 < 4; ++e4) {
+      const int ci0 = 8 * e4 + 4 * kb;
+      if (t < TAPS && (ci0 >> p.lcg) == (co_l >> p.lcg))
+        *reinterpret_cast<float4*>(orow + t * p.cg + (ci0 & (p.cg - 1))) =
+            make_float4(acc[u][e4 * 4 + 0], acc[u][e4 * 4 + 1], acc[u][e4 * 4 + 2], acc[u][e4 * 4 + 3]);
     }
-    __syncthreads();
-    if (wq == 0) {
-#pragma unroll
-      for (int t = 0; t < TAPS; ++t)
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-          const int ci0 = 8 * e4 + 4 * kb;
-          if (ci0 / p.cg == co_l / p.cg) {
-            const float4 v = *reinterpret_cast<const float4*>(red + ((size_t)cl * 32 + co_l) * K + t * p.cg + ci0 % p.cg);
-            acc[t][e4 * 4 + 0] += v.x; acc[t][e4 * 4 + 1] += v.y; acc[t][e4 * 4 + 2] += v.z; acc[t][e4 * 4 + 3] += v.w;
-          }
-        }
-    }
-    __syncthreads();
-  }
-  if (wq == 0) {
-    float* orow = p.part + ((size_t)worker * p.C + chunk * 32 + co_l) * K;
-#pragma unroll
-    for (int t = 0; t < TAPS; ++t)
-#pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
-        const int ci0 = 8 * e4 + 4 * kb;
-        if (ci0 / p.cg == co_l / p.cg)
-          *reinterpret_cast<float4*>(orow + t * p.cg + ci0 % p.cg) =
-              make_float4(acc[t][e4 * 4 + 0], acc[t][e4 * 4 + 1], acc[t][e4 * 4 + 2], acc[t][e4 * 4 + 3]);
-      }
   }
 }
 
@@ -541,36 +551,39 @@ GwPlan gw_plan(const Geom& g, int groups, int dtype, GwParams* pp) {
   if (C % 32 != 0 || (cg != 4 && cg != 8 && cg != 16 && cg != 32) || (taps != 1 && taps != 9)) return pl;
   p.N = g.N; p.Hi = g.Hin; p.Wi = g.Win; p.C = C; p.Ho = g.Hout; p.Wo = g.Wout; p.kH = g.kH; p.kW = g.kW;
   p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.cg = cg;
-  p.ntc = ceil_div(g.Wout, 64);
-  p.TC = ceil_div(g.Wout, p.ntc);
-  p.PC = (p.TC - 1) * g.sw + g.kW;
   const int nchunks = C / 32;
   double best = 0;
   size_t best_lds = 0;
-  for (int nch = 1; nch <= 4; nch *= 2) {
-    if (nchunks % nch != 0) continue;
-    const int pitch = 64 * nch + 16, nred = 4 / nch;
-    const size_t red_bytes = nred > 1 ? (size_t)nch * 32 * taps * cg * 4 : 0;
-    for (int TR = 1; TR <= g.Hout; ++TR) {
-      const int PR = (TR - 1) * g.sh + g.kH;
-      const int nk = ceil_div(TR * p.TC, 16);
-      size_t lds = (size_t)PR * p.PC * pitch + (size_t)nk * 16 * pitch + (size_t)nk * 16 * 4;
-      if (lds > 60 * 1024 || PR * p.PC * nch * 4 > 256 * GW_PPT || nk * 16 * nch * 4 > 256 * GW_ZPT) break;
-      if (lds < red_bytes) lds = red_bytes;
-      if (lds < 8192) lds = 8192;                        // the channel sums of dZ meet in the first 8 KB
-      if (lds > 64 * 1024) continue;
-      const int ntr = ceil_div(g.Hout, TR);
-      if (ceil_div(g.Hout, ntr) != TR) continue;
-      const double work = (double)ntr * ceil_div(nk, nred) * (nchunks / nch);
-      const double fetched = (double)ntr * PR / ((double)g.Hout * g.sh);
-      const double score = 1.0 / (work * (1.0 + 0.3 * (fetched - 1.0)));
-      if (score >= best) {   // ties: more channels per workgroup (longer contiguous loads)
-        best = score; best_lds = lds;
-        p.nch = nch; p.TR = TR; p.ntr = ntr; p.PR = PR; p.pitch = pitch; p.nk = nk;
+  for (int ntc = ceil_div(g.Wout, 64); ntc <= ceil_div(g.Wout, 64) + 3 && ntc <= g.Wout; ++ntc) {
+    const int TC = ceil_div(g.Wout, ntc);
+    if (ceil_div(g.Wout, TC) != ntc) continue;
+    const int PC = (TC - 1) * g.sw + g.kW;
+    for (int nch = 1; nch <= 4; nch *= 2) {
+      if (nchunks % nch != 0) continue;
+      const int pitch = 64 * nch + 16, nred = 4 / nch;
+      for (int TR = 1; TR <= g.Hout; ++TR) {
+        const int PR = (TR - 1) * g.sh + g.kH;
+        const int nk = ceil_div(TR * TC, 16);
+        size_t lds = (size_t)PR * PC * pitch + (size_t)nk * 16 * pitch + (size_t)nk * 16 * 4;
+        if (lds > 36 * 1024 || PR * PC * nch * 4 > 256 * GW_PPT || nk * 16 * nch * 4 > 256 * GW_ZPT) break;
+        if (lds < 8192) lds = 8192;                        // the channel sums of dZ meet in the first 8 KB
+        if (lds > 64 * 1024) continue;
+        const int ntr = ceil_div(g.Hout, TR);
+        if (ceil_div(g.Hout, ntr) != TR) continue;
+        const double work = (double)ntr * ntc * nk * ceil_div(taps, nred) * (nchunks / nch);   // MFMA steps of the busiest wave
+        const double fetched = ((double)ntr * PR * ntc * PC) / ((double)g.Hout * g.sh * g.Wout * g.sw);
+        const double score = 1.0 / (work * (1.0 + 0.3 * (fetched - 1.0)));
+        if (score >= best) {   // ties: more channels per workgroup (longer contiguous loads)
+          best = score; best_lds = lds;
+          p.nch = nch; p.TR = TR; p.ntr = ntr; p.PR = PR; p.pitch = pitch; p.nk = nk; p.ntc = ntc; p.TC = TC; p.PC = PC;
+        }
       }
     }
   }
   if (best == 0) return pl;
+  p.lcg = cg == 4 ? 2 : cg == 8 ? 3 : cg == 16 ? 4 : 5;
+  p.lgpp = p.nch == 1 ? 2 : p.nch == 2 ? 3 : 4;
+  p.mTC = g_magic(p.TC); p.mPC = g_magic(p.PC);
   p.npx = p.TR * p.TC;
   p.ntiles = g.N * p.ntr * p.ntc;
   p.ncg = nchunks / p.nch;
@@ -658,8 +671,10 @@ hipError_t launch_g_wgrad(const Geom& g, int groups, int dtype, const void* x, c
   const GwPlan pl = gw_plan(g, groups, dtype, &gp);
   if (pl.ok) {
     gp.x = (const bf16_t*)x; gp.dz = (const bf16_t*)dz; gp.part = part; gp.r_part = r_part;
-    if (g.kH * g.kW == 9) hipLaunchKernelGGL(g_wgrad_mfma_kernel<9>, dim3(pl.grid), dim3(256), pl.lds, st, gp);
-    else hipLaunchKernelGGL(g_wgrad_mfma_kernel<1>, dim3(pl.grid), dim3(256), pl.lds, st, gp);
+#define GWL(T, NC) hipLaunchKernelGGL((g_wgrad_mfma_kernel<T, NC>), dim3(pl.grid), dim3(256), pl.lds, st, gp)
+    if (g.kH * g.kW == 9) { if (gp.nch == 1) GWL(9, 1); else if (gp.nch == 2) GWL(9, 2); else GWL(9, 4); }
+    else { if (gp.nch == 1) GWL(1, 1); else if (gp.nch == 2) GWL(1, 2); else GWL(1, 4); }
+#undef GWL
     return hipGetLastError();
   }
   const size_t P = (size_t)g.Cout * g.kH * g.kW * cg;
