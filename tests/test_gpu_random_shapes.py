@@ -1,4 +1,4 @@
-"""Seeded sweep of randomly drawn (valid) shapes through the three blocks, each against the oracle: windows 1-7,
+"""Seeded sweep of randomly drawn (valid) shapes through the four blocks, each against the oracle: windows 1-7,
 strides 1-3, all paddings, channel counts that do and do not fit the MFMA tiles, ragged images.  Catches planner
 corner cases the hand-picked shapes miss; every draw is reproducible from the seed."""
 import random
@@ -8,7 +8,7 @@ import pytest
 from paper_2305_11624_amd import synth
 from paper_2305_11624_amd.synth import BlockShape
 
-from helpers import compare, oracle_block, oracle_dw_block, oracle_tconv_block
+from helpers import compare, oracle_block, oracle_dw_block, oracle_grouped_block, oracle_tconv_block
 
 pytestmark = pytest.mark.gpu
 
@@ -80,3 +80,31 @@ def test_depthwise_block_random_shapes():
         r = DepthwiseRun(inp, mode=mode, keep_folded=keep, poison=True)
         r.step()
         compare(r.results(), oracle_dw_block(inp), "bf16", tag=f"{shape} {mode} keep={keep}")
+
+
+def test_grouped_block_random_shapes():
+    """Mostly shapes the matrix-core kernels take (equal channel counts, groups of 4-32 channels, 3x3 or 1x1: wide and
+    tall images, both strides, paddings 0-1, so that every column split, tile height and chunk count of their planner
+    comes up), some the any-shape kernels take (other widths, unequal counts, 5x5)."""
+    from paper_2305_11624_amd.runner import GroupedRun
+    rng = random.Random(20230514)
+    for it in range(40):
+        fast = rng.random() < 0.75
+        if fast:
+            cg = rng.choice([4, 8, 16, 32])
+            cin = cout = 32 * rng.choice([1, 2, 3, 4, 6, 8])
+            groups = cin // cg
+            k = rng.choice([3, 3, 3, 1])
+        else:
+            groups = rng.choice([2, 3, 4, 6])
+            cin, cout = groups * rng.choice([2, 6, 12, 24]), groups * rng.choice([4, 8, 12])
+            k = rng.choice([1, 3, 5])
+        s = rng.choice([1, 1, 2])
+        p = rng.randint(0, k // 2)
+        h, w = rng.randint(max(k, 4), 40), rng.randint(max(k, 4), 150 if it % 5 == 0 else 40)
+        shape = BlockShape(f"rg{it}", rng.randint(1, 3), cin, h, w, cout, k, s, p, "bf16", 7000 + it)
+        mode, keep, bias = rng.choice(["tune", "tune", "eval"]), rng.random() < 0.7, rng.random() < 0.5
+        inp = synth.make_grouped_inputs(shape, groups, bias=bias)
+        r = GroupedRun(inp, mode=mode, keep_folded=keep, poison=True)
+        r.step()
+        compare(r.results(), oracle_grouped_block(inp), "bf16", tag=f"{shape} G={groups} {mode} keep={keep}")
