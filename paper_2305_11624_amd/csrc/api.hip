@@ -203,6 +203,7 @@ size_t fprop_scratch_bytes(const Geom& g, int dtype) {
 }
 size_t dgrad_scratch_bytes(const Geom& g, int dtype) {
   if (!needs_cin_pad(g, dtype)) return inner_dgrad_scratch(g, dtype);
+  if (stem_dgrad_supported(g, dtype)) return align_up(stem_dgrad_weight_bytes(g), 256);
   const Geom q = padded_geom(g);
   return align_up((size_t)q.Cout * q.K * 2, 256) + align_up((size_t)q.Min * q.Cin * 2, 256) +
          inner_dgrad_scratch(q, dtype);
@@ -258,6 +259,8 @@ hipError_t run_fprop(const Geom& g, int dtype, const void* x, const void* w_krsc
 hipError_t run_dgrad(const Geom& g, int dtype, const void* dz, const void* w_crsk, void* dx,
                      float* scratch, hipStream_t st) {
   if (!needs_cin_pad(g, dtype)) return dgrad_any(g, dtype, dz, w_crsk, nullptr, dx, scratch, st);
+  if (stem_dgrad_supported(g, dtype))   // a first layer: its own kernel; the scratch holds its packed weight
+    return launch_dgrad_stem(g, dz, w_crsk, scratch, dx, st);
   const Geom q = padded_geom(g);
   char* s = reinterpret_cast<char*>(scratch);
   void* wp = s; s += align_up((size_t)q.Cout * q.K * 2, 256);

@@ -164,6 +164,9 @@ bool stem_fprop_supported(const Geom& g, int dtype);
 bool stem_wgrad_supported(const Geom& g, int dtype);
 int stem_wgrad_slices(const Geom& g);             // fp32 partial copies of dw' (and of r) the kernel writes
 hipError_t launch_wgrad_stem(const Geom& g, const void* x, const void* dz, float* part, float* r_part, hipStream_t st);
+bool stem_dgrad_supported(const Geom& g, int dtype);
+size_t stem_dgrad_weight_bytes(const Geom& g);    // scratch for the input gradient's packed weight
+hipError_t launch_dgrad_stem(const Geom& g, const void* dz, const void* w_crsk, void* wpack, void* dx, hipStream_t st);
 size_t stem_packed_weight_bytes(const Geom& g);   // scratch for the weight padded to 8 window columns x 4 channels
 size_t stem_input_copy_bytes(const Geom& g);      // scratch for a 4-channel copy of the input (0: read as it is)
 hipError_t launch_fprop_stem(const Geom& g, const void* x, const void* w, void* wpad, const float* bias, void* z,

@@ -403,6 +403,233 @@ StemWgPlan stem_wg_plan(const Geom& g, StemWgParams* pp) {
   return pl;
 }
 
+// ---- input gradient of a first layer -------------------------------------------------------------------
+// dX[h][w][c] = sum_{i,j,co} dZ[(h + ph - i) / sh][(w + pw - j) / sw][co] w'[co][i][j][c] over the taps for which the
+// divisions are exact (Sec. 3.2.1).  With 3 input channels the result has almost no columns for a matrix product, so
+// the sh x sw pixels of a block (a, b) = (h / sh, w / sw) and their (padded) 4 channels together form the 16 rows of
+// one: every pixel of the block reads the same U x V neighbourhood of dZ -- rows a + Dh - u, columns b + Dw - v --
+// only with a different subset of the taps, so   dX[block][(phase, c)] = sum_{u,v,co} Wt[(phase, c)][(u, v, co)]
+// dZ[a + Dh - u][b + Dw - v][co],   Wt holding w' where phase (h % sh, w % sw) has a tap at (u, v) and zeros
+// elsewhere (49 of 64 positions for 7x7 / stride 2).  That is a stride-1 convolution of dZ with a U x V window whose
+// 16 output "channels" are un-shuffled to pixels (depth to space).  MFMA 16x16x32: rows = the 16 (phase, c)
+// pairs, columns = 16 blocks, 32 output channels of one (u, v) per step; as in the forward kernel the column
+// operand is read straight from the raw dZ patch in LDS (lane = block, 16 contiguous bytes = 8 channels) and the
+// packed weight (16 x U V Cout) stays resident in LDS.  A lane ends up with the 4 channels of one dX pixel; the
+// tile's pixels are gathered in LDS and leave as whole rows.
+typedef float f32x4s __attribute__((ext_vector_type(4)));
+constexpr int DG_PPT = 8;      // most 16-byte patch items a thread fetches per tile
+constexpr int DG_NBT = 2;      // most 16-block groups a wave multiplies per tile
+
+struct StemDgParams {
+  const bf16_t* dz;     // [N][Ho][Wo][Cout]
+  const bf16_t* wt;     // [16][U V Cout] packed by stem_dgrad_pack_kernel
+  bf16_t* dx;           // [N][H][W][Cin]
+  int N, H, W, Cin, Cout, Ho, Wo, sh, sw;
+  int U, V, Dh, Dw;     // block (a, b) reads dZ rows a + Dh - u (u < U), columns b + Dw - v (v < V)
+  int KT;               // U V Cout
+  int TBR, TBC;         // blocks per tile
+  int nbr, nbc, ntiles; // tiles per image column / row, tiles in all
+  int PR, PC, pitch;    // dZ patch rows (TBR + U - 1), columns (TBC + V - 1), bytes per pixel (2 Cout + 16)
+  int wpitch;           // LDS bytes per weight row (2 KT + 16)
+  int nbt;              // 16-block groups per tile
+  int orow;             // elements per staged dX row: TBC sw Cin
+  int fast_store;       // rows leave as 16-byte pieces (all alignments allow it)
+  unsigned mTBC, mPC;   // multipliers for n / TBC, n / PC (n < 65536)
+};
+
+__device__ __forceinline__ int dg_div(int n, unsigned m, int d) { return d == 1 ? n : (int)__umulhi((unsigned)n, m); }
+
+__global__ __launch_bounds__(256) void stem_dgrad_kernel(StemDgParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* wl = smem;                                         // [16][wpitch]
+  unsigned char* patch = wl + 16 * p.wpitch;                        // [PR][PC][pitch]
+  bf16_t* ost = reinterpret_cast<bf16_t*>(patch + (size_t)p.PR * p.PC * p.pitch);   // [TBR sh][orow]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 15, kg = lane >> 4;                        // MFMA column (block) / row (phase, c) and 8-channel group
+
+  // ---- resident weight
+  const int wgr = p.KT / 8;                                         // 16-byte granules per row
+  for (int e = tid; e < 16 * wgr; e += 256) {
+    const int r = e / wgr, gq = e - r * wgr;
+    *reinterpret_cast<uint4*>(wl + r * p.wpitch + gq * 16) = *reinterpret_cast<const uint4*>(p.wt + (size_t)r * p.KT + gq * 8);
+  }
+  // ---- patch items of this thread: granule gq (8 channels) of patch pixel (row, column), the same for every tile
+  const int gpp = p.Cout / 8;
+  const int nitems = p.PR * p.PC * gpp;
+  int ipr[DG_PPT], ipc[DG_PPT];
+#pragma unroll
+  for (int k = 0; k < DG_PPT; ++k) {
+    const int e = tid + 256 * k;
+    const int pix = e / gpp;
+    ipr[k] = dg_div(pix, p.mPC, p.PC);
+    ipc[k] = (pix - ipr[k] * p.PC) | ((e - pix * gpp) << 16);
+  }
+  uint4 pv[DG_PPT];
+  auto fetch = [&](int tile) {
+    const int tc = tile % p.nbc;
+    const int t2 = tile / p.nbc;
+    const int tr = t2 % p.nbr, n = t2 / p.nbr;
+    // patch row r holds dZ row a0 + Dh - (U - 1) + r, column likewise
+    const int h0 = tr * p.TBR + p.Dh - (p.U - 1), w0 = tc * p.TBC + p.Dw - (p.V - 1);
+#pragma unroll
+    for (int k = 0; k < DG_PPT; ++k) {
+      const int h = h0 + ipr[k], w = w0 + (ipc[k] & 0xffff), gq = ipc[k] >> 16;
+      const bool ok = tid + 256 * k < nitems && tile < p.ntiles && (unsigned)h < (unsigned)p.Ho && (unsigned)w < (unsigned)p.Wo;
+      const size_t off = ok ? (((size_t)n * p.Ho + h) * p.Wo + w) * p.Cout + gq * 8 : 0;
+      const uint4 v = *reinterpret_cast<const uint4*>(p.dz + off);
+      pv[k] = make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
+    }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int k = 0; k < DG_PPT; ++k)
+      if (tid + 256 * k < nitems)
+        *reinterpret_cast<uint4*>(patch + (ipr[k] * p.PC + (ipc[k] & 0xffff)) * p.pitch + (ipc[k] >> 16) * 16) = pv[k];
+  };
+
+  const int nph = p.sh * p.sw;                 // phases: rows 4 phase + c of the product
+  const int ksteps = p.Cout / 32;
+  fetch(blockIdx.x);
+  for (int tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x) {
+    const int tc = tile % p.nbc;
+    const int t2 = tile / p.nbc;
+    const int tr = t2 % p.nbr, n = t2 / p.nbr;
+    __syncthreads();   // the previous tile's patch and staged rows have been read
+    stash();
+    fetch(tile + gridDim.x);
+    __syncthreads();   // patch (and, first pass, the weight) visible
+    // the wave's block groups: wave, wave + 4 (the lane's block: q = 16 group + col -> row ar, column bc of the tile)
+    int ar[DG_NBT], bc[DG_NBT];
+    bool live[DG_NBT];
+    const unsigned char* bp[DG_NBT];
+    f32x4s acc[DG_NBT];
+#pragma unroll
+    for (int t = 0; t < DG_NBT; ++t) {
+      const int q = (wave + 4 * t) * 16 + col;
+      live[t] = wave + 4 * t < p.nbt;
+      const int a = dg_div(q, p.mTBC, p.TBC);
+      ar[t] = a; bc[t] = q - a * p.TBC;
+      const bool in = live[t] && a < p.TBR;
+      // window origin of the block in the patch: its (u, v) = (0, 0) neighbour is patch pixel (ar + U - 1, bc + V - 1)
+      bp[t] = patch + ((in ? a + p.U - 1 : p.U - 1) * p.PC + (in ? bc[t] + p.V - 1 : p.V - 1)) * p.pitch + kg * 16;
+      acc[t] = f32x4s{0.f, 0.f, 0.f, 0.f};
+    }
+    const unsigned char* ap = wl + col * p.wpitch + kg * 16;
+    for (int u = 0; u < p.U; ++u)
+      for (int v = 0; v < p.V; ++v) {
+        const int boff = -(u * p.PC + v) * p.pitch;
+        const unsigned char* aq = ap + (u * p.V + v) * p.Cout * 2;
+        for (int ks = 0; ks < ksteps; ++ks) {
+          const bf16x8 fa = *reinterpret_cast<const bf16x8*>(aq + ks * 64);
+#pragma unroll
+          for (int t = 0; t < DG_NBT; ++t) {
+            const bf16x8 fb = *reinterpret_cast<const bf16x8*>(bp[t] + boff + ks * 64);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, acc[t], 0, 0, 0);
+          }
+        }
+      }
+    // ---- lane (col, kg): block col of the group, product rows 4 kg .. 4 kg + 3 = phase kg, channels 0..3
+#pragma unroll
+    for (int t = 0; t < DG_NBT; ++t) {
+      if (!live[t] || ar[t] >= p.TBR || kg >= nph) continue;
+      const int prow = ar[t] * p.sh + kg / p.sw, pcol = bc[t] * p.sw + kg % p.sw;
+      bf16_t* o = ost + (size_t)prow * p.orow + pcol * p.Cin;
+      for (int c = 0; c < p.Cin; ++c) o[c] = from_f32<bf16_t>(acc[t][c]);
+    }
+    __syncthreads();   // the tile's dX pixels are staged
+    const int h0 = tr * p.TBR * p.sh, w0 = tc * p.TBC * p.sw;
+    const int rows = p.TBR * p.sh;
+    if (p.fast_store) {
+      const int cpr = p.orow * 2 / 16;                               // 16-byte pieces per staged row
+      const int wbytes = p.W * p.Cin * 2, b0 = w0 * p.Cin * 2;
+      for (int e = tid; e < rows * cpr; e += 256) {
+        const int r = e / cpr, c = e - r * cpr;
+        if (h0 + r < p.H && b0 + c * 16 + 16 <= wbytes)
+          *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(p.dx) + ((size_t)n * p.H + h0 + r) * wbytes + b0 + c * 16) =
+              *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(ost) + (size_t)r * p.orow * 2 + c * 16);
+      }
+    } else {
+      for (int e = tid; e < rows * p.orow; e += 256) {
+        const int r = e / p.orow, c = e - r * p.orow;
+        if (h0 + r < p.H && w0 * p.Cin + c < p.W * p.Cin)
+          p.dx[((size_t)n * p.H + h0 + r) * p.W * p.Cin + w0 * p.Cin + c] = ost[(size_t)r * p.orow + c];
+      }
+    }
+  }
+}
+
+// Wt[(phase, c)][(u, v, co)] from w' as [Cin][kH][kW][Cout]: phase (qh, qw) reaches dZ row a + dh(qh) - t through
+// window row i0(qh) + sh t, i.e. u = Dh - dh(qh) + t; zeros where a phase has no tap and in the rows of c >= Cin
+__global__ __launch_bounds__(256) void stem_dgrad_pack_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wt,
+                                                              int Cin, int Cout, int kH, int kW, int sh, int sw, int ph,
+                                                              int pw, int U, int V, int Dh, int Dw) {
+  const int KT = U * V * Cout;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= 16 * KT) return;
+  const int r = e / KT, k = e - r * KT;
+  const int co = k % Cout, uv = k / Cout, v = uv % V, u = uv / V;
+  const int phase = r >> 2, c = r & 3;
+  float val = 0.f;
+  if (phase < sh * sw && c < Cin) {
+    const int qh = phase / sw, qw = phase % sw;
+    const int i = (qh + ph) % sh + sh * (u - (Dh - (qh + ph) / sh));
+    const int j = (qw + pw) % sw + sw * (v - (Dw - (qw + pw) / sw));
+    if (u >= Dh - (qh + ph) / sh && v >= Dw - (qw + pw) / sw && i < kH && j < kW)
+      val = to_f32(w[(((size_t)c * kH + i) * kW + j) * Cout + co]);
+  }
+  wt[e] = from_f32<bf16_t>(val);
+}
+
+struct StemDgPlan { bool ok; size_t lds; int grid; };
+StemDgPlan stem_dg_plan(const Geom& g, StemDgParams* pp) {
+  StemDgPlan pl{false, 0, 0};
+  StemDgParams& p = *pp;
+  p = StemDgParams{};
+  if (g.sh > 2 || g.sw > 2 || g.Cout % 32 != 0 || g.Cout > 128) return pl;
+  p.N = g.N; p.H = g.Hin; p.W = g.Win; p.Cin = g.Cin; p.Cout = g.Cout; p.Ho = g.Hout; p.Wo = g.Wout; p.sh = g.sh; p.sw = g.sw;
+  // per phase q: first window row i0 = (q + pad) % s, its dZ row offset d = (q + pad) / s, taps T = ceil((k - i0) / s)
+  auto span = [](int k, int s, int pad, int* D, int* U) {
+    int dmax = 0;
+    for (int q = 0; q < s; ++q) dmax = (q + pad) / s > dmax ? (q + pad) / s : dmax;
+    int umax = 0;
+    for (int q = 0; q < s; ++q) {
+      const int i0 = (q + pad) % s;
+      if (i0 >= k) continue;
+      const int T = (k - i0 + s - 1) / s;
+      const int u = dmax - (q + pad) / s + T;
+      umax = u > umax ? u : umax;
+    }
+    *D = dmax; *U = umax;
+  };
+  span(g.kH, g.sh, g.ph, &p.Dh, &p.U);
+  span(g.kW, g.sw, g.pw, &p.Dw, &p.V);
+  if (p.U < 1 || p.V < 1) return pl;
+  p.KT = p.U * p.V * g.Cout;
+  p.wpitch = p.KT * 2 + 16;
+  if ((size_t)16 * p.wpitch > 36 * 1024) return pl;
+  p.pitch = g.Cout * 2 + 16;
+  const int brows = ceil_div(g.Hin, g.sh), bcols = ceil_div(g.Win, g.sw);
+  // tiles of 4 block rows x up to 32 block columns, the columns split evenly
+  p.nbc = ceil_div(bcols, 32);
+  p.TBC = ceil_div(bcols, p.nbc);
+  p.TBR = brows < 4 ? brows : 4;
+  p.nbr = ceil_div(brows, p.TBR);
+  p.PR = p.TBR + p.U - 1; p.PC = p.TBC + p.V - 1;
+  p.nbt = ceil_div(p.TBR * p.TBC, 16);
+  if (p.nbt > 4 * DG_NBT || p.PR * p.PC * (g.Cout / 8) > 256 * DG_PPT) return pl;
+  p.ntiles = g.N * p.nbr * p.nbc;
+  p.orow = p.TBC * g.sw * g.Cin;
+  p.fast_store = (p.orow * 2) % 16 == 0 && (g.Win * g.Cin * 2) % 16 == 0;
+  p.mTBC = (unsigned)((1ull << 32) / (unsigned)p.TBC + 1);
+  p.mPC = (unsigned)((1ull << 32) / (unsigned)p.PC + 1);
+  pl.lds = (size_t)16 * p.wpitch + (size_t)p.PR * p.PC * p.pitch + align_up((size_t)p.TBR * g.sh * p.orow * 2, 16);
+  if (pl.lds > 80 * 1024) return pl;   // two workgroups per CU
+  const int per_cu = (int)(160 * 1024 / pl.lds) < 2 ? 1 : 2;
+  pl.grid = p.ntiles < 256 * per_cu ? p.ntiles : 256 * per_cu;
+  pl.ok = true;
+  return pl;
+}
+
 bool stem_shape(const Geom& g, int dtype) {
   return dtype == CONVBN_BF16 && g.Cin <= 4 && g.kW <= 8 && g.kH <= 16 && g.Cout % 8 == 0 && g.Cout <= 128 && g.sw <= 4;
 }
@@ -462,6 +689,36 @@ hipError_t launch_wgrad_stem(const Geom& g, const void* x, const void* dz, float
   if (pl.x3) { if (pl.nco == 1) STEMWG(1, true); else if (pl.nco == 2) STEMWG(2, true); else STEMWG(4, true); }
   else { if (pl.nco == 1) STEMWG(1, false); else if (pl.nco == 2) STEMWG(2, false); else STEMWG(4, false); }
 #undef STEMWG
+  return hipGetLastError();
+}
+
+bool stem_dgrad_supported(const Geom& g, int dtype) {
+  if (!stem_shape(g, dtype)) return false;
+  StemDgParams p;
+  return stem_dg_plan(g, &p).ok;
+}
+size_t stem_dgrad_weight_bytes(const Geom& g) {
+  StemDgParams p;
+  return stem_dg_plan(g, &p).ok ? (size_t)16 * p.KT * 2 : 0;
+}
+// w_crsk: w' as [Cin][kH][kW][Cout]; wpack: stem_dgrad_weight_bytes() of scratch
+hipError_t launch_dgrad_stem(const Geom& g, const void* dz, const void* w_crsk, void* wpack, void* dx, hipStream_t st) {
+  StemDgParams p;
+  const StemDgPlan pl = stem_dg_plan(g, &p);
+  if (!pl.ok) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(stem_dgrad_pack_kernel, dim3(ceil_div(16 * p.KT, 256)), dim3(256), 0, st, (const bf16_t*)w_crsk,
+                     (bf16_t*)wpack, g.Cin, g.Cout, g.kH, g.kW, g.sh, g.sw, g.ph, g.pw, p.U, p.V, p.Dh, p.Dw);
+  hipError_t pe = hipGetLastError();
+  if (pe != hipSuccess) return pe;
+  p.dz = (const bf16_t*)dz; p.wt = (const bf16_t*)wpack; p.dx = (bf16_t*)dx;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stem_dgrad_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(stem_dgrad_kernel, dim3(pl.grid), dim3(256), pl.lds, st, p);
   return hipGetLastError();
 }
 
