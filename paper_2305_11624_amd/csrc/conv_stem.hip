@@ -439,6 +439,8 @@ struct StemDgParams {
 
 __device__ __forceinline__ int dg_div(int n, unsigned m, int d) { return d == 1 ? n : (int)__umulhi((unsigned)n, m); }
 
+// UU, VV, KS: the dZ neighbourhood and Cout / 32 at compile time (0: taken from the parameters)
+template <int UU, int VV, int KS>
 __global__ __launch_bounds__(256) void stem_dgrad_kernel(StemDgParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* wl = smem;                                         // [16][wpitch]
@@ -515,19 +517,27 @@ __global__ __launch_bounds__(256) void stem_dgrad_kernel(StemDgParams p) {
       acc[t] = f32x4s{0.f, 0.f, 0.f, 0.f};
     }
     const unsigned char* ap = wl + col * p.wpitch + kg * 16;
-    for (int u = 0; u < p.U; ++u)
-      for (int v = 0; v < p.V; ++v) {
-        const int boff = -(u * p.PC + v) * p.pitch;
-        const unsigned char* aq = ap + (u * p.V + v) * p.Cout * 2;
-        for (int ks = 0; ks < ksteps; ++ks) {
-          const bf16x8 fa = *reinterpret_cast<const bf16x8*>(aq + ks * 64);
+    auto step = [&](int u, int v, int ks, int nv, int cout2) {
+      const bf16x8 fa = *reinterpret_cast<const bf16x8*>(ap + (u * nv + v) * cout2 + ks * 64);
+      const int boff = -(u * p.PC + v) * p.pitch + ks * 64;
 #pragma unroll
-          for (int t = 0; t < DG_NBT; ++t) {
-            const bf16x8 fb = *reinterpret_cast<const bf16x8*>(bp[t] + boff + ks * 64);
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, acc[t], 0, 0, 0);
-          }
-        }
+      for (int t = 0; t < DG_NBT; ++t) {
+        const bf16x8 fb = *reinterpret_cast<const bf16x8*>(bp[t] + boff);
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, acc[t], 0, 0, 0);
       }
+    };
+    if constexpr (UU > 0) {
+#pragma unroll
+      for (int u = 0; u < UU; ++u)
+#pragma unroll
+        for (int v = 0; v < VV; ++v)
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) step(u, v, ks, VV, KS * 64);
+    } else {
+      for (int u = 0; u < p.U; ++u)
+        for (int v = 0; v < p.V; ++v)
+          for (int ks = 0; ks < ksteps; ++ks) step(u, v, ks, p.V, p.Cout * 2);
+    }
     // ---- lane (col, kg): block col of the group, product rows 4 kg .. 4 kg + 3 = phase kg, channels 0..3
 #pragma unroll
     for (int t = 0; t < DG_NBT; ++t) {
@@ -711,14 +721,20 @@ hipError_t launch_dgrad_stem(const Geom& g, const void* dz, const void* w_crsk, 
   hipError_t pe = hipGetLastError();
   if (pe != hipSuccess) return pe;
   p.dz = (const bf16_t*)dz; p.wt = (const bf16_t*)wpack; p.dx = (bf16_t*)dx;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stem_dgrad_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  hipLaunchKernelGGL(stem_dgrad_kernel, dim3(pl.grid), dim3(256), pl.lds, st, p);
+#define STEMDG(UUV, VVV, KSV)                                                                                         \
+  do {                                                                                                             \
+    static bool attr_set = false;                                                                                  \
+    if (!attr_set) {                                                                                               \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stem_dgrad_kernel<UUV, VVV, KSV>),          \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);                   \
+      if (e != hipSuccess) return e;                                                                               \
+      attr_set = true;                                                                                             \
+    }                                                                                                              \
+    hipLaunchKernelGGL((stem_dgrad_kernel<UUV, VVV, KSV>), dim3(pl.grid), dim3(256), pl.lds, st, p);                \
+  } while (0)
+  if (p.U == 4 && p.V == 4 && g.Cout == 64) STEMDG(4, 4, 2);   // the usual 7x7 / stride-2 stem with 64 channels: unrolled
+  else STEMDG(0, 0, 0);
+#undef STEMDG
   return hipGetLastError();
 }
 
