@@ -1,4 +1,4 @@
-"""Seeded sweep of randomly drawn (valid) shapes through the four blocks, each against the oracle: windows 1-7,
+"""Seeded sweep of randomly drawn (valid) shapes through the four blocks (the dense one also as a first layer), each against the oracle: windows 1-7,
 strides 1-3, all paddings, channel counts that do and do not fit the MFMA tiles, ragged images.  Catches planner
 corner cases the hand-picked shapes miss; every draw is reproducible from the seed."""
 import random
@@ -108,3 +108,22 @@ def test_grouped_block_random_shapes():
         r = GroupedRun(inp, mode=mode, keep_folded=keep, poison=True)
         r.step()
         compare(r.results(), oracle_grouped_block(inp), "bf16", tag=f"{shape} G={groups} {mode} keep={keep}")
+
+
+def test_first_layer_random_shapes():
+    """1-4 input channels: the first-layer kernels (forward, input gradient, weight gradient) where their plans fit,
+    the padded generic route elsewhere; row lengths that do and do not allow whole 16-byte pieces."""
+    from paper_2305_11624_amd.runner import BlockRun
+    rng = random.Random(20230515)
+    for it in range(32):
+        k = rng.choice([1, 3, 3, 5, 7, 7])
+        s = rng.choice([1, 2, 2])
+        p = rng.randint(0, k // 2)
+        cin, cout = rng.choice([1, 2, 3, 3, 3, 4]), rng.choice([32, 64, 64, 96, 128])
+        h, w = rng.randint(max(k, 6), 70), rng.choice([rng.randint(max(k, 6), 70), 4 * rng.randint(2, 40)])
+        shape = BlockShape(f"rs{it}", rng.randint(1, 3), cin, h, w, cout, k, s, p, "bf16", 8000 + it)
+        mode, keep, bias = rng.choice(["tune", "tune", "eval"]), rng.random() < 0.7, rng.random() < 0.5
+        inp = synth.make_inputs(shape, bias=bias)
+        r = BlockRun(inp, mode=mode, keep_folded=keep, poison=True)
+        r.step()
+        compare(r.results(), oracle_block(inp), "bf16", tag=f"{shape} {mode} keep={keep}")

@@ -20,7 +20,7 @@ SHAPES = [
     BlockShape("s_1x1_s2", 2, 64, 16, 16, 128, 1, 2, 0, "bf16", 54),
     BlockShape("s_deep7", 8, 256, 7, 7, 256, 3, 1, 1, "bf16", 55),
     BlockShape("s_f32", 2, 12, 10, 10, 20, 3, 1, 1, "f32", 56),
-    BlockShape("s_stem", 2, 3, 40, 40, 64, 7, 2, 3, "bf16", 58),       # 3 input channels: padded copies
+    BlockShape("s_stem", 2, 3, 40, 40, 64, 7, 2, 3, "bf16", 58),       # 3 input channels: the first-layer kernels
 ]
 
 
