@@ -120,7 +120,8 @@ __global__ __launch_bounds__(256) void g_wgrad_direct_kernel(const T* __restrict
 //     channels), tap after tap: no im2col.  A workgroup walks 2-d tiles (TR rows x TC columns of output pixels of
 //     one image) for NCH chunks of 32 channels; wave w owns chunk w % NCH and every (4 / NCH)-th group of 32 pixels.
 //   * The input gradient of a stride-1 block is the same kernel on dZ with the taps reversed and the weight read
-//     in its other order.
+//     in its other order; that of a strided block is one such launch per residue class of input positions, each
+//     with the taps that class has and a strided store.
 // n / d for 0 <= n < 65536 and 1 <= d < 65536 with m = 2^32 / d + 1 (exact: the error n (m d - 2^32) stays below 2^32)
 __device__ __forceinline__ int g_div(int n, unsigned m, int d) { return d == 1 ? n : (int)__umulhi((unsigned)n, m); }
 inline unsigned g_magic(int d) { return (unsigned)((1ull << 32) / (unsigned)d + 1); }
@@ -151,6 +152,10 @@ struct GcParams {
   int ncg, nworkers;    // channel-chunk groups (C / 32 / nch); workgroups per chunk group
   int lcg, lgpp;        // log2 of cg and of the 16-byte granules per patch pixel (4 nch)
   unsigned mTC, mPC;    // g_div multipliers of TC and PC
+  int wtaps;            // window positions of the weight tensor; position t of this launch reads its tap tapw[t]
+  int tapw[9];          // (forward: t; stride-1 input gradient: reversed; strided: one residue class's taps, reversed)
+  int OH, OW;           // the output tensor's rows and columns; pixel (r, c) of this launch is its pixel
+  int osh, osw, ooh, oow;   // (r osh + ooh, c osw + oow) -- a strided input gradient writes one residue class
 };
 
 template <int TAPS>
@@ -216,7 +221,7 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
         // all loads of the lane are in flight together
         uint4 v;
         if (p.mode == 0) {
-          const bf16_t* wr = p.w + ((size_t)(chunk * 32 + row) * TAPS + t) * p.cg;
+          const bf16_t* wr = p.w + ((size_t)(chunk * 32 + row) * p.wtaps + p.tapw[t]) * p.cg;
           if (p.cg == 4) {
             const uint2 r = *reinterpret_cast<const uint2*>(wr);
             v = make_uint4(r.x, r.y, r.x, r.y);
@@ -224,8 +229,7 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
             v = *reinterpret_cast<const uint4*>(wr + (k0 & (p.cg - 1)));
           }
         } else {
-          const int tf = TAPS - 1 - t;
-          v = *reinterpret_cast<const uint4*>(p.w + ((size_t)(row & (p.cg - 1)) * TAPS + tf) * p.C + chunk * 32 + k0);
+          v = *reinterpret_cast<const uint4*>(p.w + ((size_t)(row & (p.cg - 1)) * p.wtaps + p.tapw[t]) * p.C + chunk * 32 + k0);
         }
         v.x = lo ? v.x : 0u; v.y = lo ? v.y : 0u;
         v.z = hi ? v.z : 0u; v.w = hi ? v.w : 0u;
@@ -279,7 +283,8 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
         const int p2 = wt * 32 + sp;
         const int r2 = g_div(p2, p.mTC, p.TC), c2 = p2 - r2 * p.TC;
         if (r2 < rows && c2 < cols)
-          *reinterpret_cast<uint4*>(p.out + (((size_t)n * p.Ho + r0 + r2) * p.Wo + c0 + c2) * p.C + chunk * 32 + gq * 8) = v;
+          *reinterpret_cast<uint4*>(p.out + (((size_t)n * p.OH + (r0 + r2) * p.osh + p.ooh) * p.OW + (c0 + c2) * p.osw + p.oow) * p.C +
+                                    chunk * 32 + gq * 8) = v;
       }
     }
   }
@@ -294,9 +299,12 @@ GcPlan gc_plan(int N, int C, int cg, int in_h, int in_w, int out_h, int out_w, i
   p = GcParams{};
   if (C % 32 != 0 || (cg != 4 && cg != 8 && cg != 16 && cg != 32)) return pl;
   const int taps = kH * kW;
-  if (taps != 1 && taps != 9) return pl;
+  if (taps != 1 && taps != 2 && taps != 3 && taps != 4 && taps != 6 && taps != 9) return pl;
   p.N = N; p.Hi = in_h; p.Wi = in_w; p.C = C; p.Ho = out_h; p.Wo = out_w; p.kH = kH; p.kW = kW;
   p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.cg = cg;
+  p.wtaps = taps;
+  for (int t = 0; t < taps; ++t) p.tapw[t] = t;
+  p.OH = out_h; p.OW = out_w; p.osh = 1; p.osw = 1; p.ooh = 0; p.oow = 0;
   const int nchunks = C / 32;
   double best = 0;
   for (int ntc = ceil_div(out_w, 64); ntc <= ceil_div(out_w, 64) + 3 && ntc <= out_w; ++ntc) {
@@ -351,13 +359,61 @@ GcPlan gc_dgrad_plan(const Geom& g, int groups, int dtype, GcParams* p) {
     return GcPlan{false, 0, 0};
   GcPlan pl = gc_plan(g.N, g.Cin, g.Cin / groups, g.Hout, g.Wout, g.Hin, g.Win, g.kH, g.kW, 1, 1, g.kH - 1 - g.ph,
                       g.kW - 1 - g.pw, p);
+  if (!pl.ok) return pl;   // (also: tapw has room for the 9 positions a plan accepts, not for any window)
   p->mode = 1;
+  for (int t = 0; t < g.kH * g.kW; ++t) p->tapw[t] = g.kH * g.kW - 1 - t;
   return pl;
+}
+// One dimension of a strided input gradient: the input positions h = s a + q (residue class q) read dZ positions
+// a + d - t through window rows i0 + s t, t < T.  As a stride-1 window over dZ: T positions, padding T - 1 - d,
+// position i' reading window row i0 + s (T - 1 - i').
+struct GcClassDim { int i0, d, T, count; };
+GcClassDim gc_class_dim(int q, int s, int pad, int k, int in_size) {
+  GcClassDim c;
+  c.i0 = (q + pad) % s;
+  c.d = (q + pad) / s;
+  c.T = c.i0 < k ? (k - c.i0 + s - 1) / s : 0;
+  c.count = in_size > q ? (in_size - q + s - 1) / s : 0;
+  return c;
+}
+// dX restricted to the residue class (qh, qw) of a strided block: the forward kernel on dZ with that class's taps
+GcPlan gc_dgrad_class_plan(const Geom& g, int groups, int dtype, int qh, int qw, GcParams* p) {
+  if (dtype != CONVBN_BF16 || g.Cin != g.Cout) return GcPlan{false, 0, 0};
+  const GcClassDim a = gc_class_dim(qh, g.sh, g.ph, g.kH, g.Hin), b = gc_class_dim(qw, g.sw, g.pw, g.kW, g.Win);
+  if (a.T < 1 || b.T < 1 || a.count < 1 || b.count < 1) return GcPlan{false, 0, 0};
+  GcPlan pl = gc_plan(g.N, g.Cin, g.Cin / groups, g.Hout, g.Wout, a.count, b.count, a.T, b.T, 1, 1, a.T - 1 - a.d,
+                      b.T - 1 - b.d, p);
+  if (!pl.ok) return pl;
+  p->mode = 1;
+  p->wtaps = g.kH * g.kW;
+  for (int i = 0; i < a.T; ++i)
+    for (int j = 0; j < b.T; ++j)
+      p->tapw[i * b.T + j] = (a.i0 + g.sh * (a.T - 1 - i)) * g.kW + b.i0 + g.sw * (b.T - 1 - j);
+  p->OH = g.Hin; p->OW = g.Win; p->osh = g.sh; p->osw = g.sw; p->ooh = qh; p->oow = qw;
+  return pl;
+}
+bool gc_dgrad_strided_ok(const Geom& g, int groups, int dtype) {
+  if ((g.sh == 1 && g.sw == 1) || g.sh > 2 || g.sw > 2) return false;
+  GcParams p;
+  for (int qh = 0; qh < g.sh; ++qh)
+    for (int qw = 0; qw < g.sw; ++qw) {
+      if (g.Hin <= qh || g.Win <= qw) continue;             // an empty class
+      if (!gc_dgrad_class_plan(g, groups, dtype, qh, qw, &p).ok) return false;
+    }
+  return true;
 }
 
 hipError_t gc_launch(const GcPlan& pl, const GcParams& p, hipStream_t st) {
-  if (p.kH * p.kW == 9) hipLaunchKernelGGL(g_conv_mfma_kernel<9>, dim3(pl.grid), dim3(256), pl.lds, st, p);
-  else hipLaunchKernelGGL(g_conv_mfma_kernel<1>, dim3(pl.grid), dim3(256), pl.lds, st, p);
+#define GCL(T) hipLaunchKernelGGL(g_conv_mfma_kernel<T>, dim3(pl.grid), dim3(256), pl.lds, st, p)
+  switch (p.kH * p.kW) {
+    case 1: GCL(1); break;
+    case 2: GCL(2); break;
+    case 3: GCL(3); break;
+    case 4: GCL(4); break;
+    case 6: GCL(6); break;
+    default: GCL(9); break;
+  }
+#undef GCL
   return hipGetLastError();
 }
 
@@ -641,6 +697,17 @@ hipError_t launch_g_dgrad(const Geom& g, int groups, int dtype, const void* dz, 
   if (pl.ok) {
     gp.in = (const bf16_t*)dz; gp.w = (const bf16_t*)w_crsk; gp.bias = nullptr; gp.out = (bf16_t*)dx;
     return gc_launch(pl, gp, st);
+  }
+  if (gc_dgrad_strided_ok(g, groups, dtype)) {   // one launch per residue class of input positions
+    for (int qh = 0; qh < g.sh; ++qh)
+      for (int qw = 0; qw < g.sw; ++qw) {
+        if (g.Hin <= qh || g.Win <= qw) continue;
+        const GcPlan cp = gc_dgrad_class_plan(g, groups, dtype, qh, qw, &gp);
+        gp.in = (const bf16_t*)dz; gp.w = (const bf16_t*)w_crsk; gp.bias = nullptr; gp.out = (bf16_t*)dx;
+        const hipError_t e = gc_launch(cp, gp, st);
+        if (e != hipSuccess) return e;
+      }
+    return hipSuccess;
   }
   const size_t total = (size_t)g.Min * g.Cin;
   const dim3 grid((unsigned)((total + 255) / 256));
