@@ -42,11 +42,13 @@ WORKLOADS = {
 DW_SHAPES = [("dw_112_s2", 32, 96, 112, 112, 3, 2, 1), ("dw_56", 32, 144, 56, 56, 3, 1, 1),
              ("dw_14", 32, 576, 14, 14, 3, 1, 1)]
 
-# grouped 3x3 layers of an aggregated-transform network (32 groups of 4, 8, 16, 32 channels in its four stages) at
+# grouped 3x3 layers of an aggregated-transform network (32 groups of 4, 8, 16, 32 channels in its four stages, and
+# the stride-2 layer that opens its second stage) at
 # N = 32 (stand-ins for the ResNeXt / RegNet rows of the paper's model tables): name, N, C, H, W, window, stride,
 # padding, groups
-GROUPED_SHAPES = [("gx_56", 32, 128, 56, 56, 3, 1, 1, 32), ("gx_28", 32, 256, 28, 28, 3, 1, 1, 32),
-                  ("gx_14", 32, 512, 14, 14, 3, 1, 1, 32), ("gx_7", 32, 1024, 7, 7, 3, 1, 1, 32)]
+GROUPED_SHAPES = [("gx_56", 32, 128, 56, 56, 3, 1, 1, 32), ("gx_56_s2", 32, 256, 56, 56, 3, 2, 1, 32),
+                  ("gx_28", 32, 256, 28, 28, 3, 1, 1, 32), ("gx_14", 32, 512, 14, 14, 3, 1, 1, 32),
+                  ("gx_7", 32, 1024, 7, 7, 3, 1, 1, 32)]
 
 # 2x up-sampling blocks of an encoder-decoder network (stand-ins for the UNet rows of Sec. 4.3): name, N, Cin, Hin,
 # Win, Cout, window, stride, padding
