@@ -76,18 +76,20 @@ def test_one_group_matches_the_dense_block():
         assert (res[k] - dense[k]).abs().max() <= 2e-2 * ref[k].__abs__().max()
 
 
-def test_full_size_layer():
-    """A grouped layer at network size: 32 groups of 4 channels at 56x56, N = 32 (the first stage of an
-    aggregated-transform network), sampled against the oracle run on the first two images (the block is independent
-    across images except for the parameter gradients, compared on a two-image problem of their own)."""
-    shape = BlockShape("g_full", 32, 128, 56, 56, 128, 3, 1, 1, "bf16", 128)
+@pytest.mark.parametrize("name,C,H,stride", [("gx_56", 128, 56, 1), ("gx_56_s2", 256, 56, 2), ("gx_14", 512, 14, 1),
+                                             ("gx_7", 1024, 7, 1)])
+def test_full_size_layers(name, C, H, stride):
+    """The benchmark's grouped layers at their full size (32 groups, N = 32, the launch configuration the benchmark
+    times), sampled against the oracle run on the first two images (the block is independent across images except
+    for the parameter gradients, compared on a two-image problem of their own)."""
+    shape = BlockShape(name, 32, C, H, H, C, 3, stride, 1, "bf16", 128)
     inp = synth.make_grouped_inputs(shape, 32)
     res = _run(inp)
     small = {k: (v[:2] if k in ("x", "dy") else v) for k, v in inp.items()}
-    small["shape"] = BlockShape("g_full2", 2, 128, 56, 56, 128, 3, 1, 1, "bf16", 128)
+    small["shape"] = BlockShape(name + "_n2", 2, C, H, H, C, 3, stride, 1, "bf16", 128)
     ref = oracle_grouped_block(small)
-    compare({k: res[k][:2] for k in ("Z", "dX")}, ref, "bf16", keys=("Z", "dX"), tag="g_full[:2]")
-    compare(_run(small), ref, "bf16", keys=KEYS, tag="g_full2")
+    compare({k: res[k][:2] for k in ("Z", "dX")}, ref, "bf16", keys=("Z", "dX"), tag=name + "[:2]")
+    compare(_run(small), ref, "bf16", keys=KEYS, tag=name + "_n2")
 
 
 def test_errors():
