@@ -134,7 +134,8 @@ __device__ __forceinline__ int g_logical_block() {
 }
 
 // Small tiles on purpose: a workgroup's phases (fetch, LDS, multiply, store) run one after the other, and what hides
-// them is other workgroups on the same CU -- four fit with these sizes, and the fetch registers stay few.
+// them is the other workgroup on the same CU and the next tile's fetch -- a workgroup should walk several tiles, and
+// the fetch registers stay few.
 constexpr int GC_PPT = 8;                  // most 16-byte patch items a thread fetches per tile
 constexpr size_t GC_PATCH_MAX = 24 * 1024; // patch bytes (+ 10 KB of output staging)
 
@@ -340,7 +341,9 @@ GcPlan gc_plan(int N, int C, int cg, int in_h, int in_w, int out_h, int out_w, i
   p.ntiles = N * p.ntr * p.ntc;
   p.ncg = nchunks / p.nch;
   pl.lds = (size_t)p.PR * p.PC * p.pitch + 4 * 32 * 80;
-  const int per_cu = (int)(160 * 1024 / pl.lds) < 4 ? (int)(160 * 1024 / pl.lds) : 4;
+  // two persistent workgroups per CU, each walking several tiles (measured: 1 -> 39, 2 -> 35, 4 -> 41, 8 -> 48 us for
+  // fold + forward on 128 channels at 56 x 56: more workgroups start and finish in step and leave a longer tail)
+  const int per_cu = (int)(160 * 1024 / pl.lds) < 2 ? 1 : 2;
   int workers = ceil_div(256 * per_cu, p.ncg);
   if (workers > p.ntiles) workers = p.ntiles;
   p.nworkers = workers;
