@@ -396,8 +396,9 @@ StemWgPlan stem_wg_plan(const Geom& g, StemWgParams* pp) {
   pl.lds = align_up((size_t)g.kH * p.prow, 16) + (size_t)TPX * p.zpitch;
   if (pl.lds < 1024) pl.lds = 1024;   // the channel sums meet in the first KB at the end
   if (pl.lds > 64 * 1024) return pl;
-  // one workgroup per CU: every workgroup writes a full fp32 slice of dw', which the fold-back has to sum
-  pl.grid = p.ntiles < 256 ? p.ntiles : 256;
+  // two workgroups per CU (a lone one leaves the CU idle while it waits; 65 -> 48 us on the 7x7 stem); every
+  // workgroup writes a full fp32 slice of dw', which the fold-back has to sum, so not more
+  pl.grid = p.ntiles < 512 ? p.ntiles : 512;
   pl.x3 = x3;
   pl.ok = true;
   return pl;

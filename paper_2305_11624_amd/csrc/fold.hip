@@ -196,8 +196,8 @@ __device__ __forceinline__ void store4(bf16_t* p, const float (&w)[4]) {
 // `nsplit` partial copies of a column lie far apart in memory, so every load is a latency round trip of
 // its own.  Short rows (fewer than 256 columns): a thread keeps sixteen copies of one column in
 // flight, the copies are divided over as many thread groups as fit the block, and the groups meet in
-// LDS.  Long rows: a column per thread, four copies in flight, columns in sequence.  Otherwise one
-// element per thread, all partials in sequence.
+// LDS.  Long rows: a column per thread, four copies in flight, columns in sequence.  Rows whose length is not a
+// multiple of 4: one element per thread; short ones divide the copies over thread groups in the same way.
 template <typename T, bool VEC, int NTHR>
 __global__ __launch_bounds__(NTHR) void fold_back_kernel(
     const float* __restrict__ part, int nsplit, const float* __restrict__ r_part, int nrpart,
@@ -207,6 +207,7 @@ __global__ __launch_bounds__(NTHR) void fold_back_kernel(
     float* __restrict__ dbeta) {
   constexpr int NSL = NTHR / 64;
   __shared__ float4 red4[VEC ? NTHR : 1];
+  __shared__ float reds[VEC ? 1 : NTHR];
   __shared__ float red[NSL];
   const int co = blockIdx.x;
   const int tid = threadIdx.x;
@@ -282,6 +283,29 @@ __global__ __launch_bounds__(NTHR) void fold_back_kernel(
         v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
       }
       finish(c, v);
+    }
+  } else if (K * 2 <= NTHR) {
+    // short rows whose length is not a multiple of 4 (a first layer: 7 x 7 x 3): thread -> (element k, group g of the
+    // partial copies), eight copies in flight per thread, the groups meet in LDS
+    const int G = NTHR / K;
+    const int k = tid % K, g = tid / K;
+    float v = 0.f;
+    if (g < G) {
+      const float* col = part + (size_t)co * K + k;
+      for (int sp0 = g; sp0 < nsplit; sp0 += 8 * G) {
+        float a[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a[j] = sp0 + j * G < nsplit ? col[(size_t)(sp0 + j * G) * P] : 0.f;
+        v += ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+      }
+    }
+    reds[tid] = v;
+    __syncthreads();
+    if (g == 0) {
+      for (int l = 1; l < G; ++l) v += reds[l * K + k];
+      const size_t idx = (size_t)co * K + k;
+      dW[idx] = from_f32<T>(s * v);
+      dot += v * to_f32(W[idx]);
     }
   } else {
     for (int k = tid; k < K; k += NTHR) {
@@ -628,13 +652,16 @@ hipError_t launch_fold_back(const Geom& g, int dtype, const float* dwf_part, int
   // few output channels and many partial copies: a 1024-thread block per channel (16 waves share
   // the copies) keeps enough loads in flight on the few CUs such a grid occupies
   const bool wide = vec && g.Cout <= 128 && nsplit >= 16 && (g.K >> 2) < 256;
+  const bool wide_scalar = !vec && g.Cout <= 128 && nsplit >= 16 && g.K * 2 <= 1024;   // (a first layer's 7 x 7 x 3 rows)
   if (dtype == CONVBN_BF16) {
     if (wide) FB_LAUNCH(bf16_t, true, 1024);
     else if (vec) FB_LAUNCH(bf16_t, true, 256);
+    else if (wide_scalar) FB_LAUNCH(bf16_t, false, 1024);
     else FB_LAUNCH(bf16_t, false, 256);
   } else {
     if (wide) FB_LAUNCH(float, true, 1024);
     else if (vec) FB_LAUNCH(float, true, 256);
+    else if (wide_scalar) FB_LAUNCH(float, false, 1024);
     else FB_LAUNCH(float, false, 256);
   }
 #undef FB_LAUNCH
