@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void fold_t_kernel(const T* __restrict__ W, co
   }
 }
 
-constexpr int FB_ROWS = 32;   // (ci, tap) rows per workgroup of the fold-back
+constexpr int FB_ROWS = 8;   // (ci, tap) rows per workgroup of the fold-back
 
 __device__ __forceinline__ void load4(const float* p, float (&v)[4]) {
   const float4 t = *reinterpret_cast<const float4*>(p);
@@ -158,8 +158,19 @@ __global__ __launch_bounds__(256) void fold_back_t_finish_kernel(const float* __
   const int co = blockIdx.x * 16 + c;
   float dot = 0.f, r = 0.f;
   if (co < Co) {
-    for (int k = g; k < nchunks; k += 16) dot += dot_part[(size_t)k * Co + co];
-    for (int k = g; k < nrpart; k += 16) r += r_part[(size_t)k * Co + co];
+    // eight loads in flight per thread: the rows lie Co floats apart, each load is a round trip of its own
+    for (int k = g; k < nchunks; k += 16 * 8) {
+      float a[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) a[j] = k + 16 * j < nchunks ? dot_part[(size_t)(k + 16 * j) * Co + co] : 0.f;
+      dot += ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+    }
+    for (int k = g; k < nrpart; k += 16 * 8) {
+      float a[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) a[j] = k + 16 * j < nrpart ? r_part[(size_t)(k + 16 * j) * Co + co] : 0.f;
+      r += ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+    }
   }
   red[0][g][c] = dot;
   red[1][g][c] = r;
