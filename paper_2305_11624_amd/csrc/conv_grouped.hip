@@ -120,8 +120,8 @@ __global__ __launch_bounds__(256) void g_wgrad_direct_kernel(const T* __restrict
 //     channels), tap after tap: no im2col.  A workgroup walks 2-d tiles (TR rows x TC columns of output pixels of
 //     one image) for NCH chunks of 32 channels; wave w owns chunk w % NCH and every (4 / NCH)-th group of 32 pixels.
 //   * The input gradient of a stride-1 block is the same kernel on dZ with the taps reversed and the weight read
-//     in its other order; that of a strided block is one such launch per residue class of input positions, each
-//     with the taps that class has and a strided store.
+//     in its other order; that of a strided block runs the residue classes of input positions side by side
+//     (blockIdx.y), each with the taps that class has and a strided store.
 // n / d for 0 <= n < 65536 and 1 <= d < 65536 with m = 2^32 / d + 1 (exact: the error n (m d - 2^32) stays below 2^32)
 __device__ __forceinline__ int g_div(int n, unsigned m, int d) { return d == 1 ? n : (int)__umulhi((unsigned)n, m); }
 inline unsigned g_magic(int d) { return (unsigned)((1ull << 32) / (unsigned)d + 1); }
@@ -154,9 +154,14 @@ struct GcParams {
   int lcg, lgpp;        // log2 of cg and of the 16-byte granules per patch pixel (4 nch)
   unsigned mTC, mPC;    // g_div multipliers of TC and PC
   int wtaps;            // window positions of the weight tensor; position t of this launch reads its tap tapw[t]
-  int tapw[9];          // (forward: t; stride-1 input gradient: reversed; strided: one residue class's taps, reversed)
+  int tapw[9];          // (forward: t; stride-1 input gradient: reversed), -1: no tap (zeros)
   int OH, OW;           // the output tensor's rows and columns; pixel (r, c) of this launch is its pixel
-  int osh, osw, ooh, oow;   // (r osh + ooh, c osw + oow) -- a strided input gradient writes one residue class
+  int osh, osw, ooh, oow;   // (r osh + ooh, c osw + oow)
+  // A strided input gradient runs its residue classes of input positions as blockIdx.y = 0 .. ncls - 1 of one launch:
+  // class q has its own padding, extent, output offset and taps (the fields above hold class 0 / the common values).
+  int ncls;
+  int cph[4], cpw[4], cHo[4], cWo[4], cooh[4], coow[4];
+  int ctapw[4][9];
 };
 
 template <int TAPS>
@@ -166,6 +171,10 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
   const int kb = lane >> 5, px = lane & 31;
   const int lb = g_logical_block();
   const int cgrp = lb % p.ncg, worker = lb / p.ncg;
+  const int cls = blockIdx.y;                        // residue class (0 unless a strided input gradient)
+  const int ph = p.ncls > 1 ? p.cph[cls] : p.ph, pw = p.ncls > 1 ? p.cpw[cls] : p.pw;
+  const int Ho = p.ncls > 1 ? p.cHo[cls] : p.Ho, Wo = p.ncls > 1 ? p.cWo[cls] : p.Wo;
+  const int ooh = p.ncls > 1 ? p.cooh[cls] : p.ooh, oow = p.ncls > 1 ? p.coow[cls] : p.oow;
   const int cl = wave % p.nch;                      // this wave's chunk inside the workgroup's channels
   const int chunk = cgrp * p.nch + cl;              // ... and in the tensor
   const int wstep = 4 / p.nch, wfirst = wave / p.nch;
@@ -188,7 +197,7 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
     const int tc = tile % p.ntc;
     const int t2 = tile / p.ntc;
     const int tr = t2 % p.ntr, n = t2 / p.ntr;
-    const int h0 = tr * p.TR * p.sh - p.ph, w0 = tc * p.TC * p.sw - p.pw;
+    const int h0 = tr * p.TR * p.sh - ph, w0 = tc * p.TC * p.sw - pw;
 #pragma unroll
     for (int k = 0; k < GC_PPT; ++k) {
       const int h = h0 + ipr[k], w = w0 + (ipc[k] & 0xffff), gq = ipc[k] >> 16;
@@ -217,12 +226,14 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
         const int k0 = ks * 16 + kb * 8;             // first of the 8 reduced channels (local)
-        const bool lo = (k0 >> p.lcg) == rgrp, hi = ((k0 + 4) >> p.lcg) == rgrp;
+        const int tw = p.ncls > 1 ? p.ctapw[cls][t] : p.tapw[t];
+        const int twc = tw < 0 ? 0 : tw;                 // (no tap: load tap 0 and drop it)
+        const bool lo = tw >= 0 && (k0 >> p.lcg) == rgrp, hi = tw >= 0 && ((k0 + 4) >> p.lcg) == rgrp;
         // every address below is inside the weight whatever the masks say: load first, zero afterwards, so that
         // all loads of the lane are in flight together
         uint4 v;
         if (p.mode == 0) {
-          const bf16_t* wr = p.w + ((size_t)(chunk * 32 + row) * p.wtaps + p.tapw[t]) * p.cg;
+          const bf16_t* wr = p.w + ((size_t)(chunk * 32 + row) * p.wtaps + twc) * p.cg;
           if (p.cg == 4) {
             const uint2 r = *reinterpret_cast<const uint2*>(wr);
             v = make_uint4(r.x, r.y, r.x, r.y);
@@ -230,7 +241,7 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
             v = *reinterpret_cast<const uint4*>(wr + (k0 & (p.cg - 1)));
           }
         } else {
-          v = *reinterpret_cast<const uint4*>(p.w + ((size_t)(row & (p.cg - 1)) * p.wtaps + p.tapw[t]) * p.C + chunk * 32 + k0);
+          v = *reinterpret_cast<const uint4*>(p.w + ((size_t)(row & (p.cg - 1)) * p.wtaps + twc) * p.C + chunk * 32 + k0);
         }
         v.x = lo ? v.x : 0u; v.y = lo ? v.y : 0u;
         v.z = hi ? v.z : 0u; v.w = hi ? v.w : 0u;
@@ -248,7 +259,7 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
     const int t2 = tile / p.ntc;
     const int tr = t2 % p.ntr, n = t2 / p.ntr;
     const int r0 = tr * p.TR, c0 = tc * p.TC;
-    const int rows = min(p.TR, p.Ho - r0), cols = min(p.TC, p.Wo - c0);
+    const int rows = min(p.TR, Ho - r0), cols = min(p.TC, Wo - c0);
     __syncthreads();   // every wave is done with the previous patch
     stash();
     fetch(tile + p.nworkers);
@@ -284,7 +295,7 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
         const int p2 = wt * 32 + sp;
         const int r2 = g_div(p2, p.mTC, p.TC), c2 = p2 - r2 * p.TC;
         if (r2 < rows && c2 < cols)
-          *reinterpret_cast<uint4*>(p.out + (((size_t)n * p.OH + (r0 + r2) * p.osh + p.ooh) * p.OW + (c0 + c2) * p.osw + p.oow) * p.C +
+          *reinterpret_cast<uint4*>(p.out + (((size_t)n * p.OH + (r0 + r2) * p.osh + ooh) * p.OW + (c0 + c2) * p.osw + oow) * p.C +
                                     chunk * 32 + gq * 8) = v;
       }
     }
@@ -306,6 +317,7 @@ GcPlan gc_plan(int N, int C, int cg, int in_h, int in_w, int out_h, int out_w, i
   p.wtaps = taps;
   for (int t = 0; t < taps; ++t) p.tapw[t] = t;
   p.OH = out_h; p.OW = out_w; p.osh = 1; p.osw = 1; p.ooh = 0; p.oow = 0;
+  p.ncls = 1;
   const int nchunks = C / 32;
   double best = 0;
   for (int ntc = ceil_div(out_w, 64); ntc <= ceil_div(out_w, 64) + 3 && ntc <= out_w; ++ntc) {
@@ -368,46 +380,54 @@ GcPlan gc_dgrad_plan(const Geom& g, int groups, int dtype, GcParams* p) {
   return pl;
 }
 // One dimension of a strided input gradient: the input positions h = s a + q (residue class q) read dZ positions
-// a + d - t through window rows i0 + s t, t < T.  As a stride-1 window over dZ: T positions, padding T - 1 - d,
-// position i' reading window row i0 + s (T - 1 - i').
-struct GcClassDim { int i0, d, T, count; };
-GcClassDim gc_class_dim(int q, int s, int pad, int k, int in_size) {
+// a + d - t through window rows i0 + s t (those below k).  With T the largest number of taps of any class, every
+// class is a stride-1 window of T positions over dZ with padding T - 1 - d, position i' reading window row
+// i0 + s (T - 1 - i') -- or nothing, where that row does not exist.
+struct GcClassDim { int i0, d, count; };
+GcClassDim gc_class_dim(int q, int s, int pad, int in_size) {
   GcClassDim c;
   c.i0 = (q + pad) % s;
   c.d = (q + pad) / s;
-  c.T = c.i0 < k ? (k - c.i0 + s - 1) / s : 0;
   c.count = in_size > q ? (in_size - q + s - 1) / s : 0;
   return c;
 }
-// dX restricted to the residue class (qh, qw) of a strided block: the forward kernel on dZ with that class's taps
-GcPlan gc_dgrad_class_plan(const Geom& g, int groups, int dtype, int qh, int qw, GcParams* p) {
-  if (dtype != CONVBN_BF16 || g.Cin != g.Cout) return GcPlan{false, 0, 0};
-  const GcClassDim a = gc_class_dim(qh, g.sh, g.ph, g.kH, g.Hin), b = gc_class_dim(qw, g.sw, g.pw, g.kW, g.Win);
-  if (a.T < 1 || b.T < 1 || a.count < 1 || b.count < 1) return GcPlan{false, 0, 0};
-  GcPlan pl = gc_plan(g.N, g.Cin, g.Cin / groups, g.Hout, g.Wout, a.count, b.count, a.T, b.T, 1, 1, a.T - 1 - a.d,
-                      b.T - 1 - b.d, p);
+int gc_class_taps(int s, int pad, int k) {   // most taps a class has
+  int T = 1;
+  for (int q = 0; q < s; ++q) {
+    const int i0 = (q + pad) % s;
+    if (i0 < k && (k - i0 + s - 1) / s > T) T = (k - i0 + s - 1) / s;
+  }
+  return T;
+}
+// dX of a strided block: the forward kernel on dZ, one residue class of input positions per blockIdx.y
+GcPlan gc_dgrad_strided_plan(const Geom& g, int groups, int dtype, GcParams* p) {
+  if (dtype != CONVBN_BF16 || g.Cin != g.Cout || (g.sh == 1 && g.sw == 1) || g.sh > 2 || g.sw > 2) return GcPlan{false, 0, 0};
+  const int Th = gc_class_taps(g.sh, g.ph, g.kH), Tw = gc_class_taps(g.sw, g.pw, g.kW);
+  GcPlan pl = gc_plan(g.N, g.Cin, g.Cin / groups, g.Hout, g.Wout, ceil_div(g.Hin, g.sh), ceil_div(g.Win, g.sw), Th, Tw, 1, 1,
+                      0, 0, p);
   if (!pl.ok) return pl;
   p->mode = 1;
   p->wtaps = g.kH * g.kW;
-  for (int i = 0; i < a.T; ++i)
-    for (int j = 0; j < b.T; ++j)
-      p->tapw[i * b.T + j] = (a.i0 + g.sh * (a.T - 1 - i)) * g.kW + b.i0 + g.sw * (b.T - 1 - j);
-  p->OH = g.Hin; p->OW = g.Win; p->osh = g.sh; p->osw = g.sw; p->ooh = qh; p->oow = qw;
-  return pl;
-}
-bool gc_dgrad_strided_ok(const Geom& g, int groups, int dtype) {
-  if ((g.sh == 1 && g.sw == 1) || g.sh > 2 || g.sw > 2) return false;
-  GcParams p;
+  p->OH = g.Hin; p->OW = g.Win; p->osh = g.sh; p->osw = g.sw;
+  p->ncls = g.sh * g.sw;
   for (int qh = 0; qh < g.sh; ++qh)
     for (int qw = 0; qw < g.sw; ++qw) {
-      if (g.Hin <= qh || g.Win <= qw) continue;             // an empty class
-      if (!gc_dgrad_class_plan(g, groups, dtype, qh, qw, &p).ok) return false;
+      const int c = qh * g.sw + qw;
+      const GcClassDim a = gc_class_dim(qh, g.sh, g.ph, g.Hin), b = gc_class_dim(qw, g.sw, g.pw, g.Win);
+      p->cph[c] = Th - 1 - a.d; p->cpw[c] = Tw - 1 - b.d;
+      p->cHo[c] = a.count; p->cWo[c] = b.count;
+      p->cooh[c] = qh; p->coow[c] = qw;
+      for (int i = 0; i < Th; ++i)
+        for (int j = 0; j < Tw; ++j) {
+          const int wi = a.i0 + g.sh * (Th - 1 - i), wj = b.i0 + g.sw * (Tw - 1 - j);
+          p->ctapw[c][i * Tw + j] = (wi < g.kH && wj < g.kW) ? wi * g.kW + wj : -1;
+        }
     }
-  return true;
+  return pl;
 }
 
 hipError_t gc_launch(const GcPlan& pl, const GcParams& p, hipStream_t st) {
-#define GCL(T) hipLaunchKernelGGL(g_conv_mfma_kernel<T>, dim3(pl.grid), dim3(256), pl.lds, st, p)
+#define GCL(T) hipLaunchKernelGGL(g_conv_mfma_kernel<T>, dim3(pl.grid, p.ncls), dim3(256), pl.lds, st, p)
   switch (p.kH * p.kW) {
     case 1: GCL(1); break;
     case 2: GCL(2); break;
@@ -701,16 +721,10 @@ hipError_t launch_g_dgrad(const Geom& g, int groups, int dtype, const void* dz, 
     gp.in = (const bf16_t*)dz; gp.w = (const bf16_t*)w_crsk; gp.bias = nullptr; gp.out = (bf16_t*)dx;
     return gc_launch(pl, gp, st);
   }
-  if (gc_dgrad_strided_ok(g, groups, dtype)) {   // one launch per residue class of input positions
-    for (int qh = 0; qh < g.sh; ++qh)
-      for (int qw = 0; qw < g.sw; ++qw) {
-        if (g.Hin <= qh || g.Win <= qw) continue;
-        const GcPlan cp = gc_dgrad_class_plan(g, groups, dtype, qh, qw, &gp);
-        gp.in = (const bf16_t*)dz; gp.w = (const bf16_t*)w_crsk; gp.bias = nullptr; gp.out = (bf16_t*)dx;
-        const hipError_t e = gc_launch(cp, gp, st);
-        if (e != hipSuccess) return e;
-      }
-    return hipSuccess;
+  const GcPlan sp = gc_dgrad_strided_plan(g, groups, dtype, &gp);   // the residue classes of input positions in one launch
+  if (sp.ok) {
+    gp.in = (const bf16_t*)dz; gp.w = (const bf16_t*)w_crsk; gp.bias = nullptr; gp.out = (bf16_t*)dx;
+    return gc_launch(sp, gp, st);
   }
   const size_t total = (size_t)g.Min * g.Cin;
   const dim3 grid((unsigned)((total + 255) / 256));
