@@ -136,7 +136,7 @@ __device__ __forceinline__ int g_logical_block() {
 // Small tiles on purpose: a workgroup's phases (fetch, LDS, multiply, store) run one after the other, and what hides
 // them is the other workgroup on the same CU and the next tile's fetch -- a workgroup should walk several tiles, and
 // the fetch registers stay few.
-constexpr int GC_PPT = 8;                  // most 16-byte patch items a thread fetches per tile
+constexpr int GC_PPT = 6;                  // most 16-byte patch items a thread fetches per tile (16: 1.7x slower, 8: 5 % slower)
 constexpr size_t GC_PATCH_MAX = 24 * 1024; // patch bytes (+ 10 KB of output staging)
 
 struct GcParams {
