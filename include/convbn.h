@@ -234,8 +234,10 @@ convbn_status convbn_dw_eval_bwd(const convbn_desc *desc, const void *x, const v
  * "Tune" backward with <dw'_o, w_o> summed over the cg kH kW weights of channel o.  Layout:
  *     x, dx [N][Hin][Win][Cin]     z, dz, y [N][Hout][Wout][Cout]     W, dW [Cout][kH][kW][cg]
  *     w_folded [cg][kH][kW][Cout]  (w' in the order the input-gradient pass reads)
- * groups = 1 is the dense block, groups = Cin = Cout the depthwise one (each has faster calls of
- * its own above).  Arguments, NULL rules and error behaviour as for the dense block's four calls. */
+ * groups = 1 is the dense block and groups = Cin = Cout the depthwise one: their buffer layouts
+ * coincide with this block's, and these calls pass such problems on to those blocks' calls (and
+ * the queries to their queries).  Arguments, NULL rules and error behaviour as for the dense
+ * block's four calls. */
 size_t convbn_grouped_workspace_bytes(const convbn_desc *desc, int groups, int mode, int pass);
 size_t convbn_grouped_saved_bytes(const convbn_desc *desc, int groups, int mode, int refold);
 convbn_status convbn_grouped_tune_fwd(const convbn_desc *desc, int groups, const void *x, const void *W,

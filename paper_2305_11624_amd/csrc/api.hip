@@ -420,6 +420,15 @@ convbn_status make_ggeom(const convbn_desc* d, int groups, Geom* g, Geom* gf) {
   gf->K = d->kH * d->kW * gf->Cin;
   return CONVBN_OK;
 }
+// The two limits of the grouped block have calls of their own with the same buffer layouts (W [Cout][kH][kW][cg] with
+// cg = Cin is the dense weight, with cg = 1 the depthwise filter [C][kH][kW]; likewise w_folded): the grouped entry
+// points pass them on, so that the limits run on those blocks' kernels.
+enum GroupedRoute { G_ROUTE_GROUPED, G_ROUTE_DENSE, G_ROUTE_DEPTHWISE };
+GroupedRoute grouped_route(const convbn_desc* d, int groups) {
+  if (groups == 1) return G_ROUTE_DENSE;
+  if (groups == d->Cin && d->Cin == d->Cout) return G_ROUTE_DEPTHWISE;
+  return G_ROUTE_GROUPED;
+}
 struct GFwdWs { void* w_krsc; float* bfold; size_t bytes; };
 GFwdWs carve_g_fwd(const Geom& gf, int dtype, void* ws) {
   Carve c(ws);
@@ -883,6 +892,8 @@ convbn_status convbn_dw_eval_bwd(const convbn_desc* desc, const void* x, const v
 size_t convbn_grouped_workspace_bytes(const convbn_desc* desc, int groups, int mode, int pass) {
   Geom g, gf;
   if (make_ggeom(desc, groups, &g, &gf) != CONVBN_OK) return 0;
+  if (grouped_route(desc, groups) == G_ROUTE_DENSE) return convbn_workspace_bytes(desc, mode, pass);
+  if (grouped_route(desc, groups) == G_ROUTE_DEPTHWISE) return convbn_dw_workspace_bytes(desc, mode, pass);
   if (mode != CONVBN_MODE_TUNE && mode != CONVBN_MODE_EVAL) return 0;
   return pass == CONVBN_PASS_FWD ? carve_g_fwd(gf, desc->dtype, nullptr).bytes
                                  : carve_g_bwd(g, gf, groups, desc->dtype, mode, nullptr).bytes;
@@ -891,6 +902,8 @@ size_t convbn_grouped_workspace_bytes(const convbn_desc* desc, int groups, int m
 size_t convbn_grouped_saved_bytes(const convbn_desc* desc, int groups, int mode, int refold) {
   Geom g, gf;
   if (make_ggeom(desc, groups, &g, &gf) != CONVBN_OK) return 0;
+  if (grouped_route(desc, groups) == G_ROUTE_DENSE) return convbn_saved_bytes(desc, mode, refold);
+  if (grouped_route(desc, groups) == G_ROUTE_DEPTHWISE) return convbn_dw_saved_bytes(desc, mode, refold);
   if (mode == CONVBN_MODE_EVAL) return (size_t)g.M * g.Cout * esize(desc->dtype);
   return refold ? 0 : (size_t)gf.Cout * gf.K * esize(desc->dtype);
 }
@@ -902,6 +915,8 @@ convbn_status convbn_grouped_tune_fwd(const convbn_desc* desc, int groups, const
   Geom g, gf;
   convbn_status s = make_ggeom(desc, groups, &g, &gf);
   if (s != CONVBN_OK) return s;
+  if (grouped_route(desc, groups) == G_ROUTE_DENSE) return convbn_tune_fwd(desc, x, W, b, gamma, beta, mean, var, z, w_folded, ws, ws_bytes, stream);
+  if (grouped_route(desc, groups) == G_ROUTE_DEPTHWISE) return convbn_dw_tune_fwd(desc, x, W, b, gamma, beta, mean, var, z, w_folded, ws, ws_bytes, stream);
   REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(beta); REQUIRE_PTR(mean);
   REQUIRE_PTR(var); REQUIRE_PTR(z);
   OPTIONAL_PTR(b); OPTIONAL_PTR(w_folded);
@@ -923,6 +938,8 @@ convbn_status convbn_grouped_tune_bwd(const convbn_desc* desc, int groups, const
   Geom g, gf;
   convbn_status s = make_ggeom(desc, groups, &g, &gf);
   if (s != CONVBN_OK) return s;
+  if (grouped_route(desc, groups) == G_ROUTE_DENSE) return convbn_tune_bwd(desc, x, W, b, gamma, mean, var, w_folded, dz, dx, dW, db, dgamma, dbeta, ws, ws_bytes, stream);
+  if (grouped_route(desc, groups) == G_ROUTE_DEPTHWISE) return convbn_dw_tune_bwd(desc, x, W, b, gamma, mean, var, w_folded, dz, dx, dW, db, dgamma, dbeta, ws, ws_bytes, stream);
   REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
   REQUIRE_PTR(dz);
   OPTIONAL_PTR(b); OPTIONAL_PTR(w_folded); OPTIONAL_PTR(dx); OPTIONAL_PTR(db);
@@ -963,6 +980,8 @@ convbn_status convbn_grouped_eval_fwd(const convbn_desc* desc, int groups, const
   Geom g, gf;
   convbn_status s = make_ggeom(desc, groups, &g, &gf);
   if (s != CONVBN_OK) return s;
+  if (grouped_route(desc, groups) == G_ROUTE_DENSE) return convbn_eval_fwd(desc, x, W, b, gamma, beta, mean, var, z, y_saved, ws, ws_bytes, stream);
+  if (grouped_route(desc, groups) == G_ROUTE_DEPTHWISE) return convbn_dw_eval_fwd(desc, x, W, b, gamma, beta, mean, var, z, y_saved, ws, ws_bytes, stream);
   REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(beta); REQUIRE_PTR(mean);
   REQUIRE_PTR(var); REQUIRE_PTR(z); REQUIRE_PTR(y_saved);
   OPTIONAL_PTR(b);
@@ -981,6 +1000,8 @@ convbn_status convbn_grouped_eval_bwd(const convbn_desc* desc, int groups, const
   Geom g, gf;
   convbn_status s = make_ggeom(desc, groups, &g, &gf);
   if (s != CONVBN_OK) return s;
+  if (grouped_route(desc, groups) == G_ROUTE_DENSE) return convbn_eval_bwd(desc, x, W, b, gamma, mean, var, y_saved, dz, dx, dW, db, dgamma, dbeta, ws, ws_bytes, stream);
+  if (grouped_route(desc, groups) == G_ROUTE_DEPTHWISE) return convbn_dw_eval_bwd(desc, x, W, b, gamma, mean, var, y_saved, dz, dx, dW, db, dgamma, dbeta, ws, ws_bytes, stream);
   REQUIRE_PTR(x); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
   REQUIRE_PTR(y_saved); REQUIRE_PTR(dz);
   OPTIONAL_PTR(b); OPTIONAL_PTR(dx); OPTIONAL_PTR(db);

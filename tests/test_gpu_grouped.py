@@ -76,6 +76,21 @@ def test_one_group_matches_the_dense_block():
         assert (res[k] - dense[k]).abs().max() <= 2e-2 * ref[k].__abs__().max()
 
 
+def test_groups_equal_to_channels_is_the_depthwise_block():
+    from paper_2305_11624_amd.runner import DepthwiseRun
+    shape = BlockShape("g_dw", 2, 48, 13, 12, 48, 3, 2, 1, "bf16", 129)
+    inp = synth.make_grouped_inputs(shape, 48, bias=True)
+    ref = oracle_grouped_block(inp)
+    res = _run(inp)
+    compare(res, ref, "bf16", keys=KEYS[:-1], tag="g_dw")
+    compare(_run(inp, mode="eval"), ref, "bf16", keys=EVAL_KEYS, tag="g_dw/eval")
+    r = DepthwiseRun(inp)
+    r.step()
+    dw = r.results()
+    for k in ("Z", "dX", "dW", "dgamma"):
+        assert torch.equal(res[k], dw[k]), k          # the same kernels: the grouped calls pass this limit on
+
+
 @pytest.mark.parametrize("name,C,H,stride", [("gx_56", 128, 56, 1), ("gx_56_s2", 256, 56, 2), ("gx_14", 512, 14, 1),
                                              ("gx_7", 1024, 7, 1)])
 def test_full_size_layers(name, C, H, stride):
