@@ -242,11 +242,64 @@ __global__ __launch_bounds__(256) void g_vec_wgrad_kernel(const bf16_t* __restri
   *reinterpret_cast<float4*>(op) = make_float4(acc[0], acc[1], acc[2], acc[3]);
   *reinterpret_cast<float4*>(op + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
 }
+// The same for the usual small windows (KH x KW known at compile time): a thread owns 8 input channels of one output
+// channel for ALL window positions, so a pixel's dZ value and the loop bookkeeping are paid once for KH KW
+// 16-byte loads of x and 8 KH KW multiply-adds.
+template <int KH, int KW>
+__global__ __launch_bounds__(256) void g_vec_wgrad_win_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dz,
+                                                              float* __restrict__ part, Geom g, int cg, int og,
+                                                              int rows_per_slice) {
+  const int q8s = cg / 8;
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= g.Cout * q8s) return;
+  const int q8 = t % q8s, o = t / q8s;
+  const int c0 = (o / og) * cg + 8 * q8;
+  const int rows = g.N * g.Hout;
+  const int r0 = blockIdx.y * rows_per_slice, r1 = min(rows, r0 + rows_per_slice);
+  float acc[KH * KW][8];
+#pragma unroll
+  for (int a = 0; a < KH * KW; ++a)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[a][e] = 0.f;
+  for (int r = r0; r < r1; ++r) {
+    const int n = r / g.Hout, ho = r - n * g.Hout;
+    const bf16_t* zp = dz + (size_t)r * g.Wout * g.Cout + o;
+    const bf16_t* xn = x + (size_t)n * g.Hin * g.Win * g.Cin + c0;
+    for (int wo = 0; wo < g.Wout; ++wo) {
+      const float zv = to_f32(zp[(size_t)wo * g.Cout]);
+#pragma unroll
+      for (int i = 0; i < KH; ++i) {
+        const int h = ho * g.sh + i - g.ph;
+#pragma unroll
+        for (int j = 0; j < KW; ++j) {
+          const int w = wo * g.sw + j - g.pw;
+          const bool ok = (unsigned)h < (unsigned)g.Hin && (unsigned)w < (unsigned)g.Win;
+          const uint4 raw = *reinterpret_cast<const uint4*>(xn + (ok ? ((size_t)h * g.Win + w) * g.Cin : 0));
+          float xv[8];
+          gv_unpack(ok ? raw : make_uint4(0u, 0u, 0u, 0u), xv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[i * KW + j][e] = fmaf(zv, xv[e], acc[i * KW + j][e]);
+        }
+      }
+    }
+  }
+  float* op = part + ((size_t)blockIdx.y * g.Cout + o) * (KH * KW) * cg + 8 * q8;
+#pragma unroll
+  for (int a = 0; a < KH * KW; ++a) {
+    *reinterpret_cast<float4*>(op + (size_t)a * cg) = make_float4(acc[a][0], acc[a][1], acc[a][2], acc[a][3]);
+    *reinterpret_cast<float4*>(op + (size_t)a * cg + 4) = make_float4(acc[a][4], acc[a][5], acc[a][6], acc[a][7]);
+  }
+}
+bool gv_wgrad_win(const Geom& g) { return (g.kH == 3 && g.kW == 3) || (g.kH == 1 && g.kW == 1); }
 int gv_wgrad_slices(const Geom& g, int groups) {
   const int cg = g.Cin / groups;
-  const int wgs = ceil_div(g.Cout * g.kH * g.kW * (cg / 8), 256);
+  const int wgs = ceil_div(g.Cout * (gv_wgrad_win(g) ? 1 : g.kH * g.kW) * (cg / 8), 256);
   int want = ceil_div(1024, wgs);              // about four workgroups per CU
-  if (want > 64) want = 64;
+  // every slice is a full fp32 copy of dw' that the fold-back has to read: at most 96 MB of them, at most 128 (few
+  // slices starve the kernel of threads: 3 instead of 16 on 2048 channels at 7 x 7 took 424 instead of 142 us)
+  const size_t slice = (size_t)g.Cout * g.kH * g.kW * cg * 4;
+  const int cap = (int)((size_t)(96 << 20) / slice) < 128 ? (int)((size_t)(96 << 20) / slice) : 128;
+  if (want > cap) want = cap;
   const int rows = g.N * g.Hout;
   if (want > rows) want = rows;
   if (want < 1) want = 1;
@@ -914,9 +967,20 @@ hipError_t launch_g_wgrad(const Geom& g, int groups, int dtype, const void* x, c
   }
   if (gv_supported(g, groups, dtype)) {
     const int ns = gv_wgrad_slices(g, groups);
+    const int rps = ceil_div(g.N * g.Hout, ns);
+    if (gv_wgrad_win(g)) {
+      const dim3 wgrid(ceil_div(g.Cout * (cg / 8), 256), ns);
+      if (g.kH == 3)
+        hipLaunchKernelGGL((g_vec_wgrad_win_kernel<3, 3>), wgrid, dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)dz, part,
+                           g, cg, og, rps);
+      else
+        hipLaunchKernelGGL((g_vec_wgrad_win_kernel<1, 1>), wgrid, dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)dz, part,
+                           g, cg, og, rps);
+      return hipGetLastError();
+    }
     const dim3 vgrid(ceil_div(g.Cout * g.kH * g.kW * (cg / 8), 256), ns);
     hipLaunchKernelGGL(g_vec_wgrad_kernel, vgrid, dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)dz, part, g, cg, og,
-                       ceil_div(g.N * g.Hout, ns));
+                       rps);
     return hipGetLastError();
   }
   const size_t P = (size_t)g.Cout * g.kH * g.kW * cg;
