@@ -130,6 +130,11 @@ __device__ __forceinline__ void gv_unpack(const uint4& v, float (&f)[8]) {
   f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
 }
 
+typedef __bf16 gv_bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float gv_dot2(unsigned a, unsigned b, float c) {   // c + a.lo b.lo + a.hi b.hi
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(gv_bf16x2, a), __builtin_bit_cast(gv_bf16x2, b), c, false);
+}
+
 __global__ __launch_bounds__(256) void g_vec_conv_kernel(GvParams p) {
   const int m = blockIdx.x * 256 + threadIdx.x;          // output pixel
   const int oc0 = blockIdx.y * 8;                         // first of the thread's 8 output channels
@@ -164,15 +169,16 @@ __global__ __launch_bounds__(256) void g_vec_conv_kernel(GvParams p) {
       const bf16_t* ip = p.in + (ok ? (((size_t)n * p.Hi + h) * p.Wi + w) * p.Ci + (size_t)grp * p.gin : 0);
       const bf16_t* wp = p.w + wrow + (size_t)(i * p.kW + j) * wstep_t;
       for (int c8 = 0; c8 < p.gin; c8 += 8) {
-        const uint4 raw = *reinterpret_cast<const uint4*>(ip + c8);
-        float xv[8];
-        gv_unpack(ok ? raw : make_uint4(0u, 0u, 0u, 0u), xv);
+        uint4 xr = *reinterpret_cast<const uint4*>(ip + c8);
+        if (!ok) xr = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          float wv[8];
-          gv_unpack(*reinterpret_cast<const uint4*>(wp + e * wstep_e + c8), wv);
-#pragma unroll
-          for (int q = 0; q < 8; ++q) acc[e] = fmaf(xv[q], wv[q], acc[e]);
+          // 8 products per output channel as four packed bf16 dot products accumulated in fp32 (v_dot2c_f32_bf16)
+          const uint4 wr = *reinterpret_cast<const uint4*>(wp + e * wstep_e + c8);
+          acc[e] = gv_dot2(xr.x, wr.x, acc[e]);
+          acc[e] = gv_dot2(xr.y, wr.y, acc[e]);
+          acc[e] = gv_dot2(xr.z, wr.z, acc[e]);
+          acc[e] = gv_dot2(xr.w, wr.w, acc[e]);
         }
       }
     }
