@@ -312,7 +312,7 @@ int gv_wgrad_slices(const Geom& g, int groups) {
   return ceil_div(rows, ceil_div(rows, want));
 }
 
-// ---- bf16 MFMA kernels for groups of 4, 8, 16 or 32 channels (cg == og) ----------------------------------
+// ---- bf16 MFMA kernels for groups of 4, 8, 16 or 32 channels (cg == og; forward and input gradient also 64) ----
 // 32 consecutive channels hold whole groups, so the block is a stack of independent 32 -> 32 channel convolutions
 // whose weight is block-diagonal (32 / cg blocks of cg x cg per tap).  One MFMA 32x32x16 takes 32 output channels
 // x 32 pixels x 16 input channels of one tap: two per tap and wave.  The products outside the diagonal blocks
@@ -369,7 +369,9 @@ struct GcParams {
   int ctapw[4][9];
 };
 
-template <int TAPS>
+// KS: MFMA steps of 16 reduced channels per window position -- 2: the chunk's own 32 channels (groups of 4-32); 4: a
+// group of 64 channels = the two chunks of the workgroup (nch = 2), every output chunk reading all 64, nothing masked
+template <int TAPS, int KS>
 __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -423,21 +425,25 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
   fetch(worker);   // in flight while the weights arrive
 
   // ---- weight fragments: row = lane % 32 (output channel; mode 1: input channel), 8 consecutive reduced channels
-  bf16x8 wf[TAPS][2];
+  bf16x8 wf[TAPS][KS];
   {
     const int row = px, rgrp = row >> p.lcg;
 #pragma unroll
     for (int t = 0; t < TAPS; ++t)
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
+      for (int ks = 0; ks < KS; ++ks) {
         const int k0 = ks * 16 + kb * 8;             // first of the 8 reduced channels (local)
         const int tw = p.ncls > 1 ? p.ctapw[cls][t] : p.tapw[t];
         const int twc = tw < 0 ? 0 : tw;                 // (no tap: load tap 0 and drop it)
-        const bool lo = tw >= 0 && (k0 >> p.lcg) == rgrp, hi = tw >= 0 && ((k0 + 4) >> p.lcg) == rgrp;
+        const bool lo = tw >= 0 && (KS == 4 || (k0 >> p.lcg) == rgrp), hi = tw >= 0 && (KS == 4 || ((k0 + 4) >> p.lcg) == rgrp);
         // every address below is inside the weight whatever the masks say: load first, zero afterwards, so that
         // all loads of the lane are in flight together
         uint4 v;
-        if (p.mode == 0) {
+        if (KS == 4) {   // groups of 64: rows and columns of the group's 64 x 64 block as they are
+          v = p.mode == 0
+                  ? *reinterpret_cast<const uint4*>(p.w + ((size_t)(chunk * 32 + row) * p.wtaps + twc) * 64 + k0)
+                  : *reinterpret_cast<const uint4*>(p.w + ((size_t)(cl * 32 + row) * p.wtaps + twc) * p.C + cgrp * 64 + k0);
+        } else if (p.mode == 0) {
           const bf16_t* wr = p.w + ((size_t)(chunk * 32 + row) * p.wtaps + twc) * p.cg;
           if (p.cg == 4) {
             const uint2 r = *reinterpret_cast<const uint2*>(wr);
@@ -474,7 +480,7 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
       const int pl = wt * 32 + px;
       int r = g_div(pl, p.mTC, p.TC), c = pl - r * p.TC;
       if (r >= rows || c >= cols) { r = 0; c = 0; }   // computed and dropped
-      const unsigned char* b0 = patch + ((r * p.sh) * p.PC + c * p.sw) * p.pitch + cl * 64 + kb * 16;
+      const unsigned char* b0 = patch + ((r * p.sh) * p.PC + c * p.sw) * p.pitch + (KS == 4 ? 0 : cl * 64) + kb * 16;
       f32x16 acc;
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[e] = bv[e];
@@ -483,7 +489,7 @@ __global__ __launch_bounds__(256) void g_conv_mfma_kernel(GcParams p) {
         const int i = t / p.kW, j = t - i * p.kW;
         const unsigned char* bp = b0 + (i * p.PC + j) * p.pitch;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int ks = 0; ks < KS; ++ks) {
           const bf16x8 fb = *reinterpret_cast<const bf16x8*>(bp + ks * 32);
           acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[t][ks], fb, acc, 0, 0, 0);
         }
@@ -514,7 +520,7 @@ GcPlan gc_plan(int N, int C, int cg, int in_h, int in_w, int out_h, int out_w, i
   GcPlan pl{false, 0, 0};
   GcParams& p = *pp;
   p = GcParams{};
-  if (C % 32 != 0 || (cg != 4 && cg != 8 && cg != 16 && cg != 32)) return pl;
+  if (C % 32 != 0 || (cg != 4 && cg != 8 && cg != 16 && cg != 32 && cg != 64)) return pl;
   const int taps = kH * kW;
   if (taps != 1 && taps != 2 && taps != 3 && taps != 4 && taps != 6 && taps != 9) return pl;
   p.N = N; p.Hi = in_h; p.Wi = in_w; p.C = C; p.Ho = out_h; p.Wo = out_w; p.kH = kH; p.kW = kW;
@@ -530,6 +536,7 @@ GcPlan gc_plan(int N, int C, int cg, int in_h, int in_w, int out_h, int out_w, i
     if (ceil_div(out_w, TC) != ntc) continue;
     const int PC = (TC - 1) * sw + kW;
     for (int nch = 1; nch <= 4; nch *= 2) {
+      if (cg == 64 && nch != 2) continue;               // a group of 64 is exactly the two chunks of a workgroup
       if (nchunks % nch != 0) continue;
       const int pitch = 64 * nch + 16;
       for (int TR = 1; TR <= out_h; ++TR) {
@@ -551,7 +558,7 @@ GcPlan gc_plan(int N, int C, int cg, int in_h, int in_w, int out_h, int out_w, i
     }
   }
   if (best == 0) return pl;
-  p.lcg = cg == 4 ? 2 : cg == 8 ? 3 : cg == 16 ? 4 : 5;
+  p.lcg = cg == 4 ? 2 : cg == 8 ? 3 : cg == 16 ? 4 : cg == 32 ? 5 : 6;
   p.lgpp = p.nch == 1 ? 2 : p.nch == 2 ? 3 : 4;
   p.mTC = g_magic(p.TC); p.mPC = g_magic(p.PC);
   p.nwt = ceil_div(p.TR * p.TC, 32);
@@ -632,7 +639,11 @@ GcPlan gc_dgrad_strided_plan(const Geom& g, int groups, int dtype, GcParams* p) 
 }
 
 hipError_t gc_launch(const GcPlan& pl, const GcParams& p, hipStream_t st) {
-#define GCL(T) hipLaunchKernelGGL(g_conv_mfma_kernel<T>, dim3(pl.grid, p.ncls), dim3(256), pl.lds, st, p)
+#define GCL(T)                                                                                                       \
+  do {                                                                                                               \
+    if (p.cg == 64) hipLaunchKernelGGL((g_conv_mfma_kernel<T, 4>), dim3(pl.grid, p.ncls), dim3(256), pl.lds, st, p);   \
+    else hipLaunchKernelGGL((g_conv_mfma_kernel<T, 2>), dim3(pl.grid, p.ncls), dim3(256), pl.lds, st, p);              \
+  } while (0)
   switch (p.kH * p.kW) {
     case 1: GCL(1); break;
     case 2: GCL(2); break;

@@ -36,6 +36,7 @@ SHAPES = [
     (BlockShape("g_w24", 2, 144, 15, 14, 144, 3, 1, 1, "bf16", 119), 6),          # group width not a power of two
     (BlockShape("g_w48_s2", 2, 96, 18, 18, 96, 3, 2, 1, "bf16", 120), 2),
     (BlockShape("g_w64", 2, 128, 12, 13, 128, 3, 1, 1, "bf16", 121), 2),
+    (BlockShape("g_w64_s2", 2, 192, 17, 18, 192, 3, 2, 1, "bf16", 130), 3),       # groups of 64, stride 2
     (BlockShape("g_uneven", 2, 64, 10, 10, 32, 3, 1, 1, "bf16", 122), 4),         # 16 inputs and 8 outputs per group
     (BlockShape("g_1x1", 2, 64, 9, 9, 64, 1, 1, 0, "bf16", 123), 8),
     (BlockShape("g_5x5", 2, 32, 11, 11, 32, 5, 1, 2, "bf16", 124), 4),
@@ -92,7 +93,7 @@ def test_groups_equal_to_channels_is_the_depthwise_block():
 
 
 @pytest.mark.parametrize("name,C,H,stride", [("gx_56", 128, 56, 1), ("gx_56_s2", 256, 56, 2), ("gx_14", 512, 14, 1),
-                                             ("gx_7", 1024, 7, 1)])
+                                             ("gx_7", 1024, 7, 1), ("gx_7_w64", 2048, 7, 1)])
 def test_full_size_layers(name, C, H, stride):
     """The benchmark's grouped layers at their full size (32 groups, N = 32, the launch configuration the benchmark
     times), sampled against the oracle run on the first two images (the block is independent across images except
