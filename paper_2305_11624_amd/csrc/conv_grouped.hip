@@ -312,7 +312,7 @@ int gv_wgrad_slices(const Geom& g, int groups) {
   return ceil_div(rows, ceil_div(rows, want));
 }
 
-// ---- bf16 MFMA kernels for groups of 4, 8, 16 or 32 channels (cg == og; forward and input gradient also 64) ----
+// ---- bf16 MFMA kernels for groups of 4, 8, 16, 32 or 64 channels (cg == og) ---------------------------------
 // 32 consecutive channels hold whole groups, so the block is a stack of independent 32 -> 32 channel convolutions
 // whose weight is block-diagonal (32 / cg blocks of cg x cg per tap).  One MFMA 32x32x16 takes 32 output channels
 // x 32 pixels x 16 input channels of one tap: two per tap and wave.  The products outside the diagonal blocks
@@ -691,7 +691,9 @@ struct GwParams {
   unsigned mTC, mPC;
 };
 
-template <int TAPS, int NCH>
+// RB: 32-channel row blocks of the input side per output chunk -- 1: the chunk's own channels (groups of 4-32); 2: a
+// group of 64 = both chunks of the workgroup (NCH = 2), all of the 64 x 32 result wanted
+template <int TAPS, int NCH, int RB>
 __global__ __launch_bounds__(256) void g_wgrad_mfma_kernel(GwParams p) {
   constexpr int NRED = 4 / NCH;                       // waves that share a chunk: they divide its taps among them
   constexpr int TPW = (TAPS + NRED - 1) / NRED;       // taps per wave: wave wq takes taps wq, wq + NRED, ...
@@ -771,12 +773,14 @@ __global__ __launch_bounds__(256) void g_wgrad_mfma_kernel(GwParams p) {
       }
   };
 
-  f32x16 acc[TPW];
+  f32x16 acc[TPW][RB];
   int toff[TPW];                                      // patch offset of the wave's taps
 #pragma unroll
   for (int u = 0; u < TPW; ++u) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[u][rb][e] = 0.f;
     const int t = wq + NRED * u;
     const int i = t / p.kW, j = t - i * p.kW;
     toff[u] = (i * p.PC + j) * p.pitch;
@@ -792,13 +796,16 @@ __global__ __launch_bounds__(256) void g_wgrad_mfma_kernel(GwParams p) {
       const int pa = k * 16 + kb * 8 + eprime;        // the lane's pixel in the first transposing read; + 4 in the second
       const unsigned char* za = zt + pa * p.pitch + cl * 64 + quad * 8;
       const bf16x8 zf = g_join(g_read_tr(za), g_read_tr(za + 4 * p.pitch));
-      const unsigned char* xa = patch + poff[pa] + cl * 64 + quad * 8;
-      const unsigned char* xb = patch + poff[pa + 4] + cl * 64 + quad * 8;
+      const unsigned char* xa = patch + poff[pa] + (RB == 2 ? 0 : cl * 64) + quad * 8;
+      const unsigned char* xb = patch + poff[pa + 4] + (RB == 2 ? 0 : cl * 64) + quad * 8;
 #pragma unroll
       for (int u = 0; u < TPW; ++u) {
         if (NRED * (u + 1) <= TAPS || wq + NRED * u < TAPS) {   // (a compile-time yes except for the last of a wave's taps)
-          const bf16x8 xf = g_join(g_read_tr(xa + toff[u]), g_read_tr(xb + toff[u]));
-          acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, zf, acc[u], 0, 0, 0);
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb) {
+            const bf16x8 xf = g_join(g_read_tr(xa + toff[u] + rb * 64), g_read_tr(xb + toff[u] + rb * 64));
+            acc[u][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, zf, acc[u][rb], 0, 0, 0);
+          }
         }
       }
     }
@@ -827,12 +834,14 @@ __global__ __launch_bounds__(256) void g_wgrad_mfma_kernel(GwParams p) {
   for (int u = 0; u < TPW; ++u) {
     const int t = wq + NRED * u;
 #pragma unroll
-    for (int e4 = 0; e4 < 4; ++e4) {
-      const int ci0 = 8 * e4 + 4 * kb;
-      if (t < TAPS && (ci0 >> p.lcg) == (co_l >> p.lcg))
-        *reinterpret_cast<float4*>(orow + t * p.cg + (ci0 & (p.cg - 1))) =
-            make_float4(acc[u][e4 * 4 + 0], acc[u][e4 * 4 + 1], acc[u][e4 * 4 + 2], acc[u][e4 * 4 + 3]);
-    }
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const int ci0 = 8 * e4 + 4 * kb;
+        if (t < TAPS && (RB == 2 || (ci0 >> p.lcg) == (co_l >> p.lcg)))
+          *reinterpret_cast<float4*>(orow + t * p.cg + (RB == 2 ? rb * 32 + ci0 : (ci0 & (p.cg - 1)))) =
+              make_float4(acc[u][rb][e4 * 4 + 0], acc[u][rb][e4 * 4 + 1], acc[u][rb][e4 * 4 + 2], acc[u][rb][e4 * 4 + 3]);
+      }
   }
 }
 
@@ -843,7 +852,7 @@ GwPlan gw_plan(const Geom& g, int groups, int dtype, GwParams* pp) {
   p = GwParams{};
   const int C = g.Cin, cg = g.Cin / groups, taps = g.kH * g.kW;
   if (dtype != CONVBN_BF16 || g.Cin != g.Cout || g.sh > 2 || g.sw > 2) return pl;
-  if (C % 32 != 0 || (cg != 4 && cg != 8 && cg != 16 && cg != 32) || (taps != 1 && taps != 9)) return pl;
+  if (C % 32 != 0 || (cg != 4 && cg != 8 && cg != 16 && cg != 32 && cg != 64) || (taps != 1 && taps != 9)) return pl;
   p.N = g.N; p.Hi = g.Hin; p.Wi = g.Win; p.C = C; p.Ho = g.Hout; p.Wo = g.Wout; p.kH = g.kH; p.kW = g.kW;
   p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw; p.cg = cg;
   const int nchunks = C / 32;
@@ -856,6 +865,7 @@ GwPlan gw_plan(const Geom& g, int groups, int dtype, GwParams* pp) {
     // one or two chunks per workgroup: with four, a wave owns all nine taps of its chunk (144 accumulator registers)
     // and the tiles shrink to a handful of pixels -- measured slower on every layer (47 vs 30 us on 256 channels, stride 2)
     for (int nch = 1; nch <= 2; nch *= 2) {
+      if (cg == 64 && nch != 2) continue;               // a group of 64 is exactly the two chunks of a workgroup
       if (nchunks % nch != 0) continue;
       const int pitch = 64 * nch + 16, nred = 4 / nch;
       for (int TR = 1; TR <= g.Hout; ++TR) {
@@ -878,7 +888,7 @@ GwPlan gw_plan(const Geom& g, int groups, int dtype, GwParams* pp) {
     }
   }
   if (best == 0) return pl;
-  p.lcg = cg == 4 ? 2 : cg == 8 ? 3 : cg == 16 ? 4 : 5;
+  p.lcg = cg == 4 ? 2 : cg == 8 ? 3 : cg == 16 ? 4 : cg == 32 ? 5 : 6;
   p.lgpp = p.nch == 1 ? 2 : p.nch == 2 ? 3 : 4;
   p.mTC = g_magic(p.TC); p.mPC = g_magic(p.PC);
   p.npx = p.TR * p.TC;
@@ -976,9 +986,10 @@ hipError_t launch_g_wgrad(const Geom& g, int groups, int dtype, const void* x, c
   const GwPlan pl = gw_plan(g, groups, dtype, &gp);
   if (pl.ok) {
     gp.x = (const bf16_t*)x; gp.dz = (const bf16_t*)dz; gp.part = part; gp.r_part = r_part;
-#define GWL(T, NC) hipLaunchKernelGGL((g_wgrad_mfma_kernel<T, NC>), dim3(pl.grid), dim3(256), pl.lds, st, gp)
-    if (g.kH * g.kW == 9) { if (gp.nch == 1) GWL(9, 1); else if (gp.nch == 2) GWL(9, 2); else GWL(9, 4); }
-    else { if (gp.nch == 1) GWL(1, 1); else if (gp.nch == 2) GWL(1, 2); else GWL(1, 4); }
+#define GWL(T, NC, RBV) hipLaunchKernelGGL((g_wgrad_mfma_kernel<T, NC, RBV>), dim3(pl.grid), dim3(256), pl.lds, st, gp)
+    if (gp.cg == 64) { if (g.kH * g.kW == 9) GWL(9, 2, 2); else GWL(1, 2, 2); }
+    else if (g.kH * g.kW == 9) { if (gp.nch == 1) GWL(9, 1, 1); else GWL(9, 2, 1); }
+    else { if (gp.nch == 1) GWL(1, 1, 1); else GWL(1, 2, 1); }
 #undef GWL
     return hipGetLastError();
   }
