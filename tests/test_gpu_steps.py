@@ -92,15 +92,15 @@ def test_each_step_against_oracle(shape):
     dW = torch.full((s.Cout, s.k, s.k, s.Cin), float("nan"), dtype=dt, device=dev)
     db, dgamma, dbeta = (torch.full((s.Cout,), float("nan"), dtype=torch.float32, device=dev) for _ in range(3))
     B.convbn_fold_back(desc, dw_part, r_part, W, b, gamma, mean, var, dW, db, dgamma, dbeta)
-    sd = np.sqrt(a["rvar"] + eps)
-    sc = a["gamma"] / sd
-    dwf_np = dwf.numpy()
-    assert rel_err(B.weight_from_device(dW), sc[:, None, None, None] * dwf_np) <= tol
-    r_np = r_part.double().sum(0).cpu().numpy()
-    dgamma_ref = ((dwf_np * a["W"]).sum(axis=(1, 2, 3)) + r_np * (a["b"] - a["rmean"])) / sd
-    assert rel_err(dgamma.double().cpu(), dgamma_ref) <= 1e-4
-    assert rel_err(dbeta.double().cpu(), r_np) <= 1e-6
-    assert rel_err(db.double().cpu(), sc * r_np) <= 1e-5
+    # reference: the oracle's Tune-mode backward (Table 2 "Tune") on the same inputs; its dw' and r agree with the
+    # GPU's summed partials to 1e-5 (checked above), so the fold-back's own error is what is measured here
+    tb = oracle.tune_bwd(d, a["x"], a["W"], a["b"], a["gamma"], a["rmean"], a["rvar"], eps, Wf, a["dy"], need_dx=False)
+    assert rel_err(B.weight_from_device(dW), tb["dW"]) <= tol
+    assert rel_err(dgamma.double().cpu(), tb["dgamma"]) <= 1e-4
+    assert rel_err(db.double().cpu(), tb["db"]) <= 1e-4
+    assert rel_err(dbeta.double().cpu(), tb["dbeta"]) <= 1e-5
+    # dbeta is r itself (Table 2 "Tune": the gradient of beta is the channel sum of dZ)
+    assert rel_err(dbeta.double().cpu(), r_part.double().sum(0).cpu().numpy()) <= 1e-6
 
 
 def test_outputs_are_deterministic():
