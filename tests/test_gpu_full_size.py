@@ -39,3 +39,36 @@ def test_wide_image_128_channels():
     run = BlockRun(inp, mode="tune", poison=True)
     run.step()
     compare(run.results(), ref, "bf16", tag="wide_128/tune")
+
+
+def _distinct_backbone_shapes():
+    """One block per distinct layer shape of the ResNet-50 backbone at the benchmarked batch (N = 32, 224 x 224)."""
+    seen, out = set(), []
+    for s in synth.resnet50_blocks(32, 224, "bf16"):
+        key = (s.Cin, s.Hin, s.Cout, s.k, s.stride)
+        if key not in seen:
+            seen.add(key)
+            out.append(s)
+    return out
+
+
+BACKBONE_SHAPES = _distinct_backbone_shapes()
+
+
+def test_backbone_has_23_distinct_shapes():
+    assert len(BACKBONE_SHAPES) == 23
+
+
+@pytest.mark.parametrize("shape", BACKBONE_SHAPES, ids=lambda s: s.name)
+def test_backbone_layer_at_bench_size(shape):
+    """Every distinct layer shape of the backbone workload at the batch the benchmark times, so that the plan the
+    host picks for it (tile shape, split sums, pointwise or window kernel) is the one compared: Z, dX, dW, dgamma
+    and dbeta against the definition, every element, in Tune mode and on the Eval comparison path."""
+    from paper_2305_11624_amd.runner import BlockRun
+    inp = synth.make_inputs(shape)
+    ref = oracle_block(inp)
+    for mode in ("tune", "eval"):
+        run = BlockRun(inp, mode=mode, poison=True)
+        run.step()
+        compare(run.results(), ref, "bf16", tag=f"{shape.name}/{mode}")
+        del run
