@@ -21,7 +21,9 @@
  *   - All work is enqueued asynchronously on `stream` (a hipStream_t passed as
  *     void*; NULL = the default stream).  No call synchronises with the host.
  *   - Arguments are validated on the host before anything is launched: a call that
- *     returns an error code has had no effect on device memory.
+ *     returns a validation error (codes 1-4) has had no effect on device memory.
+ *     CONVBN_ERR_LAUNCH can come from any of the kernels a call enqueues; what the
+ *     earlier ones wrote (workspace, w_folded, dx) then stays written.
  *   - Outputs are overwritten, never accumulated into.
  *   - mu and var are frozen buffers: read-only, no gradient.
  *   - Device-side value preconditions (var + eps > 0) are documented, not checked.
@@ -137,6 +139,22 @@ convbn_status convbn_eval_bwd(const convbn_desc *desc, const void *x, const void
                               const float *var, const void *y_saved, const void *dz, void *dx,
                               void *dW, float *db, float *dgamma, float *dbeta, void *ws,
                               size_t ws_bytes, void *stream);
+
+/* convbn_tune_fwd for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * kernels as convbn_tune_fwd, without ws / ws_bytes: the forward workspace is a device array
+ * built into the library (convbn_static_workspace_limit() bytes = 32 MiB, held by every GPU
+ * the library runs on until the process ends).  The call allocates and frees nothing.  A block
+ * whose convbn_workspace_bytes(desc, CONVBN_MODE_TUNE, CONVBN_PASS_FWD) exceeds the limit is
+ * refused with CONVBN_ERR_WORKSPACE before anything is launched.  All calls on one GPU share
+ * that GPU's array: calls that overlap in time on one GPU (different streams, or different
+ * threads) race; calls on one stream are ordered and safe.  The array keeps the previous
+ * call's contents; nothing in it has to start at zero (every byte read is written first). */
+convbn_status convbn_tune_fwd_static(const convbn_desc *desc, const void *x, const void *W,
+                                     const float *b, const float *gamma, const float *beta,
+                                     const float *mean, const float *var, void *z, void *w_folded,
+                                     void *stream);
+size_t convbn_static_workspace_limit(void);
 
 /* Ablation of the fold (the forward of Sec. 3.3 without materialising w'): since the scale is per output
  * channel, Z = s (w (*) X) + b' -- the convolution reads the UNFOLDED W and its epilogue applies s and b',

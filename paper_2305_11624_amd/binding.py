@@ -30,7 +30,8 @@ EXPORTS = ["convbn_hout", "convbn_wout", "convbn_workspace_bytes", "convbn_saved
            "convbn_tconv_eval_fwd", "convbn_tconv_eval_bwd", "convbn_dw_workspace_bytes", "convbn_dw_saved_bytes",
            "convbn_dw_tune_fwd", "convbn_dw_tune_bwd", "convbn_dw_eval_fwd", "convbn_dw_eval_bwd",
            "convbn_tune_fwd_scale_epilogue", "convbn_grouped_workspace_bytes", "convbn_grouped_saved_bytes",
-           "convbn_grouped_tune_fwd", "convbn_grouped_tune_bwd", "convbn_grouped_eval_fwd", "convbn_grouped_eval_bwd"]
+           "convbn_grouped_tune_fwd", "convbn_grouped_tune_bwd", "convbn_grouped_eval_fwd", "convbn_grouped_eval_bwd",
+           "convbn_tune_fwd_static", "convbn_static_workspace_limit"]
 
 
 class Desc(C.Structure):
@@ -149,6 +150,10 @@ def lib():
             getattr(L, name).argtypes = [like.argtypes[0], C.c_int] + list(like.argtypes[1:])
         L.convbn_tune_fwd_scale_epilogue.restype = C.c_int
         L.convbn_tune_fwd_scale_epilogue.argtypes = [dp, vp, vp, fp, fp, fp, fp, fp, vp, vp]
+        L.convbn_tune_fwd_static.restype = C.c_int
+        L.convbn_tune_fwd_static.argtypes = [dp, vp, vp, fp, fp, fp, fp, fp, vp, vp, vp]
+        L.convbn_static_workspace_limit.restype = C.c_size_t
+        L.convbn_static_workspace_limit.argtypes = []
         _lib = L
     return _lib
 
@@ -226,6 +231,18 @@ def convbn_tune_fwd(desc, x, W, b, gamma, beta, mean, var, z, w_folded, ws, stre
     if check:
         _check(st)
     return st
+
+
+def convbn_tune_fwd_static(desc, x, W, b, gamma, beta, mean, var, z, w_folded, stream=None, check=True):
+    st = lib().convbn_tune_fwd_static(C.byref(desc), _ptr(x), _ptr(W), _ptr(b), _ptr(gamma), _ptr(beta),
+                                      _ptr(mean), _ptr(var), _ptr(z), _ptr(w_folded), _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_static_workspace_limit() -> int:
+    return lib().convbn_static_workspace_limit()
 
 
 def convbn_tune_bwd(desc, x, W, b, gamma, mean, var, w_folded, dz, dx, dW, db, dgamma, dbeta, ws,

@@ -4,6 +4,8 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <mutex>
+
 #include "common.h"
 
 using namespace convbn;
@@ -491,6 +493,56 @@ size_t convbn_saved_bytes(const convbn_desc* desc, int mode, int refold) {
 }
 
 const char* convbn_last_error(void) { return g_err; }
+
+// ---- Tune forward for callers that cannot allocate ---------------------------------------------------
+// The forward workspace (w' in the forward order, b', split sums) lives in a file-scope device array.  Every
+// GPU the library runs on holds its own copy of the array at its own address; the address is looked up once
+// per device, with that device current, and kept.  Host code never passes the array's name to a kernel.
+#define CONVBN_STATIC_WS_BYTES (32u << 20)
+static __device__ __align__(256) unsigned char scratch[CONVBN_STATIC_WS_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+convbn_status static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(CONVBN_ERR_LAUNCH, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(CONVBN_ERR_UNSUPPORTED, "device index %d is not below %d", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      return fail(CONVBN_ERR_LAUNCH, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return CONVBN_OK;
+}
+}  // namespace
+
+size_t convbn_static_workspace_limit(void) { return CONVBN_STATIC_WS_BYTES; }
+
+convbn_status convbn_tune_fwd_static(const convbn_desc* desc, const void* x, const void* W, const float* b,
+                                     const float* gamma, const float* beta, const float* mean, const float* var,
+                                     void* z, void* w_folded, void* stream) {
+  Geom g;
+  convbn_status s = make_geom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  const size_t need = carve_tune_fwd(g, desc->dtype, nullptr).bytes;
+  if (need > CONVBN_STATIC_WS_BYTES)
+    return fail(CONVBN_ERR_WORKSPACE, "this block needs %zu workspace bytes, the built-in buffer has %u: use convbn_tune_fwd",
+                need, CONVBN_STATIC_WS_BYTES);
+  void* ptr = nullptr;
+  s = static_scratch(&ptr);
+  if (s != CONVBN_OK) return s;
+  // nothing in the forward workspace has to start at zero: every byte a kernel reads is written first by this call
+  return convbn_tune_fwd(desc, x, W, b, gamma, beta, mean, var, z, w_folded, ptr, CONVBN_STATIC_WS_BYTES, stream);
+}
 
 convbn_status convbn_tune_fwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
                               const float* gamma, const float* beta, const float* mean,
