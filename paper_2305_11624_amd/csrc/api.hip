@@ -72,13 +72,17 @@ Geom padded_geom(const Geom& g) {
   return q;
 }
 
-struct WgradWay { int nsplit; int nrpart; bool fused_r; };
+struct WgradWay { int nsplit; int nrpart; bool fused_r; bool sq = false; };
 WgradWay wgrad_way(const Geom& g0, int dtype) {
   if (needs_cin_pad(g0, dtype) && stem_wgrad_supported(g0, dtype)) {   // a first layer: its own kernel
     const int s = stem_wgrad_slices(g0);
     return {s, s, true};
   }
   const Geom g = needs_cin_pad(g0, dtype) ? padded_geom(g0) : g0;
+  if (wgrad_sq_supported(g, dtype)) {
+    const int s = wgrad_sq_splits(g);
+    return {s, s, true, true};
+  }
   if (wgrad_tile_supported(g, dtype)) {
     const int s = wgrad_tile_splits(g);
     return {s, s, true};
@@ -189,10 +193,12 @@ convbn_status check_ws(size_t need, void* ws, size_t ws_bytes) {
 // reduced channels are split over workgroups, and the zero-padded copies of needs_cin_pad().
 size_t inner_fprop_scratch(const Geom& g, int dtype) {
   if (pw_fprop_supported(g, dtype)) return 0;
+  if (mt_fprop_supported(g, dtype)) return align_up(mt_fprop_scratch_bytes(g), 256);
   return tile_fprop_supported(g, dtype) ? align_up(tile_fprop_partial_bytes(g), 256) : 0;
 }
 size_t inner_dgrad_scratch(const Geom& g, int dtype) {
   if (pw_dgrad_supported(g, dtype)) return 0;
+  if (mt_dgrad_supported(g, dtype)) return align_up(mt_dgrad_scratch_bytes(g), 256);
   return tile_dgrad_supported(g, dtype) ? align_up(tile_dgrad_partial_bytes(g), 256) : 0;
 }
 size_t fprop_scratch_bytes(const Geom& g, int dtype) {
@@ -221,6 +227,7 @@ size_t wgrad_scratch_bytes(const Geom& g, int dtype) {
 hipError_t fprop_any(const Geom& g, int dtype, const void* x, const void* w_krsc, const float* bias,
                      void* z, float* scratch, hipStream_t st) {
   if (pw_fprop_supported(g, dtype)) return launch_fprop_pw(g, x, w_krsc, bias, z, st);
+  if (mt_fprop_supported(g, dtype)) return launch_fprop_mt(g, x, w_krsc, bias, z, scratch, st);
   if (tile_fprop_supported(g, dtype)) return launch_fprop_tile(g, x, w_krsc, bias, z, scratch, st);
   return igemm_supported(g, dtype) ? launch_fprop_igemm(g, x, w_krsc, bias, z, st)
                                    : launch_fprop_direct(g, dtype, x, w_krsc, bias, z, st);
@@ -228,6 +235,7 @@ hipError_t fprop_any(const Geom& g, int dtype, const void* x, const void* w_krsc
 hipError_t dgrad_any(const Geom& g, int dtype, const void* dz, const void* w_crsk, const float* bias, void* dx,
                      float* scratch, hipStream_t st) {
   if (pw_dgrad_supported(g, dtype)) return launch_dgrad_pw(g, dz, w_crsk, bias, dx, st);
+  if (mt_dgrad_supported(g, dtype)) return launch_dgrad_mt(g, dz, w_crsk, bias, dx, scratch, st);
   if (tile_dgrad_supported(g, dtype)) return launch_dgrad_tile(g, dz, w_crsk, bias, dx, scratch, st);
   return igemm_supported(g, dtype) ? launch_dgrad_igemm(g, dz, w_crsk, bias, dx, st)
                                    : launch_dgrad_direct(g, dtype, dz, w_crsk, bias, dx, st);
@@ -276,6 +284,7 @@ hipError_t run_dgrad(const Geom& g, int dtype, const void* dz, const void* w_crs
 // dw' partials and, when r_part != nullptr, the partial per-channel sums of dz.
 hipError_t wgrad_any(const Geom& g, int dtype, const void* x, const void* dz, float* part, float* r_part,
                      const WgradWay& way, hipStream_t st) {
+  if (way.sq) return launch_wgrad_sq(g, x, dz, part, r_part, st);
   if (way.fused_r) return launch_wgrad_tile(g, x, dz, part, r_part, st);
   hipError_t e = igemm_supported(g, dtype) ? launch_wgrad_igemm(g, x, dz, part, way.nsplit, st)
                                            : launch_wgrad_direct(g, dtype, x, dz, part, st);
@@ -597,6 +606,13 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
     LAUNCH(run_dgrad(g, dt, dz, wt, dx, w.conv_scratch, st));   // dX = w'_rot (*) dZ
   }
   if (!params) return CONVBN_OK;
+  if (!needs_cin_pad(g, dt) && wgrad_sq_fused_supported(g, dt) &&
+      wgrad_sq_fused_scratch_bytes(g) <= (size_t)w.nsplit * g.Cout * g.K * 4) {
+    // deep layers: dw', r and the fold-back in one launch (the fp32 dw' never reaches memory); the space of the
+    // fp32 copy holds the few partial sums the workgroups exchange
+    LAUNCH(launch_wgrad_sq_fused(g, x, dz, W, b, gamma, mean, var, dW, db, dgamma, dbeta, w.dwf_part, st));
+    return CONVBN_OK;
+  }
   LAUNCH(run_wgrad(g, dt, x, dz, w.dwf_part, w.r_part, w.wgrad_scratch, st));   // dw' = dZ (.) X and r = sum dZ (fp32 partials)
   LAUNCH(launch_fold_back(g, dt, w.dwf_part, w.nsplit, w.r_part, w.nrpart, W, b, gamma, mean, var, 0,
                           dW, db, dgamma, dbeta, st));

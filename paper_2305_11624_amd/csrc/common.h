@@ -199,6 +199,18 @@ bool pw_tconv_supported(const Geom& g, int dtype);
 hipError_t launch_tconv_pw(const Geom& g, const void* x, const void* w_tap_major, const float* bias_per_tap, void* z,
                            hipStream_t st);
 
+// conv_mt.hip : 3x3 / stride-1 convolutions of deep layers (channel counts that are multiples of 128, few pixels):
+// 256-pixel x 128-channel tiles, the reduced channels split over workgroups and summed by the last one to arrive.
+// `scratch` holds the arrival counters and the fp32 accumulator dumps (mt_*_scratch_bytes(), 0 = not needed).
+bool mt_fprop_supported(const Geom& g, int dtype);
+bool mt_dgrad_supported(const Geom& g, int dtype);
+size_t mt_fprop_scratch_bytes(const Geom& g);
+size_t mt_dgrad_scratch_bytes(const Geom& g);
+hipError_t launch_fprop_mt(const Geom& g, const void* x, const void* w_krsc, const float* bias, void* z,
+                           float* scratch, hipStream_t st);
+hipError_t launch_dgrad_mt(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
+                           float* scratch, hipStream_t st);
+
 bool tile_fprop_supported(const Geom& g, int dtype);
 bool tile_fprop_scaled_supported(const Geom& g, int dtype);   // ... with a BnEpilogue
 bool tile_dgrad_supported(const Geom& g, int dtype);
@@ -219,5 +231,19 @@ bool wgrad_tile_supported(const Geom& g, int dtype);
 int wgrad_tile_splits(const Geom& g);
 hipError_t launch_wgrad_tile(const Geom& g, const void* x, const void* dz, float* dwf_part, float* r_part,
                              hipStream_t st);
+
+// wgrad_sq.hip : bf16 MFMA weight gradient of 3x3 windows (any stride), one 32 x 32 channel pair x 9 taps per
+// workgroup; same outputs as launch_wgrad_tile (fp32 dw' copies [splits][Cout][taps][Cin], r_part [splits][Cout]).
+bool wgrad_sq_supported(const Geom& g, int dtype);
+int wgrad_sq_splits(const Geom& g);
+hipError_t launch_wgrad_sq(const Geom& g, const void* x, const void* dz, float* dwf_part, float* r_part,
+                           hipStream_t st);
+// Weight gradient and fold-back in one launch, for problems whose pixels need no split (deep layers): writes dW,
+// dgamma, dbeta and (b given) db directly; no fp32 copy of dw' is stored.  scratch: wgrad_sq_fused_scratch_bytes().
+bool wgrad_sq_fused_supported(const Geom& g, int dtype);
+size_t wgrad_sq_fused_scratch_bytes(const Geom& g);
+hipError_t launch_wgrad_sq_fused(const Geom& g, const void* x, const void* dz, const void* W, const float* b,
+                                 const float* gamma, const float* mean, const float* var, void* dW, float* db,
+                                 float* dgamma, float* dbeta, void* scratch, hipStream_t st);
 
 }  // namespace convbn

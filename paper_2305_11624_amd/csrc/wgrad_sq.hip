@@ -1,0 +1,605 @@
+// bf16 MFMA weight gradient of a 3x3 window, one 32 x 32 channel pair per workgroup with all nine taps:
+//   dw'[co][tap][ci] = sum_m dZ[m][co] * Xpad[m (+) tap][ci]      (Sec. 3.2.1: dJ/dw = dJ/dY (.) X)
+//   r[co]            = sum_m dZ[m][co]                            (App. B)
+//
+// Why this shape.  Every workgroup that shares the chip adds one fp32 copy of its outputs to what the
+// fold-back has to read again, so the copies must be small: a workgroup owns 32 output x 32 input channels
+// x 9 taps = 9216 outputs (36 KB).  Deep layers (512 x 512 channels: 256 channel pairs) then need no pixel
+// split at all -- one copy of dw', written once -- and wide-image layers (64 x 64 channels: 4 pairs) split
+// the pixels 60-fold for 9 MB of copies where 64 x 64 x 9 tiles wrote 30.  The nine taps share one window
+// tile of X in LDS, so a workgroup fetches a pixel of X once, not nine times; what a compute unit pulls from
+// the L2 stays near 25 bytes per clock.
+//
+// A workgroup walks its pixels in tiles of 128 KS.  Per tile the dZ rows and the window rows of X those
+// pixels touch are copied global -> LDS in their natural [pixel][32 channels] order (64-byte rows, 1 KB per
+// copy instruction, zero fill outside the tensors through an out-of-range buffer offset), double-buffered.
+// The reduced index is the pixel -- the strided direction of that layout -- so the MFMA operands are read
+// with the transposing LDS load (ds_read_b64_tr_b16: a 16-lane group turns 4 pixels x 16 channels into
+// "lane = channel, 4 pixels"); four consecutive 64-byte rows are 256 contiguous bytes, one access per bank.
+// The eight waves split each tile's pixels (16 KS each), every wave holds all nine accumulator tiles, and
+// the waves add their sums through LDS at the end.
+#include "common.h"
+
+#include <atomic>
+#include <chrono>
+#include <mutex>
+
+namespace convbn {
+
+namespace {
+
+struct FastDiv {   // exact n / d for 0 <= n < 2^31, without a branch: (hi(n mul) + n add) >> shr
+  unsigned mul, shr, add;
+  int d;
+};
+
+FastDiv make_fastdiv(int d) {
+  FastDiv f{0u, 0u, 1u, d};   // d = 1: n itself
+  if (d <= 1) return f;
+  f.add = 0u;
+  unsigned s = 0;
+  while ((1ull << (s + 1)) < (unsigned long long)d) ++s;   // 2^s < d <= 2^(s+1)
+  f.shr = s;
+  f.mul = (unsigned)((((unsigned long long)1 << (32 + s)) + d - 1) / d);
+  return f;
+}
+
+__device__ __forceinline__ int fdiv(int n, const FastDiv& f) {
+  return (int)((__umulhi((unsigned)n, f.mul) + (unsigned)n * f.add) >> f.shr);
+}
+
+constexpr int NWAVES = 8;
+constexpr int TAPS = 9;
+constexpr int MAXXU = 6;                 // window copies per wave and tile, at most
+constexpr int ROWB = 64;                 // LDS row: 32 channels of bf16, no padding
+constexpr int RED_BYTES = 4 * TAPS * 16 * 64 * 4;   // four waves' accumulators (147456): the final reduction
+constexpr unsigned OOB = 0x80000000u;
+constexpr size_t LDS_USABLE = 159 * 1024;
+
+struct SqParams {
+  const bf16_t* x;
+  const bf16_t* dz;
+  float* part;       // [nsplit][Co][taps][Cin]
+  float* r_part;     // [nsplit][Co] or null
+  // Fused fold-back (Table 2 "Tune", last four lines), one pixel split only: dW = s dw' is stored instead of the
+  // fp32 copy, the workgroups of an output-channel tile leave their partial <dw', w> in dot_part [nci][Co] and
+  // count their arrival; the last one finishes dgamma, dbeta, db for the tile's 32 channels.
+  const bf16_t* wgt;   // the unfolded weight; null: not fused
+  bf16_t* dW;
+  const float* gamma; const float* mean; const float* var; const float* b;
+  float* db; float* dgamma; float* dbeta;
+  float* dot_part;
+  unsigned long long* counters;   // [nco]: (launch tag << 8) | arrivals
+  unsigned long long tag;
+  float eps;
+  unsigned x_bytes, dz_bytes;
+  int N, H, W, Cin;
+  int x_n_stride, x_h_stride, x_w_stride;
+  int Ho, Wo, Co;
+  int kW, sh, sw, ph, pw;
+  int M, Hv, Wv;
+  int nci, nco;
+  int bc, bi, nbci, blocks_per_split, nblocks;   // workgroup -> (channel pair, split) mapping, see the kernel
+  int ntiles, tiles_per_split;
+  int hunits;         // 1 KB units of a stage's window tile
+  int stage_bytes;    // dZ tile + window tile
+  FastDiv dHoWo, dWo, dHv, dWv;
+};
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+// 1 KB copy: lane l fetches 16 bytes at byte offset voff (per lane) + soff (wave-uniform; not part of the range
+// check) and writes them to LDS at lds_wave_base + 16 l.  The compiler barrier keeps every copy in the stream:
+// the waits count copies.
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff, void* lds_wave_base) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)lds_wave_base, 16, (int)voff, (int)soff, 0, 0);
+  asm volatile("" ::: "memory");
+}
+__device__ __forceinline__ void wait_all_copies() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ unsigned lds_off(const void* p) {
+  return (unsigned)(size_t)(__attribute__((address_space(3))) const void*)p;
+}
+// Transposing LDS reads issued as inline asm with hand-counted waits: the compiler would otherwise hold
+// every LDS read until the global -> LDS copies of the NEXT tile have landed.
+__device__ __forceinline__ void tr_read(i32x2& dst, unsigned addr) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(dst) : "v"(addr));
+}
+template <int N> __device__ __forceinline__ void wait_lgkm() {
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void pin(i32x2& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void pin1(int& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void pin1f(float& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ bf16x8 join2(i32x2 a, i32x2 b) {
+  typedef int i32x4 __attribute__((ext_vector_type(4)));
+  i32x4 v = {a[0], a[1], b[0], b[1]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Values that cross workgroups (which may run on XCDs whose L2 caches are not coherent with each other) are
+// written through to memory and read past any stale line with device-scope accesses.
+__device__ __forceinline__ void store_device_scope(float* p, float v) {
+  asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ float load_device_scope(const float* p) {
+  float v;
+  asm volatile("global_load_dword %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+  return v;
+}
+
+// Number of transposing reads issued up to and including those of multiply slot s (slot = 9 k + tap): two per
+// slot, plus two for the dZ fragment of every 16-pixel step begun so far.
+constexpr int reads_through(int s) { return 2 * (s + 1) + 2 * (s / TAPS + 1); }
+
+// KS: 16-pixel steps per wave and tile (tile = 128 KS pixels).  NCPY: copies per wave and tile (KS dZ units + the
+// window units wave, wave + 8, ...; units past a tile's window rows are zero-fill copies, so the count is fixed).
+template <int KS, int NCPY>
+__global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
+  constexpr int TILE = 128 * KS;
+  constexpr int ZT = TILE * ROWB;          // dZ tile bytes
+  constexpr int NS = TAPS * KS;            // multiplies per wave and tile
+  constexpr int NXU = NCPY - KS;           // window units per wave
+  constexpr int AHEAD = 4;                 // operands are read this many multiplies ahead
+  constexpr int NSTAGE = 3;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // Workgroup -> work.  Workgroups are handed to the eight XCDs in turn (id % 8), and each XCD has its own L2:
+  // the workgroups of one XCD should read the same slices of X and dZ.  The work is cut into blocks of bc x bi
+  // channel pairs of one pixel split (pairs that share dZ slices along one side and X slices along the other);
+  // block j goes to XCD j % 8, whose k-th workgroup (k = id / 8) takes pair k % (bc bi) of its (k / (bc bi))-th block.
+  const int bsize = p.bc * p.bi;
+  const int k_x = blockIdx.x >> 3;
+  const int blk = (k_x / bsize) * 8 + (blockIdx.x & 7);
+  if (blk >= p.nblocks) return;
+  const int w_b = k_x % bsize;
+  const int split = blk / p.blocks_per_split;
+  const int jb = blk - split * p.blocks_per_split;
+  const int cot = (jb / p.nbci) * p.bc + w_b % p.bc;
+  const int cit = (jb % p.nbci) * p.bi + w_b / p.bc;
+  const int ci0 = cit * 32, co0 = cot * 32;
+  const int HoWo = p.Ho * p.Wo;
+  const int tile_beg = split * p.tiles_per_split;
+  const int tile_end = min(p.ntiles, tile_beg + p.tiles_per_split);
+
+  const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.x, p.x_bytes);
+  const __amdgpu_buffer_rsrc_t z_rsrc = make_rsrc(p.dz, p.dz_bytes);
+
+  // place of this lane in a 1 KB copy: 16 rows x 4 granules
+  const int urow = lane >> 2, ugran = lane & 3;
+  // dZ copies: rows past the last pixel lie past the end of the buffer and arrive as zeros; the tile's first
+  // pixel enters as a wave-uniform offset
+  unsigned zoff[KS];
+#pragma unroll
+  for (int j = 0; j < KS; ++j) zoff[j] = (unsigned)((((wave + NWAVES * j) * 16 + urow) * p.Co + co0 + ugran * 8) * 2);
+  // window copies: what does not depend on the tile -- the window row (slot) and the column part of the address
+  int xslot[NXU];
+  unsigned xcol[NXU];
+#pragma unroll
+  for (int j = 0; j < NXU; ++j) {
+    const int pix = (wave + NWAVES * j) * 16 + urow;
+    xslot[j] = fdiv(pix, p.dWv);
+    const int w = pix - xslot[j] * p.Wv - p.pw;
+    xcol[j] = (unsigned)w < (unsigned)p.W ? (unsigned)((w * p.x_w_stride + ci0 + ugran * 8) * 2) : OOB;
+  }
+  // the stage holds exactly p.hunits window units: the waves whose last unit lies past them issue one copy less
+  const bool has_last = wave + NWAVES * (NXU - 1) < p.hunits;
+  // first window row of a tile (wave-uniform)
+  auto tile_vfirst = [&](int tile) {
+    const int m0 = tile * TILE;
+    const int n_a = fdiv(m0, p.dHoWo);
+    return n_a * p.Hv + fdiv(m0 - n_a * HoWo, p.dWo) * p.sh;
+  };
+  // All NCPY copies of `tile` into stage `st` (zero-fill copies if the tile does not exist: the count stays fixed).
+  auto issue_copy = [&](int i, int tile, int vfirst, bool live, unsigned char* stage) {
+    if (i < KS) {
+      const int ii = i < KS ? i : 0;
+      const bool ok = live && tile * TILE + (wave + NWAVES * ii) * 16 + urow < p.M;   // the wave-uniform offset is not range-checked
+      dma16(z_rsrc, ok ? zoff[ii] : OOB, (unsigned)(tile * (TILE * 2)) * (unsigned)p.Co, stage + (wave + NWAVES * ii) * 1024);
+    } else {
+      const int j = i - KS < NXU ? i - KS : 0;
+      if (j == NXU - 1 && !has_last) return;   // wave-uniform: this wave's last unit lies past the window tile
+      const int v = vfirst + xslot[j];
+      const int n = fdiv(v, p.dHv);
+      const int h = v - n * p.Hv - p.ph;
+      const bool ok = live && (unsigned)h < (unsigned)p.H && xcol[j] != OOB;   // rows past the last image lie past the buffer
+      dma16(x_rsrc, ok ? (unsigned)((n * p.x_n_stride + h * p.x_h_stride) * 2) + xcol[j] : OOB, 0u, stage + ZT + (wave + NWAVES * j) * 1024);
+    }
+  };
+  // Byte offset (inside the window tile) of the window row of tap (0,0) of output pixel m of a tile that starts
+  // at window row vfirst.
+  auto pixel_off = [&](int m, int vfirst) {
+    const int mm = min(m, p.M - 1);
+    const int n = fdiv(mm, p.dHoWo);
+    const int rem = mm - n * HoWo;
+    const int ho = fdiv(rem, p.dWo);
+    return ((n * p.Hv + ho * p.sh - vfirst) * p.Wv + (rem - ho * p.Wo) * p.sw) * ROWB;
+  };
+
+  // tap offsets inside the window tile
+  int tapoff[TAPS];
+#pragma unroll
+  for (int t = 0; t < TAPS; ++t) tapoff[t] = ((t / 3) * p.Wv + (t % 3)) * ROWB;
+
+  const int kb = lane >> 5;
+  const int eprime = (lane & 15) >> 2;                        // pixel (of 4) this lane addresses in a transposing read
+  const int chq = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;    // channel quad inside the 32 channels
+  const int pbase = wave * (16 * KS);                          // this wave's first pixel of a tile
+  const int plane = pbase + kb * 8 + eprime;                   // ... and this lane's first pixel of a 16-pixel step
+
+  f32x16 acc[TAPS];
+#pragma unroll
+  for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+
+  const bool do_r = (cit == 0 && p.r_part != nullptr);
+  float racc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) racc[e] = 0.f;
+
+  // ---- prologue: the copies of the first two tiles, the pixel offsets of the first ----------------------------
+  int vf_cur = 0, vf_next = 0;
+  int ptv[KS][2];
+#pragma unroll
+  for (int d = 0; d < 2; ++d) {
+    const int tile = tile_beg + d;
+    const bool live = tile < tile_end;
+    const int vf = live ? tile_vfirst(tile) : 0;
+    if (d == 0) vf_cur = vf; else vf_next = vf;
+#pragma unroll
+    for (int i = 0; i < NCPY; ++i) issue_copy(i, tile, vf, live, smem + d * p.stage_bytes);
+  }
+#pragma unroll
+  for (int k = 0; k < KS; ++k) {
+    ptv[k][0] = pixel_off(tile_beg * TILE + plane + k * 16, vf_cur);
+    ptv[k][1] = pixel_off(tile_beg * TILE + plane + k * 16 + 4, vf_cur);
+  }
+
+  int stage_off = 0;                        // byte offset of the current tile's stage
+  for (int tile = tile_beg; tile < tile_end; ++tile) {
+    // this tile has landed; the next one's copies may be in flight
+    if (has_last) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCPY) : "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCPY - 1) : "memory");
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();          // ... for every wave; everybody is done with the stage refilled below
+    asm volatile("" ::: "memory");
+    unsigned char* const zs = smem + stage_off;
+    int fill_off = stage_off + 2 * p.stage_bytes;
+    if (fill_off >= NSTAGE * p.stage_bytes) fill_off -= NSTAGE * p.stage_bytes;
+    unsigned char* const fill = smem + fill_off;
+    const int tile_f = tile + 2;
+    const bool live_f = tile_f < tile_end;
+    const int vf_fill = live_f ? tile_vfirst(tile_f) : 0;
+
+    if (do_r) {
+      // column sums of the dZ tile: thread -> granule tid % 4, pixels tid / 4 + 128 j.  Read through inline asm
+      // like the operands: a compiler-visible LDS read would first drain the copies in flight.
+      typedef int i32x4 __attribute__((ext_vector_type(4)));
+      i32x4 rv[KS];
+#pragma unroll
+      for (int j = 0; j < KS; ++j)
+        asm volatile("ds_read_b128 %0, %1" : "=v"(rv[j]) : "v"(lds_off(zs) + ((tid >> 2) + 128 * j) * ROWB + ((tid & 3) << 4)));
+      wait_lgkm<0>();
+#pragma unroll
+      for (int j = 0; j < KS; ++j) {
+        asm volatile("" : "+v"(rv[j]));
+        racc[0] += bf16_lo((unsigned)rv[j][0]); racc[1] += bf16_hi((unsigned)rv[j][0]);
+        racc[2] += bf16_lo((unsigned)rv[j][1]); racc[3] += bf16_hi((unsigned)rv[j][1]);
+        racc[4] += bf16_lo((unsigned)rv[j][2]); racc[5] += bf16_hi((unsigned)rv[j][2]);
+        racc[6] += bf16_lo((unsigned)rv[j][3]); racc[7] += bf16_hi((unsigned)rv[j][3]);
+      }
+    }
+
+    const unsigned zlane = lds_off(zs) + plane * ROWB + chq * 2;
+    const unsigned xlane = lds_off(zs + ZT) + chq * 2;
+    // Operands are read AHEAD multiplies before their multiply: fx ring slot s % (AHEAD + 1); the dZ fragment of a
+    // 16-pixel step goes just before the window fragment of its first tap.
+    i32x2 fz[2][2];
+    i32x2 fx[AHEAD + 1][2];
+    int pnext[KS][2];
+    auto issue_reads = [&](int s) {
+      const int k = s / TAPS, f = s % TAPS;
+      if (f == 0) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) tr_read(fz[k & 1][h], zlane + (k * 16 + 4 * h) * ROWB);
+      }
+#pragma unroll
+      for (int h = 0; h < 2; ++h) tr_read(fx[s % (AHEAD + 1)][h], xlane + ptv[k][h] + tapoff[f]);
+    };
+#pragma unroll
+    for (int s = 0; s < AHEAD; ++s) issue_reads(s);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int k = s / TAPS, f = s % TAPS;
+      constexpr int last = NS - 1;
+      if (s + AHEAD < NS) issue_reads(s + AHEAD);
+      // everything issued after the reads of slot s may still be in flight
+      switch (reads_through(s + AHEAD < last ? s + AHEAD : last) - reads_through(s)) {
+        case 0: wait_lgkm<0>(); break;
+        case 2: wait_lgkm<2>(); break;
+        case 4: wait_lgkm<4>(); break;
+        case 6: wait_lgkm<6>(); break;
+        case 8: wait_lgkm<8>(); break;
+        default: wait_lgkm<10>(); break;
+      }
+      pin(fz[k & 1][0]); pin(fz[k & 1][1]); pin(fx[s % (AHEAD + 1)][0]); pin(fx[s % (AHEAD + 1)][1]);
+      acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(join2(fx[s % (AHEAD + 1)][0], fx[s % (AHEAD + 1)][1]),
+                                                       join2(fz[k & 1][0], fz[k & 1][1]), acc[f], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      // in the shadow of the multiply: one copy of the tile two ahead, then the pixel offsets of the next tile
+      if (s < NCPY) issue_copy(s, tile_f, vf_fill, live_f, fill);
+      if (s >= NS - 2 * KS) {
+        const int e = s - (NS - 2 * KS);
+        pnext[e >> 1][e & 1] = pixel_off((tile + 1) * TILE + plane + (e >> 1) * 16 + 4 * (e & 1), vf_next);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int k = 0; k < KS; ++k) { ptv[k][0] = pnext[k][0]; ptv[k][1] = pnext[k][1]; }
+    vf_cur = vf_next; vf_next = vf_fill;
+    stage_off += p.stage_bytes;
+    if (stage_off >= NSTAGE * p.stage_bytes) stage_off = 0;
+  }
+
+  // ---- the eight waves add their accumulators through LDS ---------------------------------------------
+  // [copy][tap][e][lane] floats; waves 4..7 hand theirs to waves 0..3, then those four copies are summed by all.
+  wait_all_copies();
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(smem);
+  if (wave >= 4) {
+    float* mine = red + (size_t)(wave - 4) * (TAPS * 16 * 64) + lane;
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mine[(t * 16 + e) * 64] = acc[t][e];
+  }
+  __syncthreads();
+  if (wave < 4) {
+    float* mine = red + (size_t)wave * (TAPS * 16 * 64) + lane;
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mine[(t * 16 + e) * 64] += acc[t][e];
+  }
+  // channel sums of dZ: a thread holds 8 channels (granule tid % 4) of its pixel rows; add the 16 lanes of a wave
+  // that share a granule, then the eight waves through LDS (behind the accumulator copies)
+  float* rred = reinterpret_cast<float*>(smem + RED_BYTES);
+  if (do_r) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float v = racc[e];
+#pragma unroll
+      for (int off = 4; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
+      if (lane < 4) rred[wave * 32 + lane * 8 + e] = v;
+    }
+  }
+  __syncthreads();
+  // Accumulator element e of lane l: ci row 8 (e / 4) + 4 (l / 32) + e % 4, co column l % 32.  Wave w sums the
+  // four copies of taps w and w + 8 in the accumulators' own [e][lane] order (consecutive lanes, consecutive
+  // banks) and stores 4 input channels per lane and instruction.
+  const bool fused = p.wgt != nullptr;
+  const int co_l = lane & 31;
+  float scale = 1.f, dot = 0.f;
+  if (fused) scale = p.gamma[co0 + co_l] / sqrtf(p.var[co0 + co_l] + p.eps);
+  for (int tap = wave; tap < TAPS; tap += NWAVES) {
+    const float* src = red + (size_t)tap * (16 * 64) + lane;
+    const size_t o = (((size_t)split * p.Co + co0 + co_l) * TAPS + tap) * p.Cin + ci0 + 4 * kb;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float* s4 = src + (q * 4 + e) * 64;
+        v[e] = (s4[0] + s4[TAPS * 16 * 64]) + (s4[2 * TAPS * 16 * 64] + s4[3 * TAPS * 16 * 64]);
+      }
+      if (fused) {
+        const uint2 w = *reinterpret_cast<const uint2*>(p.wgt + o + 8 * q);
+        dot += v[0] * bf16_lo(w.x) + v[1] * bf16_hi(w.x) + v[2] * bf16_lo(w.y) + v[3] * bf16_hi(w.y);
+        *reinterpret_cast<uint2*>(p.dW + o + 8 * q) =
+            make_uint2(pack_bf16x2(scale * v[0], scale * v[1]), pack_bf16x2(scale * v[2], scale * v[3]));
+      } else {
+        *reinterpret_cast<float4*>(p.part + o + 8 * q) = make_float4(v[0], v[1], v[2], v[3]);
+      }
+    }
+  }
+  if (do_r && tid < 32) {
+    float v = 0.f;
+    for (int w = 0; w < NWAVES; ++w) v += rred[w * 32 + tid];
+    if (fused) store_device_scope(p.dot_part + (size_t)p.nci * p.Co + co0 + tid, v);   // r behind the nci rows of dot_part
+    else p.r_part[(size_t)split * p.Co + co0 + tid] = v;
+  }
+  if (!fused) return;
+  // <dw', w> of this workgroup's channel pair: the two lane halves of a wave, then the eight waves
+  dot += __shfl_xor(dot, 32, 64);
+  float* dred = rred + NWAVES * 32;
+  if (lane < 32) dred[wave * 32 + lane] = dot;
+  __syncthreads();
+  if (tid < 32) {
+    float v = 0.f;
+    for (int w = 0; w < NWAVES; ++w) v += dred[w * 32 + tid];
+    store_device_scope(p.dot_part + (size_t)cit * p.Co + co0 + tid, v);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's values have reached memory ...
+  __syncthreads();                                    // ... and every other thread's, before the arrival is counted
+  int* flag = reinterpret_cast<int*>(dred + NWAVES * 32);
+  if (tid == 0) {
+    unsigned long long* c = p.counters + cot;
+    unsigned long long old = __hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned long long cnt;
+    for (;;) {   // a word that does not carry this launch's tag is stale: count from zero
+      cnt = (old >> 8) == p.tag ? (old & 255ull) : 0ull;
+      const unsigned long long want = (p.tag << 8) | (cnt + 1);
+      if (__hip_atomic_compare_exchange_strong(c, &old, want, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        break;
+    }
+    *flag = (int)cnt == p.nci - 1;
+  }
+  __syncthreads();
+  if (!*flag || tid >= 32) return;
+  // the last workgroup of this output-channel tile: dgamma = (<dw', w> + r (b - mu)) / sqrt(var + eps), dbeta = r, db = s r
+  const int ch = co0 + tid;
+  float d = 0.f;
+  for (int i = 0; i < p.nci; ++i) d += load_device_scope(p.dot_part + (size_t)i * p.Co + ch);
+  const float r = load_device_scope(p.dot_part + (size_t)p.nci * p.Co + ch);
+  const float sd = sqrtf(p.var[ch] + p.eps);
+  const float bb = p.b ? p.b[ch] : 0.f;
+  p.dgamma[ch] = (d + r * (bb - p.mean[ch])) / sd;
+  p.dbeta[ch] = r;
+  if (p.db) p.db[ch] = p.gamma[ch] / sd * r;
+}
+
+// Largest number of window-tile pixels any tile of `tile` consecutive output pixels needs.
+int max_window_pixels(const SqParams& p, int tile) {
+  const int HoWo = p.Ho * p.Wo;
+  int a = HoWo, b = tile;
+  while (b) { const int t = a % b; a = b; b = t; }
+  const int period = HoWo / a;
+  int best = 0;
+  for (int m0 = 0, t = 0; m0 < p.M && t <= period; m0 += tile, ++t) {
+    const int ml = (m0 + tile < p.M ? m0 + tile : p.M) - 1;
+    const int na = m0 / HoWo, hoa = (m0 - na * HoWo) / p.Wo;
+    const int nb = ml / HoWo, hob = (ml - nb * HoWo) / p.Wo;
+    const int ns = nb * p.Hv + hob * p.sh + 3 - (na * p.Hv + hoa * p.sh);
+    if (ns > best) best = ns;
+  }
+  return best * p.Wv;
+}
+
+struct SqPlan { bool ok; int ks, ncpy, nsplit; size_t lds; };
+
+SqPlan make_plan(const Geom& g, SqParams* pp) {
+  SqPlan pl{false, 0, 0, 0, 0};
+  SqParams& p = *pp;
+  p = SqParams{};
+  if (g.kH != 3 || g.kW != 3) return pl;
+  if (g.Cin % 32 || g.Cout % 32) return pl;
+  const size_t xb = (size_t)g.Min * g.Cin * 2, zb = (size_t)g.M * g.Cout * 2;
+  if (xb >= OOB || zb >= OOB) return pl;
+  p.N = g.N; p.Cin = g.Cin; p.Ho = g.Hout; p.Wo = g.Wout; p.Co = g.Cout; p.M = g.M;
+  p.kW = g.kW; p.H = g.Hin; p.W = g.Win; p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
+  p.x_n_stride = g.Hin * g.Win * g.Cin; p.x_h_stride = g.Win * g.Cin; p.x_w_stride = g.Cin;
+  p.x_bytes = (unsigned)xb; p.dz_bytes = (unsigned)zb;
+  p.Hv = (p.Ho - 1) * p.sh + 3;
+  p.Wv = (p.Wo - 1) * p.sw + 3;
+  p.dHoWo = make_fastdiv(p.Ho * p.Wo);
+  p.dWo = make_fastdiv(p.Wo);
+  p.dHv = make_fastdiv(p.Hv);
+  p.dWv = make_fastdiv(p.Wv);
+  p.nci = g.Cin / 32;
+  p.nco = g.Cout / 32;
+  // 256-pixel tiles where three stages fit the LDS and a wave carries their window copies, else 128
+  for (int ks = 2; ks >= 1; --ks) {
+    const int tile = 128 * ks;
+    const int hunits = ceil_div(max_window_pixels(p, tile), 16);
+    const int nxu = ceil_div(hunits, NWAVES);
+    const int stage = tile * ROWB + hunits * 1024;
+    size_t lds = 3 * (size_t)stage;
+    if (lds < (size_t)RED_BYTES + 4096) lds = (size_t)RED_BYTES + 4096;   // the final reduction: four accumulator copies + channel sums, dot products, flag
+    if (lds > LDS_USABLE || nxu > MAXXU) continue;
+    pl.ks = ks; pl.ncpy = ks + nxu; pl.lds = lds;
+    p.hunits = hunits; p.stage_bytes = stage;
+    p.ntiles = ceil_div(g.M, tile);
+    break;
+  }
+  if (pl.ks == 0) return pl;
+  // pixel splits: about one workgroup per compute unit
+  const int pairs = p.nci * p.nco;
+  int want = pairs >= 192 ? 1 : (256 + pairs / 2) / pairs;
+  if (want > p.ntiles) want = p.ntiles;
+  if (want < 1) want = 1;
+  p.tiles_per_split = ceil_div(p.ntiles, want);
+  pl.nsplit = ceil_div(p.ntiles, p.tiles_per_split);
+  // blocks of up to 4 x 8 channel pairs that go to one XCD together
+  p.bi = p.nci % 8 == 0 ? 8 : (p.nci <= 8 ? p.nci : 1);
+  p.bc = p.bi == 1 ? 1 : (p.nco % 4 == 0 ? 4 : (p.nco <= 4 ? p.nco : 1));
+  p.nbci = p.nci / p.bi;
+  p.blocks_per_split = p.nbci * (p.nco / p.bc);
+  p.nblocks = p.blocks_per_split * pl.nsplit;
+  pl.ok = true;
+  return pl;
+}
+
+template <int KS, int NCPY>
+hipError_t launch_inst(const SqParams& p, const SqPlan& pl, hipStream_t st) {
+  static std::once_flag once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(once, [] {
+    attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_sq_kernel<KS, NCPY>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_USABLE);
+  });
+  if (attr_err != hipSuccess) return attr_err;
+  const int grid = 8 * ceil_div(p.nblocks, 8) * p.bc * p.bi;
+  hipLaunchKernelGGL((wgrad_sq_kernel<KS, NCPY>), dim3(grid), dim3(64 * NWAVES), pl.lds, st, p);
+  return hipGetLastError();
+}
+
+unsigned long long next_tag() {
+  static std::atomic<unsigned long long> tag{
+      (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9E3779B97F4A7C15ull};
+  return tag.fetch_add(1, std::memory_order_relaxed) & ((1ull << 56) - 1);
+}
+
+hipError_t dispatch(const SqParams& p, const SqPlan& pl, hipStream_t st) {
+#define CASE(K, X) if (pl.ks == K && pl.ncpy == K + X) return launch_inst<K, K + X>(p, pl, st);
+  CASE(2, 1) CASE(2, 2) CASE(2, 3) CASE(2, 4) CASE(2, 5) CASE(2, 6)
+  CASE(1, 1) CASE(1, 2) CASE(1, 3) CASE(1, 4) CASE(1, 5) CASE(1, 6)
+#undef CASE
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+bool wgrad_sq_fused_supported(const Geom& g, int dtype) {
+  if (dtype != CONVBN_BF16) return false;
+  SqParams p;
+  const SqPlan pl = make_plan(g, &p);
+  return pl.ok && pl.nsplit == 1 && p.nci <= 255;
+}
+
+size_t wgrad_sq_fused_scratch_bytes(const Geom& g) {
+  return align_up((size_t)(g.Cout / 32) * 8, 256) + (size_t)(g.Cin / 32 + 1) * g.Cout * 4;
+}
+
+hipError_t launch_wgrad_sq_fused(const Geom& g, const void* x, const void* dz, const void* W, const float* b,
+                                 const float* gamma, const float* mean, const float* var, void* dW, float* db,
+                                 float* dgamma, float* dbeta, void* scratch, hipStream_t st) {
+  SqParams p;
+  const SqPlan pl = make_plan(g, &p);
+  if (!pl.ok || pl.nsplit != 1 || !scratch) return hipErrorInvalidValue;
+  p.x = (const bf16_t*)x; p.dz = (const bf16_t*)dz; p.part = nullptr;
+  p.r_part = reinterpret_cast<float*>(scratch);   // only its non-NULL-ness matters here: the channel sums are wanted
+  p.wgt = (const bf16_t*)W; p.dW = (bf16_t*)dW; p.gamma = gamma; p.mean = mean; p.var = var; p.b = b;
+  p.db = db; p.dgamma = dgamma; p.dbeta = dbeta; p.eps = g.eps;
+  p.counters = reinterpret_cast<unsigned long long*>(scratch);
+  p.dot_part = reinterpret_cast<float*>(reinterpret_cast<char*>(scratch) + align_up((size_t)p.nco * 8, 256));
+  p.tag = next_tag();
+  return dispatch(p, pl, st);
+}
+
+bool wgrad_sq_supported(const Geom& g, int dtype) {
+  if (dtype != CONVBN_BF16) return false;
+  SqParams p;
+  return make_plan(g, &p).ok;
+}
+
+int wgrad_sq_splits(const Geom& g) {
+  SqParams p;
+  return make_plan(g, &p).nsplit;
+}
+
+hipError_t launch_wgrad_sq(const Geom& g, const void* x, const void* dz, float* dwf_part, float* r_part,
+                           hipStream_t st) {
+  SqParams p;
+  const SqPlan pl = make_plan(g, &p);
+  if (!pl.ok) return hipErrorInvalidValue;
+  p.x = (const bf16_t*)x; p.dz = (const bf16_t*)dz; p.part = dwf_part; p.r_part = r_part;
+  return dispatch(p, pl, st);
+}
+
+}  // namespace convbn

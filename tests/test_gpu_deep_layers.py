@@ -1,0 +1,38 @@
+"""GPU parity of deep 3x3 layers (many channels, few pixels), whose backward runs the weight gradient and the
+fold-back in one launch (partial dot products exchanged between workgroups, finished by the last one to arrive at a
+tagged counter): whole blocks against the oracle with ragged pixel tails, other paddings, a bias and wide scales, and
+twice in a row on one workspace (the arrival counters of the first call are stale for the second)."""
+import pytest
+import torch
+
+from paper_2305_11624_amd import synth
+from paper_2305_11624_amd.synth import BlockShape
+
+from helpers import compare, oracle_block
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [
+    (BlockShape("deep_7x7_512", 37, 512, 7, 7, 512, 3, 1, 1, "bf16", 61), dict()),               # ragged tail
+    (BlockShape("deep_7x7_512_bias", 19, 512, 7, 7, 512, 3, 1, 1, "bf16", 66), dict(bias=True, wide_scale=True)),
+    (BlockShape("deep_14x14_256", 41, 256, 14, 14, 256, 3, 1, 1, "bf16", 62), dict(bias=True)),   # 4 splits
+    (BlockShape("deep_28x28_128", 21, 128, 28, 28, 128, 3, 1, 1, "bf16", 63), dict(wide_scale=True)),   # 2 splits
+    (BlockShape("deep_13x11_pad0", 70, 256, 13, 11, 128, 3, 1, 0, "bf16", 64), dict()),
+    (BlockShape("deep_9x12_pad2", 56, 128, 9, 12, 384, 3, 1, 2, "bf16", 65), dict(bias=True)),
+]
+
+
+@pytest.mark.parametrize("shape,kw", SHAPES, ids=lambda v: v.name if hasattr(v, "name") else "")
+def test_deep_layer_block(shape, kw):
+    from paper_2305_11624_amd.runner import BlockRun
+    inp = synth.make_inputs(shape, **kw)
+    ref = oracle_block(inp)
+    run = BlockRun(inp, mode="tune", poison=True)
+    run.step()
+    compare(run.results(), ref, "bf16", tag=shape.name + "/first")
+    first = {k: (None if v is None else v.clone()) for k, v in run.results().items()}
+    run.step()   # same workspace again
+    second = run.results()
+    compare(second, ref, "bf16", tag=shape.name + "/second")
+    for k in ("Z", "dX", "dW", "dgamma", "dbeta"):   # split sums and partial dot products are combined in a fixed order
+        assert torch.equal(first[k], second[k]), k
