@@ -54,13 +54,36 @@ GROUPED_SHAPES = [("gx_56", 32, 128, 56, 56, 3, 1, 1, 32), ("gx_56_s2", 32, 256,
 # Win, Cout, window, stride, padding
 TCONV_SHAPES = [("up_k2", 32, 256, 28, 28, 128, 2, 2, 0), ("up_k4", 32, 512, 14, 14, 256, 4, 2, 1)]
 
-# HBM bytes per launch of the dominant kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of this script (summaries under profiles/); None where not measured.
-MEASURED_TRAFFIC_BYTES = {
-    # fetched + written bytes per launch
-    "fprop@c2b": 26.0e6 + 3.2e6, "dgrad@c2b": 26.0e6 + 3.2e6, "wgrad@c2b": 29.1e6 + 37.8e6,
-    "fprop@c2a": 16.3e6 + 12.9e6, "dgrad@c2a": 16.3e6 + 12.9e6, "wgrad@c2a": 29.8e6 + 29.6e6,
-}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "c2_default_bench_hbm_traffic.txt")
+KERNEL_SOURCES = os.path.join(ROOT, "paper_2305_11624_amd", "csrc")
+
+
+def sources_digest():
+    """Digest of the kernel sources: the traffic table names the digest of the build it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(KERNEL_SOURCES)):
+        if name.endswith((".hip", ".h")):
+            with open(os.path.join(KERNEL_SOURCES, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(key):
+    """HBM bytes per launch (fetched + written) of `key` ("pass@shape") from the tracked rocprofv3 counter summary,
+    or None when the summary has no such row or was measured on other kernel sources than the ones in the tree."""
+    try:
+        rows, digest = {}, None
+        with open(TRAFFIC_TABLE) as f:
+            for ln in f:
+                if ln.startswith("sources-digest:"):
+                    digest = ln.split(":", 1)[1].strip()
+                elif ln.startswith("traffic|"):
+                    _, k, fetch, write = [t.strip() for t in ln.split("|")[:4]]
+                    rows[k] = float(fetch) + float(write)
+        return rows.get(key) if digest == sources_digest() else None
+    except (OSError, ValueError):
+        return None
 
 
 def parse():
@@ -75,6 +98,8 @@ def parse():
     ap.add_argument("--kernel-reps", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eval", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="time eager launches only (no HIP graph replay)")
+    ap.add_argument("--no-hbm-shapes", action="store_true", help="skip the memory-bound configurations 1 and 3a")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also launch a plain streaming kernel of known size (in-place ReLU over 256 MiB: "
@@ -95,15 +120,23 @@ def tensor_bytes(run):
     return n
 
 
+def keeps_folded(shape):
+    """Keep w' between forward and backward only where it is smaller than the Y that Eval mode keeps (P <= A_z,
+    App. K.1); elsewhere backward folds again and nothing but x is kept."""
+    return shape.P <= shape.A_z
+
+
 def make_pool(inp, mode, pool_mb):
     from paper_2305_11624_amd.runner import BlockRun
-    first = BlockRun(inp, mode=mode)
+    keep = keeps_folded(inp["shape"])
+    first = BlockRun(inp, mode=mode, keep_folded=keep)
     per = max(1, tensor_bytes(first))
     count = max(2, min(64, -(-pool_mb * (1 << 20) // per)))
-    return [first] + [BlockRun(inp, mode=mode) for _ in range(count - 1)]
+    return [first] + [BlockRun(inp, mode=mode, keep_folded=keep) for _ in range(count - 1)]
 
 
 def time_steps(pools, steps, warmup):
+    """Eager launches: K steps enqueued from Python, one library call after the other."""
     import torch
     it = 0
 
@@ -121,6 +154,53 @@ def time_steps(pools, steps, warmup):
         one_step()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) / steps * 1e3
+
+
+def time_steps_graph(pools, steps, warmup):
+    """The same K steps replayed from HIP graphs: one captured graph per buffer set of the rotation (the library
+    only enqueues kernels on the caller's stream, so a step is capturable as it is).  Returns None if capture is
+    not available."""
+    import torch
+    rot = max(len(p) for p in pools)
+    graphs = []
+    try:
+        side = torch.cuda.Stream()
+        for i in range(rot):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for pool in pools:
+                    pool[i % len(pool)].step()
+            graphs.append(g)
+    except Exception as e:   # capture refused: report eager numbers only
+        print(f"bench.py: graph capture not available ({e})", file=sys.stderr)
+        return None
+    for k in range(max(warmup, 1)):
+        graphs[k % rot].replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        graphs[k % rot].replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps * 1e3
+
+
+def hbm_bound_shapes(pool_mb, steps):
+    """Configurations 1 and 3a are bound by memory traffic, not by the matrix cores: their Tune step against the
+    HBM peak, in algorithmic bytes (x read by forward and weight gradient, z written, dz read by both gradient
+    passes, dx written; the weight passes are negligible there)."""
+    from paper_2305_11624_amd import synth
+    out = {}
+    for name in ("c1", "c3a"):
+        s = synth.CONFIGS[name]
+        pool = make_pool(synth.make_inputs(s), "tune", pool_mb)
+        ms = time_steps([pool], steps, 5)
+        e = s.elem_bytes
+        nbytes = e * (3 * s.A_x + 3 * s.A_z) + s.P * (6 * e + 8)
+        out[name] = {"ms_per_step": ms, "algorithmic_mb": nbytes / 1e6, "gbs": nbytes / (ms * 1e-3) / 1e9,
+                     "pct_of_hbm_peak": 100.0 * nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                     "tflops": s.step_flop / (ms * 1e-3) / 1e12}
+        del pool
+    return out
 
 
 def kernel_times(pool, reps):
@@ -571,10 +651,14 @@ def main():
     flop = sum(s.step_flop for s in shapes)
 
     tune_pools = [make_pool(inp, "tune", a.pool_mb) for inp in inputs]
-    ms_tune = time_steps(tune_pools, a.steps, a.warmup)
+    ms_eager = time_steps(tune_pools, a.steps, a.warmup)
+    ms_graph = None if a.eager else time_steps_graph(tune_pools, a.steps, a.warmup)
+    ms_tune = min(ms_eager, ms_graph) if ms_graph is not None else ms_eager   # whichever way of launching is faster
 
     ktimes = {n: kernel_times(p, a.kernel_reps) for n, p in zip(names, tune_pools)}
     saved_tune = sum(p[0].saved_bytes() for p in tune_pools)
+    saved_by_shape = {n: {"tune": p[0].saved_bytes() / 1e6, "kept": "w'" if p[0].keep_folded else "nothing (backward folds again)"}
+                      for n, p in zip(names, tune_pools)}
     del tune_pools
     torch.cuda.empty_cache()
 
@@ -582,7 +666,11 @@ def main():
     if not a.no_eval:
         eval_pools = [make_pool(inp, "eval", a.pool_mb) for inp in inputs]
         ms_eval = time_steps(eval_pools, a.steps, a.warmup)
+        if not a.eager:
+            ms_eval = min(ms_eval, time_steps_graph(eval_pools, a.steps, a.warmup) or ms_eval)
         saved_eval = sum(p[0].saved_bytes() for p in eval_pools)
+        for n, p in zip(names, eval_pools):
+            saved_by_shape[n]["eval"] = p[0].saved_bytes() / 1e6
         del eval_pools
         torch.cuda.empty_cache()
 
@@ -594,7 +682,7 @@ def main():
     roofline = {"bound": "mfma", "kernel": f"{dom[1]} @ {dom[0]}", "achieved": achieved,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                 "avg_launch_ms": dom[2],
-                "traffic": MEASURED_TRAFFIC_BYTES.get(f"{dom[1]}@{dom[0]}")}
+                "traffic": measured_traffic(f"{dom[1]}@{dom[0]}")}
 
     per_shape = {}
     for n, s in zip(names, shapes):
@@ -615,15 +703,20 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "ResNet-50 3x3 ConvBN blocks, bf16: " + ", ".join(
             f"{s.name} x[{s.N},{s.Cin},{s.Hin},{s.Win}] {s.k}x{s.k} {s.Cin}->{s.Cout} s{s.stride} p{s.pad}"
-            for s in shapes), "mode": "tune", "layout": "NHWC", "step": "fwd+bwd of every shape"},
+            for s in shapes), "mode": "tune", "layout": "NHWC", "step": "fwd+bwd of every shape",
+            "launch": "HIP graph replay, one graph per buffer set" if (ms_graph is not None and ms_graph < ms_eager) else "eager"},
         "pct_of_bf16_mfma_peak": 100.0 * flop / (ms_tune * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "eager_ms_per_step": ms_eager, "graph_replay_ms_per_step": ms_graph,
         "eval_ms_per_step": ms_eval,
         "tune_speedup_vs_eval": (ms_eval / ms_tune) if ms_eval else None,
         "saved_activation_mb": {"tune": saved_tune / 1e6,
                                 "eval": saved_eval / 1e6 if saved_eval is not None else None},
+        "saved_activation_mb_per_shape": saved_by_shape,
         "per_shape": per_shape,
         "roofline": roofline,
     }
+    if a.workload == "c2" and not a.no_hbm_shapes:
+        line["hbm_bound_configs"] = hbm_bound_shapes(a.pool_mb, max(20, a.steps // 4))
     if a.traffic_calibration:
         buf = torch.zeros(256 << 19, dtype=torch.bfloat16, device="cuda")     # 256 MiB
         for _ in range(3):

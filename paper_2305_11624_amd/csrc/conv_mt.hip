@@ -316,6 +316,9 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_mt_kernel(MtParams p) {
           break;
       }
       *flag = (int)cnt == p.ksplit - 1;
+      // the last arrival leaves the count at zero under the same tag: a replay of a captured launch (same
+      // arguments, same tag) starts from zero again
+      if (*flag) __hip_atomic_store(c, p.tag << 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (!*flag) return;

@@ -439,6 +439,9 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
         break;
     }
     *flag = (int)cnt == p.nci - 1;
+    // the last arrival leaves the count at zero under the same tag: a replay of a captured launch (same arguments,
+    // same tag) starts from zero again
+    if (*flag) __hip_atomic_store(c, p.tag << 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
   if (!*flag || tid >= 32) return;
