@@ -135,6 +135,13 @@ __device__ __forceinline__ float load_device_scope(const float* p) {
 // slot, plus two for the dZ fragment of every 16-pixel step begun so far.
 constexpr int reads_through(int s) { return 2 * (s + 1) + 2 * (s / TAPS + 1); }
 
+#ifdef SQ_TRACE
+__device__ unsigned long long sq_trace[512 * 64];
+#define STAMP(i) do { if (tid == 0 && (i) < 64) sq_trace[blockIdx.x * 64 + (i)] = clock64(); } while (0)
+#else
+#define STAMP(i) do {} while (0)
+#endif
+
 // KS: 16-pixel steps per wave and tile (tile = 128 KS pixels).  NCPY: copies per wave and tile (KS dZ units + the
 // window units wave, wave + 8, ...; units past a tile's window rows are zero-fill copies, so the count is fixed).
 template <int KS, int NCPY>
@@ -149,6 +156,7 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  STAMP(0);
   // Workgroup -> work.  Workgroups are handed to the eight XCDs in turn (id % 8), and each XCD has its own L2:
   // the workgroups of one XCD should read the same slices of X and dZ.  The work is cut into blocks of bc x bi
   // channel pairs of one pixel split (pairs that share dZ slices along one side and X slices along the other);
@@ -262,6 +270,7 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
   }
 
   int stage_off = 0;                        // byte offset of the current tile's stage
+  STAMP(1);
   for (int tile = tile_beg; tile < tile_end; ++tile) {
     // this tile has landed; the next one's copies may be in flight
     if (has_last) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCPY) : "memory");
@@ -269,6 +278,7 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();          // ... for every wave; everybody is done with the stage refilled below
     asm volatile("" ::: "memory");
+    STAMP(2 + 2 * (tile - tile_beg));
     unsigned char* const zs = smem + stage_off;
     int fill_off = stage_off + 2 * p.stage_bytes;
     if (fill_off >= NSTAGE * p.stage_bytes) fill_off -= NSTAGE * p.stage_bytes;
@@ -340,6 +350,7 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+    STAMP(3 + 2 * (tile - tile_beg));
 #pragma unroll
     for (int k = 0; k < KS; ++k) { ptv[k][0] = pnext[k][0]; ptv[k][1] = pnext[k][1]; }
     vf_cur = vf_next; vf_next = vf_fill;
@@ -349,23 +360,32 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
 
   // ---- the eight waves add their accumulators through LDS ---------------------------------------------
   // [copy][tap][e][lane] floats; waves 4..7 hand theirs to waves 0..3, then those four copies are summed by all.
+  STAMP(60);
   wait_all_copies();
   __syncthreads();
-  float* red = reinterpret_cast<float*>(smem);
+  // copies as [copy][tap][q][lane] float4 (q = accumulator elements 4 q .. 4 q + 3): every access is 16 bytes per
+  // lane, consecutive lanes consecutive banks
+  float4* red = reinterpret_cast<float4*>(smem);
+  constexpr int COPY4 = TAPS * 4 * 64;   // float4 per copy
   if (wave >= 4) {
-    float* mine = red + (size_t)(wave - 4) * (TAPS * 16 * 64) + lane;
+    float4* mine = red + (size_t)(wave - 4) * COPY4 + lane;
 #pragma unroll
     for (int t = 0; t < TAPS; ++t)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) mine[(t * 16 + e) * 64] = acc[t][e];
+      for (int q = 0; q < 4; ++q)
+        mine[(t * 4 + q) * 64] = make_float4(acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]);
   }
   __syncthreads();
   if (wave < 4) {
-    float* mine = red + (size_t)wave * (TAPS * 16 * 64) + lane;
+    float4* mine = red + (size_t)wave * COPY4 + lane;
 #pragma unroll
     for (int t = 0; t < TAPS; ++t)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) mine[(t * 16 + e) * 64] += acc[t][e];
+      for (int q = 0; q < 4; ++q) {
+        const float4 o = mine[(t * 4 + q) * 64];
+        mine[(t * 4 + q) * 64] = make_float4(o.x + acc[t][4 * q], o.y + acc[t][4 * q + 1], o.z + acc[t][4 * q + 2],
+                                             o.w + acc[t][4 * q + 3]);
+      }
   }
   // channel sums of dZ: a thread holds 8 channels (granule tid % 4) of its pixel rows; add the 16 lanes of a wave
   // that share a granule, then the eight waves through LDS (behind the accumulator copies)
@@ -383,21 +403,19 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
   // Accumulator element e of lane l: ci row 8 (e / 4) + 4 (l / 32) + e % 4, co column l % 32.  Wave w sums the
   // four copies of taps w and w + 8 in the accumulators' own [e][lane] order (consecutive lanes, consecutive
   // banks) and stores 4 input channels per lane and instruction.
+  STAMP(61);
   const bool fused = p.wgt != nullptr;
   const int co_l = lane & 31;
   float scale = 1.f, dot = 0.f;
   if (fused) scale = p.gamma[co0 + co_l] / sqrtf(p.var[co0 + co_l] + p.eps);
   for (int tap = wave; tap < TAPS; tap += NWAVES) {
-    const float* src = red + (size_t)tap * (16 * 64) + lane;
+    const float4* src = red + (size_t)tap * (4 * 64) + lane;
     const size_t o = (((size_t)split * p.Co + co0 + co_l) * TAPS + tap) * p.Cin + ci0 + 4 * kb;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      float v[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float* s4 = src + (q * 4 + e) * 64;
-        v[e] = (s4[0] + s4[TAPS * 16 * 64]) + (s4[2 * TAPS * 16 * 64] + s4[3 * TAPS * 16 * 64]);
-      }
+      const float4 c0 = src[q * 64], c1 = src[q * 64 + COPY4], c2 = src[q * 64 + 2 * COPY4], c3 = src[q * 64 + 3 * COPY4];
+      const float v[4] = {(c0.x + c1.x) + (c2.x + c3.x), (c0.y + c1.y) + (c2.y + c3.y), (c0.z + c1.z) + (c2.z + c3.z),
+                          (c0.w + c1.w) + (c2.w + c3.w)};
       if (fused) {
         const uint2 w = *reinterpret_cast<const uint2*>(p.wgt + o + 8 * q);
         dot += v[0] * bf16_lo(w.x) + v[1] * bf16_hi(w.x) + v[2] * bf16_lo(w.y) + v[3] * bf16_hi(w.y);
@@ -414,6 +432,7 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
     if (fused) store_device_scope(p.dot_part + (size_t)p.nci * p.Co + co0 + tid, v);   // r behind the nci rows of dot_part
     else p.r_part[(size_t)split * p.Co + co0 + tid] = v;
   }
+  STAMP(62);
   if (!fused) return;
   // <dw', w> of this workgroup's channel pair: the two lane halves of a wave, then the eight waves
   dot += __shfl_xor(dot, 32, 64);
@@ -606,3 +625,9 @@ hipError_t launch_wgrad_sq(const Geom& g, const void* x, const void* dz, float* 
 }
 
 }  // namespace convbn
+
+#ifdef SQ_TRACE
+extern "C" int convbn_debug_read_sq_trace(unsigned long long* host, size_t n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(convbn::sq_trace), n * sizeof(unsigned long long));
+}
+#endif
