@@ -292,10 +292,10 @@ def backbone_flop(shapes):
     return sum(s.fwd_flop * (2 if s.name == "stem" else 3) for s in shapes)
 
 
-def run_backbone(mode, N, image, steps, warmup, group_fold=False):
+def run_backbone(mode, N, image, steps, warmup, group_fold=False, group_units=False):
     import torch
     from paper_2305_11624_amd.resnet50 import ResNet50
-    net = ResNet50(N, image, "bf16", mode, group_fold=group_fold)
+    net = ResNet50(N, image, "bf16", mode, group_fold=group_fold, group_units=group_units)
     g = torch.Generator(device="cpu").manual_seed(0)
     x = torch.randn(N, image, image, 3, generator=g).to("cuda", torch.bfloat16)
     h = image // 32
@@ -308,6 +308,8 @@ def run_backbone(mode, N, image, steps, warmup, group_fold=False):
         net.backward(dout)
     torch.cuda.synchronize()
     peak = torch.cuda.max_memory_allocated() - base
+    if group_units:
+        peak += net.group_bytes   # arenas and kept w' of the per-unit grouping are allocated once, before `base`
     t0 = time.perf_counter()
     for _ in range(steps):
         net.forward(x)
@@ -380,7 +382,10 @@ def main_backbone(a):
     N, image = a.batch, a.image
     shapes = synth.resnet50_blocks(N, image, "bf16")
     flop = backbone_flop(shapes)
-    tune = run_backbone("tune", N, image, a.steps, a.warmup)
+    # Tune mode with one fold launch and one fold-back launch per bottleneck unit (the default), and with one of
+    # each per block for comparison
+    tune = run_backbone("tune", N, image, a.steps, a.warmup, group_units=True)
+    tune_pb = run_backbone("tune", N, image, a.steps, a.warmup)
     ev = None if a.no_eval else run_backbone("eval", N, image, a.steps, a.warmup)
     grouped = run_backbone("tune", N, image, a.steps, a.warmup, group_fold=True) if a.group_fold else None
     tf = flop / (tune["ms"] * 1e-3) / 1e12
@@ -390,10 +395,11 @@ def main_backbone(a):
         "ms_per_step": tune["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"ResNet-50 backbone, 53 ConvBN blocks + ReLU + residual adds + max-pool, "
-                               f"bf16, N={N}, {image}x{image}x3, frozen BN statistics", "mode": "tune",
+                               f"bf16, N={N}, {image}x{image}x3, frozen BN statistics; fold and fold-back grouped per "
+                               f"bottleneck unit", "mode": "tune",
                    "layout": "NHWC", "step": "fwd+bwd of the backbone (no gradient w.r.t. the images)"},
         "pct_of_bf16_mfma_peak": 100.0 * tf / PEAK_BF16_TFLOPS,
-        "tune": tune, "eval": ev, "tune_group_fold": grouped,
+        "tune": tune, "tune_fold_per_block": tune_pb, "eval": ev, "tune_group_fold": grouped,
         "eval_ms_per_step": ev["ms"] if ev else None,
         "tune_speedup_vs_eval": ev["ms"] / tune["ms"] if ev else None,
         "peak_activation_mb": {"tune": tune["peak_activation_mb"], "eval": ev["peak_activation_mb"] if ev else None},

@@ -317,6 +317,35 @@ convbn_status convbn_fold_group_plan(int n, const convbn_fold_item *items, void 
                                      size_t table_bytes, int *grid_blocks);
 convbn_status convbn_fold_group(int n, const void *table_dev, int grid_blocks, void *stream);
 
+/* 1 if convbn_tune_bwd computes this block's weight gradient and fold-back in one launch (deep 3x3
+ * layers whose pixels need no split: the fp32 dw' never reaches memory), else 0.  A caller that groups
+ * fold-backs (below) leaves such blocks to convbn_tune_bwd. */
+int32_t convbn_tune_bwd_is_fused(const convbn_desc *desc);
+
+/* The fold-backs of several blocks in ONE launch (Table 2 "Tune", last four lines: dW = s dw',
+ * db = s r, dgamma = (<dw', w> + r (b - mu))/sqrt(var+eps), dbeta = r, for every block of the
+ * group).  A fold-back moves little data, so one launch per block is bound by the launches.
+ *   convbn_fold_back_item: one block's convbn_fold_back arguments (device pointers; dw_part and
+ *     r_part as convbn_conv_wgrad leaves them).
+ *   convbn_fold_back_group_plan: HOST side, like convbn_fold_group_plan.  Takes bf16 blocks
+ *     whose Cin*kH*kW is a multiple of 4 (others: CONVBN_ERR_UNSUPPORTED).  Launches nothing.
+ *   convbn_fold_back_group: runs the table on `stream`.  Same sums in the same order as
+ *     convbn_fold_back's 256-thread kernel (the single call uses a 1024-thread kernel, whose
+ *     partial sums are grouped differently, for blocks of at most 128 output channels with 16
+ *     or more partial copies of short rows). */
+typedef struct {
+  const convbn_desc *desc;
+  const float *dw_part, *r_part;
+  const void *W;
+  const float *b, *gamma, *mean, *var; /* b nullable */
+  void *dW;
+  float *db, *dgamma, *dbeta;          /* db NULL exactly when b is NULL */
+} convbn_fold_back_item;
+size_t convbn_fold_back_group_table_bytes(int n);
+convbn_status convbn_fold_back_group_plan(int n, const convbn_fold_back_item *items,
+                                          void *table_host, size_t table_bytes, int *grid_blocks);
+convbn_status convbn_fold_back_group(int n, const void *table_dev, int grid_blocks, void *stream);
+
 /* Workspace bytes convbn_conv_fprop (pass = CONVBN_PASS_FWD) or convbn_conv_dgrad /
  * convbn_conv_wgrad (CONVBN_PASS_BWD, enough for either) need; 0 for most shapes (then ws
  * may be NULL). */

@@ -31,7 +31,8 @@ EXPORTS = ["convbn_hout", "convbn_wout", "convbn_workspace_bytes", "convbn_saved
            "convbn_dw_tune_fwd", "convbn_dw_tune_bwd", "convbn_dw_eval_fwd", "convbn_dw_eval_bwd",
            "convbn_tune_fwd_scale_epilogue", "convbn_grouped_workspace_bytes", "convbn_grouped_saved_bytes",
            "convbn_grouped_tune_fwd", "convbn_grouped_tune_bwd", "convbn_grouped_eval_fwd", "convbn_grouped_eval_bwd",
-           "convbn_tune_fwd_static", "convbn_static_workspace_limit"]
+           "convbn_tune_fwd_static", "convbn_static_workspace_limit", "convbn_fold_back_group_table_bytes",
+           "convbn_fold_back_group_plan", "convbn_fold_back_group", "convbn_tune_bwd_is_fused"]
 
 
 class Desc(C.Structure):
@@ -48,6 +49,13 @@ class FoldItem(C.Structure):
     _fields_ = [("desc", C.POINTER(Desc)), ("W", C.c_void_p), ("b", C.c_void_p), ("gamma", C.c_void_p),
                 ("beta", C.c_void_p), ("mean", C.c_void_p), ("var", C.c_void_p), ("w_fprop", C.c_void_p),
                 ("w_folded", C.c_void_p), ("b_folded", C.c_void_p), ("identity", C.c_int32)]
+
+
+class FoldBackItem(C.Structure):
+    """Mirror of convbn_fold_back_item."""
+    _fields_ = [("desc", C.POINTER(Desc)), ("dw_part", C.c_void_p), ("r_part", C.c_void_p), ("W", C.c_void_p),
+                ("b", C.c_void_p), ("gamma", C.c_void_p), ("mean", C.c_void_p), ("var", C.c_void_p),
+                ("dW", C.c_void_p), ("db", C.c_void_p), ("dgamma", C.c_void_p), ("dbeta", C.c_void_p)]
 
 
 class ConvBNError(RuntimeError):
@@ -150,6 +158,14 @@ def lib():
             getattr(L, name).argtypes = [like.argtypes[0], C.c_int] + list(like.argtypes[1:])
         L.convbn_tune_fwd_scale_epilogue.restype = C.c_int
         L.convbn_tune_fwd_scale_epilogue.argtypes = [dp, vp, vp, fp, fp, fp, fp, fp, vp, vp]
+        L.convbn_tune_bwd_is_fused.restype = C.c_int32
+        L.convbn_tune_bwd_is_fused.argtypes = [dp]
+        L.convbn_fold_back_group_table_bytes.restype = C.c_size_t
+        L.convbn_fold_back_group_table_bytes.argtypes = [C.c_int]
+        L.convbn_fold_back_group_plan.restype = C.c_int
+        L.convbn_fold_back_group_plan.argtypes = [C.c_int, C.POINTER(FoldBackItem), vp, C.c_size_t, C.POINTER(C.c_int)]
+        L.convbn_fold_back_group.restype = C.c_int
+        L.convbn_fold_back_group.argtypes = [C.c_int, vp, C.c_int, vp]
         L.convbn_tune_fwd_static.restype = C.c_int
         L.convbn_tune_fwd_static.argtypes = [dp, vp, vp, fp, fp, fp, fp, fp, vp, vp, vp]
         L.convbn_static_workspace_limit.restype = C.c_size_t
@@ -313,6 +329,39 @@ def convbn_fold_group_plan(blocks, device="cuda", check=True):
 
 def convbn_fold_group(n, table, grid_blocks, stream=None, check=True):
     st = lib().convbn_fold_group(n, _ptr(table), grid_blocks, _stream(stream))
+    if check:
+        _check(st)
+    return st
+
+
+def convbn_tune_bwd_is_fused(desc) -> bool:
+    return bool(lib().convbn_tune_bwd_is_fused(C.byref(desc)))
+
+
+def convbn_fold_back_group_plan(blocks, device="cuda", check=True):
+    """blocks: list of dicts with desc, dw_part, r_part, W, b, gamma, mean, var, dW, db, dgamma, dbeta (tensors or
+    None).  Returns (n, table tensor on the device, grid_blocks)."""
+    n = len(blocks)
+    items = (FoldBackItem * n)()
+    for it, blk in zip(items, blocks):
+        it.desc = C.pointer(blk["desc"])
+        for k in ("dw_part", "r_part", "W", "b", "gamma", "mean", "var", "dW", "db", "dgamma", "dbeta"):
+            t = blk.get(k)
+            setattr(it, k, None if t is None else t.data_ptr())
+    nbytes = lib().convbn_fold_back_group_table_bytes(n)
+    host = (C.c_ubyte * nbytes)()
+    grid = C.c_int(0)
+    st = lib().convbn_fold_back_group_plan(n, items, C.cast(host, C.c_void_p), nbytes, C.byref(grid))
+    if check:
+        _check(st)
+    elif st != OK:
+        return st
+    table = torch.frombuffer(bytearray(host), dtype=torch.uint8).to(device)
+    return n, table, grid.value
+
+
+def convbn_fold_back_group(n, table, grid_blocks, stream=None, check=True):
+    st = lib().convbn_fold_back_group(n, _ptr(table), grid_blocks, _stream(stream))
     if check:
         _check(st)
     return st

@@ -606,8 +606,7 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
     LAUNCH(run_dgrad(g, dt, dz, wt, dx, w.conv_scratch, st));   // dX = w'_rot (*) dZ
   }
   if (!params) return CONVBN_OK;
-  if (!needs_cin_pad(g, dt) && wgrad_sq_fused_supported(g, dt) &&
-      wgrad_sq_fused_scratch_bytes(g) <= (size_t)w.nsplit * g.Cout * g.K * 4) {
+  if (convbn_tune_bwd_is_fused(desc)) {
     // deep layers: dw', r and the fold-back in one launch (the fp32 dw' never reaches memory); the space of the
     // fp32 copy holds the few partial sums the workgroups exchange
     LAUNCH(launch_wgrad_sq_fused(g, x, dz, W, b, gamma, mean, var, dW, db, dgamma, dbeta, w.dwf_part, st));
@@ -1158,6 +1157,56 @@ convbn_status convbn_fold_group(int n, const void* table_dev, int grid_blocks, v
   if (n <= 0 || grid_blocks <= 0) return fail(CONVBN_ERR_SHAPE, "empty fold group");
   REQUIRE_PTR(table_dev);
   LAUNCH(launch_fold_group(table_dev, n, grid_blocks, static_cast<hipStream_t>(stream)));
+  return CONVBN_OK;
+}
+
+int32_t convbn_tune_bwd_is_fused(const convbn_desc* desc) {
+  Geom g;
+  if (make_geom(desc, &g) != CONVBN_OK) return 0;
+  const int dt = desc->dtype;
+  return !needs_cin_pad(g, dt) && wgrad_sq_fused_supported(g, dt) &&
+         wgrad_sq_fused_scratch_bytes(g) <= (size_t)wgrad_way(g, dt).nsplit * g.Cout * g.K * 4;
+}
+
+size_t convbn_fold_back_group_table_bytes(int n) { return n > 0 ? (size_t)n * fold_back_group_item_bytes() : 0; }
+
+convbn_status convbn_fold_back_group_plan(int n, const convbn_fold_back_item* items, void* table_host,
+                                          size_t table_bytes, int* grid_blocks) {
+  if (n <= 0) return fail(CONVBN_ERR_SHAPE, "a fold-back group needs at least one block");
+  if (!items || !table_host || !grid_blocks) return fail(CONVBN_ERR_NULL, "items, table_host and grid_blocks are required");
+  if (table_bytes < convbn_fold_back_group_table_bytes(n))
+    return fail(CONVBN_ERR_WORKSPACE, "table_host holds %zu bytes, %zu are needed", table_bytes,
+                convbn_fold_back_group_table_bytes(n));
+  int total = 0;
+  for (int i = 0; i < n; ++i) {
+    const convbn_fold_back_item& it = items[i];
+    Geom g;
+    convbn_status s = make_geom(it.desc, &g);
+    if (s != CONVBN_OK) return s;
+    const float* dw_part = it.dw_part; const float* r_part = it.r_part; const void* W = it.W; const float* b = it.b;
+    const float* gamma = it.gamma; const float* mean = it.mean; const float* var = it.var; void* dW = it.dW;
+    float* db = it.db; float* dgamma = it.dgamma; float* dbeta = it.dbeta;
+    REQUIRE_PTR(dw_part); REQUIRE_PTR(r_part); REQUIRE_PTR(W); REQUIRE_PTR(gamma); REQUIRE_PTR(mean); REQUIRE_PTR(var);
+    REQUIRE_PTR(dW); REQUIRE_PTR(dgamma); REQUIRE_PTR(dbeta);
+    OPTIONAL_PTR(b); OPTIONAL_PTR(db);
+    if ((b == nullptr) != (db == nullptr)) return fail(CONVBN_ERR_NULL, "db must be given exactly when b is given");
+    const WgradWay way = wgrad_way(g, it.desc->dtype);
+    int blocks = 0;
+    if (!fold_back_group_item(g, it.desc->dtype, dw_part, way.nsplit, r_part, way.nrpart, W, b, gamma, mean, var, dW, db,
+                              dgamma, dbeta, total, static_cast<char*>(table_host) + (size_t)i * fold_back_group_item_bytes(),
+                              &blocks))
+      return fail(CONVBN_ERR_UNSUPPORTED, "block %d: a fold-back group takes bf16 blocks whose Cin*kH*kW is a multiple "
+                  "of 4 (use convbn_fold_back for the others)", i);
+    total += blocks;
+  }
+  *grid_blocks = total;
+  return CONVBN_OK;
+}
+
+convbn_status convbn_fold_back_group(int n, const void* table_dev, int grid_blocks, void* stream) {
+  if (n <= 0 || grid_blocks <= 0) return fail(CONVBN_ERR_SHAPE, "empty fold-back group");
+  REQUIRE_PTR(table_dev);
+  LAUNCH(launch_fold_back_group(table_dev, n, grid_blocks, static_cast<hipStream_t>(stream)));
   return CONVBN_OK;
 }
 

@@ -83,6 +83,15 @@ hipError_t launch_fold_back(const Geom& g, int dtype, const float* dwf_part, int
                             const float* r_part, int nrpart, const void* W, const float* b,
                             const float* gamma, const float* mean, const float* var, int identity,
                             void* dW, float* db, float* dgamma, float* dbeta, hipStream_t st);
+// Grouped fold-back: fold_back_group_item() writes one table entry (host memory) for a bf16 block whose K is a
+// multiple of 4 (false otherwise) and returns its number of workgroups; launch_fold_back_group() runs a table
+// that has been copied to device memory.
+size_t fold_back_group_item_bytes();
+bool fold_back_group_item(const Geom& g, int dtype, const float* dwf_part, int nsplit, const float* r_part, int nrpart,
+                          const void* W, const float* b, const float* gamma, const float* mean, const float* var,
+                          void* dW, float* db, float* dgamma, float* dbeta, int first_block, void* item_out,
+                          int* blocks);
+hipError_t launch_fold_back_group(const void* items_dev, int n, int grid_blocks, hipStream_t st);
 // fold_t.hip : fold / fold-back of the transposed block, weight [Ci][taps][Co] with the scale on co.
 // w_same ([Ci][taps][Co]), w_swap ([Co][taps][Ci]) and bfold may each be NULL (skipped).  tap_major != 0:
 // w_swap is [taps][Co][Ci] and bfold [taps][Co] (b' repeated for every tap) instead.  gamma == NULL: s = 1, b' = b.

@@ -199,8 +199,8 @@ __device__ __forceinline__ void store4(bf16_t* p, const float (&w)[4]) {
 // LDS.  Long rows: a column per thread, four copies in flight, columns in sequence.  Rows whose length is not a
 // multiple of 4: one element per thread; short ones divide the copies over thread groups in the same way.
 template <typename T, bool VEC, int NTHR>
-__global__ __launch_bounds__(NTHR) void fold_back_kernel(
-    const float* __restrict__ part, int nsplit, const float* __restrict__ r_part, int nrpart,
+__device__ __forceinline__ void fold_back_row(
+    const int co, const float* __restrict__ part, int nsplit, const float* __restrict__ r_part, int nrpart,
     const T* __restrict__ W, const float* __restrict__ b, const float* __restrict__ gamma,
     const float* __restrict__ mean, const float* __restrict__ var, float eps, int identity, int Cout,
     int K, T* __restrict__ dW, float* __restrict__ db, float* __restrict__ dgamma,
@@ -209,7 +209,6 @@ __global__ __launch_bounds__(NTHR) void fold_back_kernel(
   __shared__ float4 red4[VEC ? NTHR : 1];
   __shared__ float reds[VEC ? 1 : NTHR];
   __shared__ float red[NSL];
-  const int co = blockIdx.x;
   const int tid = threadIdx.x;
   const size_t P = (size_t)Cout * K;
   float s = 1.f, sd = 1.f;
@@ -340,6 +339,37 @@ __global__ __launch_bounds__(NTHR) void fold_back_kernel(
     dgamma[co] = (dot + r * (bc - mean[co])) / sd;
     if (db) db[co] = s * r;
   }
+}
+
+template <typename T, bool VEC, int NTHR>
+__global__ __launch_bounds__(NTHR) void fold_back_kernel(
+    const float* __restrict__ part, int nsplit, const float* __restrict__ r_part, int nrpart,
+    const T* __restrict__ W, const float* __restrict__ b, const float* __restrict__ gamma,
+    const float* __restrict__ mean, const float* __restrict__ var, float eps, int identity, int Cout,
+    int K, T* __restrict__ dW, float* __restrict__ db, float* __restrict__ dgamma,
+    float* __restrict__ dbeta) {
+  fold_back_row<T, VEC, NTHR>(blockIdx.x, part, nsplit, r_part, nrpart, W, b, gamma, mean, var, eps, identity, Cout, K,
+                              dW, db, dgamma, dbeta);
+}
+
+// The fold-backs of several blocks in one launch (Table 2 "Tune", last four lines, for every block of a group):
+// workgroup w handles output channel w - first_block of the item it falls into.  Same arithmetic, in the same
+// order, as the 256-thread single-block kernel.
+struct FoldBackGroupItem {
+  const float* part; const float* r_part; const bf16_t* W; const float* b; const float* gamma; const float* mean;
+  const float* var; bf16_t* dW; float* db; float* dgamma; float* dbeta;
+  float eps; int nsplit, nrpart, Cout, K, first_block;
+};
+__global__ __launch_bounds__(256) void fold_back_group_kernel(const FoldBackGroupItem* __restrict__ items, int n) {
+  int lo = 0, hi = n - 1;   // last item whose first_block <= blockIdx.x
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (items[mid].first_block <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+  }
+  const FoldBackGroupItem it = items[lo];
+  fold_back_row<bf16_t, true, 256>(blockIdx.x - it.first_block, it.part, it.nsplit, it.r_part, it.nrpart, it.W, it.b,
+                                   it.gamma, it.mean, it.var, it.eps, 0, it.Cout, it.K, it.dW, it.db, it.dgamma,
+                                   it.dbeta);
 }
 
 // Column reductions over a [M][Cout] channels-last tensor.  `cw` threads walk the
@@ -637,6 +667,25 @@ bool fold_group_item(const Geom& g, int dtype, const void* W, const float* b, co
 
 hipError_t launch_fold_group(const void* items_dev, int n, int grid_blocks, hipStream_t st) {
   hipLaunchKernelGGL(fold_group_kernel, dim3(grid_blocks), dim3(256), 0, st, (const FoldGroupItem*)items_dev, n);
+  return hipGetLastError();
+}
+
+size_t fold_back_group_item_bytes() { return sizeof(FoldBackGroupItem); }
+
+bool fold_back_group_item(const Geom& g, int dtype, const float* dwf_part, int nsplit, const float* r_part, int nrpart,
+                          const void* W, const float* b, const float* gamma, const float* mean, const float* var,
+                          void* dW, float* db, float* dgamma, float* dbeta, int first_block, void* item_out,
+                          int* blocks) {
+  if (dtype != CONVBN_BF16 || g.K % 4 != 0) return false;
+  FoldBackGroupItem it{dwf_part, r_part, (const bf16_t*)W, b, gamma, mean, var, (bf16_t*)dW, db, dgamma, dbeta,
+                       g.eps, nsplit, nrpart, g.Cout, g.K, first_block};
+  *blocks = g.Cout;
+  memcpy(item_out, &it, sizeof(it));
+  return true;
+}
+
+hipError_t launch_fold_back_group(const void* items_dev, int n, int grid_blocks, hipStream_t st) {
+  hipLaunchKernelGGL(fold_back_group_kernel, dim3(grid_blocks), dim3(256), 0, st, (const FoldBackGroupItem*)items_dev, n);
   return hipGetLastError();
 }
 

@@ -33,12 +33,17 @@ class _Block:
         self.keep_folded = mode == "tune" and shape.P <= shape.A_z
         self.x = self.saved = None
         self.grouped = None      # buffers of the network's grouped fold (Tune mode, optional)
+        self.unit = None         # buffers of this block inside its unit's grouped fold / fold-back (Tune mode)
 
     def forward(self, x, ws):
         s = self.shape
         z = torch.empty((s.N, s.Hout, s.Wout, s.Cout), dtype=self.dt, device=x.device)
         self.x = x
-        if self.grouped is not None:
+        if self.unit is not None:
+            # w' of this block was produced by its unit's grouped fold: only the convolution is left
+            B.convbn_conv_fprop(self.desc, x, self.unit["w_fprop"], self.unit["b_folded"], z, ws)
+            self.saved = self.unit["w_folded"]
+        elif self.grouped is not None:
             # w' of this block was produced by the network's grouped fold: only the convolution is left
             B.convbn_conv_fprop(self.desc, x, self.grouped["w_fprop"], self.grouped["b_folded"], z, ws)
             self.saved = self.grouped["w_folded"]
@@ -55,6 +60,13 @@ class _Block:
 
     def backward(self, dz, ws, need_dx=True):
         dx = torch.empty_like(self.x) if need_dx else None
+        if self.unit is not None and not self.unit["fused"]:
+            # this block's fold-back runs with its unit's, in one launch: only the two gradient convolutions here
+            u = self.unit
+            B.convbn_conv_dgrad(self.desc, dz, u["w_t"], dx, ws)
+            B.convbn_conv_wgrad(self.desc, self.x, dz, u["dw_part"], u["r_part"], ws)
+            self.x = self.saved = None
+            return dx
         if self.mode == "tune":
             B.convbn_tune_bwd(self.desc, self.x, self.W, None, self.gamma, self.mean, self.var, self.saved,
                               dz, dx, self.dW, None, self.dgamma, self.dbeta, ws)
@@ -67,12 +79,16 @@ class _Block:
 
 class ResNet50:
     def __init__(self, N: int = 32, image: int = 224, dtype: str = "bf16", mode: str = "tune",
-                 device: str = "cuda", group_fold: bool = False):
+                 device: str = "cuda", group_fold: bool = False, group_units: bool = False):
         """group_fold (Tune mode): fold all blocks in one launch at the start of forward instead of one
-        launch per block.  Faster, but every w' (in both orders) then lives for the whole step."""
+        launch per block.  Faster, but every w' (in both orders) then lives for the whole step.
+        group_units (Tune mode): one fold launch and one fold-back launch per bottleneck unit (its three or four
+        blocks) instead of one per block; the forward-order w' and the fp32 partial sums live in arenas the size of
+        the largest unit."""
         assert mode in ("tune", "eval")
         self.N, self.image, self.mode, self.device = N, image, mode, device
         self.group_fold = group_fold and mode == "tune"
+        self.group_units = group_units and mode == "tune" and not self.group_fold
         self._group = None
         self.group_bytes = 0
         shapes = synth.resnet50_blocks(N, image, dtype)
@@ -84,6 +100,89 @@ class ResNet50:
         for st, nblk in enumerate((3, 4, 6, 3), start=1):
             self.stages.append([f"l{st}.{i}" for i in range(nblk)])
         self._tape = None
+        self.units = None
+        if self.group_units:
+            self._build_units()
+
+    def _build_units(self):
+        """Tables and arenas of the per-unit grouped fold and fold-back.  Everything the tables point to is allocated
+        once: the kept w' of every block (what Tune mode keeps anyway), and three arenas the size of the largest
+        unit -- the forward-order w' + b', the w' folded again in backward for blocks that keep nothing, and the
+        fp32 partial sums of the weight gradients."""
+        bl, dev = self.blocks, self.device
+        names = [[u + sfx for sfx in (".c", ".b", ".a", ".ds") if (u + sfx) in bl] for st in self.stages for u in st]
+        need = dict(fwd=0, refold=0, part=0)
+        plans = []
+        for unit in names:
+            off = dict(fwd=0, refold=0, part=0)
+            rows = []
+            for nme in unit:
+                b = bl[nme]
+                s = b.shape
+                P = s.Cout * s.K
+                # blocks whose backward is one launch anyway, or whose fp32 partial sums are large (they would set the
+                # size of the arena), keep their own backward call
+                big = B.convbn_wgrad_parts(b.desc) * P * 4 > (16 << 20)
+                row = dict(block=b, fwd=off["fwd"], fused=B.convbn_tune_bwd_is_fused(b.desc) or big)
+                off["fwd"] += (P * 2 + 255) // 256 * 256 + (s.Cout * 4 + 255) // 256 * 256
+                if not b.keep_folded and not row["fused"]:
+                    row["refold"] = off["refold"]
+                    off["refold"] += (P * 2 + 255) // 256 * 256
+                if not row["fused"]:
+                    row["part"] = off["part"]
+                    ns, nr = B.convbn_wgrad_parts(b.desc), B.convbn_rsum_parts(b.desc)
+                    row["ns"], row["nr"] = ns, nr
+                    off["part"] += (ns * P * 4 + 255) // 256 * 256 + (nr * s.Cout * 4 + 255) // 256 * 256
+                rows.append(row)
+            plans.append(rows)
+            for k in need:
+                need[k] = max(need[k], off[k])
+        # one arena: the forward-order w' of a unit lives in it during forward, the re-folded w' and the partial sums
+        # of a unit during backward
+        need["refold"] = (need["refold"] + 255) // 256 * 256
+        one = torch.empty(max(need["fwd"], need["refold"] + need["part"], 256), dtype=torch.uint8, device=dev)
+        arena = dict(fwd=one, refold=one, part=one[need["refold"]:])
+
+        def view(buf, off, nbytes, dtype):
+            return buf[off:off + nbytes].view(dtype)
+
+        self.units = {}
+        kept_bytes = 0
+        for unit, rows in zip(names, plans):
+            fold_items, refold_items, back_items = [], [], []
+            for row in rows:
+                b = row["block"]
+                s = b.shape
+                P = s.Cout * s.K
+                u = dict(fused=row["fused"])
+                u["w_fprop"] = view(arena["fwd"], row["fwd"], P * 2, self.dt)
+                u["b_folded"] = view(arena["fwd"], row["fwd"] + (P * 2 + 255) // 256 * 256, s.Cout * 4, torch.float32)
+                u["w_folded"] = torch.empty(P, dtype=self.dt, device=dev) if b.keep_folded else None
+                kept_bytes += P * 2 if b.keep_folded else 0
+                fold_items.append(dict(desc=b.desc, W=b.W, b=None, gamma=b.gamma, beta=b.beta, mean=b.mean, var=b.var,
+                                       w_fprop=u["w_fprop"], w_folded=u["w_folded"], b_folded=u["b_folded"]))
+                if not row["fused"]:
+                    if b.keep_folded:
+                        u["w_t"] = u["w_folded"]
+                    else:
+                        u["w_t"] = view(arena["refold"], row["refold"], P * 2, self.dt)
+                        refold_items.append(dict(desc=b.desc, W=b.W, b=None, gamma=b.gamma, beta=None, mean=b.mean,
+                                                 var=b.var, w_fprop=None, w_folded=u["w_t"], b_folded=None))
+                    u["dw_part"] = view(arena["part"], row["part"], row["ns"] * P * 4, torch.float32)
+                    u["r_part"] = view(arena["part"], row["part"] + (row["ns"] * P * 4 + 255) // 256 * 256,
+                                       row["nr"] * s.Cout * 4, torch.float32)
+                    back_items.append(dict(desc=b.desc, dw_part=u["dw_part"], r_part=u["r_part"], W=b.W, b=None,
+                                           gamma=b.gamma, mean=b.mean, var=b.var, dW=b.dW, db=None, dgamma=b.dgamma,
+                                           dbeta=b.dbeta))
+                b.unit = u
+            key = unit[0].rsplit(".", 1)[0]
+            self.units[key] = dict(
+                fold=B.convbn_fold_group_plan(fold_items, device=dev),
+                refold=B.convbn_fold_group_plan(refold_items, device=dev) if refold_items else None,
+                back=B.convbn_fold_back_group_plan(back_items, device=dev) if back_items else None)
+        self._unit_keep = (arena, plans)
+        # what the grouping adds to the memory a step holds: the arenas (the kept w' is counted as before)
+        self.group_bytes = one.numel() + kept_bytes
 
     def fold_group_table(self, alloc=True):
         """(n, table, grid, bytes moved) of the grouped fold over every block the group takes (all but
@@ -138,6 +237,8 @@ class ResNet50:
         cur = p
         for names in self.stages:
             for name in names:
+                if self.units is not None:
+                    B.convbn_fold_group(*self.units[name]["fold"])
                 a = bl[name + ".a"].forward(cur, ws)
                 B.convbn_aux_eltwise(B.OP_RELU, a)
                 b = bl[name + ".b"].forward(a, ws)
@@ -156,6 +257,8 @@ class ResNet50:
         ws, bl, tape = self.ws, self.blocks, self._tape
         g = dout.clone()
         for name, has_ds, a, b, out in reversed(tape["units"]):
+            if self.units is not None and self.units[name]["refold"] is not None:
+                B.convbn_fold_group(*self.units[name]["refold"])   # blocks that kept nothing: w' again, for this unit
             B.convbn_aux_eltwise(B.OP_RELU_BWD, g, out)
             gb = bl[name + ".c"].backward(g, ws)
             B.convbn_aux_eltwise(B.OP_RELU_BWD, gb, b)
@@ -170,6 +273,8 @@ class ResNet50:
                 del gds
             else:
                 B.convbn_aux_eltwise(B.OP_ADD, gin, g)
+            if self.units is not None and self.units[name]["back"] is not None:
+                B.convbn_fold_back_group(*self.units[name]["back"])   # dW, dgamma, dbeta of the unit's blocks
             g = gin
         z0, idx = tape["z0"], tape["idx"]
         gz0 = torch.empty_like(z0)
