@@ -220,6 +220,13 @@ hipError_t launch_fprop_mt(const Geom& g, const void* x, const void* w_krsc, con
 hipError_t launch_dgrad_mt(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
                            float* scratch, hipStream_t st);
 
+// conv_st.hip : 3x3 / stride-1 convolutions of deep layers on 64-pixel x 128-channel tiles shared by eight waves
+// (no split sums, no scratch).
+bool st_fprop_supported(const Geom& g, int dtype);
+bool st_dgrad_supported(const Geom& g, int dtype);
+hipError_t launch_fprop_st(const Geom& g, const void* x, const void* w_krsc, const float* bias, void* z, hipStream_t st);
+hipError_t launch_dgrad_st(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx, hipStream_t st);
+
 bool tile_fprop_supported(const Geom& g, int dtype);
 bool tile_fprop_scaled_supported(const Geom& g, int dtype);   // ... with a BnEpilogue
 bool tile_dgrad_supported(const Geom& g, int dtype);

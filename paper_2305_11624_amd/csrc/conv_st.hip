@@ -1,0 +1,391 @@
+// bf16 MFMA convolution for deep 3x3 / stride-1 layers (many channels, few pixels) without split sums:
+// 64-pixel x 128-channel workgroup tiles shared by EIGHT waves.
+//
+//   forward conv   Z  = w' (*) X + b'     (Sec. 3.1 / 3.3)   act = x,  weights [Cout][taps][Cin]
+//   input gradient dX = w'_rot (*) dZ     (Sec. 3.2.1)       act = dz, weights [Cin][taps][Cout], taps reversed
+//
+// Why this shape.  With a few thousand pixels and 512 channels the output has only about as many 64 x 128 tiles
+// as the chip has compute units, so a tile cannot be larger without splitting the reduction over workgroups --
+// and the fp32 partial sums of such a split were measured to cost more than the larger tile saves.  At 64 x 128
+// the kernel is bound by how fast a compute unit can pull the folded weight out of the L2 (16 KB per
+// 64-channel step for 256 cycles of matrix work).  That rate depends on how many waves issue the copies: four
+// waves sustain about 30 bytes per clock, eight about 50.  So the tile is shared by eight waves (2 pixel groups
+// x 4 channel groups, one 32 x 32 accumulator tile each) instead of four: every wave issues half the copies,
+// and the matrix pipe of a SIMD is fed by two waves.
+//
+// Layout in LDS.  Activations: the window rows the tile's pixels touch, [slot][column][64 channels] with zero
+// rows / columns for the padding (out-of-image pixels are copies with an out-of-range buffer offset: zeros),
+// rows 144 bytes apart (128 + one pad granule: 16 consecutive rows of a 128-bit operand read fall on distinct
+// banks, and a tap is a wave-uniform offset on a per-lane base).  All nine taps of a chunk read the same tile.
+// Weights: one [128 rows][64 channels] slab per (chunk, tap) step in a ring of four, rows 128 bytes apart with
+// the eight granules of a row permuted by (row / 2) % 8 -- chosen by the copy, which picks the granule each
+// lane fetches -- so that a slab is exactly sixteen 1 KB copies, two per wave and step.
+//
+// Pipeline: as in the large-tile kernel.  A step = one tap of one 64-channel chunk = 4 k-steps x 1 MFMA per
+// wave; the taps are unrolled; during step s a wave issues its 2 KB of the slab of step s + 3 and, in the
+// first four taps of a chunk, one unit of the next chunk's window tile.  "At most the copies of step s - 1
+// outstanding" at the barrier of step s means the slab of step s + 1 and the next window tile are resident.
+#include "common.h"
+
+#include <mutex>
+
+namespace convbn {
+
+namespace {
+
+struct FastDiv {   // exact n / d for 0 <= n < 2^31, without a branch: (hi(n mul) + n add) >> shr
+  unsigned mul, shr, add;
+  int d;
+};
+
+FastDiv make_fastdiv(int d) {
+  FastDiv f{0u, 0u, 1u, d};   // d = 1: n itself
+  if (d <= 1) return f;
+  f.add = 0u;
+  unsigned s = 0;
+  while ((1ull << (s + 1)) < (unsigned long long)d) ++s;   // 2^s < d <= 2^(s+1)
+  f.shr = s;
+  f.mul = (unsigned)((((unsigned long long)1 << (32 + s)) + d - 1) / d);
+  return f;
+}
+
+__device__ __forceinline__ int fdiv(int n, const FastDiv& f) {
+  return (int)((__umulhi((unsigned)n, f.mul) + (unsigned)n * f.add) >> f.shr);
+}
+
+constexpr int TP = 64;                  // output pixels per workgroup
+constexpr int TRC = 128;                // output channels per workgroup
+constexpr int CB = 64;                  // reduced channels per chunk
+constexpr int KK = CB / 16;             // k-steps per step
+constexpr int NWAVES = 8;
+constexpr int HROW = 144;               // window-tile row pitch: 128 bytes of channels + one pad granule
+constexpr int HRPU = 7;                 // whole rows per 1 KB copy (its last lane spills into the next row)
+constexpr int HUNIT = HRPU * HROW;      // 1008
+constexpr int HUW = 4;                  // window-tile copies per wave and chunk
+constexpr int HUNITS = NWAVES * HUW;    // 32 -> at most 224 window pixels per tile
+constexpr int HBUF = HUNITS * HUNIT + 64;
+constexpr int WSLAB = TRC * CB * 2;     // 16384
+constexpr int NBUF = 4;
+constexpr int DIST = NBUF - 1;
+constexpr int OFF_W = 1024;             // bias first
+constexpr int OFF_H = OFF_W + NBUF * WSLAB;
+constexpr int LDS_BYTES = OFF_H + 2 * HBUF;
+constexpr unsigned OOB = 0x80000000u;
+
+struct StParams {
+  const bf16_t* act;
+  const bf16_t* wgt;
+  const float* bias;
+  bf16_t* out;
+  unsigned act_bytes, wgt_bytes;
+  int N, H, W, C;
+  int act_n_stride, act_h_stride, act_w_stride;   // elements
+  int Ho, Wo, R, M;
+  int ph, pw, Hv, Wv;
+  int wrow;                       // elements per weight row (taps x C)
+  int wt0, wt_row, wt_col;        // window position (ti, tj) reads weight tap wt0 + ti wt_row + tj wt_col
+  int ntr;                        // channel tiles
+  int nchunks;
+  FastDiv dHoWo, dWo, dHv, dWv;
+};
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+// 1 KB copy: lane l fetches 16 bytes at byte offset voff (per lane) + soff (wave-uniform) and writes them to
+// LDS at lds_wave_base + 16 l.  The compiler barrier keeps every copy in the stream: the waits count copies.
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff, void* lds_wave_base) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)lds_wave_base, 16, (int)voff, (int)soff, 0, 0);
+  asm volatile("" ::: "memory");
+}
+// Workgroup barrier without the memory fence of __syncthreads() (which would drain every outstanding copy).
+__device__ __forceinline__ void block_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int KH, int KW>
+__global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
+  constexpr int TAPS = KH * KW;
+  static_assert(TAPS >= HUW + 1 && TAPS >= DIST, "the copy schedule assumes a window of at least five taps");
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  float* biasl = reinterpret_cast<float*>(smem);
+  unsigned char* wbuf = smem + OFF_W;
+  unsigned char* halo = smem + OFF_H;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wpx = wave & 1, wch = wave >> 1;
+  const int ctile = blockIdx.x % p.ntr, ptile = blockIdx.x / p.ntr;
+  const int r0 = ctile * TRC;
+  const int HoWo = p.Ho * p.Wo;
+  const int m0 = ptile * TP, len = min(TP, p.M - m0);
+  const int m_last = m0 + len - 1;
+  const int n_a = fdiv(m0, p.dHoWo), ho_a = fdiv(m0 - n_a * HoWo, p.dWo);
+  const int n_b = fdiv(m_last, p.dHoWo), ho_b = fdiv(m_last - n_b * HoWo, p.dWo);
+  const int v_first = n_a * p.Hv + ho_a;
+  const int npix = (n_b * p.Hv + ho_b + KH - v_first) * p.Wv;
+
+  const __amdgpu_buffer_rsrc_t act_rsrc = make_rsrc(p.act, p.act_bytes);
+  const __amdgpu_buffer_rsrc_t wgt_rsrc = make_rsrc(p.wgt, p.wgt_bytes);
+  const int nchunks = p.nchunks;
+
+  float bias_v = (tid < TRC && p.bias) ? p.bias[r0 + tid] : 0.f;
+
+  // window-tile copies of this wave: unit wave + 8 t, t = 0..3; per-lane byte offsets without the chunk
+  unsigned hv[HUW];
+  {
+    const int lrow = lane == 63 ? 7 : lane / 9;       // lane 63: granule 0 of the next unit's first row
+    const int lgran = lane == 63 ? 0 : lane - lrow * 9;
+#pragma unroll
+    for (int t = 0; t < HUW; ++t) {
+      const int pix = (wave + NWAVES * t) * HRPU + lrow;
+      const int slot = fdiv(pix, p.dWv);
+      const int w = pix - slot * p.Wv - p.pw;
+      const int v = v_first + slot;
+      const int n = fdiv(v, p.dHv);
+      const int h = v - n * p.Hv - p.ph;
+      const bool ok = pix < npix && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W && n < p.N && lgran < 8;
+      hv[t] = ok ? (unsigned)((n * p.act_n_stride + h * p.act_h_stride + w * p.act_w_stride + lgran * 8) * 2) : OOB;
+    }
+  }
+  // weight copies of this wave: units 2 wave and 2 wave + 1 of the slab (8 rows each), granules permuted by (row / 2) % 8
+  unsigned voff_w[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int row = (2 * wave + j) * 8 + (lane >> 3);
+    const int g = (lane & 7) ^ ((row >> 1) & 7);
+    voff_w[j] = (unsigned)(((r0 + row) * p.wrow + g * 8) * 2);
+  }
+  // byte offset of window position t inside the window tile, and of its weights inside a weight row
+  int toff[TAPS], wsoff[TAPS];
+#pragma unroll
+  for (int t = 0; t < TAPS; ++t) {
+    const int ti = t / KW, tj = t % KW;
+    toff[t] = (ti * p.Wv + tj) * HROW;
+    wsoff[t] = (p.wt0 + ti * p.wt_row + tj * p.wt_col) * p.C * 2;
+  }
+
+  // LDS byte offsets of this lane's operands
+  const int kb = lane >> 5;
+  unsigned boff;
+  {
+    const int pi = wpx * 32 + (lane & 31);
+    int pixidx = 0;
+    if (pi < len) {
+      const int m = m0 + pi;
+      const int n = fdiv(m, p.dHoWo);
+      const int rem = m - n * HoWo;
+      const int ho = fdiv(rem, p.dWo);
+      pixidx = (n * p.Hv + ho - v_first) * p.Wv + (rem - ho * p.Wo);
+    }
+    boff = (unsigned)(pixidx * HROW + kb * 16);
+  }
+  // weight row of this lane: granule 2 kk + kb sits at position (2 kk + kb) ^ key, key = (row / 2) % 8
+  unsigned aoff;
+  {
+    const int row = wch * 32 + (lane & 31);
+    const int key = (row >> 1) & 7;
+    aoff = (unsigned)(row * 128 + ((kb ^ (key & 1)) << 4) + ((key >> 1) << 5));   // k-step kk: xor (kk << 5)
+  }
+
+  f32x16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+
+  auto issue_weights = [&](int chunk, int t, int slot) {
+    const unsigned soff = (unsigned)(wsoff[t] + chunk * (CB * 2));
+#pragma unroll
+    for (int j = 0; j < 2; ++j) dma16(wgt_rsrc, voff_w[j], soff, wbuf + slot * WSLAB + (2 * wave + j) * 1024);
+  };
+  auto issue_halo = [&](int chunk, int t, int hb) {
+    dma16(act_rsrc, hv[t], (unsigned)(chunk * (CB * 2)), halo + hb * HBUF + (wave + NWAVES * t) * HUNIT);
+  };
+
+  // ---- prologue: the first chunk's window tile and the slabs of steps 0 .. DIST-1 ---------------------
+#pragma unroll
+  for (int t = 0; t < HUW; ++t) issue_halo(0, t, 0);
+#pragma unroll
+  for (int s = 0; s < DIST; ++s) issue_weights(0, s, s);
+
+  bf16x8 fa[2], fb[2];
+  // operands of k-step kk: weights from ring slot `slot`, pixels from window tile `hb` at tap offset `to`
+  auto load_frags = [&](int buf, int slot, int hb, int to, int kk) {
+    fa[buf] = *reinterpret_cast<const bf16x8*>(wbuf + slot * WSLAB + (aoff ^ (unsigned)(kk << 5)));
+    fb[buf] = *reinterpret_cast<const bf16x8*>(halo + hb * HBUF + to + kk * 32 + boff);
+  };
+
+  wait_vm<0>();
+  block_barrier();
+  load_frags(0, 0, 0, toff[0], 0);
+
+  int slot = 0;   // ring slot of the current step
+  for (int c = 0; c < nchunks; ++c) {
+    const int hb = c & 1;
+    const int cnext = min(c + 1, nchunks - 1);   // past the end: the last chunk again (nobody reads it)
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t) {
+      // copies that may still be in flight: those of the previous step (2 weight units, + 1 window unit in taps 0..3)
+      if (t == 0 || t > HUW) wait_vm<2>(); else wait_vm<3>();
+      block_barrier();
+      const int t3 = (t + DIST) % TAPS;
+      const int c3 = (t + DIST) >= TAPS ? cnext : c;
+      const int slot_n = (slot + 1) & (NBUF - 1);
+      const int slot_f = (slot + DIST) & (NBUF - 1);
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        if (kk + 1 < KK) load_frags((kk + 1) & 1, slot, hb, toff[t], kk + 1);
+        else if (t + 1 < TAPS) load_frags((kk + 1) & 1, slot_n, hb, toff[t + 1], 0);
+        else load_frags((kk + 1) & 1, slot_n, hb ^ 1, toff[0], 0);
+        __builtin_amdgcn_sched_barrier(0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1], fb[kk & 1], acc, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kk == 0) issue_weights(c3, t3, slot_f);
+        if (kk == 1 && t < HUW) issue_halo(cnext, t, hb ^ 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      slot = slot_n;
+    }
+  }
+  wait_vm<0>();   // trailing copies must not outlive the workgroup's LDS
+
+  // ---- epilogue: bias, one rounding to bf16, 16-byte stores ------------------------------------------------
+  // Accumulator element e of lane l: channel 8 (e / 4) + 4 (l / 32) + e % 4 of the wave's 32, pixel l % 32.
+  // Each wave rounds its 32 x 32 block into its own 2 KB of LDS ([pixel][32 ch], granules swizzled by pixel)
+  // and reads it back row-wise: four lanes cover one pixel's 64 contiguous bytes.
+  if (tid < TRC) biasl[tid] = bias_v;
+  __syncthreads();
+  {
+    unsigned char* stage = smem + OFF_W + wave * 2048;
+    const int px = lane & 31;
+    const int psw = (px >> 1) & 3;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int ch = q * 8 + kb * 4;
+      const float4 bb = *reinterpret_cast<const float4*>(biasl + wch * 32 + ch);
+      const uint2 v = make_uint2(pack_bf16x2(acc[q * 4 + 0] + bb.x, acc[q * 4 + 1] + bb.y),
+                                 pack_bf16x2(acc[q * 4 + 2] + bb.z, acc[q * 4 + 3] + bb.w));
+      *reinterpret_cast<uint2*>(stage + px * 64 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
+    }
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int row = it * 16 + (lane >> 2);
+      const int g = (lane & 3) ^ ((row >> 1) & 3);
+      const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 64 + ((lane & 3) << 4));
+      const int pi = wpx * 32 + row;
+      if (pi < len) *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + pi) * p.R + r0 + wch * 32 + g * 8) = v;
+    }
+  }
+}
+
+// Largest number of window-tile pixels any TP-pixel tile needs.
+int max_window_pixels(const StParams& p, int kH) {
+  const int HoWo = p.Ho * p.Wo;
+  int a = HoWo, b = TP;
+  while (b) { const int t = a % b; a = b; b = t; }
+  const int period = HoWo / a;   // tile starts repeat modulo the image size after `period` tiles
+  int best = 0;
+  for (int m0 = 0, t = 0; m0 < p.M && t <= period; m0 += TP, ++t) {
+    const int ml = (m0 + TP < p.M ? m0 + TP : p.M) - 1;
+    const int na = m0 / HoWo, hoa = (m0 - na * HoWo) / p.Wo;
+    const int nb = ml / HoWo, hob = (ml - nb * HoWo) / p.Wo;
+    const int ns = nb * p.Hv + hob + kH - (na * p.Hv + hoa);
+    if (ns > best) best = ns;
+  }
+  return best * p.Wv;
+}
+
+// Completes the plan of a problem whose tensors are described in p; false = this kernel does not take it.
+bool finish_plan(StParams& p, int kH, int kW) {
+  if (kH != 3 || kW != 3) return false;
+  if (p.C % CB || p.R % TRC) return false;
+  if (p.act_bytes >= OOB || p.wgt_bytes >= OOB) return false;
+  p.Hv = p.Ho - 1 + kH;
+  p.Wv = p.Wo - 1 + kW;
+  if (max_window_pixels(p, kH) > HUNITS * HRPU) return false;
+  p.dHoWo = make_fastdiv(p.Ho * p.Wo);
+  p.dWo = make_fastdiv(p.Wo);
+  p.dHv = make_fastdiv(p.Hv);
+  p.dWv = make_fastdiv(p.Wv);
+  p.ntr = p.R / TRC;
+  p.nchunks = p.C / CB;
+  // small tiles are for problems that would not fill the chip with larger ones
+  const long long tiles = (long long)ceil_div(p.M, TP) * p.ntr;
+  return tiles >= 96 && tiles <= 640;
+}
+
+bool fprop_params(const Geom& g, StParams* p) {
+  StParams& q = *p;
+  q = StParams{};
+  if (g.sh != 1 || g.sw != 1) return false;
+  q.N = g.N; q.C = g.Cin; q.H = g.Hin; q.W = g.Win; q.Ho = g.Hout; q.Wo = g.Wout; q.R = g.Cout; q.M = g.M;
+  q.ph = g.ph; q.pw = g.pw;
+  q.wt0 = 0; q.wt_row = g.kW; q.wt_col = 1;
+  q.wrow = g.kH * g.kW * g.Cin;
+  q.act_n_stride = g.Hin * g.Win * g.Cin; q.act_h_stride = g.Win * g.Cin; q.act_w_stride = g.Cin;
+  if ((size_t)g.Min * g.Cin * 2 >= OOB || (size_t)g.Cout * g.K * 2 >= OOB) return false;
+  q.act_bytes = (unsigned)((size_t)g.Min * g.Cin * 2);
+  q.wgt_bytes = (unsigned)((size_t)g.Cout * g.K * 2);
+  return finish_plan(q, g.kH, g.kW);
+}
+
+bool dgrad_params(const Geom& g, StParams* p) {
+  StParams& q = *p;
+  q = StParams{};
+  if (g.sh != 1 || g.sw != 1) return false;
+  if (g.ph > g.kH - 1 || g.pw > g.kW - 1) return false;
+  q.N = g.N; q.C = g.Cout; q.H = g.Hout; q.W = g.Wout; q.Ho = g.Hin; q.Wo = g.Win; q.R = g.Cin; q.M = g.Min;
+  q.ph = g.kH - 1 - g.ph; q.pw = g.kW - 1 - g.pw;
+  q.wt0 = g.kH * g.kW - 1; q.wt_row = -g.kW; q.wt_col = -1;   // rotated kernel
+  q.wrow = g.kH * g.kW * g.Cout;
+  q.act_n_stride = g.Hout * g.Wout * g.Cout; q.act_h_stride = g.Wout * g.Cout; q.act_w_stride = g.Cout;
+  if ((size_t)g.M * g.Cout * 2 >= OOB || (size_t)g.Cout * g.K * 2 >= OOB) return false;
+  q.act_bytes = (unsigned)((size_t)g.M * g.Cout * 2);
+  q.wgt_bytes = (unsigned)((size_t)g.Cout * g.K * 2);
+  return finish_plan(q, g.kH, g.kW);
+}
+
+hipError_t launch(const StParams& p, hipStream_t st) {
+  static std::once_flag once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(once, [] {
+    attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_st_kernel<3, 3>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  });
+  if (attr_err != hipSuccess) return attr_err;
+  const int tiles = ceil_div(p.M, TP) * p.ntr;
+  hipLaunchKernelGGL((conv_st_kernel<3, 3>), dim3(tiles), dim3(64 * NWAVES), LDS_BYTES, st, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool st_fprop_supported(const Geom& g, int dtype) {
+  StParams p;
+  return dtype == CONVBN_BF16 && fprop_params(g, &p);
+}
+bool st_dgrad_supported(const Geom& g, int dtype) {
+  StParams p;
+  return dtype == CONVBN_BF16 && dgrad_params(g, &p);
+}
+hipError_t launch_fprop_st(const Geom& g, const void* x, const void* w_krsc, const float* bias, void* z,
+                           hipStream_t st) {
+  StParams p;
+  if (!fprop_params(g, &p)) return hipErrorInvalidValue;
+  p.act = (const bf16_t*)x; p.wgt = (const bf16_t*)w_krsc; p.bias = bias; p.out = (bf16_t*)z;
+  return launch(p, st);
+}
+hipError_t launch_dgrad_st(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
+                           hipStream_t st) {
+  StParams p;
+  if (!dgrad_params(g, &p)) return hipErrorInvalidValue;
+  p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
+  return launch(p, st);
+}
+
+}  // namespace convbn
