@@ -9,9 +9,13 @@
 // and the fp32 partial sums of such a split were measured to cost more than the larger tile saves.  At 64 x 128
 // the kernel is bound by how fast a compute unit can pull the folded weight out of the L2 (16 KB per
 // 64-channel step for 256 cycles of matrix work).  That rate depends on how many waves issue the copies: four
-// waves sustain about 30 bytes per clock, eight about 50.  So the tile is shared by eight waves (2 pixel groups
-// x 4 channel groups, one 32 x 32 accumulator tile each) instead of four: every wave issues half the copies,
-// and the matrix pipe of a SIMD is fed by two waves.
+// waves sustain about 30 bytes per clock, eight about 50.  So the tile is shared by eight waves instead of four:
+// every wave issues half the copies, and the matrix pipe of a SIMD is fed by two waves.  The eight waves are
+// 2 pixel groups (32 pixels) x 4 quarters of the reduction: a wave multiplies one of the four 16-channel k-steps
+// of every step for all 128 output channels (4 accumulator tiles, 5 operand reads for 4 multiplies -- with one
+// 32 x 32 tile per wave it would be 2 reads per multiply, and the LDS, which serves about one wave-wide read
+// per 5 clocks whatever its width, would be the bound), and the four waves of a pixel group add their sums
+// through LDS at the end.
 //
 // Layout in LDS.  Activations: the window rows the tile's pixels touch, [slot][column][64 channels] with zero
 // rows / columns for the padding (out-of-image pixels are copies with an out-of-range buffer offset: zeros),
@@ -21,8 +25,8 @@
 // the eight granules of a row permuted by (row / 2) % 8 -- chosen by the copy, which picks the granule each
 // lane fetches -- so that a slab is exactly sixteen 1 KB copies, two per wave and step.
 //
-// Pipeline: as in the large-tile kernel.  A step = one tap of one 64-channel chunk = 4 k-steps x 1 MFMA per
-// wave; the taps are unrolled; during step s a wave issues its 2 KB of the slab of step s + 3 and, in the
+// Pipeline: as in the large-tile kernel.  A step = one tap of one 64-channel chunk = 4 MFMAs per wave (its
+// k-step, four channel subtiles); the taps are unrolled; during step s a wave issues its 2 KB of the slab of step s + 3 and, in the
 // first four taps of a chunk, one unit of the next chunk's window tile.  "At most the copies of step s - 1
 // outstanding" at the barrier of step s means the slab of step s + 1 and the next window tile are resident.
 #include "common.h"
@@ -61,15 +65,17 @@ constexpr int NWAVES = 8;
 constexpr int HROW = 144;               // window-tile row pitch: 128 bytes of channels + one pad granule
 constexpr int HRPU = 7;                 // whole rows per 1 KB copy (its last lane spills into the next row)
 constexpr int HUNIT = HRPU * HROW;      // 1008
-constexpr int HUW = 4;                  // window-tile copies per wave and chunk
-constexpr int HUNITS = NWAVES * HUW;    // 32 -> at most 224 window pixels per tile
+constexpr int HUW = 3;                  // window-tile copies per wave and chunk
+constexpr int HUNITS = NWAVES * HUW;    // 24 -> at most 168 window pixels per tile
 constexpr int HBUF = HUNITS * HUNIT + 64;
 constexpr int WSLAB = TRC * CB * 2;     // 16384
-constexpr int NBUF = 4;
+constexpr int NBUF = 6;                 // weight ring: a slab is fetched five steps before its step (L2 latency is
+                                        // several steps long)
 constexpr int DIST = NBUF - 1;
 constexpr int OFF_W = 1024;             // bias first
 constexpr int OFF_H = OFF_W + NBUF * WSLAB;
-constexpr int LDS_BYTES = OFF_H + 2 * HBUF;
+constexpr int RED_BYTES = 2 * 4 * 16 * 64 * 16;   // the final reduction: eight waves' accumulators
+constexpr int LDS_BYTES = (OFF_H + 2 * HBUF) > (OFF_W + RED_BYTES) ? (OFF_H + 2 * HBUF) : (OFF_W + RED_BYTES);
 constexpr unsigned OOB = 0x80000000u;
 
 struct StParams {
@@ -112,7 +118,7 @@ template <int N> __device__ __forceinline__ void wait_vm() {
 template <int KH, int KW>
 __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
   constexpr int TAPS = KH * KW;
-  static_assert(TAPS >= HUW + 1 && TAPS >= DIST, "the copy schedule assumes a window of at least five taps");
+  static_assert(TAPS >= HUW + DIST - 1 && DIST == 5, "the copy schedule assumes a window of at least seven taps and a ring of six slabs");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   float* biasl = reinterpret_cast<float*>(smem);
   unsigned char* wbuf = smem + OFF_W;
@@ -120,7 +126,7 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wpx = wave & 1, wch = wave >> 1;
+  const int wpx = wave & 1, kq = wave >> 1;   // pixel group, and which k-step of every step this wave multiplies
   const int ctile = blockIdx.x % p.ntr, ptile = blockIdx.x / p.ntr;
   const int r0 = ctile * TRC;
   const int HoWo = p.Ho * p.Wo;
@@ -186,17 +192,20 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
     }
     boff = (unsigned)(pixidx * HROW + kb * 16);
   }
-  // weight row of this lane: granule 2 kk + kb sits at position (2 kk + kb) ^ key, key = (row / 2) % 8
+  // weight rows of this lane (row l % 32 of each of the four 32-channel subtiles): granule 2 kq + kb sits at
+  // position (2 kq + kb) ^ key, key = (row / 2) % 8 -- the same for the four rows, which are 32 apart
   unsigned aoff;
   {
-    const int row = wch * 32 + (lane & 31);
+    const int row = lane & 31;
     const int key = (row >> 1) & 7;
-    aoff = (unsigned)(row * 128 + ((kb ^ (key & 1)) << 4) + ((key >> 1) << 5));   // k-step kk: xor (kk << 5)
+    aoff = (unsigned)(row * 128 + ((((2 * kq + kb) ^ key) & 7) << 4));
   }
 
-  f32x16 acc;
+  f32x16 acc[4];
 #pragma unroll
-  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
 
   auto issue_weights = [&](int chunk, int t, int slot) {
     const unsigned soff = (unsigned)(wsoff[t] + chunk * (CB * 2));
@@ -213,16 +222,17 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
 #pragma unroll
   for (int s = 0; s < DIST; ++s) issue_weights(0, s, s);
 
-  bf16x8 fa[2], fb[2];
-  // operands of k-step kk: weights from ring slot `slot`, pixels from window tile `hb` at tap offset `to`
-  auto load_frags = [&](int buf, int slot, int hb, int to, int kk) {
-    fa[buf] = *reinterpret_cast<const bf16x8*>(wbuf + slot * WSLAB + (aoff ^ (unsigned)(kk << 5)));
-    fb[buf] = *reinterpret_cast<const bf16x8*>(halo + hb * HBUF + to + kk * 32 + boff);
+  bf16x8 fa[2][4], fb[2];
+  // operands of this wave's k-step of a step: weights from ring slot `slot`, pixels from window tile `hb` at tap offset `to`
+  auto load_frags = [&](int buf, int slot, int hb, int to) {
+    fb[buf] = *reinterpret_cast<const bf16x8*>(halo + hb * HBUF + to + kq * 32 + boff);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(wbuf + slot * WSLAB + aoff + i * 4096);
   };
 
   wait_vm<0>();
   block_barrier();
-  load_frags(0, 0, 0, toff[0], 0);
+  load_frags(0, 0, 0, toff[0]);
 
   int slot = 0;   // ring slot of the current step
   for (int c = 0; c < nchunks; ++c) {
@@ -230,46 +240,79 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
     const int cnext = min(c + 1, nchunks - 1);   // past the end: the last chunk again (nobody reads it)
 #pragma unroll
     for (int t = 0; t < TAPS; ++t) {
-      // copies that may still be in flight: those of the previous step (2 weight units, + 1 window unit in taps 0..3)
-      if (t == 0 || t > HUW) wait_vm<2>(); else wait_vm<3>();
+      // copies that may still be in flight: those of the DIST - 2 previous steps (2 weight units each, + 1 window
+      // unit in the first HUW taps of a chunk) -- the slab of step s + 1 was issued DIST - 1 steps ago
+      {
+        int inflight = 0;
+#pragma unroll
+        for (int d = 1; d <= DIST - 2; ++d) inflight += 2 + (((t - d + TAPS) % TAPS) < HUW ? 1 : 0);
+        if (inflight == 6) wait_vm<6>(); else if (inflight == 7) wait_vm<7>(); else if (inflight == 8) wait_vm<8>();
+        else wait_vm<9>();
+      }
       block_barrier();
       const int t3 = (t + DIST) % TAPS;
       const int c3 = (t + DIST) >= TAPS ? cnext : c;
-      const int slot_n = (slot + 1) & (NBUF - 1);
-      const int slot_f = (slot + DIST) & (NBUF - 1);
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        if (kk + 1 < KK) load_frags((kk + 1) & 1, slot, hb, toff[t], kk + 1);
-        else if (t + 1 < TAPS) load_frags((kk + 1) & 1, slot_n, hb, toff[t + 1], 0);
-        else load_frags((kk + 1) & 1, slot_n, hb ^ 1, toff[0], 0);
-        __builtin_amdgcn_sched_barrier(0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1], fb[kk & 1], acc, 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (kk == 0) issue_weights(c3, t3, slot_f);
-        if (kk == 1 && t < HUW) issue_halo(cnext, t, hb ^ 1);
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      const int slot_n = slot + 1 == NBUF ? 0 : slot + 1;
+      const int slot_f = slot + DIST >= NBUF ? slot + DIST - NBUF : slot + DIST;
+      const int cur = t & 1;
+      // the next step's operands (its slab and window tile are resident, see the header) while this step multiplies
+      if (t + 1 < TAPS) load_frags(cur ^ 1, slot_n, hb, toff[t + 1]);
+      else load_frags(cur ^ 1, slot_n, hb ^ 1, toff[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][0], fb[cur], acc[0], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      issue_weights(c3, t3, slot_f);
+      __builtin_amdgcn_sched_barrier(0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][1], fb[cur], acc[1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (t < HUW) issue_halo(cnext, t, hb ^ 1);
+      __builtin_amdgcn_sched_barrier(0);
+      acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][2], fb[cur], acc[2], 0, 0, 0);
+      acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][3], fb[cur], acc[3], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
       slot = slot_n;
+    }
+    if (TAPS & 1) {   // an odd number of steps per chunk: the operands fetched last sit in buffer 1, the next chunk starts from 0
+      fb[0] = fb[1];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fa[0][i] = fa[1][i];
     }
   }
   wait_vm<0>();   // trailing copies must not outlive the workgroup's LDS
 
-  // ---- epilogue: bias, one rounding to bf16, 16-byte stores ------------------------------------------------
-  // Accumulator element e of lane l: channel 8 (e / 4) + 4 (l / 32) + e % 4 of the wave's 32, pixel l % 32.
-  // Each wave rounds its 32 x 32 block into its own 2 KB of LDS ([pixel][32 ch], granules swizzled by pixel)
-  // and reads it back row-wise: four lanes cover one pixel's 64 contiguous bytes.
+  // ---- epilogue: the four waves of a pixel group add their sums, then bias, one rounding to bf16, 16-byte stores ----
+  // Accumulator element e of lane l in subtile i: channel 32 i + 8 (e / 4) + 4 (l / 32) + e % 4, pixel l % 32.
+  // Every wave leaves its four subtiles in LDS as [pixel group][wave kq][subtile][q][lane] float4; wave kq then sums
+  // the four copies of subtile kq, rounds its 32 x 32 block into its own 2 KB of LDS ([pixel][32 ch], granules
+  // swizzled by pixel) and reads it back row-wise: four lanes cover one pixel's 64 contiguous bytes.
   if (tid < TRC) biasl[tid] = bias_v;
-  __syncthreads();
+  __syncthreads();   // every wave is done with the ring and the window tiles
   {
+    float4* red = reinterpret_cast<float4*>(smem + OFF_W);
+    float4* mine = red + ((wpx * 4 + kq) * 16) * 64 + lane;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        mine[(i * 4 + q) * 64] = make_float4(acc[i][4 * q], acc[i][4 * q + 1], acc[i][4 * q + 2], acc[i][4 * q + 3]);
+    __syncthreads();
+    float4 sum[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4* src = red + ((wpx * 4) * 16 + kq * 4 + q) * 64 + lane;
+      const float4 c0 = src[0], c1 = src[16 * 64], c2 = src[2 * 16 * 64], c3 = src[3 * 16 * 64];
+      sum[q] = make_float4((c0.x + c1.x) + (c2.x + c3.x), (c0.y + c1.y) + (c2.y + c3.y), (c0.z + c1.z) + (c2.z + c3.z),
+                           (c0.w + c1.w) + (c2.w + c3.w));
+    }
+    __syncthreads();   // all copies read: their space holds the staging blocks next
     unsigned char* stage = smem + OFF_W + wave * 2048;
     const int px = lane & 31;
     const int psw = (px >> 1) & 3;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int ch = q * 8 + kb * 4;
-      const float4 bb = *reinterpret_cast<const float4*>(biasl + wch * 32 + ch);
-      const uint2 v = make_uint2(pack_bf16x2(acc[q * 4 + 0] + bb.x, acc[q * 4 + 1] + bb.y),
-                                 pack_bf16x2(acc[q * 4 + 2] + bb.z, acc[q * 4 + 3] + bb.w));
+      const float4 bb = *reinterpret_cast<const float4*>(biasl + kq * 32 + ch);
+      const uint2 v = make_uint2(pack_bf16x2(sum[q].x + bb.x, sum[q].y + bb.y), pack_bf16x2(sum[q].z + bb.z, sum[q].w + bb.w));
       *reinterpret_cast<uint2*>(stage + px * 64 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
     }
 #pragma unroll
@@ -278,7 +321,7 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
       const int g = (lane & 3) ^ ((row >> 1) & 3);
       const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 64 + ((lane & 3) << 4));
       const int pi = wpx * 32 + row;
-      if (pi < len) *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + pi) * p.R + r0 + wch * 32 + g * 8) = v;
+      if (pi < len) *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + pi) * p.R + r0 + kq * 32 + g * 8) = v;
     }
   }
 }
