@@ -570,6 +570,13 @@ convbn_status convbn_tune_fwd(const convbn_desc* desc, const void* x, const void
   if (s != CONVBN_OK) return s;
   const TuneFwdWs w = carve_tune_fwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (!w_folded && !needs_cin_pad(g, dt) && !pw_fprop_supported(g, dt) && st_fprop_supported(g, dt)) {
+    // Nothing is kept for backward (which folds again), so no w' has to exist: the scale is per output channel,
+    // Z = s (w (*) X) + b' (Sec. 3.3), and the convolution applies s and b' in its epilogue -- one launch.
+    const BnEpilogue bn{gamma, beta, mean, var, b, g.eps};
+    LAUNCH(launch_fprop_st(g, x, W, nullptr, z, st, &bn));
+    return CONVBN_OK;
+  }
   // w' = s w (both orders), b' = (b - mu) s + beta; then Z = w' (*) X + b'
   LAUNCH(launch_fold(g, dt, W, b, gamma, beta, mean, var, 0, w.w_krsc, w_folded, w.bfold, st));
   LAUNCH(run_fprop(g, dt, x, w.w_krsc, w.bfold, z, w.conv_scratch, st));
@@ -599,19 +606,27 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
   if (s != CONVBN_OK) return s;
   const TuneBwdWs w = carve_tune_bwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool fused = params && convbn_tune_bwd_is_fused(desc);
+  // Deep layers that kept nothing: the fused weight-gradient launch reads W anyway (for <dw', w>) and leaves w' in
+  // the order the input gradient reads, so it runs first and no separate fold is launched.
+  const bool fold_in_wgrad = fused && dx && !w_folded;
+  if (fused && fold_in_wgrad)
+    LAUNCH(launch_wgrad_sq_fused(g, x, dz, W, b, gamma, mean, var, dW, db, dgamma, dbeta, w.w_crsk, w.dwf_part, st));
   if (dx) {
     const void* wt = w_folded;
     if (!wt) {  // nothing was kept: fold again, transposed order only
-      LAUNCH(launch_fold(g, dt, W, b, gamma, nullptr, mean, var, 0, nullptr, w.w_crsk, nullptr, st));
+      if (!fold_in_wgrad)
+        LAUNCH(launch_fold(g, dt, W, b, gamma, nullptr, mean, var, 0, nullptr, w.w_crsk, nullptr, st));
       wt = w.w_crsk;
     }
     LAUNCH(run_dgrad(g, dt, dz, wt, dx, w.conv_scratch, st));   // dX = w'_rot (*) dZ
   }
   if (!params) return CONVBN_OK;
-  if (convbn_tune_bwd_is_fused(desc)) {
+  if (fused) {
     // deep layers: dw', r and the fold-back in one launch (the fp32 dw' never reaches memory); the space of the
     // fp32 copy holds the few partial sums the workgroups exchange
-    LAUNCH(launch_wgrad_sq_fused(g, x, dz, W, b, gamma, mean, var, dW, db, dgamma, dbeta, w.dwf_part, st));
+    if (!fold_in_wgrad)
+      LAUNCH(launch_wgrad_sq_fused(g, x, dz, W, b, gamma, mean, var, dW, db, dgamma, dbeta, nullptr, w.dwf_part, st));
     return CONVBN_OK;
   }
   LAUNCH(run_wgrad(g, dt, x, dz, w.dwf_part, w.r_part, w.wgrad_scratch, st));   // dw' = dZ (.) X and r = sum dZ (fp32 partials)
@@ -1113,6 +1128,10 @@ convbn_status convbn_tune_fwd_scale_epilogue(const convbn_desc* desc, const void
   const BnEpilogue bn{gamma, beta, mean, var, b, g.eps};
   hipStream_t st = static_cast<hipStream_t>(stream);
   // Z = s (w (*) X) + b': the unfolded weight goes straight into the convolution, one launch in all
+  if (!needs_cin_pad(g, dt) && !pw_fprop_supported(g, dt) && st_fprop_supported(g, dt)) {
+    LAUNCH(launch_fprop_st(g, x, W, nullptr, z, st, &bn));
+    return CONVBN_OK;
+  }
   if (pw_fprop_scaled_supported(g, dt)) { LAUNCH(launch_fprop_pw(g, x, W, nullptr, z, st, &bn)); return CONVBN_OK; }
   if (!pw_fprop_supported(g, dt) && tile_fprop_scaled_supported(g, dt)) {
     LAUNCH(launch_fprop_tile(g, x, W, nullptr, z, nullptr, st, &bn));

@@ -82,6 +82,7 @@ struct StParams {
   const bf16_t* act;
   const bf16_t* wgt;
   const float* bias;
+  BnEpilogue bn;                  // bn.gamma != null: the weight is unfolded, the epilogue applies s and b' (bias unused)
   bf16_t* out;
   unsigned act_bytes, wgt_bytes;
   int N, H, W, C;
@@ -142,6 +143,12 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
   const int nchunks = p.nchunks;
 
   float bias_v = (tid < TRC && p.bias) ? p.bias[r0 + tid] : 0.f;
+  float scale_v = 1.f;
+  if (p.bn.gamma && tid < TRC) {   // Z = s (w (*) X) + b' with s and b' worked out here (Sec. 3.3), no folded weight
+    const int ch = r0 + tid;
+    scale_v = p.bn.gamma[ch] / sqrtf(p.bn.var[ch] + p.bn.eps);
+    bias_v = ((p.bn.b ? p.bn.b[ch] : 0.f) - p.bn.mean[ch]) * scale_v + p.bn.beta[ch];
+  }
 
   // window-tile copies of this wave: unit wave + 8 t, t = 0..3; per-lane byte offsets without the chunk
   unsigned hv[HUW];
@@ -285,7 +292,7 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
   // Every wave leaves its four subtiles in LDS as [pixel group][wave kq][subtile][q][lane] float4; wave kq then sums
   // the four copies of subtile kq, rounds its 32 x 32 block into its own 2 KB of LDS ([pixel][32 ch], granules
   // swizzled by pixel) and reads it back row-wise: four lanes cover one pixel's 64 contiguous bytes.
-  if (tid < TRC) biasl[tid] = bias_v;
+  if (tid < TRC) { biasl[tid] = bias_v; biasl[TRC + tid] = scale_v; }
   __syncthreads();   // every wave is done with the ring and the window tiles
   {
     float4* red = reinterpret_cast<float4*>(smem + OFF_W);
@@ -312,7 +319,9 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
     for (int q = 0; q < 4; ++q) {
       const int ch = q * 8 + kb * 4;
       const float4 bb = *reinterpret_cast<const float4*>(biasl + kq * 32 + ch);
-      const uint2 v = make_uint2(pack_bf16x2(sum[q].x + bb.x, sum[q].y + bb.y), pack_bf16x2(sum[q].z + bb.z, sum[q].w + bb.w));
+      const float4 sc = *reinterpret_cast<const float4*>(biasl + TRC + kq * 32 + ch);
+      const uint2 v = make_uint2(pack_bf16x2(fmaf(sum[q].x, sc.x, bb.x), fmaf(sum[q].y, sc.y, bb.y)),
+                                 pack_bf16x2(fmaf(sum[q].z, sc.z, bb.z), fmaf(sum[q].w, sc.w, bb.w)));
       *reinterpret_cast<uint2*>(stage + px * 64 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
     }
 #pragma unroll
@@ -417,9 +426,10 @@ bool st_dgrad_supported(const Geom& g, int dtype) {
   return dtype == CONVBN_BF16 && dgrad_params(g, &p);
 }
 hipError_t launch_fprop_st(const Geom& g, const void* x, const void* w_krsc, const float* bias, void* z,
-                           hipStream_t st) {
+                           hipStream_t st, const BnEpilogue* bn) {
   StParams p;
   if (!fprop_params(g, &p)) return hipErrorInvalidValue;
+  if (bn) p.bn = *bn;
   p.act = (const bf16_t*)x; p.wgt = (const bf16_t*)w_krsc; p.bias = bias; p.out = (bf16_t*)z;
   return launch(p, st);
 }

@@ -66,6 +66,7 @@ struct SqParams {
   // count their arrival; the last one finishes dgamma, dbeta, db for the tile's 32 channels.
   const bf16_t* wgt;   // the unfolded weight; null: not fused
   bf16_t* dW;
+  bf16_t* w_t;         // nullable: also leave w' = s w as [Cin][taps][Cout], the order the input-gradient pass reads
   const float* gamma; const float* mean; const float* var; const float* b;
   float* db; float* dgamma; float* dbeta;
   float* dot_part;
@@ -421,6 +422,12 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
         dot += v[0] * bf16_lo(w.x) + v[1] * bf16_hi(w.x) + v[2] * bf16_lo(w.y) + v[3] * bf16_hi(w.y);
         *reinterpret_cast<uint2*>(p.dW + o + 8 * q) =
             make_uint2(pack_bf16x2(scale * v[0], scale * v[1]), pack_bf16x2(scale * v[2], scale * v[3]));
+        if (p.w_t) {   // the fold of Sec. 3.3 for this block of the weight, transposed: 32 lanes = 32 consecutive output channels
+          const float wf[4] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y)};
+          bf16_t* wt = p.w_t + ((size_t)(ci0 + 8 * q + 4 * kb) * TAPS + tap) * p.Co + co0 + co_l;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) wt[(size_t)e * TAPS * p.Co] = from_f32<bf16_t>(wf[e] * scale);
+        }
       } else {
         *reinterpret_cast<float4*>(p.part + o + 8 * q) = make_float4(v[0], v[1], v[2], v[3]);
       }
@@ -590,13 +597,13 @@ size_t wgrad_sq_fused_scratch_bytes(const Geom& g) {
 
 hipError_t launch_wgrad_sq_fused(const Geom& g, const void* x, const void* dz, const void* W, const float* b,
                                  const float* gamma, const float* mean, const float* var, void* dW, float* db,
-                                 float* dgamma, float* dbeta, void* scratch, hipStream_t st) {
+                                 float* dgamma, float* dbeta, void* w_folded_out, void* scratch, hipStream_t st) {
   SqParams p;
   const SqPlan pl = make_plan(g, &p);
   if (!pl.ok || pl.nsplit != 1 || !scratch) return hipErrorInvalidValue;
   p.x = (const bf16_t*)x; p.dz = (const bf16_t*)dz; p.part = nullptr;
   p.r_part = reinterpret_cast<float*>(scratch);   // only its non-NULL-ness matters here: the channel sums are wanted
-  p.wgt = (const bf16_t*)W; p.dW = (bf16_t*)dW; p.gamma = gamma; p.mean = mean; p.var = var; p.b = b;
+  p.wgt = (const bf16_t*)W; p.dW = (bf16_t*)dW; p.w_t = (bf16_t*)w_folded_out; p.gamma = gamma; p.mean = mean; p.var = var; p.b = b;
   p.db = db; p.dgamma = dgamma; p.dbeta = dbeta; p.eps = g.eps;
   p.counters = reinterpret_cast<unsigned long long*>(scratch);
   p.dot_part = reinterpret_cast<float*>(reinterpret_cast<char*>(scratch) + align_up((size_t)p.nco * 8, 256));

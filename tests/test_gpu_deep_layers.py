@@ -36,3 +36,20 @@ def test_deep_layer_block(shape, kw):
     compare(second, ref, "bf16", tag=shape.name + "/second")
     for k in ("Z", "dX", "dW", "dgamma", "dbeta"):   # split sums and partial dot products are combined in a fixed order
         assert torch.equal(first[k], second[k]), k
+
+
+@pytest.mark.parametrize("kw", [dict(), dict(bias=True, wide_scale=True)], ids=["plain", "bias_wide_scale"])
+def test_deep_layer_that_keeps_nothing(kw):
+    """A block whose w' is larger than its output keeps nothing between the passes (P > A_z): forward then needs no
+    folded weight at all (the scale and the folded bias are applied in the convolution's epilogue) and backward folds
+    again.  Same definition, same tolerances."""
+    from paper_2305_11624_amd.runner import BlockRun
+    shape = BlockShape("deep_refold", 35, 512, 7, 7, 512, 3, 1, 1, "bf16", 67)
+    assert shape.P > shape.A_z
+    inp = synth.make_inputs(shape, **kw)
+    ref = oracle_block(inp)
+    run = BlockRun(inp, mode="tune", keep_folded=False, poison=True)
+    run.step()
+    res = run.results()
+    assert res["Wf"] is None
+    compare(res, ref, "bf16", tag="deep_refold")
