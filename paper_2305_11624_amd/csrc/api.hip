@@ -570,12 +570,13 @@ convbn_status convbn_tune_fwd(const convbn_desc* desc, const void* x, const void
   if (s != CONVBN_OK) return s;
   const TuneFwdWs w = carve_tune_fwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (!w_folded && !needs_cin_pad(g, dt) && !pw_fprop_supported(g, dt) && st_fprop_supported(g, dt)) {
-    // Nothing is kept for backward (which folds again), so no w' has to exist: the scale is per output channel,
-    // Z = s (w (*) X) + b' (Sec. 3.3), and the convolution applies s and b' in its epilogue -- one launch.
-    const BnEpilogue bn{gamma, beta, mean, var, b, g.eps};
-    LAUNCH(launch_fprop_st(g, x, W, nullptr, z, st, &bn));
-    return CONVBN_OK;
+  if (!needs_cin_pad(g, dt) && !pw_fprop_supported(g, dt) && (g.kH > 1 || g.kW > 1)) {
+    // The scale is per output channel, so Z = s (w (*) X) + b' (Sec. 3.3): the convolution reads the unfolded
+    // weight and applies s and b' in its epilogue, and -- where w' is kept for backward -- its workgroups each
+    // write a slice of w' on the side.  The forward pass is one launch; no w' is materialised for it.
+    const BnEpilogue bn{gamma, beta, mean, var, b, g.eps, w_folded, g.kH * g.kW, g.Cin, g.Cout};
+    if (st_fprop_supported(g, dt)) { LAUNCH(launch_fprop_st(g, x, W, nullptr, z, st, &bn)); return CONVBN_OK; }
+    if (tile_fprop_scaled_supported(g, dt)) { LAUNCH(launch_fprop_tile(g, x, W, nullptr, z, nullptr, st, &bn)); return CONVBN_OK; }
   }
   // w' = s w (both orders), b' = (b - mu) s + beta; then Z = w' (*) X + b'
   LAUNCH(launch_fold(g, dt, W, b, gamma, beta, mean, var, 0, w.w_krsc, w_folded, w.bfold, st));
@@ -1125,7 +1126,7 @@ convbn_status convbn_tune_fwd_scale_epilogue(const convbn_desc* desc, const void
   REQUIRE_PTR(var); REQUIRE_PTR(z);
   OPTIONAL_PTR(b);
   const int dt = desc->dtype;
-  const BnEpilogue bn{gamma, beta, mean, var, b, g.eps};
+  const BnEpilogue bn{gamma, beta, mean, var, b, g.eps, nullptr, g.kH * g.kW, g.Cin, g.Cout};
   hipStream_t st = static_cast<hipStream_t>(stream);
   // Z = s (w (*) X) + b': the unfolded weight goes straight into the convolution, one launch in all
   if (!needs_cin_pad(g, dt) && !pw_fprop_supported(g, dt) && st_fprop_supported(g, dt)) {

@@ -56,7 +56,27 @@ struct BnEpilogue {
   const float* var;
   const float* b;   // convolution bias or nullptr
   float eps;
+  // Optional: the launch also leaves w' = s w as [Cin][taps][Cout] -- what Tune mode keeps for backward (Sec. 3.4.2)
+  // -- every workgroup writing one slice of it, so that a forward pass that keeps w' is still a single launch.
+  void* w_folded_out;
+  int taps, Cin, Cout;
 };
+
+// Slice `wg` of `nwg` of w' = bf16(float(w) s), written in [Cin][taps][Cout] order (w is [Cout][taps][Cin]); the same
+// values, bit for bit, as the fold kernel's.  Called by all threads of a workgroup.
+__device__ __forceinline__ void emit_folded_slice(const BnEpilogue& bn, const bf16_t* __restrict__ w, int wg, int nwg) {
+  bf16_t* out = static_cast<bf16_t*>(bn.w_folded_out);
+  const int P = bn.Cout * bn.taps * bn.Cin;
+  const int per = (P + nwg - 1) / nwg;
+  const int end = min(P, (wg + 1) * per);
+  for (int j = wg * per + (int)threadIdx.x; j < end; j += (int)blockDim.x) {
+    const int co = j % bn.Cout;
+    const int rest = j / bn.Cout;
+    const int tap = rest % bn.taps, ci = rest / bn.taps;
+    const float s = bn.gamma[co] / sqrtf(bn.var[co] + bn.eps);
+    out[j] = (bf16_t)((float)w[((size_t)co * bn.taps + tap) * bn.Cin + ci] * s);
+  }
+}
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

@@ -237,6 +237,7 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
     for (int i = 0; i < 4; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(wbuf + slot * WSLAB + aoff + i * 4096);
   };
 
+  if (p.bn.gamma && p.bn.w_folded_out) emit_folded_slice(p.bn, p.wgt, blockIdx.x, gridDim.x);   // while the first copies are in flight
   wait_vm<0>();
   block_barrier();
   load_frags(0, 0, 0, toff[0]);

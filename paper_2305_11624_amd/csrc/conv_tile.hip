@@ -366,6 +366,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     for (int r = 0; r < NCW; ++r) fa[buf][r] = *reinterpret_cast<const bf16x8*>(a + r * 32 * ROWP + kk * 32);
   };
 
+  if (SC && p.bn.w_folded_out) emit_folded_slice(p.bn, p.wgt, blockIdx.x, gridDim.x);   // while the first copies are in flight
   wait_vm<(DIST - 1) * (WPW + HPS)>();   // the activation tile of the first chunk and the slab of step 0 have landed
   block_barrier();
   load_frags(0, wlane, bstep, 0);

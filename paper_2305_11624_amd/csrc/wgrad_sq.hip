@@ -138,7 +138,10 @@ constexpr int reads_through(int s) { return 2 * (s + 1) + 2 * (s / TAPS + 1); }
 
 #ifdef SQ_TRACE
 __device__ unsigned long long sq_trace[512 * 64];
-#define STAMP(i) do { if (tid == 0 && (i) < 64) sq_trace[blockIdx.x * 64 + (i)] = clock64(); } while (0)
+#ifndef SQ_TRACE_WAVE
+#define SQ_TRACE_WAVE 0
+#endif
+#define STAMP(i) do { if (tid == 64 * SQ_TRACE_WAVE && (i) < 64) sq_trace[blockIdx.x * 64 + (i)] = clock64(); } while (0)
 #else
 #define STAMP(i) do {} while (0)
 #endif
@@ -273,9 +276,11 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
   int stage_off = 0;                        // byte offset of the current tile's stage
   STAMP(1);
   for (int tile = tile_beg; tile < tile_end; ++tile) {
+    STAMP(20 + 2 * (tile - tile_beg) < 58 ? 20 + 2 * (tile - tile_beg) : 63);
     // this tile has landed; the next one's copies may be in flight
     if (has_last) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCPY) : "memory");
     else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCPY - 1) : "memory");
+    STAMP(21 + 2 * (tile - tile_beg) < 59 ? 21 + 2 * (tile - tile_beg) : 63);
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();          // ... for every wave; everybody is done with the stage refilled below
     asm volatile("" ::: "memory");

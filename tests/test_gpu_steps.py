@@ -167,6 +167,56 @@ def test_fold_group_matches_single_folds():
     assert B.convbn_fold_group_plan([bad], check=False) == B.ERR_UNSUPPORTED
 
 
+def test_fold_back_group_matches_single_fold_backs():
+    """Several blocks' fold-backs in one launch: bit-identical to one convbn_fold_back call per block where that call
+    runs its 256-thread kernel (more than 128 output channels, or fewer than 16 partial copies), equal up to the order
+    of the partial sums otherwise."""
+    from paper_2305_11624_amd import binding as B
+    shapes = [BlockShape("fb_3x3", 2, 64, 12, 12, 192, 3, 1, 1, "bf16", 86),
+              BlockShape("fb_1x1", 4, 256, 8, 8, 256, 1, 1, 0, "bf16", 87),
+              BlockShape("fb_few", 16, 64, 28, 28, 64, 3, 1, 1, "bf16", 88),     # few channels, many partial copies
+              BlockShape("fb_s2", 2, 128, 14, 14, 136, 3, 2, 1, "bf16", 89)]
+    blocks, singles = [], []
+    for i, sh in enumerate(shapes):
+        inp = synth.make_inputs(sh, bias=(i == 1))
+        d = B.desc_from_shape(sh, eps=inp["eps"])
+        dt = torch.bfloat16
+        x, W, dz = B.act_to_device(inp["x"], dt), B.weight_to_device(inp["W"], dt), B.act_to_device(inp["dy"], dt)
+        vec = {k: B.vec_to_device(inp[k]) for k in ("b", "gamma", "rmean", "rvar")}
+        ns, nr = B.convbn_wgrad_parts(d), B.convbn_rsum_parts(d)
+        P = sh.Cout * sh.K
+        dw_part = torch.empty(ns * P, dtype=torch.float32, device="cuda")
+        r_part = torch.empty(nr * sh.Cout, dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(16, B.convbn_conv_workspace_bytes(d, B.PASS_BWD)), dtype=torch.uint8, device="cuda")
+        B.convbn_conv_wgrad(d, x, dz, dw_part, r_part, ws)
+        outs = []
+        for _ in range(2):
+            outs.append(dict(dW=torch.full((P,), float("nan"), dtype=dt, device="cuda"),
+                             db=torch.full((sh.Cout,), float("nan"), device="cuda") if vec["b"] is not None else None,
+                             dgamma=torch.full((sh.Cout,), float("nan"), device="cuda"),
+                             dbeta=torch.full((sh.Cout,), float("nan"), device="cuda")))
+        common = dict(desc=d, dw_part=dw_part, r_part=r_part, W=W, b=vec["b"], gamma=vec["gamma"], mean=vec["rmean"],
+                      var=vec["rvar"])
+        blocks.append(dict(common, **outs[0]))
+        singles.append(dict(common, **outs[1], exact=(sh.Cout > 128 or ns < 16)))
+    n, table, grid = B.convbn_fold_back_group_plan(blocks)
+    B.convbn_fold_back_group(n, table, grid)
+    for r in singles:
+        B.convbn_fold_back(r["desc"], r["dw_part"], r["r_part"], r["W"], r["b"], r["gamma"], r["mean"], r["var"], r["dW"],
+                           r["db"], r["dgamma"], r["dbeta"])
+    torch.cuda.synchronize()
+    for g, r in zip(blocks, singles):
+        for k in ("dW", "db", "dgamma", "dbeta"):
+            if r[k] is None:
+                continue
+            assert torch.isfinite(g[k].float()).all(), k
+            if r["exact"]:
+                assert torch.equal(g[k], r[k]), (g["desc"].Cout, k)
+            else:
+                a, b_ = r[k].double(), g[k].double()
+                assert float((a - b_).abs().max() / a.abs().max()) <= (8e-3 if k == "dW" else 1e-5), k
+
+
 @pytest.mark.parametrize("name", ["c2a", "c2b", "c1"])
 def test_scale_in_the_epilogue_forward_matches_the_oracle(name):
     """Forward with the unfolded weight and the BatchNorm scale applied in the convolution's epilogue (the ablation
