@@ -607,27 +607,21 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
   if (s != CONVBN_OK) return s;
   const TuneBwdWs w = carve_tune_bwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const bool fused = params && convbn_tune_bwd_is_fused(desc);
-  // Deep layers that kept nothing: the fused weight-gradient launch reads W anyway (for <dw', w>) and leaves w' in
-  // the order the input gradient reads, so it runs first and no separate fold is launched.
-  const bool fold_in_wgrad = fused && dx && !w_folded;
-  if (fused && fold_in_wgrad)
-    LAUNCH(launch_wgrad_sq_fused(g, x, dz, W, b, gamma, mean, var, dW, db, dgamma, dbeta, w.w_crsk, w.dwf_part, st));
   if (dx) {
     const void* wt = w_folded;
     if (!wt) {  // nothing was kept: fold again, transposed order only
-      if (!fold_in_wgrad)
-        LAUNCH(launch_fold(g, dt, W, b, gamma, nullptr, mean, var, 0, nullptr, w.w_crsk, nullptr, st));
+      LAUNCH(launch_fold(g, dt, W, b, gamma, nullptr, mean, var, 0, nullptr, w.w_crsk, nullptr, st));
       wt = w.w_crsk;
     }
     LAUNCH(run_dgrad(g, dt, dz, wt, dx, w.conv_scratch, st));   // dX = w'_rot (*) dZ
   }
   if (!params) return CONVBN_OK;
-  if (fused) {
+  if (convbn_tune_bwd_is_fused(desc)) {
     // deep layers: dw', r and the fold-back in one launch (the fp32 dw' never reaches memory); the space of the
-    // fp32 copy holds the few partial sums the workgroups exchange
-    if (!fold_in_wgrad)
-      LAUNCH(launch_wgrad_sq_fused(g, x, dz, W, b, gamma, mean, var, dW, db, dgamma, dbeta, nullptr, w.dwf_part, st));
+    // fp32 copy holds the few partial sums the workgroups exchange.  (Letting this launch also write w' for the
+    // input gradient, to save the fold above, was measured: its 64-byte pieces of [Cin][taps][Cout] rows cost
+    // 22 us where the fold kernel takes 5.)
+    LAUNCH(launch_wgrad_sq_fused(g, x, dz, W, b, gamma, mean, var, dW, db, dgamma, dbeta, w.dwf_part, st));
     return CONVBN_OK;
   }
   LAUNCH(run_wgrad(g, dt, x, dz, w.dwf_part, w.r_part, w.wgrad_scratch, st));   // dw' = dZ (.) X and r = sum dZ (fp32 partials)

@@ -277,12 +277,11 @@ int wgrad_sq_splits(const Geom& g);
 hipError_t launch_wgrad_sq(const Geom& g, const void* x, const void* dz, float* dwf_part, float* r_part,
                            hipStream_t st);
 // Weight gradient and fold-back in one launch, for problems whose pixels need no split (deep layers): writes dW,
-// dgamma, dbeta and (b given) db directly; no fp32 copy of dw' is stored.  w_folded_out (nullable): also writes
-// w' = s w as [Cin][kH][kW][Cout], bit for bit what launch_fold writes.  scratch: wgrad_sq_fused_scratch_bytes().
+// dgamma, dbeta and (b given) db directly; no fp32 copy of dw' is stored.  scratch: wgrad_sq_fused_scratch_bytes().
 bool wgrad_sq_fused_supported(const Geom& g, int dtype);
 size_t wgrad_sq_fused_scratch_bytes(const Geom& g);
 hipError_t launch_wgrad_sq_fused(const Geom& g, const void* x, const void* dz, const void* W, const float* b,
                                  const float* gamma, const float* mean, const float* var, void* dW, float* db,
-                                 float* dgamma, float* dbeta, void* w_folded_out, void* scratch, hipStream_t st);
+                                 float* dgamma, float* dbeta, void* scratch, hipStream_t st);
 
 }  // namespace convbn

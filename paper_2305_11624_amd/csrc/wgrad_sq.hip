@@ -62,16 +62,14 @@ struct SqParams {
   float* part;       // [nsplit][Co][taps][Cin]
   float* r_part;     // [nsplit][Co] or null
   // Fused fold-back (Table 2 "Tune", last four lines), one pixel split only: dW = s dw' is stored instead of the
-  // fp32 copy, the workgroups of an output-channel tile leave their partial <dw', w> in dot_part [nci][Co] and
-  // count their arrival; the last one finishes dgamma, dbeta, db for the tile's 32 channels.
+  // fp32 copy, the workgroups of an output-channel tile leave their partial <dw', w> (and r) in tagged slots
+  // [nci + 1][Co]; the one that finds all of them in place finishes dgamma, dbeta, db for the tile's 32 channels.
   const bf16_t* wgt;   // the unfolded weight; null: not fused
   bf16_t* dW;
-  bf16_t* w_t;         // nullable: also leave w' = s w as [Cin][taps][Cout], the order the input-gradient pass reads
   const float* gamma; const float* mean; const float* var; const float* b;
   float* db; float* dgamma; float* dbeta;
-  float* dot_part;
-  unsigned long long* counters;   // [nco]: (launch tag << 8) | arrivals
-  unsigned long long tag;
+  uint4* slots;              // {value, tag low, tag high, 0}
+  unsigned long long tag;    // of this launch, never 0
   float eps;
   unsigned x_bytes, dz_bytes;
   int N, H, W, Cin;
@@ -123,13 +121,19 @@ __device__ __forceinline__ bf16x8 join2(i32x2 a, i32x2 b) {
 
 // Values that cross workgroups (which may run on XCDs whose L2 caches are not coherent with each other) are
 // written through to memory and read past any stale line with device-scope accesses.
-__device__ __forceinline__ void store_device_scope(float* p, float v) {
-  asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_device_scope16(uint4* p, uint4 v) {
+  const u32x4 r = {v.x, v.y, v.z, v.w};
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(r) : "memory");
 }
-__device__ __forceinline__ float load_device_scope(const float* p) {
-  float v;
-  asm volatile("global_load_dword %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
-  return v;
+__device__ __forceinline__ uint4 load_device_scope16(const uint4* p) {
+  u32x4 r;
+  asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(r) : "v"(p) : "memory");
+  return make_uint4(r.x, r.y, r.z, r.w);
+}
+// A slot of the exchange between workgroups: a value and the tag of the launch that wrote it, in one store.
+__device__ __forceinline__ void store_slot(uint4* p, float v, unsigned long long tag) {
+  store_device_scope16(p, make_uint4(__float_as_uint(v), (unsigned)tag, (unsigned)(tag >> 32), 0u));
 }
 
 // Number of transposing reads issued up to and including those of multiply slot s (slot = 9 k + tap): two per
@@ -369,6 +373,23 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
   STAMP(60);
   wait_all_copies();
   __syncthreads();
+  // Fused fold-back: what the epilogue needs from memory (this wave's 32 x 32 blocks of w, four lanes per 64-byte
+  // row, and the channel scale) is requested now and arrives while the accumulators are summed.
+  const bool fused = p.wgt != nullptr;
+  const int co_l = lane & 31;
+  uint4 wpre[2][2] = {};
+  float gam = 1.f, vr = 1.f;
+  if (fused) {
+    gam = p.gamma[co0 + co_l];
+    vr = p.var[co0 + co_l];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+      if (wave + t * NWAVES < TAPS)
+#pragma unroll
+        for (int it = 0; it < 2; ++it)
+          wpre[t][it] = *reinterpret_cast<const uint4*>(
+              p.wgt + ((size_t)(co0 + it * 16 + (lane >> 2)) * TAPS + wave + t * NWAVES) * p.Cin + ci0 + (lane & 3) * 8);
+  }
   // copies as [copy][tap][q][lane] float4 (q = accumulator elements 4 q .. 4 q + 3): every access is 16 bytes per
   // lane, consecutive lanes consecutive banks
   float4* red = reinterpret_cast<float4*>(smem);
@@ -410,38 +431,56 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
   // four copies of taps w and w + 8 in the accumulators' own [e][lane] order (consecutive lanes, consecutive
   // banks) and stores 4 input channels per lane and instruction.
   STAMP(61);
-  const bool fused = p.wgt != nullptr;
-  const int co_l = lane & 31;
-  float scale = 1.f, dot = 0.f;
-  if (fused) scale = p.gamma[co0 + co_l] / sqrtf(p.var[co0 + co_l] + p.eps);
-  for (int tap = wave; tap < TAPS; tap += NWAVES) {
+  float dot = 0.f;
+  const float scale = fused ? gam / sqrtf(vr + p.eps) : 1.f;
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int tap = wave + t * NWAVES;
+    if (tap >= TAPS) break;
     const float4* src = red + (size_t)tap * (4 * 64) + lane;
     const size_t o = (((size_t)split * p.Co + co0 + co_l) * TAPS + tap) * p.Cin + ci0 + 4 * kb;
+    float v[4][4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const float4 c0 = src[q * 64], c1 = src[q * 64 + COPY4], c2 = src[q * 64 + 2 * COPY4], c3 = src[q * 64 + 3 * COPY4];
-      const float v[4] = {(c0.x + c1.x) + (c2.x + c3.x), (c0.y + c1.y) + (c2.y + c3.y), (c0.z + c1.z) + (c2.z + c3.z),
-                          (c0.w + c1.w) + (c2.w + c3.w)};
-      if (fused) {
-        const uint2 w = *reinterpret_cast<const uint2*>(p.wgt + o + 8 * q);
-        dot += v[0] * bf16_lo(w.x) + v[1] * bf16_hi(w.x) + v[2] * bf16_lo(w.y) + v[3] * bf16_hi(w.y);
-        *reinterpret_cast<uint2*>(p.dW + o + 8 * q) =
-            make_uint2(pack_bf16x2(scale * v[0], scale * v[1]), pack_bf16x2(scale * v[2], scale * v[3]));
-        if (p.w_t) {   // the fold of Sec. 3.3 for this block of the weight, transposed: 32 lanes = 32 consecutive output channels
-          const float wf[4] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y)};
-          bf16_t* wt = p.w_t + ((size_t)(ci0 + 8 * q + 4 * kb) * TAPS + tap) * p.Co + co0 + co_l;
+      v[q][0] = (c0.x + c1.x) + (c2.x + c3.x); v[q][1] = (c0.y + c1.y) + (c2.y + c3.y);
+      v[q][2] = (c0.z + c1.z) + (c2.z + c3.z); v[q][3] = (c0.w + c1.w) + (c2.w + c3.w);
+    }
+    if (!fused) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) wt[(size_t)e * TAPS * p.Co] = from_f32<bf16_t>(wf[e] * scale);
-        }
-      } else {
-        *reinterpret_cast<float4*>(p.part + o + 8 * q) = make_float4(v[0], v[1], v[2], v[3]);
-      }
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(p.part + o + 8 * q) = make_float4(v[q][0], v[q][1], v[q][2], v[q][3]);
+      continue;
+    }
+    // Fused fold-back.  In the accumulators a lane holds 4 input channels of one output channel: stores and loads
+    // of that shape would touch memory in 8-byte pieces.  The 32 x 32 block of w and of dW for this tap therefore
+    // passes through LDS (the space of this tap's first accumulator copy, which only this wave uses): global
+    // accesses are 16 bytes per lane, four lanes per 64-byte row of the block.
+    unsigned char* wtile = reinterpret_cast<unsigned char*>(red + (size_t)tap * (4 * 64));   // [32 co][32 ci] bf16
+    unsigned char* otile = wtile + 2048;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int co = it * 16 + (lane >> 2), g = lane & 3;
+      *reinterpret_cast<uint4*>(wtile + co * 64 + g * 16) = wpre[t][it];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint2 w = *reinterpret_cast<const uint2*>(wtile + co_l * 64 + (8 * q + 4 * kb) * 2);
+      dot += v[q][0] * bf16_lo(w.x) + v[q][1] * bf16_hi(w.x) + v[q][2] * bf16_lo(w.y) + v[q][3] * bf16_hi(w.y);
+      *reinterpret_cast<uint2*>(otile + co_l * 64 + (8 * q + 4 * kb) * 2) =
+          make_uint2(pack_bf16x2(scale * v[q][0], scale * v[q][1]), pack_bf16x2(scale * v[q][2], scale * v[q][3]));
+    }
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int co = it * 16 + (lane >> 2), g = lane & 3;
+      *reinterpret_cast<uint4*>(p.dW + ((size_t)(co0 + co) * TAPS + tap) * p.Cin + ci0 + g * 8) =
+          *reinterpret_cast<const uint4*>(otile + co * 64 + g * 16);
     }
   }
   if (do_r && tid < 32) {
     float v = 0.f;
     for (int w = 0; w < NWAVES; ++w) v += rred[w * 32 + tid];
-    if (fused) store_device_scope(p.dot_part + (size_t)p.nci * p.Co + co0 + tid, v);   // r behind the nci rows of dot_part
+    if (fused) store_slot(p.slots + (size_t)p.nci * p.Co + co0 + tid, v, p.tag);   // r: the row behind the nci rows
     else p.r_part[(size_t)split * p.Co + co0 + tid] = v;
   }
   STAMP(62);
@@ -454,33 +493,40 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
   if (tid < 32) {
     float v = 0.f;
     for (int w = 0; w < NWAVES; ++w) v += dred[w * 32 + tid];
-    store_device_scope(p.dot_part + (size_t)cit * p.Co + co0 + tid, v);
+    store_slot(p.slots + (size_t)cit * p.Co + co0 + tid, v, p.tag);
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's values have reached memory ...
-  __syncthreads();                                    // ... and every other thread's, before the arrival is counted
-  int* flag = reinterpret_cast<int*>(dred + NWAVES * 32);
-  if (tid == 0) {
-    unsigned long long* c = p.counters + cot;
-    unsigned long long old = __hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    unsigned long long cnt;
-    for (;;) {   // a word that does not carry this launch's tag is stale: count from zero
-      cnt = (old >> 8) == p.tag ? (old & 255ull) : 0ull;
-      const unsigned long long want = (p.tag << 8) | (cnt + 1);
-      if (__hip_atomic_compare_exchange_strong(c, &old, want, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-        break;
-    }
-    *flag = (int)cnt == p.nci - 1;
-    // the last arrival leaves the count at zero under the same tag: a replay of a captured launch (same arguments,
-    // same tag) starts from zero again
-    if (*flag) __hip_atomic_store(c, p.tag << 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  STAMP(50);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's slots have reached memory ...
+  __syncthreads();                                    // ... and every other thread's, before anyone looks
+  STAMP(51);
+  // Which workgroup of this output-channel tile finishes last is found without a shared counter (an atomic at
+  // device scope is a round trip to memory, and a compare-and-swap loop over 16 workgroups that end together takes
+  // many): a slot carries its value and this launch's tag in one 16-byte store, every workgroup stores its own
+  // slots first and then reads all nci + 1 rows of the tile, a thread per slot.  Whoever finds every tag in place
+  // has all the values in hand and finishes the tile; the workgroup whose stores landed last always does, and if
+  // two do they write the same numbers.  Finishers clear the slots, so a replay of a captured launch (same tag)
+  // finds none of them valid.
+  float mine = 0.f, rmine = 0.f;
+  int ok = 1;
+  for (int i = tid >> 5; i <= p.nci; i += NWAVES * 2) {
+    const uint4 sl = load_device_scope16(p.slots + (size_t)i * p.Co + co0 + (tid & 31));
+    ok &= (((unsigned long long)sl.z << 32) | sl.y) == p.tag;
+    if (i < p.nci) mine += __uint_as_float(sl.x); else rmine = __uint_as_float(sl.x);
   }
+  STAMP(52);
+  if (!__syncthreads_and(ok)) return;
+  for (int i = tid >> 5; i <= p.nci; i += NWAVES * 2)
+    store_device_scope16(p.slots + (size_t)i * p.Co + co0 + (tid & 31), make_uint4(0u, 0u, 0u, 0u));
+  rred[tid] = mine;
+  if ((p.nci >> 4 << 4) + (tid >> 5) == p.nci) rred[NWAVES * 64 + (tid & 31)] = rmine;   // the thread that read row nci
   __syncthreads();
-  if (!*flag || tid >= 32) return;
-  // the last workgroup of this output-channel tile: dgamma = (<dw', w> + r (b - mu)) / sqrt(var + eps), dbeta = r, db = s r
+  STAMP(53);
+  if (tid >= 32) return;
+  // dgamma = (<dw', w> + r (b - mu)) / sqrt(var + eps), dbeta = r, db = s r
   const int ch = co0 + tid;
   float d = 0.f;
-  for (int i = 0; i < p.nci; ++i) d += load_device_scope(p.dot_part + (size_t)i * p.Co + ch);
-  const float r = load_device_scope(p.dot_part + (size_t)p.nci * p.Co + ch);
+  for (int i = 0; i < NWAVES * 2; ++i) d += rred[i * 32 + tid];
+  const float r = rred[NWAVES * 64 + tid];
   const float sd = sqrtf(p.var[ch] + p.eps);
   const float bb = p.b ? p.b[ch] : 0.f;
   p.dgamma[ch] = (d + r * (bb - p.mean[ch])) / sd;
@@ -576,7 +622,8 @@ hipError_t launch_inst(const SqParams& p, const SqPlan& pl, hipStream_t st) {
 unsigned long long next_tag() {
   static std::atomic<unsigned long long> tag{
       (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9E3779B97F4A7C15ull};
-  return tag.fetch_add(1, std::memory_order_relaxed) & ((1ull << 56) - 1);
+  const unsigned long long t = tag.fetch_add(1, std::memory_order_relaxed);
+  return t ? t : tag.fetch_add(1, std::memory_order_relaxed);   // 0 marks a cleared slot
 }
 
 hipError_t dispatch(const SqParams& p, const SqPlan& pl, hipStream_t st) {
@@ -593,25 +640,24 @@ bool wgrad_sq_fused_supported(const Geom& g, int dtype) {
   if (dtype != CONVBN_BF16) return false;
   SqParams p;
   const SqPlan pl = make_plan(g, &p);
-  return pl.ok && pl.nsplit == 1 && p.nci <= 255;
+  return pl.ok && pl.nsplit == 1;
 }
 
 size_t wgrad_sq_fused_scratch_bytes(const Geom& g) {
-  return align_up((size_t)(g.Cout / 32) * 8, 256) + (size_t)(g.Cin / 32 + 1) * g.Cout * 4;
+  return (size_t)(g.Cin / 32 + 1) * g.Cout * sizeof(uint4);
 }
 
 hipError_t launch_wgrad_sq_fused(const Geom& g, const void* x, const void* dz, const void* W, const float* b,
                                  const float* gamma, const float* mean, const float* var, void* dW, float* db,
-                                 float* dgamma, float* dbeta, void* w_folded_out, void* scratch, hipStream_t st) {
+                                 float* dgamma, float* dbeta, void* scratch, hipStream_t st) {
   SqParams p;
   const SqPlan pl = make_plan(g, &p);
   if (!pl.ok || pl.nsplit != 1 || !scratch) return hipErrorInvalidValue;
   p.x = (const bf16_t*)x; p.dz = (const bf16_t*)dz; p.part = nullptr;
   p.r_part = reinterpret_cast<float*>(scratch);   // only its non-NULL-ness matters here: the channel sums are wanted
-  p.wgt = (const bf16_t*)W; p.dW = (bf16_t*)dW; p.w_t = (bf16_t*)w_folded_out; p.gamma = gamma; p.mean = mean; p.var = var; p.b = b;
+  p.wgt = (const bf16_t*)W; p.dW = (bf16_t*)dW; p.gamma = gamma; p.mean = mean; p.var = var; p.b = b;
   p.db = db; p.dgamma = dgamma; p.dbeta = dbeta; p.eps = g.eps;
-  p.counters = reinterpret_cast<unsigned long long*>(scratch);
-  p.dot_part = reinterpret_cast<float*>(reinterpret_cast<char*>(scratch) + align_up((size_t)p.nco * 8, 256));
+  p.slots = reinterpret_cast<uint4*>(scratch);   // workspace pieces are 256-byte aligned
   p.tag = next_tag();
   return dispatch(p, pl, st);
 }
