@@ -1,7 +1,8 @@
 """GPU parity of deep 3x3 layers (many channels, few pixels), whose backward runs the weight gradient and the
-fold-back in one launch (partial dot products exchanged between workgroups, finished by the last one to arrive at a
-tagged counter): whole blocks against the oracle with ragged pixel tails, other paddings, a bias and wide scales, and
-twice in a row on one workspace (the arrival counters of the first call are stale for the second)."""
+fold-back in one launch (partial dot products exchanged between workgroups through slots that carry the launch's
+tag, finished by the workgroup that finds all of them in place): whole blocks against the oracle with ragged pixel
+tails, other paddings, a bias and wide scales, twice in a row on one workspace (the slots of the first call are
+stale for the second), and replayed from a captured graph."""
 import pytest
 import torch
 
@@ -53,3 +54,35 @@ def test_deep_layer_that_keeps_nothing(kw):
     res = run.results()
     assert res["Wf"] is None
     compare(res, ref, "bf16", tag="deep_refold")
+
+
+def test_deep_layer_replayed_from_a_graph():
+    """A captured step replays with the same arguments, the launch tag of the workgroup exchange among them: each
+    replay must find the slots of the previous one cleared.  Three replays over changing inputs, eager work and
+    synchronisations in between, each compared bit for bit with an eager step on the same inputs."""
+    from paper_2305_11624_amd import binding as B
+    from paper_2305_11624_amd.runner import BlockRun
+    shapes = [BlockShape("deep_graph", 33, 512, 7, 7, 512, 3, 1, 1, "bf16", 70 + i) for i in range(2)]
+    inps = [synth.make_inputs(s, bias=True) for s in shapes]
+    assert B.convbn_tune_bwd_is_fused(B.desc_from_shape(shapes[0], eps=inps[0]["eps"]))
+    eager = []
+    for inp in inps:
+        run = BlockRun(inp, mode="tune", keep_folded=False)
+        run.step()
+        eager.append(run.results())
+    sources = [BlockRun(inp, mode="tune", keep_folded=False) for inp in inps]
+    run = BlockRun(inps[0], mode="tune", keep_folded=False, poison=True)
+    fields = ("x", "dz", "W", "b", "gamma", "beta", "mean", "var")
+    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        run.step()
+    for which in (0, 1, 1, 0):
+        for f in fields:
+            getattr(run, f).copy_(getattr(sources[which], f))
+        for t in (run.z, run.dx, run.dW, run.dgamma, run.dbeta, run.db):
+            t.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        got = run.results()
+        for k in ("Z", "dX", "dW", "dgamma", "dbeta", "db"):
+            assert torch.equal(got[k], eager[which][k]), (which, k)
