@@ -57,26 +57,45 @@ __device__ __forceinline__ int fdiv(int n, const FastDiv& f) {
   return (int)((__umulhi((unsigned)n, f.mul) + (unsigned)n * f.add) >> f.shr);
 }
 
-constexpr int TP = 64;                  // output pixels per workgroup
-constexpr int TRC = 128;                // output channels per workgroup
 constexpr int CB = 64;                  // reduced channels per chunk
 constexpr int KK = CB / 16;             // k-steps per step
 constexpr int NWAVES = 8;
 constexpr int HROW = 144;               // window-tile row pitch: 128 bytes of channels + one pad granule
 constexpr int HRPU = 7;                 // whole rows per 1 KB copy (its last lane spills into the next row)
 constexpr int HUNIT = HRPU * HROW;      // 1008
-constexpr int HUW = 3;                  // window-tile copies per wave and chunk
-constexpr int HUNITS = NWAVES * HUW;    // 24 -> at most 168 window pixels per tile
-constexpr int HBUF = HUNITS * HUNIT + 64;
-constexpr int WSLAB = TRC * CB * 2;     // 16384
-constexpr int NBUF = 6;                 // weight ring: a slab is fetched five steps before its step (L2 latency is
-                                        // several steps long)
-constexpr int DIST = NBUF - 1;
-constexpr int OFF_W = 1024;             // bias first
-constexpr int OFF_H = OFF_W + NBUF * WSLAB;
+constexpr int OFF_W = 1024;             // bias and scale first
 constexpr int RED_BYTES = 2 * 4 * 16 * 64 * 16;   // the final reduction: eight waves' accumulators
-constexpr int LDS_BYTES = (OFF_H + 2 * HBUF) > (OFF_W + RED_BYTES) ? (OFF_H + 2 * HBUF) : (OFF_W + RED_BYTES);
 constexpr unsigned OOB = 0x80000000u;
+
+// The two tile shapes.  Both give a wave four accumulator tiles (a pixel group is half the tile's pixels):
+//   64 pixels x 128 channels: 1 pixel x 4 channel subtiles per wave, 16 KB of weights per step, small windows;
+//  128 pixels x  64 channels: 2 x 2 subtiles (4 operand reads per 4 multiplies instead of 5), 8 KB of weights per
+//                             step and a window tile about twice as large -- fewer bytes per step in all.
+template <int TP_, int TRC_>
+struct Shape {
+  static constexpr int TP = TP_;                  // output pixels per workgroup
+  static constexpr int TRC = TRC_;                // output channels per workgroup
+  static constexpr int NPS = TP / 64;             // 32-pixel subtiles per wave
+  static constexpr int NCS = TRC / 32;            // 32-channel subtiles per wave
+  static constexpr int WPW = TRC / 64;            // weight copies (8 rows each) per wave and step
+  static constexpr int HUW = TP == 64 ? 3 : 5;    // window-tile copies per wave and chunk
+  static constexpr int HUNITS = NWAVES * HUW;     // 24 / 40 -> at most 168 / 280 window pixels per tile
+  static constexpr int HBUF = HUNITS * HUNIT + 64;
+  static constexpr int WSLAB = TRC * CB * 2;      // 16384 / 8192
+  // Steps between workgroup barriers, depth of the weight ring, and how many steps before its own a slab is
+  // fetched (L2 latency is several steps long).  A barrier costs about as much as the four multiplies of a step,
+  // so the 128 x 64 shape, whose slabs are half as large, spends the LDS it saves on a ring deep enough for one
+  // barrier per kernel row: G = 3.  What the schedule needs: at the barrier that opens a group the slabs of its G
+  // steps and of the step after are resident (a step reads the operands of the next one), i.e. at most the copies
+  // of the DIST - G - 1 latest steps are in flight; a slab's slot was last read in an earlier group:
+  // DIST <= NBUF - G + 1; the next chunk's window tile is fetched in the first TAPS + 1 - DIST taps of a chunk.
+  static constexpr int G = TP == 64 ? 1 : 3;
+  static constexpr int NBUF = TP == 64 ? 6 : 9;
+  static constexpr int DIST = NBUF - G + 1;
+  static constexpr int OFF_H = OFF_W + NBUF * WSLAB;
+  static constexpr int LDS_BYTES = (OFF_H + 2 * HBUF) > (OFF_W + RED_BYTES) ? (OFF_H + 2 * HBUF) : (OFF_W + RED_BYTES);
+  static_assert(NPS * NCS == 4 && TRC <= 128, "four accumulator tiles per wave");
+};
 
 struct StParams {
   const bf16_t* act;
@@ -93,6 +112,7 @@ struct StParams {
   int wt0, wt_row, wt_col;        // window position (ti, tj) reads weight tap wt0 + ti wt_row + tj wt_col
   int ntr;                        // channel tiles
   int nchunks;
+  int wide;                       // tile shape: 0 = 64 pixels x 128 channels, 1 = 128 x 64
   FastDiv dHoWo, dWo, dHv, dWv;
 };
 
@@ -115,19 +135,44 @@ __device__ __forceinline__ void block_barrier() {
 template <int N> __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
+// n is a constant once the taps are unrolled: one wait survives
+__device__ __forceinline__ void wait_vm_upto(int n) {
+  switch (n) {
+    case 0: wait_vm<0>(); break; case 1: wait_vm<1>(); break; case 2: wait_vm<2>(); break; case 3: wait_vm<3>(); break;
+    case 4: wait_vm<4>(); break; case 5: wait_vm<5>(); break; case 6: wait_vm<6>(); break; case 7: wait_vm<7>(); break;
+    case 8: wait_vm<8>(); break; case 9: wait_vm<9>(); break; case 10: wait_vm<10>(); break; case 11: wait_vm<11>(); break;
+    case 12: wait_vm<12>(); break; case 13: wait_vm<13>(); break; case 14: wait_vm<14>(); break;
+    default: wait_vm<0>(); break;
+  }
+}
 
-template <int KH, int KW>
+#ifdef ST_TRACE
+__device__ unsigned long long st_trace[1024 * 128];
+#ifndef ST_TRACE_WAVE
+#define ST_TRACE_WAVE 0
+#endif
+#define STAMP(i) do { if (tid == 64 * ST_TRACE_WAVE && (i) < 128) st_trace[blockIdx.x * 128 + (i)] = clock64(); } while (0)
+#else
+#define STAMP(i) do {} while (0)
+#endif
+
+template <int KH, int KW, class S>
 __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
   constexpr int TAPS = KH * KW;
-  static_assert(TAPS >= HUW + DIST - 1 && DIST == 5, "the copy schedule assumes a window of at least seven taps and a ring of six slabs");
+  constexpr int TP = S::TP, TRC = S::TRC, NPS = S::NPS, NCS = S::NCS, WPW = S::WPW, HUW = S::HUW, HBUF = S::HBUF,
+                WSLAB = S::WSLAB, OFF_H = S::OFF_H, G = S::G, NBUF = S::NBUF, DIST = S::DIST;
+  constexpr int HTAPS = TAPS + 1 - DIST;           // taps of a chunk in which the next window tile is fetched
+  constexpr int HPT = (HUW + HTAPS - 1) / HTAPS;   // window units per such tap (the last may get fewer)
+  static_assert(TAPS % G == 0 && HTAPS >= 1 && DIST - G - 1 >= 1, "copy schedule");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   float* biasl = reinterpret_cast<float*>(smem);
   unsigned char* wbuf = smem + OFF_W;
   unsigned char* halo = smem + OFF_H;
 
   const int tid = threadIdx.x, lane = tid & 63;
+  STAMP(0);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wpx = wave & 1, kq = wave >> 1;   // pixel group, and which k-step of every step this wave multiplies
+  const int wpx = wave & 1, kq = wave >> 1;   // pixel group (half the tile), and which k-step of every step this wave multiplies
   const int ctile = blockIdx.x % p.ntr, ptile = blockIdx.x / p.ntr;
   const int r0 = ctile * TRC;
   const int HoWo = p.Ho * p.Wo;
@@ -167,11 +212,11 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
       hv[t] = ok ? (unsigned)((n * p.act_n_stride + h * p.act_h_stride + w * p.act_w_stride + lgran * 8) * 2) : OOB;
     }
   }
-  // weight copies of this wave: units 2 wave and 2 wave + 1 of the slab (8 rows each), granules permuted by (row / 2) % 8
-  unsigned voff_w[2];
+  // weight copies of this wave: units WPW wave .. of the slab (8 rows each), granules permuted by (row / 2) % 8
+  unsigned voff_w[WPW];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int row = (2 * wave + j) * 8 + (lane >> 3);
+  for (int j = 0; j < WPW; ++j) {
+    const int row = (WPW * wave + j) * 8 + (lane >> 3);
     const int g = (lane & 7) ^ ((row >> 1) & 7);
     voff_w[j] = (unsigned)(((r0 + row) * p.wrow + g * 8) * 2);
   }
@@ -186,9 +231,10 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
 
   // LDS byte offsets of this lane's operands
   const int kb = lane >> 5;
-  unsigned boff;
-  {
-    const int pi = wpx * 32 + (lane & 31);
+  unsigned boff[NPS];
+#pragma unroll
+  for (int ps = 0; ps < NPS; ++ps) {
+    const int pi = wpx * (TP / 2) + ps * 32 + (lane & 31);
     int pixidx = 0;
     if (pi < len) {
       const int m = m0 + pi;
@@ -197,10 +243,10 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
       const int ho = fdiv(rem, p.dWo);
       pixidx = (n * p.Hv + ho - v_first) * p.Wv + (rem - ho * p.Wo);
     }
-    boff = (unsigned)(pixidx * HROW + kb * 16);
+    boff[ps] = (unsigned)(pixidx * HROW + kb * 16);
   }
-  // weight rows of this lane (row l % 32 of each of the four 32-channel subtiles): granule 2 kq + kb sits at
-  // position (2 kq + kb) ^ key, key = (row / 2) % 8 -- the same for the four rows, which are 32 apart
+  // weight rows of this lane (row l % 32 of each 32-channel subtile): granule 2 kq + kb sits at
+  // position (2 kq + kb) ^ key, key = (row / 2) % 8 -- the same for all its rows, which are 32 apart
   unsigned aoff;
   {
     const int row = lane & 31;
@@ -208,7 +254,7 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
     aoff = (unsigned)(row * 128 + ((((2 * kq + kb) ^ key) & 7) << 4));
   }
 
-  f32x16 acc[4];
+  f32x16 acc[4];   // subtile (channel i, pixel ps) at i * NPS + ps
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -217,11 +263,14 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
   auto issue_weights = [&](int chunk, int t, int slot) {
     const unsigned soff = (unsigned)(wsoff[t] + chunk * (CB * 2));
 #pragma unroll
-    for (int j = 0; j < 2; ++j) dma16(wgt_rsrc, voff_w[j], soff, wbuf + slot * WSLAB + (2 * wave + j) * 1024);
+    for (int j = 0; j < WPW; ++j) dma16(wgt_rsrc, voff_w[j], soff, wbuf + slot * WSLAB + (WPW * wave + j) * 1024);
   };
   auto issue_halo = [&](int chunk, int t, int hb) {
     dma16(act_rsrc, hv[t], (unsigned)(chunk * (CB * 2)), halo + hb * HBUF + (wave + NWAVES * t) * HUNIT);
   };
+
+  // window units fetched in tap t of a chunk
+  auto halo_units = [&](int t) { return t < HTAPS ? (HUW - t * HPT < HPT ? (HUW - t * HPT > 0 ? HUW - t * HPT : 0) : HPT) : 0; };
 
   // ---- prologue: the first chunk's window tile and the slabs of steps 0 .. DIST-1 ---------------------
 #pragma unroll
@@ -229,17 +278,21 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
 #pragma unroll
   for (int s = 0; s < DIST; ++s) issue_weights(0, s, s);
 
-  bf16x8 fa[2][4], fb[2];
+  bf16x8 fa[2][NCS], fb[2][NPS];
   // operands of this wave's k-step of a step: weights from ring slot `slot`, pixels from window tile `hb` at tap offset `to`
   auto load_frags = [&](int buf, int slot, int hb, int to) {
-    fb[buf] = *reinterpret_cast<const bf16x8*>(halo + hb * HBUF + to + kq * 32 + boff);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(wbuf + slot * WSLAB + aoff + i * 4096);
+    for (int ps = 0; ps < NPS; ++ps)
+      fb[buf][ps] = *reinterpret_cast<const bf16x8*>(halo + hb * HBUF + to + kq * 32 + boff[ps]);
+#pragma unroll
+    for (int i = 0; i < NCS; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(wbuf + slot * WSLAB + aoff + i * 4096);
   };
 
   if (p.bn.gamma && p.bn.w_folded_out) emit_folded_slice(p.bn, p.wgt, blockIdx.x, gridDim.x);   // while the first copies are in flight
-  wait_vm<0>();
+  STAMP(1);
+  wait_vm_upto((DIST - G - 1) * WPW);   // as at every later group: the latest DIST - G - 1 slabs may still be on their way
   block_barrier();
+  STAMP(2);
   load_frags(0, 0, 0, toff[0]);
 
   int slot = 0;   // ring slot of the current step
@@ -248,16 +301,18 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
     const int cnext = min(c + 1, nchunks - 1);   // past the end: the last chunk again (nobody reads it)
 #pragma unroll
     for (int t = 0; t < TAPS; ++t) {
-      // copies that may still be in flight: those of the DIST - 2 previous steps (2 weight units each, + 1 window
-      // unit in the first HUW taps of a chunk) -- the slab of step s + 1 was issued DIST - 1 steps ago
-      {
+      // a group opens: the copies that may still be in flight are those of the DIST - G - 1 previous steps (WPW
+      // weight units each, + the window units of those taps)
+      if (t % G == 0) {
         int inflight = 0;
 #pragma unroll
-        for (int d = 1; d <= DIST - 2; ++d) inflight += 2 + (((t - d + TAPS) % TAPS) < HUW ? 1 : 0);
-        if (inflight == 6) wait_vm<6>(); else if (inflight == 7) wait_vm<7>(); else if (inflight == 8) wait_vm<8>();
-        else wait_vm<9>();
+        for (int d = 1; d <= DIST - G - 1; ++d) inflight += WPW + halo_units((t - d + TAPS) % TAPS);
+        STAMP(4 + 3 * (c * TAPS + t));
+        wait_vm_upto(inflight);
+        STAMP(5 + 3 * (c * TAPS + t));
+        block_barrier();
+        STAMP(6 + 3 * (c * TAPS + t));
       }
-      block_barrier();
       const int t3 = (t + DIST) % TAPS;
       const int c3 = (t + DIST) >= TAPS ? cnext : c;
       const int slot_n = slot + 1 == NBUF ? 0 : slot + 1;
@@ -267,32 +322,39 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
       if (t + 1 < TAPS) load_frags(cur ^ 1, slot_n, hb, toff[t + 1]);
       else load_frags(cur ^ 1, slot_n, hb ^ 1, toff[0]);
       __builtin_amdgcn_sched_barrier(0);
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][0], fb[cur], acc[0], 0, 0, 0);
+#define ST_MMA(j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][(j) / NPS], fb[cur][(j) % NPS], acc[j], 0, 0, 0)
+      ST_MMA(0);
       __builtin_amdgcn_sched_barrier(0);
       issue_weights(c3, t3, slot_f);
       __builtin_amdgcn_sched_barrier(0);
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][1], fb[cur], acc[1], 0, 0, 0);
+      ST_MMA(1);
       __builtin_amdgcn_sched_barrier(0);
-      if (t < HUW) issue_halo(cnext, t, hb ^ 1);
+#pragma unroll
+      for (int u = 0; u < HPT; ++u)
+        if (u < halo_units(t)) issue_halo(cnext, t * HPT + u, hb ^ 1);
       __builtin_amdgcn_sched_barrier(0);
-      acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][2], fb[cur], acc[2], 0, 0, 0);
-      acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][3], fb[cur], acc[3], 0, 0, 0);
+      ST_MMA(2);
+      ST_MMA(3);
+#undef ST_MMA
       __builtin_amdgcn_sched_barrier(0);
       slot = slot_n;
     }
     if (TAPS & 1) {   // an odd number of steps per chunk: the operands fetched last sit in buffer 1, the next chunk starts from 0
-      fb[0] = fb[1];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) fa[0][i] = fa[1][i];
+      for (int ps = 0; ps < NPS; ++ps) fb[0][ps] = fb[1][ps];
+#pragma unroll
+      for (int i = 0; i < NCS; ++i) fa[0][i] = fa[1][i];
     }
   }
   wait_vm<0>();   // trailing copies must not outlive the workgroup's LDS
+  STAMP(125);
 
   // ---- epilogue: the four waves of a pixel group add their sums, then bias, one rounding to bf16, 16-byte stores ----
-  // Accumulator element e of lane l in subtile i: channel 32 i + 8 (e / 4) + 4 (l / 32) + e % 4, pixel l % 32.
-  // Every wave leaves its four subtiles in LDS as [pixel group][wave kq][subtile][q][lane] float4; wave kq then sums
-  // the four copies of subtile kq, rounds its 32 x 32 block into its own 2 KB of LDS ([pixel][32 ch], granules
-  // swizzled by pixel) and reads it back row-wise: four lanes cover one pixel's 64 contiguous bytes.
+  // Accumulator element e of lane l in subtile (i, ps): channel 32 i + 8 (e / 4) + 4 (l / 32) + e % 4, pixel
+  // 32 ps + l % 32 of the pixel group.  Every wave leaves its four subtiles in LDS as
+  // [pixel group][wave kq][subtile][q][lane] float4; wave kq then sums the four copies of subtile kq, rounds its
+  // 32 x 32 block into its own 2 KB of LDS ([pixel][32 ch], granules swizzled by pixel) and reads it back row-wise:
+  // four lanes cover one pixel's 64 contiguous bytes.
   if (tid < TRC) { biasl[tid] = bias_v; biasl[TRC + tid] = scale_v; }
   __syncthreads();   // every wave is done with the ring and the window tiles
   {
@@ -316,11 +378,12 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
     unsigned char* stage = smem + OFF_W + wave * 2048;
     const int px = lane & 31;
     const int psw = (px >> 1) & 3;
+    const int ci = kq / NPS, pss = kq % NPS;   // the subtile this wave finishes
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int ch = q * 8 + kb * 4;
-      const float4 bb = *reinterpret_cast<const float4*>(biasl + kq * 32 + ch);
-      const float4 sc = *reinterpret_cast<const float4*>(biasl + TRC + kq * 32 + ch);
+      const float4 bb = *reinterpret_cast<const float4*>(biasl + ci * 32 + ch);
+      const float4 sc = *reinterpret_cast<const float4*>(biasl + TRC + ci * 32 + ch);
       const uint2 v = make_uint2(pack_bf16x2(fmaf(sum[q].x, sc.x, bb.x), fmaf(sum[q].y, sc.y, bb.y)),
                                  pack_bf16x2(fmaf(sum[q].z, sc.z, bb.z), fmaf(sum[q].w, sc.w, bb.w)));
       *reinterpret_cast<uint2*>(stage + px * 64 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
@@ -330,14 +393,15 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
       const int row = it * 16 + (lane >> 2);
       const int g = (lane & 3) ^ ((row >> 1) & 3);
       const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 64 + ((lane & 3) << 4));
-      const int pi = wpx * 32 + row;
-      if (pi < len) *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + pi) * p.R + r0 + kq * 32 + g * 8) = v;
+      const int pi = wpx * (TP / 2) + pss * 32 + row;
+      if (pi < len) *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + pi) * p.R + r0 + ci * 32 + g * 8) = v;
     }
   }
+  STAMP(126);
 }
 
 // Largest number of window-tile pixels any TP-pixel tile needs.
-int max_window_pixels(const StParams& p, int kH) {
+int max_window_pixels(const StParams& p, int kH, int TP) {
   const int HoWo = p.Ho * p.Wo;
   int a = HoWo, b = TP;
   while (b) { const int t = a % b; a = b; b = t; }
@@ -354,22 +418,39 @@ int max_window_pixels(const StParams& p, int kH) {
 }
 
 // Completes the plan of a problem whose tensors are described in p; false = this kernel does not take it.
+using Narrow = Shape<64, 128>;
+using Wide = Shape<128, 64>;
+
+template <class S>
+bool shape_fits(const StParams& p, int kH) {
+  if (p.R % S::TRC) return false;
+  if (max_window_pixels(p, kH, S::TP) > S::HUNITS * HRPU) return false;
+  // small tiles are for problems that would not fill the chip with larger ones
+  const long long tiles = (long long)ceil_div(p.M, S::TP) * (p.R / S::TRC);
+  return tiles >= 96 && tiles <= 640;
+}
+
 bool finish_plan(StParams& p, int kH, int kW) {
   if (kH != 3 || kW != 3) return false;
-  if (p.C % CB || p.R % TRC) return false;
+  if (p.C % CB) return false;
   if (p.act_bytes >= OOB || p.wgt_bytes >= OOB) return false;
   p.Hv = p.Ho - 1 + kH;
   p.Wv = p.Wo - 1 + kW;
-  if (max_window_pixels(p, kH) > HUNITS * HRPU) return false;
+  const bool wide_ok = shape_fits<Wide>(p, kH), narrow_ok = shape_fits<Narrow>(p, kH);
+#if defined(ST_FORCE_NARROW)
+  p.wide = 0;
+  if (!narrow_ok) return false;
+#else
+  if (!wide_ok && !narrow_ok) return false;
+  p.wide = wide_ok;
+#endif
   p.dHoWo = make_fastdiv(p.Ho * p.Wo);
   p.dWo = make_fastdiv(p.Wo);
   p.dHv = make_fastdiv(p.Hv);
   p.dWv = make_fastdiv(p.Wv);
-  p.ntr = p.R / TRC;
+  p.ntr = p.R / (p.wide ? Wide::TRC : Narrow::TRC);
   p.nchunks = p.C / CB;
-  // small tiles are for problems that would not fill the chip with larger ones
-  const long long tiles = (long long)ceil_div(p.M, TP) * p.ntr;
-  return tiles >= 96 && tiles <= 640;
+  return true;
 }
 
 bool fprop_params(const Geom& g, StParams* p) {
@@ -403,17 +484,22 @@ bool dgrad_params(const Geom& g, StParams* p) {
   return finish_plan(q, g.kH, g.kW);
 }
 
-hipError_t launch(const StParams& p, hipStream_t st) {
+template <class S>
+hipError_t launch_shape(const StParams& p, hipStream_t st) {
   static std::once_flag once;
   static hipError_t attr_err = hipSuccess;
   std::call_once(once, [] {
-    attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_st_kernel<3, 3>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_st_kernel<3, 3, S>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS_BYTES);
   });
   if (attr_err != hipSuccess) return attr_err;
-  const int tiles = ceil_div(p.M, TP) * p.ntr;
-  hipLaunchKernelGGL((conv_st_kernel<3, 3>), dim3(tiles), dim3(64 * NWAVES), LDS_BYTES, st, p);
+  const int tiles = ceil_div(p.M, S::TP) * p.ntr;
+  hipLaunchKernelGGL((conv_st_kernel<3, 3, S>), dim3(tiles), dim3(64 * NWAVES), S::LDS_BYTES, st, p);
   return hipGetLastError();
+}
+
+hipError_t launch(const StParams& p, hipStream_t st) {
+  return p.wide ? launch_shape<Wide>(p, st) : launch_shape<Narrow>(p, st);
 }
 
 }  // namespace
@@ -443,3 +529,9 @@ hipError_t launch_dgrad_st(const Geom& g, const void* dz, const void* w_crsk, co
 }
 
 }  // namespace convbn
+
+#ifdef ST_TRACE
+extern "C" int convbn_debug_read_st_trace(unsigned long long* host, size_t n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(convbn::st_trace), n * sizeof(unsigned long long));
+}
+#endif
