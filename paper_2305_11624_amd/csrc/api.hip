@@ -192,12 +192,12 @@ convbn_status check_ws(size_t need, void* ws, size_t ws_bytes) {
 // Scratch the three convolutions of a problem need (0 for most): fp32 partial outputs when the
 // reduced channels are split over workgroups, and the zero-padded copies of needs_cin_pad().
 size_t inner_fprop_scratch(const Geom& g, int dtype) {
-  if (pw_fprop_supported(g, dtype) || st_fprop_supported(g, dtype)) return 0;
+  if (pw_fprop_supported(g, dtype) || rw_fprop_supported(g, dtype) || st_fprop_supported(g, dtype)) return 0;
   if (mt_fprop_supported(g, dtype)) return align_up(mt_fprop_scratch_bytes(g), 256);
   return tile_fprop_supported(g, dtype) ? align_up(tile_fprop_partial_bytes(g), 256) : 0;
 }
 size_t inner_dgrad_scratch(const Geom& g, int dtype) {
-  if (pw_dgrad_supported(g, dtype) || st_dgrad_supported(g, dtype)) return 0;
+  if (pw_dgrad_supported(g, dtype) || rw_dgrad_supported(g, dtype) || st_dgrad_supported(g, dtype)) return 0;
   if (mt_dgrad_supported(g, dtype)) return align_up(mt_dgrad_scratch_bytes(g), 256);
   return tile_dgrad_supported(g, dtype) ? align_up(tile_dgrad_partial_bytes(g), 256) : 0;
 }
@@ -227,6 +227,7 @@ size_t wgrad_scratch_bytes(const Geom& g, int dtype) {
 hipError_t fprop_any(const Geom& g, int dtype, const void* x, const void* w_krsc, const float* bias,
                      void* z, float* scratch, hipStream_t st) {
   if (pw_fprop_supported(g, dtype)) return launch_fprop_pw(g, x, w_krsc, bias, z, st);
+  if (rw_fprop_supported(g, dtype)) return launch_fprop_rw(g, x, w_krsc, bias, z, st);
   if (st_fprop_supported(g, dtype)) return launch_fprop_st(g, x, w_krsc, bias, z, st);
   if (mt_fprop_supported(g, dtype)) return launch_fprop_mt(g, x, w_krsc, bias, z, scratch, st);
   if (tile_fprop_supported(g, dtype)) return launch_fprop_tile(g, x, w_krsc, bias, z, scratch, st);
@@ -236,6 +237,7 @@ hipError_t fprop_any(const Geom& g, int dtype, const void* x, const void* w_krsc
 hipError_t dgrad_any(const Geom& g, int dtype, const void* dz, const void* w_crsk, const float* bias, void* dx,
                      float* scratch, hipStream_t st) {
   if (pw_dgrad_supported(g, dtype)) return launch_dgrad_pw(g, dz, w_crsk, bias, dx, st);
+  if (rw_dgrad_supported(g, dtype)) return launch_dgrad_rw(g, dz, w_crsk, bias, dx, st);
   if (st_dgrad_supported(g, dtype)) return launch_dgrad_st(g, dz, w_crsk, bias, dx, st);
   if (mt_dgrad_supported(g, dtype)) return launch_dgrad_mt(g, dz, w_crsk, bias, dx, scratch, st);
   if (tile_dgrad_supported(g, dtype)) return launch_dgrad_tile(g, dz, w_crsk, bias, dx, scratch, st);
@@ -575,6 +577,7 @@ convbn_status convbn_tune_fwd(const convbn_desc* desc, const void* x, const void
     // weight and applies s and b' in its epilogue, and -- where w' is kept for backward -- its workgroups each
     // write a slice of w' on the side.  The forward pass is one launch; no w' is materialised for it.
     const BnEpilogue bn{gamma, beta, mean, var, b, g.eps, w_folded, g.kH * g.kW, g.Cin, g.Cout};
+    if (rw_fprop_supported(g, dt)) { LAUNCH(launch_fprop_rw(g, x, W, nullptr, z, st, &bn)); return CONVBN_OK; }
     if (st_fprop_supported(g, dt)) { LAUNCH(launch_fprop_st(g, x, W, nullptr, z, st, &bn)); return CONVBN_OK; }
     if (tile_fprop_scaled_supported(g, dt)) { LAUNCH(launch_fprop_tile(g, x, W, nullptr, z, nullptr, st, &bn)); return CONVBN_OK; }
   }
@@ -1123,6 +1126,10 @@ convbn_status convbn_tune_fwd_scale_epilogue(const convbn_desc* desc, const void
   const BnEpilogue bn{gamma, beta, mean, var, b, g.eps, nullptr, g.kH * g.kW, g.Cin, g.Cout};
   hipStream_t st = static_cast<hipStream_t>(stream);
   // Z = s (w (*) X) + b': the unfolded weight goes straight into the convolution, one launch in all
+  if (!needs_cin_pad(g, dt) && !pw_fprop_supported(g, dt) && rw_fprop_supported(g, dt)) {
+    LAUNCH(launch_fprop_rw(g, x, W, nullptr, z, st, &bn));
+    return CONVBN_OK;
+  }
   if (!needs_cin_pad(g, dt) && !pw_fprop_supported(g, dt) && st_fprop_supported(g, dt)) {
     LAUNCH(launch_fprop_st(g, x, W, nullptr, z, st, &bn));
     return CONVBN_OK;

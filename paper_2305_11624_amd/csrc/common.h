@@ -249,6 +249,15 @@ hipError_t launch_fprop_st(const Geom& g, const void* x, const void* w_krsc, con
                            const BnEpilogue* bn = nullptr);
 hipError_t launch_dgrad_st(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx, hipStream_t st);
 
+// conv_rw.hip : 3x3 / stride-1 convolutions of shallow layers (64 -> 64 channels, long pixel streams): weight and
+// window resident in LDS, one barrier per workgroup (no scratch).
+bool rw_fprop_supported(const Geom& g, int dtype);
+bool rw_dgrad_supported(const Geom& g, int dtype);
+// bn != nullptr: w_krsc is the UNFOLDED weight and the epilogue applies the BatchNorm scale and folded bias itself
+hipError_t launch_fprop_rw(const Geom& g, const void* x, const void* w_krsc, const float* bias, void* z, hipStream_t st,
+                           const BnEpilogue* bn = nullptr);
+hipError_t launch_dgrad_rw(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx, hipStream_t st);
+
 bool tile_fprop_supported(const Geom& g, int dtype);
 bool tile_fprop_scaled_supported(const Geom& g, int dtype);   // ... with a BnEpilogue
 bool tile_dgrad_supported(const Geom& g, int dtype);

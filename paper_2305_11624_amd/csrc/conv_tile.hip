@@ -152,8 +152,19 @@ template <int NCH, int CB> struct TileCfg {
 // workgroup (row k of wave w = copy unit w + NW k; rows past the tile hold the zero-fill offset).
 // SC: the weight is unfolded and the epilogue applies the BatchNorm scale and folded bias it works out itself (an
 // instantiation of its own, so the default kernels carry none of it).
+#ifdef TILE_TRACE
+__device__ unsigned long long tile_trace[1024 * 32];
+#ifndef TILE_TRACE_WAVE
+#define TILE_TRACE_WAVE 0
+#endif
+#define STAMP(i) do { if (threadIdx.x == 64 * TILE_TRACE_WAVE) { tile_trace[blockIdx.x * 32 + (i)] = clock64(); tile_trace[blockIdx.x * 32 + 16 + (i)] = wall_clock64(); } } while (0)
+#else
+#define STAMP(i) do {} while (0)
+#endif
+
 template <int NW, int NWC, int NCH, int CB, int HPS, bool SC = false>
 __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
+  STAMP(0);
   using Cfg = TileCfg<NCH, CB>;
   constexpr int NWP = NW / NWC;            // waves along the pixels
   constexpr int NCW = NCH / NWC;           // 32-channel subtiles per wave
@@ -367,8 +378,10 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   };
 
   if (SC && p.bn.w_folded_out) emit_folded_slice(p.bn, p.wgt, blockIdx.x, gridDim.x);   // while the first copies are in flight
+  STAMP(1);
   wait_vm<(DIST - 1) * (WPW + HPS)>();   // the activation tile of the first chunk and the slab of step 0 have landed
   block_barrier();
+  STAMP(2);
   load_frags(0, wlane, bstep, 0);
 
   auto step = [&](auto slot) {
@@ -426,6 +439,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     if constexpr (NBUF == 5) { step(std::integral_constant<int, 4>{}); if (--left == 0) break; }
   }
   wait_vm<0>();   // trailing copies must not outlive the workgroup's LDS
+  STAMP(3);
 
   // ---- epilogue -------------------------------------------------------------------------------
   // Accumulator element e of lane l: channel 8*(e/4) + 4*(l/32) + e%4, pixel l%32.  Each wave
@@ -492,10 +506,25 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
           const int ho = fdiv(rem, p.dWo);
           o = (size_t)p.out_base + (size_t)n * p.out_n + (size_t)ho * p.out_h + (size_t)(rem - ho * p.Wo) * p.out_w;
         }
+#if defined(TILE_NT_STORE)
+        if (pi < len && ch < p.R) {
+          typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+          const u32x4_t vv = {v.x, v.y, v.z, v.w};
+          __builtin_nontemporal_store(vv, reinterpret_cast<u32x4_t*>(p.out + o + ch));
+        }
+#elif defined(TILE_SC1_STORE)
+        if (pi < len && ch < p.R) {
+          typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+          const u32x4_t vv = {v.x, v.y, v.z, v.w};
+          asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p.out + o + ch), "v"(vv) : "memory");
+        }
+#else
         if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + o + ch) = v;
+#endif
       }
     }
   }
+  STAMP(4);
 }
 
 // out[m][r] = bf16( sum_s part[s][m][r] + bias[r] ), eight channels per thread (R % 8 == 0).
@@ -950,3 +979,9 @@ hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, 
 }
 
 }  // namespace convbn
+
+#ifdef TILE_TRACE
+extern "C" int convbn_debug_read_tile_trace(unsigned long long* host, size_t n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(convbn::tile_trace), n * sizeof(unsigned long long));
+}
+#endif
