@@ -308,8 +308,12 @@ def run_backbone(mode, N, image, steps, warmup, group_fold=False, group_units=Fa
         net.backward(dout)
     torch.cuda.synchronize()
     peak = torch.cuda.max_memory_allocated() - base
+    # Workspace (the library's scratch and, with per-unit grouping, the arena of a unit's w' and partial sums) is
+    # allocated once before `base` and reported on its own; the w' that per-unit grouping keeps between the passes is
+    # preallocated too and belongs to the activation figure, as the w' a single block allocates in forward does.
+    workspace = net.ws.numel() + net.arena_bytes
     if group_units:
-        peak += net.group_bytes   # arenas and kept w' of the per-unit grouping are allocated once, before `base`
+        peak += net.kept_bytes
     t0 = time.perf_counter()
     for _ in range(steps):
         net.forward(x)
@@ -320,7 +324,8 @@ def run_backbone(mode, N, image, steps, warmup, group_fold=False, group_units=Fa
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
     ev[0].record(); net.forward(x); ev[1].record(); net.backward(dout); ev[2].record()
     torch.cuda.synchronize()
-    out = dict(ms=ms, peak_activation_mb=peak / 1e6, saved_model_mb=net.saved_bytes_model() / 1e6,
+    out = dict(ms=ms, peak_activation_mb=peak / 1e6, workspace_mb=workspace / 1e6,
+               saved_model_mb=net.saved_bytes_model() / 1e6,
                fwd_ms=ev[0].elapsed_time(ev[1]), bwd_ms=ev[1].elapsed_time(ev[2]),
                refold_blocks=sum(1 for b in net.blocks.values() if mode == "tune" and not b.keep_folded))
     if group_fold:
@@ -403,6 +408,8 @@ def main_backbone(a):
         "eval_ms_per_step": ev["ms"] if ev else None,
         "tune_speedup_vs_eval": ev["ms"] / tune["ms"] if ev else None,
         "peak_activation_mb": {"tune": tune["peak_activation_mb"], "eval": ev["peak_activation_mb"] if ev else None},
+        "peak_with_workspace_mb": {"tune": tune["peak_activation_mb"] + tune["workspace_mb"],
+                                   "eval": ev["peak_activation_mb"] + ev["workspace_mb"] if ev else None},
         "roofline": {"bound": "mfma", "kernel": "whole backbone step (all kernels)", "achieved": tf,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tf / PEAK_BF16_TFLOPS, "traffic": None},
     }

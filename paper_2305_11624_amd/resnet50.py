@@ -91,6 +91,7 @@ class ResNet50:
         self.group_units = group_units and mode == "tune" and not self.group_fold
         self._group = None
         self.group_bytes = 0
+        self.arena_bytes = self.kept_bytes = 0   # per-unit grouping: the shared arena (workspace) and the kept w'
         shapes = synth.resnet50_blocks(N, image, dtype)
         self.blocks: Dict[str, _Block] = {s.name: _Block(s, device, mode) for s in shapes}
         self.order: List[str] = [s.name for s in shapes]
@@ -183,6 +184,7 @@ class ResNet50:
         self._unit_keep = (arena, plans)
         # what the grouping adds to the memory a step holds: the arenas (the kept w' is counted as before)
         self.group_bytes = one.numel() + kept_bytes
+        self.arena_bytes, self.kept_bytes = one.numel(), kept_bytes
 
     def fold_group_table(self, alloc=True):
         """(n, table, grid, bytes moved) of the grouped fold over every block the group takes (all but
