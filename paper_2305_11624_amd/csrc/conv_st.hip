@@ -1,34 +1,35 @@
 // bf16 MFMA convolution for deep 3x3 / stride-1 layers (many channels, few pixels) without split sums:
-// 64-pixel x 128-channel workgroup tiles shared by EIGHT waves.
+// workgroup tiles of 128 pixels x 64 channels (or 64 x 128) shared by EIGHT waves.
 //
 //   forward conv   Z  = w' (*) X + b'     (Sec. 3.1 / 3.3)   act = x,  weights [Cout][taps][Cin]
 //   input gradient dX = w'_rot (*) dZ     (Sec. 3.2.1)       act = dz, weights [Cin][taps][Cout], taps reversed
 //
-// Why this shape.  With a few thousand pixels and 512 channels the output has only about as many 64 x 128 tiles
-// as the chip has compute units, so a tile cannot be larger without splitting the reduction over workgroups --
-// and the fp32 partial sums of such a split were measured to cost more than the larger tile saves.  At 64 x 128
-// the kernel is bound by how fast a compute unit can pull the folded weight out of the L2 (16 KB per
-// 64-channel step for 256 cycles of matrix work).  That rate depends on how many waves issue the copies: four
-// waves sustain about 30 bytes per clock, eight about 50.  So the tile is shared by eight waves instead of four:
-// every wave issues half the copies, and the matrix pipe of a SIMD is fed by two waves.  The eight waves are
-// 2 pixel groups (32 pixels) x 4 quarters of the reduction: a wave multiplies one of the four 16-channel k-steps
-// of every step for all 128 output channels (4 accumulator tiles, 5 operand reads for 4 multiplies -- with one
-// 32 x 32 tile per wave it would be 2 reads per multiply, and the LDS, which serves about one wave-wide read
-// per 5 clocks whatever its width, would be the bound), and the four waves of a pixel group add their sums
-// through LDS at the end.
+// Why these shapes.  With a few thousand pixels and 512 channels the output has only about as many 8192-element
+// tiles as the chip has compute units, so a tile cannot be larger without splitting the reduction over workgroups
+// -- and the fp32 partial sums of such a split were measured to cost more than the larger tile saves.  At this
+// size the kernel is bound by how fast a compute unit can pull the folded weight out of the L2 (a 64-channel step
+// is 256 cycles of matrix work).  That rate depends on how many waves issue the copies: four waves sustain about
+// 30 bytes per clock, eight about 50.  So the tile is shared by eight waves instead of four: every wave issues a
+// share of the copies, and the matrix pipe of a SIMD is fed by two waves.  The eight waves are 2 pixel groups
+// (half the tile's pixels) x 4 quarters of the reduction: a wave multiplies one of the four 16-channel k-steps of
+// every step for all the tile's channels (4 accumulator tiles; 128 x 64: 2 pixel x 2 channel subtiles, 4 operand
+// reads for 4 multiplies; 64 x 128: 1 x 4, 5 reads -- with one 32 x 32 tile per wave it would be 2 reads per
+// multiply, and the LDS, which serves about one wave-wide read per 5 clocks whatever its width, would be the
+// bound), and the four waves of a pixel group add their sums through LDS at the end.  128 x 64 is preferred where
+// its window fits: half the weight bytes per step, and a ring deep enough for one barrier per kernel row.
 //
 // Layout in LDS.  Activations: the window rows the tile's pixels touch, [slot][column][64 channels] with zero
 // rows / columns for the padding (out-of-image pixels are copies with an out-of-range buffer offset: zeros),
 // rows 144 bytes apart (128 + one pad granule: 16 consecutive rows of a 128-bit operand read fall on distinct
 // banks, and a tap is a wave-uniform offset on a per-lane base).  All nine taps of a chunk read the same tile.
-// Weights: one [128 rows][64 channels] slab per (chunk, tap) step in a ring of four, rows 128 bytes apart with
-// the eight granules of a row permuted by (row / 2) % 8 -- chosen by the copy, which picks the granule each
-// lane fetches -- so that a slab is exactly sixteen 1 KB copies, two per wave and step.
+// Weights: one [rows][64 channels] slab per (chunk, tap) step in a ring, rows 128 bytes apart with the eight
+// granules of a row permuted by (row / 2) % 8 -- chosen by the copy, which picks the granule each lane fetches
+// -- so that a slab is exactly eight or sixteen 1 KB copies, one or two per wave and step.
 //
-// Pipeline: as in the large-tile kernel.  A step = one tap of one 64-channel chunk = 4 MFMAs per wave (its
-// k-step, four channel subtiles); the taps are unrolled; during step s a wave issues its 2 KB of the slab of step s + 3 and, in the
-// first four taps of a chunk, one unit of the next chunk's window tile.  "At most the copies of step s - 1
-// outstanding" at the barrier of step s means the slab of step s + 1 and the next window tile are resident.
+// Pipeline.  A step = one tap of one 64-channel chunk = 4 MFMAs per wave; the taps are unrolled; during step s a
+// wave issues its share of the slab of step s + DIST and, in the first taps of a chunk, units of the next chunk's
+// window tile; operands of step s + 1 are read while step s multiplies.  Barriers open groups of G steps; the
+// constants and what they must satisfy are stated at the tile shapes below.
 #include "common.h"
 
 #include <mutex>
