@@ -24,6 +24,12 @@ convbn_status fail(convbn_status code, const char* fmt, ...) {
 
 int out_size(int in, int k, int s, int p) { return (in + 2 * p - k) / s + 1; }
 
+struct WgradWay;
+WgradWay wgrad_way(const Geom& g, int dtype);
+bool needs_cin_pad(const Geom& g, int dtype);
+Geom padded_geom(const Geom& g);
+long long widest_partial_elems(const Geom& g, int dtype);
+
 // Fills `g`; returns CONVBN_OK or the reason the descriptor is not usable.
 convbn_status make_geom(const convbn_desc* d, Geom* g) {
   if (!d) return fail(CONVBN_ERR_NULL, "descriptor is NULL");
@@ -53,6 +59,9 @@ convbn_status make_geom(const convbn_desc* d, Geom* g) {
   g->M = d->N * g->Hout * g->Wout;
   g->Min = d->N * d->Hin * d->Win;
   g->K = d->kH * d->kW * d->Cin;
+  // the kernels index the fp32 partial copies of split sums with 32 bits as well
+  if (widest_partial_elems(*g, d->dtype) > lim)
+    return fail(CONVBN_ERR_UNSUPPORTED, "a buffer of partial sums would have more than 2^31-1 elements");
   return CONVBN_OK;
 }
 
@@ -90,6 +99,23 @@ WgradWay wgrad_way(const Geom& g0, int dtype) {
   return {igemm_supported(g, dtype) ? wgrad_splits(g) : wgrad_direct_splits(g), colsum_parts(g), false};
 }
 int nsplit_for(const Geom& g, int dtype) { return wgrad_way(g, dtype).nsplit; }
+
+size_t inner_fprop_scratch(const Geom& g, int dtype);
+size_t inner_dgrad_scratch(const Geom& g, int dtype);
+// Elements of the largest fp32 buffer of partial sums a problem's kernels would write: the split copies of dw' and
+// the partial outputs of convolutions whose reduced channels are divided over workgroups.  Only problems large
+// enough to come near the limit are planned here (every split count is far below 1024, every channel split below 64).
+long long widest_partial_elems(const Geom& g0, int dtype) {
+  const long long lim = 0x7fffffffLL;
+  const long long pp = (long long)g0.Cout * g0.kH * g0.kW * ((g0.Cin + 7) / 8 * 8);
+  const long long act = (long long)(g0.M > g0.Min ? g0.M : g0.Min) * (g0.Cout > g0.Cin ? g0.Cout : g0.Cin);
+  if (pp <= lim / 1024 && act <= lim / 64) return 0;
+  const Geom g = needs_cin_pad(g0, dtype) ? padded_geom(g0) : g0;
+  long long widest = (long long)wgrad_way(g0, dtype).nsplit * g.Cout * g.K;
+  const long long conv = (long long)((inner_fprop_scratch(g, dtype) > inner_dgrad_scratch(g, dtype)
+                                          ? inner_fprop_scratch(g, dtype) : inner_dgrad_scratch(g, dtype)) / 4);
+  return widest > conv ? widest : conv;
+}
 
 size_t fprop_scratch_bytes(const Geom& g, int dtype);
 size_t dgrad_scratch_bytes(const Geom& g, int dtype);
@@ -1336,6 +1362,7 @@ convbn_status convbn_aux_maxpool_fwd(int dtype, const void* x, void* y, void* id
                                      int32_t W, int32_t C, void* stream) {
   if (dtype != CONVBN_F32 && dtype != CONVBN_BF16) return fail(CONVBN_ERR_UNSUPPORTED, "dtype %d", dtype);
   if (N < 1 || H < 1 || W < 1 || C < 1) return fail(CONVBN_ERR_SHAPE, "non-positive dimension");
+  if ((long long)N * H * W * C > 0x7fffffffLL) return fail(CONVBN_ERR_UNSUPPORTED, "the input has more than 2^31-1 elements");
   REQUIRE_PTR(x); REQUIRE_PTR(y); REQUIRE_PTR(idx);
   LAUNCH(launch_maxpool_fwd(dtype, x, y, static_cast<unsigned char*>(idx), N, H, W, C,
                             static_cast<hipStream_t>(stream)));
@@ -1346,6 +1373,7 @@ convbn_status convbn_aux_maxpool_bwd(int dtype, const void* dy, const void* idx,
                                      int32_t W, int32_t C, void* stream) {
   if (dtype != CONVBN_F32 && dtype != CONVBN_BF16) return fail(CONVBN_ERR_UNSUPPORTED, "dtype %d", dtype);
   if (N < 1 || H < 1 || W < 1 || C < 1) return fail(CONVBN_ERR_SHAPE, "non-positive dimension");
+  if ((long long)N * H * W * C > 0x7fffffffLL) return fail(CONVBN_ERR_UNSUPPORTED, "the input has more than 2^31-1 elements");
   REQUIRE_PTR(dy); REQUIRE_PTR(idx); REQUIRE_PTR(dx);
   LAUNCH(launch_maxpool_bwd(dtype, dy, static_cast<const unsigned char*>(idx), dx, N, H, W, C,
                             static_cast<hipStream_t>(stream)));

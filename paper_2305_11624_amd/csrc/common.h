@@ -1,6 +1,8 @@
 // Shared device helpers and the internal launch interface of libconvbn (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <mutex>
 #include <stdint.h>
 
 #include "../../include/convbn.h"
@@ -79,6 +81,17 @@ __device__ __forceinline__ void emit_folded_slice(const BnEpilogue& bn, const bf
 }
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Raises a kernel's dynamic-LDS limit once per process -- also when several host threads launch it for the first
+// time together -- and remembers the outcome.
+struct LdsLimitOnce {
+  std::once_flag once;
+  hipError_t err = hipSuccess;
+};
+inline hipError_t set_lds_limit_once(LdsLimitOnce& s, const void* kernel, int bytes) {
+  std::call_once(s.once, [&] { s.err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); });
+  return s.err;
+}
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- launchers (each enqueues on `st`, returns the hipError of the launch) ----

@@ -336,13 +336,9 @@ PwPlan make_plan(PwParams& p) {
 
 template <int NW, int NCH, int CB, bool SC = false>
 hipError_t launch_inst(const PwParams& p, const PwPlan& pl, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_pw_kernel<NW, NCH, CB, SC>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_USABLE);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsLimitOnce lds_once;
+  if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&conv_pw_kernel<NW, NCH, CB, SC>),
+                                        (int)LDS_USABLE); e != hipSuccess) return e;
   hipLaunchKernelGGL((conv_pw_kernel<NW, NCH, CB, SC>), dim3(p.ntr * p.groups), dim3(64 * NW), pl.lds, st, p);
   return hipGetLastError();
 }

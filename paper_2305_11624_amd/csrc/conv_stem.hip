@@ -724,13 +724,9 @@ hipError_t launch_dgrad_stem(const Geom& g, const void* dz, const void* w_crsk, 
   p.dz = (const bf16_t*)dz; p.wt = (const bf16_t*)wpack; p.dx = (bf16_t*)dx;
 #define STEMDG(UUV, VVV, KSV)                                                                                         \
   do {                                                                                                             \
-    static bool attr_set = false;                                                                                  \
-    if (!attr_set) {                                                                                               \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stem_dgrad_kernel<UUV, VVV, KSV>),          \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);                   \
-      if (e != hipSuccess) return e;                                                                               \
-      attr_set = true;                                                                                             \
-    }                                                                                                              \
+    static LdsLimitOnce lds_once;                                                                                  \
+    if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&stem_dgrad_kernel<UUV, VVV, KSV>), \
+                                          80 * 1024); e != hipSuccess) return e;                                   \
     hipLaunchKernelGGL((stem_dgrad_kernel<UUV, VVV, KSV>), dim3(pl.grid), dim3(256), pl.lds, st, p);                \
   } while (0)
   if (p.U == 4 && p.V == 4 && g.Cout == 64) STEMDG(4, 4, 2);   // the usual 7x7 / stride-2 stem with 64 channels: unrolled
@@ -762,13 +758,9 @@ hipError_t launch_fprop_stem(const Geom& g, const void* x, const void* w, void* 
   p.x = (const bf16_t*)x; p.w = (const bf16_t*)wpad; p.bias = bias; p.z = (bf16_t*)z;
 #define STEM(NC, KHV, X3V)                                                                                              \
   do {                                                                                                             \
-    static bool attr_set = false;                                                                                  \
-    if (!attr_set) {                                                                                               \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stem_fprop_kernel<NC, KHV, X3V>),          \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);                   \
-      if (e != hipSuccess) return e;                                                                               \
-      attr_set = true;                                                                                             \
-    }                                                                                                              \
+    static LdsLimitOnce lds_once;                                                                                  \
+    if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&stem_fprop_kernel<NC, KHV, X3V>), \
+                                          64 * 1024); e != hipSuccess) return e;                                   \
     hipLaunchKernelGGL((stem_fprop_kernel<NC, KHV, X3V>), dim3(pl.grid), dim3(256), pl.lds, st, p);                \
   } while (0)
   if (pl.nco == 2 && g.kH == 7 && pl.x3) STEM(2, 7, true);   // the usual 7x7 RGB stem with 64 channels: rows unrolled

@@ -506,21 +506,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
           const int ho = fdiv(rem, p.dWo);
           o = (size_t)p.out_base + (size_t)n * p.out_n + (size_t)ho * p.out_h + (size_t)(rem - ho * p.Wo) * p.out_w;
         }
-#if defined(TILE_NT_STORE)
-        if (pi < len && ch < p.R) {
-          typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-          const u32x4_t vv = {v.x, v.y, v.z, v.w};
-          __builtin_nontemporal_store(vv, reinterpret_cast<u32x4_t*>(p.out + o + ch));
-        }
-#elif defined(TILE_SC1_STORE)
-        if (pi < len && ch < p.R) {
-          typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-          const u32x4_t vv = {v.x, v.y, v.z, v.w};
-          asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p.out + o + ch), "v"(vv) : "memory");
-        }
-#else
         if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + o + ch) = v;
-#endif
       }
     }
   }
@@ -727,13 +713,9 @@ TilePlan make_plan(TileParams& p) {
 
 template <int NW, int NWC, int NCH, int CB, int HPS, bool SC = false>
 hipError_t launch_inst(const TileParams& p, const TilePlan& pl, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_tile_kernel<NW, NWC, NCH, CB, HPS, SC>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_USABLE);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsLimitOnce lds_once;
+  if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&conv_tile_kernel<NW, NWC, NCH, CB, HPS, SC>),
+                                        (int)LDS_USABLE); e != hipSuccess) return e;
   const int ptiles = p.tile_rows > 0 ? p.N * p.tiles_per_image : ceil_div(p.M, 32 * (NW / NWC));
   hipLaunchKernelGGL((conv_tile_kernel<NW, NWC, NCH, CB, HPS, SC>), dim3(p.ntr * ptiles, p.ksplit), dim3(64 * NW), pl.lds, st,
                      p);

@@ -562,13 +562,9 @@ WgPlan make_plan(const Geom& g, WgParams* pp) {
 
 template <int TPB, int NA, int NB, int NT>
 hipError_t launch_inst(const WgParams& p, const WgPlan& pl, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_tile_kernel<TPB, NA, NB, NT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_USABLE);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsLimitOnce lds_once;
+  if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&wgrad_tile_kernel<TPB, NA, NB, NT>),
+                                        (int)LDS_USABLE); e != hipSuccess) return e;
   hipLaunchKernelGGL((wgrad_tile_kernel<TPB, NA, NB, NT>), dim3(p.nci * p.nco * p.ntg, pl.nsplit), dim3(256 * NT), pl.lds,
                      st, p);
   return hipGetLastError();

@@ -222,3 +222,18 @@ def test_grouped_block_queries_and_validation():
     assert bwd(ok, ok, None, None, ok) == B.ERR_NULL         # dgamma missing
     assert bwd(None, None, None, None, None) == B.ERR_NULL   # nothing asked for
     assert L.convbn_grouped_eval_fwd(C.byref(d), G, ok, ok, None, ok, ok, ok, ok, ok, None, ok, need, None) == B.ERR_NULL   # y_saved
+
+
+def test_sizes_beyond_32_bit_indexing_are_rejected_on_the_host():
+    """The kernels index tensors and buffers of partial sums with 32 bits: larger problems are turned down by the
+    host checks (no launch, so this runs without a GPU)."""
+    fake = C.c_void_p(4096)
+    L = B.lib()
+    big = (B.BF16, fake, fake, fake, 1 << 12, 1 << 10, 1 << 10, 8, None)   # 2^35 elements
+    assert L.convbn_aux_maxpool_fwd(*big) == B.ERR_UNSUPPORTED, B.convbn_last_error()
+    assert L.convbn_aux_maxpool_bwd(*big) == B.ERR_UNSUPPORTED, B.convbn_last_error()
+    # every tensor of this block fits, and so do the partial sums its plan would write: accepted, sizes consistent
+    d = B.make_desc(N=4, Cin=4096, Hin=14, Win=14, Cout=4096, kH=3, kW=3, stride=1, pad=1, dtype=B.BF16)
+    need = B.convbn_workspace_bytes(d, B.MODE_TUNE, B.PASS_BWD)
+    assert need > 0 and need % 256 == 0
+    assert B.convbn_wgrad_parts(d) * 4096 * 9 * 4096 <= 0x7fffffff
