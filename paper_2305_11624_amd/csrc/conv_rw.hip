@@ -302,21 +302,28 @@ bool finish_plan(RwParams& p, int kH, int kW, int C, int R) {
   if (p.M < 64 * 256) return false;   // a stream of pixels long enough to give every compute unit two subtiles
   p.Hv = p.Ho + 2;
   p.Wv = p.Wo + 2;
-  // one workgroup per compute unit if its pixels' window fits, else two, three, ... rounds
-  for (int rounds = 1; rounds <= 8; ++rounds) {
-    p.L = ceil_div(p.M, 256 * rounds);
-    if (p.L > MAX_L) continue;
-    const int nwg = ceil_div(p.M, p.L);
-    bool fits = true;
-    for (int b = 0; b < nwg && fits; ++b) fits = window_pixels(p, b) <= MAX_UNITS * 8;
-    if (!fits) continue;
-    p.dHoWo = make_fastdiv(p.Ho * p.Wo);
-    p.dWo = make_fastdiv(p.Wo);
-    p.dHv = make_fastdiv(p.Hv);
-    p.dWv = make_fastdiv(p.Wv);
-    return true;
+  // one workgroup per compute unit if its pixels' window fits, else two, three, ... rounds.  The search walks over
+  // every workgroup's window; a caller asks for the same problem several times per launch, so the last answer is kept.
+  static thread_local struct { int M, Ho, Wo, L; } memo = {0, 0, 0, 0};
+  if (memo.M != p.M || memo.Ho != p.Ho || memo.Wo != p.Wo) {
+    int found = 0;
+    for (int rounds = 1; rounds <= 8 && !found; ++rounds) {
+      p.L = ceil_div(p.M, 256 * rounds);
+      if (p.L > MAX_L) continue;
+      const int nwg = ceil_div(p.M, p.L);
+      bool fits = true;
+      for (int b = 0; b < nwg && fits; ++b) fits = window_pixels(p, b) <= MAX_UNITS * 8;
+      if (fits) found = p.L;
+    }
+    memo = {p.M, p.Ho, p.Wo, found};
   }
-  return false;
+  if (!memo.L) return false;
+  p.L = memo.L;
+  p.dHoWo = make_fastdiv(p.Ho * p.Wo);
+  p.dWo = make_fastdiv(p.Wo);
+  p.dHv = make_fastdiv(p.Hv);
+  p.dWv = make_fastdiv(p.Wv);
+  return true;
 }
 
 bool fprop_params(const Geom& g, RwParams* p) {
