@@ -636,6 +636,15 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
   if (s != CONVBN_OK) return s;
   const TuneBwdWs w = carve_tune_bwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (params && convbn_tune_bwd_is_fused(desc)) {
+    // deep layers: dw', r and the fold-back in one launch (the fp32 dw' never reaches memory); the space of the
+    // fp32 copy holds the few partial sums the workgroups exchange.  Where nothing was kept, the same launch leaves
+    // w' for the input gradient, which then runs second: no fold launch.
+    void* refold = (dx && !w_folded) ? w.w_crsk : nullptr;
+    LAUNCH(launch_wgrad_sq_fused(g, x, dz, W, b, gamma, mean, var, dW, db, dgamma, dbeta, w.dwf_part, refold, st));
+    if (dx) LAUNCH(run_dgrad(g, dt, dz, w_folded ? w_folded : w.w_crsk, dx, w.conv_scratch, st));   // dX = w'_rot (*) dZ
+    return CONVBN_OK;
+  }
   if (dx) {
     const void* wt = w_folded;
     if (!wt) {  // nothing was kept: fold again, transposed order only
@@ -645,14 +654,6 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
     LAUNCH(run_dgrad(g, dt, dz, wt, dx, w.conv_scratch, st));   // dX = w'_rot (*) dZ
   }
   if (!params) return CONVBN_OK;
-  if (convbn_tune_bwd_is_fused(desc)) {
-    // deep layers: dw', r and the fold-back in one launch (the fp32 dw' never reaches memory); the space of the
-    // fp32 copy holds the few partial sums the workgroups exchange.  (Letting this launch also write w' for the
-    // input gradient, to save the fold above, was measured: its 64-byte pieces of [Cin][taps][Cout] rows cost
-    // 22 us where the fold kernel takes 5.)
-    LAUNCH(launch_wgrad_sq_fused(g, x, dz, W, b, gamma, mean, var, dW, db, dgamma, dbeta, w.dwf_part, st));
-    return CONVBN_OK;
-  }
   LAUNCH(run_wgrad(g, dt, x, dz, w.dwf_part, w.r_part, w.wgrad_scratch, st));   // dw' = dZ (.) X and r = sum dZ (fp32 partials)
   LAUNCH(launch_fold_back(g, dt, w.dwf_part, w.nsplit, w.r_part, w.nrpart, W, b, gamma, mean, var, 0,
                           dW, db, dgamma, dbeta, st));

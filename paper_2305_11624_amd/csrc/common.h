@@ -300,10 +300,12 @@ hipError_t launch_wgrad_sq(const Geom& g, const void* x, const void* dz, float* 
                            hipStream_t st);
 // Weight gradient and fold-back in one launch, for problems whose pixels need no split (deep layers): writes dW,
 // dgamma, dbeta and (b given) db directly; no fp32 copy of dw' is stored.  scratch: wgrad_sq_fused_scratch_bytes().
+// w_folded_out (optional): the launch also leaves w' = s w there as [Cin][taps][Cout], for an input gradient that
+// runs after it.
 bool wgrad_sq_fused_supported(const Geom& g, int dtype);
 size_t wgrad_sq_fused_scratch_bytes(const Geom& g);
 hipError_t launch_wgrad_sq_fused(const Geom& g, const void* x, const void* dz, const void* W, const float* b,
                                  const float* gamma, const float* mean, const float* var, void* dW, float* db,
-                                 float* dgamma, float* dbeta, void* scratch, hipStream_t st);
+                                 float* dgamma, float* dbeta, void* scratch, void* w_folded_out, hipStream_t st);
 
 }  // namespace convbn

@@ -66,6 +66,7 @@ struct SqParams {
   // [nci + 1][Co]; the one that finds all of them in place finishes dgamma, dbeta, db for the tile's 32 channels.
   const bf16_t* wgt;   // the unfolded weight; null: not fused
   bf16_t* dW;
+  bf16_t* w_t;         // optional: w' = s w is left here as [Cin][taps][Cout], for the input gradient that follows
   const float* gamma; const float* mean; const float* var; const float* b;
   float* db; float* dgamma; float* dbeta;
   uint4* slots;              // {value, tag low, tag high, 0}
@@ -463,12 +464,29 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
       const int co = it * 16 + (lane >> 2), g = lane & 3;
       *reinterpret_cast<uint4*>(wtile + co * 64 + g * 16) = wpre[t][it];
     }
+    // w' of this block in the transposed order: [32 ci][32 co], in the space of this tap's second accumulator copy
+    unsigned short* ttile = reinterpret_cast<unsigned short*>(red + COPY4 + (size_t)tap * (4 * 64));
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const uint2 w = *reinterpret_cast<const uint2*>(wtile + co_l * 64 + (8 * q + 4 * kb) * 2);
       dot += v[q][0] * bf16_lo(w.x) + v[q][1] * bf16_hi(w.x) + v[q][2] * bf16_lo(w.y) + v[q][3] * bf16_hi(w.y);
       *reinterpret_cast<uint2*>(otile + co_l * 64 + (8 * q + 4 * kb) * 2) =
           make_uint2(pack_bf16x2(scale * v[q][0], scale * v[q][1]), pack_bf16x2(scale * v[q][2], scale * v[q][3]));
+      if (p.w_t) {   // the same product and rounding as the fold kernel's
+        const unsigned a = pack_bf16x2(bf16_lo(w.x) * scale, bf16_hi(w.x) * scale);
+        const unsigned b = pack_bf16x2(bf16_lo(w.y) * scale, bf16_hi(w.y) * scale);
+        unsigned short* col = ttile + (8 * q + 4 * kb) * 32 + co_l;
+        col[0] = (unsigned short)a; col[32] = (unsigned short)(a >> 16);
+        col[64] = (unsigned short)b; col[96] = (unsigned short)(b >> 16);
+      }
+    }
+    if (p.w_t) {
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {
+        const int ci = it * 16 + (lane >> 2), g = lane & 3;
+        *reinterpret_cast<uint4*>(p.w_t + ((size_t)(ci0 + ci) * TAPS + tap) * p.Co + co0 + g * 8) =
+            *reinterpret_cast<const uint4*>(ttile + ci * 32 + g * 8);
+      }
     }
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
@@ -649,13 +667,13 @@ size_t wgrad_sq_fused_scratch_bytes(const Geom& g) {
 
 hipError_t launch_wgrad_sq_fused(const Geom& g, const void* x, const void* dz, const void* W, const float* b,
                                  const float* gamma, const float* mean, const float* var, void* dW, float* db,
-                                 float* dgamma, float* dbeta, void* scratch, hipStream_t st) {
+                                 float* dgamma, float* dbeta, void* scratch, void* w_folded_out, hipStream_t st) {
   SqParams p;
   const SqPlan pl = make_plan(g, &p);
   if (!pl.ok || pl.nsplit != 1 || !scratch) return hipErrorInvalidValue;
   p.x = (const bf16_t*)x; p.dz = (const bf16_t*)dz; p.part = nullptr;
   p.r_part = reinterpret_cast<float*>(scratch);   // only its non-NULL-ness matters here: the channel sums are wanted
-  p.wgt = (const bf16_t*)W; p.dW = (bf16_t*)dW; p.gamma = gamma; p.mean = mean; p.var = var; p.b = b;
+  p.wgt = (const bf16_t*)W; p.dW = (bf16_t*)dW; p.w_t = (bf16_t*)w_folded_out; p.gamma = gamma; p.mean = mean; p.var = var; p.b = b;
   p.db = db; p.dgamma = dgamma; p.dbeta = dbeta; p.eps = g.eps;
   p.slots = reinterpret_cast<uint4*>(scratch);   // workspace pieces are 256-byte aligned
   p.tag = next_tag();
