@@ -651,6 +651,13 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
       LAUNCH(launch_fold(g, dt, W, b, gamma, nullptr, mean, var, 0, nullptr, w.w_crsk, nullptr, st));
       wt = w.w_crsk;
     }
+    if (params && !needs_cin_pad(g, dt) && wgrad_way(g, dt).sq && wgrad_dgrad_pair_supported(g, dt)) {
+      // shallow layers: the two gradient passes are independent and share one launch (see wgrad_sq.hip)
+      LAUNCH(launch_wgrad_dgrad_pair(g, x, dz, wt, dx, w.dwf_part, w.r_part, st));
+      LAUNCH(launch_fold_back(g, dt, w.dwf_part, w.nsplit, w.r_part, w.nrpart, W, b, gamma, mean, var, 0,
+                              dW, db, dgamma, dbeta, st));
+      return CONVBN_OK;
+    }
     LAUNCH(run_dgrad(g, dt, dz, wt, dx, w.conv_scratch, st));   // dX = w'_rot (*) dZ
   }
   if (!params) return CONVBN_OK;

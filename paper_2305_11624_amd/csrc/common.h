@@ -298,6 +298,11 @@ bool wgrad_sq_supported(const Geom& g, int dtype);
 int wgrad_sq_splits(const Geom& g);
 hipError_t launch_wgrad_sq(const Geom& g, const void* x, const void* dz, float* dwf_part, float* r_part,
                            hipStream_t st);
+// Input gradient and weight gradient (fp32 copies as launch_wgrad_sq writes them) of a block in one launch, where the
+// resident-weight convolution takes the input gradient.
+bool wgrad_dgrad_pair_supported(const Geom& g, int dtype);
+hipError_t launch_wgrad_dgrad_pair(const Geom& g, const void* x, const void* dz, const void* w_crsk, void* dx,
+                                   float* dwf_part, float* r_part, hipStream_t st);
 // Weight gradient and fold-back in one launch, for problems whose pixels need no split (deep layers): writes dW,
 // dgamma, dbeta and (b given) db directly; no fp32 copy of dw' is stored.  scratch: wgrad_sq_fused_scratch_bytes().
 // w_folded_out (optional): the launch also leaves w' = s w there as [Cin][taps][Cout], for an input gradient that

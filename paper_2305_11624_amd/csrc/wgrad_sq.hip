@@ -19,6 +19,7 @@
 // The eight waves split each tile's pixels (16 KS each), every wave holds all nine accumulator tiles, and
 // the waves add their sums through LDS at the end.
 #include "common.h"
+#include "conv_rw_impl.h"   // the input gradient that can share a launch with this kernel
 
 #include <atomic>
 #include <chrono>
@@ -146,23 +147,22 @@ __device__ unsigned long long sq_trace[512 * 64];
 #ifndef SQ_TRACE_WAVE
 #define SQ_TRACE_WAVE 0
 #endif
-#define STAMP(i) do { if (tid == 64 * SQ_TRACE_WAVE && (i) < 64) sq_trace[blockIdx.x * 64 + (i)] = clock64(); } while (0)
+#define STAMP(i) do { if (tid == 64 * SQ_TRACE_WAVE && (i) < 64) sq_trace[block * 64 + (i)] = clock64(); } while (0)
 #else
 #define STAMP(i) do {} while (0)
 #endif
 
 // KS: 16-pixel steps per wave and tile (tile = 128 KS pixels).  NCPY: copies per wave and tile (KS dZ units + the
 // window units wave, wave + 8, ...; units past a tile's window rows are zero-fill copies, so the count is fixed).
+// The work of workgroup `block`; smem: the workgroup's LDS.
 template <int KS, int NCPY>
-__global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
+__device__ __forceinline__ void sq_body(const SqParams& p, int block, unsigned char* smem) {
   constexpr int TILE = 128 * KS;
   constexpr int ZT = TILE * ROWB;          // dZ tile bytes
   constexpr int NS = TAPS * KS;            // multiplies per wave and tile
   constexpr int NXU = NCPY - KS;           // window units per wave
   constexpr int AHEAD = 4;                 // operands are read this many multiplies ahead
   constexpr int NSTAGE = 3;
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   STAMP(0);
@@ -171,8 +171,8 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
   // channel pairs of one pixel split (pairs that share dZ slices along one side and X slices along the other);
   // block j goes to XCD j % 8, whose k-th workgroup (k = id / 8) takes pair k % (bc bi) of its (k / (bc bi))-th block.
   const int bsize = p.bc * p.bi;
-  const int k_x = blockIdx.x >> 3;
-  const int blk = (k_x / bsize) * 8 + (blockIdx.x & 7);
+  const int k_x = block >> 3;
+  const int blk = (k_x / bsize) * 8 + (block & 7);
   if (blk >= p.nblocks) return;
   const int w_b = k_x % bsize;
   const int split = blk / p.blocks_per_split;
@@ -552,6 +552,24 @@ __global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
   if (p.db) p.db[ch] = p.gamma[ch] / sd * r;
 }
 
+template <int KS, int NCPY>
+__global__ __launch_bounds__(64 * NWAVES) void wgrad_sq_kernel(SqParams p) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  sq_body<KS, NCPY>(p, blockIdx.x, smem);
+}
+
+// Weight gradient and input gradient of one block in ONE launch: the two passes are independent (both read dZ), each
+// fills the chip with one workgroup per compute unit and a tail of its own, and two launches cannot overlap.  As one
+// grid the first nsq workgroups are the weight gradient's, the rest the input gradient's (conv_rw_impl.h): compute
+// units that finish -- or never had -- a workgroup of the first take workgroups of the second, and the phases in
+// which all workgroups of one pass load or drain at once are filled by the other's multiplies.
+template <int KS, int NCPY>
+__global__ __launch_bounds__(64 * NWAVES) void wgrad_dgrad_pair_kernel(SqParams ps, rw::RwParams pr, int nsq) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  if ((int)blockIdx.x < nsq) sq_body<KS, NCPY>(ps, blockIdx.x, smem);
+  else rw::body(pr, (int)blockIdx.x - nsq, (int)gridDim.x - nsq, smem);
+}
+
 // Largest number of window-tile pixels any tile of `tile` consecutive output pixels needs.
 int max_window_pixels(const SqParams& p, int tile) {
   const int HoWo = p.Ho * p.Wo;
@@ -637,6 +655,18 @@ hipError_t launch_inst(const SqParams& p, const SqPlan& pl, hipStream_t st) {
   return hipGetLastError();
 }
 
+template <int KS, int NCPY>
+hipError_t launch_pair_inst(const SqParams& ps, const SqPlan& pl, const rw::RwParams& pr, hipStream_t st) {
+  static LdsLimitOnce lds_once;
+  if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&wgrad_dgrad_pair_kernel<KS, NCPY>),
+                                        (int)LDS_USABLE); e != hipSuccess) return e;
+  const int nsq = 8 * ceil_div(ps.nblocks, 8) * ps.bc * ps.bi;
+  const int nrw = ceil_div(pr.M, pr.L);
+  const size_t lds = pl.lds > (size_t)pr.lds_bytes ? pl.lds : (size_t)pr.lds_bytes;   // <= LDS_USABLE: checked by the caller
+  hipLaunchKernelGGL((wgrad_dgrad_pair_kernel<KS, NCPY>), dim3(nsq + nrw), dim3(64 * NWAVES), lds, st, ps, pr, nsq);
+  return hipGetLastError();
+}
+
 unsigned long long next_tag() {
   static std::atomic<unsigned long long> tag{
       (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9E3779B97F4A7C15ull};
@@ -678,6 +708,31 @@ hipError_t launch_wgrad_sq_fused(const Geom& g, const void* x, const void* dz, c
   p.slots = reinterpret_cast<uint4*>(scratch);   // workspace pieces are 256-byte aligned
   p.tag = next_tag();
   return dispatch(p, pl, st);
+}
+
+// One launch for the input gradient (resident-weight kernel) and the weight gradient (fp32 copies for the fold-back)
+// of a block: where both kernels take the problem and the weight gradient runs on 256-pixel tiles.
+bool wgrad_dgrad_pair_supported(const Geom& g, int dtype) {
+  if (dtype != CONVBN_BF16) return false;
+  SqParams ps;
+  rw::RwParams pr;
+  const SqPlan pl = make_plan(g, &ps);
+  // (the weight-gradient kernel keeps a KB of LDS of its own, so the pair has LDS_USABLE, not all 160 KB, for either body)
+  return pl.ok && pl.ks == 2 && rw::dgrad_params(g, &pr) && (size_t)pr.lds_bytes <= LDS_USABLE;
+}
+
+hipError_t launch_wgrad_dgrad_pair(const Geom& g, const void* x, const void* dz, const void* w_crsk, void* dx,
+                                   float* dwf_part, float* r_part, hipStream_t st) {
+  SqParams ps;
+  rw::RwParams pr;
+  const SqPlan pl = make_plan(g, &ps);
+  if (!pl.ok || pl.ks != 2 || !rw::dgrad_params(g, &pr) || (size_t)pr.lds_bytes > LDS_USABLE) return hipErrorInvalidValue;
+  ps.x = (const bf16_t*)x; ps.dz = (const bf16_t*)dz; ps.part = dwf_part; ps.r_part = r_part;
+  pr.act = (const bf16_t*)dz; pr.wgt = (const bf16_t*)w_crsk; pr.bias = nullptr; pr.out = (bf16_t*)dx;
+#define CASE(X) if (pl.ncpy == 2 + X) return launch_pair_inst<2, 2 + X>(ps, pl, pr, st);
+  CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6)
+#undef CASE
+  return hipErrorInvalidValue;
 }
 
 bool wgrad_sq_supported(const Geom& g, int dtype) {
