@@ -378,18 +378,16 @@ __device__ __forceinline__ void sq_body(const SqParams& p, int block, unsigned c
   // row, and the channel scale) is requested now and arrives while the accumulators are summed.
   const bool fused = p.wgt != nullptr;
   const int co_l = lane & 31;
-  uint4 wpre[2][2] = {};
+  uint4 wpa0 = make_uint4(0u, 0u, 0u, 0u), wpb0 = wpa0, wpa1 = wpa0, wpb1 = wpa0;   // (tap wave | wave + 8) x (rows 0..15 | 16..31)
   float gam = 1.f, vr = 1.f;
   if (fused) {
     gam = p.gamma[co0 + co_l];
     vr = p.var[co0 + co_l];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-      if (wave + t * NWAVES < TAPS)
-#pragma unroll
-        for (int it = 0; it < 2; ++it)
-          wpre[t][it] = *reinterpret_cast<const uint4*>(
-              p.wgt + ((size_t)(co0 + it * 16 + (lane >> 2)) * TAPS + wave + t * NWAVES) * p.Cin + ci0 + (lane & 3) * 8);
+    auto w_block = [&](int tap, int it) {
+      return *reinterpret_cast<const uint4*>(p.wgt + ((size_t)(co0 + it * 16 + (lane >> 2)) * TAPS + tap) * p.Cin + ci0 + (lane & 3) * 8);
+    };
+    wpa0 = w_block(wave, 0); wpb0 = w_block(wave, 1);
+    if (wave + NWAVES < TAPS) { wpa1 = w_block(wave + NWAVES, 0); wpb1 = w_block(wave + NWAVES, 1); }
   }
   // copies as [copy][tap][q][lane] float4 (q = accumulator elements 4 q .. 4 q + 3): every access is 16 bytes per
   // lane, consecutive lanes consecutive banks
@@ -434,10 +432,7 @@ __device__ __forceinline__ void sq_body(const SqParams& p, int block, unsigned c
   STAMP(61);
   float dot = 0.f;
   const float scale = fused ? gam / sqrtf(vr + p.eps) : 1.f;
-#pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    const int tap = wave + t * NWAVES;
-    if (tap >= TAPS) break;
+  auto finish_tap = [&](int tap, const uint4& wpa, const uint4& wpb) {
     const float4* src = red + (size_t)tap * (4 * 64) + lane;
     const size_t o = (((size_t)split * p.Co + co0 + co_l) * TAPS + tap) * p.Cin + ci0 + 4 * kb;
     float v[4][4];
@@ -451,7 +446,7 @@ __device__ __forceinline__ void sq_body(const SqParams& p, int block, unsigned c
 #pragma unroll
       for (int q = 0; q < 4; ++q)
         *reinterpret_cast<float4*>(p.part + o + 8 * q) = make_float4(v[q][0], v[q][1], v[q][2], v[q][3]);
-      continue;
+      return;
     }
     // Fused fold-back.  In the accumulators a lane holds 4 input channels of one output channel: stores and loads
     // of that shape would touch memory in 8-byte pieces.  The 32 x 32 block of w and of dW for this tap therefore
@@ -459,11 +454,8 @@ __device__ __forceinline__ void sq_body(const SqParams& p, int block, unsigned c
     // accesses are 16 bytes per lane, four lanes per 64-byte row of the block.
     unsigned char* wtile = reinterpret_cast<unsigned char*>(red + (size_t)tap * (4 * 64));   // [32 co][32 ci] bf16
     unsigned char* otile = wtile + 2048;
-#pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const int co = it * 16 + (lane >> 2), g = lane & 3;
-      *reinterpret_cast<uint4*>(wtile + co * 64 + g * 16) = wpre[t][it];
-    }
+    *reinterpret_cast<uint4*>(wtile + (lane >> 2) * 64 + (lane & 3) * 16) = wpa;
+    *reinterpret_cast<uint4*>(wtile + (16 + (lane >> 2)) * 64 + (lane & 3) * 16) = wpb;
     // w' of this block in the transposed order: [32 ci][32 co], in the space of this tap's second accumulator copy
     unsigned short* ttile = reinterpret_cast<unsigned short*>(red + COPY4 + (size_t)tap * (4 * 64));
 #pragma unroll
@@ -494,7 +486,9 @@ __device__ __forceinline__ void sq_body(const SqParams& p, int block, unsigned c
       *reinterpret_cast<uint4*>(p.dW + ((size_t)(co0 + co) * TAPS + tap) * p.Cin + ci0 + g * 8) =
           *reinterpret_cast<const uint4*>(otile + co * 64 + g * 16);
     }
-  }
+  };
+  finish_tap(wave, wpa0, wpb0);
+  if (wave + NWAVES < TAPS) finish_tap(wave + NWAVES, wpa1, wpb1);
   if (do_r && tid < 32) {
     float v = 0.f;
     for (int w = 0; w < NWAVES; ++w) v += rred[w * 32 + tid];
