@@ -219,12 +219,10 @@ convbn_status check_ws(size_t need, void* ws, size_t ws_bytes) {
 // reduced channels are split over workgroups, and the zero-padded copies of needs_cin_pad().
 size_t inner_fprop_scratch(const Geom& g, int dtype) {
   if (pw_fprop_supported(g, dtype) || rw_fprop_supported(g, dtype) || st_fprop_supported(g, dtype)) return 0;
-  if (mt_fprop_supported(g, dtype)) return align_up(mt_fprop_scratch_bytes(g), 256);
   return tile_fprop_supported(g, dtype) ? align_up(tile_fprop_partial_bytes(g), 256) : 0;
 }
 size_t inner_dgrad_scratch(const Geom& g, int dtype) {
   if (pw_dgrad_supported(g, dtype) || rw_dgrad_supported(g, dtype) || st_dgrad_supported(g, dtype)) return 0;
-  if (mt_dgrad_supported(g, dtype)) return align_up(mt_dgrad_scratch_bytes(g), 256);
   return tile_dgrad_supported(g, dtype) ? align_up(tile_dgrad_partial_bytes(g), 256) : 0;
 }
 size_t fprop_scratch_bytes(const Geom& g, int dtype) {
@@ -255,7 +253,6 @@ hipError_t fprop_any(const Geom& g, int dtype, const void* x, const void* w_krsc
   if (pw_fprop_supported(g, dtype)) return launch_fprop_pw(g, x, w_krsc, bias, z, st);
   if (rw_fprop_supported(g, dtype)) return launch_fprop_rw(g, x, w_krsc, bias, z, st);
   if (st_fprop_supported(g, dtype)) return launch_fprop_st(g, x, w_krsc, bias, z, st);
-  if (mt_fprop_supported(g, dtype)) return launch_fprop_mt(g, x, w_krsc, bias, z, scratch, st);
   if (tile_fprop_supported(g, dtype)) return launch_fprop_tile(g, x, w_krsc, bias, z, scratch, st);
   return igemm_supported(g, dtype) ? launch_fprop_igemm(g, x, w_krsc, bias, z, st)
                                    : launch_fprop_direct(g, dtype, x, w_krsc, bias, z, st);
@@ -265,7 +262,6 @@ hipError_t dgrad_any(const Geom& g, int dtype, const void* dz, const void* w_crs
   if (pw_dgrad_supported(g, dtype)) return launch_dgrad_pw(g, dz, w_crsk, bias, dx, st);
   if (rw_dgrad_supported(g, dtype)) return launch_dgrad_rw(g, dz, w_crsk, bias, dx, st);
   if (st_dgrad_supported(g, dtype)) return launch_dgrad_st(g, dz, w_crsk, bias, dx, st);
-  if (mt_dgrad_supported(g, dtype)) return launch_dgrad_mt(g, dz, w_crsk, bias, dx, scratch, st);
   if (tile_dgrad_supported(g, dtype)) return launch_dgrad_tile(g, dz, w_crsk, bias, dx, scratch, st);
   return igemm_supported(g, dtype) ? launch_dgrad_igemm(g, dz, w_crsk, bias, dx, st)
                                    : launch_dgrad_direct(g, dtype, dz, w_crsk, bias, dx, st);

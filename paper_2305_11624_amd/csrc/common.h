@@ -241,18 +241,6 @@ bool pw_tconv_supported(const Geom& g, int dtype);
 hipError_t launch_tconv_pw(const Geom& g, const void* x, const void* w_tap_major, const float* bias_per_tap, void* z,
                            hipStream_t st);
 
-// conv_mt.hip : 3x3 / stride-1 convolutions of deep layers (channel counts that are multiples of 128, few pixels):
-// 256-pixel x 128-channel tiles, the reduced channels split over workgroups and summed by the last one to arrive.
-// `scratch` holds the arrival counters and the fp32 accumulator dumps (mt_*_scratch_bytes(), 0 = not needed).
-bool mt_fprop_supported(const Geom& g, int dtype);
-bool mt_dgrad_supported(const Geom& g, int dtype);
-size_t mt_fprop_scratch_bytes(const Geom& g);
-size_t mt_dgrad_scratch_bytes(const Geom& g);
-hipError_t launch_fprop_mt(const Geom& g, const void* x, const void* w_krsc, const float* bias, void* z,
-                           float* scratch, hipStream_t st);
-hipError_t launch_dgrad_mt(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
-                           float* scratch, hipStream_t st);
-
 // conv_st.hip : 3x3 / stride-1 convolutions of deep layers on 64-pixel x 128-channel tiles shared by eight waves
 // (no split sums, no scratch).
 bool st_fprop_supported(const Geom& g, int dtype);
