@@ -391,6 +391,10 @@ convbn_status convbn_fold_back(const convbn_desc *desc, const float *dw_part, co
  *     [N][Ho][Wo][C], Ho = (H-1)/2+1; idx (one byte per output element) records the winner.
  *   convbn_aux_maxpool_bwd: dx [N][H][W][C] from dy and idx. */
 convbn_status convbn_aux_eltwise(int op, int dtype, void *a, const void *b, size_t n, void *stream);
+/* a = y > 0 ? a + b : 0 -- op 3 followed by op 1 (same rounding of the sum) in one pass: where the gradients of a
+ * residual unit's two branches meet in front of the ReLU that produced y. */
+convbn_status convbn_aux_add_relu_bwd(int dtype, void *a, const void *b, const void *y, size_t n,
+                                      void *stream);
 convbn_status convbn_aux_maxpool_fwd(int dtype, const void *x, void *y, void *idx, int32_t N,
                                      int32_t H, int32_t W, int32_t C, void *stream);
 convbn_status convbn_aux_maxpool_bwd(int dtype, const void *dy, const void *idx, void *dx,

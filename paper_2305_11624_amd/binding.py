@@ -23,7 +23,7 @@ EXPORTS = ["convbn_hout", "convbn_wout", "convbn_workspace_bytes", "convbn_saved
            "convbn_tune_fwd", "convbn_tune_bwd", "convbn_eval_fwd", "convbn_eval_bwd",
            "convbn_last_error", "convbn_fold", "convbn_conv_fprop", "convbn_conv_dgrad",
            "convbn_wgrad_parts", "convbn_rsum_parts", "convbn_conv_wgrad", "convbn_fold_back",
-           "convbn_conv_workspace_bytes", "convbn_aux_eltwise", "convbn_aux_maxpool_fwd",
+           "convbn_conv_workspace_bytes", "convbn_aux_eltwise", "convbn_aux_add_relu_bwd", "convbn_aux_maxpool_fwd",
            "convbn_aux_maxpool_bwd", "convbn_fold_group_table_bytes", "convbn_fold_group_plan",
            "convbn_fold_group", "convbn_tconv_hout", "convbn_tconv_wout", "convbn_tconv_workspace_bytes",
            "convbn_tconv_tune_fwd", "convbn_tconv_tune_bwd", "convbn_tconv_saved_bytes",
@@ -122,6 +122,8 @@ def lib():
         L.convbn_fold_back.argtypes = [dp, fp, fp, vp, fp, fp, fp, fp, vp, fp, fp, fp, vp]
         L.convbn_aux_eltwise.restype = C.c_int
         L.convbn_aux_eltwise.argtypes = [C.c_int, C.c_int, vp, vp, C.c_size_t, vp]
+        L.convbn_aux_add_relu_bwd.restype = C.c_int
+        L.convbn_aux_add_relu_bwd.argtypes = [C.c_int, vp, vp, vp, C.c_size_t, vp]
         L.convbn_aux_maxpool_fwd.restype = C.c_int
         L.convbn_aux_maxpool_fwd.argtypes = [C.c_int, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp]
         L.convbn_aux_maxpool_bwd.restype = C.c_int
@@ -425,6 +427,10 @@ def _dtype_code(t: torch.Tensor) -> int:
 
 def convbn_aux_eltwise(op, a, b=None, stream=None):
     _check(lib().convbn_aux_eltwise(op, _dtype_code(a), _ptr(a), _ptr(b), a.numel(), _stream(stream)))
+
+
+def convbn_aux_add_relu_bwd(a, b, y, stream=None):
+    _check(lib().convbn_aux_add_relu_bwd(_dtype_code(a), _ptr(a), _ptr(b), _ptr(y), a.numel(), _stream(stream)))
 
 
 def convbn_aux_maxpool_fwd(x, y, idx, stream=None):

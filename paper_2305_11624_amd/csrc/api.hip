@@ -1358,7 +1358,15 @@ convbn_status convbn_aux_eltwise(int op, int dtype, void* a, const void* b, size
   REQUIRE_PTR(a);
   if (op != 0) REQUIRE_PTR(b);
   if (n % 8 != 0) return fail(CONVBN_ERR_SHAPE, "element count must be a multiple of 8");
-  LAUNCH(launch_eltwise(op, dtype, a, b, n, static_cast<hipStream_t>(stream)));
+  LAUNCH(launch_eltwise(op, dtype, a, b, nullptr, n, static_cast<hipStream_t>(stream)));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_aux_add_relu_bwd(int dtype, void* a, const void* b, const void* y, size_t n, void* stream) {
+  if (dtype != CONVBN_F32 && dtype != CONVBN_BF16) return fail(CONVBN_ERR_UNSUPPORTED, "dtype %d", dtype);
+  REQUIRE_PTR(a); REQUIRE_PTR(b); REQUIRE_PTR(y);
+  if (n % 8 != 0) return fail(CONVBN_ERR_SHAPE, "element count must be a multiple of 8");
+  LAUNCH(launch_eltwise(4, dtype, a, b, y, n, static_cast<hipStream_t>(stream)));
   return CONVBN_OK;
 }
 

@@ -31,27 +31,31 @@ template <> __device__ __forceinline__ void stv<float>(float* p, const float (&v
   *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
 }
 
-enum { OP_RELU = 0, OP_RELU_BWD = 1, OP_ADD_RELU = 2, OP_ADD = 3 };
+enum { OP_RELU = 0, OP_RELU_BWD = 1, OP_ADD_RELU = 2, OP_ADD = 3, OP_ADD_RELU_BWD = 4 };
 
 // a (in/out), b (second operand; unused for OP_RELU).  n is a multiple of the vector width.
 //   OP_RELU      a = max(a, 0)
 //   OP_RELU_BWD  a = b > 0 ? a : 0          (a = gradient, b = the ReLU's output)
 //   OP_ADD_RELU  a = max(a + b, 0)
 //   OP_ADD       a = a + b
+//   OP_ADD_RELU_BWD  a = c > 0 ? a + b : 0  (two gradient branches meet in front of a ReLU whose output is c: the
+//                    sum rounded as OP_ADD rounds it, then OP_RELU_BWD, in one pass over the tensors)
 template <typename T, int OP>
-__global__ __launch_bounds__(256) void eltwise_kernel(T* __restrict__ a, const T* __restrict__ b, size_t n) {
+__global__ __launch_bounds__(256) void eltwise_kernel(T* __restrict__ a, const T* __restrict__ b, const T* __restrict__ c, size_t n) {
   constexpr int V = Vec<T>::N;
   const size_t nv = n / V;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nv; i += (size_t)gridDim.x * 256) {
-    float x[V], y[V];
+    float x[V], y[V], m[V];
     ldv<T>(a + i * V, x);
     if (OP != OP_RELU) ldv<T>(b + i * V, y);
+    if (OP == OP_ADD_RELU_BWD) ldv<T>(c + i * V, m);
 #pragma unroll
     for (int e = 0; e < V; ++e) {
       if (OP == OP_RELU) x[e] = fmaxf(x[e], 0.f);
       if (OP == OP_RELU_BWD) x[e] = y[e] > 0.f ? x[e] : 0.f;
       if (OP == OP_ADD_RELU) x[e] = fmaxf(to_f32(from_f32<T>(x[e] + y[e])), 0.f);
       if (OP == OP_ADD) x[e] = x[e] + y[e];
+      if (OP == OP_ADD_RELU_BWD) x[e] = m[e] > 0.f ? x[e] + y[e] : 0.f;
     }
     stv<T>(a + i * V, x);
   }
@@ -203,14 +207,14 @@ int blocks_for(size_t work) {
 
 }  // namespace
 
-hipError_t launch_eltwise(int op, int dtype, void* a, const void* b, size_t n, hipStream_t st) {
-#define EL(T, OP) hipLaunchKernelGGL((eltwise_kernel<T, OP>), dim3(blocks_for(n / Vec<T>::N)), dim3(256), 0, st, (T*)a, (const T*)b, n)
+hipError_t launch_eltwise(int op, int dtype, void* a, const void* b, const void* c, size_t n, hipStream_t st) {
+#define EL(T, OP) hipLaunchKernelGGL((eltwise_kernel<T, OP>), dim3(blocks_for(n / Vec<T>::N)), dim3(256), 0, st, (T*)a, (const T*)b, (const T*)c, n)
   if (dtype == CONVBN_BF16) {
     if (op == OP_RELU) EL(bf16_t, OP_RELU); else if (op == OP_RELU_BWD) EL(bf16_t, OP_RELU_BWD);
-    else if (op == OP_ADD_RELU) EL(bf16_t, OP_ADD_RELU); else EL(bf16_t, OP_ADD);
+    else if (op == OP_ADD_RELU) EL(bf16_t, OP_ADD_RELU); else if (op == OP_ADD_RELU_BWD) EL(bf16_t, OP_ADD_RELU_BWD); else EL(bf16_t, OP_ADD);
   } else {
     if (op == OP_RELU) EL(float, OP_RELU); else if (op == OP_RELU_BWD) EL(float, OP_RELU_BWD);
-    else if (op == OP_ADD_RELU) EL(float, OP_ADD_RELU); else EL(float, OP_ADD);
+    else if (op == OP_ADD_RELU) EL(float, OP_ADD_RELU); else if (op == OP_ADD_RELU_BWD) EL(float, OP_ADD_RELU_BWD); else EL(float, OP_ADD);
   }
 #undef EL
   return hipGetLastError();

@@ -157,7 +157,7 @@ hipError_t launch_repitch(int elem_bytes, size_t rows, size_t inner_in, size_t i
 
 // aux_ops.hip : glue between blocks for the whole-backbone measurement
 //   op: 0 relu (a), 1 relu backward (a = b > 0 ? a : 0), 2 a = relu(a + b), 3 a += b;  n % 8 == 0
-hipError_t launch_eltwise(int op, int dtype, void* a, const void* b, size_t n, hipStream_t st);
+hipError_t launch_eltwise(int op, int dtype, void* a, const void* b, const void* c, size_t n, hipStream_t st);
 hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, unsigned char* idx, int N, int H, int W, int C,
                               hipStream_t st);
 hipError_t launch_maxpool_bwd(int dtype, const void* dy, const unsigned char* idx, void* dx, int N, int H, int W,

@@ -258,10 +258,11 @@ class ResNet50:
     def backward(self, dout: torch.Tensor, need_input_grad: bool = False) -> Optional[torch.Tensor]:
         ws, bl, tape = self.ws, self.blocks, self._tape
         g = dout.clone()
-        for name, has_ds, a, b, out in reversed(tape["units"]):
+        order = list(reversed(tape["units"]))
+        B.convbn_aux_eltwise(B.OP_RELU_BWD, g, order[0][4])   # the last unit's ReLU; the others' ride on the adds below
+        for i, (name, has_ds, a, b, out) in enumerate(order):
             if self.units is not None and self.units[name]["refold"] is not None:
                 B.convbn_fold_group(*self.units[name]["refold"])   # blocks that kept nothing: w' again, for this unit
-            B.convbn_aux_eltwise(B.OP_RELU_BWD, g, out)
             gb = bl[name + ".c"].backward(g, ws)
             B.convbn_aux_eltwise(B.OP_RELU_BWD, gb, b)
             ga = bl[name + ".b"].backward(gb, ws)
@@ -269,12 +270,14 @@ class ResNet50:
             B.convbn_aux_eltwise(B.OP_RELU_BWD, ga, a)
             gin = bl[name + ".a"].backward(ga, ws)
             del ga
-            if has_ds:
-                gds = bl[name + ".ds"].backward(g, ws)
-                B.convbn_aux_eltwise(B.OP_ADD, gin, gds)
-                del gds
+            # the two branches meet at the unit's input, which is the output of the previous unit's ReLU (of the
+            # max-pool for the first unit): sum and ReLU backward in one pass
+            other = bl[name + ".ds"].backward(g, ws) if has_ds else g
+            if i + 1 < len(order):
+                B.convbn_aux_add_relu_bwd(gin, other, order[i + 1][4])
             else:
-                B.convbn_aux_eltwise(B.OP_ADD, gin, g)
+                B.convbn_aux_eltwise(B.OP_ADD, gin, other)
+            del other
             if self.units is not None and self.units[name]["back"] is not None:
                 B.convbn_fold_back_group(*self.units[name]["back"])   # dW, dgamma, dbeta of the unit's blocks
             g = gin

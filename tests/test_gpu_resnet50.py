@@ -122,6 +122,10 @@ def test_glue_kernels(dtype, shape):
     assert np.array_equal(B.act_from_device(t).numpy(), s)
     t = da.clone(); B.convbn_aux_eltwise(B.OP_ADD_RELU, t, db_)
     assert np.array_equal(B.act_from_device(t).numpy(), np.maximum(s, 0))
+    # add followed by relu backward in one pass: the rounded sum where the third operand is positive
+    c3 = torch.randn(n, c, h, w, generator=g).to(tdt).float()
+    t = da.clone(); B.convbn_aux_add_relu_bwd(t, db_, B.act_to_device(c3, tdt))
+    assert np.array_equal(B.act_from_device(t).numpy(), s * (c3.double().numpy() > 0))
     # max-pool
     ho, wo = (h - 1) // 2 + 1, (w - 1) // 2 + 1
     y = torch.empty((n, ho, wo, c), dtype=tdt, device="cuda")
