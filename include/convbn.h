@@ -76,7 +76,20 @@ typedef struct {
   float eps;                  /* BatchNorm epsilon, inside the square root          */
   int32_t dtype;              /* convbn_dtype of x, W, z, y, dz, dx, dW, w_folded   */
   int32_t layout;             /* convbn_layout                                      */
+  int32_t act;                /* CONVBN_ACT_* bits, 0 = none (see below)            */
 } convbn_desc;
+
+/* Activations around a block.  What follows a block does not change the block's computation (Sec. 3.1); these
+ * bits only let the convolution kernels apply a neighbouring ReLU while the values are still in registers,
+ * instead of a separate pass over the tensor.  Honoured by convbn_tune_fwd / _bwd, convbn_eval_fwd / _bwd,
+ * convbn_tune_fwd_static, convbn_tune_fwd_scale_epilogue and convbn_conv_fprop; the transposed, depthwise and
+ * grouped entry points reject a descriptor with act != 0.
+ *   CONVBN_ACT_RELU_OUT  the forward calls return max(z, 0) in z.  Backward is unchanged: dz stays the gradient
+ *                        with respect to the block's own output Z, i.e. the caller (or the next block, see the
+ *                        other bit) has already applied the ReLU's backward mask.
+ *   CONVBN_ACT_RELU_IN   x is the output of a ReLU: the backward calls return dx masked with x > 0, which is the
+ *                        gradient with respect to that ReLU's input. */
+enum { CONVBN_ACT_RELU_OUT = 1, CONVBN_ACT_RELU_IN = 2 };
 
 /* Output spatial size for a descriptor (0 on a NULL / invalid descriptor). */
 int32_t convbn_hout(const convbn_desc *desc);
@@ -360,6 +373,11 @@ convbn_status convbn_conv_fprop(const convbn_desc *desc, const void *x, const vo
 /* Input gradient  dx = w_rot (*) dz  (Sec. 3.2.1).  w_t is [Cin][kH][kW][Cout]. */
 convbn_status convbn_conv_dgrad(const convbn_desc *desc, const void *dz, const void *w_t,
                                 void *dx, void *ws, size_t ws_bytes, void *stream);
+/* The same with the backward mask of a ReLU in front of the block (CONVBN_ACT_RELU_IN; desc->act itself is not
+ * looked at here): dx = x > 0 ? (w_rot (*) dz) : 0, x being the block's input, laid out like dx. */
+convbn_status convbn_conv_dgrad_masked(const convbn_desc *desc, const void *dz, const void *w_t,
+                                       const void *x, void *dx, void *ws, size_t ws_bytes,
+                                       void *stream);
 
 /* Weight gradient  dw = dz (.) x  and  r_c = sum_{n,h,w} dz  (Sec. 3.2.1; App. B), left as
  * fp32 partial sums over slices of the output pixels:
@@ -384,7 +402,7 @@ convbn_status convbn_fold_back(const convbn_desc *desc, const float *dw_part, co
  * What follows a block does not change the block's computation (Sec. 3.1).  These three
  * calls exist only so that a whole backbone (ResNet-50: ReLU, residual add, 3x3/2 max-pool)
  * can be chained on the GPU for the end-to-end time / memory measurement (App. D).
- *   convbn_aux_eltwise, n elements (n % 8 == 0), a is updated in place:
+ *   convbn_aux_eltwise, n elements, a is updated in place:
  *     op 0: a = max(a, 0)            op 1: a = b > 0 ? a : 0   (ReLU backward; b = ReLU output)
  *     op 2: a = max(a + b, 0)        op 3: a = a + b
  *   convbn_aux_maxpool_fwd: 3x3 window, stride 2, padding 1 over x [N][H][W][C] -> y

@@ -21,7 +21,7 @@ PASS_FWD, PASS_BWD = 0, 1
 
 EXPORTS = ["convbn_hout", "convbn_wout", "convbn_workspace_bytes", "convbn_saved_bytes",
            "convbn_tune_fwd", "convbn_tune_bwd", "convbn_eval_fwd", "convbn_eval_bwd",
-           "convbn_last_error", "convbn_fold", "convbn_conv_fprop", "convbn_conv_dgrad",
+           "convbn_last_error", "convbn_fold", "convbn_conv_fprop", "convbn_conv_dgrad", "convbn_conv_dgrad_masked",
            "convbn_wgrad_parts", "convbn_rsum_parts", "convbn_conv_wgrad", "convbn_fold_back",
            "convbn_conv_workspace_bytes", "convbn_aux_eltwise", "convbn_aux_add_relu_bwd", "convbn_aux_maxpool_fwd",
            "convbn_aux_maxpool_bwd", "convbn_fold_group_table_bytes", "convbn_fold_group_plan",
@@ -41,7 +41,7 @@ class Desc(C.Structure):
                 ("Cout", C.c_int32), ("kH", C.c_int32), ("kW", C.c_int32),
                 ("stride_h", C.c_int32), ("stride_w", C.c_int32),
                 ("pad_h", C.c_int32), ("pad_w", C.c_int32),
-                ("eps", C.c_float), ("dtype", C.c_int32), ("layout", C.c_int32)]
+                ("eps", C.c_float), ("dtype", C.c_int32), ("layout", C.c_int32), ("act", C.c_int32)]
 
 
 class FoldItem(C.Structure):
@@ -110,6 +110,8 @@ def lib():
         L.convbn_conv_fprop.argtypes = [dp, vp, vp, fp, vp, vp, C.c_size_t, vp]
         L.convbn_conv_dgrad.restype = C.c_int
         L.convbn_conv_dgrad.argtypes = [dp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.convbn_conv_dgrad_masked.restype = C.c_int
+        L.convbn_conv_dgrad_masked.argtypes = [dp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.convbn_conv_workspace_bytes.restype = C.c_size_t
         L.convbn_conv_workspace_bytes.argtypes = [dp, C.c_int]
         L.convbn_wgrad_parts.restype = C.c_int32
@@ -176,10 +178,13 @@ def lib():
     return _lib
 
 
+ACT_RELU_OUT, ACT_RELU_IN = 1, 2
+
+
 def make_desc(N, Cin, Hin, Win, Cout, kH, kW, stride=1, pad=0, eps=1e-5, dtype=BF16,
-              layout=LAYOUT_NHWC, stride_w=None, pad_w=None) -> Desc:
+              layout=LAYOUT_NHWC, stride_w=None, pad_w=None, act=0) -> Desc:
     return Desc(N, Cin, Hin, Win, Cout, kH, kW, stride, stride if stride_w is None else stride_w,
-                pad, pad if pad_w is None else pad_w, eps, dtype, layout)
+                pad, pad if pad_w is None else pad_w, eps, dtype, layout, act)
 
 
 def desc_from_shape(s, eps=1e-5) -> Desc:
@@ -382,10 +387,14 @@ def convbn_conv_fprop(desc, x, w, bias, z, ws=None, stream=None, check=True):
     return st
 
 
-def convbn_conv_dgrad(desc, dz, w_t, dx, ws=None, stream=None, check=True):
+def convbn_conv_dgrad(desc, dz, w_t, dx, ws=None, stream=None, check=True, x_mask=None):
     p, n = _ws(ws)
-    st = lib().convbn_conv_dgrad(C.byref(desc), _ptr(dz), _ptr(w_t), _ptr(dx), p, n,
-                                 _stream(stream))
+    if x_mask is not None:
+        st = lib().convbn_conv_dgrad_masked(C.byref(desc), _ptr(dz), _ptr(w_t), _ptr(x_mask), _ptr(dx), p, n,
+                                            _stream(stream))
+    else:
+        st = lib().convbn_conv_dgrad(C.byref(desc), _ptr(dz), _ptr(w_t), _ptr(dx), p, n,
+                                     _stream(stream))
     if check:
         _check(st)
     return st

@@ -44,6 +44,9 @@ convbn_status make_geom(const convbn_desc* d, Geom* g) {
   if (d->layout != CONVBN_LAYOUT_NHWC)
     return fail(CONVBN_ERR_UNSUPPORTED, "layout %d: only CONVBN_LAYOUT_NHWC is supported", d->layout);
   if (!(d->eps >= 0.f)) return fail(CONVBN_ERR_SHAPE, "eps must be >= 0");
+  if (d->act < 0 || d->act > (CONVBN_ACT_RELU_OUT | CONVBN_ACT_RELU_IN))
+    return fail(CONVBN_ERR_UNSUPPORTED, "act %d: unknown activation bits", d->act);
+  g->act = d->act; g->post_relu = 0; g->post_mask = nullptr;
   g->N = d->N; g->Cin = d->Cin; g->Hin = d->Hin; g->Win = d->Win;
   g->Cout = d->Cout; g->kH = d->kH; g->kW = d->kW;
   g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
@@ -248,23 +251,46 @@ size_t wgrad_scratch_bytes(const Geom& g, int dtype) {
          align_up((size_t)wgrad_way(g, dtype).nsplit * q.Cout * q.K * 4, 256);
 }
 
+// The post-operation of g (ReLU, mask) as a pass of its own over `out` (n elements): for the kernels that do not
+// apply it in their epilogue.
+hipError_t post_op_pass(const Geom& g, int dtype, void* out, size_t n, hipStream_t st) {
+  if (g.post_relu) {
+    hipError_t e = launch_eltwise(0 /* max(a, 0) */, dtype, out, nullptr, nullptr, n, st);
+    if (e != hipSuccess) return e;
+  }
+  if (g.post_mask) return launch_eltwise(1 /* b > 0 ? a : 0 */, dtype, out, g.post_mask, nullptr, n, st);
+  return hipSuccess;
+}
+bool has_post_op(const Geom& g) { return g.post_relu || g.post_mask; }
+
+// FUSED_*: the kernel applies g's post-operation itself.
+constexpr bool FUSED_PW = false, FUSED_RW = false, FUSED_ST = false, FUSED_TILE = false;
+
 hipError_t fprop_any(const Geom& g, int dtype, const void* x, const void* w_krsc, const float* bias,
                      void* z, float* scratch, hipStream_t st) {
-  if (pw_fprop_supported(g, dtype)) return launch_fprop_pw(g, x, w_krsc, bias, z, st);
-  if (rw_fprop_supported(g, dtype)) return launch_fprop_rw(g, x, w_krsc, bias, z, st);
-  if (st_fprop_supported(g, dtype)) return launch_fprop_st(g, x, w_krsc, bias, z, st);
-  if (tile_fprop_supported(g, dtype)) return launch_fprop_tile(g, x, w_krsc, bias, z, scratch, st);
-  return igemm_supported(g, dtype) ? launch_fprop_igemm(g, x, w_krsc, bias, z, st)
-                                   : launch_fprop_direct(g, dtype, x, w_krsc, bias, z, st);
+  hipError_t e;
+  bool fused = false;
+  if (pw_fprop_supported(g, dtype)) { e = launch_fprop_pw(g, x, w_krsc, bias, z, st); fused = FUSED_PW; }
+  else if (rw_fprop_supported(g, dtype)) { e = launch_fprop_rw(g, x, w_krsc, bias, z, st); fused = FUSED_RW; }
+  else if (st_fprop_supported(g, dtype)) { e = launch_fprop_st(g, x, w_krsc, bias, z, st); fused = FUSED_ST; }
+  else if (tile_fprop_supported(g, dtype)) { e = launch_fprop_tile(g, x, w_krsc, bias, z, scratch, st); fused = FUSED_TILE; }
+  else e = igemm_supported(g, dtype) ? launch_fprop_igemm(g, x, w_krsc, bias, z, st)
+                                     : launch_fprop_direct(g, dtype, x, w_krsc, bias, z, st);
+  if (e != hipSuccess || fused || !has_post_op(g)) return e;
+  return post_op_pass(g, dtype, z, (size_t)g.M * g.Cout, st);
 }
 hipError_t dgrad_any(const Geom& g, int dtype, const void* dz, const void* w_crsk, const float* bias, void* dx,
                      float* scratch, hipStream_t st) {
-  if (pw_dgrad_supported(g, dtype)) return launch_dgrad_pw(g, dz, w_crsk, bias, dx, st);
-  if (rw_dgrad_supported(g, dtype)) return launch_dgrad_rw(g, dz, w_crsk, bias, dx, st);
-  if (st_dgrad_supported(g, dtype)) return launch_dgrad_st(g, dz, w_crsk, bias, dx, st);
-  if (tile_dgrad_supported(g, dtype)) return launch_dgrad_tile(g, dz, w_crsk, bias, dx, scratch, st);
-  return igemm_supported(g, dtype) ? launch_dgrad_igemm(g, dz, w_crsk, bias, dx, st)
-                                   : launch_dgrad_direct(g, dtype, dz, w_crsk, bias, dx, st);
+  hipError_t e;
+  bool fused = false;
+  if (pw_dgrad_supported(g, dtype)) { e = launch_dgrad_pw(g, dz, w_crsk, bias, dx, st); fused = FUSED_PW; }
+  else if (rw_dgrad_supported(g, dtype)) { e = launch_dgrad_rw(g, dz, w_crsk, bias, dx, st); fused = FUSED_RW; }
+  else if (st_dgrad_supported(g, dtype)) { e = launch_dgrad_st(g, dz, w_crsk, bias, dx, st); fused = FUSED_ST; }
+  else if (tile_dgrad_supported(g, dtype)) { e = launch_dgrad_tile(g, dz, w_crsk, bias, dx, scratch, st); fused = FUSED_TILE; }
+  else e = igemm_supported(g, dtype) ? launch_dgrad_igemm(g, dz, w_crsk, bias, dx, st)
+                                     : launch_dgrad_direct(g, dtype, dz, w_crsk, bias, dx, st);
+  if (e != hipSuccess || fused || !has_post_op(g)) return e;
+  return post_op_pass(g, dtype, dx, (size_t)g.Min * g.Cin, st);
 }
 
 #define TRY(expr)                       \
@@ -280,9 +306,13 @@ hipError_t run_fprop(const Geom& g, int dtype, const void* x, const void* w_krsc
     char* sp = reinterpret_cast<char*>(scratch);
     void* wpad = sp;
     sp += align_up(stem_packed_weight_bytes(g), 256);
-    if (stem_input_copy_bytes(g) == 0) return launch_fprop_stem(g, x, w_krsc, wpad, bias, z, st);
-    TRY(launch_repitch(2, (size_t)g.Min, g.Cin, 4, x, sp, st));   // ... and a 4-channel copy of the input
-    return launch_fprop_stem(g, sp, w_krsc, wpad, bias, z, st);
+    if (stem_input_copy_bytes(g) == 0) {
+      TRY(launch_fprop_stem(g, x, w_krsc, wpad, bias, z, st));
+    } else {
+      TRY(launch_repitch(2, (size_t)g.Min, g.Cin, 4, x, sp, st));   // ... and a 4-channel copy of the input
+      TRY(launch_fprop_stem(g, sp, w_krsc, wpad, bias, z, st));
+    }
+    return post_op_pass(g, dtype, z, (size_t)g.M * g.Cout, st);
   }
   const Geom q = padded_geom(g);
   char* s = reinterpret_cast<char*>(scratch);
@@ -295,9 +325,12 @@ hipError_t run_fprop(const Geom& g, int dtype, const void* x, const void* w_krsc
 hipError_t run_dgrad(const Geom& g, int dtype, const void* dz, const void* w_crsk, void* dx,
                      float* scratch, hipStream_t st) {
   if (!needs_cin_pad(g, dtype)) return dgrad_any(g, dtype, dz, w_crsk, nullptr, dx, scratch, st);
-  if (stem_dgrad_supported(g, dtype))   // a first layer: its own kernel; the scratch holds its packed weight
-    return launch_dgrad_stem(g, dz, w_crsk, scratch, dx, st);
-  const Geom q = padded_geom(g);
+  if (stem_dgrad_supported(g, dtype)) {   // a first layer: its own kernel; the scratch holds its packed weight
+    TRY(launch_dgrad_stem(g, dz, w_crsk, scratch, dx, st));
+    return post_op_pass(g, dtype, dx, (size_t)g.Min * g.Cin, st);
+  }
+  Geom q = padded_geom(g);
+  q.post_relu = 0; q.post_mask = nullptr;   // the mask is laid out like dx, not like its padded copy: applied at the end
   char* s = reinterpret_cast<char*>(scratch);
   void* wp = s; s += align_up((size_t)q.Cout * q.K * 2, 256);
   void* dxp = s; s += align_up((size_t)q.Min * q.Cin * 2, 256);
@@ -305,7 +338,8 @@ hipError_t run_dgrad(const Geom& g, int dtype, const void* dz, const void* w_crs
   const size_t row = (size_t)g.kH * g.kW * g.Cout;
   TRY(launch_repitch(2, 1, (size_t)g.Cin * row, (size_t)q.Cin * row, w_crsk, wp, st));
   TRY(dgrad_any(q, dtype, dz, wp, nullptr, dxp, reinterpret_cast<float*>(s), st));
-  return launch_repitch(2, (size_t)g.Min, q.Cin, g.Cin, dxp, dx, st);
+  TRY(launch_repitch(2, (size_t)g.Min, q.Cin, g.Cin, dxp, dx, st));
+  return post_op_pass(g, dtype, dx, (size_t)g.Min * g.Cin, st);
 }
 // dw' partials and, when r_part != nullptr, the partial per-channel sums of dz.
 hipError_t wgrad_any(const Geom& g, int dtype, const void* x, const void* dz, float* part, float* r_part,
@@ -594,14 +628,28 @@ convbn_status convbn_tune_fwd(const convbn_desc* desc, const void* x, const void
   if (s != CONVBN_OK) return s;
   const TuneFwdWs w = carve_tune_fwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
+  g.post_relu = g.act & CONVBN_ACT_RELU_OUT;
+  const size_t nz = (size_t)g.M * g.Cout;
   if (!needs_cin_pad(g, dt) && !pw_fprop_supported(g, dt) && (g.kH > 1 || g.kW > 1)) {
     // The scale is per output channel, so Z = s (w (*) X) + b' (Sec. 3.3): the convolution reads the unfolded
     // weight and applies s and b' in its epilogue, and -- where w' is kept for backward -- its workgroups each
     // write a slice of w' on the side.  The forward pass is one launch; no w' is materialised for it.
     const BnEpilogue bn{gamma, beta, mean, var, b, g.eps, w_folded, g.kH * g.kW, g.Cin, g.Cout};
-    if (rw_fprop_supported(g, dt)) { LAUNCH(launch_fprop_rw(g, x, W, nullptr, z, st, &bn)); return CONVBN_OK; }
-    if (st_fprop_supported(g, dt)) { LAUNCH(launch_fprop_st(g, x, W, nullptr, z, st, &bn)); return CONVBN_OK; }
-    if (tile_fprop_scaled_supported(g, dt)) { LAUNCH(launch_fprop_tile(g, x, W, nullptr, z, nullptr, st, &bn)); return CONVBN_OK; }
+    if (rw_fprop_supported(g, dt)) {
+      LAUNCH(launch_fprop_rw(g, x, W, nullptr, z, st, &bn));
+      if (!FUSED_RW) LAUNCH(post_op_pass(g, dt, z, nz, st));
+      return CONVBN_OK;
+    }
+    if (st_fprop_supported(g, dt)) {
+      LAUNCH(launch_fprop_st(g, x, W, nullptr, z, st, &bn));
+      if (!FUSED_ST) LAUNCH(post_op_pass(g, dt, z, nz, st));
+      return CONVBN_OK;
+    }
+    if (tile_fprop_scaled_supported(g, dt)) {
+      LAUNCH(launch_fprop_tile(g, x, W, nullptr, z, nullptr, st, &bn));
+      if (!FUSED_TILE) LAUNCH(post_op_pass(g, dt, z, nz, st));
+      return CONVBN_OK;
+    }
   }
   // w' = s w (both orders), b' = (b - mu) s + beta; then Z = w' (*) X + b'
   LAUNCH(launch_fold(g, dt, W, b, gamma, beta, mean, var, 0, w.w_krsc, w_folded, w.bfold, st));
@@ -632,6 +680,7 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
   if (s != CONVBN_OK) return s;
   const TuneBwdWs w = carve_tune_bwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (g.act & CONVBN_ACT_RELU_IN) g.post_mask = x;   // dx comes out masked with x > 0
   if (params && convbn_tune_bwd_is_fused(desc)) {
     // deep layers: dw', r and the fold-back in one launch (the fp32 dw' never reaches memory); the space of the
     // fp32 copy holds the few partial sums the workgroups exchange.  Where nothing was kept, the same launch leaves
@@ -650,6 +699,7 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
     if (params && !needs_cin_pad(g, dt) && wgrad_way(g, dt).sq && wgrad_dgrad_pair_supported(g, dt)) {
       // shallow layers: the two gradient passes are independent and share one launch (see wgrad_sq.hip)
       LAUNCH(launch_wgrad_dgrad_pair(g, x, dz, wt, dx, w.dwf_part, w.r_part, st));
+      if (!FUSED_RW) LAUNCH(post_op_pass(g, dt, dx, (size_t)g.Min * g.Cin, st));
       LAUNCH(launch_fold_back(g, dt, w.dwf_part, w.nsplit, w.r_part, w.nrpart, W, b, gamma, mean, var, 0,
                               dW, db, dgamma, dbeta, st));
       return CONVBN_OK;
@@ -680,6 +730,8 @@ convbn_status convbn_eval_fwd(const convbn_desc* desc, const void* x, const void
   hipStream_t st = static_cast<hipStream_t>(stream);
   LAUNCH(run_fprop(g, dt, x, W, b, y_saved, w.conv_scratch, st));         // Y = w (*) X + b
   LAUNCH(launch_bn_affine_fwd(g, dt, y_saved, gamma, beta, mean, var, z, st));  // Z from Y
+  g.post_relu = g.act & CONVBN_ACT_RELU_OUT;
+  LAUNCH(post_op_pass(g, dt, z, (size_t)g.M * g.Cout, st));
   return CONVBN_OK;
 }
 
@@ -706,6 +758,7 @@ convbn_status convbn_eval_bwd(const convbn_desc* desc, const void* x, const void
   if (s != CONVBN_OK) return s;
   const EvalBwdWs w = carve_eval_bwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (g.act & CONVBN_ACT_RELU_IN) g.post_mask = x;   // dx comes out masked with x > 0
   // dY = s dZ, partial per-channel sums of dZ and dZ (Y-mu)/sqrt(var+eps)
   LAUNCH(launch_bn_bwd(g, dt, dz, y_saved, gamma, mean, var, w.dy, w.bn_part, st));
   if (params) LAUNCH(launch_bn_bwd_finalize(g, w.bn_part, w.nparts, gamma, var, dgamma, dbeta, db, st));
@@ -750,6 +803,7 @@ size_t convbn_tconv_saved_bytes(const convbn_desc* desc, int mode, int refold) {
 convbn_status convbn_tconv_tune_fwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
                                     const float* gamma, const float* beta, const float* mean, const float* var,
                                     void* z, void* w_folded, void* ws, size_t ws_bytes, void* stream) {
+  if (desc && desc->act) return fail(CONVBN_ERR_UNSUPPORTED, "this entry point takes no activation bits (act must be 0)");
   Geom g;
   convbn_status s = make_tgeom(desc, &g);
   if (s != CONVBN_OK) return s;
@@ -775,6 +829,7 @@ convbn_status convbn_tconv_tune_bwd(const convbn_desc* desc, const void* x, cons
                                     const float* gamma, const float* mean, const float* var, const void* w_folded,
                                     const void* dz, void* dx, void* dW, float* db, float* dgamma, float* dbeta,
                                     void* ws, size_t ws_bytes, void* stream) {
+  if (desc && desc->act) return fail(CONVBN_ERR_UNSUPPORTED, "this entry point takes no activation bits (act must be 0)");
   Geom g;
   convbn_status s = make_tgeom(desc, &g);
   if (s != CONVBN_OK) return s;
@@ -816,6 +871,7 @@ convbn_status convbn_tconv_tune_bwd(const convbn_desc* desc, const void* x, cons
 convbn_status convbn_tconv_eval_fwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
                                     const float* gamma, const float* beta, const float* mean, const float* var,
                                     void* z, void* y_saved, void* ws, size_t ws_bytes, void* stream) {
+  if (desc && desc->act) return fail(CONVBN_ERR_UNSUPPORTED, "this entry point takes no activation bits (act must be 0)");
   Geom g;
   convbn_status s = make_tgeom(desc, &g);
   if (s != CONVBN_OK) return s;
@@ -842,6 +898,7 @@ convbn_status convbn_tconv_eval_bwd(const convbn_desc* desc, const void* x, cons
                                     const float* gamma, const float* mean, const float* var, const void* y_saved,
                                     const void* dz, void* dx, void* dW, float* db, float* dgamma, float* dbeta,
                                     void* ws, size_t ws_bytes, void* stream) {
+  if (desc && desc->act) return fail(CONVBN_ERR_UNSUPPORTED, "this entry point takes no activation bits (act must be 0)");
   Geom g;
   convbn_status s = make_tgeom(desc, &g);
   if (s != CONVBN_OK) return s;
@@ -890,6 +947,7 @@ size_t convbn_dw_saved_bytes(const convbn_desc* desc, int mode, int refold) {
 convbn_status convbn_dw_tune_fwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
                                  const float* gamma, const float* beta, const float* mean, const float* var,
                                  void* z, void* w_folded, void* ws, size_t ws_bytes, void* stream) {
+  if (desc && desc->act) return fail(CONVBN_ERR_UNSUPPORTED, "this entry point takes no activation bits (act must be 0)");
   Geom g;
   convbn_status s = make_dwgeom(desc, &g);
   if (s != CONVBN_OK) return s;
@@ -911,6 +969,7 @@ convbn_status convbn_dw_tune_bwd(const convbn_desc* desc, const void* x, const v
                                  const float* gamma, const float* mean, const float* var, const void* w_folded,
                                  const void* dz, void* dx, void* dW, float* db, float* dgamma, float* dbeta,
                                  void* ws, size_t ws_bytes, void* stream) {
+  if (desc && desc->act) return fail(CONVBN_ERR_UNSUPPORTED, "this entry point takes no activation bits (act must be 0)");
   Geom g;
   convbn_status s = make_dwgeom(desc, &g);
   if (s != CONVBN_OK) return s;
@@ -948,6 +1007,7 @@ convbn_status convbn_dw_tune_bwd(const convbn_desc* desc, const void* x, const v
 convbn_status convbn_dw_eval_fwd(const convbn_desc* desc, const void* x, const void* W, const float* b,
                                  const float* gamma, const float* beta, const float* mean, const float* var,
                                  void* z, void* y_saved, void* ws, size_t ws_bytes, void* stream) {
+  if (desc && desc->act) return fail(CONVBN_ERR_UNSUPPORTED, "this entry point takes no activation bits (act must be 0)");
   Geom g;
   convbn_status s = make_dwgeom(desc, &g);
   if (s != CONVBN_OK) return s;
@@ -969,6 +1029,7 @@ convbn_status convbn_dw_eval_bwd(const convbn_desc* desc, const void* x, const v
                                  const float* gamma, const float* mean, const float* var, const void* y_saved,
                                  const void* dz, void* dx, void* dW, float* db, float* dgamma, float* dbeta,
                                  void* ws, size_t ws_bytes, void* stream) {
+  if (desc && desc->act) return fail(CONVBN_ERR_UNSUPPORTED, "this entry point takes no activation bits (act must be 0)");
   Geom g;
   convbn_status s = make_dwgeom(desc, &g);
   if (s != CONVBN_OK) return s;
@@ -1024,6 +1085,7 @@ convbn_status convbn_grouped_tune_fwd(const convbn_desc* desc, int groups, const
                                       const float* b, const float* gamma, const float* beta, const float* mean,
                                       const float* var, void* z, void* w_folded, void* ws, size_t ws_bytes,
                                       void* stream) {
+  if (desc && desc->act) return fail(CONVBN_ERR_UNSUPPORTED, "this entry point takes no activation bits (act must be 0)");
   Geom g, gf;
   convbn_status s = make_ggeom(desc, groups, &g, &gf);
   if (s != CONVBN_OK) return s;
@@ -1047,6 +1109,7 @@ convbn_status convbn_grouped_tune_bwd(const convbn_desc* desc, int groups, const
                                       const float* b, const float* gamma, const float* mean, const float* var,
                                       const void* w_folded, const void* dz, void* dx, void* dW, float* db,
                                       float* dgamma, float* dbeta, void* ws, size_t ws_bytes, void* stream) {
+  if (desc && desc->act) return fail(CONVBN_ERR_UNSUPPORTED, "this entry point takes no activation bits (act must be 0)");
   Geom g, gf;
   convbn_status s = make_ggeom(desc, groups, &g, &gf);
   if (s != CONVBN_OK) return s;
@@ -1089,6 +1152,7 @@ convbn_status convbn_grouped_eval_fwd(const convbn_desc* desc, int groups, const
                                       const float* b, const float* gamma, const float* beta, const float* mean,
                                       const float* var, void* z, void* y_saved, void* ws, size_t ws_bytes,
                                       void* stream) {
+  if (desc && desc->act) return fail(CONVBN_ERR_UNSUPPORTED, "this entry point takes no activation bits (act must be 0)");
   Geom g, gf;
   convbn_status s = make_ggeom(desc, groups, &g, &gf);
   if (s != CONVBN_OK) return s;
@@ -1109,6 +1173,7 @@ convbn_status convbn_grouped_eval_bwd(const convbn_desc* desc, int groups, const
                                       const float* b, const float* gamma, const float* mean, const float* var,
                                       const void* y_saved, const void* dz, void* dx, void* dW, float* db,
                                       float* dgamma, float* dbeta, void* ws, size_t ws_bytes, void* stream) {
+  if (desc && desc->act) return fail(CONVBN_ERR_UNSUPPORTED, "this entry point takes no activation bits (act must be 0)");
   Geom g, gf;
   convbn_status s = make_ggeom(desc, groups, &g, &gf);
   if (s != CONVBN_OK) return s;
@@ -1155,18 +1220,27 @@ convbn_status convbn_tune_fwd_scale_epilogue(const convbn_desc* desc, const void
   const int dt = desc->dtype;
   const BnEpilogue bn{gamma, beta, mean, var, b, g.eps, nullptr, g.kH * g.kW, g.Cin, g.Cout};
   hipStream_t st = static_cast<hipStream_t>(stream);
+  g.post_relu = g.act & CONVBN_ACT_RELU_OUT;
+  const size_t nz = (size_t)g.M * g.Cout;
   // Z = s (w (*) X) + b': the unfolded weight goes straight into the convolution, one launch in all
   if (!needs_cin_pad(g, dt) && !pw_fprop_supported(g, dt) && rw_fprop_supported(g, dt)) {
     LAUNCH(launch_fprop_rw(g, x, W, nullptr, z, st, &bn));
+    if (!FUSED_RW) LAUNCH(post_op_pass(g, dt, z, nz, st));
     return CONVBN_OK;
   }
   if (!needs_cin_pad(g, dt) && !pw_fprop_supported(g, dt) && st_fprop_supported(g, dt)) {
     LAUNCH(launch_fprop_st(g, x, W, nullptr, z, st, &bn));
+    if (!FUSED_ST) LAUNCH(post_op_pass(g, dt, z, nz, st));
     return CONVBN_OK;
   }
-  if (pw_fprop_scaled_supported(g, dt)) { LAUNCH(launch_fprop_pw(g, x, W, nullptr, z, st, &bn)); return CONVBN_OK; }
+  if (pw_fprop_scaled_supported(g, dt)) {
+    LAUNCH(launch_fprop_pw(g, x, W, nullptr, z, st, &bn));
+    if (!FUSED_PW) LAUNCH(post_op_pass(g, dt, z, nz, st));
+    return CONVBN_OK;
+  }
   if (!pw_fprop_supported(g, dt) && tile_fprop_scaled_supported(g, dt)) {
     LAUNCH(launch_fprop_tile(g, x, W, nullptr, z, nullptr, st, &bn));
+    if (!FUSED_TILE) LAUNCH(post_op_pass(g, dt, z, nz, st));
     return CONVBN_OK;
   }
   return fail(CONVBN_ERR_UNSUPPORTED, "the scale-in-the-epilogue forward is built for a few plans of the LDS-tile "
@@ -1294,6 +1368,7 @@ convbn_status convbn_conv_fprop(const convbn_desc* desc, const void* x, const vo
   REQUIRE_PTR(x); REQUIRE_PTR(w); REQUIRE_PTR(z); OPTIONAL_PTR(bias);
   s = check_ws(fprop_scratch_bytes(g, desc->dtype), ws, ws_bytes);
   if (s != CONVBN_OK) return s;
+  g.post_relu = g.act & CONVBN_ACT_RELU_OUT;
   LAUNCH(run_fprop(g, desc->dtype, x, w, bias, z, (float*)ws, static_cast<hipStream_t>(stream)));
   return CONVBN_OK;
 }
@@ -1306,6 +1381,19 @@ convbn_status convbn_conv_dgrad(const convbn_desc* desc, const void* dz, const v
   REQUIRE_PTR(dz); REQUIRE_PTR(w_t); REQUIRE_PTR(dx);
   s = check_ws(dgrad_scratch_bytes(g, desc->dtype), ws, ws_bytes);
   if (s != CONVBN_OK) return s;
+  LAUNCH(run_dgrad(g, desc->dtype, dz, w_t, dx, (float*)ws, static_cast<hipStream_t>(stream)));
+  return CONVBN_OK;
+}
+
+convbn_status convbn_conv_dgrad_masked(const convbn_desc* desc, const void* dz, const void* w_t, const void* x,
+                                       void* dx, void* ws, size_t ws_bytes, void* stream) {
+  Geom g;
+  convbn_status s = make_geom(desc, &g);
+  if (s != CONVBN_OK) return s;
+  REQUIRE_PTR(dz); REQUIRE_PTR(w_t); REQUIRE_PTR(x); REQUIRE_PTR(dx);
+  s = check_ws(dgrad_scratch_bytes(g, desc->dtype), ws, ws_bytes);
+  if (s != CONVBN_OK) return s;
+  g.post_mask = x;
   LAUNCH(run_dgrad(g, desc->dtype, dz, w_t, dx, (float*)ws, static_cast<hipStream_t>(stream)));
   return CONVBN_OK;
 }
@@ -1357,7 +1445,6 @@ convbn_status convbn_aux_eltwise(int op, int dtype, void* a, const void* b, size
   if (dtype != CONVBN_F32 && dtype != CONVBN_BF16) return fail(CONVBN_ERR_UNSUPPORTED, "dtype %d", dtype);
   REQUIRE_PTR(a);
   if (op != 0) REQUIRE_PTR(b);
-  if (n % 8 != 0) return fail(CONVBN_ERR_SHAPE, "element count must be a multiple of 8");
   LAUNCH(launch_eltwise(op, dtype, a, b, nullptr, n, static_cast<hipStream_t>(stream)));
   return CONVBN_OK;
 }
@@ -1365,7 +1452,6 @@ convbn_status convbn_aux_eltwise(int op, int dtype, void* a, const void* b, size
 convbn_status convbn_aux_add_relu_bwd(int dtype, void* a, const void* b, const void* y, size_t n, void* stream) {
   if (dtype != CONVBN_F32 && dtype != CONVBN_BF16) return fail(CONVBN_ERR_UNSUPPORTED, "dtype %d", dtype);
   REQUIRE_PTR(a); REQUIRE_PTR(b); REQUIRE_PTR(y);
-  if (n % 8 != 0) return fail(CONVBN_ERR_SHAPE, "element count must be a multiple of 8");
   LAUNCH(launch_eltwise(4, dtype, a, b, y, n, static_cast<hipStream_t>(stream)));
   return CONVBN_OK;
 }

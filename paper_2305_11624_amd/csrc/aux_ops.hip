@@ -59,6 +59,17 @@ __global__ __launch_bounds__(256) void eltwise_kernel(T* __restrict__ a, const T
     }
     stv<T>(a + i * V, x);
   }
+  // the elements past the last whole vector (callers inside the library pass any n)
+  for (size_t i = nv * V + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    float x = to_f32(a[i]);
+    const float y = OP != OP_RELU ? to_f32(b[i]) : 0.f;
+    if (OP == OP_RELU) x = fmaxf(x, 0.f);
+    if (OP == OP_RELU_BWD) x = y > 0.f ? x : 0.f;
+    if (OP == OP_ADD_RELU) x = fmaxf(to_f32(from_f32<T>(x + y)), 0.f);
+    if (OP == OP_ADD) x = x + y;
+    if (OP == OP_ADD_RELU_BWD) x = to_f32(c[i]) > 0.f ? x + y : 0.f;
+    a[i] = from_f32<T>(x);
+  }
 }
 
 // 3x3 window, stride 2, padding 1 max-pool over [N][H][W][C]; idx keeps the winning window

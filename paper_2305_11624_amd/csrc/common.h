@@ -46,7 +46,35 @@ struct Geom {
   int Min;    // N*Hin*Win     (input pixels)
   int K;      // kH*kW*Cin     (reduction length of the forward conv)
   float eps;
+  int act;    // the descriptor's CONVBN_ACT_* bits
+  // What the convolution launched with this Geom does to its output on the way out (set per call by the host side,
+  // not part of the problem): ReLU, and / or zero where `post_mask` (a tensor laid out like the output) is <= 0.
+  int post_relu;
+  const void* post_mask;
 };
+
+// The same on 8 packed bf16 values about to be stored at element offset o of the output.
+__device__ __forceinline__ uint4 post_op8(uint4 v, int relu, const bf16_t* mask, size_t o) {
+  unsigned w[4] = {v.x, v.y, v.z, v.w};
+  if (relu) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const unsigned neg = ((w[i] >> 15) & 0x00010001u) * 0xffffu;   // 0xffff in every half whose sign bit is set
+      w[i] &= ~neg;
+    }
+  }
+  if (mask) {
+    const uint4 m4 = *reinterpret_cast<const uint4*>(mask + o);
+    const unsigned m[4] = {m4.x, m4.y, m4.z, m4.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const unsigned lo = __uint_as_float(m[i] << 16) > 0.f ? 0x0000ffffu : 0u;
+      const unsigned hi = __uint_as_float(m[i] & 0xffff0000u) > 0.f ? 0xffff0000u : 0u;
+      w[i] &= lo | hi;
+    }
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
 
 // Per-channel epilogue of a forward convolution that is given the UNFOLDED weight: Z = s (w (*) X) + b' with
 // s = gamma / sqrt(var + eps) and b' = (b - mu) s + beta worked out by the kernel itself -- the same forward

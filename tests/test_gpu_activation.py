@@ -1,0 +1,92 @@
+"""GPU parity of the activation bits of the descriptor: a ReLU behind the block (forward output) and the backward mask
+of a ReLU in front of it (input gradient), for every convolution kernel family the planner picks -- the ones that apply
+them in their epilogue and the ones that get a pass of their own.  Reference: the oracle's block, with max(., 0) on its
+Z and its dX zeroed where the block's input is not positive; and, bit for bit, the same calls without the bits followed
+by the stand-alone element-wise kernels."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2305_11624_amd import binding as B
+from paper_2305_11624_amd import synth
+from paper_2305_11624_amd.synth import BlockShape
+
+from helpers import compare, oracle_block
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [
+    BlockShape("act_pw_1x1", 6, 256, 20, 20, 64, 1, 1, 0, "bf16", 301),          # pointwise kernel
+    BlockShape("act_pw_1x1_wide", 5, 64, 28, 28, 256, 1, 1, 0, "bf16", 302),
+    BlockShape("act_pw_strided", 4, 256, 28, 28, 512, 1, 2, 0, "bf16", 303),      # a downsampling shortcut
+    BlockShape("act_shallow_3x3", 9, 64, 47, 53, 64, 3, 1, 1, "bf16", 304),       # weight and window resident in LDS
+    BlockShape("act_deep_3x3", 10, 512, 7, 7, 512, 3, 1, 1, "bf16", 305),         # deep-layer kernel, fused weight gradient
+    BlockShape("act_mid_3x3", 6, 128, 28, 28, 128, 3, 1, 1, "bf16", 306),         # LDS-tile kernel
+    BlockShape("act_mid_3x3_s2", 6, 128, 28, 28, 128, 3, 2, 1, "bf16", 307),      # strided: residue classes in the input gradient
+    BlockShape("act_split_sums", 2, 256, 14, 14, 256, 3, 1, 1, "bf16", 308),      # split sums + their reduction
+    BlockShape("act_stem", 2, 3, 64, 64, 64, 7, 2, 3, "bf16", 309),               # first layer: padded channels
+    BlockShape("act_odd_bf16", 2, 24, 9, 11, 40, 3, 1, 1, "bf16", 310),           # generic kernels
+    BlockShape("act_f32", 2, 16, 12, 10, 24, 3, 1, 1, "f32", 311),
+    BlockShape("act_f32_ragged", 1, 5, 7, 9, 7, 3, 2, 1, "f32", 312),             # element counts that are not multiples of 8
+]
+BOTH = B.ACT_RELU_OUT | B.ACT_RELU_IN
+
+
+def _inputs(shape):
+    inp = synth.make_inputs(shape, bias=True)
+    inp["x"] = torch.clamp(inp["x"], min=0)   # the block's input is a ReLU's output: about half of it zero
+    return inp
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: s.name)
+@pytest.mark.parametrize("mode,keep", [("tune", True), ("tune", False), ("eval", True)],
+                         ids=["tune_keeps_w", "tune_keeps_nothing", "eval"])
+def test_activation_bits_against_oracle_and_unfused_calls(shape, mode, keep):
+    from paper_2305_11624_amd.runner import BlockRun
+    inp = _inputs(shape)
+    ref = oracle_block(inp)
+    x = inp["x"].double().numpy()
+    ref["Z"] = np.maximum(ref["Z"], 0)
+    ref["dX"] = ref["dX"] * (x > 0)
+    run = BlockRun(inp, mode=mode, keep_folded=keep, poison=True, act=BOTH)
+    run.step()
+    got = run.results()
+    compare(got, ref, shape.dtype, tag=shape.name + "/" + mode)
+
+    plain = BlockRun(inp, mode=mode, keep_folded=keep, poison=True, act=0)
+    plain.step()
+    B.convbn_aux_eltwise(B.OP_RELU, plain.z)
+    B.convbn_aux_eltwise(B.OP_RELU_BWD, plain.dx, plain.x)
+    want = plain.results()
+    for k in ("Z", "dX", "dW", "dgamma", "dbeta", "db"):
+        assert torch.equal(got[k], want[k]), k
+
+
+@pytest.mark.parametrize("shape", [SHAPES[0], SHAPES[3], SHAPES[5], SHAPES[8], SHAPES[11]], ids=lambda s: s.name)
+def test_step_entry_points_with_activation(shape):
+    """convbn_conv_fprop with the output bit and convbn_conv_dgrad_masked, against the same calls plus element-wise passes."""
+    from paper_2305_11624_amd.runner import BlockRun
+    inp = _inputs(shape)
+    r = BlockRun(inp, "tune")
+    d = r.desc
+    P = shape.Cout * shape.K
+    dev = r.x.device
+    w_fprop = torch.empty(P, dtype=r.dt, device=dev)
+    w_t = torch.empty(P, dtype=r.dt, device=dev)
+    bfold = torch.empty(shape.Cout, dtype=torch.float32, device=dev)
+    B.convbn_fold(d, r.W, r.b, r.gamma, r.beta, r.mean, r.var, w_fprop, w_t, bfold)
+    ws = torch.empty(max(16, B.convbn_conv_workspace_bytes(d, B.PASS_FWD), B.convbn_conv_workspace_bytes(d, B.PASS_BWD)),
+                     dtype=torch.uint8, device=dev)
+    z0, z1 = torch.empty_like(r.z), torch.empty_like(r.z)
+    dx0, dx1 = torch.empty_like(r.dx), torch.empty_like(r.dx)
+    B.convbn_conv_fprop(d, r.x, w_fprop, bfold, z0, ws)
+    B.convbn_aux_eltwise(B.OP_RELU, z0)
+    B.convbn_conv_dgrad(d, r.dz, w_t, dx0, ws)
+    B.convbn_aux_eltwise(B.OP_RELU_BWD, dx0, r.x)
+    d.act = B.ACT_RELU_OUT
+    B.convbn_conv_fprop(d, r.x, w_fprop, bfold, z1, ws)
+    B.convbn_conv_dgrad(d, r.dz, w_t, dx1, ws, x_mask=r.x)
+    torch.cuda.synchronize()
+    assert torch.equal(z0, z1)
+    assert torch.equal(dx0, dx1)
+    assert (z1.float() >= 0).all() and (dx1.float()[r.x.float() <= 0] == 0).all()
