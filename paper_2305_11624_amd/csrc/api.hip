@@ -264,7 +264,7 @@ hipError_t post_op_pass(const Geom& g, int dtype, void* out, size_t n, hipStream
 bool has_post_op(const Geom& g) { return g.post_relu || g.post_mask; }
 
 // FUSED_*: the kernel applies g's post-operation itself.
-constexpr bool FUSED_PW = false, FUSED_RW = false, FUSED_ST = false, FUSED_TILE = false;
+constexpr bool FUSED_PW = true, FUSED_RW = true, FUSED_ST = true, FUSED_TILE = true;
 
 hipError_t fprop_any(const Geom& g, int dtype, const void* x, const void* w_krsc, const float* bias,
                      void* z, float* scratch, hipStream_t st) {

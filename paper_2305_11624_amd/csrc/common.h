@@ -53,27 +53,34 @@ struct Geom {
   const void* post_mask;
 };
 
-// The same on 8 packed bf16 values about to be stored at element offset o of the output.
-__device__ __forceinline__ uint4 post_op8(uint4 v, int relu, const bf16_t* mask, size_t o) {
+// The same on 8 packed bf16 values: max(., 0), and zero where the 8 packed bf16 values of m4 are <= 0.
+__device__ __forceinline__ uint4 relu8(uint4 v) {
   unsigned w[4] = {v.x, v.y, v.z, v.w};
-  if (relu) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const unsigned neg = ((w[i] >> 15) & 0x00010001u) * 0xffffu;   // 0xffff in every half whose sign bit is set
-      w[i] &= ~neg;
-    }
-  }
-  if (mask) {
-    const uint4 m4 = *reinterpret_cast<const uint4*>(mask + o);
-    const unsigned m[4] = {m4.x, m4.y, m4.z, m4.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const unsigned lo = __uint_as_float(m[i] << 16) > 0.f ? 0x0000ffffu : 0u;
-      const unsigned hi = __uint_as_float(m[i] & 0xffff0000u) > 0.f ? 0xffff0000u : 0u;
-      w[i] &= lo | hi;
-    }
+  for (int i = 0; i < 4; ++i) {
+    const unsigned neg = ((w[i] >> 15) & 0x00010001u) * 0xffffu;   // 0xffff in every half whose sign bit is set
+    w[i] &= ~neg;
   }
   return make_uint4(w[0], w[1], w[2], w[3]);
+}
+__device__ __forceinline__ uint4 mask8(uint4 v, uint4 m4) {
+  unsigned w[4] = {v.x, v.y, v.z, v.w};
+  const unsigned m[4] = {m4.x, m4.y, m4.z, m4.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const unsigned lo = __uint_as_float(m[i] << 16) > 0.f ? 0x0000ffffu : 0u;
+    const unsigned hi = __uint_as_float(m[i] & 0xffff0000u) > 0.f ? 0xffff0000u : 0u;
+    w[i] &= lo | hi;
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+// ... about to be stored at element offset o of the output, the mask read on the spot.  (Requesting the mask values
+// before the multiplies was measured on all four kernels that use this and changed nothing: what the mask costs them
+// is its bytes, not the wait.)
+__device__ __forceinline__ uint4 post_op8(uint4 v, int relu, const bf16_t* mask, size_t o) {
+  if (relu) v = relu8(v);
+  if (mask) v = mask8(v, *reinterpret_cast<const uint4*>(mask + o));
+  return v;
 }
 
 // Per-channel epilogue of a forward convolution that is given the UNFOLDED weight: Z = s (w (*) X) + b' with

@@ -46,6 +46,8 @@ struct PwParams {
   const float* bias;     // [R] or null
   BnEpilogue bn;         // bn.gamma != null: the weight is unfolded, the epilogue applies s and b' (bias unused)
   bf16_t* out;           // [M][R]
+  int relu;              // the output leaves as max(., 0)
+  const bf16_t* mask;    // not null: [M][R], the output is zeroed where this is <= 0
   unsigned act_bytes, wgt_bytes;
   int M, C, R;
   int ntr;               // channel tiles
@@ -276,7 +278,7 @@ __global__ __launch_bounds__(64 * NW) void conv_pw_kernel(PwParams p) {
             o = (((size_t)n * (p.d2s_H * p.d2s_kh) + h * p.d2s_kh + ta) * (p.d2s_W * p.d2s_kw) + w * p.d2s_kw + tb) *
                     p.d2s_co + (ch - tap * p.d2s_co);
           }
-          if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + o) = v;
+          if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + o) = post_op8(v, p.relu, p.mask, o);
         }
       }
       m0 += tile_stride;
@@ -429,6 +431,7 @@ hipError_t launch_fprop_pw(const Geom& g, const void* x, const void* w_krsc, con
   if (!pl.ok) return hipErrorInvalidValue;
   if (bn) p.bn = *bn;
   p.act = (const bf16_t*)x; p.wgt = (const bf16_t*)w_krsc; p.bias = bias; p.out = (bf16_t*)z;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
   return launch_plan(p, pl, st);
 }
 hipError_t launch_dgrad_pw(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
@@ -437,6 +440,7 @@ hipError_t launch_dgrad_pw(const Geom& g, const void* dz, const void* w_crsk, co
   const PwPlan pl = make_plan(p);
   if (!pl.ok) return hipErrorInvalidValue;
   p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
   return launch_plan(p, pl, st);
 }
 

@@ -76,6 +76,8 @@ struct RwParams {
   const float* bias;
   BnEpilogue bn;                  // bn.gamma != null: the weight is unfolded, the epilogue applies s and b' (bias unused)
   bf16_t* out;
+  int relu;                       // the output leaves as max(., 0)
+  const bf16_t* mask;             // not null: laid out like out, the output is zeroed where this is <= 0
   unsigned act_bytes, wgt_bytes;
   int N, H, W;
   int act_n_stride, act_h_stride, act_w_stride;   // elements
@@ -187,7 +189,6 @@ __device__ __forceinline__ void run_wave(const RwParams& p, unsigned char* smem,
 #pragma unroll
   for (int ps = 0; ps < NP; ++ps) {
     const int pi = sub[ps] * 32 + (lane & 31);
-    bf16_t* orow = p.out + (size_t)(m0 + pi) * CH;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -205,8 +206,10 @@ __device__ __forceinline__ void run_wave(const RwParams& p, unsigned char* smem,
         // (a, b) -> (a of lanes 0..31 | b of lanes 0..31,  a of lanes 32..63 | b of lanes 32..63)
         const auto lo = __builtin_amdgcn_permlane32_swap(pk[0][0], pk[1][0], false, false);
         const auto hi = __builtin_amdgcn_permlane32_swap(pk[0][1], pk[1][1], false, false);
-        if (pi < len)
-          *reinterpret_cast<uint4*>(orow + (4 * i + 2 * j + kb) * 8) = make_uint4(lo[0], hi[0], lo[1], hi[1]);
+        if (pi < len) {
+          const size_t o = (size_t)(m0 + pi) * CH + (4 * i + 2 * j + kb) * 8;
+          *reinterpret_cast<uint4*>(p.out + o) = post_op8(make_uint4(lo[0], hi[0], lo[1], hi[1]), p.relu, p.mask, o);
+        }
       }
   }
 }

@@ -104,6 +104,8 @@ struct StParams {
   const float* bias;
   BnEpilogue bn;                  // bn.gamma != null: the weight is unfolded, the epilogue applies s and b' (bias unused)
   bf16_t* out;
+  int relu;                       // the output leaves as max(., 0)
+  const bf16_t* mask;             // not null: laid out like out, the output is zeroed where this is <= 0
   unsigned act_bytes, wgt_bytes;
   int N, H, W, C;
   int act_n_stride, act_h_stride, act_w_stride;   // elements
@@ -255,6 +257,14 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
     aoff = (unsigned)(row * 128 + ((((2 * kq + kb) ^ key) & 7) << 4));
   }
 
+  // Element offset of the 8 channels this lane stores in epilogue iteration it (wave kq finishes subtile kq: channel
+  // subtile kq / NPS, pixel subtile kq % NPS of its pixel group); -1 past the last pixel.
+  auto store_off = [&](int it) -> long long {
+    const int row = it * 16 + (lane >> 2);
+    const int g = (lane & 3) ^ ((row >> 1) & 3);
+    const int pi = wpx * (TP / 2) + (kq % NPS) * 32 + row;
+    return pi < len ? (long long)((size_t)(m0 + pi) * p.R + r0 + (kq / NPS) * 32 + g * 8) : -1;
+  };
   f32x16 acc[4];   // subtile (channel i, pixel ps) at i * NPS + ps
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -392,10 +402,10 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
       const int row = it * 16 + (lane >> 2);
-      const int g = (lane & 3) ^ ((row >> 1) & 3);
       const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 64 + ((lane & 3) << 4));
-      const int pi = wpx * (TP / 2) + pss * 32 + row;
-      if (pi < len) *reinterpret_cast<uint4*>(p.out + (size_t)(m0 + pi) * p.R + r0 + ci * 32 + g * 8) = v;
+      (void)pss;
+      const long long o = store_off(it);
+      if (o >= 0) *reinterpret_cast<uint4*>(p.out + o) = post_op8(v, p.relu, p.mask, (size_t)o);
     }
   }
   STAMP(126);
@@ -519,6 +529,7 @@ hipError_t launch_fprop_st(const Geom& g, const void* x, const void* w_krsc, con
   if (!fprop_params(g, &p)) return hipErrorInvalidValue;
   if (bn) p.bn = *bn;
   p.act = (const bf16_t*)x; p.wgt = (const bf16_t*)w_krsc; p.bias = bias; p.out = (bf16_t*)z;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
   return launch(p, st);
 }
 hipError_t launch_dgrad_st(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
@@ -526,6 +537,7 @@ hipError_t launch_dgrad_st(const Geom& g, const void* dz, const void* w_crsk, co
   StParams p;
   if (!dgrad_params(g, &p)) return hipErrorInvalidValue;
   p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
   return launch(p, st);
 }
 

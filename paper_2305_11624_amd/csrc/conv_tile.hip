@@ -57,6 +57,8 @@ struct TileParams {
   const float* bias;     // [R] or null
   BnEpilogue bn;         // bn.gamma != null: the weight is unfolded, the epilogue applies s and b' (bias unused)
   bf16_t* out;           // [M][R]
+  int relu;              // the output leaves as max(., 0)
+  const bf16_t* mask;    // not null: laid out like out, the output is zeroed where this is <= 0
   unsigned act_bytes, wgt_bytes;
   int N, H, W, C;        // activation grid the window slides over
   int act_n_stride, act_h_stride, act_w_stride;
@@ -431,6 +433,24 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     bstep = nbstep; nbstep = n2bstep;
     cp = ncp;
   };
+  // Element offset of the channel block a lane stores for epilogue iteration (rp, i): pixel 32 wp + 8 i + lane / 8,
+  // channels r0 + (cw0 / 2 + rp) 64 + 8 g; -1 where nothing is stored.
+  auto store_off = [&](int rp, int i) -> long long {
+    const int row = i * 8 + (lane >> 3);
+    const int g = (lane & 7) ^ ((row >> 1) & 7);
+    const int pi = wp * 32 + row;
+    const int ch = r0 + (cw0 / 2 + rp) * 64 + g * 8;
+    if (pi >= len || ch >= p.R) return -1;
+    size_t o = (size_t)(m0 + pi) * p.R;
+    if (p.out_strided) {
+      const int m = m0 + pi;
+      const int n = fdiv(m, p.dHoWo);
+      const int rem = m - n * HoWo;
+      const int ho = fdiv(rem, p.dWo);
+      o = (size_t)p.out_base + (size_t)n * p.out_n + (size_t)ho * p.out_h + (size_t)(rem - ho * p.Wo) * p.out_w;
+    }
+    return (long long)(o + ch);
+  };
   for (int left = nsteps;;) {
     step(std::integral_constant<int, 0>{}); if (--left == 0) break;
     step(std::integral_constant<int, 1>{}); if (--left == 0) break;
@@ -496,17 +516,9 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
         const int row = i * 8 + (lane >> 3);
         const int g = (lane & 7) ^ ((row >> 1) & 7);
         const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 128 + ((lane & 7) << 4));
-        const int pi = pbase + row;
-        const int ch = r0 + (cw0 / 2 + rp) * 64 + g * 8;
-        size_t o = (size_t)(m0 + pi) * p.R;
-        if (p.out_strided) {
-          const int m = m0 + pi;
-          const int n = fdiv(m, p.dHoWo);
-          const int rem = m - n * HoWo;
-          const int ho = fdiv(rem, p.dWo);
-          o = (size_t)p.out_base + (size_t)n * p.out_n + (size_t)ho * p.out_h + (size_t)(rem - ho * p.Wo) * p.out_w;
-        }
-        if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + o + ch) = v;
+        (void)g; (void)pbase;
+        const long long o = store_off(rp, i);
+        if (o >= 0) *reinterpret_cast<uint4*>(p.out + o) = post_op8(v, p.relu, p.mask, (size_t)o);
       }
     }
   }
@@ -724,7 +736,11 @@ hipError_t launch_inst(const TileParams& p, const TilePlan& pl, hipStream_t st) 
   const size_t MR = (size_t)p.M * p.R;
   const int rblocks = (int)(((MR >> 3) + 255) / 256 < 2048 ? ((MR >> 3) + 255) / 256 : 2048);
   hipLaunchKernelGGL(reduce_partials_kernel, dim3(rblocks), dim3(256), 0, st, p.part, p.ksplit, MR, p.R, p.bias, p.out);
-  return hipGetLastError();
+  le = hipGetLastError();
+  // split sums: the reduction wrote the output, ReLU and mask follow as passes of their own
+  if (le == hipSuccess && p.relu) le = launch_eltwise(0, CONVBN_BF16, p.out, nullptr, nullptr, MR, st);
+  if (le == hipSuccess && p.mask) le = launch_eltwise(1, CONVBN_BF16, p.out, p.mask, nullptr, MR, st);
+  return le;
 }
 
 // The scale-in-the-epilogue ablation is built for the plans of the 3x3 benchmark shapes only.
@@ -922,6 +938,7 @@ hipError_t launch_fprop_tile(const Geom& g, const void* x, const void* w_krsc, c
   if (bn && !scaled_plan(pl)) return hipErrorInvalidValue;
   if (bn) p.bn = *bn;
   p.act = (const bf16_t*)x; p.wgt = (const bf16_t*)w_krsc; p.bias = bias; p.out = (bf16_t*)z;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
   p.part = partials;
   return launch_plan(p, pl, st);
 }
@@ -946,6 +963,7 @@ hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, 
         const TilePlan pl = make_plan(p);
         if (!pl.ok) return hipErrorInvalidValue;
         p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
+        p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
         p.part = nullptr;
         hipError_t e = launch_plan(p, pl, st);
         if (e != hipSuccess) return e;
@@ -956,6 +974,7 @@ hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, 
   const TilePlan pl = make_plan(p);
   if (p.ksplit > 1 && !partials) return hipErrorInvalidValue;
   p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
   p.part = partials;
   return launch_plan(p, pl, st);
 }

@@ -15,10 +15,11 @@ from . import synth
 
 
 class _Block:
-    def __init__(self, shape, device, mode):
+    def __init__(self, shape, device, mode, act=0):
         self.shape, self.mode = shape, mode
         p = synth.make_params(shape)
         self.desc = B.desc_from_shape(shape, eps=p["eps"])
+        self.desc.act = act   # the ReLUs next to the block that its convolutions apply on the way out
         dt = B.torch_dtype(self.desc)
         self.dt = dt
         self.W = B.weight_to_device(p["W"], dt, device)
@@ -63,7 +64,8 @@ class _Block:
         if self.unit is not None and not self.unit["fused"]:
             # this block's fold-back runs with its unit's, in one launch: only the two gradient convolutions here
             u = self.unit
-            B.convbn_conv_dgrad(self.desc, dz, u["w_t"], dx, ws)
+            B.convbn_conv_dgrad(self.desc, dz, u["w_t"], dx, ws,
+                                x_mask=self.x if self.desc.act & B.ACT_RELU_IN else None)
             B.convbn_conv_wgrad(self.desc, self.x, dz, u["dw_part"], u["r_part"], ws)
             self.x = self.saved = None
             return dx
@@ -93,7 +95,11 @@ class ResNet50:
         self.group_bytes = 0
         self.arena_bytes = self.kept_bytes = 0   # per-unit grouping: the shared arena (workspace) and the kept w'
         shapes = synth.resnet50_blocks(N, image, dtype)
-        self.blocks: Dict[str, _Block] = {s.name: _Block(s, device, mode) for s in shapes}
+        # inside a bottleneck unit: ReLU behind the first two blocks, hence in front of the last two (the ReLU behind
+        # the unit follows the residual sum and stays an element-wise pass, like the stem's in front of the max-pool)
+        act = {"a": B.ACT_RELU_OUT, "b": B.ACT_RELU_OUT | B.ACT_RELU_IN, "c": B.ACT_RELU_IN}
+        self.blocks: Dict[str, _Block] = {s.name: _Block(s, device, mode, act.get(s.name.rsplit(".", 1)[-1], 0))
+                                          for s in shapes}
         self.order: List[str] = [s.name for s in shapes]
         self.ws = torch.empty(max(b.ws_bytes for b in self.blocks.values()) + 256, dtype=torch.uint8, device=device)
         self.dt = self.blocks["stem"].dt
@@ -241,10 +247,8 @@ class ResNet50:
             for name in names:
                 if self.units is not None:
                     B.convbn_fold_group(*self.units[name]["fold"])
-                a = bl[name + ".a"].forward(cur, ws)
-                B.convbn_aux_eltwise(B.OP_RELU, a)
+                a = bl[name + ".a"].forward(cur, ws)     # (ReLU applied by the block: its act bits)
                 b = bl[name + ".b"].forward(a, ws)
-                B.convbn_aux_eltwise(B.OP_RELU, b)
                 c_ = bl[name + ".c"].forward(b, ws)
                 has_ds = (name + ".ds") in bl
                 sc = bl[name + ".ds"].forward(cur, ws) if has_ds else cur
@@ -263,11 +267,9 @@ class ResNet50:
         for i, (name, has_ds, a, b, out) in enumerate(order):
             if self.units is not None and self.units[name]["refold"] is not None:
                 B.convbn_fold_group(*self.units[name]["refold"])   # blocks that kept nothing: w' again, for this unit
-            gb = bl[name + ".c"].backward(g, ws)
-            B.convbn_aux_eltwise(B.OP_RELU_BWD, gb, b)
-            ga = bl[name + ".b"].backward(gb, ws)
+            gb = bl[name + ".c"].backward(g, ws)     # (masked with b > 0 by the block: its act bits)
+            ga = bl[name + ".b"].backward(gb, ws)    # (masked with a > 0)
             del gb
-            B.convbn_aux_eltwise(B.OP_RELU_BWD, ga, a)
             gin = bl[name + ".a"].backward(ga, ws)
             del ga
             # the two branches meet at the unit's input, which is the output of the previous unit's ReLU (of the
