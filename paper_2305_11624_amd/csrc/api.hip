@@ -729,9 +729,8 @@ convbn_status convbn_eval_fwd(const convbn_desc* desc, const void* x, const void
   const EvalFwdWs w = carve_eval_fwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
   LAUNCH(run_fprop(g, dt, x, W, b, y_saved, w.conv_scratch, st));         // Y = w (*) X + b
+  g.post_relu = g.act & CONVBN_ACT_RELU_OUT;   // applied to Z, not to the stored Y
   LAUNCH(launch_bn_affine_fwd(g, dt, y_saved, gamma, beta, mean, var, z, st));  // Z from Y
-  g.post_relu = g.act & CONVBN_ACT_RELU_OUT;
-  LAUNCH(post_op_pass(g, dt, z, (size_t)g.M * g.Cout, st));
   return CONVBN_OK;
 }
 
