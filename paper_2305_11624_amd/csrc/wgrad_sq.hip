@@ -84,6 +84,10 @@ struct SqParams {
   int ntiles, tiles_per_split;
   int hunits;         // 1 KB units of a stage's window tile
   int stage_bytes;    // dZ tile + window tile
+  // A tile is TILE consecutive output pixels = step_n images + step_h rows + step_w pixels; what that step adds to a
+  // pixel's byte offset among the window rows of the whole tensor, and what the carries out of the column and the row add
+  int step_h, step_w, step_off, carry_w_off, carry_h_off;
+  int max_pixel_off;  // largest offset (inside a stage's window tile) a pixel of the tile can have
   FastDiv dHoWo, dWo, dHv, dWv;
 };
 
@@ -108,6 +112,11 @@ __device__ __forceinline__ unsigned lds_off(const void* p) {
 // every LDS read until the global -> LDS copies of the NEXT tile have landed.
 __device__ __forceinline__ void tr_read(i32x2& dst, unsigned addr) {
   asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(dst) : "v"(addr));
+}
+// ... at a compile-time byte offset from the address (the instruction's offset field): the taps of a kernel row and
+// the 16-pixel steps of a tile cost no address arithmetic
+template <int OFF> __device__ __forceinline__ void tr_read_at(i32x2& dst, unsigned addr) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
 }
 template <int N> __device__ __forceinline__ void wait_lgkm() {
   asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
@@ -189,65 +198,106 @@ __device__ __forceinline__ void sq_body(const SqParams& p, int block, unsigned c
 
   // place of this lane in a 1 KB copy: 16 rows x 4 granules
   const int urow = lane >> 2, ugran = lane & 3;
-  // dZ copies: rows past the last pixel lie past the end of the buffer and arrive as zeros; the tile's first
-  // pixel enters as a wave-uniform offset
+  // Everything a copy or an operand read needs per lane is kept as running state that a step to the next tile
+  // updates with additions, compares and selects: the loop is bound by the instructions a wave issues between
+  // its multiplies, and a division or a 32-bit multiply per address costs several multiplies' worth of issue slots.
+  //
+  // dZ copies: per-lane byte offset inside a tile; the tile's first row is added per copy (the range check of the
+  // copy covers only the per-lane offset: rows past the last pixel then lie past the buffer and arrive as zeros)
   unsigned zoff[KS];
 #pragma unroll
   for (int j = 0; j < KS; ++j) zoff[j] = (unsigned)((((wave + NWAVES * j) * 16 + urow) * p.Co + co0 + ugran * 8) * 2);
-  // window copies: what does not depend on the tile -- the window row (slot) and the column part of the address
-  int xslot[NXU];
-  unsigned xcol[NXU];
-#pragma unroll
-  for (int j = 0; j < NXU; ++j) {
-    const int pix = (wave + NWAVES * j) * 16 + urow;
-    xslot[j] = fdiv(pix, p.dWv);
-    const int w = pix - xslot[j] * p.Wv - p.pw;
-    xcol[j] = (unsigned)w < (unsigned)p.W ? (unsigned)((w * p.x_w_stride + ci0 + ugran * 8) * 2) : OOB;
-  }
-  // the stage holds exactly p.hunits window units: the waves whose last unit lies past them issue one copy less
-  const bool has_last = wave + NWAVES * (NXU - 1) < p.hunits;
+  const unsigned ztile_bytes = (unsigned)(TILE * 2) * (unsigned)p.Co;
   // first window row of a tile (wave-uniform)
   auto tile_vfirst = [&](int tile) {
     const int m0 = tile * TILE;
     const int n_a = fdiv(m0, p.dHoWo);
     return n_a * p.Hv + fdiv(m0 - n_a * HoWo, p.dWo) * p.sh;
   };
-  // All NCPY copies of `tile` into stage `st` (zero-fill copies if the tile does not exist: the count stays fixed).
-  auto issue_copy = [&](int i, int tile, int vfirst, bool live, unsigned char* stage) {
+  // window copies: unit u = wave + 8 j covers window pixels 16 u .. of the tile; this lane's pixel is column w of
+  // window row vfirst + slot.  State: the row's place hv inside its image's Hv window rows and the byte offset xo
+  // of the lane's 16 bytes (meaningless while the row is padding).  A step of dv = dn Hv + dh window rows adds
+  // xstep = dn (image) + dh (row) bytes, and one image less Hv rows where hv wraps.
+  const int ns_b = p.x_n_stride * 2, hs_b = p.x_h_stride * 2;
+  const int wrap_b = ns_b - p.Hv * hs_b;
+  int xhv[NXU];
+  unsigned xo[NXU];
+  bool xcol_ok[NXU];
+  const int vf_beg = tile_vfirst(tile_beg);
+#pragma unroll
+  for (int j = 0; j < NXU; ++j) {
+    const int pix = (wave + NWAVES * j) * 16 + urow;
+    const int slot = fdiv(pix, p.dWv);
+    const int w = pix - slot * p.Wv - p.pw;
+    xcol_ok[j] = (unsigned)w < (unsigned)p.W;
+    const int v = vf_beg + slot;
+    const int n = fdiv(v, p.dHv);
+    xhv[j] = v - n * p.Hv;
+    xo[j] = (unsigned)(n * ns_b + (xhv[j] - p.ph) * hs_b + (w * p.x_w_stride + ci0 + ugran * 8) * 2);
+  }
+  // the stage holds exactly p.hunits window units: the waves whose last unit lies past them issue one copy less
+  const bool has_last = wave + NWAVES * (NXU - 1) < p.hunits;
+  // the step from one tile's first window row to the next one's, split on the scalar unit
+  int x_dh = 0, x_step = 0;
+  auto set_step = [&](int dv) {
+    const int dn = fdiv(dv, p.dHv);
+    x_dh = dv - dn * p.Hv;
+    x_step = dn * ns_b + x_dh * hs_b;
+  };
+  auto advance_window = [&](int j) {
+    int hv = xhv[j] + x_dh;
+    const bool wr = hv >= p.Hv;
+    xhv[j] = wr ? hv - p.Hv : hv;
+    xo[j] += (unsigned)(x_step + (wr ? wrap_b : 0));
+  };
+  // Copy i of a tile into `stage` (a zero-fill copy if the tile does not exist: the count stays fixed).  ztile: byte
+  // offset of the tile's first dZ row, past any buffer for a tile that does not exist.  The window state must have
+  // been advanced to the tile.
+  auto issue_copy = [&](int i, unsigned ztile, bool live, unsigned char* stage) {
     if (i < KS) {
       const int ii = i < KS ? i : 0;
-      const bool ok = live && tile * TILE + (wave + NWAVES * ii) * 16 + urow < p.M;   // the wave-uniform offset is not range-checked
-      dma16(z_rsrc, ok ? zoff[ii] : OOB, (unsigned)(tile * (TILE * 2)) * (unsigned)p.Co, stage + (wave + NWAVES * ii) * 1024);
+      dma16(z_rsrc, zoff[ii] + ztile, 0u, stage + (wave + NWAVES * ii) * 1024);
     } else {
       const int j = i - KS < NXU ? i - KS : 0;
       if (j == NXU - 1 && !has_last) return;   // wave-uniform: this wave's last unit lies past the window tile
-      const int v = vfirst + xslot[j];
-      const int n = fdiv(v, p.dHv);
-      const int h = v - n * p.Hv - p.ph;
-      const bool ok = live && (unsigned)h < (unsigned)p.H && xcol[j] != OOB;   // rows past the last image lie past the buffer
-      dma16(x_rsrc, ok ? (unsigned)((n * p.x_n_stride + h * p.x_h_stride) * 2) + xcol[j] : OOB, 0u, stage + ZT + (wave + NWAVES * j) * 1024);
+      const bool ok = live && xcol_ok[j] && (unsigned)(xhv[j] - p.ph) < (unsigned)p.H;   // rows past the last image lie past the buffer
+      dma16(x_rsrc, ok ? xo[j] : OOB, 0u, stage + ZT + (wave + NWAVES * j) * 1024);
     }
   };
-  // Byte offset (inside the window tile) of the window row of tap (0,0) of output pixel m of a tile that starts
-  // at window row vfirst.
-  auto pixel_off = [&](int m, int vfirst) {
-    const int mm = min(m, p.M - 1);
-    const int n = fdiv(mm, p.dHoWo);
-    const int rem = mm - n * HoWo;
-    const int ho = fdiv(rem, p.dWo);
-    return ((n * p.Hv + ho * p.sh - vfirst) * p.Wv + (rem - ho * p.Wo) * p.sw) * ROWB;
-  };
 
-  // tap offsets inside the window tile
-  int tapoff[TAPS];
-#pragma unroll
-  for (int t = 0; t < TAPS; ++t) tapoff[t] = ((t / 3) * p.Wv + (t % 3)) * ROWB;
-
+  // Operand reads.  Output pixel m = (n, ho, wo) reads window row n Hv + ho sh, column wo sw (+ tap): state per
+  // pixel this lane addresses (two per 16-pixel step) is (wo, ho) and the byte offset pg of that place among the
+  // window rows of the whole tensor; inside a tile's window tile the offset is pg - (first window row) Wv ROWB.
   const int kb = lane >> 5;
   const int eprime = (lane & 15) >> 2;                        // pixel (of 4) this lane addresses in a transposing read
   const int chq = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;    // channel quad inside the 32 channels
   const int pbase = wave * (16 * KS);                          // this wave's first pixel of a tile
   const int plane = pbase + kb * 8 + eprime;                   // ... and this lane's first pixel of a 16-pixel step
+  const int row_b = p.Wv * ROWB;                               // one window row
+  int pwo[KS][2], pho[KS][2], pg[KS][2];
+#pragma unroll
+  for (int k = 0; k < KS; ++k)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int m = tile_beg * TILE + plane + k * 16 + 4 * h;   // (past the last pixel: an image that does not exist)
+      const int n = fdiv(m, p.dHoWo);
+      const int rem = m - n * HoWo;
+      pho[k][h] = fdiv(rem, p.dWo);
+      pwo[k][h] = rem - pho[k][h] * p.Wo;
+      pg[k][h] = ((n * p.Hv + pho[k][h] * p.sh) * p.Wv + pwo[k][h] * p.sw) * ROWB;
+    }
+  auto advance_pixel = [&](int k, int h) {
+    int wo = pwo[k][h] + p.step_w;
+    const bool cw = wo >= p.Wo;
+    pwo[k][h] = cw ? wo - p.Wo : wo;
+    int ho = pho[k][h] + p.step_h + (cw ? 1 : 0);
+    const bool ch = ho >= p.Ho;
+    pho[k][h] = ch ? ho - p.Ho : ho;
+    pg[k][h] += p.step_off + (cw ? p.carry_w_off : 0) + (ch ? p.carry_h_off : 0);
+  };
+  // offset inside the window tile of a tile whose first window row is vfirst; pixels past the last one (their dZ
+  // rows are zeros) are held inside the tile so that they read numbers, not whatever else the LDS holds
+  auto pixel_rel = [&](int k, int h, int vfirst) { return min(pg[k][h] - vfirst * row_b, p.max_pixel_off); };
 
   f32x16 acc[TAPS];
 #pragma unroll
@@ -261,23 +311,27 @@ __device__ __forceinline__ void sq_body(const SqParams& p, int block, unsigned c
   for (int e = 0; e < 8; ++e) racc[e] = 0.f;
 
   // ---- prologue: the copies of the first two tiles, the pixel offsets of the first ----------------------------
-  int vf_cur = 0, vf_next = 0;
+  int vf_cur = vf_beg, vf_next = 0;
   int ptv[KS][2];
 #pragma unroll
-  for (int d = 0; d < 2; ++d) {
-    const int tile = tile_beg + d;
-    const bool live = tile < tile_end;
-    const int vf = live ? tile_vfirst(tile) : 0;
-    if (d == 0) vf_cur = vf; else vf_next = vf;
+  for (int k = 0; k < KS; ++k)
 #pragma unroll
-    for (int i = 0; i < NCPY; ++i) issue_copy(i, tile, vf, live, smem + d * p.stage_bytes);
-  }
+    for (int h = 0; h < 2; ++h) ptv[k][h] = pixel_rel(k, h, vf_beg);
+  {
+    const bool live0 = tile_beg < tile_end;
 #pragma unroll
-  for (int k = 0; k < KS; ++k) {
-    ptv[k][0] = pixel_off(tile_beg * TILE + plane + k * 16, vf_cur);
-    ptv[k][1] = pixel_off(tile_beg * TILE + plane + k * 16 + 4, vf_cur);
+    for (int i = 0; i < NCPY; ++i) issue_copy(i, live0 ? (unsigned)tile_beg * ztile_bytes : OOB, live0, smem);
+    const bool live1 = tile_beg + 1 < tile_end;
+    vf_next = live1 ? tile_vfirst(tile_beg + 1) : vf_beg;
+    set_step(vf_next - vf_beg);
+#pragma unroll
+    for (int j = 0; j < NXU; ++j) advance_window(j);
+#pragma unroll
+    for (int i = 0; i < NCPY; ++i) issue_copy(i, live1 ? (unsigned)(tile_beg + 1) * ztile_bytes : OOB, live1, smem + p.stage_bytes);
   }
 
+  const unsigned zlane0 = lds_off(smem) + plane * ROWB + chq * 2;
+  const unsigned xlane0 = lds_off(smem) + ZT + chq * 2;
   int stage_off = 0;                        // byte offset of the current tile's stage
   STAMP(1);
   for (int tile = tile_beg; tile < tile_end; ++tile) {
@@ -296,7 +350,9 @@ __device__ __forceinline__ void sq_body(const SqParams& p, int block, unsigned c
     unsigned char* const fill = smem + fill_off;
     const int tile_f = tile + 2;
     const bool live_f = tile_f < tile_end;
-    const int vf_fill = live_f ? tile_vfirst(tile_f) : 0;
+    const int vf_fill = live_f ? tile_vfirst(tile_f) : vf_next;
+    set_step(vf_fill - vf_next);            // the window state stands at tile + 1
+    const unsigned ztile_f = live_f ? (unsigned)tile_f * ztile_bytes : OOB;
 
     if (do_r) {
       // column sums of the dZ tile: thread -> granule tid % 4, pixels tid / 4 + 128 j.  Read through inline asm
@@ -317,21 +373,47 @@ __device__ __forceinline__ void sq_body(const SqParams& p, int block, unsigned c
       }
     }
 
-    const unsigned zlane = lds_off(zs) + plane * ROWB + chq * 2;
-    const unsigned xlane = lds_off(zs + ZT) + chq * 2;
+    // Read addresses of this tile: one register per (16-pixel step, half, kernel row); the tap's column and the dZ
+    // rows of a step are compile-time offsets of the read.
+    const unsigned zlane = zlane0 + (unsigned)stage_off;
+    const unsigned xlane = xlane0 + (unsigned)stage_off;
+    unsigned rb[KS][2][3];
+#pragma unroll
+    for (int k = 0; k < KS; ++k)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        rb[k][h][0] = xlane + (unsigned)ptv[k][h];
+        rb[k][h][1] = rb[k][h][0] + (unsigned)row_b;
+        rb[k][h][2] = rb[k][h][1] + (unsigned)row_b;
+      }
     // Operands are read AHEAD multiplies before their multiply: fx ring slot s % (AHEAD + 1); the dZ fragment of a
     // 16-pixel step goes just before the window fragment of its first tap.
     i32x2 fz[2][2];
     i32x2 fx[AHEAD + 1][2];
     int pnext[KS][2];
+    auto read_z = [&](i32x2& dst, int k, int h) {
+      switch (k * 2 + h) {
+        case 0: tr_read_at<0>(dst, zlane); break;
+        case 1: tr_read_at<4 * ROWB>(dst, zlane); break;
+        case 2: tr_read_at<16 * ROWB>(dst, zlane); break;
+        default: tr_read_at<20 * ROWB>(dst, zlane); break;
+      }
+    };
+    auto read_x = [&](i32x2& dst, unsigned base, int col) {
+      switch (col) {
+        case 0: tr_read_at<0>(dst, base); break;
+        case 1: tr_read_at<ROWB>(dst, base); break;
+        default: tr_read_at<2 * ROWB>(dst, base); break;
+      }
+    };
     auto issue_reads = [&](int s) {
       const int k = s / TAPS, f = s % TAPS;
       if (f == 0) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) tr_read(fz[k & 1][h], zlane + (k * 16 + 4 * h) * ROWB);
+        for (int h = 0; h < 2; ++h) read_z(fz[k & 1][h], k, h);
       }
 #pragma unroll
-      for (int h = 0; h < 2; ++h) tr_read(fx[s % (AHEAD + 1)][h], xlane + ptv[k][h] + tapoff[f]);
+      for (int h = 0; h < 2; ++h) read_x(fx[s % (AHEAD + 1)][h], rb[k][h][f / 3], f % 3);
     };
 #pragma unroll
     for (int s = 0; s < AHEAD; ++s) issue_reads(s);
@@ -353,11 +435,16 @@ __device__ __forceinline__ void sq_body(const SqParams& p, int block, unsigned c
       acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(join2(fx[s % (AHEAD + 1)][0], fx[s % (AHEAD + 1)][1]),
                                                        join2(fz[k & 1][0], fz[k & 1][1]), acc[f], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      // in the shadow of the multiply: one copy of the tile two ahead, then the pixel offsets of the next tile
-      if (s < NCPY) issue_copy(s, tile_f, vf_fill, live_f, fill);
+      // in the shadow of the multiply: one copy of the tile two ahead (its window state stepped first), then the
+      // pixel offsets of the next tile
+      if (s < NCPY) {
+        if (s >= KS && s - KS < NXU) advance_window(s - KS);
+        issue_copy(s, ztile_f, live_f, fill);
+      }
       if (s >= NS - 2 * KS) {
         const int e = s - (NS - 2 * KS);
-        pnext[e >> 1][e & 1] = pixel_off((tile + 1) * TILE + plane + (e >> 1) * 16 + 4 * (e & 1), vf_next);
+        advance_pixel(e >> 1, e & 1);
+        pnext[e >> 1][e & 1] = pixel_rel(e >> 1, e & 1, vf_next);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -368,6 +455,7 @@ __device__ __forceinline__ void sq_body(const SqParams& p, int block, unsigned c
     stage_off += p.stage_bytes;
     if (stage_off >= NSTAGE * p.stage_bytes) stage_off = 0;
   }
+  (void)vf_cur;
 
   // ---- the eight waves add their accumulators through LDS ---------------------------------------------
   // [copy][tap][e][lane] floats; waves 4..7 hand theirs to waves 0..3, then those four copies are summed by all.
@@ -597,6 +685,8 @@ SqPlan make_plan(const Geom& g, SqParams* pp) {
   p.x_bytes = (unsigned)xb; p.dz_bytes = (unsigned)zb;
   p.Hv = (p.Ho - 1) * p.sh + 3;
   p.Wv = (p.Wo - 1) * p.sw + 3;
+  // byte offsets among the window rows of the whole tensor (and two images past it) are kept in 32 bits
+  if ((long long)(p.N + 2) * p.Hv * p.Wv * ROWB >= (long long)OOB) return pl;
   p.dHoWo = make_fastdiv(p.Ho * p.Wo);
   p.dWo = make_fastdiv(p.Wo);
   p.dHv = make_fastdiv(p.Hv);
@@ -615,6 +705,13 @@ SqPlan make_plan(const Geom& g, SqParams* pp) {
     pl.ks = ks; pl.ncpy = ks + nxu; pl.lds = lds;
     p.hunits = hunits; p.stage_bytes = stage;
     p.ntiles = ceil_div(g.M, tile);
+    const int rem = tile % (p.Ho * p.Wo);
+    p.step_h = rem / p.Wo;
+    p.step_w = rem % p.Wo;
+    p.step_off = (((tile / (p.Ho * p.Wo)) * p.Hv + p.step_h * p.sh) * p.Wv + p.step_w * p.sw) * ROWB;
+    p.carry_w_off = (p.sh * p.Wv - p.Wo * p.sw) * ROWB;
+    p.carry_h_off = (p.Hv - p.Ho * p.sh) * p.Wv * ROWB;
+    p.max_pixel_off = hunits * 1024 - (2 * p.Wv + 3) * ROWB;
     break;
   }
   if (pl.ks == 0) return pl;
