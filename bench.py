@@ -404,7 +404,7 @@ def main_backbone(a):
         "ms_per_step": tune["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"ResNet-50 backbone, 53 ConvBN blocks + ReLU + residual adds + max-pool, "
-                               f"bf16, N={N}, {image}x{image}x3, frozen BN statistics; fold and fold-back grouped per "
+                               f"bf16, N={N}, {image}x{image}x3, frozen BN statistics; residual sums applied by the convolutions; fold and fold-back grouped per "
                                f"bottleneck unit", "mode": "tune",
                    "layout": "NHWC", "step": "fwd+bwd of the backbone (no gradient w.r.t. the images)"},
         "pct_of_bf16_mfma_peak": 100.0 * tf / PEAK_BF16_TFLOPS,

@@ -77,6 +77,8 @@ typedef struct {
   int32_t dtype;              /* convbn_dtype of x, W, z, y, dz, dx, dW, w_folded   */
   int32_t layout;             /* convbn_layout                                      */
   int32_t act;                /* CONVBN_ACT_* bits, 0 = none (see below)            */
+  const void *add_out;        /* device tensor laid out like z  (CONVBN_ACT_ADD_OUT) */
+  const void *add_in;         /* device tensor laid out like dx (CONVBN_ACT_ADD_IN)  */
 } convbn_desc;
 
 /* Activations around a block.  What follows a block does not change the block's computation (Sec. 3.1); these
@@ -88,8 +90,16 @@ typedef struct {
  *                        with respect to the block's own output Z, i.e. the caller (or the next block, see the
  *                        other bit) has already applied the ReLU's backward mask.
  *   CONVBN_ACT_RELU_IN   x is the output of a ReLU: the backward calls return dx masked with x > 0, which is the
- *                        gradient with respect to that ReLU's input. */
-enum { CONVBN_ACT_RELU_OUT = 1, CONVBN_ACT_RELU_IN = 2 };
+ *                        gradient with respect to that ReLU's input.
+ *   CONVBN_ACT_ADD_OUT   a residual connection joins behind the block: the forward calls return z + add_out (the sum
+ *                        of the two tensors, each rounded to dtype, rounded once more), before the ReLU of
+ *                        CONVBN_ACT_RELU_OUT if that bit is set too.  add_out must not overlap z.
+ *   CONVBN_ACT_ADD_IN    x also feeds a second branch whose gradient is add_in: the backward calls (and
+ *                        convbn_conv_dgrad / convbn_conv_dgrad_masked) return dx + add_in, before the mask of
+ *                        CONVBN_ACT_RELU_IN.  add_in must not overlap dx.
+ * The addend pointers are read only when their bit is set (then they must not be NULL); they are caller-owned and
+ * only read. */
+enum { CONVBN_ACT_RELU_OUT = 1, CONVBN_ACT_RELU_IN = 2, CONVBN_ACT_ADD_OUT = 4, CONVBN_ACT_ADD_IN = 8 };
 
 /* Output spatial size for a descriptor (0 on a NULL / invalid descriptor). */
 int32_t convbn_hout(const convbn_desc *desc);

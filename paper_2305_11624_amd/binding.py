@@ -41,7 +41,8 @@ class Desc(C.Structure):
                 ("Cout", C.c_int32), ("kH", C.c_int32), ("kW", C.c_int32),
                 ("stride_h", C.c_int32), ("stride_w", C.c_int32),
                 ("pad_h", C.c_int32), ("pad_w", C.c_int32),
-                ("eps", C.c_float), ("dtype", C.c_int32), ("layout", C.c_int32), ("act", C.c_int32)]
+                ("eps", C.c_float), ("dtype", C.c_int32), ("layout", C.c_int32), ("act", C.c_int32),
+                ("add_out", C.c_void_p), ("add_in", C.c_void_p)]
 
 
 class FoldItem(C.Structure):
@@ -178,7 +179,14 @@ def lib():
     return _lib
 
 
-ACT_RELU_OUT, ACT_RELU_IN = 1, 2
+ACT_RELU_OUT, ACT_RELU_IN, ACT_ADD_OUT, ACT_ADD_IN = 1, 2, 4, 8
+
+
+def set_addends(desc, add_out=None, add_in=None):
+    """Point the descriptor at the tensors of its ACT_ADD_OUT / ACT_ADD_IN bits (device tensors, or None); the caller
+    keeps them alive until the calls that read them have been enqueued."""
+    desc.add_out = None if add_out is None else add_out.data_ptr()
+    desc.add_in = None if add_in is None else add_in.data_ptr()
 
 
 def make_desc(N, Cin, Hin, Win, Cout, kH, kW, stride=1, pad=0, eps=1e-5, dtype=BF16,

@@ -44,9 +44,13 @@ convbn_status make_geom(const convbn_desc* d, Geom* g) {
   if (d->layout != CONVBN_LAYOUT_NHWC)
     return fail(CONVBN_ERR_UNSUPPORTED, "layout %d: only CONVBN_LAYOUT_NHWC is supported", d->layout);
   if (!(d->eps >= 0.f)) return fail(CONVBN_ERR_SHAPE, "eps must be >= 0");
-  if (d->act < 0 || d->act > (CONVBN_ACT_RELU_OUT | CONVBN_ACT_RELU_IN))
+  if (d->act < 0 || d->act > (CONVBN_ACT_RELU_OUT | CONVBN_ACT_RELU_IN | CONVBN_ACT_ADD_OUT | CONVBN_ACT_ADD_IN))
     return fail(CONVBN_ERR_UNSUPPORTED, "act %d: unknown activation bits", d->act);
-  g->act = d->act; g->post_relu = 0; g->post_mask = nullptr;
+  if (((d->act & CONVBN_ACT_ADD_OUT) && !d->add_out) || ((d->act & CONVBN_ACT_ADD_IN) && !d->add_in))
+    return fail(CONVBN_ERR_NULL, "act %d asks for an addend that the descriptor does not give", d->act);
+  g->act = d->act; g->post_relu = 0; g->post_mask = nullptr; g->post_add = nullptr;
+  g->add_out = (d->act & CONVBN_ACT_ADD_OUT) ? d->add_out : nullptr;
+  g->add_in = (d->act & CONVBN_ACT_ADD_IN) ? d->add_in : nullptr;
   g->N = d->N; g->Cin = d->Cin; g->Hin = d->Hin; g->Win = d->Win;
   g->Cout = d->Cout; g->kH = d->kH; g->kW = d->kW;
   g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
@@ -251,9 +255,13 @@ size_t wgrad_scratch_bytes(const Geom& g, int dtype) {
          align_up((size_t)wgrad_way(g, dtype).nsplit * q.Cout * q.K * 4, 256);
 }
 
-// The post-operation of g (ReLU, mask) as a pass of its own over `out` (n elements): for the kernels that do not
-// apply it in their epilogue.
+// The post-operation of g (addend, ReLU, mask) as passes of their own over `out` (n elements): for the kernels that
+// do not apply it in their epilogue.
 hipError_t post_op_pass(const Geom& g, int dtype, void* out, size_t n, hipStream_t st) {
+  if (g.post_add) {
+    hipError_t e = launch_eltwise(3 /* a + b */, dtype, out, g.post_add, nullptr, n, st);
+    if (e != hipSuccess) return e;
+  }
   if (g.post_relu) {
     hipError_t e = launch_eltwise(0 /* max(a, 0) */, dtype, out, nullptr, nullptr, n, st);
     if (e != hipSuccess) return e;
@@ -261,7 +269,7 @@ hipError_t post_op_pass(const Geom& g, int dtype, void* out, size_t n, hipStream
   if (g.post_mask) return launch_eltwise(1 /* b > 0 ? a : 0 */, dtype, out, g.post_mask, nullptr, n, st);
   return hipSuccess;
 }
-bool has_post_op(const Geom& g) { return g.post_relu || g.post_mask; }
+bool has_post_op(const Geom& g) { return g.post_relu || g.post_mask || g.post_add; }
 
 // FUSED_*: the kernel applies g's post-operation itself.
 constexpr bool FUSED_PW = true, FUSED_RW = true, FUSED_ST = true, FUSED_TILE = true;
@@ -330,7 +338,7 @@ hipError_t run_dgrad(const Geom& g, int dtype, const void* dz, const void* w_crs
     return post_op_pass(g, dtype, dx, (size_t)g.Min * g.Cin, st);
   }
   Geom q = padded_geom(g);
-  q.post_relu = 0; q.post_mask = nullptr;   // the mask is laid out like dx, not like its padded copy: applied at the end
+  q.post_relu = 0; q.post_mask = nullptr; q.post_add = nullptr;   // mask and addend are laid out like dx, not like its padded copy: applied at the end
   char* s = reinterpret_cast<char*>(scratch);
   void* wp = s; s += align_up((size_t)q.Cout * q.K * 2, 256);
   void* dxp = s; s += align_up((size_t)q.Min * q.Cin * 2, 256);
@@ -628,7 +636,7 @@ convbn_status convbn_tune_fwd(const convbn_desc* desc, const void* x, const void
   if (s != CONVBN_OK) return s;
   const TuneFwdWs w = carve_tune_fwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  g.post_relu = g.act & CONVBN_ACT_RELU_OUT;
+  g.post_relu = g.act & CONVBN_ACT_RELU_OUT; g.post_add = g.add_out;
   const size_t nz = (size_t)g.M * g.Cout;
   if (!needs_cin_pad(g, dt) && !pw_fprop_supported(g, dt) && (g.kH > 1 || g.kW > 1)) {
     // The scale is per output channel, so Z = s (w (*) X) + b' (Sec. 3.3): the convolution reads the unfolded
@@ -681,6 +689,7 @@ convbn_status convbn_tune_bwd(const convbn_desc* desc, const void* x, const void
   const TuneBwdWs w = carve_tune_bwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (g.act & CONVBN_ACT_RELU_IN) g.post_mask = x;   // dx comes out masked with x > 0
+  g.post_add = g.add_in;                             // ... after the addend
   if (params && convbn_tune_bwd_is_fused(desc)) {
     // deep layers: dw', r and the fold-back in one launch (the fp32 dw' never reaches memory); the space of the
     // fp32 copy holds the few partial sums the workgroups exchange.  Where nothing was kept, the same launch leaves
@@ -729,7 +738,7 @@ convbn_status convbn_eval_fwd(const convbn_desc* desc, const void* x, const void
   const EvalFwdWs w = carve_eval_fwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
   LAUNCH(run_fprop(g, dt, x, W, b, y_saved, w.conv_scratch, st));         // Y = w (*) X + b
-  g.post_relu = g.act & CONVBN_ACT_RELU_OUT;   // applied to Z, not to the stored Y
+  g.post_relu = g.act & CONVBN_ACT_RELU_OUT; g.post_add = g.add_out;   // applied to Z, not to the stored Y
   LAUNCH(launch_bn_affine_fwd(g, dt, y_saved, gamma, beta, mean, var, z, st));  // Z from Y
   return CONVBN_OK;
 }
@@ -758,6 +767,7 @@ convbn_status convbn_eval_bwd(const convbn_desc* desc, const void* x, const void
   const EvalBwdWs w = carve_eval_bwd(g, dt, ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (g.act & CONVBN_ACT_RELU_IN) g.post_mask = x;   // dx comes out masked with x > 0
+  g.post_add = g.add_in;                             // ... after the addend
   // dY = s dZ, partial per-channel sums of dZ and dZ (Y-mu)/sqrt(var+eps)
   LAUNCH(launch_bn_bwd(g, dt, dz, y_saved, gamma, mean, var, w.dy, w.bn_part, st));
   if (params) LAUNCH(launch_bn_bwd_finalize(g, w.bn_part, w.nparts, gamma, var, dgamma, dbeta, db, st));
@@ -1219,7 +1229,7 @@ convbn_status convbn_tune_fwd_scale_epilogue(const convbn_desc* desc, const void
   const int dt = desc->dtype;
   const BnEpilogue bn{gamma, beta, mean, var, b, g.eps, nullptr, g.kH * g.kW, g.Cin, g.Cout};
   hipStream_t st = static_cast<hipStream_t>(stream);
-  g.post_relu = g.act & CONVBN_ACT_RELU_OUT;
+  g.post_relu = g.act & CONVBN_ACT_RELU_OUT; g.post_add = g.add_out;
   const size_t nz = (size_t)g.M * g.Cout;
   // Z = s (w (*) X) + b': the unfolded weight goes straight into the convolution, one launch in all
   if (!needs_cin_pad(g, dt) && !pw_fprop_supported(g, dt) && rw_fprop_supported(g, dt)) {
@@ -1367,7 +1377,7 @@ convbn_status convbn_conv_fprop(const convbn_desc* desc, const void* x, const vo
   REQUIRE_PTR(x); REQUIRE_PTR(w); REQUIRE_PTR(z); OPTIONAL_PTR(bias);
   s = check_ws(fprop_scratch_bytes(g, desc->dtype), ws, ws_bytes);
   if (s != CONVBN_OK) return s;
-  g.post_relu = g.act & CONVBN_ACT_RELU_OUT;
+  g.post_relu = g.act & CONVBN_ACT_RELU_OUT; g.post_add = g.add_out;
   LAUNCH(run_fprop(g, desc->dtype, x, w, bias, z, (float*)ws, static_cast<hipStream_t>(stream)));
   return CONVBN_OK;
 }
@@ -1380,6 +1390,7 @@ convbn_status convbn_conv_dgrad(const convbn_desc* desc, const void* dz, const v
   REQUIRE_PTR(dz); REQUIRE_PTR(w_t); REQUIRE_PTR(dx);
   s = check_ws(dgrad_scratch_bytes(g, desc->dtype), ws, ws_bytes);
   if (s != CONVBN_OK) return s;
+  g.post_add = g.add_in;
   LAUNCH(run_dgrad(g, desc->dtype, dz, w_t, dx, (float*)ws, static_cast<hipStream_t>(stream)));
   return CONVBN_OK;
 }
@@ -1392,7 +1403,7 @@ convbn_status convbn_conv_dgrad_masked(const convbn_desc* desc, const void* dz, 
   REQUIRE_PTR(dz); REQUIRE_PTR(w_t); REQUIRE_PTR(x); REQUIRE_PTR(dx);
   s = check_ws(dgrad_scratch_bytes(g, desc->dtype), ws, ws_bytes);
   if (s != CONVBN_OK) return s;
-  g.post_mask = x;
+  g.post_mask = x; g.post_add = g.add_in;
   LAUNCH(run_dgrad(g, desc->dtype, dz, w_t, dx, (float*)ws, static_cast<hipStream_t>(stream)));
   return CONVBN_OK;
 }

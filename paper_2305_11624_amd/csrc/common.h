@@ -48,9 +48,13 @@ struct Geom {
   float eps;
   int act;    // the descriptor's CONVBN_ACT_* bits
   // What the convolution launched with this Geom does to its output on the way out (set per call by the host side,
-  // not part of the problem): ReLU, and / or zero where `post_mask` (a tensor laid out like the output) is <= 0.
+  // not part of the problem): `post_add` (a tensor laid out like the output, or null) is added first, then ReLU, and /
+  // or zero where `post_mask` (a tensor laid out like the output) is <= 0.
   int post_relu;
   const void* post_mask;
+  const void* post_add;
+  const void* add_out;   // the descriptor's addends (CONVBN_ACT_ADD_OUT / _IN), null where the bit is not set
+  const void* add_in;
 };
 
 // The same on 8 packed bf16 values: max(., 0), and zero where the 8 packed bf16 values of m4 are <= 0.
@@ -74,10 +78,23 @@ __device__ __forceinline__ uint4 mask8(uint4 v, uint4 m4) {
   }
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
-// ... about to be stored at element offset o of the output, the mask read on the spot.  (Requesting the mask values
+// v + a on 8 packed bf16 values each, added in fp32 and rounded once: what the element-wise sum of the two rounded
+// tensors gives.
+__device__ __forceinline__ uint4 add8(uint4 v, uint4 a4) {
+  const unsigned w[4] = {v.x, v.y, v.z, v.w};
+  const unsigned a[4] = {a4.x, a4.y, a4.z, a4.w};
+  unsigned r[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    r[i] = pack_bf16x2(__uint_as_float(w[i] << 16) + __uint_as_float(a[i] << 16),
+                       __uint_as_float(w[i] & 0xffff0000u) + __uint_as_float(a[i] & 0xffff0000u));
+  return make_uint4(r[0], r[1], r[2], r[3]);
+}
+// ... about to be stored at element offset o of the output, the addend and the mask read on the spot.  (Requesting the mask values
 // before the multiplies was measured on all four kernels that use this and changed nothing: what the mask costs them
 // is its bytes, not the wait.)
-__device__ __forceinline__ uint4 post_op8(uint4 v, int relu, const bf16_t* mask, size_t o) {
+__device__ __forceinline__ uint4 post_op8(uint4 v, int relu, const bf16_t* mask, const bf16_t* add, size_t o) {
+  if (add) v = add8(v, *reinterpret_cast<const uint4*>(add + o));
   if (relu) v = relu8(v);
   if (mask) v = mask8(v, *reinterpret_cast<const uint4*>(mask + o));
   return v;

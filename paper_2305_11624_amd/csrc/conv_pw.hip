@@ -48,6 +48,7 @@ struct PwParams {
   bf16_t* out;           // [M][R]
   int relu;              // the output leaves as max(., 0)
   const bf16_t* mask;    // not null: [M][R], the output is zeroed where this is <= 0
+  const bf16_t* add;     // not null: [M][R], added to the (rounded) output before the ReLU and the mask
   unsigned act_bytes, wgt_bytes;
   int M, C, R;
   int ntr;               // channel tiles
@@ -203,6 +204,32 @@ __global__ __launch_bounds__(64 * NW) void conv_pw_kernel(PwParams p) {
   };
 
   int c = 0, m0 = grp * TP;                                    // chunk and first pixel of the current step
+
+  // Where this lane's 16 bytes of epilogue store (rp, i) go: element offset into out, or -1 past the tensor.  Row
+  // i * 8 + lane / 8 of the wave's 32 pixels, granule (lane % 8) ^ swizzle of the 64-channel pair rp.
+  auto out_off = [&](int rp, int i, int m_first) -> long long {
+    const int row = i * 8 + (lane >> 3);
+    const int g = (lane & 7) ^ ((row >> 1) & 7);
+    const int pi = wave * 32 + row;
+    const int ch = r0 + rp * 64 + g * 8;
+    if (pi >= min(TP, p.M - m_first) || ch >= p.R) return -1;
+    size_t o = (size_t)(m_first + pi) * p.R + ch;
+    if (p.d2s_co > 0) {
+      const int tap = pdiv(r0 + rp * 64, p.d_co);          // the whole 64-channel block is one tap's
+      const int ta = pdiv(tap, p.d_kw), tb = tap - ta * p.d2s_kw;
+      const int m = m_first + pi;
+      const int n = pdiv(m, p.d_HW), rem = m - n * (p.d2s_H * p.d2s_W);
+      const int h = pdiv(rem, p.d_W), w = rem - h * p.d2s_W;
+      o = (((size_t)n * (p.d2s_H * p.d2s_kh) + h * p.d2s_kh + ta) * (p.d2s_W * p.d2s_kw) + w * p.d2s_kw + tb) *
+              p.d2s_co + (ch - tap * p.d2s_co);
+    }
+    return (long long)o;
+  };
+  // The addend and the mask of a tile's outputs are requested when the tile's last chunk begins, a step before
+  // the epilogue needs them: loads return in order, so a load issued in the epilogue itself would wait for every
+  // copy of the following steps that is already in flight -- the ring would drain once per tile.
+  const bool has_post = p.add != nullptr || p.mask != nullptr;
+  uint4 addv[NCH / 2][4], maskv[NCH / 2][4];
   wait_vm<(DIST - 1) * APW>();   // the weights and the slab of step 0 have landed
   __syncthreads();               // (the bias too)
   load_frags(0, 0, 0, 0);
@@ -214,6 +241,16 @@ __global__ __launch_bounds__(64 * NW) void conv_pw_kernel(PwParams p) {
     const int nc = tile_end ? 0 : c + 1;
     wait_vm<(DIST - 2) * APW>();
     block_barrier();   // the next step's slab is resident for every wave; the previous step's slot is free
+    if (tile_end && has_post) {
+#pragma unroll
+      for (int rp = 0; rp < NCH / 2; ++rp)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const long long o = out_off(rp, i, m0);
+          addv[rp][i] = (p.add && o >= 0) ? *reinterpret_cast<const uint4*>(p.add + o) : make_uint4(0u, 0u, 0u, 0u);
+          maskv[rp][i] = (p.mask && o >= 0) ? *reinterpret_cast<const uint4*>(p.mask + o) : make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       if (kk + 1 < KK) load_frags((kk + 1) & 1, S * SLOT, c * CB * 2, kk + 1);
@@ -237,7 +274,6 @@ __global__ __launch_bounds__(64 * NW) void conv_pw_kernel(PwParams p) {
       // cover one pixel's 128 contiguous bytes.
       unsigned char* const st = stage + wave * 4096;
       const int px = lane & 31, psw = (px >> 1) & 7;
-      const int len = min(TP, p.M - m0);
 #pragma unroll
       for (int rp = 0; rp < NCH / 2; ++rp) {
 #pragma unroll
@@ -264,21 +300,12 @@ __global__ __launch_bounds__(64 * NW) void conv_pw_kernel(PwParams p) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int row = i * 8 + (lane >> 3);
-          const int g = (lane & 7) ^ ((row >> 1) & 7);
-          const uint4 v = *reinterpret_cast<const uint4*>(st + row * 128 + ((lane & 7) << 4));
-          const int pi = wave * 32 + row;
-          const int ch = r0 + rp * 64 + g * 8;
-          size_t o = (size_t)(m0 + pi) * p.R + ch;
-          if (p.d2s_co > 0) {
-            const int tap = pdiv(r0 + rp * 64, p.d_co);          // the whole 64-channel block is one tap's
-            const int ta = pdiv(tap, p.d_kw), tb = tap - ta * p.d2s_kw;
-            const int m = m0 + pi;
-            const int n = pdiv(m, p.d_HW), rem = m - n * (p.d2s_H * p.d2s_W);
-            const int h = pdiv(rem, p.d_W), w = rem - h * p.d2s_W;
-            o = (((size_t)n * (p.d2s_H * p.d2s_kh) + h * p.d2s_kh + ta) * (p.d2s_W * p.d2s_kw) + w * p.d2s_kw + tb) *
-                    p.d2s_co + (ch - tap * p.d2s_co);
-          }
-          if (pi < len && ch < p.R) *reinterpret_cast<uint4*>(p.out + o) = post_op8(v, p.relu, p.mask, o);
+          uint4 v = *reinterpret_cast<const uint4*>(st + row * 128 + ((lane & 7) << 4));
+          const long long o = out_off(rp, i, m0);
+          if (p.add) v = add8(v, addv[rp][i]);
+          if (p.relu) v = relu8(v);
+          if (p.mask) v = mask8(v, maskv[rp][i]);
+          if (o >= 0) *reinterpret_cast<uint4*>(p.out + o) = v;
         }
       }
       m0 += tile_stride;
@@ -431,7 +458,7 @@ hipError_t launch_fprop_pw(const Geom& g, const void* x, const void* w_krsc, con
   if (!pl.ok) return hipErrorInvalidValue;
   if (bn) p.bn = *bn;
   p.act = (const bf16_t*)x; p.wgt = (const bf16_t*)w_krsc; p.bias = bias; p.out = (bf16_t*)z;
-  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask; p.add = (const bf16_t*)g.post_add;
   return launch_plan(p, pl, st);
 }
 hipError_t launch_dgrad_pw(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
@@ -440,7 +467,7 @@ hipError_t launch_dgrad_pw(const Geom& g, const void* dz, const void* w_crsk, co
   const PwPlan pl = make_plan(p);
   if (!pl.ok) return hipErrorInvalidValue;
   p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
-  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask; p.add = (const bf16_t*)g.post_add;
   return launch_plan(p, pl, st);
 }
 

@@ -41,7 +41,7 @@ hipError_t launch_fprop_rw(const Geom& g, const void* x, const void* w_krsc, con
   if (!fprop_params(g, &p)) return hipErrorInvalidValue;
   if (bn) p.bn = *bn;
   p.act = (const bf16_t*)x; p.wgt = (const bf16_t*)w_krsc; p.bias = bias; p.out = (bf16_t*)z;
-  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask; p.add = (const bf16_t*)g.post_add;
   return launch(p, st);
 }
 hipError_t launch_dgrad_rw(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
@@ -49,7 +49,7 @@ hipError_t launch_dgrad_rw(const Geom& g, const void* dz, const void* w_crsk, co
   RwParams p;
   if (!dgrad_params(g, &p)) return hipErrorInvalidValue;
   p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
-  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask; p.add = (const bf16_t*)g.post_add;
   return launch(p, st);
 }
 

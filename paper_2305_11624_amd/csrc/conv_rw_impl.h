@@ -78,6 +78,7 @@ struct RwParams {
   bf16_t* out;
   int relu;                       // the output leaves as max(., 0)
   const bf16_t* mask;             // not null: laid out like out, the output is zeroed where this is <= 0
+  const bf16_t* add;              // not null: laid out like out, added to the (rounded) output before the ReLU and the mask
   unsigned act_bytes, wgt_bytes;
   int N, H, W;
   int act_n_stride, act_h_stride, act_w_stride;   // elements
@@ -208,7 +209,7 @@ __device__ __forceinline__ void run_wave(const RwParams& p, unsigned char* smem,
         const auto hi = __builtin_amdgcn_permlane32_swap(pk[0][1], pk[1][1], false, false);
         if (pi < len) {
           const size_t o = (size_t)(m0 + pi) * CH + (4 * i + 2 * j + kb) * 8;
-          *reinterpret_cast<uint4*>(p.out + o) = post_op8(make_uint4(lo[0], hi[0], lo[1], hi[1]), p.relu, p.mask, o);
+          *reinterpret_cast<uint4*>(p.out + o) = post_op8(make_uint4(lo[0], hi[0], lo[1], hi[1]), p.relu, p.mask, p.add, o);
         }
       }
   }

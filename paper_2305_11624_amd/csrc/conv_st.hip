@@ -106,6 +106,7 @@ struct StParams {
   bf16_t* out;
   int relu;                       // the output leaves as max(., 0)
   const bf16_t* mask;             // not null: laid out like out, the output is zeroed where this is <= 0
+  const bf16_t* add;              // not null: laid out like out, added to the (rounded) output before the ReLU and the mask
   unsigned act_bytes, wgt_bytes;
   int N, H, W, C;
   int act_n_stride, act_h_stride, act_w_stride;   // elements
@@ -405,7 +406,7 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_st_kernel(StParams p) {
       const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 64 + ((lane & 3) << 4));
       (void)pss;
       const long long o = store_off(it);
-      if (o >= 0) *reinterpret_cast<uint4*>(p.out + o) = post_op8(v, p.relu, p.mask, (size_t)o);
+      if (o >= 0) *reinterpret_cast<uint4*>(p.out + o) = post_op8(v, p.relu, p.mask, p.add, (size_t)o);
     }
   }
   STAMP(126);
@@ -529,7 +530,7 @@ hipError_t launch_fprop_st(const Geom& g, const void* x, const void* w_krsc, con
   if (!fprop_params(g, &p)) return hipErrorInvalidValue;
   if (bn) p.bn = *bn;
   p.act = (const bf16_t*)x; p.wgt = (const bf16_t*)w_krsc; p.bias = bias; p.out = (bf16_t*)z;
-  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask; p.add = (const bf16_t*)g.post_add;
   return launch(p, st);
 }
 hipError_t launch_dgrad_st(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
@@ -537,7 +538,7 @@ hipError_t launch_dgrad_st(const Geom& g, const void* dz, const void* w_crsk, co
   StParams p;
   if (!dgrad_params(g, &p)) return hipErrorInvalidValue;
   p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
-  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask; p.add = (const bf16_t*)g.post_add;
   return launch(p, st);
 }
 

@@ -59,6 +59,7 @@ struct TileParams {
   bf16_t* out;           // [M][R]
   int relu;              // the output leaves as max(., 0)
   const bf16_t* mask;    // not null: laid out like out, the output is zeroed where this is <= 0
+  const bf16_t* add;     // not null: laid out like out, added to the (rounded) output before the ReLU and the mask
   unsigned act_bytes, wgt_bytes;
   int N, H, W, C;        // activation grid the window slides over
   int act_n_stride, act_h_stride, act_w_stride;
@@ -518,7 +519,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
         const uint4 v = *reinterpret_cast<const uint4*>(stage + row * 128 + ((lane & 7) << 4));
         (void)g; (void)pbase;
         const long long o = store_off(rp, i);
-        if (o >= 0) *reinterpret_cast<uint4*>(p.out + o) = post_op8(v, p.relu, p.mask, (size_t)o);
+        if (o >= 0) *reinterpret_cast<uint4*>(p.out + o) = post_op8(v, p.relu, p.mask, p.add, (size_t)o);
       }
     }
   }
@@ -738,6 +739,7 @@ hipError_t launch_inst(const TileParams& p, const TilePlan& pl, hipStream_t st) 
   hipLaunchKernelGGL(reduce_partials_kernel, dim3(rblocks), dim3(256), 0, st, p.part, p.ksplit, MR, p.R, p.bias, p.out);
   le = hipGetLastError();
   // split sums: the reduction wrote the output, ReLU and mask follow as passes of their own
+  if (le == hipSuccess && p.add) le = launch_eltwise(3 /* a + b */, CONVBN_BF16, p.out, p.add, nullptr, MR, st);
   if (le == hipSuccess && p.relu) le = launch_eltwise(0, CONVBN_BF16, p.out, nullptr, nullptr, MR, st);
   if (le == hipSuccess && p.mask) le = launch_eltwise(1, CONVBN_BF16, p.out, p.mask, nullptr, MR, st);
   return le;
@@ -938,7 +940,7 @@ hipError_t launch_fprop_tile(const Geom& g, const void* x, const void* w_krsc, c
   if (bn && !scaled_plan(pl)) return hipErrorInvalidValue;
   if (bn) p.bn = *bn;
   p.act = (const bf16_t*)x; p.wgt = (const bf16_t*)w_krsc; p.bias = bias; p.out = (bf16_t*)z;
-  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask; p.add = (const bf16_t*)g.post_add;
   p.part = partials;
   return launch_plan(p, pl, st);
 }
@@ -950,6 +952,8 @@ hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, 
     bool zero_first = false;
     for (int a = 0; a < g.sh; ++a)
       for (int b = 0; b < g.sw; ++b) zero_first |= dgrad_class_params(g, a, b, &p) == CLASS_ZERO;
+    // an addend also reaches the positions no tap does: then the whole post-operation follows as passes of its own
+    const bool defer = zero_first && g.post_add != nullptr;
     if (zero_first) {   // positions no tap reaches hold the bias alone: fill dX once, the other classes overwrite theirs
       const size_t n16 = (size_t)g.Min * g.Cin * 2 / 16;
       const int blocks = (int)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
@@ -963,18 +967,26 @@ hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, 
         const TilePlan pl = make_plan(p);
         if (!pl.ok) return hipErrorInvalidValue;
         p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
-        p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
+        p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask; p.add = (const bf16_t*)g.post_add;
+        if (defer) { p.relu = 0; p.mask = nullptr; p.add = nullptr; }
         p.part = nullptr;
         hipError_t e = launch_plan(p, pl, st);
         if (e != hipSuccess) return e;
       }
+    if (defer) {
+      const size_t n = (size_t)g.Min * g.Cin;
+      hipError_t e = launch_eltwise(3 /* a + b */, CONVBN_BF16, dx, g.post_add, nullptr, n, st);
+      if (e == hipSuccess && g.post_relu) e = launch_eltwise(0, CONVBN_BF16, dx, nullptr, nullptr, n, st);
+      if (e == hipSuccess && g.post_mask) e = launch_eltwise(1, CONVBN_BF16, dx, g.post_mask, nullptr, n, st);
+      return e;
+    }
     return hipSuccess;
   }
   dgrad_params(g, &p);
   const TilePlan pl = make_plan(p);
   if (p.ksplit > 1 && !partials) return hipErrorInvalidValue;
   p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
-  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask;
+  p.relu = g.post_relu; p.mask = (const bf16_t*)g.post_mask; p.add = (const bf16_t*)g.post_add;
   p.part = partials;
   return launch_plan(p, pl, st);
 }

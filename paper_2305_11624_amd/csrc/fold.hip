@@ -450,7 +450,7 @@ __global__ __launch_bounds__(256) void bn_affine_fwd_kernel(const T* __restrict_
 __global__ __launch_bounds__(256) void bn_affine_fwd_bf16x8_kernel(
     const uint4* __restrict__ y, const float* __restrict__ gamma, const float* __restrict__ beta,
     const float* __restrict__ mean, const float* __restrict__ var, float eps, size_t nvec, int Cout,
-    uint4* __restrict__ z, int relu) {
+    uint4* __restrict__ z, int relu, const uint4* __restrict__ add) {
   extern __shared__ float sm[];
   float* s_s = sm;
   float* s_t = sm + Cout;
@@ -471,8 +471,9 @@ __global__ __launch_bounds__(256) void bn_affine_fwd_bf16x8_kernel(
       const int c = co + 2 * e;
       o[e] = pack_bf16x2(bf16_lo(w[e]) * s_s[c] + s_t[c], bf16_hi(w[e]) * s_s[c + 1] + s_t[c + 1]);
     }
-    const uint4 r = make_uint4(o[0], o[1], o[2], o[3]);
-    z[i] = relu ? relu8(r) : r;   // (a ReLU behind the block: the descriptor's activation bit)
+    uint4 r = make_uint4(o[0], o[1], o[2], o[3]);
+    if (add) r = add8(r, add[i]);   // (an addend and a ReLU behind the block: the descriptor's activation bits)
+    z[i] = relu ? relu8(r) : r;
   }
 }
 
@@ -743,7 +744,7 @@ hipError_t launch_bn_affine_fwd(const Geom& g, int dtype, const void* y, const f
     const size_t nvec = total / 8;
     const int blocks = (int)min((size_t)2048, (nvec + 255) / 256);
     hipLaunchKernelGGL(bn_affine_fwd_bf16x8_kernel, dim3(blocks), dim3(256), 2 * g.Cout * sizeof(float), st, (const uint4*)y,
-                       gamma, beta, mean, var, g.eps, nvec, g.Cout, (uint4*)z, g.post_relu);
+                       gamma, beta, mean, var, g.eps, nvec, g.Cout, (uint4*)z, g.post_relu, (const uint4*)g.post_add);
   } else {
     const int blocks = (int)min((size_t)4096, (total + 255) / 256);
     if (dtype == CONVBN_BF16)
@@ -752,6 +753,10 @@ hipError_t launch_bn_affine_fwd(const Geom& g, int dtype, const void* y, const f
     else
       hipLaunchKernelGGL(bn_affine_fwd_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)y,
                          gamma, beta, mean, var, g.eps, total, g.Cout, (float*)z);
+    if (g.post_add && hipGetLastError() == hipSuccess) {
+      const hipError_t e = launch_eltwise(3 /* a + b */, dtype, z, g.post_add, nullptr, total, st);
+      if (e != hipSuccess) return e;
+    }
     if (g.post_relu && hipGetLastError() == hipSuccess) return launch_eltwise(0 /* max(a, 0) */, dtype, z, nullptr, nullptr, total, st);
   }
   return hipGetLastError();

@@ -820,7 +820,7 @@ hipError_t launch_wgrad_dgrad_pair(const Geom& g, const void* x, const void* dz,
   if (!pl.ok || pl.ks != 2 || !rw::dgrad_params(g, &pr) || (size_t)pr.lds_bytes > LDS_USABLE) return hipErrorInvalidValue;
   ps.x = (const bf16_t*)x; ps.dz = (const bf16_t*)dz; ps.part = dwf_part; ps.r_part = r_part;
   pr.act = (const bf16_t*)dz; pr.wgt = (const bf16_t*)w_crsk; pr.bias = nullptr; pr.out = (bf16_t*)dx;
-  pr.relu = g.post_relu; pr.mask = (const bf16_t*)g.post_mask;
+  pr.relu = g.post_relu; pr.mask = (const bf16_t*)g.post_mask; pr.add = (const bf16_t*)g.post_add;
 #define CASE(X) if (pl.ncpy == 2 + X) return launch_pair_inst<2, 2 + X>(ps, pl, pr, st);
   CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6)
 #undef CASE

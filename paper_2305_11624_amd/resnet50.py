@@ -19,7 +19,8 @@ class _Block:
         self.shape, self.mode = shape, mode
         p = synth.make_params(shape)
         self.desc = B.desc_from_shape(shape, eps=p["eps"])
-        self.desc.act = act   # the ReLUs next to the block that its convolutions apply on the way out
+        self.act = act        # the ReLUs next to the block that its convolutions apply on the way out
+        self.desc.act = act
         dt = B.torch_dtype(self.desc)
         self.dt = dt
         self.W = B.weight_to_device(p["W"], dt, device)
@@ -36,10 +37,23 @@ class _Block:
         self.grouped = None      # buffers of the network's grouped fold (Tune mode, optional)
         self.unit = None         # buffers of this block inside its unit's grouped fold / fold-back (Tune mode)
 
-    def forward(self, x, ws):
+    def forward(self, x, ws, add=None):
+        """add: the other branch of a residual sum that joins behind this block; the block then returns
+        max(z + add, 0) (the descriptor's addend and ReLU bits, for this call)."""
         s = self.shape
         z = torch.empty((s.N, s.Hout, s.Wout, s.Cout), dtype=self.dt, device=x.device)
         self.x = x
+        if add is not None:
+            B.set_addends(self.desc, add_out=add)
+            self.desc.act = self.act | B.ACT_ADD_OUT | B.ACT_RELU_OUT
+        try:
+            return self._forward(x, z, ws)
+        finally:
+            self.desc.act = self.act
+            B.set_addends(self.desc)
+
+    def _forward(self, x, z, ws):
+        s = self.shape
         if self.unit is not None:
             # w' of this block was produced by its unit's grouped fold: only the convolution is left
             B.convbn_conv_fprop(self.desc, x, self.unit["w_fprop"], self.unit["b_folded"], z, ws)
@@ -59,7 +73,19 @@ class _Block:
                               self.saved, ws)
         return z
 
-    def backward(self, dz, ws, need_dx=True):
+    def backward(self, dz, ws, need_dx=True, add=None, relu_in=False):
+        """add: the gradient that reaches this block's input through another branch; the block then returns
+        dx + add, zeroed where its input is not positive if relu_in (the input is a ReLU's output)."""
+        if add is not None:
+            B.set_addends(self.desc, add_in=add)
+            self.desc.act = self.act | B.ACT_ADD_IN | (B.ACT_RELU_IN if relu_in else 0)
+        try:
+            return self._backward(dz, ws, need_dx)
+        finally:
+            self.desc.act = self.act
+            B.set_addends(self.desc)
+
+    def _backward(self, dz, ws, need_dx):
         dx = torch.empty_like(self.x) if need_dx else None
         if self.unit is not None and not self.unit["fused"]:
             # this block's fold-back runs with its unit's, in one launch: only the two gradient convolutions here
@@ -81,7 +107,8 @@ class _Block:
 
 class ResNet50:
     def __init__(self, N: int = 32, image: int = 224, dtype: str = "bf16", mode: str = "tune",
-                 device: str = "cuda", group_fold: bool = False, group_units: bool = False):
+                 device: str = "cuda", group_fold: bool = False, group_units: bool = False,
+                 fuse_residual: bool = True):
         """group_fold (Tune mode): fold all blocks in one launch at the start of forward instead of one
         launch per block.  Faster, but every w' (in both orders) then lives for the whole step.
         group_units (Tune mode): one fold launch and one fold-back launch per bottleneck unit (its three or four
@@ -89,6 +116,9 @@ class ResNet50:
         the largest unit."""
         assert mode in ("tune", "eval")
         self.N, self.image, self.mode, self.device = N, image, mode, device
+        # the residual sum of a unit (and the ReLU behind it) applied by the unit's last convolution, the sum of the two
+        # gradient branches at its input (and that ReLU's backward) by the first block's input gradient -- both modes
+        self.fuse_residual = fuse_residual
         self.group_fold = group_fold and mode == "tune"
         self.group_units = group_units and mode == "tune" and not self.group_fold
         self._group = None
@@ -249,10 +279,13 @@ class ResNet50:
                     B.convbn_fold_group(*self.units[name]["fold"])
                 a = bl[name + ".a"].forward(cur, ws)     # (ReLU applied by the block: its act bits)
                 b = bl[name + ".b"].forward(a, ws)
-                c_ = bl[name + ".c"].forward(b, ws)
                 has_ds = (name + ".ds") in bl
                 sc = bl[name + ".ds"].forward(cur, ws) if has_ds else cur
-                B.convbn_aux_eltwise(B.OP_ADD_RELU, c_, sc)
+                if self.fuse_residual:
+                    c_ = bl[name + ".c"].forward(b, ws, add=sc)   # max(z + shortcut, 0) on the convolution's way out
+                else:
+                    c_ = bl[name + ".c"].forward(b, ws)
+                    B.convbn_aux_eltwise(B.OP_ADD_RELU, c_, sc)
                 tape["units"].append((name, has_ds, a, b, c_))
                 del sc
                 cur = c_
@@ -270,15 +303,21 @@ class ResNet50:
             gb = bl[name + ".c"].backward(g, ws)     # (masked with b > 0 by the block: its act bits)
             ga = bl[name + ".b"].backward(gb, ws)    # (masked with a > 0)
             del gb
-            gin = bl[name + ".a"].backward(ga, ws)
-            del ga
             # the two branches meet at the unit's input, which is the output of the previous unit's ReLU (of the
-            # max-pool for the first unit): sum and ReLU backward in one pass
-            other = bl[name + ".ds"].backward(g, ws) if has_ds else g
-            if i + 1 < len(order):
-                B.convbn_aux_add_relu_bwd(gin, other, order[i + 1][4])
+            # max-pool for the first unit): sum and ReLU backward on the way out of the first block's input gradient,
+            # or in one element-wise pass
+            if self.fuse_residual:
+                other = bl[name + ".ds"].backward(g, ws) if has_ds else g
+                gin = bl[name + ".a"].backward(ga, ws, add=other, relu_in=i + 1 < len(order))
+                del ga
             else:
-                B.convbn_aux_eltwise(B.OP_ADD, gin, other)
+                gin = bl[name + ".a"].backward(ga, ws)
+                del ga
+                other = bl[name + ".ds"].backward(g, ws) if has_ds else g
+                if i + 1 < len(order):
+                    B.convbn_aux_add_relu_bwd(gin, other, order[i + 1][4])
+                else:
+                    B.convbn_aux_eltwise(B.OP_ADD, gin, other)
             del other
             if self.units is not None and self.units[name]["back"] is not None:
                 B.convbn_fold_back_group(*self.units[name]["back"])   # dW, dgamma, dbeta of the unit's blocks

@@ -16,12 +16,15 @@ class BlockRun:
     """
 
     def __init__(self, inp: Dict[str, object], mode: str = "tune", keep_folded: bool = True,
-                 need_dx: bool = True, device: str = "cuda", poison: bool = False, act: int = 0):
+                 need_dx: bool = True, device: str = "cuda", poison: bool = False, act: int = 0,
+                 add_out=None, add_in=None):
         assert mode in ("tune", "eval")
         s = inp["shape"]
         self.shape, self.mode, self.keep_folded, self.need_dx = s, mode, keep_folded, need_dx
         self.desc = B.desc_from_shape(s, eps=inp["eps"])
-        self.desc.act = act   # binding.ACT_* bits: a ReLU behind and / or in front of the block
+        self.desc.act = act   # binding.ACT_* bits: a ReLU and / or a residual sum behind and / or in front of the block
+        self.add_out, self.add_in = add_out, add_in   # device tensors of the ACT_ADD_* bits (kept alive here)
+        B.set_addends(self.desc, add_out, add_in)
         dt = B.torch_dtype(self.desc)
         self.dt = dt
         self.x = B.act_to_device(inp["x"], dt, device)

@@ -90,3 +90,63 @@ def test_step_entry_points_with_activation(shape):
     assert torch.equal(z0, z1)
     assert torch.equal(dx0, dx1)
     assert (z1.float() >= 0).all() and (dx1.float()[r.x.float() <= 0] == 0).all()
+
+
+def _addends(shape, run_like):
+    """Seeded tensors laid out like z and dx (a shortcut branch and the gradient of a second consumer of x)."""
+    g = torch.Generator().manual_seed(shape.seed + 7000)
+    a_out = torch.randn((shape.N, shape.Cout, shape.Hout, shape.Wout), generator=g, dtype=torch.float32)
+    a_in = torch.randn((shape.N, shape.Cin, shape.Hin, shape.Win), generator=g, dtype=torch.float32)
+    if shape.dtype == "bf16":
+        a_out, a_in = a_out.bfloat16().float(), a_in.bfloat16().float()
+    dev = "cuda"
+    return (a_out, a_in, B.act_to_device(a_out, run_like, dev), B.act_to_device(a_in, run_like, dev))
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: s.name)
+@pytest.mark.parametrize("mode,keep", [("tune", True), ("tune", False), ("eval", True)],
+                         ids=["tune_keeps_w", "tune_keeps_nothing", "eval"])
+@pytest.mark.parametrize("relu", [True, False], ids=["add_relu", "add_only"])
+def test_residual_addends_against_oracle_and_unfused_calls(shape, mode, keep, relu):
+    """ACT_ADD_OUT / ACT_ADD_IN: a residual sum behind the block and a second gradient branch at its input, with and
+    without the ReLU bits.  Reference: the oracle's block with the addends applied to its Z and dX in fp64; and, bit for
+    bit, the plain calls followed by the stand-alone element-wise kernels."""
+    from paper_2305_11624_amd.runner import BlockRun
+    inp = _inputs(shape)
+    dt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    a_out, a_in, d_out, d_in = _addends(shape, dt)
+    ref = oracle_block(inp)
+    x = inp["x"].double().numpy()
+    ref["Z"] = ref["Z"] + a_out.double().numpy()
+    ref["dX"] = ref["dX"] + a_in.double().numpy()
+    if relu:
+        ref["Z"] = np.maximum(ref["Z"], 0)
+        ref["dX"] = ref["dX"] * (x > 0)
+    act = B.ACT_ADD_OUT | B.ACT_ADD_IN | (BOTH if relu else 0)
+    run = BlockRun(inp, mode=mode, keep_folded=keep, poison=True, act=act, add_out=d_out, add_in=d_in)
+    run.step()
+    got = run.results()
+    compare(got, ref, shape.dtype, tag=shape.name + "/" + mode + ("/relu" if relu else ""))
+
+    plain = BlockRun(inp, mode=mode, keep_folded=keep, poison=True, act=0)
+    plain.step()
+    if relu:
+        B.convbn_aux_eltwise(B.OP_ADD_RELU, plain.z, d_out)
+        B.convbn_aux_add_relu_bwd(plain.dx, d_in, plain.x)
+    else:
+        B.convbn_aux_eltwise(B.OP_ADD, plain.z, d_out)
+        B.convbn_aux_eltwise(B.OP_ADD, plain.dx, d_in)
+    want = plain.results()
+    for k in ("Z", "dX", "dW", "dgamma", "dbeta", "db"):
+        assert torch.equal(got[k], want[k]), k
+
+
+def test_addend_bit_without_a_tensor_is_refused():
+    from paper_2305_11624_amd.runner import BlockRun
+    run = BlockRun(_inputs(SHAPES[0]), mode="tune")
+    run.desc.act = B.ACT_ADD_OUT
+    with pytest.raises(B.ConvBNError):
+        run.forward()
+    run.desc.act = B.ACT_ADD_IN
+    with pytest.raises(B.ConvBNError):
+        run.backward()

@@ -43,7 +43,7 @@ def test_output_size_and_workspace_queries():
 BAD_DESCS = [
     (dict(N=0), B.ERR_SHAPE), (dict(Cin=-1), B.ERR_SHAPE), (dict(stride=0), B.ERR_SHAPE),
     (dict(pad=-1), B.ERR_SHAPE), (dict(kH=9, kW=9, pad=0), B.ERR_SHAPE),
-    (dict(dtype=7), B.ERR_UNSUPPORTED), (dict(layout=1), B.ERR_UNSUPPORTED), (dict(act=4), B.ERR_UNSUPPORTED),
+    (dict(dtype=7), B.ERR_UNSUPPORTED), (dict(layout=1), B.ERR_UNSUPPORTED), (dict(act=16), B.ERR_UNSUPPORTED), (dict(act=4), B.ERR_NULL), (dict(act=8), B.ERR_NULL),
     (dict(N=1 << 20, Hin=64, Win=64), B.ERR_UNSUPPORTED),
 ]
 
