@@ -286,7 +286,8 @@ class ResNet50:
                 else:
                     c_ = bl[name + ".c"].forward(b, ws)
                     B.convbn_aux_eltwise(B.OP_ADD_RELU, c_, sc)
-                tape["units"].append((name, has_ds, a, b, c_))
+                tape["units"].append((name, has_ds, c_))   # (a and b live on as the next blocks' inputs)
+                del a, b
                 del sc
                 cur = c_
         self._tape = tape
@@ -295,9 +296,13 @@ class ResNet50:
     def backward(self, dout: torch.Tensor, need_input_grad: bool = False) -> Optional[torch.Tensor]:
         ws, bl, tape = self.ws, self.blocks, self._tape
         g = dout.clone()
-        order = list(reversed(tape["units"]))
-        B.convbn_aux_eltwise(B.OP_RELU_BWD, g, order[0][4])   # the last unit's ReLU; the others' ride on the adds below
-        for i, (name, has_ds, a, b, out) in enumerate(order):
+        units = tape["units"]
+        B.convbn_aux_eltwise(B.OP_RELU_BWD, g, units[-1][2])   # the last unit's ReLU; the others' ride on the adds below
+        while units:
+            # a unit's entry leaves the tape when its turn comes: its activations are freed as its blocks finish
+            name, has_ds, out = units.pop()
+            del out
+            first = not units   # the first unit's input comes from the max-pool, not from a ReLU
             if self.units is not None and self.units[name]["refold"] is not None:
                 B.convbn_fold_group(*self.units[name]["refold"])   # blocks that kept nothing: w' again, for this unit
             gb = bl[name + ".c"].backward(g, ws)     # (masked with b > 0 by the block: its act bits)
@@ -308,14 +313,14 @@ class ResNet50:
             # or in one element-wise pass
             if self.fuse_residual:
                 other = bl[name + ".ds"].backward(g, ws) if has_ds else g
-                gin = bl[name + ".a"].backward(ga, ws, add=other, relu_in=i + 1 < len(order))
+                gin = bl[name + ".a"].backward(ga, ws, add=other, relu_in=not first)
                 del ga
             else:
                 gin = bl[name + ".a"].backward(ga, ws)
                 del ga
                 other = bl[name + ".ds"].backward(g, ws) if has_ds else g
-                if i + 1 < len(order):
-                    B.convbn_aux_add_relu_bwd(gin, other, order[i + 1][4])
+                if not first:
+                    B.convbn_aux_add_relu_bwd(gin, other, units[-1][2])
                 else:
                     B.convbn_aux_eltwise(B.OP_ADD, gin, other)
             del other
