@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libconvbn.so")
 OBJDIR = os.path.join(HERE, "_build")   # objects and compiler temporaries stay out of the source folder
-SOURCES = ["api.hip", "fold.hip", "fold_t.hip", "depthwise.hip", "conv_grouped.hip", "conv_direct.hip", "conv_igemm.hip", "conv_tile.hip", "conv_st.hip", "conv_rw.hip", "conv_pw.hip", "conv_stem.hip", "wgrad_tile.hip", "wgrad_sq.hip", "aux_ops.hip"]
+SOURCES = ["api.hip", "fold.hip", "fold_t.hip", "depthwise.hip", "conv_grouped.hip", "conv_direct.hip", "conv_igemm.hip", "conv_tile.hip", "conv_st.hip", "conv_rw.hip", "conv_pw.hip", "conv_gm.hip", "conv_stem.hip", "wgrad_tile.hip", "wgrad_sq.hip", "aux_ops.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

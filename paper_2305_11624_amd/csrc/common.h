@@ -279,6 +279,11 @@ hipError_t launch_wgrad_igemm(const Geom& g, const void* x, const void* dz, floa
 // conv_tile.hip : bf16 MFMA convolution with the input window tile resident in LDS
 // (every input element is fetched once per block and reused by all taps).
 // conv_pw.hip: persistent weight-stationary kernel for 1x1 / stride-1 convolutions over long pixel ranges
+// the tiled matrix product that takes the pointwise layers of the middle stages (conv_gm.hip); reached through the
+// pw_* calls below
+bool gm_supported(int M, int C, int R);
+hipError_t launch_gm(int M, int C, int R, const void* act, const void* wgt, const float* bias, const BnEpilogue* bn,
+                     void* out, int relu, const void* mask, const void* add, hipStream_t st);
 bool pw_fprop_supported(const Geom& g, int dtype);
 bool pw_fprop_scaled_supported(const Geom& g, int dtype);     // ... with a BnEpilogue
 bool pw_dgrad_supported(const Geom& g, int dtype);

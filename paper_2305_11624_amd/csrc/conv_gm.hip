@@ -1,0 +1,287 @@
+// Pointwise (1x1, stride 1, unpadded) bf16 convolution of the middle stages as a tiled matrix product
+//     out[m][r] = sum_c act[m][c] wgt[r][c] (+ bias[r]),     m over all N*H*W pixels:
+//   forward conv   Z  = w' (*) X + b'   (Sec. 3.1 / 3.3)   act = x,   wgt = w' as [Cout][Cin]
+//   input gradient dX = w'_rot (*) dZ   (Sec. 3.2.1)       act = dz,  wgt = w' as [Cin][Cout]
+//
+// For a few thousand to a few ten thousand pixels and 128 .. 2048 channels on either side (the 28 x 28, 14 x 14
+// and 7 x 7 stages of a ResNet-50) the product is a few GFLOP over a few tens of MB: one output tile per
+// workgroup, and the tile as large as still fills the chip -- 256 (or 128) pixels x 128 channels, shared by EIGHT
+// waves as 4 (2) pixel groups x 2 channel groups, so that a wave owns 64 x 64 (32 x 64) outputs and reads four
+// (three) operand fragments for four (two) multiplies, and the matrix pipe of every SIMD is fed by two waves.
+// The weight-stationary streaming kernel (conv_pw.hip) stays with the long pixel streams of the first stage.
+//
+// Pipeline.  The reduction runs over 64-channel chunks.  A chunk of the activation tile and of the weight tile
+// is copied global -> LDS directly (1 KB per instruction: 8 rows x 128 bytes) into one of three stages, two chunks
+// ahead; every wave issues the same number of copies per chunk, so "at most that many copies outstanding" means
+// the current chunk has landed; one barrier per chunk.  LDS rows are 128 bytes, unpadded: the copy permutes the
+// eight 16-byte granules of row r by (r / 2) % 8 (it chooses which granule each lane fetches), so that the 128-bit
+// operand reads of 16 consecutive rows fall on distinct banks.  The copies of a chunk are issued between its
+// multiplies; operands are double-buffered in registers one 16-channel step ahead.
+#include "common.h"
+
+namespace convbn {
+
+namespace {
+
+constexpr int NWAVES = 8;
+constexpr int CB = 64;                 // reduced channels per chunk
+constexpr int KK = CB / 16;
+constexpr int TN = 128;                // output channels per workgroup
+constexpr int NSTAGE = 3;
+constexpr unsigned OOB = 0x80000000u;  // beyond any buffer: the load returns zeros
+
+struct GmParams {
+  const bf16_t* act;     // [M][C]
+  const bf16_t* wgt;     // [R][C]
+  const float* bias;     // [R] or null
+  BnEpilogue bn;         // bn.gamma != null: the weight is unfolded, the epilogue applies s and b' (bias unused)
+  bf16_t* out;           // [M][R]
+  int relu;
+  const bf16_t* mask;    // not null: [M][R], the output is zeroed where this is <= 0
+  const bf16_t* add;     // not null: [M][R], added to the (rounded) output before the ReLU and the mask
+  unsigned act_bytes, wgt_bytes;
+  int M, C, R;
+  int ntr;               // channel tiles
+  int nchunks;
+};
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+// 1 KB copy: lane l fetches 16 bytes at voff (per lane, range-checked) + soff (wave-uniform) and writes them to LDS
+// at lds_wave_base + 16 l.  The compiler barrier keeps every copy in the instruction stream: the waits count copies.
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff, void* lds_wave_base) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)lds_wave_base, 16, (int)voff, (int)soff, 0, 0);
+  asm volatile("" ::: "memory");
+}
+__device__ __forceinline__ void block_barrier() {   // no memory fence: that would drain the copies
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vm() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// TM: pixels per workgroup (256: a wave owns 2 x 2 subtiles of 32 x 32; 128: 1 x 2).
+template <int TM>
+struct GmCfg {
+  static constexpr int NPS = TM / 128;                  // 32-pixel subtiles per wave
+  static constexpr int NCS = 2;                         // 32-channel subtiles per wave
+  static constexpr int AUW = TM / 8 / NWAVES;           // activation copies (8 rows each) per wave and chunk
+  static constexpr int WUW = TN / 8 / NWAVES;           // weight copies per wave and chunk
+  static constexpr int CPW = AUW + WUW;
+  static constexpr int STAGE = (TM + TN) * 128;
+  static constexpr int OFF_BIAS = NSTAGE * STAGE;       // [TN] bias, [TN] scale
+  static constexpr int LDS_BYTES = OFF_BIAS + 2 * TN * 4;
+  static_assert(NWAVES * 64 * 64 * 2 <= NSTAGE * STAGE, "the epilogue stages every wave's outputs in the ring");
+};
+
+template <int TM>
+__global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
+  using Cfg = GmCfg<TM>;
+  constexpr int NPS = Cfg::NPS, NCS = Cfg::NCS, AUW = Cfg::AUW, WUW = Cfg::WUW, CPW = Cfg::CPW, STAGE = Cfg::STAGE;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  float* biasl = reinterpret_cast<float*>(smem + Cfg::OFF_BIAS);
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;      // pixel group, channel group
+  const int ctile = blockIdx.x % p.ntr, ptile = blockIdx.x / p.ntr;
+  const int r0 = ctile * TN, m0 = ptile * TM;
+  const __amdgpu_buffer_rsrc_t act_rsrc = make_rsrc(p.act, p.act_bytes);
+  const __amdgpu_buffer_rsrc_t wgt_rsrc = make_rsrc(p.wgt, p.wgt_bytes);
+
+  if (tid < TN) {
+    const int ch = r0 + tid;
+    float bias_v = p.bias ? p.bias[ch] : 0.f, scale_v = 1.f;
+    if (p.bn.gamma) {   // Z = s (w (*) X) + b' (Sec. 3.3), s and b' worked out here
+      scale_v = p.bn.gamma[ch] / sqrtf(p.bn.var[ch] + p.bn.eps);
+      bias_v = ((p.bn.b ? p.bn.b[ch] : 0.f) - p.bn.mean[ch]) * scale_v + p.bn.beta[ch];
+    }
+    biasl[tid] = bias_v;
+    biasl[TN + tid] = scale_v;
+  }
+
+  // ---- copies of this wave: unit u covers rows 8 u .. 8 u + 7 of its tile; lane l writes LDS granule l % 8 of row
+  // 8 u + l / 8 and fetches the granule that belongs there, (l % 8) ^ key(row), key = (row / 2) % 8
+  const int crow = lane >> 3, cpos = lane & 7;
+  unsigned voff_a[AUW], voff_w[WUW];
+#pragma unroll
+  for (int j = 0; j < AUW; ++j) {
+    const int row = (wave + NWAVES * j) * 8 + crow;
+    const int g = cpos ^ ((row >> 1) & 7);
+    voff_a[j] = m0 + row < p.M ? (unsigned)(((size_t)(m0 + row) * p.C + g * 8) * 2) : OOB;   // rows past the last pixel: zeros
+  }
+#pragma unroll
+  for (int j = 0; j < WUW; ++j) {
+    const int row = (wave + NWAVES * j) * 8 + crow;
+    const int g = cpos ^ ((row >> 1) & 7);
+    voff_w[j] = (unsigned)(((size_t)(r0 + row) * p.C + g * 8) * 2);
+  }
+  auto issue_copy = [&](int i, int chunk, unsigned char* stage) {   // copy i (0 .. CPW-1) of a chunk
+    const unsigned soff = (unsigned)(chunk * (CB * 2));
+    if (i < AUW) dma16(act_rsrc, voff_a[i < AUW ? i : 0], soff, stage + (wave + NWAVES * i) * 1024);
+    else dma16(wgt_rsrc, voff_w[i - AUW < WUW ? i - AUW : 0], soff, stage + TM * 128 + (wave + NWAVES * (i - AUW)) * 1024);
+  };
+
+  // ---- operand addresses: row l % 32 of a subtile, granule 2 kk + l / 32 of the chunk, which sits at position
+  // (2 kk + kb) ^ key = (2 kk) ^ (kb ^ key); key depends on l % 32 only (subtiles start at multiples of 32 rows)
+  const int kb = lane >> 5;
+  const int rl = lane & 31;
+  const unsigned lane_off = (unsigned)(rl * 128 + (((kb ^ ((rl >> 1) & 7)) & 7) << 4));
+  unsigned boff[NPS], aoff[NCS];
+#pragma unroll
+  for (int ps = 0; ps < NPS; ++ps) boff[ps] = (unsigned)((wm * (32 * NPS) + ps * 32) * 128) + lane_off;
+#pragma unroll
+  for (int i = 0; i < NCS; ++i) aoff[i] = (unsigned)(TM * 128 + (wn * 64 + i * 32) * 128) + lane_off;
+
+  f32x16 acc[NCS][NPS];
+#pragma unroll
+  for (int i = 0; i < NCS; ++i)
+#pragma unroll
+    for (int ps = 0; ps < NPS; ++ps)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][ps][e] = 0.f;
+
+  bf16x8 fa[2][NCS], fb[2][NPS];
+  auto load_frags = [&](int buf, const unsigned char* stage, int kk) {
+#pragma unroll
+    for (int ps = 0; ps < NPS; ++ps) fb[buf][ps] = *reinterpret_cast<const bf16x8*>(stage + (boff[ps] ^ (unsigned)(kk << 5)));
+#pragma unroll
+    for (int i = 0; i < NCS; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(stage + (aoff[i] ^ (unsigned)(kk << 5)));
+  };
+
+  // ---- prologue: chunks 0 and 1 (a chunk past the end is the last one again, into a stage nobody reads)
+  const int nchunks = p.nchunks;
+#pragma unroll
+  for (int i = 0; i < CPW; ++i) issue_copy(i, 0, smem);
+#pragma unroll
+  for (int i = 0; i < CPW; ++i) issue_copy(i, min(1, nchunks - 1), smem + STAGE);
+
+  int st_cur = 0;   // stage of the current chunk
+  for (int c = 0; c < nchunks; ++c) {
+    wait_vm<CPW>();    // this chunk has landed (the next one's copies may be in flight) ...
+    block_barrier();   // ... for every wave, and everybody is done with the stage refilled below
+    const unsigned char* const stage = smem + st_cur * STAGE;
+    const int st_fill = st_cur >= 1 ? st_cur - 1 : NSTAGE - 1;   // (c + 2) % 3
+    unsigned char* const fill = smem + st_fill * STAGE;
+    const int cf = min(c + 2, nchunks - 1);
+    load_frags(0, stage, 0);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const int cur = kk & 1;
+      if (kk + 1 < KK) load_frags(cur ^ 1, stage, kk + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      // the copies of the chunk two ahead, spread over the multiplies of this one
+      constexpr int PER = (CPW + KK - 1) / KK;
+      int issued = 0;
+#pragma unroll
+      for (int i = 0; i < NCS; ++i)
+#pragma unroll
+        for (int ps = 0; ps < NPS; ++ps) {
+          acc[i][ps] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][ps], acc[i][ps], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (issued < PER && kk * PER + issued < CPW) {
+            issue_copy(kk * PER + issued, cf, fill);
+            ++issued;
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+#pragma unroll
+      for (; issued < PER; ++issued)
+        if (kk * PER + issued < CPW) issue_copy(kk * PER + issued, cf, fill);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    st_cur = st_cur + 1 == NSTAGE ? 0 : st_cur + 1;
+  }
+  wait_vm<0>();      // trailing copies must not outlive the loop: the ring becomes the staging space
+  __syncthreads();   // (and the bias is visible)
+
+  // ---- epilogue.  Accumulator element e of lane l in subtile (i, ps): channel 32 i + 8 (e / 4) + 4 (l / 32) + e % 4,
+  // pixel 32 ps + l % 32 of the wave's block.  Per 32-pixel subtile the wave rounds 32 pixels x 64 channels to bf16
+  // into its own 4 KB ([pixel][64 ch], granules swizzled by pixel) and reads them back row-wise: every store is 16
+  // bytes per lane, eight lanes cover one pixel's 128 contiguous bytes.
+  unsigned char* const st = smem + wave * 4096;
+  const int px = lane & 31, psw = (px >> 1) & 7;
+#pragma unroll
+  for (int ps = 0; ps < NPS; ++ps) {
+#pragma unroll
+    for (int i = 0; i < NCS; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int ch = i * 32 + q * 8 + kb * 4;
+        const float4 bb = *reinterpret_cast<const float4*>(biasl + wn * 64 + ch);
+        const float4 sc = *reinterpret_cast<const float4*>(biasl + TN + wn * 64 + ch);
+        const uint2 v = make_uint2(pack_bf16x2(fmaf(acc[i][ps][q * 4 + 0], sc.x, bb.x), fmaf(acc[i][ps][q * 4 + 1], sc.y, bb.y)),
+                                   pack_bf16x2(fmaf(acc[i][ps][q * 4 + 2], sc.z, bb.z), fmaf(acc[i][ps][q * 4 + 3], sc.w, bb.w)));
+        *reinterpret_cast<uint2*>(st + px * 128 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
+      }
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int row = it * 8 + (lane >> 3);
+      const int g = (lane & 7) ^ ((row >> 1) & 7);
+      const uint4 v = *reinterpret_cast<const uint4*>(st + row * 128 + ((lane & 7) << 4));
+      const int m = m0 + wm * (32 * NPS) + ps * 32 + row;
+      if (m < p.M) {
+        const size_t o = (size_t)m * p.R + r0 + wn * 64 + g * 8;
+        *reinterpret_cast<uint4*>(p.out + o) = post_op8(v, p.relu, p.mask, p.add, o);
+      }
+    }
+  }
+}
+
+constexpr int MIN_TILES = 160;       // fewer output tiles leave too many compute units without one
+constexpr int MAX_PIXELS = 32768;    // longer pixel ranges stream through the weight-stationary kernel
+
+// 0: not taken; else the pixel tile (256 or 128)
+int choose_tile(const GmParams& p) {
+  if (p.C % CB || p.R % TN || p.M > MAX_PIXELS) return 0;
+  if ((size_t)p.M * p.C * 2 >= OOB || (size_t)p.M * p.R * 2 >= OOB || (size_t)p.R * p.C * 2 >= OOB) return 0;
+  const int ntr = p.R / TN;
+  if (ceil_div(p.M, 256) * ntr >= MIN_TILES) return 256;
+  if (ceil_div(p.M, 128) * ntr >= MIN_TILES) return 128;
+  return 0;
+}
+
+template <int TM>
+hipError_t launch_inst(const GmParams& p, hipStream_t st) {
+  static LdsLimitOnce lds_once;
+  if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&conv_gm_kernel<TM>),
+                                        GmCfg<TM>::LDS_BYTES); e != hipSuccess) return e;
+  hipLaunchKernelGGL((conv_gm_kernel<TM>), dim3(ceil_div(p.M, TM) * p.ntr), dim3(64 * NWAVES), GmCfg<TM>::LDS_BYTES, st, p);
+  return hipGetLastError();
+}
+
+GmParams make_params(int M, int C, int R) {
+  GmParams p{};
+  p.M = M; p.C = C; p.R = R;
+  p.act_bytes = (unsigned)((size_t)M * C * 2);
+  p.wgt_bytes = (unsigned)((size_t)R * C * 2);
+  p.ntr = R / TN;
+  p.nchunks = C / CB;
+  return p;
+}
+
+}  // namespace
+
+bool gm_supported(int M, int C, int R) {
+  if (M < 1 || C < CB || R < TN) return false;
+  if ((size_t)M * C * 2 >= OOB || (size_t)R * C * 2 >= OOB) return false;
+  return choose_tile(make_params(M, C, R)) != 0;
+}
+
+hipError_t launch_gm(int M, int C, int R, const void* act, const void* wgt, const float* bias, const BnEpilogue* bn,
+                     void* out, int relu, const void* mask, const void* add, hipStream_t st) {
+  if (!gm_supported(M, C, R)) return hipErrorInvalidValue;
+  GmParams p = make_params(M, C, R);
+  p.act = (const bf16_t*)act; p.wgt = (const bf16_t*)wgt; p.bias = bias; p.out = (bf16_t*)out;
+  if (bn) p.bn = *bn;
+  p.relu = relu; p.mask = (const bf16_t*)mask; p.add = (const bf16_t*)add;
+  return choose_tile(p) == 256 ? launch_inst<256>(p, st) : launch_inst<128>(p, st);
+}
+
+}  // namespace convbn

@@ -437,22 +437,27 @@ hipError_t launch_tconv_pw(const Geom& g, const void* x, const void* w_tap_major
 
 bool pw_fprop_scaled_supported(const Geom& g, int dtype) {
   if (dtype != CONVBN_BF16 || !pointwise(g)) return false;
+  if (gm_supported(g.M, g.Cin, g.Cout)) return true;
   PwParams p = fprop_params(g);
   const PwPlan pl = make_plan(p);
   return pl.ok && pl.cb == 64;
 }
 bool pw_fprop_supported(const Geom& g, int dtype) {
   if (dtype != CONVBN_BF16 || !pointwise(g)) return false;
+  if (gm_supported(g.M, g.Cin, g.Cout)) return true;
   PwParams p = fprop_params(g);
   return make_plan(p).ok;
 }
 bool pw_dgrad_supported(const Geom& g, int dtype) {
   if (dtype != CONVBN_BF16 || !pointwise(g)) return false;
+  if (gm_supported(g.M, g.Cout, g.Cin)) return true;
   PwParams p = dgrad_params(g);
   return make_plan(p).ok;
 }
 hipError_t launch_fprop_pw(const Geom& g, const void* x, const void* w_krsc, const float* bias, void* z,
                            hipStream_t st, const BnEpilogue* bn) {
+  if (gm_supported(g.M, g.Cin, g.Cout))   // the middle stages: one output tile per workgroup
+    return launch_gm(g.M, g.Cin, g.Cout, x, w_krsc, bias, bn, z, g.post_relu, g.post_mask, g.post_add, st);
   PwParams p = fprop_params(g);
   const PwPlan pl = make_plan(p);
   if (!pl.ok) return hipErrorInvalidValue;
@@ -463,6 +468,8 @@ hipError_t launch_fprop_pw(const Geom& g, const void* x, const void* w_krsc, con
 }
 hipError_t launch_dgrad_pw(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
                            hipStream_t st) {
+  if (gm_supported(g.M, g.Cout, g.Cin))
+    return launch_gm(g.M, g.Cout, g.Cin, dz, w_crsk, bias, nullptr, dx, g.post_relu, g.post_mask, g.post_add, st);
   PwParams p = dgrad_params(g);
   const PwPlan pl = make_plan(p);
   if (!pl.ok) return hipErrorInvalidValue;
