@@ -72,14 +72,16 @@ constexpr unsigned OOB = 0x80000000u;
 //   64 pixels x 128 channels: 1 pixel x 4 channel subtiles per wave, 16 KB of weights per step, small windows;
 //  128 pixels x  64 channels: 2 x 2 subtiles (4 operand reads per 4 multiplies instead of 5), 8 KB of weights per
 //                             step and a window tile about twice as large -- fewer bytes per step in all.
-template <int TP_, int TRC_>
+//  128 x 64 with a taller window: six window copies per wave (336 window pixels: 128-pixel tiles of 28 x 28 images that
+//                             cross an image boundary need up to 300) paid for with a ring of seven slabs
+template <int TP_, int TRC_, int HUW_ = 0, int NBUF_ = 0>
 struct Shape {
   static constexpr int TP = TP_;                  // output pixels per workgroup
   static constexpr int TRC = TRC_;                // output channels per workgroup
   static constexpr int NPS = TP / 64;             // 32-pixel subtiles per wave
   static constexpr int NCS = TRC / 32;            // 32-channel subtiles per wave
   static constexpr int WPW = TRC / 64;            // weight copies (8 rows each) per wave and step
-  static constexpr int HUW = TP == 64 ? 3 : 5;    // window-tile copies per wave and chunk
+  static constexpr int HUW = HUW_ ? HUW_ : (TP == 64 ? 3 : 5);    // window-tile copies per wave and chunk
   static constexpr int HUNITS = NWAVES * HUW;     // 24 / 40 -> at most 168 / 280 window pixels per tile
   static constexpr int HBUF = HUNITS * HUNIT + 64;
   static constexpr int WSLAB = TRC * CB * 2;      // 16384 / 8192
@@ -91,7 +93,7 @@ struct Shape {
   // of the DIST - G - 1 latest steps are in flight; a slab's slot was last read in an earlier group:
   // DIST <= NBUF - G + 1; the next chunk's window tile is fetched in the first TAPS + 1 - DIST taps of a chunk.
   static constexpr int G = TP == 64 ? 1 : 3;
-  static constexpr int NBUF = TP == 64 ? 6 : 9;
+  static constexpr int NBUF = NBUF_ ? NBUF_ : (TP == 64 ? 6 : 9);
   static constexpr int DIST = NBUF - G + 1;
   static constexpr int OFF_H = OFF_W + NBUF * WSLAB;
   static constexpr int LDS_BYTES = (OFF_H + 2 * HBUF) > (OFF_W + RED_BYTES) ? (OFF_H + 2 * HBUF) : (OFF_W + RED_BYTES);
@@ -116,7 +118,7 @@ struct StParams {
   int wt0, wt_row, wt_col;        // window position (ti, tj) reads weight tap wt0 + ti wt_row + tj wt_col
   int ntr;                        // channel tiles
   int nchunks;
-  int wide;                       // tile shape: 0 = 64 pixels x 128 channels, 1 = 128 x 64
+  int wide;                       // tile shape: 0 = 64 pixels x 128 channels, 1 = 128 x 64, 2 = 128 x 64 with the taller window
   FastDiv dHoWo, dWo, dHv, dWv;
 };
 
@@ -432,6 +434,7 @@ int max_window_pixels(const StParams& p, int kH, int TP) {
 // Completes the plan of a problem whose tensors are described in p; false = this kernel does not take it.
 using Narrow = Shape<64, 128>;
 using Wide = Shape<128, 64>;
+using Tall = Shape<128, 64, 6, 7>;
 
 template <class S>
 bool shape_fits(const StParams& p, int kH) {
@@ -449,18 +452,19 @@ bool finish_plan(StParams& p, int kH, int kW) {
   p.Hv = p.Ho - 1 + kH;
   p.Wv = p.Wo - 1 + kW;
   const bool wide_ok = shape_fits<Wide>(p, kH), narrow_ok = shape_fits<Narrow>(p, kH);
+  const bool tall_ok = !wide_ok && shape_fits<Tall>(p, kH);
 #if defined(ST_FORCE_NARROW)
   p.wide = 0;
   if (!narrow_ok) return false;
 #else
-  if (!wide_ok && !narrow_ok) return false;
-  p.wide = wide_ok;
+  if (!wide_ok && !narrow_ok && !tall_ok) return false;
+  p.wide = wide_ok ? 1 : (narrow_ok ? 0 : 2);
 #endif
   p.dHoWo = make_fastdiv(p.Ho * p.Wo);
   p.dWo = make_fastdiv(p.Wo);
   p.dHv = make_fastdiv(p.Hv);
   p.dWv = make_fastdiv(p.Wv);
-  p.ntr = p.R / (p.wide ? Wide::TRC : Narrow::TRC);
+  p.ntr = p.R / (p.wide ? Wide::TRC : Narrow::TRC);   // (Tall has Wide's channel tile)
   p.nchunks = p.C / CB;
   return true;
 }
@@ -511,7 +515,7 @@ hipError_t launch_shape(const StParams& p, hipStream_t st) {
 }
 
 hipError_t launch(const StParams& p, hipStream_t st) {
-  return p.wide ? launch_shape<Wide>(p, st) : launch_shape<Narrow>(p, st);
+  return p.wide == 1 ? launch_shape<Wide>(p, st) : (p.wide == 2 ? launch_shape<Tall>(p, st) : launch_shape<Narrow>(p, st));
 }
 
 }  // namespace
