@@ -155,6 +155,27 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
     for (int i = 0; i < NCS; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(stage + (aoff[i] ^ (unsigned)(kk << 5)));
   };
 
+  // ---- the addend and the mask of this lane's outputs (see the epilogue for the lane -> output map) are requested
+  // before the first copy, so that they arrive while the product runs instead of holding up every store
+  auto out_off = [&](int ps, int it) -> long long {
+    const int row = it * 8 + (lane >> 3);
+    const int g = (lane & 7) ^ ((row >> 1) & 7);
+    const int m = m0 + wm * (32 * NPS) + ps * 32 + row;
+    return m < p.M ? (long long)((size_t)m * p.R + r0 + wn * 64 + g * 8) : -1;
+  };
+  uint4 addv[NPS][4], maskv[NPS][4];
+  if (p.add || p.mask) {
+#pragma unroll
+    for (int ps = 0; ps < NPS; ++ps)
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const long long o = out_off(ps, it);
+        addv[ps][it] = (p.add && o >= 0) ? *reinterpret_cast<const uint4*>(p.add + o) : make_uint4(0u, 0u, 0u, 0u);
+        maskv[ps][it] = (p.mask && o >= 0) ? *reinterpret_cast<const uint4*>(p.mask + o) : make_uint4(0u, 0u, 0u, 0u);
+      }
+    asm volatile("" ::: "memory");
+  }
+
   // ---- prologue: chunks 0 and 1 (a chunk past the end is the last one again, into a stage nobody reads)
   const int nchunks = p.nchunks;
 #pragma unroll
@@ -223,13 +244,12 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       const int row = it * 8 + (lane >> 3);
-      const int g = (lane & 7) ^ ((row >> 1) & 7);
-      const uint4 v = *reinterpret_cast<const uint4*>(st + row * 128 + ((lane & 7) << 4));
-      const int m = m0 + wm * (32 * NPS) + ps * 32 + row;
-      if (m < p.M) {
-        const size_t o = (size_t)m * p.R + r0 + wn * 64 + g * 8;
-        *reinterpret_cast<uint4*>(p.out + o) = post_op8(v, p.relu, p.mask, p.add, o);
-      }
+      uint4 v = *reinterpret_cast<const uint4*>(st + row * 128 + ((lane & 7) << 4));
+      const long long o = out_off(ps, it);
+      if (p.add) v = add8(v, addv[ps][it]);
+      if (p.relu) v = relu8(v);
+      if (p.mask) v = mask8(v, maskv[ps][it]);
+      if (o >= 0) *reinterpret_cast<uint4*>(p.out + o) = v;
     }
   }
 }
