@@ -29,6 +29,10 @@ SHAPES = [
     BlockShape("act_gm_fwd_256", 5, 128, 31, 33, 1024, 1, 1, 0, "bf16", 313),    # tiled matrix product, 256-pixel tiles, ragged tail
     BlockShape("act_gm_fwd_128", 5, 192, 31, 33, 512, 1, 1, 0, "bf16", 314),     # ... 128-pixel tiles, three chunks
     BlockShape("act_gm_bwd", 5, 1024, 31, 33, 128, 1, 1, 0, "bf16", 315),        # ... in the input gradient
+    BlockShape("act_gm_one_fwd", 10, 64, 56, 55, 256, 1, 1, 0, "bf16", 316),     # ... single-chunk variant (64 reduced channels, long pixel range)
+    BlockShape("act_gm_one_bwd", 10, 256, 56, 55, 64, 1, 1, 0, "bf16", 317),     # ... in the input gradient
+    BlockShape("act_gm_two_fwd", 5, 128, 56, 55, 512, 1, 1, 0, "bf16", 318),     # ... two resident chunks
+    BlockShape("act_gm_two_bwd", 5, 512, 56, 55, 128, 1, 1, 0, "bf16", 319),
     BlockShape("act_f32", 2, 16, 12, 10, 24, 3, 1, 1, "f32", 311),
     BlockShape("act_f32_ragged", 1, 5, 7, 9, 7, 3, 2, 1, "f32", 312),             # element counts that are not multiples of 8
 ]
@@ -65,7 +69,7 @@ def test_activation_bits_against_oracle_and_unfused_calls(shape, mode, keep):
         assert torch.equal(got[k], want[k]), k
 
 
-@pytest.mark.parametrize("shape", [SHAPES[0], SHAPES[3], SHAPES[5], SHAPES[8], SHAPES[10], SHAPES[12], SHAPES[14]], ids=lambda s: s.name)
+@pytest.mark.parametrize("shape", [SHAPES[0], SHAPES[3], SHAPES[5], SHAPES[8], SHAPES[10], SHAPES[12], SHAPES[13], SHAPES[14], SHAPES[15], SHAPES[18]], ids=lambda s: s.name)
 def test_step_entry_points_with_activation(shape):
     """convbn_conv_fprop with the output bit and convbn_conv_dgrad_masked, against the same calls plus element-wise passes."""
     from paper_2305_11624_amd.runner import BlockRun
