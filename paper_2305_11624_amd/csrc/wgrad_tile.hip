@@ -482,9 +482,16 @@ int max_slots(const WgParams& p) {
 
 struct WgPlan { bool ok; int tpb, na, nb, nt, nsplit; size_t lds; };
 
-bool base_params(const Geom& g, WgParams* p) {
+bool base_params(const Geom& g_in, WgParams* p) {
   WgParams& q = *p;
   q = WgParams{};
+  // A 1x1 / stride-1 / unpadded layer is a product over pixels, whatever the image shape: presented as images of one
+  // row of TP pixels, a tile's window rows are exactly its own pixels (as rows of a 56-wide image a 128-pixel tile
+  // would fetch four of them, 224 pixels).
+  Geom g = g_in;
+  if (g.kH == 1 && g.kW == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0 && g.M % TP == 0) {
+    g.N = g.M / TP; g.Hin = g.Hout = 1; g.Win = g.Wout = TP;
+  }
   q.N = g.N; q.Cin = g.Cin; q.Ho = g.Hout; q.Wo = g.Wout; q.Co = g.Cout; q.M = g.M;
   q.kH = g.kH; q.kW = g.kW;
   if (g.kH == 1 && g.kW == 1 && g.ph == 0 && g.pw == 0) {
