@@ -266,7 +266,9 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
   }
 }
 
-constexpr int MIN_TILES = 160;       // fewer output tiles leave too many compute units without one
+constexpr int MIN_TILES = 160;       // fewer 256-pixel tiles leave too many compute units without one: 128-pixel tiles then,
+constexpr int MIN_TILES_SMALL = 96;  // down to this many (measured against the split-sum plans of the LDS-tile kernel:
+                                     // 1024 -> 256 at 14 x 14, 98 tiles, 10.8 against 12.0 us)
 constexpr int MAX_PIXELS = 32768;    // longer pixel ranges with short reductions stream through the weight-stationary kernel
 
 // 0: not taken; else the pixel tile (256 or 128; 1, 2: 128 pixels, all 1 or 2 chunks resident)
@@ -280,7 +282,7 @@ int choose_tile(const GmParams& p) {
   if ((size_t)p.M * p.C * 2 >= OOB || (size_t)p.M * p.R * 2 >= OOB || (size_t)p.R * p.C * 2 >= OOB) return 0;
   const int ntr = p.R / TN;
   if (ceil_div(p.M, 256) * ntr >= MIN_TILES) return 256;
-  if (ceil_div(p.M, 128) * ntr >= MIN_TILES) return 128;
+  if (ceil_div(p.M, 128) * ntr >= MIN_TILES_SMALL) return 128;
   return 0;
 }
 
