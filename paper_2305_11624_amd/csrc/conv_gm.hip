@@ -26,7 +26,6 @@ namespace {
 constexpr int NWAVES = 8;
 constexpr int CB = 64;                 // reduced channels per chunk
 constexpr int KK = CB / 16;
-constexpr int TN = 128;                // output channels per workgroup
 constexpr int NSTAGE = 3;
 constexpr unsigned OOB = 0x80000000u;  // beyond any buffer: the load returns zeros
 
@@ -70,24 +69,31 @@ template <int N> __device__ __forceinline__ void wait_vm() {
 // RES > 0: the reduction is RES chunks in all (64 or 128 channels), each with a stage of its own and requested at the
 // start: no ring, few registers -- what such a layer needs is several workgroups per compute unit, so that one's
 // stores and another's loads overlap.
-template <int TM, int RES = 0>
+// TN: output channels per workgroup (128; 64 for layers whose channel count is no multiple of 128 -- the two channel
+// groups of waves then own 32 channels each).
+template <int TM, int RES = 0, int TN = 128>
 struct GmCfg {
   static constexpr bool ONE = RES > 0;
+  static constexpr int CW = TN / 2;                     // channels per wave
   static constexpr int NPS = TM / 128;                  // 32-pixel subtiles per wave
-  static constexpr int NCS = 2;                         // 32-channel subtiles per wave
+  static constexpr int NCS = CW / 32;                   // 32-channel subtiles per wave
   static constexpr int AUW = TM / 8 / NWAVES;           // activation copies (8 rows each) per wave and chunk
   static constexpr int WUW = TN / 8 / NWAVES;           // weight copies per wave and chunk
   static constexpr int CPW = AUW + WUW;
   static constexpr int STAGE = (TM + TN) * 128;
   static constexpr int OFF_BIAS = (RES ? RES : NSTAGE) * STAGE;   // [TN] bias, [TN] scale
   static constexpr int LDS_BYTES = OFF_BIAS + 2 * TN * 4;
-  static_assert(NWAVES * 4096 <= STAGE, "the epilogue stages every wave's outputs (4 KB at a time) in the first stage");
+  static_assert(NWAVES * 32 * CW * 2 <= STAGE, "the epilogue stages every wave's outputs (32 pixels at a time) in the first stage");
 };
 
-template <int TM, int RES = 0>
+template <int TM, int RES = 0, int TN = 128>
 __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
-  using Cfg = GmCfg<TM, RES>;
+  using Cfg = GmCfg<TM, RES, TN>;
   constexpr bool ONE = Cfg::ONE;
+  constexpr int CW = Cfg::CW;
+  constexpr int GR = CW / 8;          // 16-byte granules of a wave's staged output row
+  constexpr int RPI = 64 / GR;        // rows one store instruction covers
+  constexpr int ITS = 32 / RPI;       // store instructions per 32-pixel subtile
   constexpr int NPS = Cfg::NPS, NCS = Cfg::NCS, AUW = Cfg::AUW, WUW = Cfg::WUW, CPW = Cfg::CPW, STAGE = Cfg::STAGE;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   float* biasl = reinterpret_cast<float*>(smem + Cfg::OFF_BIAS);
@@ -142,7 +148,7 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
 #pragma unroll
   for (int ps = 0; ps < NPS; ++ps) boff[ps] = (unsigned)((wm * (32 * NPS) + ps * 32) * 128) + lane_off;
 #pragma unroll
-  for (int i = 0; i < NCS; ++i) aoff[i] = (unsigned)(TM * 128 + (wn * 64 + i * 32) * 128) + lane_off;
+  for (int i = 0; i < NCS; ++i) aoff[i] = (unsigned)(TM * 128 + (wn * CW + i * 32) * 128) + lane_off;
 
   f32x16 acc[NCS][NPS];
 #pragma unroll
@@ -163,17 +169,17 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
   // ---- the addend and the mask of this lane's outputs (see the epilogue for the lane -> output map) are requested
   // before the first copy, so that they arrive while the product runs instead of holding up every store
   auto out_off = [&](int ps, int it) -> long long {
-    const int row = it * 8 + (lane >> 3);
-    const int g = (lane & 7) ^ ((row >> 1) & 7);
+    const int row = it * RPI + lane / GR;
+    const int g = (lane % GR) ^ ((row >> 1) & (GR - 1));
     const int m = m0 + wm * (32 * NPS) + ps * 32 + row;
-    return m < p.M ? (long long)((size_t)m * p.R + r0 + wn * 64 + g * 8) : -1;
+    return m < p.M ? (long long)((size_t)m * p.R + r0 + wn * CW + g * 8) : -1;
   };
-  uint4 addv[NPS][4], maskv[NPS][4];
+  uint4 addv[NPS][ITS], maskv[NPS][ITS];
   if (!ONE && (p.add || p.mask)) {
 #pragma unroll
     for (int ps = 0; ps < NPS; ++ps)
 #pragma unroll
-      for (int it = 0; it < 4; ++it) {
+      for (int it = 0; it < ITS; ++it) {
         const long long o = out_off(ps, it);
         addv[ps][it] = (p.add && o >= 0) ? *reinterpret_cast<const uint4*>(p.add + o) : make_uint4(0u, 0u, 0u, 0u);
         maskv[ps][it] = (p.mask && o >= 0) ? *reinterpret_cast<const uint4*>(p.mask + o) : make_uint4(0u, 0u, 0u, 0u);
@@ -231,11 +237,11 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
   __syncthreads();   // (and the bias is visible)
 
   // ---- epilogue.  Accumulator element e of lane l in subtile (i, ps): channel 32 i + 8 (e / 4) + 4 (l / 32) + e % 4,
-  // pixel 32 ps + l % 32 of the wave's block.  Per 32-pixel subtile the wave rounds 32 pixels x 64 channels to bf16
-  // into its own 4 KB ([pixel][64 ch], granules swizzled by pixel) and reads them back row-wise: every store is 16
-  // bytes per lane, eight lanes cover one pixel's 128 contiguous bytes.
-  unsigned char* const st = smem + wave * 4096;
-  const int px = lane & 31, psw = (px >> 1) & 7;
+  // pixel 32 ps + l % 32 of the wave's block.  Per 32-pixel subtile the wave rounds 32 pixels x CW channels to bf16
+  // into its own 64 CW bytes ([pixel][CW ch], granules swizzled by pixel) and reads them back row-wise: every store is 16
+  // bytes per lane, GR lanes cover one pixel's CW contiguous channels.
+  unsigned char* const st = smem + wave * (32 * CW * 2);
+  const int px = lane & 31, psw = (px >> 1) & (GR - 1);
 #pragma unroll
   for (int ps = 0; ps < NPS; ++ps) {
 #pragma unroll
@@ -243,16 +249,16 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int ch = i * 32 + q * 8 + kb * 4;
-        const float4 bb = *reinterpret_cast<const float4*>(biasl + wn * 64 + ch);
-        const float4 sc = *reinterpret_cast<const float4*>(biasl + TN + wn * 64 + ch);
+        const float4 bb = *reinterpret_cast<const float4*>(biasl + wn * CW + ch);
+        const float4 sc = *reinterpret_cast<const float4*>(biasl + TN + wn * CW + ch);
         const uint2 v = make_uint2(pack_bf16x2(fmaf(acc[i][ps][q * 4 + 0], sc.x, bb.x), fmaf(acc[i][ps][q * 4 + 1], sc.y, bb.y)),
                                    pack_bf16x2(fmaf(acc[i][ps][q * 4 + 2], sc.z, bb.z), fmaf(acc[i][ps][q * 4 + 3], sc.w, bb.w)));
-        *reinterpret_cast<uint2*>(st + px * 128 + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
+        *reinterpret_cast<uint2*>(st + px * (CW * 2) + (((ch >> 3) ^ psw) << 4) + ((ch & 7) << 1)) = v;
       }
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int row = it * 8 + (lane >> 3);
-      uint4 v = *reinterpret_cast<const uint4*>(st + row * 128 + ((lane & 7) << 4));
+    for (int it = 0; it < ITS; ++it) {
+      const int row = it * RPI + lane / GR;
+      uint4 v = *reinterpret_cast<const uint4*>(st + row * (CW * 2) + ((lane % GR) << 4));
       const long long o = out_off(ps, it);
       if constexpr (ONE) {
         if (o >= 0) *reinterpret_cast<uint4*>(p.out + o) = post_op8(v, p.relu, p.mask, p.add, (size_t)o);
@@ -271,60 +277,58 @@ constexpr int MIN_TILES_SMALL = 96;  // down to this many (measured against the 
                                      // 1024 -> 256 at 14 x 14, 98 tiles, 10.8 against 12.0 us)
 constexpr int MAX_PIXELS = 32768;    // longer pixel ranges with short reductions stream through the weight-stationary kernel
 
-// 0: not taken; else the pixel tile (256 or 128; 1, 2: 128 pixels, all 1 or 2 chunks resident)
-int choose_tile(const GmParams& p) {
-  if ((p.C == CB || p.C == 2 * CB) && p.R % TN == 0 && ceil_div(p.M, 128) * (p.R / TN) >= 3 * MIN_TILES &&
-      (size_t)p.M * p.C * 2 < OOB && (size_t)p.M * p.R * 2 < OOB)
-    return p.C / CB;
+struct GmPlan { int tm, res, tn; };   // tm == 0: not taken
+
+GmPlan choose_plan(int M, int C, int R) {
+  GmPlan none{0, 0, 0};
+  if (M < 1 || C < CB || C % CB || R % 64) return none;
+  if ((size_t)M * C * 2 >= OOB || (size_t)M * R * 2 >= OOB || (size_t)R * C * 2 >= OOB) return none;
+  const int tn = R % 128 == 0 ? 128 : 64;
+  const int ntr = R / tn;
+  const long long t128 = (long long)ceil_div(M, 128) * ntr, t256 = (long long)ceil_div(M, 256) * ntr;
+  // short reductions over many tiles: every chunk resident, several workgroups per compute unit
+  if ((C == CB || C == 2 * CB) && t128 >= 3 * MIN_TILES) return GmPlan{128, C / CB, tn};
+  if (tn == 64) return t128 >= MIN_TILES_SMALL ? GmPlan{128, 0, 64} : none;
   // (measured on the 56 x 56 stage: with 256 reduced channels the tile beats the streaming kernel, 21.9 against 26.1 us
   // for 256 -> 128; with 64 or 128 both are bound by their stores and take the same time)
-  if (p.C % CB || p.R % TN || (p.M > MAX_PIXELS && p.C < 256)) return 0;
-  if ((size_t)p.M * p.C * 2 >= OOB || (size_t)p.M * p.R * 2 >= OOB || (size_t)p.R * p.C * 2 >= OOB) return 0;
-  const int ntr = p.R / TN;
-  if (ceil_div(p.M, 256) * ntr >= MIN_TILES) return 256;
-  if (ceil_div(p.M, 128) * ntr >= MIN_TILES_SMALL) return 128;
-  return 0;
+  if (M > MAX_PIXELS && C < 256) return none;
+  if (t256 >= MIN_TILES) return GmPlan{256, 0, 128};
+  if (t128 >= MIN_TILES_SMALL) return GmPlan{128, 0, 128};
+  return none;
 }
 
-template <int TM, int ONE = 0>
+template <int TM, int RES, int TN>
 hipError_t launch_inst(const GmParams& p, hipStream_t st) {
   static LdsLimitOnce lds_once;
-  if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&conv_gm_kernel<TM, ONE>),
-                                        GmCfg<TM, ONE>::LDS_BYTES); e != hipSuccess) return e;
-  constexpr int lds = GmCfg<TM, ONE>::LDS_BYTES;
-  hipLaunchKernelGGL((conv_gm_kernel<TM, ONE>), dim3(ceil_div(p.M, TM) * p.ntr), dim3(64 * NWAVES), lds, st, p);
+  constexpr int lds = GmCfg<TM, RES, TN>::LDS_BYTES;
+  if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&conv_gm_kernel<TM, RES, TN>), lds);
+      e != hipSuccess) return e;
+  hipLaunchKernelGGL((conv_gm_kernel<TM, RES, TN>), dim3(ceil_div(p.M, TM) * p.ntr), dim3(64 * NWAVES), lds, st, p);
   return hipGetLastError();
-}
-
-GmParams make_params(int M, int C, int R) {
-  GmParams p{};
-  p.M = M; p.C = C; p.R = R;
-  p.act_bytes = (unsigned)((size_t)M * C * 2);
-  p.wgt_bytes = (unsigned)((size_t)R * C * 2);
-  p.ntr = R / TN;
-  p.nchunks = C / CB;
-  return p;
 }
 
 }  // namespace
 
-bool gm_supported(int M, int C, int R) {
-  if (M < 1 || C < CB || R < TN) return false;
-  if ((size_t)M * C * 2 >= OOB || (size_t)R * C * 2 >= OOB) return false;
-  return choose_tile(make_params(M, C, R)) != 0;
-}
+bool gm_supported(int M, int C, int R) { return choose_plan(M, C, R).tm != 0; }
 
 hipError_t launch_gm(int M, int C, int R, const void* act, const void* wgt, const float* bias, const BnEpilogue* bn,
                      void* out, int relu, const void* mask, const void* add, hipStream_t st) {
-  if (!gm_supported(M, C, R)) return hipErrorInvalidValue;
-  GmParams p = make_params(M, C, R);
+  const GmPlan pl = choose_plan(M, C, R);
+  if (pl.tm == 0) return hipErrorInvalidValue;
+  GmParams p{};
+  p.M = M; p.C = C; p.R = R;
+  p.act_bytes = (unsigned)((size_t)M * C * 2);
+  p.wgt_bytes = (unsigned)((size_t)R * C * 2);
+  p.ntr = R / pl.tn;
+  p.nchunks = C / CB;
   p.act = (const bf16_t*)act; p.wgt = (const bf16_t*)wgt; p.bias = bias; p.out = (bf16_t*)out;
   if (bn) p.bn = *bn;
   p.relu = relu; p.mask = (const bf16_t*)mask; p.add = (const bf16_t*)add;
-  const int tile = choose_tile(p);
-  if (tile == 1) return launch_inst<128, 1>(p, st);
-  if (tile == 2) return launch_inst<128, 2>(p, st);
-  return tile == 256 ? launch_inst<256>(p, st) : launch_inst<128>(p, st);
+#define GM_CASE(TM_, RES_, TN_) if (pl.tm == TM_ && pl.res == RES_ && pl.tn == TN_) return launch_inst<TM_, RES_, TN_>(p, st);
+  GM_CASE(256, 0, 128) GM_CASE(128, 0, 128) GM_CASE(128, 1, 128) GM_CASE(128, 2, 128)
+  GM_CASE(128, 0, 64) GM_CASE(128, 1, 64) GM_CASE(128, 2, 64)
+#undef GM_CASE
+  return hipErrorInvalidValue;
 }
 
 }  // namespace convbn
