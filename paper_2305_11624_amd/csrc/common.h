@@ -282,8 +282,13 @@ hipError_t launch_wgrad_igemm(const Geom& g, const void* x, const void* dz, floa
 // the tiled matrix product that takes the pointwise layers of the middle stages (conv_gm.hip); reached through the
 // pw_* calls below
 bool gm_supported(int M, int C, int R);
+// sd != null: a strided pointwise layer -- the M rows are the pixels of the dense side [N][Ho][Wo], and the rows of the
+// activations (scatter == 0) or of the output (scatter == 1; no post-operation then) are pixel (n, ho sh, wo sw) of an
+// [N][Hs][Ws] tensor.
+struct GmStride { int scatter, N, Ho, Wo, Hs, Ws, sh, sw; };
 hipError_t launch_gm(int M, int C, int R, const void* act, const void* wgt, const float* bias, const BnEpilogue* bn,
-                     void* out, int relu, const void* mask, const void* add, hipStream_t st);
+                     void* out, int relu, const void* mask, const void* add, hipStream_t st, const GmStride* sd = nullptr);
+hipError_t launch_gm_fill(void* p, size_t rows, int R, const float* bias, hipStream_t st);   // rows of bias (null: zeros), R % 8 == 0
 bool pw_fprop_supported(const Geom& g, int dtype);
 bool pw_fprop_scaled_supported(const Geom& g, int dtype);     // ... with a BnEpilogue
 bool pw_dgrad_supported(const Geom& g, int dtype);

@@ -42,7 +42,21 @@ struct GmParams {
   int M, C, R;
   int ntr;               // channel tiles
   int nchunks;
+  // A pointwise layer with a stride (a downsampling shortcut) is the same product over the output pixels, whose rows
+  // of the strided tensor are not consecutive: row m = (n, ho, wo) of the dense side is pixel (n, ho sh, wo sw) of an
+  // [N][Hs][Ws] tensor.  gather: the activation rows are taken from there (forward); scatter: the output rows go there
+  // (input gradient; the other pixels of dx are zero and are filled by the caller).
+  int gather, scatter;
+  int Ho, Wo, Hs, Ws, sh, sw;
 };
+
+// pixel index in the strided tensor of row m of the dense side
+__device__ __forceinline__ size_t strided_row(const GmParams& p, int m) {
+  const int hw = p.Ho * p.Wo;
+  const int n = m / hw, rem = m - n * hw;
+  const int ho = rem / p.Wo, wo = rem - ho * p.Wo;
+  return ((size_t)n * p.Hs + (size_t)ho * p.sh) * p.Ws + (size_t)wo * p.sw;
+}
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
@@ -125,7 +139,8 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
   for (int j = 0; j < AUW; ++j) {
     const int row = (wave + NWAVES * j) * 8 + crow;
     const int g = cpos ^ ((row >> 1) & 7);
-    voff_a[j] = m0 + row < p.M ? (unsigned)(((size_t)(m0 + row) * p.C + g * 8) * 2) : OOB;   // rows past the last pixel: zeros
+    const size_t arow = (p.gather && m0 + row < p.M) ? strided_row(p, m0 + row) : (size_t)(m0 + row);
+    voff_a[j] = m0 + row < p.M ? (unsigned)((arow * p.C + g * 8) * 2) : OOB;   // rows past the last pixel: zeros
   }
 #pragma unroll
   for (int j = 0; j < WUW; ++j) {
@@ -172,7 +187,9 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
     const int row = it * RPI + lane / GR;
     const int g = (lane % GR) ^ ((row >> 1) & (GR - 1));
     const int m = m0 + wm * (32 * NPS) + ps * 32 + row;
-    return m < p.M ? (long long)((size_t)m * p.R + r0 + wn * CW + g * 8) : -1;
+    if (m >= p.M) return -1;
+    const size_t orow = p.scatter ? strided_row(p, m) : (size_t)m;
+    return (long long)(orow * p.R + r0 + wn * CW + g * 8);
   };
   uint4 addv[NPS][ITS], maskv[NPS][ITS];
   if (!ONE && (p.add || p.mask)) {
@@ -311,13 +328,40 @@ hipError_t launch_inst(const GmParams& p, hipStream_t st) {
 
 bool gm_supported(int M, int C, int R) { return choose_plan(M, C, R).tm != 0; }
 
+// every row of a [rows][R] bf16 tensor <- bias (zeros if null); R is a multiple of 8
+__global__ __launch_bounds__(256) void gm_fill_kernel(uint4* __restrict__ p, size_t n16, int R8, const float* __restrict__ bias) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (bias) {
+      const float* b = bias + (i % (size_t)R8) * 8;
+      v = make_uint4(pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3]), pack_bf16x2(b[4], b[5]), pack_bf16x2(b[6], b[7]));
+    }
+    p[i] = v;
+  }
+}
+
+hipError_t launch_gm_fill(void* p, size_t rows, int R, const float* bias, hipStream_t st) {
+  const size_t n16 = rows * (size_t)R / 8;
+  const int blocks = (int)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
+  hipLaunchKernelGGL(gm_fill_kernel, dim3(blocks < 1 ? 1 : blocks), dim3(256), 0, st, (uint4*)p, n16, R / 8, bias);
+  return hipGetLastError();
+}
+
 hipError_t launch_gm(int M, int C, int R, const void* act, const void* wgt, const float* bias, const BnEpilogue* bn,
-                     void* out, int relu, const void* mask, const void* add, hipStream_t st) {
+                     void* out, int relu, const void* mask, const void* add, hipStream_t st, const GmStride* sd) {
   const GmPlan pl = choose_plan(M, C, R);
   if (pl.tm == 0) return hipErrorInvalidValue;
   GmParams p{};
   p.M = M; p.C = C; p.R = R;
   p.act_bytes = (unsigned)((size_t)M * C * 2);
+  if (sd) {
+    const size_t strided_pixels = (size_t)sd->N * sd->Hs * sd->Ws;
+    if (strided_pixels * (size_t)(sd->scatter ? R : C) * 2 >= OOB) return hipErrorInvalidValue;
+    p.gather = !sd->scatter; p.scatter = sd->scatter;
+    p.Ho = sd->Ho; p.Wo = sd->Wo; p.Hs = sd->Hs; p.Ws = sd->Ws; p.sh = sd->sh; p.sw = sd->sw;
+    if (p.gather) p.act_bytes = (unsigned)(strided_pixels * C * 2);
+    if (p.scatter && (mask || add || relu)) return hipErrorInvalidValue;   // the caller applies them to all of dx
+  }
   p.wgt_bytes = (unsigned)((size_t)R * C * 2);
   p.ntr = R / pl.tn;
   p.nchunks = C / CB;

@@ -388,6 +388,15 @@ hipError_t launch_plan(const PwParams& p, const PwPlan& pl, hipStream_t st) {
 bool pointwise(const Geom& g) {
   return g.kH == 1 && g.kW == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0;
 }
+// a downsampling shortcut: 1x1 window, a stride, no padding -- the product over the output pixels, whose input rows
+// (forward) or output rows (input gradient) are every stride-th pixel
+bool strided_pointwise(const Geom& g) {
+  return g.kH == 1 && g.kW == 1 && (g.sh > 1 || g.sw > 1) && g.ph == 0 && g.pw == 0 && g.Cin % 8 == 0 && g.Cout % 8 == 0;
+}
+GmStride stride_of(const Geom& g, int scatter) {
+  return GmStride{scatter, g.N, g.Hout, g.Wout, g.Hin, g.Win, g.sh, g.sw};
+}
+bool strided_fits(const Geom& g) { return (size_t)g.Min * g.Cin * 2 < OOB && (size_t)g.M * g.Cout * 2 < OOB; }
 PwParams fprop_params(const Geom& g) {
   PwParams p{};
   p.M = g.M; p.C = g.Cin; p.R = g.Cout;
@@ -436,6 +445,7 @@ hipError_t launch_tconv_pw(const Geom& g, const void* x, const void* w_tap_major
 }
 
 bool pw_fprop_scaled_supported(const Geom& g, int dtype) {
+  if (dtype == CONVBN_BF16 && strided_pointwise(g)) return strided_fits(g) && gm_supported(g.M, g.Cin, g.Cout);
   if (dtype != CONVBN_BF16 || !pointwise(g)) return false;
   if (gm_supported(g.M, g.Cin, g.Cout)) return true;
   PwParams p = fprop_params(g);
@@ -443,12 +453,14 @@ bool pw_fprop_scaled_supported(const Geom& g, int dtype) {
   return pl.ok && pl.cb == 64;
 }
 bool pw_fprop_supported(const Geom& g, int dtype) {
+  if (dtype == CONVBN_BF16 && strided_pointwise(g)) return strided_fits(g) && gm_supported(g.M, g.Cin, g.Cout);
   if (dtype != CONVBN_BF16 || !pointwise(g)) return false;
   if (gm_supported(g.M, g.Cin, g.Cout)) return true;
   PwParams p = fprop_params(g);
   return make_plan(p).ok;
 }
 bool pw_dgrad_supported(const Geom& g, int dtype) {
+  if (dtype == CONVBN_BF16 && strided_pointwise(g)) return strided_fits(g) && gm_supported(g.M, g.Cout, g.Cin);
   if (dtype != CONVBN_BF16 || !pointwise(g)) return false;
   if (gm_supported(g.M, g.Cout, g.Cin)) return true;
   PwParams p = dgrad_params(g);
@@ -456,6 +468,10 @@ bool pw_dgrad_supported(const Geom& g, int dtype) {
 }
 hipError_t launch_fprop_pw(const Geom& g, const void* x, const void* w_krsc, const float* bias, void* z,
                            hipStream_t st, const BnEpilogue* bn) {
+  if (strided_pointwise(g)) {
+    const GmStride sd = stride_of(g, 0);
+    return launch_gm(g.M, g.Cin, g.Cout, x, w_krsc, bias, bn, z, g.post_relu, g.post_mask, g.post_add, st, &sd);
+  }
   if (gm_supported(g.M, g.Cin, g.Cout))   // the middle stages: one output tile per workgroup
     return launch_gm(g.M, g.Cin, g.Cout, x, w_krsc, bias, bn, z, g.post_relu, g.post_mask, g.post_add, st);
   PwParams p = fprop_params(g);
@@ -468,6 +484,18 @@ hipError_t launch_fprop_pw(const Geom& g, const void* x, const void* w_krsc, con
 }
 hipError_t launch_dgrad_pw(const Geom& g, const void* dz, const void* w_crsk, const float* bias, void* dx,
                            hipStream_t st) {
+  if (strided_pointwise(g)) {
+    // the pixels no output pixel reads hold the bias alone (an input gradient has none: zeros): those rows everywhere
+    // first, then the product lands on every stride-th pixel; a post-operation covers all of dx, as passes of its own
+    const size_t n = (size_t)g.Min * g.Cin;
+    if (hipError_t e = launch_gm_fill(dx, (size_t)g.Min, g.Cin, bias, st); e != hipSuccess) return e;
+    const GmStride sd = stride_of(g, 1);
+    hipError_t e = launch_gm(g.M, g.Cout, g.Cin, dz, w_crsk, bias, nullptr, dx, 0, nullptr, nullptr, st, &sd);
+    if (e == hipSuccess && g.post_add) e = launch_eltwise(3 /* a + b */, CONVBN_BF16, dx, g.post_add, nullptr, n, st);
+    if (e == hipSuccess && g.post_relu) e = launch_eltwise(0, CONVBN_BF16, dx, nullptr, nullptr, n, st);
+    if (e == hipSuccess && g.post_mask) e = launch_eltwise(1, CONVBN_BF16, dx, g.post_mask, nullptr, n, st);
+    return e;
+  }
   if (gm_supported(g.M, g.Cout, g.Cin))
     return launch_gm(g.M, g.Cout, g.Cin, dz, w_crsk, bias, nullptr, dx, g.post_relu, g.post_mask, g.post_add, st);
   PwParams p = dgrad_params(g);

@@ -35,6 +35,7 @@ SHAPES = [
     BlockShape("act_gm_two_bwd", 5, 512, 56, 55, 128, 1, 1, 0, "bf16", 319),
     BlockShape("act_gm_64_one", 20, 64, 56, 55, 64, 1, 1, 0, "bf16", 320),       # ... 64-channel tiles, one resident chunk
     BlockShape("act_gm_64_two", 20, 128, 56, 55, 64, 1, 1, 0, "bf16", 321),      # ... two
+    BlockShape("act_gm_strided", 30, 256, 27, 29, 512, 1, 2, 0, "bf16", 322),    # ... a downsampling shortcut: gathered / scattered rows
     BlockShape("act_f32", 2, 16, 12, 10, 24, 3, 1, 1, "f32", 311),
     BlockShape("act_f32_ragged", 1, 5, 7, 9, 7, 3, 2, 1, "f32", 312),             # element counts that are not multiples of 8
 ]
