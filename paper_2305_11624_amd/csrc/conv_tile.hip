@@ -76,6 +76,7 @@ struct TileParams {
   int Hv, Wv;            // rows / columns of one image's (virtually padded) window footprint
   int ntr;               // channel tiles
   int nhb, hps, spread;  // activation tile ring depth, copy units per wave and step, steps a prefetch spans
+  int min_hps;           // host side: the planner picks at least this many copy units per wave and step
   int ksplit, chunks_per_split;   // channel chunks are divided over gridDim.y workgroups
   float* part;           // [ksplit][M][R] fp32 partial outputs when ksplit > 1
   int halo_stride;       // bytes per activation tile buffer
@@ -160,13 +161,14 @@ __device__ unsigned long long tile_trace[1024 * 32];
 #ifndef TILE_TRACE_WAVE
 #define TILE_TRACE_WAVE 0
 #endif
-#define STAMP(i) do { if (threadIdx.x == 64 * TILE_TRACE_WAVE) { tile_trace[blockIdx.x * 32 + (i)] = clock64(); tile_trace[blockIdx.x * 32 + 16 + (i)] = wall_clock64(); } } while (0)
+#define STAMP(i) do { if (threadIdx.x == 64 * TILE_TRACE_WAVE) { tile_trace[bx * 32 + (i)] = clock64(); tile_trace[bx * 32 + 16 + (i)] = wall_clock64(); } } while (0)
 #else
 #define STAMP(i) do {} while (0)
 #endif
 
+// The work of workgroup (bx, by) of a launch of gx x (splits) workgroups; smem: the workgroup's LDS.
 template <int NW, int NWC, int NCH, int CB, int HPS, bool SC = false>
-__global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
+__device__ __forceinline__ void tile_body(const TileParams& p, int bx, int by, int gx, unsigned char* smem) {
   STAMP(0);
   using Cfg = TileCfg<NCH, CB>;
   constexpr int NWP = NW / NWC;            // waves along the pixels
@@ -179,7 +181,6 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   constexpr int WPW = (WUNITS + NW - 1) / NW;  // weight copies per wave and step (surplus ones are dummies)
   constexpr bool MULTI = HPS > 0;
   constexpr int CPS = HPS + WPW;               // copies per wave and step
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   float* biasl = reinterpret_cast<float*>(smem);               // [TRC] bias of this channel tile (first KB)
   unsigned char* wbuf = smem + 1024;                           // [NBUF] weight slabs
   unsigned char* scratch = wbuf + NBUF * WSLAB;                // 1 KB target of the dummy copies (zeros only)
@@ -189,7 +190,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wp = wave % NWP;               // pixel group and channel group of this wave
   const int cw0 = (wave / NWP) * NCW;      // its first 32-channel subtile
-  const int ctile = blockIdx.x % p.ntr, ptile = blockIdx.x / p.ntr;
+  const int ctile = bx % p.ntr, ptile = bx / p.ntr;
   const int r0 = ctile * TRC;
   const int HoWo = p.Ho * p.Wo;
   // pixels [m0, m0 + len) of this tile: TP consecutive pixels, or whole rows of one image
@@ -211,7 +212,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
   const __amdgpu_buffer_rsrc_t act_rsrc = make_rsrc(p.act, p.act_bytes);
   const __amdgpu_buffer_rsrc_t wgt_rsrc = make_rsrc(p.wgt, p.wgt_bytes);
   const int taps = p.kH * p.kW;
-  const int cbeg = blockIdx.y * p.chunks_per_split;                       // first channel chunk of this workgroup
+  const int cbeg = by * p.chunks_per_split;                       // first channel chunk of this workgroup
   const int nchunks = min(p.C / CB, cbeg + p.chunks_per_split);           // one past its last chunk
   const int nsteps = (nchunks - cbeg) * taps;
   // bias of this channel tile: fetched now, parked in LDS after the main loop (nothing waits for it)
@@ -380,7 +381,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     for (int r = 0; r < NCW; ++r) fa[buf][r] = *reinterpret_cast<const bf16x8*>(a + r * 32 * ROWP + kk * 32);
   };
 
-  if (SC && p.bn.w_folded_out) emit_folded_slice(p.bn, p.wgt, blockIdx.x, gridDim.x);   // while the first copies are in flight
+  if (SC && p.bn.w_folded_out) emit_folded_slice(p.bn, p.wgt, bx, gx);   // while the first copies are in flight
   STAMP(1);
   wait_vm<(DIST - 1) * (WPW + HPS)>();   // the activation tile of the first chunk and the slab of step 0 have landed
   block_barrier();
@@ -471,7 +472,7 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     // fp32 partial sums of this workgroup's channel chunks; bias and rounding happen in the reduction
     const int pi = wp * 32 + (lane & 31);
     if (pi < len) {
-      float* orow = p.part + ((size_t)blockIdx.y * p.M + m0 + pi) * p.R;
+      float* orow = p.part + ((size_t)by * p.M + m0 + pi) * p.R;
 #pragma unroll
       for (int r = 0; r < NCW; ++r)
 #pragma unroll
@@ -524,6 +525,30 @@ __global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
     }
   }
   STAMP(4);
+}
+
+template <int NW, int NWC, int NCH, int CB, int HPS, bool SC = false>
+__global__ __launch_bounds__(64 * NW) void conv_tile_kernel(TileParams p) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  tile_body<NW, NWC, NCH, CB, HPS, SC>(p, (int)blockIdx.x, (int)blockIdx.y, (int)gridDim.x, smem);
+}
+
+// Several problems of one kernel shape in ONE launch (the residue classes of a strided input gradient: each alone
+// leaves most of the chip idle, and launches of one stream do not overlap): the workgroups of problem c are
+// [first[c], first[c + 1]).  No split sums.
+struct TileMulti {
+  TileParams p[4];
+  int first[5];
+  int n;
+};
+template <int NW, int NWC, int NCH, int CB, int HPS>
+__global__ __launch_bounds__(64 * NW) void conv_tile_multi_kernel(TileMulti m) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const int b = (int)blockIdx.x;
+  int c = 0;
+  while (c + 1 < m.n && b >= m.first[c + 1]) ++c;
+  c = __builtin_amdgcn_readfirstlane(c);
+  tile_body<NW, NWC, NCH, CB, HPS, false>(m.p[c], b - m.first[c], 0, m.first[c + 1] - m.first[c], smem);
 }
 
 // out[m][r] = bf16( sum_s part[s][m][r] + bias[r] ), eight channels per thread (R % 8 == 0).
@@ -627,7 +652,7 @@ size_t plan_lds_cfg(TileParams& p, int nw, int nwc, bool rows) {
     static const int hps_values[] = {1, 2, 3, 4, 6, 8};
     hps = 0;
     for (int v : hps_values)
-      if (ceil_div(per_wave, v) <= max_spread) { hps = v; break; }
+      if (v >= p.min_hps && ceil_div(per_wave, v) <= max_spread) { hps = v; break; }
     if (hps == 0) return 0;
     spread = ceil_div(per_wave, hps);
   }
@@ -769,6 +794,27 @@ hipError_t launch_plan(const TileParams& p, const TilePlan& pl, hipStream_t st) 
   CASES(4, 2, 4, 32) CASES(4, 2, 4, 64) CASES(16, 1, 2, 64)
 #undef CASES
 #undef CASE
+  return hipErrorInvalidValue;
+}
+
+template <int NW, int NWC, int NCH, int CB, int HPS>
+hipError_t launch_multi_inst(const TileMulti& m, size_t lds, hipStream_t st) {
+  static LdsLimitOnce lds_once;
+  if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&conv_tile_multi_kernel<NW, NWC, NCH, CB, HPS>),
+                                        (int)LDS_USABLE); e != hipSuccess) return e;
+  hipLaunchKernelGGL((conv_tile_multi_kernel<NW, NWC, NCH, CB, HPS>), dim3(m.first[m.n]), dim3(64 * NW), lds, st, m);
+  return hipGetLastError();
+}
+// the kernel shapes the strided 3x3 layers of a ResNet ask for; anything else runs class by class
+bool multi_shape(const TilePlan& pl) {
+  return (pl.nw == 4 && pl.nwc == 2 && pl.nch == 4 && pl.cb == 64 && (pl.hps == 2 || pl.hps == 3)) ||
+         (pl.nw == 4 && pl.nwc == 1 && pl.nch == 4 && pl.cb == 32 && (pl.hps == 4 || pl.hps == 6));
+}
+hipError_t launch_multi(const TileMulti& m, const TilePlan& pl, size_t lds, hipStream_t st) {
+  if (pl.cb == 64 && pl.hps == 2) return launch_multi_inst<4, 2, 4, 64, 2>(m, lds, st);
+  if (pl.cb == 64 && pl.hps == 3) return launch_multi_inst<4, 2, 4, 64, 3>(m, lds, st);
+  if (pl.cb == 32 && pl.hps == 4) return launch_multi_inst<4, 1, 4, 32, 4>(m, lds, st);
+  if (pl.cb == 32 && pl.hps == 6) return launch_multi_inst<4, 1, 4, 32, 6>(m, lds, st);
   return hipErrorInvalidValue;
 }
 
@@ -961,6 +1007,57 @@ hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, 
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
     }
+    // all classes as one launch where they share a kernel shape (the one that needs the most copy units per step
+    // sets it for all), at most four of them, none with split sums
+    {
+      TileMulti m{};
+      TilePlan pls[4];
+      int n = 0, hps = 0;
+      bool same = true;
+      for (int a = 0; a < g.sh && same; ++a)
+        for (int b = 0; b < g.sw && same; ++b) {
+          TileParams q;
+          if (dgrad_class_params(g, a, b, &q) != CLASS_RUN) continue;
+          if (n == 4) { same = false; break; }
+          pls[n] = make_plan(q);
+          same = pls[n].ok && q.ksplit == 1 && multi_shape(pls[n]) &&
+                 (n == 0 || (pls[n].nw == pls[0].nw && pls[n].nwc == pls[0].nwc && pls[n].nch == pls[0].nch && pls[n].cb == pls[0].cb));
+          if (pls[n].hps > hps) hps = pls[n].hps;
+          ++n;
+        }
+      if (same && n >= 2) {
+        size_t lds = 0;
+        n = 0;
+        for (int a = 0; a < g.sh && same; ++a)
+          for (int b = 0; b < g.sw && same; ++b) {
+            TileParams& q = m.p[n];
+            if (dgrad_class_params(g, a, b, &q) != CLASS_RUN) continue;
+            q.min_hps = hps;
+            const TilePlan pl = make_plan(q);
+            same = pl.ok && q.ksplit == 1 && pl.hps == hps && pl.nw == pls[0].nw && pl.nwc == pls[0].nwc &&
+                   pl.nch == pls[0].nch && pl.cb == pls[0].cb;
+            if (!same) break;
+            q.act = (const bf16_t*)dz; q.wgt = (const bf16_t*)w_crsk; q.bias = bias; q.out = (bf16_t*)dx;
+            q.relu = g.post_relu; q.mask = (const bf16_t*)g.post_mask; q.add = (const bf16_t*)g.post_add;
+            if (defer) { q.relu = 0; q.mask = nullptr; q.add = nullptr; }
+            q.part = nullptr;
+            const int ptiles = q.tile_rows > 0 ? q.N * q.tiles_per_image : ceil_div(q.M, 32 * (pl.nw / pl.nwc));
+            m.first[n + 1] = m.first[n] + q.ntr * ptiles;
+            if (pl.lds > lds) lds = pl.lds;
+            pls[n] = pl;
+            ++n;
+          }
+        // (measured: it pays for the deep layer, whose classes are long reductions over few pixels -- 512 channels,
+        // 14 x 14, 100 workgroups per class: 48.5 -> 33.5 us; with 256 channels at 28 x 28, 98 workgroups per class,
+        // the classes are bound by their traffic and one launch takes 42.9 against 40.4 us)
+        if (same && m.first[n] <= 448 && g.Cout >= 512) {
+          m.n = n;
+          hipError_t e = launch_multi(m, pls[0], lds, st);
+          if (e != hipSuccess) return e;
+          goto classes_done;
+        }
+      }
+    }
     for (int a = 0; a < g.sh; ++a)
       for (int b = 0; b < g.sw; ++b) {
         if (dgrad_class_params(g, a, b, &p) != CLASS_RUN) continue;
@@ -973,6 +1070,7 @@ hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, 
         hipError_t e = launch_plan(p, pl, st);
         if (e != hipSuccess) return e;
       }
+  classes_done:
     if (defer) {
       const size_t n = (size_t)g.Min * g.Cin;
       hipError_t e = launch_eltwise(3 /* a + b */, CONVBN_BF16, dx, g.post_add, nullptr, n, st);
