@@ -286,6 +286,22 @@ bool gm_supported(int M, int C, int R);
 // activations (scatter == 0) or of the output (scatter == 1; no post-operation then) are pixel (n, ho sh, wo sw) of an
 // [N][Hs][Ws] tensor.
 struct GmStride { int scatter, N, Ho, Wo, Hs, Ws, sh, sw; };
+// Window mode of the same kernel (no window tile in LDS: every tap gathers its rows; for strided layers).  A kH x kW
+// window slides with stride (csh, csw) and padding (cph, cpw) over an [N][aH][aW] activation grid with element strides
+// a_n, a_h, a_w; output pixel (n, ho, wo) of an [N][oHo][oWo] grid is stored at element out_base + n out_n + ho out_h +
+// wo out_w (out_strided) or at row m of a dense [M][R] tensor; window position (ti, tj) multiplies with tap
+// wt0 + ti wt_row + tj wt_col of the weight tensor, whose rows (one per output channel) have wrow elements.
+struct GmConv {
+  int kH, kW, cph, cpw, csh, csw, aH, aW;
+  int a_n, a_h, a_w;
+  int oHo, oWo;
+  int wt0, wt_row, wt_col, wrow;
+  int out_strided, out_base, out_n, out_h, out_w;
+};
+bool gm_conv_supported(int M, int C, int R, const GmConv& cv);
+hipError_t launch_gm_conv(int M, int C, int R, const GmConv& cv, const void* act, unsigned act_bytes, const void* wgt,
+                          unsigned wgt_bytes, const float* bias, void* out, int relu, const void* mask, const void* add,
+                          hipStream_t st);
 hipError_t launch_gm(int M, int C, int R, const void* act, const void* wgt, const float* bias, const BnEpilogue* bn,
                      void* out, int relu, const void* mask, const void* add, hipStream_t st, const GmStride* sd = nullptr);
 hipError_t launch_gm_fill(void* p, size_t rows, int R, const float* bias, hipStream_t st);   // rows of bias (null: zeros), R % 8 == 0

@@ -48,6 +48,11 @@ struct GmParams {
   // (input gradient; the other pixels of dx are zero and are filled by the caller).
   int gather, scatter;
   int Ho, Wo, Hs, Ws, sh, sw;
+  // Window mode (template flag CONV): a kH x kW window slides with stride (csh, csw) and padding (cph, cpw) over an
+  // [N][aH][aW] activation grid; output pixel m = (n, ho, wo) of an [N][oHo][oWo] grid.  Every tap is a step of its own
+  // in the reduction, its activation rows gathered per output pixel (zeros outside the grid): no window tile in LDS,
+  // the taps re-read their rows through the L2 -- for strided layers, whose windows hardly overlap.
+  GmConv cv;
 };
 
 // pixel index in the strided tensor of row m of the dense side
@@ -100,8 +105,9 @@ struct GmCfg {
   static_assert(NWAVES * 32 * CW * 2 <= STAGE, "the epilogue stages every wave's outputs (32 pixels at a time) in the first stage");
 };
 
-template <int TM, int RES = 0, int TN = 128>
+template <int TM, int RES = 0, int TN = 128, bool CONV = false>
 __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
+  static_assert(!CONV || RES == 0, "window mode runs on the ring");
   using Cfg = GmCfg<TM, RES, TN>;
   constexpr bool ONE = Cfg::ONE;
   constexpr int CW = Cfg::CW;
@@ -135,23 +141,48 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
   // 8 u + l / 8 and fetches the granule that belongs there, (l % 8) ^ key(row), key = (row / 2) % 8
   const int crow = lane >> 3, cpos = lane & 7;
   unsigned voff_a[AUW], voff_w[WUW];
+  int cv_h[AUW], cv_w[AUW];   // window mode: the row's window origin (h, w of tap (0, 0)); voff_a holds its image and granule
 #pragma unroll
   for (int j = 0; j < AUW; ++j) {
     const int row = (wave + NWAVES * j) * 8 + crow;
     const int g = cpos ^ ((row >> 1) & 7);
-    const size_t arow = (p.gather && m0 + row < p.M) ? strided_row(p, m0 + row) : (size_t)(m0 + row);
-    voff_a[j] = m0 + row < p.M ? (unsigned)((arow * p.C + g * 8) * 2) : OOB;   // rows past the last pixel: zeros
+    if constexpr (CONV) {
+      const int m = min(m0 + row, p.M - 1);
+      const int hw = p.cv.oHo * p.cv.oWo;
+      const int n = m / hw, rem = m - n * hw;
+      const int ho = rem / p.cv.oWo, wo = rem - ho * p.cv.oWo;
+      cv_h[j] = m0 + row < p.M ? ho * p.cv.csh - p.cv.cph : -(1 << 20);   // rows past the last pixel: never inside the grid
+      cv_w[j] = wo * p.cv.csw - p.cv.cpw;
+      voff_a[j] = (unsigned)((n * p.cv.a_n + g * 8) * 2);
+    } else {
+      const size_t arow = (p.gather && m0 + row < p.M) ? strided_row(p, m0 + row) : (size_t)(m0 + row);
+      voff_a[j] = m0 + row < p.M ? (unsigned)((arow * p.C + g * 8) * 2) : OOB;   // rows past the last pixel: zeros
+      cv_h[j] = cv_w[j] = 0;
+    }
   }
 #pragma unroll
   for (int j = 0; j < WUW; ++j) {
     const int row = (wave + NWAVES * j) * 8 + crow;
     const int g = cpos ^ ((row >> 1) & 7);
-    voff_w[j] = (unsigned)(((size_t)(r0 + row) * p.C + g * 8) * 2);
+    voff_w[j] = (unsigned)(((size_t)(r0 + row) * (CONV ? p.cv.wrow : p.C) + g * 8) * 2);
   }
-  auto issue_copy = [&](int i, int chunk, unsigned char* stage) {   // copy i (0 .. CPW-1) of a chunk
+  // copy i (0 .. CPW-1) of a reduction step: chunk `chunk` of (window mode) tap (ti, tj)
+  auto issue_copy = [&](int i, int chunk, int ti, int tj, unsigned char* stage) {
     const unsigned soff = (unsigned)(chunk * (CB * 2));
-    if (i < AUW) dma16(act_rsrc, voff_a[i < AUW ? i : 0], soff, stage + (wave + NWAVES * i) * 1024);
-    else dma16(wgt_rsrc, voff_w[i - AUW < WUW ? i - AUW : 0], soff, stage + TM * 128 + (wave + NWAVES * (i - AUW)) * 1024);
+    if (i < AUW) {
+      const int ii = i < AUW ? i : 0;
+      unsigned voff = voff_a[ii];
+      if constexpr (CONV) {
+        const int h = cv_h[ii] + ti, w = cv_w[ii] + tj;
+        const bool ok = (unsigned)h < (unsigned)p.cv.aH && (unsigned)w < (unsigned)p.cv.aW;
+        voff = ok ? voff + (unsigned)((h * p.cv.a_h + w * p.cv.a_w) * 2) : OOB;
+      }
+      dma16(act_rsrc, voff, soff, stage + (wave + NWAVES * i) * 1024);
+    } else {
+      const int jj = i - AUW < WUW ? i - AUW : 0;
+      const unsigned wsoff = CONV ? (unsigned)((p.cv.wt0 + ti * p.cv.wt_row + tj * p.cv.wt_col) * p.C * 2) + soff : soff;
+      dma16(wgt_rsrc, voff_w[jj], wsoff, stage + TM * 128 + (wave + NWAVES * (i - AUW)) * 1024);
+    }
   };
 
   // ---- operand addresses: row l % 32 of a subtile, granule 2 kk + l / 32 of the chunk, which sits at position
@@ -188,6 +219,15 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
     const int g = (lane % GR) ^ ((row >> 1) & (GR - 1));
     const int m = m0 + wm * (32 * NPS) + ps * 32 + row;
     if (m >= p.M) return -1;
+    if constexpr (CONV) {
+      if (p.cv.out_strided) {
+        const int hw = p.cv.oHo * p.cv.oWo;
+        const int n = m / hw, rem = m - n * hw;
+        const int ho = rem / p.cv.oWo, wo = rem - ho * p.cv.oWo;
+        return (long long)p.cv.out_base + (long long)n * p.cv.out_n + (long long)ho * p.cv.out_h + (long long)wo * p.cv.out_w +
+               r0 + wn * CW + g * 8;
+      }
+    }
     const size_t orow = p.scatter ? strided_row(p, m) : (size_t)m;
     return (long long)(orow * p.R + r0 + wn * CW + g * 8);
   };
@@ -205,13 +245,27 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
   }
 
   // ---- prologue: chunks 0 and 1 (a chunk past the end is the last one again, into a stage nobody reads)
+  // (window mode: a step is (tap, chunk), chunks innermost; p.nchunks counts the steps and cpt the chunks per tap)
   const int nchunks = p.nchunks;
+  const int cpt = CONV ? p.C / CB : nchunks;
+  int f_c = 0, f_i = 0, f_j = 0;   // the step whose copies are issued next: chunk and tap
+  auto advance_fill = [&]() {       // ... the one after it (the last step stays)
+    if constexpr (CONV) {
+      if (f_c + 1 < cpt) ++f_c;
+      else if (f_j + 1 < p.cv.kW) { f_c = 0; ++f_j; }
+      else if (f_i + 1 < p.cv.kH) { f_c = 0; f_j = 0; ++f_i; }
+    } else {
+      if (f_c + 1 < nchunks) ++f_c;
+    }
+  };
 #pragma unroll
-  for (int i = 0; i < CPW; ++i) issue_copy(i, 0, smem);
+  for (int i = 0; i < CPW; ++i) issue_copy(i, f_c, f_i, f_j, smem);
+  advance_fill();
   if constexpr (RES != 1) {
 #pragma unroll
-    for (int i = 0; i < CPW; ++i) issue_copy(i, min(1, nchunks - 1), smem + STAGE);
+    for (int i = 0; i < CPW; ++i) issue_copy(i, f_c, f_i, f_j, smem + STAGE);
   }
+  advance_fill();
 
   int st_cur = 0;   // stage of the current chunk
   for (int c = 0; c < nchunks; ++c) {
@@ -221,7 +275,6 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
     const unsigned char* const stage = smem + st_cur * STAGE;
     const int st_fill = st_cur >= 1 ? st_cur - 1 : NSTAGE - 1;   // (c + 2) % 3
     unsigned char* const fill = smem + st_fill * STAGE;
-    const int cf = min(c + 2, nchunks - 1);
     load_frags(0, stage, 0);
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
@@ -238,17 +291,18 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
           acc[i][ps] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][ps], acc[i][ps], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
           if (!ONE && issued < PER && kk * PER + issued < CPW) {
-            issue_copy(kk * PER + issued, cf, fill);
+            issue_copy(kk * PER + issued, f_c, f_i, f_j, fill);
             ++issued;
             __builtin_amdgcn_sched_barrier(0);
           }
         }
 #pragma unroll
       for (; issued < PER; ++issued)
-        if (!ONE && kk * PER + issued < CPW) issue_copy(kk * PER + issued, cf, fill);
+        if (!ONE && kk * PER + issued < CPW) issue_copy(kk * PER + issued, f_c, f_i, f_j, fill);
       __builtin_amdgcn_sched_barrier(0);
     }
     st_cur = st_cur + 1 == NSTAGE ? 0 : st_cur + 1;
+    advance_fill();
   }
   wait_vm<0>();      // trailing copies must not outlive the loop: the ring becomes the staging space
   __syncthreads();   // (and the bias is visible)
@@ -324,7 +378,44 @@ hipError_t launch_inst(const GmParams& p, hipStream_t st) {
   return hipGetLastError();
 }
 
+template <int TM>
+hipError_t launch_conv_inst(const GmParams& p, hipStream_t st) {
+  static LdsLimitOnce lds_once;
+  constexpr int lds = GmCfg<TM, 0, 128>::LDS_BYTES;
+  if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&conv_gm_kernel<TM, 0, 128, true>), lds);
+      e != hipSuccess) return e;
+  hipLaunchKernelGGL((conv_gm_kernel<TM, 0, 128, true>), dim3(ceil_div(p.M, TM) * p.ntr), dim3(64 * NWAVES), lds, st, p);
+  return hipGetLastError();
+}
+
+// pixel tile of the window mode: 0 = not taken
+int conv_tile_pixels(int M, int C, int R, const GmConv& cv) {
+  if (M < 1 || C % CB || R % 128 || cv.kH < 1 || cv.kW < 1 || cv.kH * cv.kW > 16) return 0;
+  const long long t256 = (long long)ceil_div(M, 256) * (R / 128), t128 = (long long)ceil_div(M, 128) * (R / 128);
+  if (t256 >= MIN_TILES) return 256;
+  if (t128 >= MIN_TILES_SMALL) return 128;
+  return 0;
+}
+
 }  // namespace
+
+bool gm_conv_supported(int M, int C, int R, const GmConv& cv) { return conv_tile_pixels(M, C, R, cv) != 0; }
+
+hipError_t launch_gm_conv(int M, int C, int R, const GmConv& cv, const void* act, unsigned act_bytes, const void* wgt,
+                          unsigned wgt_bytes, const float* bias, void* out, int relu, const void* mask, const void* add,
+                          hipStream_t st) {
+  const int tm = conv_tile_pixels(M, C, R, cv);
+  if (tm == 0 || act_bytes >= OOB || wgt_bytes >= OOB) return hipErrorInvalidValue;
+  GmParams p{};
+  p.M = M; p.C = C; p.R = R;
+  p.act_bytes = act_bytes; p.wgt_bytes = wgt_bytes;
+  p.ntr = R / 128;
+  p.nchunks = cv.kH * cv.kW * (C / CB);   // steps: (tap, chunk)
+  p.cv = cv;
+  p.act = (const bf16_t*)act; p.wgt = (const bf16_t*)wgt; p.bias = bias; p.out = (bf16_t*)out;
+  p.relu = relu; p.mask = (const bf16_t*)mask; p.add = (const bf16_t*)add;
+  return tm == 256 ? launch_conv_inst<256>(p, st) : launch_conv_inst<128>(p, st);
+}
 
 bool gm_supported(int M, int C, int R) { return choose_plan(M, C, R).tm != 0; }
 

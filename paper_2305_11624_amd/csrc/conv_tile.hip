@@ -920,6 +920,18 @@ ClassKind dgrad_class_params(const Geom& g, int a, int b, TileParams* p) {
   return CLASS_RUN;
 }
 
+// The same problem for the tiled product's window mode (conv_gm.hip), which takes strided windows: they hardly overlap,
+// so a window tile in LDS buys little and costs the chunk width (32-channel chunks here against 64 there).
+GmConv gm_conv_of(const TileParams& q) {
+  GmConv c{};
+  c.kH = q.kH; c.kW = q.kW; c.cph = q.ph; c.cpw = q.pw; c.csh = q.sh; c.csw = q.sw; c.aH = q.H; c.aW = q.W;
+  c.a_n = q.act_n_stride; c.a_h = q.act_h_stride; c.a_w = q.act_w_stride;
+  c.oHo = q.Ho; c.oWo = q.Wo;
+  c.wt0 = q.wt0; c.wt_row = q.wt_row; c.wt_col = q.wt_col; c.wrow = q.wrow;
+  c.out_strided = q.out_strided; c.out_base = q.out_base; c.out_n = q.out_n; c.out_h = q.out_h; c.out_w = q.out_w;
+  return c;
+}
+
 // Every pixel row of out ([pixels][R] bf16, R % 8 == 0) := bf16(bias) (zeros without a bias).
 __global__ __launch_bounds__(256) void fill_rows_kernel(uint4* __restrict__ out, size_t n16, int R,
                                                         const float* __restrict__ bias) {
@@ -940,7 +952,11 @@ __global__ __launch_bounds__(256) void fill_rows_kernel(uint4* __restrict__ out,
 bool tile_fprop_supported(const Geom& g, int dtype) {
   if (dtype != CONVBN_BF16) return false;
   TileParams p;
-  return fprop_params(g, &p) && make_plan(p).ok;
+  if (!fprop_params(g, &p)) return false;
+  if ((g.sh > 1 || g.sw > 1) && g.kH * g.kW > 1 && p.C % 8 == 0 && p.act_bytes < OOB && p.wgt_bytes < OOB &&
+      (size_t)p.M * p.R * 2 < OOB && gm_conv_supported(p.M, p.C, p.R, gm_conv_of(p)))
+    return true;   // the tiled product's window mode takes it
+  return make_plan(p).ok;
 }
 
 bool tile_dgrad_supported(const Geom& g, int dtype) {
@@ -951,6 +967,7 @@ bool tile_dgrad_supported(const Geom& g, int dtype) {
   for (int a = 0; a < g.sh; ++a)
     for (int b = 0; b < g.sw; ++b) {
       const ClassKind k = dgrad_class_params(g, a, b, &p);
+      if (k == CLASS_RUN && p.act_bytes < OOB && p.wgt_bytes < OOB && gm_conv_supported(p.M, p.C, p.R, gm_conv_of(p))) continue;
       if (k == CLASS_UNSUPPORTED || (k == CLASS_RUN && !make_plan(p).ok)) return false;
     }
   return true;
@@ -981,6 +998,12 @@ hipError_t launch_fprop_tile(const Geom& g, const void* x, const void* w_krsc, c
                              void* z, float* partials, hipStream_t st, const BnEpilogue* bn) {
   TileParams p;
   fprop_params(g, &p);
+  if (!bn && (g.sh > 1 || g.sw > 1) && g.kH * g.kW > 1) {
+    const GmConv cv = gm_conv_of(p);
+    if (gm_conv_supported(p.M, p.C, p.R, cv))
+      return launch_gm_conv(p.M, p.C, p.R, cv, x, p.act_bytes, w_krsc, p.wgt_bytes, bias, z, g.post_relu, g.post_mask,
+                            g.post_add, st);
+  }
   const TilePlan pl = make_plan(p);
   if (p.ksplit > 1 && (!partials || bn)) return hipErrorInvalidValue;   // split sums add the bias in their reduction
   if (bn && !scaled_plan(pl)) return hipErrorInvalidValue;
@@ -1061,6 +1084,16 @@ hipError_t launch_dgrad_tile(const Geom& g, const void* dz, const void* w_crsk, 
     for (int a = 0; a < g.sh; ++a)
       for (int b = 0; b < g.sw; ++b) {
         if (dgrad_class_params(g, a, b, &p) != CLASS_RUN) continue;
+        {
+          const GmConv cv = gm_conv_of(p);
+          if (gm_conv_supported(p.M, p.C, p.R, cv)) {
+            hipError_t e = launch_gm_conv(p.M, p.C, p.R, cv, dz, p.act_bytes, w_crsk, p.wgt_bytes, bias, dx,
+                                          defer ? 0 : g.post_relu, defer ? nullptr : g.post_mask,
+                                          defer ? nullptr : g.post_add, st);
+            if (e != hipSuccess) return e;
+            continue;
+          }
+        }
         const TilePlan pl = make_plan(p);
         if (!pl.ok) return hipErrorInvalidValue;
         p.act = (const bf16_t*)dz; p.wgt = (const bf16_t*)w_crsk; p.bias = bias; p.out = (bf16_t*)dx;
