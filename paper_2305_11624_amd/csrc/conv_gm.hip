@@ -1,22 +1,29 @@
-// Pointwise (1x1, stride 1, unpadded) bf16 convolution of the middle stages as a tiled matrix product
-//     out[m][r] = sum_c act[m][c] wgt[r][c] (+ bias[r]),     m over all N*H*W pixels:
-//   forward conv   Z  = w' (*) X + b'   (Sec. 3.1 / 3.3)   act = x,   wgt = w' as [Cout][Cin]
-//   input gradient dX = w'_rot (*) dZ   (Sec. 3.2.1)       act = dz,  wgt = w' as [Cin][Cout]
+// bf16 convolution as a tiled matrix product without a window tile in LDS
+//     out[m][r] = sum_{tap, c} act[row(m, tap)][c] wgt[r][tap][c] (+ bias[r]),     m over the output pixels:
+//   forward conv   Z  = w' (*) X + b'   (Sec. 3.1 / 3.3)   act = x,   wgt = w' as [Cout][taps][Cin]
+//   input gradient dX = w'_rot (*) dZ   (Sec. 3.2.1)       act = dz,  wgt = w' as [Cin][taps][Cout]
+// for pointwise (1x1) layers with or without a stride, and -- window mode -- for strided 3x3 layers, forward and the
+// residue classes of the input gradient.
 //
-// For a few thousand to a few ten thousand pixels and 128 .. 2048 channels on either side (the 28 x 28, 14 x 14
-// and 7 x 7 stages of a ResNet-50) the product is a few GFLOP over a few tens of MB: one output tile per
-// workgroup, and the tile as large as still fills the chip -- 256 (or 128) pixels x 128 channels, shared by EIGHT
-// waves as 4 (2) pixel groups x 2 channel groups, so that a wave owns 64 x 64 (32 x 64) outputs and reads four
-// (three) operand fragments for four (two) multiplies, and the matrix pipe of every SIMD is fed by two waves.
-// The weight-stationary streaming kernel (conv_pw.hip) stays with the long pixel streams of the first stage.
+// One output tile per workgroup, as large as still fills the chip: 256 (or 128) pixels x 128 channels, shared by
+// EIGHT waves as 4 (2) pixel groups x 2 channel groups, so that a wave owns 64 x 64 (32 x 64) outputs and reads four
+// (three) operand fragments for four (two) multiplies, and the matrix pipe of every SIMD is fed by two waves.  Channel
+// counts that are no multiple of 128 get 128 x 64 tiles.
 //
-// Pipeline.  The reduction runs over 64-channel chunks.  A chunk of the activation tile and of the weight tile
-// is copied global -> LDS directly (1 KB per instruction: 8 rows x 128 bytes) into one of three stages, two chunks
-// ahead; every wave issues the same number of copies per chunk, so "at most that many copies outstanding" means
-// the current chunk has landed; one barrier per chunk.  LDS rows are 128 bytes, unpadded: the copy permutes the
-// eight 16-byte granules of row r by (r / 2) % 8 (it chooses which granule each lane fetches), so that the 128-bit
-// operand reads of 16 consecutive rows fall on distinct banks.  The copies of a chunk are issued between its
-// multiplies; operands are double-buffered in registers one 16-channel step ahead.
+// Pipeline.  The reduction runs over 64-channel chunks (window mode: over the taps, chunks innermost).  A chunk of
+// the activation tile and of the weight tile is copied global -> LDS directly (1 KB per instruction: 8 rows x 128
+// bytes) into one of three stages, two chunks ahead; every wave issues the same number of copies per chunk, so "at
+// most that many copies outstanding" means the current chunk has landed; one barrier per chunk.  LDS rows are 128
+// bytes, unpadded: the copy permutes the eight 16-byte granules of row r by (r / 2) % 8 (it chooses which granule
+// each lane fetches), so that the 128-bit operand reads of 16 consecutive rows fall on distinct banks.  The copies of
+// a chunk are issued between its multiplies; operands are double-buffered in registers one 16-channel step ahead.
+// A copy's per-lane byte offset is free, which is all a stride needs: a strided pointwise layer gathers every
+// stride-th pixel's row (forward) or scatters its output rows (input gradient); in window mode the offset of a row
+// is recomputed per tap from the output pixel's window origin, rows outside the image being zero-fill copies.
+//
+// Layers that are bound by their stores rather than by the product (64 or 128 reduced channels over tens of
+// thousands of pixels) run a variant with all their one or two chunks resident: no ring, about 70 registers, 33 or
+// 65 KB of LDS -- several workgroups share a compute unit, and one's stores overlap another's loads.
 #include "common.h"
 
 namespace convbn {

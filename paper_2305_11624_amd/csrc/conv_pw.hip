@@ -4,6 +4,9 @@
 //   forward conv   Z  = w' (*) X + b'   (Sec. 3.1 / 3.3)   act = x,   wgt = w' as [Cout][Cin]
 //   input gradient dX = w'_rot (*) dZ   (Sec. 3.2.1)       act = dz,  wgt = w' as [Cin][Cout]
 //
+// (Shapes the tiled product of conv_gm.hip takes -- most layers of a ResNet-50, and every strided pointwise layer -- are
+// handed on to it by the launch functions at the end of this file; this kernel keeps the rest.)
+//
 // Most of these layers move many MB of activations for a few GFLOP: they are bound by memory (or by the
 // global->LDS copy path), and a kernel that hands every pixel tile to a workgroup of its own pays that workgroup's
 // start-up (weights, tables, first copies in flight) and drain (stores) once per tile, with the memory
