@@ -128,7 +128,12 @@ __global__ __launch_bounds__(64 * NWAVES) void conv_gm_kernel(GmParams p) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;      // pixel group, channel group
-  const int ctile = blockIdx.x % p.ntr, ptile = blockIdx.x / p.ntr;
+  // Workgroups are handed to the eight XCDs in turn (id % 8), and each XCD has its own L2: the channel tiles of one
+  // pixel tile read the same activation rows and should share one.  Pixel tiles go in groups of eight, one per XCD;
+  // the k-th workgroup of an XCD (k = id / 8) is channel tile k % ntr of the XCD's (k / ntr)-th pixel tile.
+  const int kx = (int)blockIdx.x >> 3;
+  const int ctile = kx % p.ntr, ptile = (kx / p.ntr) * 8 + ((int)blockIdx.x & 7);
+  if (ptile * TM >= p.M) return;   // (the last group of eight may be short)
   const int r0 = ctile * TN, m0 = ptile * TM;
   const __amdgpu_buffer_rsrc_t act_rsrc = make_rsrc(p.act, p.act_bytes);
   const __amdgpu_buffer_rsrc_t wgt_rsrc = make_rsrc(p.wgt, p.wgt_bytes);
@@ -381,7 +386,7 @@ hipError_t launch_inst(const GmParams& p, hipStream_t st) {
   constexpr int lds = GmCfg<TM, RES, TN>::LDS_BYTES;
   if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&conv_gm_kernel<TM, RES, TN>), lds);
       e != hipSuccess) return e;
-  hipLaunchKernelGGL((conv_gm_kernel<TM, RES, TN>), dim3(ceil_div(p.M, TM) * p.ntr), dim3(64 * NWAVES), lds, st, p);
+  hipLaunchKernelGGL((conv_gm_kernel<TM, RES, TN>), dim3(ceil_div(ceil_div(p.M, TM), 8) * 8 * p.ntr), dim3(64 * NWAVES), lds, st, p);
   return hipGetLastError();
 }
 
@@ -391,7 +396,7 @@ hipError_t launch_conv_inst(const GmParams& p, hipStream_t st) {
   constexpr int lds = GmCfg<TM, 0, 128>::LDS_BYTES;
   if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&conv_gm_kernel<TM, 0, 128, true>), lds);
       e != hipSuccess) return e;
-  hipLaunchKernelGGL((conv_gm_kernel<TM, 0, 128, true>), dim3(ceil_div(p.M, TM) * p.ntr), dim3(64 * NWAVES), lds, st, p);
+  hipLaunchKernelGGL((conv_gm_kernel<TM, 0, 128, true>), dim3(ceil_div(ceil_div(p.M, TM), 8) * 8 * p.ntr), dim3(64 * NWAVES), lds, st, p);
   return hipGetLastError();
 }
 
