@@ -8,7 +8,7 @@
 // One output tile per workgroup, as large as still fills the chip: 256 (or 128) pixels x 128 channels, shared by
 // EIGHT waves as 4 (2) pixel groups x 2 channel groups, so that a wave owns 64 x 64 (32 x 64) outputs and reads four
 // (three) operand fragments for four (two) multiplies, and the matrix pipe of every SIMD is fed by two waves.  Channel
-// counts that are no multiple of 128 get 128 x 64 tiles.
+// counts that are no multiple of 128 get 128 x 64 tiles, and so do layers with too few 128 x 128 tiles for the chip.
 //
 // Pipeline.  The reduction runs over 64-channel chunks (window mode: over the taps, chunks innermost).  A chunk of
 // the activation tile and of the weight tile is copied global -> LDS directly (1 KB per instruction: 8 rows x 128
@@ -376,6 +376,9 @@ GmPlan choose_plan(int M, int C, int R) {
   // for 256 -> 128; with 64 or 128 both are bound by their stores and take the same time)
   if (M > MAX_PIXELS && C < 256) return none;
   if (t256 >= MIN_TILES) return GmPlan{256, 0, 128};
+  // too few 128 x 128 tiles for the chip: twice as many of half the channels (measured: 1024 -> 256 at 14 x 14, 98 tiles,
+  // 10.4 -> 9.0 us; 2048 -> 512 at 7 x 7, 52 tiles, 16.8 us on the split-sum tile kernel -> 12.6)
+  if (t128 < MIN_TILES && 2 * t128 >= MIN_TILES_SMALL) return GmPlan{128, 0, 64};
   if (t128 >= MIN_TILES_SMALL) return GmPlan{128, 0, 128};
   return none;
 }
@@ -390,43 +393,49 @@ hipError_t launch_inst(const GmParams& p, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <int TM>
+template <int TM, int TN>
 hipError_t launch_conv_inst(const GmParams& p, hipStream_t st) {
   static LdsLimitOnce lds_once;
-  constexpr int lds = GmCfg<TM, 0, 128>::LDS_BYTES;
-  if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&conv_gm_kernel<TM, 0, 128, true>), lds);
+  constexpr int lds = GmCfg<TM, 0, TN>::LDS_BYTES;
+  if (hipError_t e = set_lds_limit_once(lds_once, reinterpret_cast<const void*>(&conv_gm_kernel<TM, 0, TN, true>), lds);
       e != hipSuccess) return e;
-  hipLaunchKernelGGL((conv_gm_kernel<TM, 0, 128, true>), dim3(ceil_div(ceil_div(p.M, TM), 8) * 8 * p.ntr), dim3(64 * NWAVES), lds, st, p);
+  hipLaunchKernelGGL((conv_gm_kernel<TM, 0, TN, true>), dim3(ceil_div(ceil_div(p.M, TM), 8) * 8 * p.ntr), dim3(64 * NWAVES), lds, st, p);
   return hipGetLastError();
 }
 
-// pixel tile of the window mode: 0 = not taken
-int conv_tile_pixels(int M, int C, int R, const GmConv& cv) {
-  if (M < 1 || C % CB || R % 128 || cv.kH < 1 || cv.kW < 1 || cv.kH * cv.kW > 16) return 0;
+// tile of the window mode: tm = 0: not taken
+GmPlan conv_tile_plan(int M, int C, int R, const GmConv& cv) {
+  GmPlan none{0, 0, 0};
+  if (M < 1 || C % CB || R % 128 || cv.kH < 1 || cv.kW < 1 || cv.kH * cv.kW > 16) return none;
   const long long t256 = (long long)ceil_div(M, 256) * (R / 128), t128 = (long long)ceil_div(M, 128) * (R / 128);
-  if (t256 >= MIN_TILES) return 256;
-  if (t128 >= MIN_TILES_SMALL) return 128;
-  return 0;
+  if (t256 >= MIN_TILES) return GmPlan{256, 0, 128};
+  // (as in the plain mode; 3x3 / 2 layers: 512 channels to 7 x 7, 52 tiles, forward 30.8 -> 27.9 us; 256 channels to 14 x 14,
+  // 98 tiles, forward 19.5 -> 17.9, input gradient 33.4 -> 28.8)
+  if (t128 < MIN_TILES && 2 * t128 >= MIN_TILES_SMALL) return GmPlan{128, 0, 64};
+  if (t128 >= MIN_TILES_SMALL) return GmPlan{128, 0, 128};
+  return none;
 }
 
 }  // namespace
 
-bool gm_conv_supported(int M, int C, int R, const GmConv& cv) { return conv_tile_pixels(M, C, R, cv) != 0; }
+bool gm_conv_supported(int M, int C, int R, const GmConv& cv) { return conv_tile_plan(M, C, R, cv).tm != 0; }
 
 hipError_t launch_gm_conv(int M, int C, int R, const GmConv& cv, const void* act, unsigned act_bytes, const void* wgt,
                           unsigned wgt_bytes, const float* bias, void* out, int relu, const void* mask, const void* add,
                           hipStream_t st) {
-  const int tm = conv_tile_pixels(M, C, R, cv);
+  const GmPlan pl = conv_tile_plan(M, C, R, cv);
+  const int tm = pl.tm;
   if (tm == 0 || act_bytes >= OOB || wgt_bytes >= OOB) return hipErrorInvalidValue;
   GmParams p{};
   p.M = M; p.C = C; p.R = R;
   p.act_bytes = act_bytes; p.wgt_bytes = wgt_bytes;
-  p.ntr = R / 128;
+  p.ntr = R / pl.tn;
   p.nchunks = cv.kH * cv.kW * (C / CB);   // steps: (tap, chunk)
   p.cv = cv;
   p.act = (const bf16_t*)act; p.wgt = (const bf16_t*)wgt; p.bias = bias; p.out = (bf16_t*)out;
   p.relu = relu; p.mask = (const bf16_t*)mask; p.add = (const bf16_t*)add;
-  return tm == 256 ? launch_conv_inst<256>(p, st) : launch_conv_inst<128>(p, st);
+  if (pl.tn == 64) return launch_conv_inst<128, 64>(p, st);
+  return tm == 256 ? launch_conv_inst<256, 128>(p, st) : launch_conv_inst<128, 128>(p, st);
 }
 
 bool gm_supported(int M, int C, int R) { return choose_plan(M, C, R).tm != 0; }
